@@ -1,0 +1,152 @@
+"""Device byte layout of a packed GQSA matrix, re-derived from its written
+specification -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+
+The layout is a pure permutation/padding of the canonical BSR arrays of the
+paper's Sec. 3.2 listing (rowIndex / groups / values) and the per-group scale
+and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
+
+ 1. Stream.  The stored groups in canonical order g = 0..nnzg-1 form a stream;
+    it is padded with null groups (all bytes zero) to nblocks*64 positions,
+    nblocks = ceil(nnzg/64).
+ 2. Partition.  n_waves workers each own a contiguous run of blocks: worker w
+    owns n_w = nblocks div n_waves (+1 if w < nblocks mod n_waves) blocks,
+    starting at block b_w = sum of the earlier workers' counts.
+ 3. Superblocks.  A worker's run is cut, from its start, into superblocks of 4
+    blocks as long as 4 fit, then one of 2 blocks if at least 2 remain, then
+    one of 1 block if one remains.  A superblock of U blocks starting at block
+    b covers stream positions 64b .. 64(b+U)-1 of the stream; the position
+    64b + p lives in block b + (p mod U), lane p div U.
+ 4. Block.  Each block is (G*bits/8 + 6)*64 bytes: 64 lanes x code bytes, then
+    64 x uint32 (fp16 scale bits | fp16 zero bits << 16), then 64 x uint16
+    (group-column | 0x8000 if the group is the first stored group of its row).
+    4-bit codes, G = 16: a lane holds two little-endian uint32; word h holds
+    elements 8h..8h+7 of the group, element 8h+2m in bits 4m..4m+3 and element
+    8h+2m+1 in bits 16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j of the
+    lane's 16 bytes is element j.
+ 5. Side tables (int32): rank_base[n_waves] = (number of row-head groups at
+    stream positions before worker w's first position) - 1; row_of_rank[r] =
+    index of the r-th non-empty row; empty_rows = indices of the empty rows.
+ 6. Blob = blocks, rank_base, row_of_rank, empty_rows, each region starting
+    at a multiple of 256 bytes, zero padded, total a multiple of 256 (>= 256).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+LANES = 64
+ALIGN = 256
+MAX_WAVES = 4096
+WAVES_PER_WORKGROUP = 16
+
+
+def default_n_waves(nnzg: int) -> int:
+    """Worker count the library picks when not told otherwise: whole workgroups
+    of 16 wavefronts, at most 256 of them, no more than the blocks can feed."""
+    nblocks = (nnzg + LANES - 1) // LANES
+    wgs = (nblocks + WAVES_PER_WORKGROUP - 1) // WAVES_PER_WORKGROUP
+    wgs = max(1, min(MAX_WAVES // WAVES_PER_WORKGROUP, wgs))
+    return wgs * WAVES_PER_WORKGROUP
+
+
+def _align(n: int) -> int:
+    return (n + ALIGN - 1) // ALIGN * ALIGN
+
+
+def stream_placement(nblocks: int, n_waves: int):
+    """For every stream position: (block, lane) it is stored at (spec items 2-3)."""
+    base, extra = divmod(nblocks, n_waves)
+    n_w = np.full(n_waves, base, dtype=np.int64)
+    n_w[:extra] += 1
+    b_w = np.concatenate(([0], np.cumsum(n_w)[:-1]))
+    pos = np.arange(nblocks * LANES, dtype=np.int64)
+    blk_of_pos = pos // LANES
+    # worker owning each position: last w with b_w <= block (skip zero-sized workers)
+    w = np.searchsorted(b_w, blk_of_pos, side="right") - 1
+    # workers without blocks all start at block nblocks, which no position has
+    assert (n_w[w] > 0).all()
+    q = pos - LANES * b_w[w]                    # position inside the worker's run
+    nw = n_w[w]
+    n4 = nw // 4
+    rem = nw % 4
+    in4 = q < 256 * n4
+    qq = q - 256 * n4
+    has2 = rem >= 2
+    in2 = (~in4) & has2 & (qq < 128)
+    in1 = (~in4) & (~in2)
+    U = np.where(in4, 4, np.where(in2, 2, 1))
+    sb_blk = np.where(in4, 4 * (q // 256), np.where(in2, 4 * n4, 4 * n4 + np.where(has2, 2, 0)))
+    p = np.where(in4, q % 256, np.where(in2, qq, qq - np.where(has2, 128, 0)))
+    assert (p[in1] < 64).all() and (p >= 0).all()
+    block = b_w[w] + sb_blk + (p % U)
+    lane = p // U
+    return block, lane, b_w
+
+
+def device_blob(c, n_waves: int) -> bytes:
+    """Exact bytes the library must hold on the device for canonical arrays `c`."""
+    if c.G != 16 or c.bits not in (4, 8):
+        raise ValueError("device layout is specified for G=16, bits in {4,8}")
+    nnzg = c.nnzg
+    nblocks = (nnzg + LANES - 1) // LANES
+    code_bytes = c.G * c.bits // 8
+    blk_bytes = (code_bytes + 6) * LANES
+
+    ri = np.asarray(c.rowIndex, dtype=np.int64)
+    counts = ri[1:] - ri[:-1]
+    nonempty = np.nonzero(counts > 0)[0].astype(np.int32)
+    empty = np.nonzero(counts == 0)[0].astype(np.int32)
+    head_pos = ri[:-1][counts > 0]                 # stream position of each row's first group
+
+    blocks = np.zeros((nblocks, blk_bytes), dtype=np.uint8)
+    rank_base = np.zeros(n_waves, dtype=np.int32)
+    if nblocks > 0:
+        block, lane, b_w = stream_placement(nblocks, n_waves)
+        block = block[:nnzg]
+        lane = lane[:nnzg]
+        # codes
+        vals = np.asarray(c.values, dtype=np.uint8).reshape(nnzg, code_bytes)
+        if c.bits == 4:
+            elems = np.empty((nnzg, 16), dtype=np.uint32)
+            elems[:, 0::2] = vals & 0xF
+            elems[:, 1::2] = vals >> 4
+            words = np.zeros((nnzg, 2), dtype=np.uint32)
+            for h in range(2):
+                for m in range(4):
+                    words[:, h] |= elems[:, 8 * h + 2 * m] << np.uint32(4 * m)
+                    words[:, h] |= elems[:, 8 * h + 2 * m + 1] << np.uint32(16 + 4 * m)
+            lane_bytes = words.astype("<u4").view(np.uint8).reshape(nnzg, 8)
+        else:
+            lane_bytes = vals
+        codes_view = blocks[:, :LANES * code_bytes].reshape(nblocks, LANES, code_bytes)
+        codes_view[block, lane, :] = lane_bytes
+        # scale | zero << 16
+        sz = (np.asarray(c.scales, dtype=np.uint32) |
+              (np.asarray(c.zeros, dtype=np.uint32) << np.uint32(16))).astype("<u4")
+        sz_off = LANES * code_bytes
+        sz_view = blocks[:, sz_off:sz_off + LANES * 4].reshape(nblocks, LANES, 4)
+        sz_view[block, lane, :] = sz.view(np.uint8).reshape(nnzg, 4)
+        # group-column | head flag
+        is_head = np.zeros(nnzg, dtype=np.uint16)
+        is_head[head_pos] = 0x8000
+        gcol = np.asarray(c.groups, dtype=np.int64)
+        if gcol.size and gcol.max() >= 0x8000:
+            raise ValueError("group-column does not fit 15 bits")
+        idx = (gcol.astype(np.uint16) | is_head).astype("<u2")
+        idx_off = sz_off + LANES * 4
+        idx_view = blocks[:, idx_off:idx_off + LANES * 2].reshape(nblocks, LANES, 2)
+        idx_view[block, lane, :] = idx.view(np.uint8).reshape(nnzg, 2)
+        # rank_base: heads strictly before the worker's first stream position, minus one
+        first_pos = LANES * b_w
+        rank_base = (np.searchsorted(head_pos, first_pos, side="left") - 1).astype(np.int32)
+    else:
+        rank_base[:] = -1
+
+    parts = [blocks.tobytes(), rank_base.astype("<i4").tobytes(),
+             nonempty.astype("<i4").tobytes(), empty.astype("<i4").tobytes()]
+    out = bytearray()
+    for part in parts:
+        out += part
+        out += b"\0" * (_align(len(out)) - len(out))
+    if len(out) == 0:
+        out += b"\0" * ALIGN
+    return bytes(out)
