@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the GQSA W4S50 G=16 decode GEMV path on one MI355X.
+
+A step is one pass of the hot path over one LLaMA-7B-like decoder layer set at batch 1:
+seven gqsa_gemv calls (q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), W4, 50 %
+of the groups of every row pruned, G = 16.  Successive steps walk a pool of distinct layers
+larger than 1 GB, so every call reads its weights from HBM, as real decoding does (each
+layer's weights are read once per token).  Inputs are resident in HBM before timing starts.
+
+Prints ONE JSON line: value = achieved GB/s over the algorithmic compressed bytes
+(stored groups x 14 B + row pointers + x + y), with the roofline and cpu_baseline objects.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=240)
+    p.add_argument("--warmup", type=int, default=24)
+    p.add_argument("--pool-layers", type=int, default=12, help="distinct layer sets in HBM (12 = 1.07 GB)")
+    p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    p.add_argument("--skip-cpu", action="store_true", help="skip the cpu_baseline leg (for profiling runs)")
+    p.add_argument("--skip-extras", action="store_true", help="skip per-shape / dense / stream-read legs")
+    p.add_argument("--cpu-seconds", type=float, default=12.0)
+    return p.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
+              "(the path shards by output rows, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import gqsa_inputs as gi
+    import paper_2412_17560_amd as gq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no HIP device", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    workers = min(16, os.cpu_count() or 8)
+
+    # ------------------------------------------------------------------ pool of packed layers
+    t_build = time.time()
+    layers = []          # layers[l] = list of (handle, shape_index)
+    info0 = []
+    for l in range(args.pool_layers):
+        mats = []
+        for i, (name, N, K) in enumerate(gi.LLAMA7B_LAYER):
+            W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(2, i) + 100000 * l, workers=workers)
+            h = gq.gqsa_pack(W, 16, 4, 0.5)
+            gq.gqsa_upload(h)
+            mats.append((h, i))
+            if l == 0:
+                info0.append(gq.gqsa_info(h))
+            del W
+        layers.append(mats)
+    bytes_per_call = [inf["algorithmic_bytes"] for inf in info0]
+    bytes_per_step = int(sum(bytes_per_call))
+    pool_bytes = sum(inf["device_bytes"] for inf in info0) * args.pool_layers
+    t_build = time.time() - t_build
+
+    xs = {K: torch.from_numpy(gi.activations(1, K, seed=gi.config_seed(2, 0))).to(dev) for K in (4096, 11008)}
+    ys = [torch.empty((1, N), dtype=torch.float16, device=dev) for (_, N, _) in gi.LLAMA7B_LAYER]
+
+    def enqueue_step(k):
+        for h, i in layers[k % args.pool_layers]:
+            gq.gqsa_gemv(h, xs[gi.LLAMA7B_LAYER[i][2]], ys[i])
+
+    stream = torch.cuda.Stream()
+    calls_per_step = len(gi.LLAMA7B_LAYER)
+
+    def timed_region(fn):
+        """fn enqueues the work on `stream`; returns elapsed ms measured with events on that stream."""
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1)
+
+    with torch.cuda.stream(stream):
+        for k in range(args.warmup):
+            enqueue_step(k)
+    torch.cuda.synchronize()
+
+    eager_ms = timed_region(lambda: [enqueue_step(args.warmup + k) for k in range(args.steps)])
+    mode = "eager"
+    total_ms = eager_ms
+    graph_ms = None
+    if not args.no_graph:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            for k in range(args.steps):
+                enqueue_step(args.warmup + k)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            g.replay()                      # untimed replay
+        torch.cuda.synchronize()
+        graph_ms = timed_region(lambda: g.replay())
+        total_ms = graph_ms
+        mode = "hip_graph_replay"
+
+    ms_per_step = total_ms / args.steps
+    value = bytes_per_step / (ms_per_step * 1e-3) / 1e9
+    us_per_call = ms_per_step * 1e3 / calls_per_step
+
+    out = {
+        "metric": "achieved HBM GB/s per GQSA W4S50 GEMV call (batch 1)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 6),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "llama7b_decode_layer_set_w4s50_g16_batch1",
+            "calls_per_step": calls_per_step,
+            "shapes_NxK": [[N, K] for (_, N, K) in gi.LLAMA7B_LAYER],
+            "bits": 4, "group_size": 16, "sparsity": 0.5, "batch": 1,
+            "algorithmic_bytes_per_step": bytes_per_step,
+            "pool_layers": args.pool_layers,
+            "pool_device_bytes": int(pool_bytes),
+            "launch_mode": mode,
+        },
+        "us_per_call": round(us_per_call, 3),
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "eager_ms_per_step": round(eager_ms / args.steps, 6),
+        "pool_build_s": round(t_build, 1),
+    }
+    # dominant kernel: gqsa_gemv_kernel<4>, one launch per call.  Average launch duration is
+    # the event-timed region divided by the launches in it (so it contains the carry fix-up
+    # launches and the gaps between kernels); bytes are the algorithmic bytes of the calls.
+    launches = args.steps * calls_per_step
+    avg_launch_s = total_ms * 1e-3 / launches
+    achieved = (bytes_per_step / calls_per_step) / avg_launch_s / 1e9
+    out["roofline"] = {
+        "bound": "hbm",
+        "kernel": "gqsa_gemv_kernel<4>",
+        "achieved": round(achieved, 2),
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "avg_launch_us": round(avg_launch_s * 1e6, 3),
+        "algorithmic_bytes_per_launch": int(bytes_per_step / calls_per_step),
+        "traffic": None,
+    }
+
+    # ------------------------------------------------------------------ extras: per shape, baselines
+    if not args.skip_extras:
+        def time_calls(fn_of_k, n=200, warm=20):
+            with torch.cuda.stream(stream):
+                for k in range(warm):
+                    fn_of_k(k)
+            ms = timed_region(lambda: [fn_of_k(warm + k) for k in range(n)])
+            return ms * 1e3 / n   # us per call
+
+        per_shape = []
+        for idx in (0, 4, 6):
+            name, N, K = gi.LLAMA7B_LAYER[idx]
+            hs = [layers[l][idx][0] for l in range(args.pool_layers)]
+            if idx == 0:   # q,k,v,o are four distinct matrices of the same shape per layer
+                hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]
+            us = time_calls(lambda k, hs=hs, K=K, idx=idx: gq.gqsa_gemv(hs[k % len(hs)], xs[K], ys[idx]))
+            us_warm = time_calls(lambda k, hs=hs, K=K, idx=idx: gq.gqsa_gemv(hs[0], xs[K], ys[idx]))
+            b = bytes_per_call[idx]
+            per_shape.append({"shape": f"{N}x{K}", "us_cold": round(us, 3),
+                              "GBps_cold": round(b / us / 1e3, 1),
+                              "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2),
+                              "us_cache_warm": round(us_warm, 3),
+                              "distinct_matrices": len(hs), "mode": "eager back-to-back"})
+        out["per_shape"] = per_shape
+
+        # achievable read ceiling: plain streaming kernel over 2 GiB
+        big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        big.random_(0, 255)
+        sink = torch.zeros(gq.gqsa_stream_read_workgroups(), dtype=torch.int32, device=dev)
+        us = time_calls(lambda k: gq.gqsa_stream_read(big, sink), n=20, warm=3)
+        out["stream_read_GBps"] = round(big.numel() / us / 1e3, 1)
+        del big
+
+        # our own dense fp16 GEMV on the same shapes (pool of distinct fp16 matrices > 1 GB)
+        dense = []
+        for idx in (0, 4, 6):
+            name, N, K = gi.LLAMA7B_LAYER[idx]
+            n_mats = max(2, int((1 << 30) // (N * K * 2)) + 1)
+            Ws = [torch.randn((N, K), dtype=torch.float16, device=dev) * 0.02 for _ in range(n_mats)]
+            yb = torch.empty((1, N), dtype=torch.float16, device=dev)
+            us = time_calls(lambda k, Ws=Ws, K=K, yb=yb: gq.gqsa_dense_f16_gemv(Ws[k % len(Ws)], xs[K], yb))
+            b = N * K * 2 + (N + K) * 2
+            dense.append({"shape": f"{N}x{K}", "us_cold": round(us, 3), "GBps_cold": round(b / us / 1e3, 1)})
+            del Ws
+        out["dense_f16_gemv"] = dense
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    if not args.skip_cpu:
+        import oracle
+        canon = []
+        for i, (name, N, K) in enumerate(gi.LLAMA7B_LAYER):
+            W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(2, i), workers=workers)
+            canon.append(oracle.pack(W, 16, 4, sparsity=0.5))
+            del W
+        xh = {K: xs[K].cpu().numpy() for K in xs}
+        threads = oracle.max_threads()
+        for c in canon:                                  # one untimed pass
+            oracle.gemv(c, xh[c.K], threads=threads)
+        reps = 0
+        t0 = time.time()
+        while time.time() - t0 < args.cpu_seconds:
+            for c in canon:
+                oracle.gemv(c, xh[c.K], threads=threads)
+            reps += 1
+        dt = time.time() - t0
+        out["cpu_baseline"] = {
+            "value": round(bytes_per_step * reps / dt / 1e9, 3),
+            "unit": "GB/s",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": f"{reps} passes over one layer set (7 GEMVs, same shapes and sparsity) in {dt:.1f} s; "
+                      f"{dt / reps * 1e3 / calls_per_step:.2f} ms per call",
+        }
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

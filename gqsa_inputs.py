@@ -112,3 +112,32 @@ def unit_vector(k: int, index: int, batch: int = 1) -> np.ndarray:
 
 def ones_vector(k: int, batch: int = 1) -> np.ndarray:
     return np.ones((batch, k), dtype=np.float16)
+
+
+def dense_weight_chunked(n: int, k: int, seed: int, outliers: bool = True,
+                         sigma: float = 0.02, outlier_frac: float = 0.01,
+                         outlier_gain: float = 20.0, workers: int = 8) -> np.ndarray:
+    """Same distribution as dense_weight, drawn in 16 independent row chunks so that several
+    host threads can fill a large pool quickly.  The result depends on the seed only (the
+    chunking is fixed), not on the number of workers.  Used for benchmark pools."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    n_chunks = 16
+    w = np.empty((n, k), dtype=np.float32)
+    bounds = np.linspace(0, n, n_chunks + 1).astype(np.int64)
+
+    def fill(j):
+        rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, j])))
+        part = w[bounds[j]:bounds[j + 1]]
+        rng.standard_normal(part.shape, dtype=np.float32, out=part)
+        part *= np.float32(sigma)
+
+    with ThreadPoolExecutor(max_workers=max(1, workers)) as ex:
+        list(ex.map(fill, range(n_chunks)))
+    if outliers:
+        ncol = int(round(outlier_frac * k))
+        if ncol > 0:
+            rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 9999])))
+            cols = rng.choice(k, size=ncol, replace=False)
+            w[:, cols] *= np.float32(outlier_gain)
+    return w

@@ -1,0 +1,151 @@
+/*
+ * gqsa.h -- C ABI of the MI355X (gfx950) GQSA group-sparse, group-quantised GEMV.
+ *
+ * The library implements the inference hot path of GQSA ("Group Quantization
+ * and Sparsity for Accelerating LLM Inference"): a linear layer y = W x whose
+ * weight is stored in the paper's Block-Sparse-Row form (Sec. 3.2) -- only the
+ * surviving length-G groups of every output row are kept, as n-bit codes with
+ * one scale and one zero-point per group (Sec. 3.1, Eq. 1-2), a group-column
+ * index per stored group and row pointers -- multiplied at decode time as a
+ * 1xNxK GEMV (Sec. 3.5) with in-register dequantisation (Eq. 3).
+ *
+ * Conventions
+ *   - plain C linkage, plain pointers and sizes; every pointer is marked
+ *     [host] or [device] below; nothing is thrown across the boundary.
+ *   - every call returns a gqsa_status_t; on failure output handles are NULL
+ *     and output buffers are unspecified.
+ *   - a handle owns its host arrays, its device image and its device carry
+ *     workspace; x and y are borrowed for the duration of the enqueued work.
+ *   - pack / import / export / info never touch the GPU and work on a machine
+ *     without one; the device image is created by gqsa_upload or by the first
+ *     gqsa_gemv on the handle.
+ *   - one gqsa_gemv may be in flight per handle at a time (the carry workspace
+ *     is shared); calls on one stream are ordered and therefore safe.
+ */
+#ifndef GQSA_H
+#define GQSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gqsa_matrix* gqsa_handle_t;
+
+typedef enum {
+    GQSA_OK = 0,
+    GQSA_ERR_NULL = 1,         /* a required pointer is NULL */
+    GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K/G > 32768, inconsistent arrays */
+    GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 16, batch outside 1..16 */
+    GQSA_ERR_RANGE = 4,        /* sparsity outside [0,1], keep count outside [0,K/G], non-finite W */
+    GQSA_ERR_ALLOC = 5,        /* host allocation failed */
+    GQSA_ERR_HIP = 6,          /* a HIP runtime call failed (no device, launch error, ...) */
+    GQSA_ERR_BUFSIZE = 7,      /* caller buffer smaller than required */
+    GQSA_ERR_ALIGN = 8         /* device pointer not 16-byte aligned */
+} gqsa_status_t;
+
+typedef struct {
+    int64_t N;                  /* output rows */
+    int64_t K;                  /* reduction length */
+    int32_t G;                  /* group size */
+    int32_t bits;               /* code width */
+    int64_t nnz_groups;         /* stored groups = rowIndex[N] */
+    int64_t values_bytes;       /* bytes of the canonical `values` array */
+    int64_t n_blocks;           /* 64-group blocks of the device stream */
+    int32_t n_waves;            /* wavefront workers the stream is partitioned over */
+    int32_t needs_fixup;        /* 1 if some row spans two workers (carry fix-up runs) */
+    int64_t n_empty_rows;       /* rows without any stored group */
+    int64_t device_bytes;       /* size of the device image */
+    int64_t algorithmic_bytes;  /* compressed bytes one batch-1 call must move (see README of bench) */
+    int32_t on_device;          /* 1 once the device image exists */
+    int32_t reserved;
+} gqsa_info_t;
+
+/*
+ * Offline pre-processing (Sec. 3.2; Fig. 3): group the fp32 matrix along K in
+ * runs of G, score every group by its sum of squares, prune the least salient
+ * groups of every row and quantise the kept ones with Eq. 1-2.
+ *   W_host   [host] row-major fp32 [N,K], finite
+ *   sparsity fraction of the K/G groups pruned in EVERY row; the pruned count is
+ *            floor(sparsity*K/G + 0.5); equal saliencies prune the lower column first
+ *   out      [host] receives the handle
+ * Scale is stored as fp16 (floored at 2^-14); zero-point = round-half-even(-min/scale)
+ * clamped to +-2048 and stored as fp16; codes = clamp(round(w/scale)+zero, 0, 2^bits-1).
+ */
+gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bits,
+                        double sparsity, gqsa_handle_t* out);
+
+/* Same, with the kept-group count of every row given (imbalanced sparsity; the worked
+ * example of Sec. 3.2 keeps 1, 2, 0, 1 groups).  keep_per_row [host] int32[N]. */
+gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, int bits,
+                             const int32_t* keep_per_row, gqsa_handle_t* out);
+
+/*
+ * Build a handle from existing canonical arrays (the BSR listing of Sec. 3.2 plus the
+ * per-group parameters of Eq. 1, which Sec. 3.4 fine-tunes freely -- so scale and zero
+ * are arbitrary finite fp16 values here).  All arrays [host]; they are copied.
+ *   rowIndex int32[N+1] non-decreasing from 0; groups int32[nnzg] strictly ascending
+ *   inside a row, in [0,K/G); values uint8[nnzg*G*bits/8] (4-bit: element 2b in the low
+ *   nibble of byte b, 2b+1 in the high nibble); scales_f16/zeros_f16 uint16[nnzg].
+ */
+gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const uint8_t* values,
+                          const uint16_t* scales_f16, const uint16_t* zeros_f16,
+                          int64_t N, int64_t K, int G, int bits, gqsa_handle_t* out);
+
+/* Re-partition the group stream over n_waves wavefront workers (1..65536) and rebuild the
+ * host copy of the device image.  Only before the handle is uploaded.  The default chosen
+ * by pack/import is 16*min(256, ceil(n_blocks/16)). */
+gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_waves);
+
+/* Create the device image and carry workspace on the current HIP device (synchronous). */
+gqsa_status_t gqsa_upload(gqsa_handle_t h);
+
+/*
+ * The hot path (Sec. 3.5): enqueue y = W^ x on `hip_stream` and return.
+ *   x_dev [device] fp16 [batch,K] row-major, 16-byte aligned
+ *   y_dev [device] fp16 [batch,N] row-major, fully overwritten; rows without stored
+ *         groups receive +0
+ *   batch 1..16
+ *   hip_stream a hipStream_t (NULL = the default stream)
+ * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
+ * bit-identical from run to run.  Does not synchronise.
+ */
+gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
+                        void* hip_stream);
+
+gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out);
+
+/* Copy the canonical arrays out; any pointer may be NULL to skip it.  Sizes from gqsa_info:
+ * rowIndex N+1, groups/scales/zeros nnz_groups, values values_bytes. */
+gqsa_status_t gqsa_export(gqsa_handle_t h, int32_t* rowIndex, int32_t* groups, uint8_t* values,
+                          uint16_t* scales_f16, uint16_t* zeros_f16);
+
+/* Copy the exact bytes of the device image (host copy) into host_buf; bytes >= device_bytes. */
+gqsa_status_t gqsa_export_device_blob(gqsa_handle_t h, void* host_buf, size_t bytes);
+
+void gqsa_free(gqsa_handle_t h);
+
+const char* gqsa_status_string(gqsa_status_t s);
+
+/* ------------------------------------------------------------------------------------------
+ * Side-by-side kernels measured next to the GQSA path (same GPU, same harness): a dense fp16
+ * GEMV and a dense 4-bit group-quantised GEMV (the paper's W4 baseline of Tab. 4 / Tab. 10,
+ * i.e. Eq. 1-3 with nothing pruned), plus a read-only streaming kernel that measures the
+ * achievable HBM read rate.
+ * ------------------------------------------------------------------------------------------ */
+
+/* y[batch,N] = W[N,K] x[batch,K], all fp16 [device], fp32 accumulation. */
+gqsa_status_t gqsa_dense_f16_gemv(const void* W_dev, const void* x_dev, void* y_dev,
+                                  int64_t N, int64_t K, int batch, void* hip_stream);
+
+/* Sum `bytes` (multiple of 16) of device memory into sink_dev[0..n_wg-1] (uint32 each, n_wg
+ * from gqsa_stream_read_workgroups()); a pure read at full width. */
+gqsa_status_t gqsa_stream_read(const void* buf_dev, size_t bytes, void* sink_dev, void* hip_stream);
+int gqsa_stream_read_workgroups(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GQSA_H */

@@ -23,10 +23,13 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     elements 8h..8h+7 of the group, element 8h+2m in bits 4m..4m+3 and element
     8h+2m+1 in bits 16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j of the
     lane's 16 bytes is element j.
- 5. Side tables (int32): rank_base[n_waves] = (number of row-head groups at
-    stream positions before worker w's first position) - 1; row_of_rank[r] =
-    index of the r-th non-empty row; empty_rows = indices of the empty rows.
- 6. Blob = blocks, rank_base, row_of_rank, empty_rows, each region starting
+ 5. Side tables (int32): wave_info[n_waves][2] = {rank_base, tail_closed} with
+    rank_base = (number of row-head groups at stream positions before worker
+    w's first position) - 1 and tail_closed = 1 if the first position after the
+    worker's run is at or beyond nnzg or holds a row-head group, else 0;
+    row_of_rank[r] = index of the r-th non-empty row; empty_rows = indices of
+    the empty rows.
+ 6. Blob = blocks, wave_info, row_of_rank, empty_rows, each region starting
     at a multiple of 256 bytes, zero padded, total a multiple of 256 (>= 256).
 """
 from __future__ import annotations
@@ -98,7 +101,9 @@ def device_blob(c, n_waves: int) -> bytes:
     head_pos = ri[:-1][counts > 0]                 # stream position of each row's first group
 
     blocks = np.zeros((nblocks, blk_bytes), dtype=np.uint8)
-    rank_base = np.zeros(n_waves, dtype=np.int32)
+    wave_info = np.zeros((n_waves, 2), dtype=np.int32)
+    wave_info[:, 0] = -1
+    wave_info[:, 1] = 1
     if nblocks > 0:
         block, lane, b_w = stream_placement(nblocks, n_waves)
         block = block[:nnzg]
@@ -137,11 +142,17 @@ def device_blob(c, n_waves: int) -> bytes:
         idx_view[block, lane, :] = idx.view(np.uint8).reshape(nnzg, 2)
         # rank_base: heads strictly before the worker's first stream position, minus one
         first_pos = LANES * b_w
-        rank_base = (np.searchsorted(head_pos, first_pos, side="left") - 1).astype(np.int32)
-    else:
-        rank_base[:] = -1
+        wave_info[:, 0] = np.searchsorted(head_pos, first_pos, side="left") - 1
+        # tail_closed: does the row that is open at the end of the run stop there?
+        base, extra = divmod(nblocks, n_waves)
+        n_w = np.full(n_waves, base, dtype=np.int64)
+        n_w[:extra] += 1
+        end_pos = LANES * (b_w + n_w)
+        head_set = np.zeros(nblocks * LANES + 1, dtype=bool)
+        head_set[head_pos] = True
+        wave_info[:, 1] = np.where(end_pos >= nnzg, 1, head_set[np.minimum(end_pos, nblocks * LANES)])
 
-    parts = [blocks.tobytes(), rank_base.astype("<i4").tobytes(),
+    parts = [blocks.tobytes(), wave_info.astype("<i4").tobytes(),
              nonempty.astype("<i4").tobytes(), empty.astype("<i4").tobytes()]
     out = bytearray()
     for part in parts:

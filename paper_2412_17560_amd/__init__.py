@@ -1,0 +1,25 @@
+"""MI355X-native GQSA group-sparse, group-quantised GEMV (paper Sec. 3.2, 3.5).
+
+Thin ctypes binding over libgqsa.so (C ABI declared in include/gqsa.h).  The
+binding only marshals arguments: every step of the hot path runs in the HIP
+kernels.  PyTorch is used by callers for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    GqsaError,
+    GqsaHandle,
+    gqsa_dense_f16_gemv,
+    gqsa_export,
+    gqsa_export_device_blob,
+    gqsa_free,
+    gqsa_gemv,
+    gqsa_import,
+    gqsa_info,
+    gqsa_pack,
+    gqsa_pack_rows,
+    gqsa_set_partition,
+    gqsa_status_string,
+    gqsa_stream_read,
+    gqsa_stream_read_workgroups,
+    gqsa_upload,
+    library_path,
+)

@@ -1,0 +1,238 @@
+"""ctypes marshalling for libgqsa.so -- same names as the C ABI, no arithmetic here."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+class GqsaError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {gqsa_status_string(status)} (status {status})")
+        self.status = status
+
+
+class _Info(C.Structure):
+    _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("G", C.c_int32), ("bits", C.c_int32),
+                ("nnz_groups", C.c_int64), ("values_bytes", C.c_int64), ("n_blocks", C.c_int64),
+                ("n_waves", C.c_int32), ("needs_fixup", C.c_int32), ("n_empty_rows", C.c_int64),
+                ("device_bytes", C.c_int64), ("algorithmic_bytes", C.c_int64),
+                ("on_device", C.c_int32), ("reserved", C.c_int32)]
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def _lib():
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = _build.LIB
+    if not os.path.exists(path):
+        _build.build()           # nothing built yet: build once, in-tree
+    if not os.path.exists(path):
+        raise ImportError(f"libgqsa.so is missing at {path}; run `python -m paper_2412_17560_amd.build`")
+    lib = C.CDLL(path)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int
+    lib.gqsa_pack.restype = C.c_int
+    lib.gqsa_pack.argtypes = [vp, i64, i64, i32, i32, C.c_double, C.POINTER(vp)]
+    lib.gqsa_pack_rows.restype = C.c_int
+    lib.gqsa_pack_rows.argtypes = [vp, i64, i64, i32, i32, vp, C.POINTER(vp)]
+    lib.gqsa_import.restype = C.c_int
+    lib.gqsa_import.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, C.POINTER(vp)]
+    lib.gqsa_set_partition.restype = C.c_int
+    lib.gqsa_set_partition.argtypes = [vp, i32]
+    lib.gqsa_upload.restype = C.c_int
+    lib.gqsa_upload.argtypes = [vp]
+    lib.gqsa_gemv.restype = C.c_int
+    lib.gqsa_gemv.argtypes = [vp, vp, vp, i32, vp]
+    lib.gqsa_info.restype = C.c_int
+    lib.gqsa_info.argtypes = [vp, C.POINTER(_Info)]
+    lib.gqsa_export.restype = C.c_int
+    lib.gqsa_export.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.gqsa_export_device_blob.restype = C.c_int
+    lib.gqsa_export_device_blob.argtypes = [vp, vp, C.c_size_t]
+    lib.gqsa_free.restype = None
+    lib.gqsa_free.argtypes = [vp]
+    lib.gqsa_status_string.restype = C.c_char_p
+    lib.gqsa_status_string.argtypes = [C.c_int]
+    lib.gqsa_dense_f16_gemv.restype = C.c_int
+    lib.gqsa_dense_f16_gemv.argtypes = [vp, vp, vp, i64, i64, i32, vp]
+    lib.gqsa_stream_read.restype = C.c_int
+    lib.gqsa_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+    lib.gqsa_stream_read_workgroups.restype = C.c_int
+    lib.gqsa_stream_read_workgroups.argtypes = []
+    _LIB = lib
+    return lib
+
+
+def gqsa_status_string(status: int) -> str:
+    return _lib().gqsa_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise GqsaError(status, what)
+
+
+class GqsaHandle:
+    """Owns one gqsa_handle_t; freed on gqsa_free() or garbage collection."""
+
+    def __init__(self, ptr: int):
+        self.ptr = C.c_void_p(ptr)
+
+    def __del__(self):
+        try:
+            gqsa_free(self)
+        except Exception:
+            pass
+
+
+def _np_ptr(a):
+    return None if a is None else C.c_void_p(a.ctypes.data)
+
+
+def gqsa_pack(W: np.ndarray, G: int = 16, bits: int = 4, sparsity: float = 0.5) -> GqsaHandle:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    if W.ndim != 2:
+        raise ValueError("W must be [N, K]")
+    out = C.c_void_p()
+    _check(_lib().gqsa_pack(_np_ptr(W), W.shape[0], W.shape[1], G, bits, float(sparsity),
+                            C.byref(out)), "gqsa_pack")
+    return GqsaHandle(out.value)
+
+
+def gqsa_pack_rows(W: np.ndarray, keep_per_row: np.ndarray, G: int = 16, bits: int = 4) -> GqsaHandle:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    keep = np.ascontiguousarray(keep_per_row, dtype=np.int32)
+    if W.ndim != 2 or keep.shape != (W.shape[0],):
+        raise ValueError("W must be [N, K] and keep_per_row [N]")
+    out = C.c_void_p()
+    _check(_lib().gqsa_pack_rows(_np_ptr(W), W.shape[0], W.shape[1], G, bits, _np_ptr(keep),
+                                 C.byref(out)), "gqsa_pack_rows")
+    return GqsaHandle(out.value)
+
+
+def gqsa_import(rowIndex, groups, values, scales_f16, zeros_f16, N: int, K: int, G: int = 16,
+                bits: int = 4) -> GqsaHandle:
+    ri = np.ascontiguousarray(rowIndex, dtype=np.int32)
+    gr = np.ascontiguousarray(groups, dtype=np.int32)
+    va = np.ascontiguousarray(values, dtype=np.uint8)
+    sc = np.ascontiguousarray(scales_f16, dtype=np.uint16)
+    ze = np.ascontiguousarray(zeros_f16, dtype=np.uint16)
+    if ri.shape != (N + 1,):
+        raise ValueError("rowIndex must have N+1 entries")
+    nnz = int(ri[-1])
+    if gr.size != nnz or sc.size != nnz or ze.size != nnz or va.size != nnz * G * bits // 8:
+        raise ValueError("array sizes do not match rowIndex[N]")
+    out = C.c_void_p()
+    _check(_lib().gqsa_import(_np_ptr(ri), _np_ptr(gr), _np_ptr(va), _np_ptr(sc), _np_ptr(ze),
+                              N, K, G, bits, C.byref(out)), "gqsa_import")
+    return GqsaHandle(out.value)
+
+
+def gqsa_set_partition(h: GqsaHandle, n_waves: int) -> None:
+    _check(_lib().gqsa_set_partition(h.ptr, int(n_waves)), "gqsa_set_partition")
+
+
+def gqsa_upload(h: GqsaHandle) -> None:
+    _check(_lib().gqsa_upload(h.ptr), "gqsa_upload")
+
+
+def gqsa_info(h: GqsaHandle) -> dict:
+    info = _Info()
+    _check(_lib().gqsa_info(h.ptr, C.byref(info)), "gqsa_info")
+    return {name: getattr(info, name) for name, _ in _Info._fields_ if name != "reserved"}
+
+
+def gqsa_export(h: GqsaHandle) -> dict:
+    info = gqsa_info(h)
+    nnz = info["nnz_groups"]
+    ri = np.zeros(info["N"] + 1, dtype=np.int32)
+    gr = np.zeros(nnz, dtype=np.int32)
+    va = np.zeros(info["values_bytes"], dtype=np.uint8)
+    sc = np.zeros(nnz, dtype=np.uint16)
+    ze = np.zeros(nnz, dtype=np.uint16)
+    _check(_lib().gqsa_export(h.ptr, _np_ptr(ri), _np_ptr(gr) if nnz else None,
+                              _np_ptr(va) if nnz else None, _np_ptr(sc) if nnz else None,
+                              _np_ptr(ze) if nnz else None), "gqsa_export")
+    return {"rowIndex": ri, "groups": gr, "values": va, "scales": sc, "zeros": ze}
+
+
+def gqsa_export_device_blob(h: GqsaHandle) -> bytes:
+    n = gqsa_info(h)["device_bytes"]
+    buf = np.zeros(n, dtype=np.uint8)
+    _check(_lib().gqsa_export_device_blob(h.ptr, _np_ptr(buf), n), "gqsa_export_device_blob")
+    return buf.tobytes()
+
+
+def gqsa_free(h: GqsaHandle) -> None:
+    if h.ptr is not None and h.ptr.value:
+        _lib().gqsa_free(h.ptr)
+        h.ptr = C.c_void_p()
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def _dev_ptr(t, dtype_name: str, what: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous device tensor")
+    if str(t.dtype) != dtype_name:
+        raise ValueError(f"{what} must be {dtype_name}")
+    return C.c_void_p(t.data_ptr())
+
+
+def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None):
+    """y[batch,N] (fp16, device) = W^ x[batch,K]; enqueues on `stream` (default: torch's current)."""
+    import torch
+    info = gqsa_info(h)
+    if x.dim() == 1:
+        x = x.unsqueeze(0)
+    batch = x.shape[0]
+    if x.shape[1] != info["K"]:
+        raise ValueError("x must be [batch, K]")
+    if y is None:
+        y = torch.empty((batch, info["N"]), dtype=torch.float16, device=x.device)
+    if tuple(y.shape) != (batch, info["N"]):
+        raise ValueError("y must be [batch, N]")
+    _check(_lib().gqsa_gemv(h.ptr, _dev_ptr(x, "torch.float16", "x"),
+                            _dev_ptr(y, "torch.float16", "y"), batch, _stream_ptr(stream)),
+           "gqsa_gemv")
+    return y
+
+
+def gqsa_dense_f16_gemv(W, x, y=None, stream=None):
+    import torch
+    if x.dim() == 1:
+        x = x.unsqueeze(0)
+    N, K = W.shape
+    batch = x.shape[0]
+    if y is None:
+        y = torch.empty((batch, N), dtype=torch.float16, device=x.device)
+    _check(_lib().gqsa_dense_f16_gemv(_dev_ptr(W, "torch.float16", "W"),
+                                      _dev_ptr(x, "torch.float16", "x"),
+                                      _dev_ptr(y, "torch.float16", "y"), N, K, batch,
+                                      _stream_ptr(stream)), "gqsa_dense_f16_gemv")
+    return y
+
+
+def gqsa_stream_read_workgroups() -> int:
+    return int(_lib().gqsa_stream_read_workgroups())
+
+
+def gqsa_stream_read(buf, sink, stream=None) -> None:
+    nbytes = buf.numel() * buf.element_size()
+    _check(_lib().gqsa_stream_read(C.c_void_p(buf.data_ptr()), nbytes, C.c_void_p(sink.data_ptr()),
+                                   _stream_ptr(stream)), "gqsa_stream_read")

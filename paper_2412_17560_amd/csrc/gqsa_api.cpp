@@ -1,0 +1,193 @@
+// extern "C" surface of libgqsa: argument checking, handle life-cycle, export/import.
+// The arithmetic lives in gqsa_pack.cpp (host) and gqsa_gemv.hip (device).
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "gqsa_internal.hpp"
+
+namespace {
+
+gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
+{
+    if (N <= 0 || K <= 0 || G <= 0) return GQSA_ERR_SHAPE;
+    if (bits != 4 && bits != 8) return GQSA_ERR_UNSUPPORTED;
+    if (G != 16) return GQSA_ERR_UNSUPPORTED;
+    if (K % G != 0) return GQSA_ERR_SHAPE;
+    if (K / G > gqsa::kMaxGroupColumns) return GQSA_ERR_SHAPE;
+    if (N > (int64_t{1} << 30)) return GQSA_ERR_SHAPE;
+    return GQSA_OK;
+}
+
+gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
+{
+    if (st == GQSA_OK) {
+        const int64_t nb = (m->nnzg() + gqsa::kLanes - 1) / gqsa::kLanes;
+        st = gqsa::build_image(m, gqsa::default_n_waves(nb));
+    }
+    if (st != GQSA_OK) {
+        delete m;
+        return st;
+    }
+    *out = m;
+    return GQSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bits,
+                        double sparsity, gqsa_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!W_host || !out) return GQSA_ERR_NULL;
+    if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
+    if (!(sparsity >= 0.0 && sparsity <= 1.0)) return GQSA_ERR_RANGE;
+    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
+    if (!m) return GQSA_ERR_ALLOC;
+    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, nullptr, sparsity, m), out);
+}
+
+gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, int bits,
+                             const int32_t* keep_per_row, gqsa_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!W_host || !out || !keep_per_row) return GQSA_ERR_NULL;
+    if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
+    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
+    if (!m) return GQSA_ERR_ALLOC;
+    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, keep_per_row, 0.0, m), out);
+}
+
+gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const uint8_t* values,
+                          const uint16_t* scales_f16, const uint16_t* zeros_f16,
+                          int64_t N, int64_t K, int G, int bits, gqsa_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!rowIndex || !out) return GQSA_ERR_NULL;
+    if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
+    const int64_t kg = K / G;
+    if (rowIndex[0] != 0) return GQSA_ERR_SHAPE;
+    for (int64_t n = 0; n < N; ++n) {
+        const int64_t cnt = static_cast<int64_t>(rowIndex[n + 1]) - rowIndex[n];
+        if (cnt < 0 || cnt > kg) return GQSA_ERR_SHAPE;
+    }
+    const int64_t nnz = rowIndex[N];
+    if (nnz > 0 && (!groups || !values || !scales_f16 || !zeros_f16)) return GQSA_ERR_NULL;
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t g = rowIndex[n]; g < rowIndex[n + 1]; ++g) {
+            if (groups[g] < 0 || groups[g] >= kg) return GQSA_ERR_SHAPE;
+            if (g > rowIndex[n] && groups[g] <= groups[g - 1]) return GQSA_ERR_SHAPE;
+        }
+    }
+    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
+    if (!m) return GQSA_ERR_ALLOC;
+    m->N = N; m->K = K; m->G = G; m->bits = bits;
+    try {
+        m->rowIndex.assign(rowIndex, rowIndex + N + 1);
+        m->groups.assign(groups, groups + nnz);
+        m->values.assign(values, values + nnz * (G * bits / 8));
+        m->scales.assign(scales_f16, scales_f16 + nnz);
+        m->zeros.assign(zeros_f16, zeros_f16 + nnz);
+    } catch (const std::bad_alloc&) {
+        delete m;
+        return GQSA_ERR_ALLOC;
+    }
+    return finish(m, GQSA_OK, out);
+}
+
+gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_waves)
+{
+    if (!h) return GQSA_ERR_NULL;
+    if (h->d_image) return GQSA_ERR_UNSUPPORTED;
+    if (n_waves < 1 || n_waves > gqsa::kMaxWaves) return GQSA_ERR_RANGE;
+    return gqsa::build_image(h, n_waves);
+}
+
+gqsa_status_t gqsa_upload(gqsa_handle_t h)
+{
+    if (!h) return GQSA_ERR_NULL;
+    if (h->d_image) return GQSA_OK;
+    return gqsa::device_upload(h);
+}
+
+gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
+                        void* hip_stream)
+{
+    if (!h || !x_dev || !y_dev) return GQSA_ERR_NULL;
+    if (batch < 1 || batch > gqsa::kMaxBatch) return GQSA_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x_dev) & 15u) != 0) return GQSA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(y_dev) & 1u) != 0) return GQSA_ERR_ALIGN;
+    if (!h->d_image) {
+        if (gqsa_status_t st = gqsa::device_upload(h)) return st;
+    }
+    return gqsa::device_gemv(h, x_dev, y_dev, batch, hip_stream);
+}
+
+gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)
+{
+    if (!h || !out) return GQSA_ERR_NULL;
+    std::memset(out, 0, sizeof(*out));
+    out->N = h->N;
+    out->K = h->K;
+    out->G = h->G;
+    out->bits = h->bits;
+    out->nnz_groups = h->nnzg();
+    out->values_bytes = h->nnzg() * h->code_bytes();
+    out->n_blocks = h->n_blocks;
+    out->n_waves = h->n_waves;
+    out->needs_fixup = h->needs_fixup;
+    out->n_empty_rows = h->n_empty;
+    out->device_bytes = static_cast<int64_t>(h->map.total);
+    out->algorithmic_bytes = h->nnzg() * (h->code_bytes() + 6) + (h->N + 1) * 4 + (h->K + h->N) * 2;
+    out->on_device = h->d_image ? 1 : 0;
+    return GQSA_OK;
+}
+
+gqsa_status_t gqsa_export(gqsa_handle_t h, int32_t* rowIndex, int32_t* groups, uint8_t* values,
+                          uint16_t* scales_f16, uint16_t* zeros_f16)
+{
+    if (!h) return GQSA_ERR_NULL;
+    if (rowIndex) std::memcpy(rowIndex, h->rowIndex.data(), h->rowIndex.size() * 4);
+    if (groups && !h->groups.empty()) std::memcpy(groups, h->groups.data(), h->groups.size() * 4);
+    if (values && !h->values.empty()) std::memcpy(values, h->values.data(), h->values.size());
+    if (scales_f16 && !h->scales.empty())
+        std::memcpy(scales_f16, h->scales.data(), h->scales.size() * 2);
+    if (zeros_f16 && !h->zeros.empty())
+        std::memcpy(zeros_f16, h->zeros.data(), h->zeros.size() * 2);
+    return GQSA_OK;
+}
+
+gqsa_status_t gqsa_export_device_blob(gqsa_handle_t h, void* host_buf, size_t bytes)
+{
+    if (!h || !host_buf) return GQSA_ERR_NULL;
+    if (bytes < h->image.size()) return GQSA_ERR_BUFSIZE;
+    std::memcpy(host_buf, h->image.data(), h->image.size());
+    return GQSA_OK;
+}
+
+void gqsa_free(gqsa_handle_t h)
+{
+    if (!h) return;
+    gqsa::device_release(h);
+    delete h;
+}
+
+const char* gqsa_status_string(gqsa_status_t s)
+{
+    switch (s) {
+        case GQSA_OK: return "ok";
+        case GQSA_ERR_NULL: return "null pointer";
+        case GQSA_ERR_SHAPE: return "bad shape";
+        case GQSA_ERR_UNSUPPORTED: return "unsupported format or batch";
+        case GQSA_ERR_RANGE: return "value out of range";
+        case GQSA_ERR_ALLOC: return "host allocation failed";
+        case GQSA_ERR_HIP: return "HIP runtime error";
+        case GQSA_ERR_BUFSIZE: return "buffer too small";
+        case GQSA_ERR_ALIGN: return "misaligned device pointer";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Internal definitions shared by the host packer, the device-image builder and the
+// HIP launch code of libgqsa.  Not part of the public ABI.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "gqsa.h"
+
+namespace gqsa {
+
+constexpr int kLanes = 64;             // one stored group per lane per block
+constexpr int kWavesPerWorkgroup = 16; // 1024 threads: one workgroup per compute unit
+constexpr int kMaxDefaultWorkgroups = 256;  // MI355X: 256 compute units
+constexpr int kMaxWaves = 65536;
+constexpr int kMaxBatch = 16;
+constexpr int64_t kMaxGroupColumns = 32768; // 15-bit group-column + head flag in 16 bits
+constexpr size_t kAlign = 256;
+
+// Offsets (bytes) of the regions inside the device image.
+struct ImageMap {
+    size_t blocks = 0;      // n_blocks * block_bytes
+    size_t wave_info = 0;   // n_waves * {int32 rank_base, int32 tail_closed}
+    size_t row_of_rank = 0; // int32 per non-empty row
+    size_t empty_rows = 0;  // int32 per empty row
+    size_t total = 0;
+};
+
+// Per-worker record the GEMV kernel leaves for the carry fix-up.
+struct CarryRecord {
+    float lead;    // sum of the groups before the worker's first row head
+    float tail;    // sum of the groups after its last row head (or all, if it has none)
+    int32_t heads; // row heads inside the worker's run
+    int32_t pad;
+};
+
+}  // namespace gqsa
+
+struct gqsa_matrix {
+    int64_t N = 0, K = 0;
+    int G = 0, bits = 0;
+    // canonical arrays (Sec. 3.2 listing + Eq. 1 parameters)
+    std::vector<int32_t> rowIndex;
+    std::vector<int32_t> groups;
+    std::vector<uint8_t> values;
+    std::vector<uint16_t> scales;
+    std::vector<uint16_t> zeros;
+    // device image (host copy) and its map
+    int n_waves = 0;
+    int64_t n_blocks = 0;
+    int64_t n_empty = 0;
+    int needs_fixup = 0;
+    gqsa::ImageMap map;
+    std::vector<uint8_t> image;
+    // device side
+    int device = -1;
+    void* d_image = nullptr;
+    void* d_carry = nullptr;  // n_waves * kMaxBatch CarryRecord
+
+    int64_t nnzg() const { return rowIndex.empty() ? 0 : rowIndex.back(); }
+    int code_bytes() const { return G * bits / 8; }
+    int block_bytes() const { return (code_bytes() + 6) * gqsa::kLanes; }
+};
+
+namespace gqsa {
+
+// host packer (gqsa_pack.cpp)
+gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
+                         const int32_t* keep_per_row, double sparsity, gqsa_matrix* m);
+int default_n_waves(int64_t n_blocks);
+gqsa_status_t build_image(gqsa_matrix* m, int n_waves);
+
+// device side (gqsa_gemv.hip)
+gqsa_status_t device_upload(gqsa_matrix* m);
+void device_release(gqsa_matrix* m);
+gqsa_status_t device_gemv(gqsa_matrix* m, const void* x, void* y, int batch, void* stream);
+
+}  // namespace gqsa

@@ -1,0 +1,288 @@
+// Host side of libgqsa: offline pre-processing of a dense matrix into the GQS layer's
+// storage (paper Sec. 3.2) and construction of the device image.
+//
+//   - group pruning: weights are grouped along the row (K) dimension in runs of G, each
+//     group gets one saliency, the least salient groups of a row are dropped (Fig. 3);
+//     here the saliency is the group's sum of squares, because the Hessian metric of
+//     Eq. 4 needs calibration activations;
+//   - quantisation of the kept groups: Eq. 1 (scale, zero-point) and Eq. 2 (codes);
+//   - storage: the BSR arrays rowIndex / groups / values of the Sec. 3.2 listing plus
+//     one fp16 scale and zero per stored group.
+//
+// Nothing in this file touches the GPU.
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <numeric>
+#include <thread>
+
+#include "gqsa_internal.hpp"
+
+namespace gqsa {
+namespace {
+
+inline uint16_t half_bits(float f)
+{
+    _Float16 h = static_cast<_Float16>(f);  // round-to-nearest-even
+    uint16_t b;
+    std::memcpy(&b, &h, 2);
+    return b;
+}
+
+inline float half_value(uint16_t b)
+{
+    _Float16 h;
+    std::memcpy(&h, &b, 2);
+    return static_cast<float>(h);
+}
+
+// Eq. 1 and Eq. 2 on one kept group of G weights.  The scale is rounded to fp16 first and
+// the rounded value is the one the zero-point and the codes are derived from, so that the
+// kernel's (q - z) * s uses exactly the parameters the codes were made with.
+void quantise_group(const float* w, int G, int bits, uint8_t* q_out, uint16_t* s_out,
+                    uint16_t* z_out)
+{
+    const float levels = static_cast<float>((1 << bits) - 1);
+    const auto mm = std::minmax_element(w, w + G);
+    const float lo = *mm.first, hi = *mm.second;
+    float s = (hi - lo) / levels;
+    uint16_t sb = half_bits(s);
+    s = half_value(sb);
+    constexpr float kMinScale = 0x1p-14f;  // smallest normal fp16: constant groups, underflow
+    if (!(s >= kMinScale)) {
+        s = kMinScale;
+        sb = half_bits(s);
+    }
+    float z = std::nearbyint(-lo / s);     // round-half-even; Eq. 1 has no clamp to the code range
+    z = std::min(2048.0f, std::max(-2048.0f, z));  // keep it exact in fp16
+    *s_out = sb;
+    *z_out = half_bits(z);
+    for (int j = 0; j < G; ++j) {
+        float q = std::nearbyint(w[j] / s) + z;
+        q = std::min(levels, std::max(0.0f, q));
+        q_out[j] = static_cast<uint8_t>(q);
+    }
+}
+
+// Kept group-columns of one row, ascending.  Order of pruning: ascending saliency, and
+// among equal saliencies the lower column goes first.
+bool select_row(const float* wrow, int64_t kg, int G, int64_t keep, std::vector<double>& sal,
+                std::vector<int32_t>& order, std::vector<int32_t>& kept)
+{
+    bool finite = true;
+    for (int64_t c = 0; c < kg; ++c) {
+        double acc = 0.0;
+        const float* p = wrow + c * G;
+        for (int j = 0; j < G; ++j) acc += static_cast<double>(p[j]) * static_cast<double>(p[j]);
+        sal[c] = acc;
+        finite &= std::isfinite(acc);
+    }
+    kept.clear();
+    if (keep == 0 || !finite) return finite;
+    std::iota(order.begin(), order.end(), 0);
+    const int64_t drop = kg - keep;
+    auto less = [&](int32_t a, int32_t b) {
+        return sal[a] < sal[b] || (sal[a] == sal[b] && a < b);
+    };
+    if (drop > 0) std::nth_element(order.begin(), order.begin() + drop, order.end(), less);
+    kept.assign(order.begin() + drop, order.end());
+    std::sort(kept.begin(), kept.end());
+    return true;
+}
+
+int64_t balanced_keep(int64_t kg, double sparsity)
+{
+    double drop = std::floor(sparsity * static_cast<double>(kg) + 0.5);
+    drop = std::min(static_cast<double>(kg), std::max(0.0, drop));
+    return kg - static_cast<int64_t>(drop);
+}
+
+}  // namespace
+
+gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
+                         const int32_t* keep_per_row, double sparsity, gqsa_matrix* m)
+{
+    const int64_t kg = K / G;
+    const int cb = G * bits / 8;
+    m->N = N; m->K = K; m->G = G; m->bits = bits;
+    try {
+        m->rowIndex.assign(static_cast<size_t>(N) + 1, 0);
+    } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
+
+    const int64_t uniform_keep = keep_per_row ? -1 : balanced_keep(kg, sparsity);
+    int64_t total = 0;
+    for (int64_t n = 0; n < N; ++n) {
+        const int64_t keep = keep_per_row ? keep_per_row[n] : uniform_keep;
+        if (keep < 0 || keep > kg) return GQSA_ERR_RANGE;
+        total += keep;
+        if (total > std::numeric_limits<int32_t>::max()) return GQSA_ERR_SHAPE;
+        m->rowIndex[n + 1] = static_cast<int32_t>(total);
+    }
+    try {
+        m->groups.assign(total, 0);
+        m->values.assign(static_cast<size_t>(total) * cb, 0);
+        m->scales.assign(total, 0);
+        m->zeros.assign(total, 0);
+    } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
+
+    // rows are independent: split them over host threads
+    unsigned nthreads = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+    if (N * K < (1 << 20)) nthreads = 1;
+    std::atomic<int64_t> next_row{0};
+    std::atomic<bool> bad{false};
+    auto work = [&]() {
+        std::vector<double> sal(kg);
+        std::vector<int32_t> order(kg), kept;
+        std::vector<uint8_t> q(G);
+        constexpr int64_t kChunk = 16;
+        for (;;) {
+            const int64_t r0 = next_row.fetch_add(kChunk);
+            if (r0 >= N) break;
+            const int64_t r1 = std::min(N, r0 + kChunk);
+            for (int64_t n = r0; n < r1; ++n) {
+                const float* wrow = W + n * K;
+                const int64_t g0 = m->rowIndex[n];
+                const int64_t keep = m->rowIndex[n + 1] - g0;
+                if (!select_row(wrow, kg, G, keep, sal, order, kept)) { bad = true; continue; }
+                for (int64_t i = 0; i < keep; ++i) {
+                    const int64_t g = g0 + i;
+                    const int32_t c = kept[i];
+                    m->groups[g] = c;
+                    quantise_group(wrow + static_cast<int64_t>(c) * G, G, bits, q.data(),
+                                   &m->scales[g], &m->zeros[g]);
+                    uint8_t* dst = &m->values[static_cast<size_t>(g) * cb];
+                    if (bits == 8) {
+                        std::memcpy(dst, q.data(), G);
+                    } else {
+                        for (int j = 0; j < G; j += 2)
+                            dst[j / 2] = static_cast<uint8_t>(q[j] | (q[j + 1] << 4));
+                    }
+                }
+            }
+        }
+    };
+    if (nthreads == 1) {
+        work();
+    } else {
+        std::vector<std::thread> pool;
+        for (unsigned t = 0; t < nthreads; ++t) pool.emplace_back(work);
+        for (auto& t : pool) t.join();
+    }
+    if (bad) return GQSA_ERR_RANGE;
+    return GQSA_OK;
+}
+
+int default_n_waves(int64_t n_blocks)
+{
+    int64_t wgs = (n_blocks + kWavesPerWorkgroup - 1) / kWavesPerWorkgroup;
+    wgs = std::max<int64_t>(1, std::min<int64_t>(kMaxDefaultWorkgroups, wgs));
+    return static_cast<int>(wgs * kWavesPerWorkgroup);
+}
+
+// Device image.  The stored groups, in canonical order, form a stream that is cut into
+// 64-group blocks and dealt to n_waves wavefront workers in contiguous, near-equal runs
+// (the nnz-balanced version of the paper's task-centric split, Sec. 3.5).  Inside a run the
+// blocks are taken 4, then 2, then 1 at a time ("superblocks"); in a superblock of U blocks
+// lane l owns U consecutive stream positions, stored one per block so that every block is a
+// fully coalesced, lane-interleaved load:
+//     stream position (first of superblock) + p  ->  block (p mod U), lane (p div U).
+// Block = 64 x code bytes | 64 x (scale | zero << 16) | 64 x (group-column | head << 15).
+// 4-bit code words are nibble-permuted so that one AND per pair of elements yields a packed
+// fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m at bits 4m and
+// element 8h+2m+1 at bits 16+4m.
+gqsa_status_t build_image(gqsa_matrix* m, int n_waves)
+{
+    if (n_waves < 1 || n_waves > kMaxWaves) return GQSA_ERR_RANGE;
+    const int64_t nnz = m->nnzg();
+    const int64_t nb = (nnz + kLanes - 1) / kLanes;
+    const int cb = m->code_bytes();
+    const size_t bb = static_cast<size_t>(m->block_bytes());
+    auto align = [](size_t v) { return (v + kAlign - 1) / kAlign * kAlign; };
+
+    std::vector<int32_t> nonempty, empty;
+    std::vector<uint8_t> head(static_cast<size_t>(nnz) + 1, 0);
+    for (int64_t n = 0; n < m->N; ++n) {
+        if (m->rowIndex[n + 1] > m->rowIndex[n]) {
+            nonempty.push_back(static_cast<int32_t>(n));
+            head[m->rowIndex[n]] = 1;
+        } else {
+            empty.push_back(static_cast<int32_t>(n));
+        }
+    }
+
+    ImageMap map;
+    map.blocks = 0;
+    map.wave_info = align(static_cast<size_t>(nb) * bb);
+    map.row_of_rank = align(map.wave_info + static_cast<size_t>(n_waves) * 8);
+    map.empty_rows = align(map.row_of_rank + nonempty.size() * 4);
+    map.total = std::max(kAlign, align(map.empty_rows + empty.size() * 4));
+
+    std::vector<uint8_t> img;
+    try {
+        img.assign(map.total, 0);
+    } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
+
+    auto put_group = [&](int64_t g, int64_t block, int lane) {
+        uint8_t* base = img.data() + static_cast<size_t>(block) * bb;
+        const uint8_t* v = &m->values[static_cast<size_t>(g) * cb];
+        if (m->bits == 4) {
+            uint32_t word[2] = {0, 0};
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t q = (j & 1) ? (v[j >> 1] >> 4) : (v[j >> 1] & 0xF);
+                const int h = j >> 3, m2 = (j & 7) >> 1;
+                word[h] |= q << ((j & 1) ? 16 + 4 * m2 : 4 * m2);
+            }
+            std::memcpy(base + static_cast<size_t>(lane) * 8, word, 8);
+        } else {
+            std::memcpy(base + static_cast<size_t>(lane) * cb, v, cb);
+        }
+        const uint32_t sz = static_cast<uint32_t>(m->scales[g]) |
+                            (static_cast<uint32_t>(m->zeros[g]) << 16);
+        std::memcpy(base + static_cast<size_t>(kLanes) * cb + lane * 4, &sz, 4);
+        const uint16_t ix = static_cast<uint16_t>(m->groups[g]) | (head[g] ? 0x8000u : 0u);
+        std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
+    };
+
+    int32_t* info = reinterpret_cast<int32_t*>(img.data() + map.wave_info);
+    const int64_t per = nb / n_waves, extra = nb % n_waves;
+    int64_t block0 = 0;
+    int32_t heads_before = 0;
+    int64_t counted = 0;  // stream positions whose head flags are already in heads_before
+    int fix = 0;
+    for (int w = 0; w < n_waves; ++w) {
+        const int64_t mine = per + (w < extra ? 1 : 0);
+        const int64_t first = block0 * kLanes;
+        for (; counted < std::min(first, nnz); ++counted) heads_before += head[counted];
+        info[2 * w] = heads_before - 1;
+        int64_t pos = first, blk = block0, left = mine;
+        while (left > 0) {
+            const int U = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
+            for (int p = 0; p < kLanes * U && pos + p < nnz; ++p)
+                put_group(pos + p, blk + p % U, p / U);
+            pos += static_cast<int64_t>(kLanes) * U;
+            blk += U;
+            left -= U;
+        }
+        const int64_t end = (block0 + mine) * kLanes;
+        const int closed = (end >= nnz || head[end]) ? 1 : 0;
+        info[2 * w + 1] = closed;
+        if (mine > 0 && !closed) fix = 1;
+        block0 += mine;
+    }
+    if (!nonempty.empty())
+        std::memcpy(img.data() + map.row_of_rank, nonempty.data(), nonempty.size() * 4);
+    if (!empty.empty())
+        std::memcpy(img.data() + map.empty_rows, empty.data(), empty.size() * 4);
+
+    m->image.swap(img);
+    m->map = map;
+    m->n_waves = n_waves;
+    m->n_blocks = nb;
+    m->n_empty = static_cast<int64_t>(empty.size());
+    m->needs_fixup = fix;
+    return GQSA_OK;
+}
+
+}  // namespace gqsa

@@ -147,13 +147,16 @@ def test_blob_decodes_back_to_canonical(bits, n_waves):
     nblocks = (nn + 63) // 64
     cb = 16 * bits // 8
     off = (nblocks * (cb + 6) * 64 + 255) // 256 * 256
-    rank_base = np.frombuffer(blob, dtype="<i4", count=n_waves, offset=off)
+    wave_info = np.frombuffer(blob, dtype="<i4", count=2 * n_waves, offset=off).reshape(n_waves, 2)
     b = 0
     for w in range(n_waves):
         n_w = nblocks // n_waves + (1 if w < nblocks % n_waves else 0)
-        assert rank_base[w] == int(exp_heads[:min(64 * b, nn)].sum()) - 1
+        assert wave_info[w, 0] == int(exp_heads[:min(64 * b, nn)].sum()) - 1
         b += n_w
-    off = (off + 4 * n_waves + 255) // 256 * 256
+        end = 64 * b
+        closed = 1 if end >= nn or exp_heads[end] else 0
+        assert wave_info[w, 1] == closed
+    off = (off + 8 * n_waves + 255) // 256 * 256
     nonempty = [n for n in range(N) if keep[n] > 0]
     empty = [n for n in range(N) if keep[n] == 0]
     assert list(np.frombuffer(blob, dtype="<i4", count=len(nonempty), offset=off)) == nonempty
@@ -166,7 +169,8 @@ def test_blob_of_empty_matrix():
     W = gi.dense_weight(8, 64, seed=1)
     c = oracle.pack(W, sparsity=1.0)
     blob = oracle.device_blob(c, 16)
-    # no blocks; rank_base = -1 for every worker; no non-empty rows; 8 empty rows
-    assert np.array_equal(np.frombuffer(blob, dtype="<i4", count=16), np.full(16, -1))
+    # no blocks; {rank_base, tail_closed} = {-1, 1} for every worker; no non-empty rows; 8 empty rows
+    assert np.array_equal(np.frombuffer(blob, dtype="<i4", count=32).reshape(16, 2),
+                          np.tile(np.array([-1, 1]), (16, 1)))
     assert list(np.frombuffer(blob, dtype="<i4", count=8, offset=256)) == list(range(8))
     assert len(blob) == 512

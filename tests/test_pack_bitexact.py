@@ -1,0 +1,107 @@
+"""The library's host packer and device-image builder against the oracle, bit for bit.
+
+Runs without a GPU: gqsa_pack / gqsa_export / gqsa_export_device_blob never touch HIP.
+"""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+import gqsa_inputs as gi
+import oracle
+import paper_2412_17560_amd as gq
+
+
+def assert_same_canonical(h, c):
+    e = gq.gqsa_export(h)
+    assert np.array_equal(e["rowIndex"], c.rowIndex)
+    assert np.array_equal(e["groups"], c.groups)
+    assert np.array_equal(e["values"], c.values)
+    assert np.array_equal(e["scales"], c.scales)
+    assert np.array_equal(e["zeros"], c.zeros)
+
+
+def assert_same_blob(h, c):
+    info = gq.gqsa_info(h)
+    blob = gq.gqsa_export_device_blob(h)
+    ref = oracle.device_blob(c, info["n_waves"])
+    assert len(blob) == len(ref) == info["device_bytes"]
+    assert blob == ref
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("sparsity", [0.0, 0.3, 0.5, 0.7, 1.0])
+def test_tiny_config_balanced(bits, sparsity):
+    W, _ = gi.tiny_config()
+    h = gq.gqsa_pack(W, 16, bits, sparsity)
+    c = oracle.pack(W, 16, bits, sparsity=sparsity)
+    assert_same_canonical(h, c)
+    assert_same_blob(h, c)
+    info = gq.gqsa_info(h)
+    assert info["nnz_groups"] == c.nnzg
+    assert info["n_waves"] == oracle.default_n_waves(c.nnzg)
+    assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_outliers_and_imbalanced_rows(bits):
+    N, K = 333, 1024
+    W = gi.dense_weight(N, K, seed=77)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=77)
+    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+    assert_same_canonical(h, c)
+    for n_waves in (None, 1, 2, 3, 5, 16, 17, 64, 1000):
+        if n_waves is not None:
+            gq.gqsa_set_partition(h, n_waves)
+            assert gq.gqsa_info(h)["n_waves"] == n_waves
+        assert_same_blob(h, c)
+
+
+def test_planted_ties_and_constant_groups():
+    rng = np.random.default_rng(8)
+    W = rng.standard_normal((20, 160)).astype(np.float32)
+    W[:, 16:32] = W[:, 0:16]            # duplicate groups: equal saliency
+    W[:, 48:64] = 0.0                   # all-zero groups
+    W[3] = 0.25                         # a constant row: every group degenerate, all tie
+    W[4] = 0.0
+    for s in (0.3, 0.5, 0.8):
+        h = gq.gqsa_pack(W, 16, 4, s)
+        c = oracle.pack(W, 16, 4, sparsity=s)
+        assert_same_canonical(h, c)
+        assert_same_blob(h, c)
+
+
+def test_full_size_7b_shape_bit_exact():
+    """One full decode shape (4096x4096, W4S50) of the LLaMA-7B layer set, default partition."""
+    W = gi.dense_weight(4096, 4096, seed=gi.config_seed(2, 0))
+    h = gq.gqsa_pack(W, 16, 4, 0.5)
+    c = oracle.pack(W, 16, 4, sparsity=0.5)
+    assert_same_canonical(h, c)
+    assert_same_blob(h, c)
+    info = gq.gqsa_info(h)
+    assert info["nnz_groups"] == 524288 and info["n_waves"] == 4096
+    assert info["algorithmic_bytes"] == 7372804
+    assert info["needs_fixup"] == 0      # 128 groups per row: every worker's run ends on a row end
+
+
+def test_full_size_down_proj_shape_needs_fixup():
+    W = gi.dense_weight(1024, 11008, seed=gi.config_seed(2, 6))   # a 1024-row slice of down_proj
+    h = gq.gqsa_pack(W, 16, 4, 0.5)
+    c = oracle.pack(W, 16, 4, sparsity=0.5)
+    assert_same_canonical(h, c)
+    assert_same_blob(h, c)
+    assert gq.gqsa_info(h)["needs_fixup"] == 1   # 344 groups per row do not align with 64-group blocks
+
+
+def test_import_round_trip_and_free_parameters():
+    W = gi.dense_weight(50, 256, seed=3)
+    keep = gi.imbalanced_keep_counts(50, 16, seed=3)
+    c = oracle.pack(W, 16, 4, keep_per_row=keep)
+    # Sec. 3.4 fine-tunes s and z freely: perturb them to non-integer zeros and other scales
+    rng = np.random.default_rng(1)
+    c.scales = (c.scales.view(np.float16) * np.float16(1.37)).view(np.uint16)
+    c.zeros = (c.zeros.view(np.float16) + rng.standard_normal(c.nnzg).astype(np.float16)).view(np.uint16)
+    h = gq.gqsa_import(c.rowIndex, c.groups, c.values, c.scales, c.zeros, 50, 256, 16, 4)
+    assert_same_canonical(h, c)
+    assert_same_blob(h, c)
