@@ -33,6 +33,10 @@ def _lib():
     global _LIB
     if _LIB is not None:
         return _LIB
+    # PyTorch ships its own HIP runtime (same SONAME as the system one).  Streams and device
+    # pointers handed to libgqsa come from PyTorch, so both must live in ONE runtime: import
+    # torch first, and the loader resolves libgqsa's libamdhip64 to the copy already mapped.
+    import torch  # noqa: F401
     path = _build.LIB
     if not os.path.exists(path):
         _build.build()           # nothing built yet: build once, in-tree

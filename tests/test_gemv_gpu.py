@@ -197,8 +197,12 @@ def test_gemv_error_paths_on_device(torch_cuda):
         gq.gqsa_gemv(h, x)
     assert e.value.status == 3
     xm = torch.zeros((1, 64 + 4), dtype=torch.float16, device="cuda")[:, 4:]
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_gemv(h, xm)           # 8 bytes past a 16-byte boundary
+    assert e.value.status == 8
+    xt = torch.zeros((64, 2), dtype=torch.float16, device="cuda").t()
     with pytest.raises(ValueError):
-        gq.gqsa_gemv(h, xm)           # not contiguous: refused by the binding
+        gq.gqsa_gemv(h, xt)           # not contiguous: refused by the binding
     gq.gqsa_upload(h)
     with pytest.raises(gq.GqsaError) as e:
         gq.gqsa_set_partition(h, 8)   # not after upload
