@@ -175,11 +175,22 @@ def main():
     # ------------------------------------------------------------------ extras: per shape, baselines
     if not args.skip_extras:
         def time_calls(fn_of_k, n=200, warm=20):
+            """us per call of n back-to-back calls replayed from a HIP graph (eager if --no-graph)."""
             with torch.cuda.stream(stream):
                 for k in range(warm):
                     fn_of_k(k)
-            ms = timed_region(lambda: [fn_of_k(warm + k) for k in range(n)])
-            return ms * 1e3 / n   # us per call
+            torch.cuda.synchronize()
+            if args.no_graph:
+                return timed_region(lambda: [fn_of_k(warm + k) for k in range(n)]) * 1e3 / n
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=stream):
+                for k in range(n):
+                    fn_of_k(warm + k)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(stream):
+                gr.replay()
+            torch.cuda.synchronize()
+            return min(timed_region(lambda: gr.replay()) for _ in range(3)) * 1e3 / n
 
         per_shape = []
         for idx in (0, 4, 6):
@@ -194,7 +205,7 @@ def main():
                               "GBps_cold": round(b / us / 1e3, 1),
                               "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2),
                               "us_cache_warm": round(us_warm, 3),
-                              "distinct_matrices": len(hs), "mode": "eager back-to-back"})
+                              "distinct_matrices": len(hs), "mode": "back-to-back calls, " + mode})
         out["per_shape"] = per_shape
 
         # achievable read ceiling: plain streaming kernel over 2 GiB

@@ -54,8 +54,10 @@ typedef struct {
     int64_t nnz_groups;         /* stored groups = rowIndex[N] */
     int64_t values_bytes;       /* bytes of the canonical `values` array */
     int64_t n_blocks;           /* 64-group blocks of the device stream */
-    int32_t n_waves;            /* wavefront workers the stream is partitioned over */
-    int32_t needs_fixup;        /* 1 if some row spans two workers (carry fix-up runs) */
+    int32_t n_workgroups;       /* workgroups the group stream is dealt to */
+    int32_t waves_per_workgroup;/* wavefront workers per workgroup */
+    int32_t needs_fixup;        /* 1 if some row is shared by two or more wavefront workers */
+    int32_t reserved0;
     int64_t n_empty_rows;       /* rows without any stored group */
     int64_t device_bytes;       /* size of the device image */
     int64_t algorithmic_bytes;  /* compressed bytes one batch-1 call must move (see README of bench) */
@@ -94,10 +96,11 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
                           const uint16_t* scales_f16, const uint16_t* zeros_f16,
                           int64_t N, int64_t K, int G, int bits, gqsa_handle_t* out);
 
-/* Re-partition the group stream over n_waves wavefront workers (1..65536) and rebuild the
- * host copy of the device image.  Only before the handle is uploaded.  The default chosen
- * by pack/import is 16*min(256, ceil(n_blocks/16)). */
-gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_waves);
+/* Re-partition the group stream over n_workgroups (1..4096) workgroups of waves_per_workgroup
+ * (1..16) wavefront workers and rebuild the host copy of the device image.  Only before the
+ * handle is uploaded.  The default chosen by pack/import is min(256, ceil(n_blocks/16))
+ * workgroups of 16 wavefronts (one workgroup per compute unit of an MI355X). */
+gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
 
 /* Create the device image and carry workspace on the current HIP device (synchronous). */
 gqsa_status_t gqsa_upload(gqsa_handle_t h);

@@ -189,4 +189,4 @@ def rel_error(y: np.ndarray, y_ref: np.ndarray) -> float:
     return float(np.max(np.abs(y - y_ref) / den))
 
 
-from .layout import device_blob, default_n_waves  # noqa: E402,F401
+from .layout import device_blob, default_partition  # noqa: E402,F401

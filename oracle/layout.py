@@ -8,9 +8,13 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
  1. Stream.  The stored groups in canonical order g = 0..nnzg-1 form a stream;
     it is padded with null groups (all bytes zero) to nblocks*64 positions,
     nblocks = ceil(nnzg/64).
- 2. Partition.  n_waves workers each own a contiguous run of blocks: worker w
-    owns n_w = nblocks div n_waves (+1 if w < nblocks mod n_waves) blocks,
-    starting at block b_w = sum of the earlier workers' counts.
+ 2. Partition, two levels.  The blocks are dealt to n_workgroups workgroups in
+    contiguous runs: workgroup g gets nblocks div n_workgroups blocks (+1 if
+    g < nblocks mod n_workgroups).  A workgroup's run of m blocks is dealt the
+    same way to its waves_per_workgroup wavefronts: wavefront l gets
+    m div waves_per_workgroup (+1 if l < m mod waves_per_workgroup).  Worker
+    w = g*waves_per_workgroup + l; n_waves = n_workgroups*waves_per_workgroup;
+    b_w = first block of worker w = sum of the earlier workers' counts.
  3. Superblocks.  A worker's run is cut, from its start, into superblocks of 4
     blocks as long as 4 fit, then one of 2 blocks if at least 2 remain, then
     one of 1 block if one remains.  A superblock of U blocks starting at block
@@ -23,10 +27,19 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     elements 8h..8h+7 of the group, element 8h+2m in bits 4m..4m+3 and element
     8h+2m+1 in bits 16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j of the
     lane's 16 bytes is element j.
- 5. Side tables (int32): wave_info[n_waves][2] = {rank_base, tail_closed} with
-    rank_base = (number of row-head groups at stream positions before worker
-    w's first position) - 1 and tail_closed = 1 if the first position after the
-    worker's run is at or beyond nnzg or holds a row-head group, else 0;
+ 5. Side tables (int32): wave_info[n_waves][4] = {rank_base, tail_closed,
+    lead_first, chain_len} with
+      rank_base   = (number of row-head groups at stream positions before
+                    worker w's first position) - 1;
+      tail_closed = 1 if the first position after the worker's run is at or
+                    beyond nnzg or holds a row-head group, else 0;
+      lead_first  = for a worker (with or without blocks) whose first position
+                    b_w*64 holds a stored group that is not a row head: the
+                    worker that owns the head group of that group's row; else -1;
+      chain_len   = for a worker with blocks, tail_closed = 0 and at least one
+                    row head inside its run: (worker owning the last stored
+                    group of the row that is open at the end of its run) - w + 1;
+                    else 0;
     row_of_rank[r] = index of the r-th non-empty row; empty_rows = indices of
     the empty rows.
  6. Blob = blocks, wave_info, row_of_rank, empty_rows, each region starting
@@ -42,31 +55,40 @@ MAX_WAVES = 4096
 WAVES_PER_WORKGROUP = 16
 
 
-def default_n_waves(nnzg: int) -> int:
-    """Worker count the library picks when not told otherwise: whole workgroups
-    of 16 wavefronts, at most 256 of them, no more than the blocks can feed."""
+def default_partition(nnzg: int):
+    """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise:
+    workgroups of 16 wavefronts, at most 256 of them, no more than the blocks can feed."""
     nblocks = (nnzg + LANES - 1) // LANES
     wgs = (nblocks + WAVES_PER_WORKGROUP - 1) // WAVES_PER_WORKGROUP
     wgs = max(1, min(MAX_WAVES // WAVES_PER_WORKGROUP, wgs))
-    return wgs * WAVES_PER_WORKGROUP
+    return wgs, WAVES_PER_WORKGROUP
+
+
+def worker_block_counts(nblocks: int, n_workgroups: int, waves_per_workgroup: int) -> np.ndarray:
+    """Blocks owned by every worker (spec item 2)."""
+    base, extra = divmod(nblocks, n_workgroups)
+    out = np.zeros(n_workgroups * waves_per_workgroup, dtype=np.int64)
+    for g in range(n_workgroups):
+        m = base + (1 if g < extra else 0)
+        b2, e2 = divmod(m, waves_per_workgroup)
+        row = np.full(waves_per_workgroup, b2, dtype=np.int64)
+        row[:e2] += 1
+        out[g * waves_per_workgroup:(g + 1) * waves_per_workgroup] = row
+    return out
 
 
 def _align(n: int) -> int:
     return (n + ALIGN - 1) // ALIGN * ALIGN
 
 
-def stream_placement(nblocks: int, n_waves: int):
+def stream_placement(nblocks: int, n_workgroups: int, waves_per_workgroup: int):
     """For every stream position: (block, lane) it is stored at (spec items 2-3)."""
-    base, extra = divmod(nblocks, n_waves)
-    n_w = np.full(n_waves, base, dtype=np.int64)
-    n_w[:extra] += 1
+    n_w = worker_block_counts(nblocks, n_workgroups, waves_per_workgroup)
     b_w = np.concatenate(([0], np.cumsum(n_w)[:-1]))
     pos = np.arange(nblocks * LANES, dtype=np.int64)
     blk_of_pos = pos // LANES
-    # worker owning each position: last w with b_w <= block (skip zero-sized workers)
-    w = np.searchsorted(b_w, blk_of_pos, side="right") - 1
-    # workers without blocks all start at block nblocks, which no position has
-    assert (n_w[w] > 0).all()
+    # worker owning each block: block counts expanded
+    w = np.repeat(np.arange(n_w.size), n_w)[blk_of_pos]
     q = pos - LANES * b_w[w]                    # position inside the worker's run
     nw = n_w[w]
     n4 = nw // 4
@@ -82,10 +104,10 @@ def stream_placement(nblocks: int, n_waves: int):
     assert (p[in1] < 64).all() and (p >= 0).all()
     block = b_w[w] + sb_blk + (p % U)
     lane = p // U
-    return block, lane, b_w
+    return block, lane, b_w, n_w
 
 
-def device_blob(c, n_waves: int) -> bytes:
+def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     """Exact bytes the library must hold on the device for canonical arrays `c`."""
     if c.G != 16 or c.bits not in (4, 8):
         raise ValueError("device layout is specified for G=16, bits in {4,8}")
@@ -100,12 +122,14 @@ def device_blob(c, n_waves: int) -> bytes:
     empty = np.nonzero(counts == 0)[0].astype(np.int32)
     head_pos = ri[:-1][counts > 0]                 # stream position of each row's first group
 
+    n_waves = n_workgroups * waves_per_workgroup
     blocks = np.zeros((nblocks, blk_bytes), dtype=np.uint8)
-    wave_info = np.zeros((n_waves, 2), dtype=np.int32)
+    wave_info = np.zeros((n_waves, 4), dtype=np.int32)
     wave_info[:, 0] = -1
     wave_info[:, 1] = 1
+    wave_info[:, 2] = -1
     if nblocks > 0:
-        block, lane, b_w = stream_placement(nblocks, n_waves)
+        block, lane, b_w, n_w = stream_placement(nblocks, n_workgroups, waves_per_workgroup)
         block = block[:nnzg]
         lane = lane[:nnzg]
         # codes
@@ -144,13 +168,24 @@ def device_blob(c, n_waves: int) -> bytes:
         first_pos = LANES * b_w
         wave_info[:, 0] = np.searchsorted(head_pos, first_pos, side="left") - 1
         # tail_closed: does the row that is open at the end of the run stop there?
-        base, extra = divmod(nblocks, n_waves)
-        n_w = np.full(n_waves, base, dtype=np.int64)
-        n_w[:extra] += 1
         end_pos = LANES * (b_w + n_w)
         head_set = np.zeros(nblocks * LANES + 1, dtype=bool)
         head_set[head_pos] = True
         wave_info[:, 1] = np.where(end_pos >= nnzg, 1, head_set[np.minimum(end_pos, nblocks * LANES)])
+        # carry chains: which worker owns a given block
+        owner = np.repeat(np.arange(n_waves), n_w)
+        for w in range(n_waves):
+            f = int(first_pos[w])
+            e = int(end_pos[w])
+            if f < nnzg and not head_set[f]:
+                row_head = int(head_pos[np.searchsorted(head_pos, f, side="right") - 1])
+                wave_info[w, 2] = owner[row_head // LANES]
+            heads_inside = (np.searchsorted(head_pos, min(e, nnzg), side="left") -
+                            np.searchsorted(head_pos, f, side="left"))
+            if n_w[w] > 0 and wave_info[w, 1] == 0 and heads_inside > 0:
+                nxt = int(np.searchsorted(head_pos, e, side="left"))
+                row_last = (int(head_pos[nxt]) if nxt < len(head_pos) else nnzg) - 1
+                wave_info[w, 3] = owner[row_last // LANES] - w + 1
 
     parts = [blocks.tobytes(), wave_info.astype("<i4").tobytes(),
              nonempty.astype("<i4").tobytes(), empty.astype("<i4").tobytes()]

@@ -20,7 +20,8 @@ class GqsaError(RuntimeError):
 class _Info(C.Structure):
     _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("G", C.c_int32), ("bits", C.c_int32),
                 ("nnz_groups", C.c_int64), ("values_bytes", C.c_int64), ("n_blocks", C.c_int64),
-                ("n_waves", C.c_int32), ("needs_fixup", C.c_int32), ("n_empty_rows", C.c_int64),
+                ("n_workgroups", C.c_int32), ("waves_per_workgroup", C.c_int32),
+                ("needs_fixup", C.c_int32), ("reserved0", C.c_int32), ("n_empty_rows", C.c_int64),
                 ("device_bytes", C.c_int64), ("algorithmic_bytes", C.c_int64),
                 ("on_device", C.c_int32), ("reserved", C.c_int32)]
 
@@ -51,7 +52,7 @@ def _lib():
     lib.gqsa_import.restype = C.c_int
     lib.gqsa_import.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, C.POINTER(vp)]
     lib.gqsa_set_partition.restype = C.c_int
-    lib.gqsa_set_partition.argtypes = [vp, i32]
+    lib.gqsa_set_partition.argtypes = [vp, i32, i32]
     lib.gqsa_upload.restype = C.c_int
     lib.gqsa_upload.argtypes = [vp]
     lib.gqsa_gemv.restype = C.c_int
@@ -141,8 +142,9 @@ def gqsa_import(rowIndex, groups, values, scales_f16, zeros_f16, N: int, K: int,
     return GqsaHandle(out.value)
 
 
-def gqsa_set_partition(h: GqsaHandle, n_waves: int) -> None:
-    _check(_lib().gqsa_set_partition(h.ptr, int(n_waves)), "gqsa_set_partition")
+def gqsa_set_partition(h: GqsaHandle, n_workgroups: int, waves_per_workgroup: int = 16) -> None:
+    _check(_lib().gqsa_set_partition(h.ptr, int(n_workgroups), int(waves_per_workgroup)),
+           "gqsa_set_partition")
 
 
 def gqsa_upload(h: GqsaHandle) -> None:
@@ -152,7 +154,7 @@ def gqsa_upload(h: GqsaHandle) -> None:
 def gqsa_info(h: GqsaHandle) -> dict:
     info = _Info()
     _check(_lib().gqsa_info(h.ptr, C.byref(info)), "gqsa_info")
-    return {name: getattr(info, name) for name, _ in _Info._fields_ if name != "reserved"}
+    return {name: getattr(info, name) for name, _ in _Info._fields_ if not name.startswith("reserved")}
 
 
 def gqsa_export(h: GqsaHandle) -> dict:

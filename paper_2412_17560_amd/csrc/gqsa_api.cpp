@@ -23,7 +23,7 @@ gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
 {
     if (st == GQSA_OK) {
         const int64_t nb = (m->nnzg() + gqsa::kLanes - 1) / gqsa::kLanes;
-        st = gqsa::build_image(m, gqsa::default_n_waves(nb));
+        st = gqsa::build_image(m, gqsa::default_workgroups(nb), gqsa::kWavesPerWorkgroup);
     }
     if (st != GQSA_OK) {
         delete m;
@@ -97,12 +97,11 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
     return finish(m, GQSA_OK, out);
 }
 
-gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_waves)
+gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup)
 {
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
-    if (n_waves < 1 || n_waves > gqsa::kMaxWaves) return GQSA_ERR_RANGE;
-    return gqsa::build_image(h, n_waves);
+    return gqsa::build_image(h, n_workgroups, waves_per_workgroup);
 }
 
 gqsa_status_t gqsa_upload(gqsa_handle_t h)
@@ -136,7 +135,8 @@ gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)
     out->nnz_groups = h->nnzg();
     out->values_bytes = h->nnzg() * h->code_bytes();
     out->n_blocks = h->n_blocks;
-    out->n_waves = h->n_waves;
+    out->n_workgroups = h->n_workgroups;
+    out->waves_per_workgroup = h->waves_per_workgroup;
     out->needs_fixup = h->needs_fixup;
     out->n_empty_rows = h->n_empty;
     out->device_bytes = static_cast<int64_t>(h->map.total);

@@ -13,7 +13,7 @@ namespace gqsa {
 constexpr int kLanes = 64;             // one stored group per lane per block
 constexpr int kWavesPerWorkgroup = 16; // 1024 threads: one workgroup per compute unit
 constexpr int kMaxDefaultWorkgroups = 256;  // MI355X: 256 compute units
-constexpr int kMaxWaves = 65536;
+constexpr int kMaxWorkgroups = 4096;
 constexpr int kMaxBatch = 16;
 constexpr int64_t kMaxGroupColumns = 32768; // 15-bit group-column + head flag in 16 bits
 constexpr size_t kAlign = 256;
@@ -21,13 +21,13 @@ constexpr size_t kAlign = 256;
 // Offsets (bytes) of the regions inside the device image.
 struct ImageMap {
     size_t blocks = 0;      // n_blocks * block_bytes
-    size_t wave_info = 0;   // n_waves * {int32 rank_base, int32 tail_closed}
+    size_t wave_info = 0;   // n_waves * int32[4] {rank_base, tail_closed, lead_first, chain_len}
     size_t row_of_rank = 0; // int32 per non-empty row
     size_t empty_rows = 0;  // int32 per empty row
     size_t total = 0;
 };
 
-// Per-worker record the GEMV kernel leaves for the carry fix-up.
+// Per-worker record the GEMV kernel publishes for the rows it shares with its neighbours.
 struct CarryRecord {
     float lead;    // sum of the groups before the worker's first row head
     float tail;    // sum of the groups after its last row head (or all, if it has none)
@@ -47,7 +47,9 @@ struct gqsa_matrix {
     std::vector<uint16_t> scales;
     std::vector<uint16_t> zeros;
     // device image (host copy) and its map
-    int n_waves = 0;
+    int n_workgroups = 0;
+    int waves_per_workgroup = 0;
+    int n_waves = 0;          // n_workgroups * waves_per_workgroup
     int64_t n_blocks = 0;
     int64_t n_empty = 0;
     int needs_fixup = 0;
@@ -56,7 +58,7 @@ struct gqsa_matrix {
     // device side
     int device = -1;
     void* d_image = nullptr;
-    void* d_carry = nullptr;  // n_waves * kMaxBatch CarryRecord
+    void* d_carry = nullptr;  // n_waves CarryRecord, then n_waves int32 arrival counters
 
     int64_t nnzg() const { return rowIndex.empty() ? 0 : rowIndex.back(); }
     int code_bytes() const { return G * bits / 8; }
@@ -68,8 +70,8 @@ namespace gqsa {
 // host packer (gqsa_pack.cpp)
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          const int32_t* keep_per_row, double sparsity, gqsa_matrix* m);
-int default_n_waves(int64_t n_blocks);
-gqsa_status_t build_image(gqsa_matrix* m, int n_waves);
+int default_workgroups(int64_t n_blocks);
+gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup);
 
 // device side (gqsa_gemv.hip)
 gqsa_status_t device_upload(gqsa_matrix* m);

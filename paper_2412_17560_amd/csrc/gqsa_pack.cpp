@@ -174,16 +174,16 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
     return GQSA_OK;
 }
 
-int default_n_waves(int64_t n_blocks)
+int default_workgroups(int64_t n_blocks)
 {
     int64_t wgs = (n_blocks + kWavesPerWorkgroup - 1) / kWavesPerWorkgroup;
-    wgs = std::max<int64_t>(1, std::min<int64_t>(kMaxDefaultWorkgroups, wgs));
-    return static_cast<int>(wgs * kWavesPerWorkgroup);
+    return static_cast<int>(std::max<int64_t>(1, std::min<int64_t>(kMaxDefaultWorkgroups, wgs)));
 }
 
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
-// 64-group blocks and dealt to n_waves wavefront workers in contiguous, near-equal runs
-// (the nnz-balanced version of the paper's task-centric split, Sec. 3.5).  Inside a run the
+// 64-group blocks and dealt in contiguous, near-equal runs first to the workgroups and then,
+// inside each workgroup, to its wavefronts (the nnz-balanced version of the paper's
+// task-centric split, Sec. 3.5; a row may be shared by neighbouring wavefronts).  Inside a run the
 // blocks are taken 4, then 2, then 1 at a time ("superblocks"); in a superblock of U blocks
 // lane l owns U consecutive stream positions, stored one per block so that every block is a
 // fully coalesced, lane-interleaved load:
@@ -192,9 +192,11 @@ int default_n_waves(int64_t n_blocks)
 // 4-bit code words are nibble-permuted so that one AND per pair of elements yields a packed
 // fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m at bits 4m and
 // element 8h+2m+1 at bits 16+4m.
-gqsa_status_t build_image(gqsa_matrix* m, int n_waves)
+gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup)
 {
-    if (n_waves < 1 || n_waves > kMaxWaves) return GQSA_ERR_RANGE;
+    if (n_workgroups < 1 || n_workgroups > kMaxWorkgroups) return GQSA_ERR_RANGE;
+    if (waves_per_workgroup < 1 || waves_per_workgroup > kWavesPerWorkgroup) return GQSA_ERR_RANGE;
+    const int n_waves = n_workgroups * waves_per_workgroup;
     const int64_t nnz = m->nnzg();
     const int64_t nb = (nnz + kLanes - 1) / kLanes;
     const int cb = m->code_bytes();
@@ -215,7 +217,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_waves)
     ImageMap map;
     map.blocks = 0;
     map.wave_info = align(static_cast<size_t>(nb) * bb);
-    map.row_of_rank = align(map.wave_info + static_cast<size_t>(n_waves) * 8);
+    map.row_of_rank = align(map.wave_info + static_cast<size_t>(n_waves) * 16);
     map.empty_rows = align(map.row_of_rank + nonempty.size() * 4);
     map.total = std::max(kAlign, align(map.empty_rows + empty.size() * 4));
 
@@ -245,17 +247,49 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_waves)
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
 
+    // Per worker: {rank_base, tail_closed, lead_first, chain_len}.
+    //   rank_base   rank (among non-empty rows) of the row that is open when the run starts,
+    //               i.e. (row heads before the run) - 1
+    //   tail_closed 1 if the row open at the end of the run has no group beyond it
+    //   lead_first  worker holding the head of the row that the run's first groups continue,
+    //               or -1 if the run starts on a row head or past the last group; a worker
+    //               without blocks in the middle of a row has it too (it passes 0 along)
+    //   chain_len   for a worker that holds the head of a row continuing past its run: the
+    //               number of consecutive workers holding groups of that row, else 0
+    std::vector<int64_t> head_pos;          // stream positions of the row heads, ascending
+    head_pos.reserve(nonempty.size());
+    for (int32_t n : nonempty) head_pos.push_back(m->rowIndex[n]);
+    auto heads_below = [&](int64_t pos) {
+        return static_cast<int64_t>(std::lower_bound(head_pos.begin(), head_pos.end(), pos) -
+                                    head_pos.begin());
+    };
+    // two-level deal: blocks -> workgroups -> wavefronts
+    std::vector<int64_t> first_block(static_cast<size_t>(n_waves) + 1, 0);
+    {
+        const int64_t per_wg = nb / n_workgroups, extra_wg = nb % n_workgroups;
+        int64_t b = 0;
+        for (int g = 0; g < n_workgroups; ++g) {
+            const int64_t in_wg = per_wg + (g < extra_wg ? 1 : 0);
+            const int64_t per_wave = in_wg / waves_per_workgroup, extra_wave = in_wg % waves_per_workgroup;
+            for (int l = 0; l < waves_per_workgroup; ++l) {
+                first_block[static_cast<size_t>(g) * waves_per_workgroup + l] = b;
+                b += per_wave + (l < extra_wave ? 1 : 0);
+            }
+        }
+        first_block[n_waves] = b;
+    }
+    auto worker_of = [&](int64_t pos) {   // the worker whose run contains stream position pos
+        const int64_t blk = pos / kLanes;
+        return static_cast<int32_t>(std::upper_bound(first_block.begin(), first_block.end(), blk) -
+                                    first_block.begin() - 1);
+    };
     int32_t* info = reinterpret_cast<int32_t*>(img.data() + map.wave_info);
-    const int64_t per = nb / n_waves, extra = nb % n_waves;
-    int64_t block0 = 0;
-    int32_t heads_before = 0;
-    int64_t counted = 0;  // stream positions whose head flags are already in heads_before
     int fix = 0;
     for (int w = 0; w < n_waves; ++w) {
-        const int64_t mine = per + (w < extra ? 1 : 0);
+        const int64_t block0 = first_block[w];
+        const int64_t mine = first_block[w + 1] - block0;
         const int64_t first = block0 * kLanes;
-        for (; counted < std::min(first, nnz); ++counted) heads_before += head[counted];
-        info[2 * w] = heads_before - 1;
+        const int64_t end = (block0 + mine) * kLanes;
         int64_t pos = first, blk = block0, left = mine;
         while (left > 0) {
             const int U = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
@@ -265,11 +299,20 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_waves)
             blk += U;
             left -= U;
         }
-        const int64_t end = (block0 + mine) * kLanes;
+        const int64_t hb = heads_below(std::min(first, nnz));
+        const int64_t he = heads_below(std::min(end, nnz));
         const int closed = (end >= nnz || head[end]) ? 1 : 0;
-        info[2 * w + 1] = closed;
-        if (mine > 0 && !closed) fix = 1;
-        block0 += mine;
+        int32_t lead_first = -1, chain_len = 0;
+        if (first < nnz && !head[first]) lead_first = worker_of(head_pos[hb - 1]);
+        if (mine > 0 && !closed && he > hb) {
+            const int64_t row_last = (he < static_cast<int64_t>(head_pos.size()) ? head_pos[he] : nnz) - 1;
+            chain_len = worker_of(row_last) - w + 1;
+            fix = 1;
+        }
+        info[4 * w + 0] = static_cast<int32_t>(hb - 1);
+        info[4 * w + 1] = closed;
+        info[4 * w + 2] = lead_first;
+        info[4 * w + 3] = chain_len;
     }
     if (!nonempty.empty())
         std::memcpy(img.data() + map.row_of_rank, nonempty.data(), nonempty.size() * 4);
@@ -278,6 +321,8 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_waves)
 
     m->image.swap(img);
     m->map = map;
+    m->n_workgroups = n_workgroups;
+    m->waves_per_workgroup = waves_per_workgroup;
     m->n_waves = n_waves;
     m->n_blocks = nb;
     m->n_empty = static_cast<int64_t>(empty.size());

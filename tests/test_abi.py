@@ -82,8 +82,10 @@ def test_import_validation():
 def test_partition_and_blob_buffer_errors():
     W = gi.dense_weight(8, 64, seed=1)
     h = gq.gqsa_pack(W, 16, 4, 0.5)
-    assert status_of(gq.gqsa_set_partition, h, 0) == 4
-    assert status_of(gq.gqsa_set_partition, h, 70000) == 4
+    assert status_of(gq.gqsa_set_partition, h, 0, 16) == 4
+    assert status_of(gq.gqsa_set_partition, h, 5000, 16) == 4
+    assert status_of(gq.gqsa_set_partition, h, 4, 0) == 4
+    assert status_of(gq.gqsa_set_partition, h, 4, 17) == 4
     lib = binding._lib()
     buf = np.zeros(16, dtype=np.uint8)
     assert lib.gqsa_export_device_blob(h.ptr, C.c_void_p(buf.ctypes.data), 16) == 7

@@ -67,15 +67,17 @@ def test_balanced_ragged_shapes(torch_cuda, bits, sparsity):
     check(torch_cuda, h, c, gi.activations(1, K, seed=5))
 
 
-@pytest.mark.parametrize("n_waves", [1, 2, 3, 7, 16, 33, 200, 4096])
-def test_partition_sweep_imbalanced(torch_cuda, n_waves):
-    """Rows shared by 2 and by many workers, empty rows, dense rows: the carry fix-up."""
+@pytest.mark.parametrize("part", [(1, 1), (2, 1), (3, 1), (7, 1), (1, 16), (2, 16), (3, 5), (33, 2),
+                                  (13, 16), (200, 1), (256, 16)])
+def test_partition_sweep_imbalanced(torch_cuda, part):
+    """Rows shared by 2 and by many wavefronts, inside one workgroup and across workgroups,
+    empty rows, dense rows: the carry fix-up through LDS and through device memory."""
     N, K = 257, 2048
     W = gi.dense_weight(N, K, seed=31)
     keep = gi.imbalanced_keep_counts(N, K // 16, seed=31)
     c = oracle.pack(W, 16, 4, keep_per_row=keep)
     h = gq.gqsa_pack_rows(W, keep, 16, 4)
-    gq.gqsa_set_partition(h, n_waves)
+    gq.gqsa_set_partition(h, *part)
     check(torch_cuda, h, c, gi.activations(1, K, seed=6))
 
 
@@ -93,15 +95,15 @@ def adversarial_keeps(N, kg):
 
 @pytest.mark.parametrize("name", ["one_row", "alternating", "singles", "singles_gaps", "ends_empty",
                                   "ramp", "exact64"])
-@pytest.mark.parametrize("n_waves", [None, 5])
-def test_adversarial_row_structures(torch_cuda, name, n_waves):
+@pytest.mark.parametrize("part", [None, (5, 1), (2, 3)])
+def test_adversarial_row_structures(torch_cuda, name, part):
     N, K = 96, 2048
     keep = adversarial_keeps(N, K // 16)[name]
     W = gi.dense_weight(N, K, seed=41)
     c = oracle.pack(W, 16, 4, keep_per_row=keep)
     h = gq.gqsa_pack_rows(W, keep, 16, 4)
-    if n_waves:
-        gq.gqsa_set_partition(h, n_waves)
+    if part:
+        gq.gqsa_set_partition(h, *part)
     check(torch_cuda, h, c, gi.activations(2, K, seed=7))
 
 
@@ -161,15 +163,24 @@ def test_small_batches(torch_cuda, bits):
         assert np.array_equal(yb.view(np.uint16), y16[:b].view(np.uint16))
 
 
-def test_run_to_run_determinism(torch_cuda):
-    N, K = 1024, 11008
+@pytest.mark.parametrize("part", [None, (37, 3)])
+def test_run_to_run_determinism(torch_cuda, part):
+    """Same input -> same bits, also when calls with other inputs run in between (a stale
+    carry record or counter from an earlier call would show up here)."""
+    N, K = 1000, 11008
     W = gi.dense_weight(N, K, seed=67)
     h = gq.gqsa_pack(W, 16, 4, 0.5)
+    if part:
+        gq.gqsa_set_partition(h, *part)     # rows shared across workgroups
     assert gq.gqsa_info(h)["needs_fixup"] == 1
-    x = gi.activations(1, K, seed=11)
-    first = run_gemv(torch_cuda, h, x)
-    for _ in range(20):
-        assert np.array_equal(run_gemv(torch_cuda, h, x).view(np.uint16), first.view(np.uint16))
+    c = oracle.pack(W, 16, 4, sparsity=0.5)
+    xa = gi.activations(1, K, seed=11)
+    xb = gi.activations(1, K, seed=12)
+    ya, _ = check(torch_cuda, h, c, xa)
+    yb, _ = check(torch_cuda, h, c, xb)
+    for _ in range(10):
+        assert np.array_equal(run_gemv(torch_cuda, h, xa).view(np.uint16), ya.view(np.uint16))
+        assert np.array_equal(run_gemv(torch_cuda, h, xb).view(np.uint16), yb.view(np.uint16))
 
 
 def test_y_is_fully_overwritten_and_nothing_else(torch_cuda):
@@ -205,7 +216,7 @@ def test_gemv_error_paths_on_device(torch_cuda):
         gq.gqsa_gemv(h, xt)           # not contiguous: refused by the binding
     gq.gqsa_upload(h)
     with pytest.raises(gq.GqsaError) as e:
-        gq.gqsa_set_partition(h, 8)   # not after upload
+        gq.gqsa_set_partition(h, 8, 16)   # not after upload
     assert e.value.status == 3
     assert gq.gqsa_info(h)["on_device"] == 1
 
@@ -220,7 +231,8 @@ def test_llama7b_layer_shapes_full_size(torch_cuda, idx):
     W = gi.dense_weight(N, K, seed=gi.config_seed(2, idx))
     h = gq.gqsa_pack(W, 16, 4, 0.5)
     c = oracle.pack(W, 16, 4, sparsity=0.5)
-    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, gq.gqsa_info(h)["n_waves"])
+    info = gq.gqsa_info(h)
+    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"])
     check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(2, idx)))
 
 

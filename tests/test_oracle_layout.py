@@ -14,17 +14,27 @@ import oracle
 from oracle import layout
 
 
-def test_default_worker_count():
-    assert oracle.default_n_waves(0) == 16
-    assert oracle.default_n_waves(2048) == 32            # 32 blocks -> 2 workgroups of 16
-    assert oracle.default_n_waves(64 * 17) == 32
-    assert oracle.default_n_waves(524288) == 4096        # 8192 blocks -> capped at 256 workgroups
-    assert oracle.default_n_waves(64 * 4096) == 4096
-    assert oracle.default_n_waves(64 * 1000) == 1008
+def test_default_partition():
+    assert oracle.default_partition(0) == (1, 16)
+    assert oracle.default_partition(2048) == (2, 16)           # 32 blocks -> 2 workgroups of 16
+    assert oracle.default_partition(64 * 17) == (2, 16)
+    assert oracle.default_partition(524288) == (256, 16)       # 8192 blocks -> capped at 256 workgroups
+    assert oracle.default_partition(64 * 4096) == (256, 16)
+    assert oracle.default_partition(64 * 1000) == (63, 16)
+
+
+def test_two_level_block_deal_by_hand():
+    # 23 blocks over 3 workgroups of 4 wavefronts: workgroups get 8, 8, 7; inside: 2,2,2,2 / 2,2,2,2 / 2,2,2,1
+    assert list(layout.worker_block_counts(23, 3, 4)) == [2, 2, 2, 2, 2, 2, 2, 2, 2, 2, 2, 1]
+    # 5 blocks over 2 workgroups of 4: 3 and 2 -> 1,1,1,0 / 1,1,0,0
+    assert list(layout.worker_block_counts(5, 2, 4)) == [1, 1, 1, 0, 1, 1, 0, 0]
+    # LLaMA-7B down_proj at W4S50: 22016 blocks over 256 x 16 -> 86 per workgroup = 6x6 + 10x5
+    c = layout.worker_block_counts(22016, 256, 16)
+    assert list(c[:16]) == [6] * 6 + [5] * 10 and c.sum() == 22016
 
 
 def test_placement_single_worker_7_blocks_by_hand():
-    block, lane, b_w = layout.stream_placement(7, 1)
+    block, lane, b_w, _ = layout.stream_placement(7, 1, 1)
     assert list(b_w) == [0]
     # superblock of 4 blocks: position p -> block p mod 4, lane p div 4
     assert (block[0], lane[0]) == (0, 0)
@@ -41,7 +51,7 @@ def test_placement_single_worker_7_blocks_by_hand():
 
 
 def test_placement_three_workers_7_blocks_by_hand():
-    block, lane, b_w = layout.stream_placement(7, 3)
+    block, lane, b_w, _ = layout.stream_placement(7, 3, 1)
     assert list(b_w) == [0, 3, 5]                        # 3, 2, 2 blocks
     # worker 0: superblocks of 2 then 1
     assert (block[1], lane[1]) == (1, 0)
@@ -56,14 +66,25 @@ def test_placement_three_workers_7_blocks_by_hand():
     assert (block[447], lane[447]) == (6, 63)
 
 
-@pytest.mark.parametrize("nblocks,n_waves", [(1, 1), (5, 16), (16, 16), (37, 16), (100, 7), (9, 4096)])
-def test_placement_is_a_bijection(nblocks, n_waves):
-    block, lane, _ = layout.stream_placement(nblocks, n_waves)
+@pytest.mark.parametrize("nblocks,n_wg,wpw", [(1, 1, 1), (5, 1, 16), (16, 1, 16), (37, 2, 8), (100, 7, 3),
+                                               (9, 256, 16)])
+def test_placement_is_a_bijection(nblocks, n_wg, wpw):
+    block, lane, _, _ = layout.stream_placement(nblocks, n_wg, wpw)
     slot = block * 64 + lane
     assert np.array_equal(np.sort(slot), np.arange(nblocks * 64))
 
 
-def decode_blob(blob, N, K, bits, nnzg, n_waves):
+def hand_counts(nblocks, n_wg, wpw):
+    """Blocks per worker, written out with plain loops."""
+    out = []
+    for g in range(n_wg):
+        m = nblocks // n_wg + (1 if g < nblocks % n_wg else 0)
+        for l in range(wpw):
+            out.append(m // wpw + (1 if l < m % wpw else 0))
+    return out
+
+
+def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw):
     """Invert the layout with plain loops, walking workers / superblocks / lanes."""
     G = 16
     cb = G * bits // 8
@@ -77,8 +98,9 @@ def decode_blob(blob, N, K, bits, nnzg, n_waves):
     heads = np.zeros(nblocks * 64, dtype=bool)
     pos = 0
     b = 0
-    for w in range(n_waves):
-        n_w = nblocks // n_waves + (1 if w < nblocks % n_waves else 0)
+    counts = hand_counts(nblocks, n_wg, wpw)
+    for w in range(n_wg * wpw):
+        n_w = counts[w]
         sizes = [4] * (n_w // 4)
         if n_w % 4 >= 2:
             sizes.append(2)
@@ -113,17 +135,18 @@ def decode_blob(blob, N, K, bits, nnzg, n_waves):
 
 
 @pytest.mark.parametrize("bits", [4, 8])
-@pytest.mark.parametrize("n_waves", [1, 3, 16, 48])
-def test_blob_decodes_back_to_canonical(bits, n_waves):
+@pytest.mark.parametrize("n_wg,wpw", [(1, 1), (3, 1), (1, 16), (3, 16), (5, 4), (2, 7)])
+def test_blob_decodes_back_to_canonical(bits, n_wg, wpw):
+    n_waves = n_wg * wpw
     N, K = 40, 512
     W = gi.dense_weight(N, K, seed=41)
     keep = gi.imbalanced_keep_counts(N, K // 16, seed=41)
     keep[5] = 0
     keep[N - 1] = 0
     c = oracle.pack(W, bits=bits, keep_per_row=keep)
-    blob = oracle.device_blob(c, n_waves)
+    blob = oracle.device_blob(c, n_wg, wpw)
     assert len(blob) % 256 == 0
-    codes, scales, zeros, cols, heads = decode_blob(blob, N, K, bits, c.nnzg, n_waves)
+    codes, scales, zeros, cols, heads = decode_blob(blob, N, K, bits, c.nnzg, n_wg, wpw)
     nn = c.nnzg
     if bits == 4:
         v = np.asarray(c.values).reshape(nn, 8)
@@ -147,16 +170,34 @@ def test_blob_decodes_back_to_canonical(bits, n_waves):
     nblocks = (nn + 63) // 64
     cb = 16 * bits // 8
     off = (nblocks * (cb + 6) * 64 + 255) // 256 * 256
-    wave_info = np.frombuffer(blob, dtype="<i4", count=2 * n_waves, offset=off).reshape(n_waves, 2)
+    wave_info = np.frombuffer(blob, dtype="<i4", count=4 * n_waves, offset=off).reshape(n_waves, 4)
+    # brute force: the row and the worker of every stored group
+    row_of = np.repeat(np.arange(N), np.diff(c.rowIndex))
+    worker_of = np.empty(nn, dtype=np.int64)
+    counts = hand_counts(nblocks, n_wg, wpw)
     b = 0
     for w in range(n_waves):
-        n_w = nblocks // n_waves + (1 if w < nblocks % n_waves else 0)
-        assert wave_info[w, 0] == int(exp_heads[:min(64 * b, nn)].sum()) - 1
+        n_w = counts[w]
+        worker_of[64 * b:min(64 * (b + n_w), nn)] = w
+        b += n_w
+    b = 0
+    for w in range(n_waves):
+        n_w = counts[w]
+        first = 64 * b
+        assert wave_info[w, 0] == int(exp_heads[:min(first, nn)].sum()) - 1
         b += n_w
         end = 64 * b
         closed = 1 if end >= nn or exp_heads[end] else 0
         assert wave_info[w, 1] == closed
-    off = (off + 8 * n_waves + 255) // 256 * 256
+        lead_first, chain_len = -1, 0
+        if first < nn and not exp_heads[first]:
+            lead_first = worker_of[c.rowIndex[row_of[first]]]
+        if n_w > 0 and not closed and exp_heads[first:end].any():
+            last_row = row_of[end - 1]
+            chain_len = worker_of[c.rowIndex[last_row + 1] - 1] - w + 1
+        assert wave_info[w, 2] == lead_first
+        assert wave_info[w, 3] == chain_len
+    off = (off + 16 * n_waves + 255) // 256 * 256
     nonempty = [n for n in range(N) if keep[n] > 0]
     empty = [n for n in range(N) if keep[n] == 0]
     assert list(np.frombuffer(blob, dtype="<i4", count=len(nonempty), offset=off)) == nonempty
@@ -168,9 +209,9 @@ def test_blob_decodes_back_to_canonical(bits, n_waves):
 def test_blob_of_empty_matrix():
     W = gi.dense_weight(8, 64, seed=1)
     c = oracle.pack(W, sparsity=1.0)
-    blob = oracle.device_blob(c, 16)
-    # no blocks; {rank_base, tail_closed} = {-1, 1} for every worker; no non-empty rows; 8 empty rows
-    assert np.array_equal(np.frombuffer(blob, dtype="<i4", count=32).reshape(16, 2),
-                          np.tile(np.array([-1, 1]), (16, 1)))
+    blob = oracle.device_blob(c, 1, 16)
+    # no blocks; wave_info = {-1, 1, -1, 0} for every worker; no non-empty rows; 8 empty rows
+    assert np.array_equal(np.frombuffer(blob, dtype="<i4", count=64).reshape(16, 4),
+                          np.tile(np.array([-1, 1, -1, 0]), (16, 1)))
     assert list(np.frombuffer(blob, dtype="<i4", count=8, offset=256)) == list(range(8))
     assert len(blob) == 512

@@ -24,7 +24,7 @@ def assert_same_canonical(h, c):
 def assert_same_blob(h, c):
     info = gq.gqsa_info(h)
     blob = gq.gqsa_export_device_blob(h)
-    ref = oracle.device_blob(c, info["n_waves"])
+    ref = oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"])
     assert len(blob) == len(ref) == info["device_bytes"]
     assert blob == ref
 
@@ -39,7 +39,7 @@ def test_tiny_config_balanced(bits, sparsity):
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == c.nnzg
-    assert info["n_waves"] == oracle.default_n_waves(c.nnzg)
+    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
 
 
@@ -51,10 +51,11 @@ def test_outliers_and_imbalanced_rows(bits):
     h = gq.gqsa_pack_rows(W, keep, 16, bits)
     c = oracle.pack(W, 16, bits, keep_per_row=keep)
     assert_same_canonical(h, c)
-    for n_waves in (None, 1, 2, 3, 5, 16, 17, 64, 1000):
-        if n_waves is not None:
-            gq.gqsa_set_partition(h, n_waves)
-            assert gq.gqsa_info(h)["n_waves"] == n_waves
+    for part in (None, (1, 1), (2, 1), (3, 1), (5, 3), (1, 16), (17, 2), (4, 16), (63, 16), (256, 16)):
+        if part is not None:
+            gq.gqsa_set_partition(h, *part)
+            info = gq.gqsa_info(h)
+            assert (info["n_workgroups"], info["waves_per_workgroup"]) == part
         assert_same_blob(h, c)
 
 
@@ -80,7 +81,7 @@ def test_full_size_7b_shape_bit_exact():
     assert_same_canonical(h, c)
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
-    assert info["nnz_groups"] == 524288 and info["n_waves"] == 4096
+    assert info["nnz_groups"] == 524288 and info["n_workgroups"] == 256 and info["waves_per_workgroup"] == 16
     assert info["algorithmic_bytes"] == 7372804
     assert info["needs_fixup"] == 0      # 128 groups per row: every worker's run ends on a row end
 
