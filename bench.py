@@ -214,6 +214,18 @@ def main():
         sink = torch.zeros(gq.gqsa_stream_read_workgroups(), dtype=torch.int32, device=dev)
         us = time_calls(lambda k: gq.gqsa_stream_read(big, sink), n=20, warm=3)
         out["stream_read_GBps"] = round(big.numel() / us / 1e3, 1)
+        # the same read kernel on slices as small as one packed matrix, walking the 2 GiB buffer
+        # (cold): what a pure read of that many bytes costs, launch included
+        small = []
+        for idx in (0, 4):
+            nbytes = info0[idx]["device_bytes"] // 4096 * 4096
+            nslices = big.numel() // nbytes
+            us = time_calls(lambda k, nbytes=nbytes, nslices=nslices: gq.gqsa_stream_read(
+                big[(k % nslices) * nbytes:(k % nslices + 1) * nbytes], sink))
+            small.append({"bytes": int(nbytes), "us_cold": round(us, 3), "GBps_cold": round(nbytes / us / 1e3, 1)})
+        out["stream_read_matrix_sized"] = small
+        us = time_calls(lambda k: gq.gqsa_launch_floor(256, 9216, sink))
+        out["empty_launch_us"] = round(us, 3)
         del big
 
         # our own dense fp16 GEMV on the same shapes (pool of distinct fp16 matrices > 1 GB)

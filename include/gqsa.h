@@ -37,7 +37,7 @@ typedef struct gqsa_matrix* gqsa_handle_t;
 typedef enum {
     GQSA_OK = 0,
     GQSA_ERR_NULL = 1,         /* a required pointer is NULL */
-    GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K/G > 32768, inconsistent arrays */
+    GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K/G > 4096, inconsistent arrays */
     GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 16, batch outside 1..16 */
     GQSA_ERR_RANGE = 4,        /* sparsity outside [0,1], keep count outside [0,K/G], non-finite W */
     GQSA_ERR_ALLOC = 5,        /* host allocation failed */
@@ -112,6 +112,7 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
  *         groups receive +0
  *   batch 1..16
  *   hip_stream a hipStream_t (NULL = the default stream)
+ * K/G must not exceed 2048 (x and its group sums are staged in LDS); GQSA_ERR_UNSUPPORTED else.
  * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
  * bit-identical from run to run.  Does not synchronise.
  */
@@ -134,9 +135,9 @@ const char* gqsa_status_string(gqsa_status_t s);
 
 /* ------------------------------------------------------------------------------------------
  * Side-by-side kernels measured next to the GQSA path (same GPU, same harness): a dense fp16
- * GEMV and a dense 4-bit group-quantised GEMV (the paper's W4 baseline of Tab. 4 / Tab. 10,
- * i.e. Eq. 1-3 with nothing pruned), plus a read-only streaming kernel that measures the
- * achievable HBM read rate.
+ * GEMV (the FP16 baseline of the paper's Tab. 4 / Tab. 13), a read-only streaming kernel that
+ * measures the achievable HBM read rate, and an empty launch.  The dense 4-bit baseline of
+ * Tab. 4 / Tab. 10 (Eq. 1-3 with nothing pruned) is gqsa_pack with sparsity 0.
  * ------------------------------------------------------------------------------------------ */
 
 /* y[batch,N] = W[N,K] x[batch,K], all fp16 [device], fp32 accumulation. */
@@ -147,6 +148,10 @@ gqsa_status_t gqsa_dense_f16_gemv(const void* W_dev, const void* x_dev, void* y_
  * from gqsa_stream_read_workgroups()); a pure read at full width. */
 gqsa_status_t gqsa_stream_read(const void* buf_dev, size_t bytes, void* sink_dev, void* hip_stream);
 int gqsa_stream_read_workgroups(void);
+
+/* Launch an empty kernel with the GEMV's geometry (n_workgroups x 1024 threads, lds_bytes of
+ * LDS): the cost of a launch by itself, for the benchmark report.  sink_dev [device] non-NULL. */
+gqsa_status_t gqsa_launch_floor(int n_workgroups, int lds_bytes, void* sink_dev, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     64b + p lives in block b + (p mod U), lane p div U.
  4. Block.  Each block is (G*bits/8 + 6)*64 bytes: 64 lanes x code bytes, then
     64 x uint32 (fp16 scale bits | fp16 zero bits << 16), then 64 x uint16
-    (group-column | 0x8000 if the group is the first stored group of its row).
+    (group-column << 4, plus 1 if the group is the first stored group of its
+    row; group-columns are below 4096).
     4-bit codes, G = 16: a lane holds two little-endian uint32; word h holds
     elements 8h..8h+7 of the group, element 8h+2m in bits 4m..4m+3 and element
     8h+2m+1 in bits 16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j of the
@@ -156,11 +157,11 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
         sz_view[block, lane, :] = sz.view(np.uint8).reshape(nnzg, 4)
         # group-column | head flag
         is_head = np.zeros(nnzg, dtype=np.uint16)
-        is_head[head_pos] = 0x8000
+        is_head[head_pos] = 1
         gcol = np.asarray(c.groups, dtype=np.int64)
-        if gcol.size and gcol.max() >= 0x8000:
-            raise ValueError("group-column does not fit 15 bits")
-        idx = (gcol.astype(np.uint16) | is_head).astype("<u2")
+        if gcol.size and gcol.max() >= 4096:
+            raise ValueError("group-column does not fit 12 bits")
+        idx = ((gcol << 4).astype(np.uint16) | is_head).astype("<u2")
         idx_off = sz_off + LANES * 4
         idx_view = blocks[:, idx_off:idx_off + LANES * 2].reshape(nblocks, LANES, 2)
         idx_view[block, lane, :] = idx.view(np.uint8).reshape(nnzg, 2)

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     gqsa_gemv,
     gqsa_import,
     gqsa_info,
+    gqsa_launch_floor,
     gqsa_pack,
     gqsa_pack_rows,
     gqsa_set_partition,

@@ -71,6 +71,8 @@ def _lib():
     lib.gqsa_dense_f16_gemv.argtypes = [vp, vp, vp, i64, i64, i32, vp]
     lib.gqsa_stream_read.restype = C.c_int
     lib.gqsa_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+    lib.gqsa_launch_floor.restype = C.c_int
+    lib.gqsa_launch_floor.argtypes = [i32, i32, vp, vp]
     lib.gqsa_stream_read_workgroups.restype = C.c_int
     lib.gqsa_stream_read_workgroups.argtypes = []
     _LIB = lib
@@ -236,6 +238,11 @@ def gqsa_dense_f16_gemv(W, x, y=None, stream=None):
 
 def gqsa_stream_read_workgroups() -> int:
     return int(_lib().gqsa_stream_read_workgroups())
+
+
+def gqsa_launch_floor(n_workgroups: int, lds_bytes: int, sink, stream=None) -> None:
+    _check(_lib().gqsa_launch_floor(int(n_workgroups), int(lds_bytes), C.c_void_p(sink.data_ptr()),
+                                    _stream_ptr(stream)), "gqsa_launch_floor")
 
 
 def gqsa_stream_read(buf, sink, stream=None) -> None:

@@ -32,11 +32,14 @@ struct GemvArgs {
     int* counters;               // arrivals per carry chain, indexed by the chain's first worker
     const uint16_t* x;           // fp16 [K]
     uint16_t* y;                 // fp16 [N]
-    long long n_blocks;
-    int n_waves;
+    int per_wg;                  // blocks per workgroup (the first extra_wg workgroups hold one more)
+    int extra_wg;
     int n_empty;
     int n_ranks;                 // non-empty rows
     int kg;                      // group-columns K/G
+    // nibble masks and the fp16 pair (1024, 1024); passed in registers so that mask-and-splice
+    // is one three-operand instruction instead of two with literal operands
+    uint32_t nib_lo, nib_hi, k1024x2;
 };
 
 __device__ __forceinline__ float half_to_float(uint32_t bits16)
@@ -55,16 +58,25 @@ __device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_c
 // nibble-permuted at pack time: element 2m sits at bits 4m, element 2m+1 at bits 16+4m, so
 // one AND/OR splices a pair of codes into the mantissas of the fp16 pair (1024+q, 1024+q')
 // or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
-__device__ __forceinline__ float dot8_w4(uint32_t w, uint4 x, float acc)
+// (w & mask) | splice in one instruction; mask is wave-uniform, splice sits in a vector register
+// (the three-operand form takes a single scalar operand).
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t splice)
+{
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(splice));
+    return r;
+}
+
+__device__ __forceinline__ float dot8_w4(const GemvArgs& a, uint32_t w, uint4 x, float acc)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
     const half2_t k64 = {(_Float16)64.0f, (_Float16)64.0f};
     const uint32_t w2 = w >> 8;
-    half2_t q0 = as_half2((w & 0x000F000Fu) | 0x64006400u) - k1024;
-    half2_t q1 = as_half2((w & 0x00F000F0u) | 0x64006400u) * k16th - k64;
-    half2_t q2 = as_half2((w2 & 0x000F000Fu) | 0x64006400u) - k1024;
-    half2_t q3 = as_half2((w2 & 0x00F000F0u) | 0x64006400u) * k16th - k64;
+    half2_t q0 = as_half2(and_or(w, a.nib_lo, a.k1024x2)) - k1024;
+    half2_t q1 = as_half2(and_or(w, a.nib_hi, a.k1024x2)) * k16th - k64;
+    half2_t q2 = as_half2(and_or(w2, a.nib_lo, a.k1024x2)) - k1024;
+    half2_t q3 = as_half2(and_or(w2, a.nib_hi, a.k1024x2)) * k16th - k64;
     acc = __builtin_amdgcn_fdot2(q0, as_half2(x.x), acc, false);
     acc = __builtin_amdgcn_fdot2(q1, as_half2(x.y), acc, false);
     acc = __builtin_amdgcn_fdot2(q2, as_half2(x.z), acc, false);
@@ -85,16 +97,22 @@ __device__ __forceinline__ float dot4_w8(uint32_t w, uint32_t x01, uint32_t x23,
     return acc;
 }
 
-// Value of v in another lane, selected by a DPP control; lanes whose source lane does not
-// exist (or whose row is masked off) read 0.
-// The empty asm pins the cross-lane move where it is written: it must execute with every
-// lane active, so it may not be sunk into the lane-predicated addition that uses its result.
+// v from the lane CTRL names (DPP); lanes whose source lane does not exist, or whose row is
+// not in ROW_MASK, read 0.
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_or_zero(float v)
 {
-    int t = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
-    asm volatile("" : "+v"(t));
-    return __builtin_bit_cast(float, t);
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL,
+                                                                 ROW_MASK, 0xF, ROW_MASK == 0xF));
+}
+
+// t in the lanes whose bit is set in the wave-uniform mask, 0 elsewhere: one select that takes
+// the lane mask straight from a scalar register pair (the masks are made with scalar ops).
+__device__ __forceinline__ float keep_lanes(unsigned long long mask, float t)
+{
+    float r;
+    asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(t), "s"(mask));
+    return r;
 }
 
 struct WaveState {
@@ -119,50 +137,58 @@ struct Tile {
     uint32_t ix[4];
 };
 
-// (1) stream the compressed groups: coalesced loads, all issued before anything waits.
+// (1) stream the compressed groups: coalesced loads, all issued before anything waits.  The
+// block pointer is wave-uniform (scalar base), the lane supplies a 32-bit byte offset.
+template <typename T>
+__device__ __forceinline__ T load_at(const uint8_t* base, uint32_t byte_offset)
+{
+    return *reinterpret_cast<const T*>(base + byte_offset);
+}
+
 template <int BITS>
 __device__ __forceinline__ void load_tile(Tile<BITS>& t, const uint8_t* p, int U, int lane)
 {
     constexpr int CB = 16 * BITS / 8;                 // code bytes per group
     constexpr int BB = (CB + 6) * kLanes;             // block bytes
+    const uint32_t ulane = static_cast<uint32_t>(lane);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         if (u < U) {
-            const uint8_t* blk = p + static_cast<size_t>(u) * BB;
             if constexpr (BITS == 4) {
-                const uint2 c = reinterpret_cast<const uint2*>(blk)[lane];
+                const uint2 c = load_at<uint2>(p, ulane * 8u + u * BB);
                 t.code[u][0] = c.x; t.code[u][1] = c.y;
             } else {
-                const uint4 c = reinterpret_cast<const uint4*>(blk)[lane];
+                const uint4 c = load_at<uint4>(p, ulane * 16u + u * BB);
                 t.code[u][0] = c.x; t.code[u][1] = c.y; t.code[u][2] = c.z; t.code[u][3] = c.w;
             }
-            t.sz[u] = reinterpret_cast<const uint32_t*>(blk + CB * kLanes)[lane];
-            t.ix[u] = reinterpret_cast<const uint16_t*>(blk + (CB + 4) * kLanes)[lane];
+            t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * BB + CB * kLanes));
+            t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * BB + (CB + 4) * kLanes));
         }
     }
 }
 
-template <int BITS, int U>
+// x in LDS: three arrays of 16-byte slots indexed by group-column -- elements 0..7, elements
+// 8..15 and (first 4 bytes) the fp32 sum of the 16 -- KGP slots apart, so that one address
+// register plus immediate offsets serves all three reads of a gather, and a gather of 16 B
+// per lane spreads over all banks.
+template <int BITS, int KGP, int U>
 __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>& t, int lane,
-                                             const uint4* x_lo, const uint4* x_hi,
-                                             const float* x_sum, WaveState& st)
+                                             const uint8_t* xlds, WaveState& st)
 {
     // (2)-(4) gather the activation group by real group index, dequantise, multiply:
     //   sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j)
     float part[U];
-    int heads_before = 0;   // row heads of this superblock in lower lanes
-    int heads_total = 0;
     uint32_t head_bits = 0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const int col = t.ix[u] & 0x7FFF;
-        const uint4 xl = x_lo[col];
-        const uint4 xh = x_hi[col];
-        const float xs = x_sum[col];
+        const uint8_t* xg = xlds + (t.ix[u] & 0xFFF0u);      // index word = column << 4 | head
+        const uint4 xl = *reinterpret_cast<const uint4*>(xg);
+        const uint4 xh = *reinterpret_cast<const uint4*>(xg + 16 * KGP);
+        const float xs = *reinterpret_cast<const float*>(xg + 32 * KGP);
         float d = 0.0f;
         if constexpr (BITS == 4) {
-            d = dot8_w4(t.code[u][0], xl, d);
-            d = dot8_w4(t.code[u][1], xh, d);
+            d = dot8_w4(a, t.code[u][0], xl, d);
+            d = dot8_w4(a, t.code[u][1], xh, d);
         } else {
             d = dot4_w8(t.code[u][0], xl.x, xl.y, d);
             d = dot4_w8(t.code[u][1], xl.z, xl.w, d);
@@ -172,53 +198,73 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
         const float s = half_to_float(t.sz[u] & 0xFFFFu);
         const float z = half_to_float(t.sz[u] >> 16);
         part[u] = s * __builtin_fmaf(-z, xs, d);
-
-        const bool is_head = (t.ix[u] >> 15) != 0;
-        head_bits |= is_head ? (1u << u) : 0u;
-        const unsigned long long bal = __ballot(is_head);
-        heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(bal >> 32),
-                       __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal), heads_before));
-        heads_total += __popcll(bal);
+        head_bits |= (t.ix[u] & 1u) << u;
     }
 
-    // (5a) serial segmented sum over the lane's U consecutive groups
-    float acc = 0.0f, lead = 0.0f;
-    int nh = 0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if (head_bits & (1u << u)) {
-            if (nh == 0) {
-                lead = acc;                       // belongs to the row entering from the left
-            } else {
-                store_row(a, st.rank + heads_before + nh, acc);   // a whole row inside one lane
-            }
-            acc = 0.0f;
-            ++nh;
-        }
-        acc += part[u];
-    }
-
-    // (5b) cross-lane segmented inclusive scan of the lanes' open sums with DPP.  dist = how
-    // far to the left the lane's segment reaches (a lane holding a head starts a segment).
-    // Four shifts inside each row of 16 lanes, then the row totals are handed to the next
-    // rows (lane 15 -> row 1, lane 47 -> row 3, then lane 31 -> rows 2 and 3).
-    const bool has = nh > 0;
+    // (5a) serial segmented sum over the lane's U consecutive groups: lead = what precedes the
+    // lane's first row head, acc = what follows its last one (everything, if it has none)
+    const bool has = head_bits != 0;
     const unsigned long long hmask = __ballot(has);
-    const unsigned long long upto = hmask & ((2ull << lane) - 1ull);
-    const int dist = upto ? lane - (63 - __builtin_clzll(upto)) : lane;
+    float acc = 0.0f, lead = 0.0f;
+    int heads_before;   // row heads of this superblock in lower lanes
+    int heads_total;
+    if (__ballot((head_bits & (head_bits - 1u)) != 0) == 0) {
+        // no lane holds two heads (rows are not shorter than U groups here): branch-free
+        heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(hmask >> 32),
+                       __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(hmask), 0));
+        heads_total = __popcll(hmask);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool before = (head_bits >> u) > 1u;      // the head comes later in this lane
+            lead += before ? part[u] : 0.0f;
+            acc += before ? 0.0f : part[u];
+        }
+    } else {
+        heads_before = 0;
+        heads_total = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned long long bal = __ballot((head_bits >> u) & 1u);
+            heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(bal >> 32),
+                           __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal), heads_before));
+            heads_total += __popcll(bal);
+        }
+        int nh = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (head_bits & (1u << u)) {
+                if (nh == 0) lead = acc;
+                else store_row(a, st.rank + heads_before + nh, acc);   // a whole row inside one lane
+                acc = 0.0f;
+                ++nh;
+            }
+            acc += part[u];
+        }
+    }
+
+    // (5b) cross-lane segmented inclusive scan of the lanes' open sums: DPP shifts inside each
+    // row of 16 lanes, then the row totals are handed on (lane 15 -> row 1, lane 47 -> row 3,
+    // lane 31 -> rows 2 and 3).  A lane takes the value offered at distance d only if no lane
+    // in between (itself included) starts a new segment; those lane sets are wave-uniform
+    // masks, smeared from the head mask with scalar shifts that stay inside a row.
+    const unsigned long long p1 = hmask;
+    const unsigned long long p2 = p1 | ((p1 << 1) & 0xFFFEFFFEFFFEFFFEull);
+    const unsigned long long p4 = p2 | ((p2 << 2) & 0xFFFCFFFCFFFCFFFCull);
+    const unsigned long long p8 = p4 | ((p4 << 4) & 0xFFF0FFF0FFF0FFF0ull);
+    const unsigned long long p16 = p8 | ((p8 << 8) & 0xFF00FF00FF00FF00ull);
+    unsigned long long open31 = ~p16;                       // rows 2, 3 taking lane 31's total
+    if ((hmask >> 32) & 0xFFFFull) open31 &= 0x0000FFFFFFFFFFFFull;   // a head in row 2 cuts row 3 off
     float v = acc;
-    float sh;
-    sh = dpp_or_zero<0x111, 0xF>(v); v += dist >= 1 ? sh : 0.0f;           // row_shr:1
-    sh = dpp_or_zero<0x112, 0xF>(v); v += dist >= 2 ? sh : 0.0f;           // row_shr:2
-    sh = dpp_or_zero<0x114, 0xF>(v); v += dist >= 4 ? sh : 0.0f;           // row_shr:4
-    sh = dpp_or_zero<0x118, 0xF>(v); v += dist >= 8 ? sh : 0.0f;           // row_shr:8
-    sh = dpp_or_zero<0x142, 0xA>(v); v += dist > (lane & 15) ? sh : 0.0f;  // row_bcast:15
-    sh = dpp_or_zero<0x143, 0xC>(v); v += dist > lane - 32 ? sh : 0.0f;    // row_bcast:31
+    v += keep_lanes(~p1, dpp_or_zero<0x111, 0xF>(v));       // row_shr:1
+    v += keep_lanes(~p2, dpp_or_zero<0x112, 0xF>(v));       // row_shr:2
+    v += keep_lanes(~p4, dpp_or_zero<0x114, 0xF>(v));       // row_shr:4
+    v += keep_lanes(~p8, dpp_or_zero<0x118, 0xF>(v));       // row_shr:8
+    v += keep_lanes(~p16, dpp_or_zero<0x142, 0xA>(v));      // row_bcast:15
+    v += keep_lanes(open31, dpp_or_zero<0x143, 0xC>(v));    // row_bcast:31
     // sum flowing into this lane from the left: the previous lane's segment sum, plus the
-    // run's carry if no lower lane holds a head
-    float inflow = dpp_or_zero<0x138, 0xF>(v);                          // wave_shr:1
-    const bool head_before = (hmask & ((1ull << lane) - 1ull)) != 0;
-    if (!head_before) inflow += st.carry;
+    // run's carry for the lanes up to and including the first one that holds a head
+    const unsigned long long upto_first = hmask ? (hmask ^ (hmask - 1ull)) : ~0ull;
+    const float inflow = dpp_or_zero<0x138, 0xF>(v) + keep_lanes(upto_first, st.carry);   // wave_shr:1
 
     const float total = inflow + lead;            // the row this lane's first head closes
     int first_lane = -1;
@@ -270,44 +316,37 @@ struct LdsRecord {
     int chain_len;
 };
 
-template <int BITS>
+template <int BITS, int KGP>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(GemvArgs a)
 {
-    extern __shared__ __align__(16) uint8_t lds[];
-    uint4* x_lo = reinterpret_cast<uint4*>(lds);          // elements 0..7 of every group-column
-    uint4* x_hi = x_lo + a.kg;                            // elements 8..15
-    float* x_sum = reinterpret_cast<float*>(x_hi + a.kg); // sum of the 16 activations
-    __shared__ LdsRecord rec[kWavesPerWorkgroup];
+    extern __shared__ __align__(16) uint8_t xlds[];      // x arrays (48*KGP bytes), then the records
+    LdsRecord* rec = reinterpret_cast<LdsRecord*>(xlds + 48 * KGP);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wpw = blockDim.x >> 6;
-    const int wl = tid >> 6;
+    const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     const int wg = blockIdx.x;
     const int wave = wg * wpw + wl;
     constexpr int BB = (16 * BITS / 8 + 6) * kLanes;
 
     // this worker's run of blocks: the blocks are dealt evenly to the workgroups, a
     // workgroup's blocks evenly to its wavefronts (contiguous runs, equal counts)
-    long long left;
-    const uint8_t* p;
-    {
-        const long long per_wg = a.n_blocks / gridDim.x;
-        const int extra_wg = static_cast<int>(a.n_blocks % gridDim.x);
-        const long long in_wg = per_wg + (wg < extra_wg ? 1 : 0);
-        const long long wg_first = per_wg * wg + (wg < extra_wg ? wg : extra_wg);
-        const long long per_wave = in_wg / wpw;
-        const int extra_wave = static_cast<int>(in_wg % wpw);
-        left = per_wave + (wl < extra_wave ? 1 : 0);
-        p = a.blocks + static_cast<size_t>(wg_first + per_wave * wl + (wl < extra_wave ? wl : extra_wave)) * BB;
-    }
-    auto next_size = [](long long n) { return n >= 4 ? 4 : (n >= 2 ? 2 : static_cast<int>(n)); };
+    const unsigned in_wg = a.per_wg + (wg < a.extra_wg ? 1 : 0);
+    const unsigned wg_first = a.per_wg * wg + (wg < a.extra_wg ? wg : a.extra_wg);
+    const unsigned per_wave = in_wg / static_cast<unsigned>(wpw);
+    const unsigned extra_wave = in_wg - per_wave * wpw;
+    int left = per_wave + (static_cast<unsigned>(wl) < extra_wave ? 1 : 0);
+    const uint8_t* p = a.blocks + static_cast<size_t>(wg_first + per_wave * wl +
+                                                      (static_cast<unsigned>(wl) < extra_wave ? wl : extra_wave)) * BB;
+    auto next_size = [](int n) { return n >= 4 ? 4 : (n >= 2 ? 2 : n); };
 
     // issue the loads of x first and of the first superblock right behind them, so that the
     // weights are already on their way while x is staged in LDS
     auto stage = [&](int c, uint4 lo, uint4 hi) {
-        x_lo[c] = lo;
-        x_hi[c] = hi;
+        uint8_t* slot = xlds + c * 16;
+        *reinterpret_cast<uint4*>(slot) = lo;
+        *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         float s = 0.0f;
 #pragma unroll
@@ -315,7 +354,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
             s += half_to_float(w[i] & 0xFFFFu);
             s += half_to_float(w[i] >> 16);
         }
-        x_sum[c] = s;
+        *reinterpret_cast<float*>(slot + 32 * KGP) = s;
     };
     uint4 lo0 = {0, 0, 0, 0}, hi0 = {0, 0, 0, 0};
     if (tid < a.kg) {
@@ -342,12 +381,12 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     if (active) {
         for (;;) {
             left -= u_cur;
-            const uint8_t* p_next = p + static_cast<size_t>(u_cur) * BB;
+            const uint8_t* p_next = p + u_cur * BB;
             const int u_next = next_size(left);
             load_tile<BITS>(nxt, p_next, u_next, lane);   // next superblock in flight during this one
-            if (u_cur == 4) compute_tile<BITS, 4>(a, cur, lane, x_lo, x_hi, x_sum, st);
-            else if (u_cur == 2) compute_tile<BITS, 2>(a, cur, lane, x_lo, x_hi, x_sum, st);
-            else compute_tile<BITS, 1>(a, cur, lane, x_lo, x_hi, x_sum, st);
+            if (u_cur == 4) compute_tile<BITS, KGP, 4>(a, cur, lane, xlds, st);
+            else if (u_cur == 2) compute_tile<BITS, KGP, 2>(a, cur, lane, xlds, st);
+            else compute_tile<BITS, KGP, 1>(a, cur, lane, xlds, st);
             if (u_next == 0) break;
             cur = nxt;
             u_cur = u_next;
@@ -386,6 +425,21 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     }
 }
 
+using KernelFn = void (*)(GemvArgs);
+
+// The kernel is compiled for group-column counts rounded up to a power of two (the LDS
+// offsets between the three x arrays are immediates).
+template <int BITS>
+KernelFn pick_kernel(int kg, int* kgp)
+{
+    if (kg <= 256) { *kgp = 256; return gqsa_gemv_kernel<BITS, 256>; }
+    if (kg <= 512) { *kgp = 512; return gqsa_gemv_kernel<BITS, 512>; }
+    if (kg <= 1024) { *kgp = 1024; return gqsa_gemv_kernel<BITS, 1024>; }
+    if (kg <= 2048) { *kgp = 2048; return gqsa_gemv_kernel<BITS, 2048>; }
+    *kgp = 0;
+    return nullptr;
+}
+
 #define GQSA_HIP(call)                                                                      \
     do {                                                                                    \
         hipError_t e_ = (call);                                                             \
@@ -399,16 +453,16 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 
 gqsa_status_t device_upload(gqsa_matrix* m)
 {
-    const size_t lds = static_cast<size_t>(m->K / m->G) * 36;
-    if (lds > 160 * 1024) return GQSA_ERR_UNSUPPORTED;
+    int kgp = 0;
+    KernelFn fn = m->bits == 4 ? pick_kernel<4>(static_cast<int>(m->K / m->G), &kgp)
+                               : pick_kernel<8>(static_cast<int>(m->K / m->G), &kgp);
+    if (!fn) return GQSA_ERR_UNSUPPORTED;      // K/G above 2048: x does not fit the LDS layout
     int dev = 0;
     GQSA_HIP(hipGetDevice(&dev));
-    if (lds > 64 * 1024) {
-        GQSA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gqsa_gemv_kernel<4>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        GQSA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gqsa_gemv_kernel<8>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-    }
+    const size_t lds = static_cast<size_t>(kgp) * 48 + kWavesPerWorkgroup * 16;
+    if (lds > 64 * 1024)
+        GQSA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
     void* img = nullptr;
     void* carry = nullptr;
     GQSA_HIP(hipMalloc(&img, m->image.size()));
@@ -449,22 +503,25 @@ gqsa_status_t device_gemv(gqsa_matrix* m, const void* x, void* y, int batch, voi
     a.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
     a.carry = static_cast<CarryRecord*>(m->d_carry);
     a.counters = reinterpret_cast<int*>(a.carry + m->n_waves);
-    a.n_blocks = m->n_blocks;
-    a.n_waves = m->n_waves;
+    a.per_wg = static_cast<int>(m->n_blocks / m->n_workgroups);
+    a.extra_wg = static_cast<int>(m->n_blocks % m->n_workgroups);
     a.n_empty = static_cast<int>(m->n_empty);
     a.n_ranks = static_cast<int>(m->N - m->n_empty);
     a.kg = static_cast<int>(m->K / m->G);
+    a.nib_lo = 0x000F000Fu;
+    a.nib_hi = 0x00F000F0u;
+    a.k1024x2 = 0x64006400u;
 
+    int kgp = 0;
+    KernelFn fn = m->bits == 4 ? pick_kernel<4>(a.kg, &kgp) : pick_kernel<8>(a.kg, &kgp);
+    if (!fn) return GQSA_ERR_UNSUPPORTED;
     const int threads = m->waves_per_workgroup * kLanes;
     const int grid = m->n_workgroups;
-    const size_t lds = static_cast<size_t>(a.kg) * 36;
+    const size_t lds = static_cast<size_t>(kgp) * 48 + kWavesPerWorkgroup * 16;
     for (int b = 0; b < batch; ++b) {
         a.x = static_cast<const uint16_t*>(x) + static_cast<size_t>(b) * m->K;
         a.y = static_cast<uint16_t*>(y) + static_cast<size_t>(b) * m->N;
-        if (m->bits == 4)
-            hipLaunchKernelGGL(gqsa_gemv_kernel<4>, dim3(grid), dim3(threads), lds, s, a);
-        else
-            hipLaunchKernelGGL(gqsa_gemv_kernel<8>, dim3(grid), dim3(threads), lds, s, a);
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;

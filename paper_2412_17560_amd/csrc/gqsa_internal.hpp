@@ -15,7 +15,7 @@ constexpr int kWavesPerWorkgroup = 16; // 1024 threads: one workgroup per comput
 constexpr int kMaxDefaultWorkgroups = 256;  // MI355X: 256 compute units
 constexpr int kMaxWorkgroups = 4096;
 constexpr int kMaxBatch = 16;
-constexpr int64_t kMaxGroupColumns = 32768; // 15-bit group-column + head flag in 16 bits
+constexpr int64_t kMaxGroupColumns = 4096;  // 12-bit group-column << 4 | head flag in 16 bits
 constexpr size_t kAlign = 256;
 
 // Offsets (bytes) of the regions inside the device image.

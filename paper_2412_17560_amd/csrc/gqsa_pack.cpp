@@ -188,7 +188,8 @@ int default_workgroups(int64_t n_blocks)
 // lane l owns U consecutive stream positions, stored one per block so that every block is a
 // fully coalesced, lane-interleaved load:
 //     stream position (first of superblock) + p  ->  block (p mod U), lane (p div U).
-// Block = 64 x code bytes | 64 x (scale | zero << 16) | 64 x (group-column | head << 15).
+// Block = 64 x code bytes | 64 x (scale | zero << 16) | 64 x (group-column << 4 | head), the
+// last one being the byte offset of the activation group in LDS with the row-head flag in bit 0.
 // 4-bit code words are nibble-permuted so that one AND per pair of elements yields a packed
 // fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m at bits 4m and
 // element 8h+2m+1 at bits 16+4m.
@@ -243,7 +244,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         const uint32_t sz = static_cast<uint32_t>(m->scales[g]) |
                             (static_cast<uint32_t>(m->zeros[g]) << 16);
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + lane * 4, &sz, 4);
-        const uint16_t ix = static_cast<uint16_t>(m->groups[g]) | (head[g] ? 0x8000u : 0u);
+        const uint16_t ix = static_cast<uint16_t>((m->groups[g] << 4) | (head[g] ? 1 : 0));
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
 

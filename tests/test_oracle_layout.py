@@ -126,8 +126,9 @@ def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw):
                 zeros[pos] = sz >> 16
                 o = base + 64 * cb + 256 + ln * 2
                 ix = int.from_bytes(raw[o:o + 2].tobytes(), "little")
-                cols[pos] = ix & 0x7FFF
-                heads[pos] = bool(ix & 0x8000)
+                cols[pos] = ix >> 4
+                heads[pos] = bool(ix & 1)
+                assert ix & 0xE == 0
                 pos += 1
             b += U
     assert b == nblocks
