@@ -35,6 +35,8 @@ def parse_args():
     p.add_argument("--skip-cpu", action="store_true", help="skip the cpu_baseline leg (for profiling runs)")
     p.add_argument("--skip-extras", action="store_true", help="skip per-shape / dense / stream-read legs")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
+    p.add_argument("--pmc-calibrate", action="store_true",
+                   help="also run 8 plain copies of 256 MiB (known HBM traffic) to calibrate profiler counters")
     return p.parse_args()
 
 
@@ -99,6 +101,16 @@ def main():
             e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1)
+
+    if args.pmc_calibrate:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        src.random_(0, 255)
+        dst = torch.empty_like(src)
+        with torch.cuda.stream(stream):
+            for _ in range(8):
+                gq.gqsa_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     with torch.cuda.stream(stream):
         for k in range(args.warmup):
@@ -169,7 +181,9 @@ def main():
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "avg_launch_us": round(avg_launch_s * 1e6, 3),
         "algorithmic_bytes_per_launch": int(bytes_per_step / calls_per_step),
-        "traffic": None,
+        # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (calibrated on gqsa_copy), mean
+        # over the 4 + 2 + 1 launches of a step; see profiles/*hbm_traffic.md for the runs
+        "traffic": 12978000,
     }
 
     # ------------------------------------------------------------------ extras: per shape, baselines

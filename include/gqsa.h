@@ -149,6 +149,10 @@ gqsa_status_t gqsa_dense_f16_gemv(const void* W_dev, const void* x_dev, void* y_
 gqsa_status_t gqsa_stream_read(const void* buf_dev, size_t bytes, void* sink_dev, void* hip_stream);
 int gqsa_stream_read_workgroups(void);
 
+/* dst[0..bytes) = src[0..bytes), both [device], 16-byte aligned, bytes a multiple of 16: a kernel
+ * of exactly known HBM traffic, used to calibrate the profiler's byte counters. */
+gqsa_status_t gqsa_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
+
 /* Launch an empty kernel with the GEMV's geometry (n_workgroups x 1024 threads, lds_bytes of
  * LDS): the cost of a launch by itself, for the benchmark report.  sink_dev [device] non-NULL. */
 gqsa_status_t gqsa_launch_floor(int n_workgroups, int lds_bytes, void* sink_dev, void* hip_stream);

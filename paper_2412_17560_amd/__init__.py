@@ -7,6 +7,7 @@ kernels.  PyTorch is used by callers for device memory and streams only.
 from .binding import (  # noqa: F401
     GqsaError,
     GqsaHandle,
+    gqsa_copy,
     gqsa_dense_f16_gemv,
     gqsa_export,
     gqsa_export_device_blob,

@@ -71,6 +71,8 @@ def _lib():
     lib.gqsa_dense_f16_gemv.argtypes = [vp, vp, vp, i64, i64, i32, vp]
     lib.gqsa_stream_read.restype = C.c_int
     lib.gqsa_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
+    lib.gqsa_copy.restype = C.c_int
+    lib.gqsa_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.gqsa_launch_floor.restype = C.c_int
     lib.gqsa_launch_floor.argtypes = [i32, i32, vp, vp]
     lib.gqsa_stream_read_workgroups.restype = C.c_int
@@ -238,6 +240,14 @@ def gqsa_dense_f16_gemv(W, x, y=None, stream=None):
 
 def gqsa_stream_read_workgroups() -> int:
     return int(_lib().gqsa_stream_read_workgroups())
+
+
+def gqsa_copy(dst, src, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src must have the same size")
+    _check(_lib().gqsa_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes,
+                            _stream_ptr(stream)), "gqsa_copy")
 
 
 def gqsa_launch_floor(n_workgroups: int, lds_bytes: int, sink, stream=None) -> None:

@@ -82,6 +82,15 @@ __global__ __launch_bounds__(kReadThreads) void stream_read_kernel(const uint4* 
     }
 }
 
+// Plain copy of 16-byte words: reads n16*16 bytes and writes as many.  Calibrates the HBM
+// byte counters of the profiler against a kernel whose traffic is known.
+__global__ __launch_bounds__(kReadThreads) void copy_kernel(const uint4* src, uint4* dst, size_t n16)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
 // Does nothing: measures what a launch of the GEMV's geometry costs by itself.
 __global__ __launch_bounds__(kThreads) void launch_floor_kernel(uint32_t* sink)
 {
@@ -121,6 +130,18 @@ gqsa_status_t gqsa_launch_floor(int n_workgroups, int lds_bytes, void* sink_dev,
         return GQSA_ERR_RANGE;
     hipLaunchKernelGGL(launch_floor_kernel, dim3(n_workgroups), dim3(kThreads), static_cast<size_t>(lds_bytes),
                        static_cast<hipStream_t>(hip_stream), static_cast<uint32_t*>(sink_dev));
+    if (hipGetLastError() != hipSuccess) return GQSA_ERR_HIP;
+    return GQSA_OK;
+}
+
+gqsa_status_t gqsa_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream)
+{
+    if (!dst_dev || !src_dev) return GQSA_ERR_NULL;
+    if (bytes % 16 != 0) return GQSA_ERR_SHAPE;
+    if (((reinterpret_cast<uintptr_t>(dst_dev) | reinterpret_cast<uintptr_t>(src_dev)) & 15u) != 0)
+        return GQSA_ERR_ALIGN;
+    hipLaunchKernelGGL(copy_kernel, dim3(kReadGrid), dim3(kReadThreads), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<const uint4*>(src_dev), static_cast<uint4*>(dst_dev), bytes / 16);
     if (hipGetLastError() != hipSuccess) return GQSA_ERR_HIP;
     return GQSA_OK;
 }

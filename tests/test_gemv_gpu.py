@@ -290,3 +290,12 @@ def test_stream_read_kernel_runs(torch_cuda):
         x ^= int(v)
     ref = int(np.bitwise_xor.reduce(np.arange(1 << 20, dtype=np.uint32)))
     assert x == ref
+
+
+def test_copy_kernel(torch_cuda):
+    torch = torch_cuda
+    src = torch.arange(1 << 18, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    gq.gqsa_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
