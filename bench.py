@@ -222,6 +222,16 @@ def main():
                               "distinct_matrices": len(hs), "mode": "back-to-back calls, " + mode})
         out["per_shape"] = per_shape
 
+        # small batches on the 4096x4096 shape (weights decoded once for up to 8 rows per launch)
+        hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]
+        small_batch = []
+        for B in (1, 2, 4, 8, 16):
+            xb = torch.from_numpy(gi.activations(B, 4096, seed=gi.config_seed(5, 0))).to(dev)
+            yb = torch.empty((B, 4096), dtype=torch.float16, device=dev)
+            us = time_calls(lambda k, xb=xb, yb=yb: gq.gqsa_gemv(hs[k % len(hs)], xb, yb), n=96)
+            small_batch.append({"batch": B, "us_cold": round(us, 3), "us_per_row": round(us / B, 3)})
+        out["small_batch_4096x4096"] = small_batch
+
         # achievable read ceiling: plain streaming kernel over 2 GiB
         big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
         big.random_(0, 255)

@@ -16,7 +16,8 @@ SOURCES = ["gqsa_pack.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_baselines.hip
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wextra", "-Wno-unused-parameter"]
 # device code: gfx950 only; packed-fp32 instruction selection is switched off
-HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-ffp-contract=off"]   # fused multiply-adds only where the source asks for them
 # host arithmetic of the quantiser: every fp32 operation is a single IEEE operation
 HOST_FLAGS = ["-ffp-contract=off", "-fno-fast-math"]
 

@@ -4,13 +4,16 @@
 // group named by each stored group's real group index, dequantise in registers (Eq. 3),
 // multiply-accumulate, write back -- with the work split "task-centric" (Sec. 3.5, Fig. 5):
 // every wavefront owns an equal, contiguous count of stored groups regardless of row
-// boundaries, reduces them with a segmented wavefront scan, and leaves the partial sums of
-// the rows it shares with its neighbours to a carry fix-up.
+// boundaries, reduces them with a segmented wavefront scan, and settles the rows it shares
+// with its neighbours in a carry fix-up at the end of the same kernel.
 //
 // Wavefront = 64 lanes.  A block is 64 stored groups, one per lane, so that every load is
 // one fully coalesced instruction; in a superblock of U blocks lane l owns the U
 // consecutive stream positions U*l .. U*l+U-1, sums them serially and takes part in ONE
 // cross-lane segmented scan per superblock.
+//
+// Small batches: the kernel is compiled for NB = 1, 2, 4, 8 activation rows per launch; each
+// decoded group is multiplied with all NB rows (weights are read and dequantised once).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -23,15 +26,19 @@ namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
+constexpr int kMaxRowsPerLaunch = 8;      // NB values compiled: 1, 2, 4, 8
+constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one gfx950 compute unit
+
 struct GemvArgs {
     const uint8_t* blocks;
     const int4* wave_info;       // {rank_base, tail_closed, lead_first, chain_len} per worker
     const int32_t* row_of_rank;  // row index of the r-th non-empty row (nullptr: identity)
     const int32_t* empty_rows;
-    CarryRecord* carry;
+    CarryRecord* carry;          // [worker][kMaxRowsPerLaunch]
     int* counters;               // arrivals per carry chain, indexed by the chain's first worker
-    const uint16_t* x;           // fp16 [K]
-    uint16_t* y;                 // fp16 [N]
+    const uint16_t* x;           // fp16 [NB][K]
+    uint16_t* y;                 // fp16 [NB][N]
+    long long N, K;
     int per_wg;                  // blocks per workgroup (the first extra_wg workgroups hold one more)
     int extra_wg;
     int n_empty;
@@ -54,10 +61,6 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
 
 __device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 
-// Eight 4-bit codes of one word against eight activations (four fp16 pairs).  The word is
-// nibble-permuted at pack time: element 2m sits at bits 4m, element 2m+1 at bits 16+4m, so
-// one AND/OR splices a pair of codes into the mantissas of the fp16 pair (1024+q, 1024+q')
-// or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
 // (w & mask) | splice in one instruction; mask is wave-uniform, splice sits in a vector register
 // (the three-operand form takes a single scalar operand).
 __device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t splice)
@@ -67,34 +70,48 @@ __device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t s
     return r;
 }
 
-__device__ __forceinline__ float dot8_w4(const GemvArgs& a, uint32_t w, uint4 x, float acc)
+// The 16 codes of one stored group as eight fp16 pairs (element 2i, 2i+1), exact.
+struct Codes {
+    half2_t q[8];
+};
+
+// 4-bit: the code words are nibble-permuted at pack time (element 2m at bits 4m, element 2m+1
+// at bits 16+4m), so one AND-OR splices a pair of codes into the mantissas of the fp16 pair
+// (1024+q, 1024+q') or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
+__device__ __forceinline__ void decode_w4(const GemvArgs& a, uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
     const half2_t k64 = {(_Float16)64.0f, (_Float16)64.0f};
     const uint32_t w2 = w >> 8;
-    half2_t q0 = as_half2(and_or(w, a.nib_lo, a.k1024x2)) - k1024;
-    half2_t q1 = as_half2(and_or(w, a.nib_hi, a.k1024x2)) * k16th - k64;
-    half2_t q2 = as_half2(and_or(w2, a.nib_lo, a.k1024x2)) - k1024;
-    half2_t q3 = as_half2(and_or(w2, a.nib_hi, a.k1024x2)) * k16th - k64;
-    acc = __builtin_amdgcn_fdot2(q0, as_half2(x.x), acc, false);
-    acc = __builtin_amdgcn_fdot2(q1, as_half2(x.y), acc, false);
-    acc = __builtin_amdgcn_fdot2(q2, as_half2(x.z), acc, false);
-    acc = __builtin_amdgcn_fdot2(q3, as_half2(x.w), acc, false);
-    return acc;
+    q[0] = as_half2(and_or(w, a.nib_lo, a.k1024x2)) - k1024;
+    q[1] = as_half2(and_or(w, a.nib_hi, a.k1024x2)) * k16th - k64;
+    q[2] = as_half2(and_or(w2, a.nib_lo, a.k1024x2)) - k1024;
+    q[3] = as_half2(and_or(w2, a.nib_hi, a.k1024x2)) * k16th - k64;
 }
 
-// Four 8-bit codes (bytes of w, element order) against two fp16 pairs: a byte permute
-// drops each code into the mantissa of 1024.0 (0x64xx), one packed subtract removes the bias.
-__device__ __forceinline__ float dot4_w8(uint32_t w, uint32_t x01, uint32_t x23, float acc)
+// 8-bit: a byte permute drops each code (bytes of w, element order) into the mantissa of
+// 1024.0 (0x64xx), one packed subtract removes the bias.
+__device__ __forceinline__ void decode_w8(uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const uint32_t k64s = 0x64646464u;
-    half2_t q01 = as_half2(__builtin_amdgcn_perm(w, k64s, 0x00050004u)) - k1024;
-    half2_t q23 = as_half2(__builtin_amdgcn_perm(w, k64s, 0x00070006u)) - k1024;
-    acc = __builtin_amdgcn_fdot2(q01, as_half2(x01), acc, false);
-    acc = __builtin_amdgcn_fdot2(q23, as_half2(x23), acc, false);
-    return acc;
+    q[0] = as_half2(__builtin_amdgcn_perm(w, k64s, 0x00050004u)) - k1024;
+    q[1] = as_half2(__builtin_amdgcn_perm(w, k64s, 0x00070006u)) - k1024;
+}
+
+__device__ __forceinline__ float dot16(const Codes& c, uint4 xl, uint4 xh)
+{
+    float d = 0.0f;
+    d = __builtin_amdgcn_fdot2(c.q[0], as_half2(xl.x), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[1], as_half2(xl.y), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[2], as_half2(xl.z), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[3], as_half2(xl.w), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[4], as_half2(xh.x), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[5], as_half2(xh.y), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[6], as_half2(xh.z), d, false);
+    d = __builtin_amdgcn_fdot2(c.q[7], as_half2(xh.w), d, false);
+    return d;
 }
 
 // v from the lane CTRL names (DPP); lanes whose source lane does not exist, or whose row is
@@ -115,18 +132,24 @@ __device__ __forceinline__ float keep_lanes(unsigned long long mask, float t)
     return r;
 }
 
+__device__ __forceinline__ float read_lane(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+template <int NB>
 struct WaveState {
-    float carry;   // sum of the groups since the last row head (or since the run began)
-    float lead;    // sum of the groups before the run's first row head
-    int rank;      // rank (among non-empty rows) of the row that is open now
-    int heads;     // row heads seen so far in this worker's run
+    float carry[NB];   // per activation row: sum of the groups since the last row head
+    float lead[NB];    // sum of the groups before the run's first row head
+    int rank;          // rank (among non-empty rows) of the row that is open now
+    int heads;         // row heads seen so far in this worker's run
 };
 
-__device__ __forceinline__ void store_row(const GemvArgs& a, int rank, float v)
+__device__ __forceinline__ void store_row(const GemvArgs& a, int b, int rank, float v)
 {
     if (static_cast<unsigned>(rank) >= static_cast<unsigned>(a.n_ranks)) return;  // never for a valid image
     const int row = a.row_of_rank ? a.row_of_rank[rank] : rank;
-    a.y[row] = float_to_half_bits(v);
+    a.y[b * a.N + row] = float_to_half_bits(v);
 }
 
 // The compressed groups of up to four blocks, as loaded (one group per lane per block).
@@ -167,61 +190,28 @@ __device__ __forceinline__ void load_tile(Tile<BITS>& t, const uint8_t* p, int U
     }
 }
 
-// x in LDS: three arrays of 16-byte slots indexed by group-column -- elements 0..7, elements
-// 8..15 and (first 4 bytes) the fp32 sum of the 16 -- KGP slots apart, so that one address
-// register plus immediate offsets serves all three reads of a gather, and a gather of 16 B
-// per lane spreads over all banks.
-template <int BITS, int KGP, int U>
+// x in LDS, per activation row: three arrays of 16-byte slots indexed by group-column --
+// elements 0..7, elements 8..15 and (first 4 bytes) the fp32 sum of the 16 -- KGP slots
+// apart, so that one address register plus immediate offsets serves all reads of a gather, and
+// a gather of 16 B per lane spreads over all banks.  Row b starts at b * 48 * KGP.
+template <int BITS, int KGP, int U, int NB>
 __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>& t, int lane,
-                                             const uint8_t* xlds, WaveState& st)
+                                             const uint8_t* xlds, WaveState<NB>& st)
 {
-    // (2)-(4) gather the activation group by real group index, dequantise, multiply:
-    //   sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j)
-    float part[U];
     uint32_t head_bits = 0;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const uint8_t* xg = xlds + (t.ix[u] & 0xFFF0u);      // index word = column << 4 | head
-        const uint4 xl = *reinterpret_cast<const uint4*>(xg);
-        const uint4 xh = *reinterpret_cast<const uint4*>(xg + 16 * KGP);
-        const float xs = *reinterpret_cast<const float*>(xg + 32 * KGP);
-        float d = 0.0f;
-        if constexpr (BITS == 4) {
-            d = dot8_w4(a, t.code[u][0], xl, d);
-            d = dot8_w4(a, t.code[u][1], xh, d);
-        } else {
-            d = dot4_w8(t.code[u][0], xl.x, xl.y, d);
-            d = dot4_w8(t.code[u][1], xl.z, xl.w, d);
-            d = dot4_w8(t.code[u][2], xh.x, xh.y, d);
-            d = dot4_w8(t.code[u][3], xh.z, xh.w, d);
-        }
-        const float s = half_to_float(t.sz[u] & 0xFFFFu);
-        const float z = half_to_float(t.sz[u] >> 16);
-        part[u] = s * __builtin_fmaf(-z, xs, d);
-        head_bits |= (t.ix[u] & 1u) << u;
-    }
-
-    // (5a) serial segmented sum over the lane's U consecutive groups: lead = what precedes the
-    // lane's first row head, acc = what follows its last one (everything, if it has none)
+    for (int u = 0; u < U; ++u) head_bits |= (t.ix[u] & 1u) << u;   // index word = column << 4 | head
     const bool has = head_bits != 0;
     const unsigned long long hmask = __ballot(has);
-    float acc = 0.0f, lead = 0.0f;
-    int heads_before;   // row heads of this superblock in lower lanes
-    int heads_total;
-    if (__ballot((head_bits & (head_bits - 1u)) != 0) == 0) {
-        // no lane holds two heads (rows are not shorter than U groups here): branch-free
+    // no lane holds two heads (no row shorter than U groups here): branch-free serial sums
+    const bool simple = __ballot((head_bits & (head_bits - 1u)) != 0) == 0;
+    int heads_before = 0;   // row heads of this superblock in lower lanes
+    int heads_total = 0;
+    if (simple) {
         heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(hmask >> 32),
                        __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(hmask), 0));
         heads_total = __popcll(hmask);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool before = (head_bits >> u) > 1u;      // the head comes later in this lane
-            lead += before ? part[u] : 0.0f;
-            acc += before ? 0.0f : part[u];
-        }
     } else {
-        heads_before = 0;
-        heads_total = 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const unsigned long long bal = __ballot((head_bits >> u) & 1u);
@@ -229,16 +219,59 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
                            __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal), heads_before));
             heads_total += __popcll(bal);
         }
-        int nh = 0;
+    }
+
+    // (2)-(4) gather the activation group by real group index, dequantise, multiply:
+    //   sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j)
+    // (5a) and add serially over the lane's U consecutive groups: lead = what precedes the
+    // lane's first row head, acc = what follows its last one (everything, if it has none)
+    float acc[NB], lead[NB];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (head_bits & (1u << u)) {
-                if (nh == 0) lead = acc;
-                else store_row(a, st.rank + heads_before + nh, acc);   // a whole row inside one lane
-                acc = 0.0f;
+    for (int b = 0; b < NB; ++b) { acc[b] = 0.0f; lead[b] = 0.0f; }
+    int nh = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        Codes c;
+        if constexpr (BITS == 4) {
+            decode_w4(a, t.code[u][0], &c.q[0]);
+            decode_w4(a, t.code[u][1], &c.q[4]);
+        } else {
+            decode_w8(t.code[u][0], &c.q[0]);
+            decode_w8(t.code[u][1], &c.q[2]);
+            decode_w8(t.code[u][2], &c.q[4]);
+            decode_w8(t.code[u][3], &c.q[6]);
+        }
+        const float s = half_to_float(t.sz[u] & 0xFFFFu);
+        const float z = half_to_float(t.sz[u] >> 16);
+        const uint8_t* xg = xlds + (t.ix[u] & 0xFFF0u);
+        float dotz[NB];   // sum_j q_j x_j - z sum_j x_j; times s it is the group's contribution
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const uint8_t* xb = xg + b * (48 * KGP);
+            const uint4 xl = *reinterpret_cast<const uint4*>(xb);
+            const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
+            const float xs = *reinterpret_cast<const float*>(xb + 32 * KGP);
+            dotz[b] = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
+        }
+        const bool head_here = (head_bits >> u) & 1u;
+        if (simple) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                lead[b] = head_here ? acc[b] : lead[b];     // the only head of this lane
+                acc[b] = __builtin_fmaf(s, dotz[b], head_here ? 0.0f : acc[b]);
+            }
+        } else {
+            if (head_here) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    if (nh == 0) lead[b] = acc[b];
+                    else store_row(a, b, st.rank + heads_before + nh, acc[b]);   // a whole row inside one lane
+                    acc[b] = 0.0f;
+                }
                 ++nh;
             }
-            acc += part[u];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(s, dotz[b], acc[b]);
         }
     }
 
@@ -254,30 +287,29 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
     const unsigned long long p16 = p8 | ((p8 << 8) & 0xFF00FF00FF00FF00ull);
     unsigned long long open31 = ~p16;                       // rows 2, 3 taking lane 31's total
     if ((hmask >> 32) & 0xFFFFull) open31 &= 0x0000FFFFFFFFFFFFull;   // a head in row 2 cuts row 3 off
-    float v = acc;
-    v += keep_lanes(~p1, dpp_or_zero<0x111, 0xF>(v));       // row_shr:1
-    v += keep_lanes(~p2, dpp_or_zero<0x112, 0xF>(v));       // row_shr:2
-    v += keep_lanes(~p4, dpp_or_zero<0x114, 0xF>(v));       // row_shr:4
-    v += keep_lanes(~p8, dpp_or_zero<0x118, 0xF>(v));       // row_shr:8
-    v += keep_lanes(~p16, dpp_or_zero<0x142, 0xA>(v));      // row_bcast:15
-    v += keep_lanes(open31, dpp_or_zero<0x143, 0xC>(v));    // row_bcast:31
-    // sum flowing into this lane from the left: the previous lane's segment sum, plus the
-    // run's carry for the lanes up to and including the first one that holds a head
+    // the run's carry flows into the lanes up to and including the first one that holds a head
     const unsigned long long upto_first = hmask ? (hmask ^ (hmask - 1ull)) : ~0ull;
-    const float inflow = dpp_or_zero<0x138, 0xF>(v) + keep_lanes(upto_first, st.carry);   // wave_shr:1
-
-    const float total = inflow + lead;            // the row this lane's first head closes
+    // first head of the whole run: what precedes it belongs to a row that began in an earlier
+    // worker's run (or to nothing, if the run starts on a head)
     int first_lane = -1;
-    if (st.heads == 0 && hmask != 0) {
-        // first head of the whole run: what precedes it belongs to a row that began in an
-        // earlier worker's run (or to nothing, if the run starts on a head)
-        first_lane = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hmask));
-        st.lead = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, total), first_lane));
-    }
-    if (has && lane != first_lane) store_row(a, st.rank + heads_before, total);
+    if (st.heads == 0 && hmask != 0) first_lane = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hmask));
 
-    const float last = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
-    st.carry = (hmask ? 0.0f : st.carry) + last;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        float v = acc[b];
+        v += keep_lanes(~p1, dpp_or_zero<0x111, 0xF>(v));       // row_shr:1
+        v += keep_lanes(~p2, dpp_or_zero<0x112, 0xF>(v));       // row_shr:2
+        v += keep_lanes(~p4, dpp_or_zero<0x114, 0xF>(v));       // row_shr:4
+        v += keep_lanes(~p8, dpp_or_zero<0x118, 0xF>(v));       // row_shr:8
+        v += keep_lanes(~p16, dpp_or_zero<0x142, 0xA>(v));      // row_bcast:15
+        v += keep_lanes(open31, dpp_or_zero<0x143, 0xC>(v));    // row_bcast:31
+        // sum flowing into this lane from the left: the previous lane's segment sum (+ carry)
+        const float inflow = dpp_or_zero<0x138, 0xF>(v) + keep_lanes(upto_first, st.carry[b]);   // wave_shr:1
+        const float total = inflow + lead[b];       // the row this lane's first head closes
+        if (first_lane >= 0) st.lead[b] = read_lane(total, first_lane);
+        if (has && lane != first_lane) store_row(a, b, st.rank + heads_before, total);
+        st.carry[b] = (hmask ? 0.0f : st.carry[b]) + read_lane(v, 63);
+    }
     st.rank += heads_total;
     st.heads += heads_total;
 }
@@ -288,6 +320,7 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
 // order (so the sum does not depend on arrival order) and writes the row.  All accesses to
 // the records and counters are device-scope atomics, ordered by program order plus a wait
 // for the stores to complete -- no cache write-back or invalidate is needed.
+template <int NB>
 __device__ __forceinline__ void chain_arrive(const GemvArgs& a, int first)
 {
     const int4 head_info = a.wave_info[first];
@@ -295,32 +328,38 @@ __device__ __forceinline__ void chain_arrive(const GemvArgs& a, int first)
     const int old = __hip_atomic_fetch_add(&a.counters[first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old != len - 1) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    const int heads0 = __hip_atomic_load(&a.carry[first].heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    float sum = __hip_atomic_load(&a.carry[first].tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int b = first + 1; b < first + len; ++b) {
-        const int hb = __hip_atomic_load(&a.carry[b].heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const float piece = hb == 0
-            ? __hip_atomic_load(&a.carry[b].tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)   // whole run
-            : __hip_atomic_load(&a.carry[b].lead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // up to its first head
-        sum += piece;
+    for (int b = 0; b < NB; ++b) {
+        const CarryRecord* r0 = &a.carry[first * kMaxRowsPerLaunch + b];
+        const int heads0 = __hip_atomic_load(&r0->heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        float sum = __hip_atomic_load(&r0->tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int w = first + 1; w < first + len; ++w) {
+            const CarryRecord* r = &a.carry[w * kMaxRowsPerLaunch + b];
+            const int hw = __hip_atomic_load(&r->heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sum += hw == 0 ? __hip_atomic_load(&r->tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)    // whole run
+                           : __hip_atomic_load(&r->lead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // up to its first head
+        }
+        store_row(a, b, head_info.x + heads0, sum);
     }
-    store_row(a, head_info.x + heads0, sum);
     __hip_atomic_store(&a.counters[first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
 }
 
 // What a wavefront tells its workgroup about the rows it shares with its neighbours.
-struct LdsRecord {
+struct LdsSums {
     float lead;
     float tail;
+};
+struct LdsCounts {
     int heads;
     int chain_len;
 };
 
-template <int BITS, int KGP>
+template <int BITS, int KGP, int NB>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(GemvArgs a)
 {
-    extern __shared__ __align__(16) uint8_t xlds[];      // x arrays (48*KGP bytes), then the records
-    LdsRecord* rec = reinterpret_cast<LdsRecord*>(xlds + 48 * KGP);
+    // x arrays (NB * 48 * KGP bytes), then the wavefronts' records
+    extern __shared__ __align__(16) uint8_t xlds[];
+    LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);
+    LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + kWavesPerWorkgroup);   // [wavefront][NB]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -343,8 +382,9 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 
     // issue the loads of x first and of the first superblock right behind them, so that the
     // weights are already on their way while x is staged in LDS
-    auto stage = [&](int c, uint4 lo, uint4 hi) {
-        uint8_t* slot = xlds + c * 16;
+    auto stage = [&](int c, uint4 lo, uint4 hi) {   // c = slot over all rows: b * kg + column
+        const int b = NB == 1 ? 0 : c / a.kg;
+        uint8_t* slot = xlds + b * (48 * KGP) + (c - b * a.kg) * 16;
         *reinterpret_cast<uint4*>(slot) = lo;
         *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -356,8 +396,9 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         }
         *reinterpret_cast<float*>(slot + 32 * KGP) = s;
     };
+    const int n_slots = NB * a.kg;                  // x is [NB][K] contiguous: slot c holds x[16c .. 16c+15]
     uint4 lo0 = {0, 0, 0, 0}, hi0 = {0, 0, 0, 0};
-    if (tid < a.kg) {
+    if (tid < n_slots) {
         const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(tid) * 16);
         lo0 = src[0];
         hi0 = src[1];
@@ -367,26 +408,33 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     const bool active = u_cur > 0;
     load_tile<BITS>(cur, p, u_cur, lane);
     const int4 info = a.wave_info[wave];   // a worker without blocks may still sit inside a row
-    if (tid < a.kg) stage(tid, lo0, hi0);
-    for (int c = tid + blockDim.x; c < a.kg; c += blockDim.x) {
+    if (tid < n_slots) stage(tid, lo0, hi0);
+    for (int c = tid + blockDim.x; c < n_slots; c += blockDim.x) {
         const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(c) * 16);
         stage(c, src[0], src[1]);
     }
     // rows without stored groups: exactly +0
-    for (int i = blockIdx.x * blockDim.x + tid; i < a.n_empty; i += gridDim.x * blockDim.x)
-        a.y[a.empty_rows[i]] = 0;
+    for (int i = blockIdx.x * blockDim.x + tid; i < a.n_empty; i += gridDim.x * blockDim.x) {
+        const int row = a.empty_rows[i];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) a.y[b * a.N + row] = 0;
+    }
     __syncthreads();
 
-    WaveState st{0.0f, 0.0f, info.x, 0};
+    WaveState<NB> st;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) { st.carry[b] = 0.0f; st.lead[b] = 0.0f; }
+    st.rank = info.x;
+    st.heads = 0;
     if (active) {
         for (;;) {
             left -= u_cur;
             const uint8_t* p_next = p + u_cur * BB;
             const int u_next = next_size(left);
             load_tile<BITS>(nxt, p_next, u_next, lane);   // next superblock in flight during this one
-            if (u_cur == 4) compute_tile<BITS, KGP, 4>(a, cur, lane, xlds, st);
-            else if (u_cur == 2) compute_tile<BITS, KGP, 2>(a, cur, lane, xlds, st);
-            else compute_tile<BITS, KGP, 1>(a, cur, lane, xlds, st);
+            if (u_cur == 4) compute_tile<BITS, KGP, 4, NB>(a, cur, lane, xlds, st);
+            else if (u_cur == 2) compute_tile<BITS, KGP, 2, NB>(a, cur, lane, xlds, st);
+            else compute_tile<BITS, KGP, 1, NB>(a, cur, lane, xlds, st);
             if (u_next == 0) break;
             cur = nxt;
             u_cur = u_next;
@@ -396,48 +444,94 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 
     // Carry fix-up for the rows this run shares with its neighbours.  Inside a workgroup the
     // pieces meet in LDS; only rows spread over several workgroups go through device memory.
-    if (lane == 0) rec[wl] = LdsRecord{st.lead, st.carry, st.heads, info.w};
+    if (lane == 0) {
+        rec_n[wl] = LdsCounts{st.heads, info.w};
+#pragma unroll
+        for (int b = 0; b < NB; ++b) rec_s[wl * NB + b] = LdsSums{st.lead[b], st.carry[b]};
+    }
     __syncthreads();
     if (lane != 0) return;
 
-    if (info.y != 0 && st.heads > 0) store_row(a, st.rank, st.carry);   // last row ends with the run
+    if (info.y != 0 && st.heads > 0) {        // last row ends with the run
+#pragma unroll
+        for (int b = 0; b < NB; ++b) store_row(a, b, st.rank, st.carry[b]);
+    }
     bool global_tail = false, global_lead = false;
     if (info.w > 0) {                         // this worker holds the head of a row that continues
         if (wl + info.w <= wpw) {
-            float sum = st.carry;
-            for (int b = wl + 1; b < wl + info.w; ++b) sum += rec[b].heads == 0 ? rec[b].tail : rec[b].lead;
-            store_row(a, st.rank, sum);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                float sum = st.carry[b];
+                for (int w = wl + 1; w < wl + info.w; ++w)
+                    sum += rec_n[w].heads == 0 ? rec_s[w * NB + b].tail : rec_s[w * NB + b].lead;
+                store_row(a, b, st.rank, sum);
+            }
         } else {
             global_tail = true;
         }
     }
     if (info.z >= 0) {                        // its first groups continue a row of an earlier worker
         const int fl = info.z - wg * wpw;     // that worker's index in this workgroup (if >= 0)
-        global_lead = fl < 0 || fl + rec[fl < 0 ? 0 : fl].chain_len > wpw;
+        global_lead = fl < 0 || fl + rec_n[fl < 0 ? 0 : fl].chain_len > wpw;
     }
     if (global_tail || global_lead) {
-        __hip_atomic_store(&a.carry[wave].lead, st.lead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.carry[wave].tail, st.carry, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&a.carry[wave].heads, st.heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            CarryRecord* r = &a.carry[wave * kMaxRowsPerLaunch + b];
+            __hip_atomic_store(&r->lead, st.lead[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&r->tail, st.carry[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&r->heads, st.heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
-        if (global_lead) chain_arrive(a, info.z);
-        if (global_tail) chain_arrive(a, wave);
+        if (global_lead) chain_arrive<NB>(a, info.z);
+        if (global_tail) chain_arrive<NB>(a, wave);
     }
 }
 
 using KernelFn = void (*)(GemvArgs);
 
-// The kernel is compiled for group-column counts rounded up to a power of two (the LDS
-// offsets between the three x arrays are immediates).
-template <int BITS>
-KernelFn pick_kernel(int kg, int* kgp)
+constexpr size_t lds_bytes(int kgp, int nb)
 {
-    if (kg <= 256) { *kgp = 256; return gqsa_gemv_kernel<BITS, 256>; }
-    if (kg <= 512) { *kgp = 512; return gqsa_gemv_kernel<BITS, 512>; }
-    if (kg <= 1024) { *kgp = 1024; return gqsa_gemv_kernel<BITS, 1024>; }
-    if (kg <= 2048) { *kgp = 2048; return gqsa_gemv_kernel<BITS, 2048>; }
+    return static_cast<size_t>(nb) * 48 * kgp + kWavesPerWorkgroup * (sizeof(LdsCounts) + nb * sizeof(LdsSums));
+}
+
+template <int BITS, int KGP, int NB>
+KernelFn kernel_if_it_fits()
+{
+    if constexpr (lds_bytes(KGP, NB) <= kMaxLdsBytes) return gqsa_gemv_kernel<BITS, KGP, NB>;
+    else return nullptr;
+}
+
+template <int BITS, int KGP>
+KernelFn pick_rows(int nb)
+{
+    switch (nb) {
+        case 1: return kernel_if_it_fits<BITS, KGP, 1>();
+        case 2: return kernel_if_it_fits<BITS, KGP, 2>();
+        case 4: return kernel_if_it_fits<BITS, KGP, 4>();
+        case 8: return kernel_if_it_fits<BITS, KGP, 8>();
+    }
+    return nullptr;
+}
+
+// The kernel is compiled for group-column counts rounded up to a power of two (the LDS
+// offsets between the x arrays are immediates) and for 1, 2, 4 or 8 activation rows per
+// launch, as far as NB copies of x fit the 160 KB of LDS.
+template <int BITS>
+KernelFn pick_kernel(int kg, int nb, int* kgp)
+{
+    if (kg <= 256) { *kgp = 256; return pick_rows<BITS, 256>(nb); }
+    if (kg <= 512) { *kgp = 512; return pick_rows<BITS, 512>(nb); }
+    if (kg <= 1024) { *kgp = 1024; return pick_rows<BITS, 1024>(nb); }
+    if (kg <= 2048) { *kgp = 2048; return pick_rows<BITS, 2048>(nb); }
     *kgp = 0;
     return nullptr;
+}
+
+KernelFn pick(const gqsa_matrix* m, int nb, int* kgp)
+{
+    const int kg = static_cast<int>(m->K / m->G);
+    return m->bits == 4 ? pick_kernel<4>(kg, nb, kgp) : pick_kernel<8>(kg, nb, kgp);
 }
 
 #define GQSA_HIP(call)                                                                      \
@@ -454,20 +548,22 @@ KernelFn pick_kernel(int kg, int* kgp)
 gqsa_status_t device_upload(gqsa_matrix* m)
 {
     int kgp = 0;
-    KernelFn fn = m->bits == 4 ? pick_kernel<4>(static_cast<int>(m->K / m->G), &kgp)
-                               : pick_kernel<8>(static_cast<int>(m->K / m->G), &kgp);
-    if (!fn) return GQSA_ERR_UNSUPPORTED;      // K/G above 2048: x does not fit the LDS layout
+    if (!pick(m, 1, &kgp)) return GQSA_ERR_UNSUPPORTED;      // K/G above 2048: x does not fit the LDS layout
     int dev = 0;
     GQSA_HIP(hipGetDevice(&dev));
-    const size_t lds = static_cast<size_t>(kgp) * 48 + kWavesPerWorkgroup * 16;
-    if (lds > 64 * 1024)
-        GQSA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)));
+    for (int nb = 1; nb <= kMaxRowsPerLaunch; nb *= 2) {
+        KernelFn fn = pick(m, nb, &kgp);
+        if (fn && lds_bytes(kgp, nb) > 64 * 1024)
+            GQSA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         static_cast<int>(lds_bytes(kgp, nb))));
+    }
     void* img = nullptr;
     void* carry = nullptr;
     GQSA_HIP(hipMalloc(&img, m->image.size()));
-    // carry records followed by one arrival counter per worker (zero between calls)
-    const size_t carry_bytes = static_cast<size_t>(m->n_waves) * (sizeof(CarryRecord) + sizeof(int));
+    // carry records (per worker and activation row) followed by one arrival counter per worker
+    const size_t carry_bytes = static_cast<size_t>(m->n_waves) *
+                               (kMaxRowsPerLaunch * sizeof(CarryRecord) + sizeof(int));
     hipError_t e = hipMalloc(&carry, carry_bytes);
     if (e == hipSuccess) e = hipMemcpy(img, m->image.data(), m->image.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(carry, 0, carry_bytes);
@@ -502,7 +598,9 @@ gqsa_status_t device_gemv(gqsa_matrix* m, const void* x, void* y, int batch, voi
     a.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
     a.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
     a.carry = static_cast<CarryRecord*>(m->d_carry);
-    a.counters = reinterpret_cast<int*>(a.carry + m->n_waves);
+    a.counters = reinterpret_cast<int*>(a.carry + static_cast<size_t>(m->n_waves) * kMaxRowsPerLaunch);
+    a.N = m->N;
+    a.K = m->K;
     a.per_wg = static_cast<int>(m->n_blocks / m->n_workgroups);
     a.extra_wg = static_cast<int>(m->n_blocks % m->n_workgroups);
     a.n_empty = static_cast<int>(m->n_empty);
@@ -512,16 +610,23 @@ gqsa_status_t device_gemv(gqsa_matrix* m, const void* x, void* y, int batch, voi
     a.nib_hi = 0x00F000F0u;
     a.k1024x2 = 0x64006400u;
 
-    int kgp = 0;
-    KernelFn fn = m->bits == 4 ? pick_kernel<4>(a.kg, &kgp) : pick_kernel<8>(a.kg, &kgp);
-    if (!fn) return GQSA_ERR_UNSUPPORTED;
     const int threads = m->waves_per_workgroup * kLanes;
     const int grid = m->n_workgroups;
-    const size_t lds = static_cast<size_t>(kgp) * 48 + kWavesPerWorkgroup * 16;
-    for (int b = 0; b < batch; ++b) {
-        a.x = static_cast<const uint16_t*>(x) + static_cast<size_t>(b) * m->K;
-        a.y = static_cast<uint16_t*>(y) + static_cast<size_t>(b) * m->N;
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds, s, a);
+    // the batch goes out in launches of 8, 4, 2 or 1 rows: the most that fits LDS and is left
+    int done = 0;
+    while (done < batch) {
+        int nb = kMaxRowsPerLaunch, kgp = 0;
+        KernelFn fn = nullptr;
+        for (; nb >= 1; nb /= 2) {
+            if (nb > batch - done) continue;
+            fn = pick(m, nb, &kgp);
+            if (fn) break;
+        }
+        if (!fn) return GQSA_ERR_UNSUPPORTED;
+        a.x = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m->K;
+        a.y = static_cast<uint16_t*>(y) + static_cast<size_t>(done) * m->N;
+        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds_bytes(kgp, nb), s, a);
+        done += nb;
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;
