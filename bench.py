@@ -32,6 +32,7 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=24)
     p.add_argument("--pool-layers", type=int, default=12, help="distinct layer sets in HBM (12 = 1.07 GB)")
     p.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    p.add_argument("--separate", action="store_true", help="seven separate launches per layer instead of 4")
     p.add_argument("--skip-cpu", action="store_true", help="skip the cpu_baseline leg (for profiling runs)")
     p.add_argument("--skip-extras", action="store_true", help="skip per-shape / dense / stream-read legs")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -84,8 +85,17 @@ def main():
     ys = [torch.empty((1, N), dtype=torch.float16, device=dev) for (_, N, _) in gi.LLAMA7B_LAYER]
 
     def enqueue_step(k):
-        for h, i in layers[k % args.pool_layers]:
-            gq.gqsa_gemv(h, xs[gi.LLAMA7B_LAYER[i][2]], ys[i])
+        """One decoder layer: seven GEMVs.  Calls that share their input go out as one launch
+        (q/k/v and gate/up), as a decoder would issue them: 4 launches per layer."""
+        mats = layers[k % args.pool_layers]
+        if args.separate:
+            for h, i in mats:
+                gq.gqsa_gemv(h, xs[gi.LLAMA7B_LAYER[i][2]], ys[i])
+            return
+        gq.gqsa_gemv_multi([mats[0][0], mats[1][0], mats[2][0]], xs[4096], ys[0:3])
+        gq.gqsa_gemv(mats[3][0], xs[4096], ys[3])
+        gq.gqsa_gemv_multi([mats[4][0], mats[5][0]], xs[4096], ys[4:6])
+        gq.gqsa_gemv(mats[6][0], xs[11008], ys[6])
 
     stream = torch.cuda.Stream()
     calls_per_step = len(gi.LLAMA7B_LAYER)
@@ -160,27 +170,30 @@ def main():
             "pool_layers": args.pool_layers,
             "pool_device_bytes": int(pool_bytes),
             "launch_mode": mode,
+            "launches_per_step": 7 if args.separate else 4,
         },
         "us_per_call": round(us_per_call, 3),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "eager_ms_per_step": round(eager_ms / args.steps, 6),
         "pool_build_s": round(t_build, 1),
     }
-    # dominant kernel: gqsa_gemv_kernel<4>, one launch per call.  Average launch duration is
-    # the event-timed region divided by the launches in it (so it contains the carry fix-up
-    # launches and the gaps between kernels); bytes are the algorithmic bytes of the calls.
-    launches = args.steps * calls_per_step
+    # dominant kernel: gqsa_gemv_kernel<4, KGP, 1>; a launch covers one call, or the calls of a
+    # layer that share x (q/k/v, gate/up).  Average launch duration is the event-timed region
+    # divided by the launches in it (so it contains the gaps between dependent kernels); bytes are
+    # the algorithmic bytes of the calls a launch covers.
+    launches_per_step = 7 if args.separate else 4
+    launches = args.steps * launches_per_step
     avg_launch_s = total_ms * 1e-3 / launches
-    achieved = (bytes_per_step / calls_per_step) / avg_launch_s / 1e9
+    achieved = (bytes_per_step / launches_per_step) / avg_launch_s / 1e9
     out["roofline"] = {
         "bound": "hbm",
-        "kernel": "gqsa_gemv_kernel<4>",
+        "kernel": "gqsa_gemv_kernel<4, KGP, 1>",
         "achieved": round(achieved, 2),
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "avg_launch_us": round(avg_launch_s * 1e6, 3),
-        "algorithmic_bytes_per_launch": int(bytes_per_step / calls_per_step),
+        "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step),
         # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (calibrated on gqsa_copy), mean
         # over the 4 + 2 + 1 launches of a step; see profiles/*hbm_traffic.md for the runs
         "traffic": 12978000,

@@ -119,6 +119,21 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
 gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
                         void* hip_stream);
 
+/*
+ * Several matrices that share the activation vector -- q/k/v or gate/up of a decoder layer, the
+ * way the paper's engine runs seven GEMVs per layer (Sec. 4.4) -- in ONE launch:
+ * y_devs[i] = W^_i x for i < n_matrices (1..4).  Every wavefront walks its share of the first
+ * matrix, then of the second, ... as one pipelined stream, so launch, x staging and first-byte
+ * latency are paid once.
+ *   handles  [host] array of n_matrices distinct handles with equal K, G, bits and equal
+ *            partition (n_workgroups, waves_per_workgroup); GQSA_ERR_SHAPE otherwise
+ *   x_dev    [device] fp16 [batch,K], 16-byte aligned
+ *   y_devs   [host] array of n_matrices [device] pointers, y_devs[i] fp16 [batch,N_i]
+ * Results are bit-identical to n_matrices separate gqsa_gemv calls.
+ */
+gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, const void* x_dev,
+                              void* const* y_devs, int batch, void* hip_stream);
+
 gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out);
 
 /* Copy the canonical arrays out; any pointer may be NULL to skip it.  Sizes from gqsa_info:

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     gqsa_export_device_blob,
     gqsa_free,
     gqsa_gemv,
+    gqsa_gemv_multi,
     gqsa_import,
     gqsa_info,
     gqsa_launch_floor,

@@ -57,6 +57,8 @@ def _lib():
     lib.gqsa_upload.argtypes = [vp]
     lib.gqsa_gemv.restype = C.c_int
     lib.gqsa_gemv.argtypes = [vp, vp, vp, i32, vp]
+    lib.gqsa_gemv_multi.restype = C.c_int
+    lib.gqsa_gemv_multi.argtypes = [C.POINTER(vp), i32, vp, C.POINTER(vp), i32, vp]
     lib.gqsa_info.restype = C.c_int
     lib.gqsa_info.argtypes = [vp, C.POINTER(_Info)]
     lib.gqsa_export.restype = C.c_int
@@ -221,6 +223,27 @@ def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None):
                             _dev_ptr(y, "torch.float16", "y"), batch, _stream_ptr(stream)),
            "gqsa_gemv")
     return y
+
+
+def gqsa_gemv_multi(hs, x, ys=None, stream=None):
+    """ys[i][batch,N_i] = W^_i x for several matrices sharing x, in one launch."""
+    import torch
+    infos = [gqsa_info(h) for h in hs]
+    if x.dim() == 1:
+        x = x.unsqueeze(0)
+    batch = x.shape[0]
+    if any(x.shape[1] != inf["K"] for inf in infos):
+        raise ValueError("x must be [batch, K] for every matrix")
+    if ys is None:
+        ys = [torch.empty((batch, inf["N"]), dtype=torch.float16, device=x.device) for inf in infos]
+    if len(ys) != len(hs) or any(tuple(y.shape) != (batch, inf["N"]) for y, inf in zip(ys, infos)):
+        raise ValueError("ys[i] must be [batch, N_i]")
+    n = len(hs)
+    harr = (C.c_void_p * n)(*[h.ptr.value for h in hs])
+    yarr = (C.c_void_p * n)(*[_dev_ptr(y, "torch.float16", "y").value for y in ys])
+    _check(_lib().gqsa_gemv_multi(harr, n, _dev_ptr(x, "torch.float16", "x"), yarr, batch,
+                                  _stream_ptr(stream)), "gqsa_gemv_multi")
+    return ys
 
 
 def gqsa_dense_f16_gemv(W, x, y=None, stream=None):

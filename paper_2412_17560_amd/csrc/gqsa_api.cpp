@@ -121,7 +121,34 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
     if (!h->d_image) {
         if (gqsa_status_t st = gqsa::device_upload(h)) return st;
     }
-    return gqsa::device_gemv(h, x_dev, y_dev, batch, hip_stream);
+    return gqsa::device_gemv(&h, 1, x_dev, &y_dev, batch, hip_stream);
+}
+
+gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, const void* x_dev,
+                              void* const* y_devs, int batch, void* hip_stream)
+{
+    if (!handles || !x_dev || !y_devs) return GQSA_ERR_NULL;
+    if (n_matrices < 1 || n_matrices > gqsa::kMaxMatricesPerLaunch) return GQSA_ERR_UNSUPPORTED;
+    if (batch < 1 || batch > gqsa::kMaxBatch) return GQSA_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x_dev) & 15u) != 0) return GQSA_ERR_ALIGN;
+    for (int i = 0; i < n_matrices; ++i) {
+        if (!handles[i] || !y_devs[i]) return GQSA_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(y_devs[i]) & 1u) != 0) return GQSA_ERR_ALIGN;
+        const gqsa_matrix* m = handles[i];
+        const gqsa_matrix* m0 = handles[0];
+        // one stream of work: same x, same code width, same deal of blocks to wavefronts
+        if (m->K != m0->K || m->G != m0->G || m->bits != m0->bits) return GQSA_ERR_SHAPE;
+        if (m->n_workgroups != m0->n_workgroups || m->waves_per_workgroup != m0->waves_per_workgroup)
+            return GQSA_ERR_SHAPE;
+        for (int j = 0; j < i; ++j)
+            if (handles[j] == handles[i]) return GQSA_ERR_SHAPE;   // a handle has one carry workspace
+    }
+    for (int i = 0; i < n_matrices; ++i) {
+        if (!handles[i]->d_image) {
+            if (gqsa_status_t st = gqsa::device_upload(handles[i])) return st;
+        }
+    }
+    return gqsa::device_gemv(handles, n_matrices, x_dev, y_devs, batch, hip_stream);
 }
 
 gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)

@@ -16,6 +16,7 @@
 // decoded group is multiplied with all NB rows (weights are read and dequantised once).
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdint>
 #include <cstdio>
 
@@ -29,25 +30,89 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 constexpr int kMaxRowsPerLaunch = 8;      // NB values compiled: 1, 2, 4, 8
 constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one gfx950 compute unit
 
-struct GemvArgs {
+constexpr int kMaxMatrices = 4;           // matrices sharing x that one launch can take
+
+// One packed matrix as the kernel sees it, split by when it is needed.  The argument block is
+// read with scalar loads one 64-byte line at a time and every line is a round trip of its own
+// (the block may live in host memory), so everything the first weight load depends on sits in
+// the first line; the rest is fetched in one batch while those weights are on their way.
+struct MatRun {                  // where a worker's run of blocks is (32 bytes)
     const uint8_t* blocks;
-    const int4* wave_info;       // {rank_base, tail_closed, lead_first, chain_len} per worker
+    int per_wg;                  // blocks per workgroup (the first extra_wg workgroups hold one more)
+    int extra_wg;
+    int per_wave[2];             // blocks per wavefront in a workgroup of per_wg (+1) blocks ...
+    int extra_wave[2];           // ... of which the first extra_wave wavefronts hold one more
+};
+
+struct MatArgs {                 // where results go (56 bytes)
     const int32_t* row_of_rank;  // row index of the r-th non-empty row (nullptr: identity)
     const int32_t* empty_rows;
     CarryRecord* carry;          // [worker][kMaxRowsPerLaunch]
     int* counters;               // arrivals per carry chain, indexed by the chain's first worker
-    const uint16_t* x;           // fp16 [NB][K]
     uint16_t* y;                 // fp16 [NB][N]
-    long long N, K;
-    int per_wg;                  // blocks per workgroup (the first extra_wg workgroups hold one more)
-    int extra_wg;
+    long long N;
     int n_empty;
     int n_ranks;                 // non-empty rows
+};
+
+template <int NM>
+struct GemvArgsT {
+    // ---- first 64-byte line
+    const uint16_t* x;           // fp16 [NB][K], shared by the matrices
+    int n_mats;
     int kg;                      // group-columns K/G
     // nibble masks and the fp16 pair (1024, 1024); passed in registers so that mask-and-splice
     // is one three-operand instruction instead of two with literal operands
     uint32_t nib_lo, nib_hi, k1024x2;
+    int wpw;                     // wavefronts per workgroup
+    MatRun run[NM];              // run[0] completes the first line
+    // ---- later lines
+    const int4* wave_info[NM];   // {rank_base, tail_closed, lead_first, chain_len} per worker
+    int n_wg;                    // workgroups
+    int pad;
+    MatArgs m[NM];
 };
+typedef GemvArgsT<kMaxMatrices> GemvArgs;     // what the host fills in; a launch passes the first NM
+static_assert(offsetof(GemvArgs, run) == 32 && sizeof(MatRun) == 32, "the first matrix's run closes line 0");
+
+// run[i] / m[i] of the kernel's argument block for a wave-uniform i, read from the
+// kernel-argument segment itself (scalar loads from constant memory); indexing the by-value
+// argument with a run-time i would make the compiler copy the whole block to scratch.
+// GemvArgs is the kernel's only parameter, so it sits at offset 0 of the segment.
+template <int NM>
+__device__ __forceinline__ MatRun matrix_run(int i)
+{
+    typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
+    typedef const __attribute__((address_space(4))) MatRun* ConstRunPtr;
+    ConstRunPtr src = (ConstRunPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(GemvArgsT<NM>, run)) + i;
+    MatRun r;
+    r.blocks = src->blocks;
+    r.per_wg = src->per_wg;
+    r.extra_wg = src->extra_wg;
+    r.per_wave[0] = src->per_wave[0];
+    r.per_wave[1] = src->per_wave[1];
+    r.extra_wave[0] = src->extra_wave[0];
+    r.extra_wave[1] = src->extra_wave[1];
+    return r;
+}
+
+template <int NM>
+__device__ __forceinline__ MatArgs matrix_args(int i)
+{
+    typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
+    typedef const __attribute__((address_space(4))) MatArgs* ConstMatPtr;
+    ConstMatPtr src = (ConstMatPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(GemvArgsT<NM>, m)) + i;
+    MatArgs r;
+    r.row_of_rank = src->row_of_rank;
+    r.empty_rows = src->empty_rows;
+    r.carry = src->carry;
+    r.counters = src->counters;
+    r.y = src->y;
+    r.N = src->N;
+    r.n_empty = src->n_empty;
+    r.n_ranks = src->n_ranks;
+    return r;
+}
 
 __device__ __forceinline__ float half_to_float(uint32_t bits16)
 {
@@ -78,7 +143,8 @@ struct Codes {
 // 4-bit: the code words are nibble-permuted at pack time (element 2m at bits 4m, element 2m+1
 // at bits 16+4m), so one AND-OR splices a pair of codes into the mantissas of the fp16 pair
 // (1024+q, 1024+q') or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
-__device__ __forceinline__ void decode_w4(const GemvArgs& a, uint32_t w, half2_t* q)
+template <typename Args>
+__device__ __forceinline__ void decode_w4(const Args& a, uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
@@ -145,11 +211,11 @@ struct WaveState {
     int heads;         // row heads seen so far in this worker's run
 };
 
-__device__ __forceinline__ void store_row(const GemvArgs& a, int b, int rank, float v)
+__device__ __forceinline__ void store_row(const MatArgs& m, int b, int rank, float v)
 {
-    if (static_cast<unsigned>(rank) >= static_cast<unsigned>(a.n_ranks)) return;  // never for a valid image
-    const int row = a.row_of_rank ? a.row_of_rank[rank] : rank;
-    a.y[b * a.N + row] = float_to_half_bits(v);
+    if (static_cast<unsigned>(rank) >= static_cast<unsigned>(m.n_ranks)) return;  // never for a valid image
+    const int row = m.row_of_rank ? m.row_of_rank[rank] : rank;
+    m.y[b * m.N + row] = float_to_half_bits(v);
 }
 
 // The compressed groups of up to four blocks, as loaded (one group per lane per block).
@@ -166,6 +232,26 @@ template <typename T>
 __device__ __forceinline__ T load_at(const uint8_t* base, uint32_t byte_offset)
 {
     return *reinterpret_cast<const T*>(base + byte_offset);
+}
+
+template <int BITS, int U>
+__device__ __forceinline__ void load_tile_n(Tile<BITS>& t, const uint8_t* p, int lane)
+{
+    constexpr int CB = 16 * BITS / 8;                 // code bytes per group
+    constexpr int BB = (CB + 6) * kLanes;             // block bytes
+    const uint32_t ulane = static_cast<uint32_t>(lane);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if constexpr (BITS == 4) {
+            const uint2 c = load_at<uint2>(p, ulane * 8u + u * BB);
+            t.code[u][0] = c.x; t.code[u][1] = c.y;
+        } else {
+            const uint4 c = load_at<uint4>(p, ulane * 16u + u * BB);
+            t.code[u][0] = c.x; t.code[u][1] = c.y; t.code[u][2] = c.z; t.code[u][3] = c.w;
+        }
+        t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * BB + CB * kLanes));
+        t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * BB + (CB + 4) * kLanes));
+    }
 }
 
 template <int BITS>
@@ -194,31 +280,32 @@ __device__ __forceinline__ void load_tile(Tile<BITS>& t, const uint8_t* p, int U
 // elements 0..7, elements 8..15 and (first 4 bytes) the fp32 sum of the 16 -- KGP slots
 // apart, so that one address register plus immediate offsets serves all reads of a gather, and
 // a gather of 16 B per lane spreads over all banks.  Row b starts at b * 48 * KGP.
-template <int BITS, int KGP, int U, int NB>
-__device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>& t, int lane,
-                                             const uint8_t* xlds, WaveState<NB>& st)
+template <int BITS, int KGP, int U, int NB, typename Args>
+__device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, const Tile<BITS>& t,
+                                             int lane, const uint8_t* xlds, WaveState<NB>& st)
 {
-    uint32_t head_bits = 0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) head_bits |= (t.ix[u] & 1u) << u;   // index word = column << 4 | head
-    const bool has = head_bits != 0;
-    const unsigned long long hmask = __ballot(has);
-    // no lane holds two heads (no row shorter than U groups here): branch-free serial sums
-    const bool simple = __ballot((head_bits & (head_bits - 1u)) != 0) == 0;
-    int heads_before = 0;   // row heads of this superblock in lower lanes
+    // Row heads as wave-uniform lane masks, one per position of the superblock (index word =
+    // column << 4 | head); counting them is scalar work.
+    unsigned long long bal[U];
+    unsigned long long hmask = 0;
     int heads_total = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        bal[u] = __ballot((t.ix[u] & 1u) != 0);
+        hmask |= bal[u];
+        heads_total += __popcll(bal[u]);
+    }
+    // no lane holds two heads (no row shorter than U groups here): branch-free serial sums
+    const bool simple = heads_total == static_cast<int>(__popcll(hmask));
+    int heads_before = 0;   // row heads of this superblock in lower lanes
     if (simple) {
         heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(hmask >> 32),
                        __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(hmask), 0));
-        heads_total = __popcll(hmask);
     } else {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const unsigned long long bal = __ballot((head_bits >> u) & 1u);
-            heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(bal >> 32),
-                           __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal), heads_before));
-            heads_total += __popcll(bal);
-        }
+        for (int u = 0; u < U; ++u)
+            heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(bal[u] >> 32),
+                           __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal[u]), heads_before));
     }
 
     // (2)-(4) gather the activation group by real group index, dequantise, multiply:
@@ -253,7 +340,7 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
             const float xs = *reinterpret_cast<const float*>(xb + 32 * KGP);
             dotz[b] = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
         }
-        const bool head_here = (head_bits >> u) & 1u;
+        const bool head_here = (t.ix[u] & 1u) != 0;
         if (simple) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -265,7 +352,7 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     if (nh == 0) lead[b] = acc[b];
-                    else store_row(a, b, st.rank + heads_before + nh, acc[b]);   // a whole row inside one lane
+                    else store_row(m, b, st.rank + heads_before + nh, acc[b]);   // a whole row inside one lane
                     acc[b] = 0.0f;
                 }
                 ++nh;
@@ -292,7 +379,7 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
     // first head of the whole run: what precedes it belongs to a row that began in an earlier
     // worker's run (or to nothing, if the run starts on a head)
     int first_lane = -1;
-    if (st.heads == 0 && hmask != 0) first_lane = __builtin_amdgcn_readfirstlane(__builtin_ctzll(hmask));
+    if (st.heads == 0 && hmask != 0) first_lane = static_cast<int>(__builtin_ctzll(hmask));   // (uniform: a scalar)
 
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -307,7 +394,7 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
         const float inflow = dpp_or_zero<0x138, 0xF>(v) + keep_lanes(upto_first, st.carry[b]);   // wave_shr:1
         const float total = inflow + lead[b];       // the row this lane's first head closes
         if (first_lane >= 0) st.lead[b] = read_lane(total, first_lane);
-        if (has && lane != first_lane) store_row(a, b, st.rank + heads_before, total);
+        if (((hmask >> lane) & 1ull) != 0 && lane != first_lane) store_row(m, b, st.rank + heads_before, total);
         st.carry[b] = (hmask ? 0.0f : st.carry[b]) + read_lane(v, 63);
     }
     st.rank += heads_total;
@@ -321,26 +408,26 @@ __device__ __forceinline__ void compute_tile(const GemvArgs& a, const Tile<BITS>
 // the records and counters are device-scope atomics, ordered by program order plus a wait
 // for the stores to complete -- no cache write-back or invalidate is needed.
 template <int NB>
-__device__ __forceinline__ void chain_arrive(const GemvArgs& a, int first)
+__device__ __forceinline__ void chain_arrive(const MatArgs& m, const int4* wave_info, int first)
 {
-    const int4 head_info = a.wave_info[first];
+    const int4 head_info = wave_info[first];
     const int len = head_info.w;
-    const int old = __hip_atomic_fetch_add(&a.counters[first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int old = __hip_atomic_fetch_add(&m.counters[first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old != len - 1) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     for (int b = 0; b < NB; ++b) {
-        const CarryRecord* r0 = &a.carry[first * kMaxRowsPerLaunch + b];
+        const CarryRecord* r0 = &m.carry[first * kMaxRowsPerLaunch + b];
         const int heads0 = __hip_atomic_load(&r0->heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         float sum = __hip_atomic_load(&r0->tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (int w = first + 1; w < first + len; ++w) {
-            const CarryRecord* r = &a.carry[w * kMaxRowsPerLaunch + b];
+            const CarryRecord* r = &m.carry[w * kMaxRowsPerLaunch + b];
             const int hw = __hip_atomic_load(&r->heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             sum += hw == 0 ? __hip_atomic_load(&r->tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)    // whole run
                            : __hip_atomic_load(&r->lead, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // up to its first head
         }
-        store_row(a, b, head_info.x + heads0, sum);
+        store_row(m, b, head_info.x + heads0, sum);
     }
-    __hip_atomic_store(&a.counters[first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
+    __hip_atomic_store(&m.counters[first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
 }
 
 // What a wavefront tells its workgroup about the rows it shares with its neighbours.
@@ -349,35 +436,107 @@ struct LdsSums {
     float tail;
 };
 struct LdsCounts {
-    int heads;
-    int chain_len;
+    int4 info;     // the worker's {rank_base, tail_closed, lead_first, chain_len} in this matrix
+    int heads;     // row heads inside its run
+    int pad[3];
 };
 
-template <int BITS, int KGP, int NB>
-__global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(GemvArgs a)
+// Carry fix-up of one matrix by lane 0 of a wavefront, after the workgroup's records are in LDS:
+// rows shared inside the workgroup are summed in worker order by the wavefront holding their
+// head; rows spread over several workgroups go through device memory (chain_arrive).
+template <int NB>
+__device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave_info, int4 info, int heads,
+                                             const float* own_lead, const float* own_tail,
+                                             const LdsCounts* cn, const LdsSums* cs, int wl, int wg, int wpw,
+                                             int wave)
 {
-    // x arrays (NB * 48 * KGP bytes), then the wavefronts' records
+    const int rank_open = info.x + heads;
+    if (info.y != 0 && heads > 0) {           // last row ends with the run
+#pragma unroll
+        for (int b = 0; b < NB; ++b) store_row(mo, b, rank_open, own_tail[b]);
+    }
+    bool global_tail = false, global_lead = false;
+    if (info.w > 0) {                         // this worker holds the head of a row that continues
+        if (wl + info.w <= wpw) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                float sum = own_tail[b];
+                for (int w = wl + 1; w < wl + info.w; ++w)
+                    sum += cn[w].heads == 0 ? cs[w * NB + b].tail : cs[w * NB + b].lead;
+                store_row(mo, b, rank_open, sum);
+            }
+        } else {
+            global_tail = true;
+        }
+    }
+    if (info.z >= 0) {                        // its first groups continue a row of an earlier worker
+        const int fl = info.z - wg * wpw;     // that worker's index in this workgroup (if >= 0)
+        global_lead = fl < 0 || fl + cn[fl < 0 ? 0 : fl].info.w > wpw;
+    }
+    if (global_tail || global_lead) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            CarryRecord* r = &mo.carry[wave * kMaxRowsPerLaunch + b];
+            __hip_atomic_store(&r->lead, own_lead[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&r->tail, own_tail[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&r->heads, heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
+        if (global_lead) chain_arrive<NB>(mo, wave_info, info.z);
+        if (global_tail) chain_arrive<NB>(mo, wave_info, wave);
+    }
+}
+
+// v_i for i < NM, chosen with scalar selects (arguments by value: an object holding them would
+// be indexed in memory).
+template <int NM>
+__device__ __forceinline__ int pick_of(int i, int v0, int v1, int v2, int v3)
+{
+    int r = v0;
+    if (NM > 1 && i == 1) r = v1;
+    if (NM > 2 && i == 2) r = v2;
+    if (NM > 3 && i == 3) r = v3;
+    return r;
+}
+
+// One launch multiplies up to kMaxMatrices packed matrices that share x (q/k/v or gate/up of a
+// decoder layer) -- the wavefront walks its run in the first matrix, then its run in the
+// second, ... as one pipelined stream, so launch, x staging and first-byte latency are paid
+// once.  With one matrix this is the plain GEMV.
+struct ParkedArgs {
+    MatArgs m;
+    const int4* wave_info;
+};
+
+template <int BITS, int KGP, int NB, int NM>
+__global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(GemvArgsT<NM> a)
+{
+    // x arrays (NB * 48 * KGP bytes), then the wavefronts' records per matrix
     extern __shared__ __align__(16) uint8_t xlds[];
-    LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);
-    LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + kWavesPerWorkgroup);   // [wavefront][NB]
+    LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);            // [matrix][wavefront]
+    LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + NM * kWavesPerWorkgroup);  // [matrix][wavefront][NB]
+    // the output arguments of every matrix, parked for the fix-up at the end of the kernel (reading
+    // them from the argument block there would put a round trip on the kernel's tail)
+    ParkedArgs* parked = reinterpret_cast<ParkedArgs*>(rec_s + NM * kWavesPerWorkgroup * NB);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wpw = blockDim.x >> 6;
+    const int wpw = a.wpw;
+    const int n_threads = wpw * kLanes;
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     const int wg = blockIdx.x;
     const int wave = wg * wpw + wl;
     constexpr int BB = (16 * BITS / 8 + 6) * kLanes;
 
-    // this worker's run of blocks: the blocks are dealt evenly to the workgroups, a
+    // a worker's run of blocks in a matrix: the blocks are dealt evenly to the workgroups, a
     // workgroup's blocks evenly to its wavefronts (contiguous runs, equal counts)
-    const unsigned in_wg = a.per_wg + (wg < a.extra_wg ? 1 : 0);
-    const unsigned wg_first = a.per_wg * wg + (wg < a.extra_wg ? wg : a.extra_wg);
-    const unsigned per_wave = in_wg / static_cast<unsigned>(wpw);
-    const unsigned extra_wave = in_wg - per_wave * wpw;
-    int left = per_wave + (static_cast<unsigned>(wl) < extra_wave ? 1 : 0);
-    const uint8_t* p = a.blocks + static_cast<size_t>(wg_first + per_wave * wl +
-                                                      (static_cast<unsigned>(wl) < extra_wave ? wl : extra_wave)) * BB;
+    auto run_of = [&](const MatRun& r, int& left, const uint8_t*& p) {
+        const int big = wg < r.extra_wg ? 1 : 0;              // this workgroup holds per_wg + 1 blocks
+        const int wg_first = r.per_wg * wg + (big ? wg : r.extra_wg);
+        const int per_wave = r.per_wave[big], extra_wave = r.extra_wave[big];
+        left = per_wave + (wl < extra_wave ? 1 : 0);
+        p = r.blocks + static_cast<size_t>(wg_first + per_wave * wl + (wl < extra_wave ? wl : extra_wave)) * BB;
+    };
     auto next_size = [](int n) { return n >= 4 ? 4 : (n >= 2 ? 2 : n); };
 
     // issue the loads of x first and of the first superblock right behind them, so that the
@@ -397,141 +556,239 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         *reinterpret_cast<float*>(slot + 32 * KGP) = s;
     };
     const int n_slots = NB * a.kg;                  // x is [NB][K] contiguous: slot c holds x[16c .. 16c+15]
+
+    // the first matrix in which this worker owns blocks
+    int mi = 0, left = 0;
+    const uint8_t* p = nullptr;
+    run_of(a.run[0], left, p);
+    while (left == 0 && mi + 1 < NM) {
+        ++mi;
+        run_of(matrix_run<NM>(mi), left, p);
+    }
+    // The first superblock's loads go out first, x right behind them (both need only the first
+    // line of the argument block); then the per-matrix worker records (what the fix-up needs to
+    // know about this worker; a worker without blocks may still sit inside a row) and the
+    // output arguments; then x is staged in LDS.
+    Tile<BITS> cur, nxt;
+    int u_cur = next_size(left);
+    load_tile<BITS>(cur, p, u_cur, lane);
     uint4 lo0 = {0, 0, 0, 0}, hi0 = {0, 0, 0, 0};
     if (tid < n_slots) {
         const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(tid) * 16);
         lo0 = src[0];
         hi0 = src[1];
     }
-    Tile<BITS> cur, nxt;
-    int u_cur = next_size(left);
-    const bool active = u_cur > 0;
-    load_tile<BITS>(cur, p, u_cur, lane);
-    const int4 info = a.wave_info[wave];   // a worker without blocks may still sit inside a row
+    // Everything else comes from later lines of the argument block and from the worker table:
+    // requested now, while the weights are on their way.  (Left alone, the compiler issues these
+    // loads where their results are first used -- after the wait for x -- and their latency
+    // would land on the critical path; the worker record is therefore fetched with a vector
+    // load through a lane offset the compiler cannot see through, and the arguments are pinned.)
+    int lane_zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+    typedef int int4_t __attribute__((ext_vector_type(4)));
+    auto info_of = [&](int i) { return reinterpret_cast<const int4_t*>(a.wave_info[i])[wave + lane_zero]; };
+    const int4_t info0 = info_of(0);
+    const int4_t info1 = NM > 1 ? info_of(1) : int4_t{-1, 1, -1, 0};
+    const int4_t info2 = NM > 2 ? info_of(2) : int4_t{-1, 1, -1, 0};
+    const int4_t info3 = NM > 3 ? info_of(3) : int4_t{-1, 1, -1, 0};
+    MatArgs m = a.m[0];
+    if constexpr (NM > 1) m = matrix_args<NM>(mi);
+    asm volatile("" ::"s"(m.row_of_rank), "s"(m.y), "s"(m.N), "s"(m.n_ranks));
+#pragma unroll
+    for (int i = 0; i < NM; ++i)
+        asm volatile("" ::"s"(a.m[i].empty_rows), "s"(a.m[i].carry), "s"(a.m[i].counters), "s"(a.m[i].y),
+                     "s"(a.m[i].n_empty), "s"(a.wave_info[i]), "s"(a.n_wg));
     if (tid < n_slots) stage(tid, lo0, hi0);
-    for (int c = tid + blockDim.x; c < n_slots; c += blockDim.x) {
+    for (int c = tid + n_threads; c < n_slots; c += n_threads) {
         const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(c) * 16);
         stage(c, src[0], src[1]);
     }
-    // rows without stored groups: exactly +0
-    for (int i = blockIdx.x * blockDim.x + tid; i < a.n_empty; i += gridDim.x * blockDim.x) {
-        const int row = a.empty_rows[i];
+    // rows without stored groups: exactly +0; and this worker's records start out as "nothing"
 #pragma unroll
-        for (int b = 0; b < NB; ++b) a.y[b * a.N + row] = 0;
+    for (int i = 0; i < NM; ++i) {
+        {
+            if (NM > 1 && tid == 0) parked[i] = ParkedArgs{a.m[i], a.wave_info[i]};
+            if (lane == 0) {
+                rec_n[i * kWavesPerWorkgroup + wl].heads = 0;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) rec_s[(i * kWavesPerWorkgroup + wl) * NB + b] = LdsSums{0.0f, 0.0f};
+            }
+            for (int e = wg * n_threads + tid; e < a.m[i].n_empty; e += a.n_wg * n_threads) {
+                const int row = a.m[i].empty_rows[e];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) a.m[i].y[b * a.m[i].N + row] = 0;
+            }
+        }
     }
     __syncthreads();
 
     WaveState<NB> st;
 #pragma unroll
     for (int b = 0; b < NB; ++b) { st.carry[b] = 0.0f; st.lead[b] = 0.0f; }
-    st.rank = info.x;
+    // The rank bases move to scalar registers here, where every load has arrived anyway: waiting
+    // for the worker records inside the loop would also wait for the superblock prefetched
+    // there, since loads complete in order.
+    const int rb0 = __builtin_amdgcn_readfirstlane(info0.x);
+    const int rb1 = NM > 1 ? __builtin_amdgcn_readfirstlane(info1.x) : 0;
+    const int rb2 = NM > 2 ? __builtin_amdgcn_readfirstlane(info2.x) : 0;
+    const int rb3 = NM > 3 ? __builtin_amdgcn_readfirstlane(info3.x) : 0;
+    asm volatile("" ::"s"(rb0), "s"(rb1), "s"(rb2), "s"(rb3));
+    auto rank_base_of = [=](int i) { return pick_of<NM>(i, rb0, rb1, rb2, rb3); };
+    st.rank = rank_base_of(mi);
     st.heads = 0;
-    if (active) {
+    WaveState<NB> fin = st;      // the finished run's sums (with one matrix the fix-up takes them from here)
+    if (u_cur > 0) {
         for (;;) {
+            // where the stream goes on: the next superblock of this run, or the first one of the
+            // worker's run in the next matrix that has blocks for it
             left -= u_cur;
             const uint8_t* p_next = p + u_cur * BB;
-            const int u_next = next_size(left);
-            load_tile<BITS>(nxt, p_next, u_next, lane);   // next superblock in flight during this one
-            if (u_cur == 4) compute_tile<BITS, KGP, 4, NB>(a, cur, lane, xlds, st);
-            else if (u_cur == 2) compute_tile<BITS, KGP, 2, NB>(a, cur, lane, xlds, st);
-            else compute_tile<BITS, KGP, 1, NB>(a, cur, lane, xlds, st);
+            int u_next = next_size(left);
+            int mi_next = mi;
+            while (u_next == 0 && mi_next + 1 < NM) {
+                ++mi_next;
+                run_of(matrix_run<NM>(mi_next), left, p_next);
+                u_next = next_size(left);
+            }
+            load_tile<BITS>(nxt, p_next, u_next, lane);   // in flight during this superblock
+            if (u_cur == 4) compute_tile<BITS, KGP, 4, NB>(a, m, cur, lane, xlds, st);
+            else if (u_cur == 2) compute_tile<BITS, KGP, 2, NB>(a, m, cur, lane, xlds, st);
+            else compute_tile<BITS, KGP, 1, NB>(a, m, cur, lane, xlds, st);
+            if (mi_next != mi || u_next == 0) {           // this matrix's run is complete
+                if (lane == 0) {
+                    rec_n[mi * kWavesPerWorkgroup + wl].heads = st.heads;   // (info is filled in below)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        rec_s[(mi * kWavesPerWorkgroup + wl) * NB + b] = LdsSums{st.lead[b], st.carry[b]};
+                }
+                if constexpr (NM > 1) {     // (with one matrix the state stays in registers for the fix-up)
+                    fin = st;
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) { st.carry[b] = 0.0f; st.lead[b] = 0.0f; }
+                    st.rank = rank_base_of(mi_next);
+                    st.heads = 0;
+                }
+            }
             if (u_next == 0) break;
             cur = nxt;
             u_cur = u_next;
             p = p_next;
+            if (mi_next != mi) m = matrix_args<NM>(mi_next);
+            mi = mi_next;
         }
     }
 
-    // Carry fix-up for the rows this run shares with its neighbours.  Inside a workgroup the
+    if constexpr (NM == 1) fin = st;
+    // Carry fix-up for the rows a run shares with its neighbours.  Inside a workgroup the
     // pieces meet in LDS; only rows spread over several workgroups go through device memory.
     if (lane == 0) {
-        rec_n[wl] = LdsCounts{st.heads, info.w};
-#pragma unroll
-        for (int b = 0; b < NB; ++b) rec_s[wl * NB + b] = LdsSums{st.lead[b], st.carry[b]};
+        auto park = [&](int i, int4_t v) { rec_n[i * kWavesPerWorkgroup + wl].info = int4{v.x, v.y, v.z, v.w}; };  // (lane 0's copy)
+        park(0, info0);
+        if (NM > 1) park(1, info1);
+        if (NM > 2) park(2, info2);
+        if (NM > 3) park(3, info3);
     }
     __syncthreads();
     if (lane != 0) return;
-
-    if (info.y != 0 && st.heads > 0) {        // last row ends with the run
+    if constexpr (NM == 1) {
+        // everything this worker contributes is still in registers
+        fixup_matrix<NB>(a.m[0], a.wave_info[0], int4{info0.x, info0.y, info0.z, info0.w}, fin.heads, fin.lead,
+                         fin.carry, rec_n, rec_s, wl, wg, wpw, wave);
+    } else {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) store_row(a, b, st.rank, st.carry[b]);
-    }
-    bool global_tail = false, global_lead = false;
-    if (info.w > 0) {                         // this worker holds the head of a row that continues
-        if (wl + info.w <= wpw) {
+        for (int i = 0; i < NM; ++i) {
+            const LdsCounts* cn = rec_n + i * kWavesPerWorkgroup;
+            const LdsSums* cs = rec_s + i * kWavesPerWorkgroup * NB;
+            float own_lead[NB], own_tail[NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float sum = st.carry[b];
-                for (int w = wl + 1; w < wl + info.w; ++w)
-                    sum += rec_n[w].heads == 0 ? rec_s[w * NB + b].tail : rec_s[w * NB + b].lead;
-                store_row(a, b, st.rank, sum);
-            }
-        } else {
-            global_tail = true;
+            for (int b = 0; b < NB; ++b) { own_lead[b] = cs[wl * NB + b].lead; own_tail[b] = cs[wl * NB + b].tail; }
+            fixup_matrix<NB>(parked[i].m, parked[i].wave_info, cn[wl].info, cn[wl].heads, own_lead, own_tail, cn, cs,
+                             wl, wg, wpw, wave);
         }
     }
-    if (info.z >= 0) {                        // its first groups continue a row of an earlier worker
-        const int fl = info.z - wg * wpw;     // that worker's index in this workgroup (if >= 0)
-        global_lead = fl < 0 || fl + rec_n[fl < 0 ? 0 : fl].chain_len > wpw;
-    }
-    if (global_tail || global_lead) {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            CarryRecord* r = &a.carry[wave * kMaxRowsPerLaunch + b];
-            __hip_atomic_store(&r->lead, st.lead[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&r->tail, st.carry[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&r->heads, st.heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
-        if (global_lead) chain_arrive<NB>(a, info.z);
-        if (global_tail) chain_arrive<NB>(a, wave);
-    }
 }
 
-using KernelFn = void (*)(GemvArgs);
+// A launchable variant: the kernel for NM matrices takes the first NM entries of the host's
+// argument block.
+struct Variant {
+    const void* fn = nullptr;    // device function, for attribute setting
+    void (*launch)(const GemvArgs&, dim3, dim3, size_t, hipStream_t) = nullptr;
+    explicit operator bool() const { return fn != nullptr; }
+};
 
-constexpr size_t lds_bytes(int kgp, int nb)
+constexpr size_t lds_bytes(int kgp, int nb, int nm)
 {
-    return static_cast<size_t>(nb) * 48 * kgp + kWavesPerWorkgroup * (sizeof(LdsCounts) + nb * sizeof(LdsSums));
+    return static_cast<size_t>(nb) * 48 * kgp +
+           nm * (kWavesPerWorkgroup * (sizeof(LdsCounts) + nb * sizeof(LdsSums)) + sizeof(ParkedArgs));
 }
 
-template <int BITS, int KGP, int NB>
-KernelFn kernel_if_it_fits()
+template <int NM>
+GemvArgsT<NM> first_matrices(const GemvArgs& a)
 {
-    if constexpr (lds_bytes(KGP, NB) <= kMaxLdsBytes) return gqsa_gemv_kernel<BITS, KGP, NB>;
-    else return nullptr;
+    GemvArgsT<NM> r{};
+    r.x = a.x; r.n_mats = NM; r.kg = a.kg;
+    r.nib_lo = a.nib_lo; r.nib_hi = a.nib_hi; r.k1024x2 = a.k1024x2;
+    r.wpw = a.wpw; r.n_wg = a.n_wg;
+    for (int i = 0; i < NM; ++i) { r.run[i] = a.run[i]; r.wave_info[i] = a.wave_info[i]; r.m[i] = a.m[i]; }
+    return r;
 }
 
+template <int BITS, int KGP, int NB, int NM>
+void launch_variant(const GemvArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s)
+{
+    hipLaunchKernelGGL((gqsa_gemv_kernel<BITS, KGP, NB, NM>), grid, block, lds, s, first_matrices<NM>(a));
+}
+
+template <int BITS, int KGP, int NB, int NM>
+Variant variant_if_it_fits()
+{
+    Variant v;
+    if constexpr (lds_bytes(KGP, NB, NM) <= kMaxLdsBytes) {
+        v.fn = reinterpret_cast<const void*>(&gqsa_gemv_kernel<BITS, KGP, NB, NM>);
+        v.launch = &launch_variant<BITS, KGP, NB, NM>;
+    }
+    return v;
+}
+
+// Compiled variants: 1, 2, 4 or 8 activation rows for one matrix (as far as NB copies of x fit
+// the 160 KB of LDS), and 2, 3 or 4 matrices for one activation row.
 template <int BITS, int KGP>
-KernelFn pick_rows(int nb)
+Variant pick_variant(int nb, int nm)
 {
-    switch (nb) {
-        case 1: return kernel_if_it_fits<BITS, KGP, 1>();
-        case 2: return kernel_if_it_fits<BITS, KGP, 2>();
-        case 4: return kernel_if_it_fits<BITS, KGP, 4>();
-        case 8: return kernel_if_it_fits<BITS, KGP, 8>();
+    if (nm == 1) {
+        switch (nb) {
+            case 1: return variant_if_it_fits<BITS, KGP, 1, 1>();
+            case 2: return variant_if_it_fits<BITS, KGP, 2, 1>();
+            case 4: return variant_if_it_fits<BITS, KGP, 4, 1>();
+            case 8: return variant_if_it_fits<BITS, KGP, 8, 1>();
+        }
+    } else if (nb == 1) {
+        switch (nm) {
+            case 2: return variant_if_it_fits<BITS, KGP, 1, 2>();
+            case 3: return variant_if_it_fits<BITS, KGP, 1, 3>();
+            case 4: return variant_if_it_fits<BITS, KGP, 1, 4>();
+        }
     }
-    return nullptr;
+    return Variant{};
 }
 
 // The kernel is compiled for group-column counts rounded up to a power of two (the LDS
-// offsets between the x arrays are immediates) and for 1, 2, 4 or 8 activation rows per
-// launch, as far as NB copies of x fit the 160 KB of LDS.
+// offsets between the x arrays are immediates).
 template <int BITS>
-KernelFn pick_kernel(int kg, int nb, int* kgp)
+Variant pick_kernel(int kg, int nb, int nm, int* kgp)
 {
-    if (kg <= 256) { *kgp = 256; return pick_rows<BITS, 256>(nb); }
-    if (kg <= 512) { *kgp = 512; return pick_rows<BITS, 512>(nb); }
-    if (kg <= 1024) { *kgp = 1024; return pick_rows<BITS, 1024>(nb); }
-    if (kg <= 2048) { *kgp = 2048; return pick_rows<BITS, 2048>(nb); }
+    if (kg <= 256) { *kgp = 256; return pick_variant<BITS, 256>(nb, nm); }
+    if (kg <= 512) { *kgp = 512; return pick_variant<BITS, 512>(nb, nm); }
+    if (kg <= 1024) { *kgp = 1024; return pick_variant<BITS, 1024>(nb, nm); }
+    if (kg <= 2048) { *kgp = 2048; return pick_variant<BITS, 2048>(nb, nm); }
     *kgp = 0;
-    return nullptr;
+    return Variant{};
 }
 
-KernelFn pick(const gqsa_matrix* m, int nb, int* kgp)
+Variant pick(const gqsa_matrix* m, int nb, int nm, int* kgp)
 {
     const int kg = static_cast<int>(m->K / m->G);
-    return m->bits == 4 ? pick_kernel<4>(kg, nb, kgp) : pick_kernel<8>(kg, nb, kgp);
+    return m->bits == 4 ? pick_kernel<4>(kg, nb, nm, kgp) : pick_kernel<8>(kg, nb, nm, kgp);
 }
 
 #define GQSA_HIP(call)                                                                      \
@@ -548,15 +805,16 @@ KernelFn pick(const gqsa_matrix* m, int nb, int* kgp)
 gqsa_status_t device_upload(gqsa_matrix* m)
 {
     int kgp = 0;
-    if (!pick(m, 1, &kgp)) return GQSA_ERR_UNSUPPORTED;      // K/G above 2048: x does not fit the LDS layout
+    if (!pick(m, 1, 1, &kgp)) return GQSA_ERR_UNSUPPORTED;   // K/G above 2048: x does not fit the LDS layout
     int dev = 0;
     GQSA_HIP(hipGetDevice(&dev));
     for (int nb = 1; nb <= kMaxRowsPerLaunch; nb *= 2) {
-        KernelFn fn = pick(m, nb, &kgp);
-        if (fn && lds_bytes(kgp, nb) > 64 * 1024)
-            GQSA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         static_cast<int>(lds_bytes(kgp, nb))));
+        for (int nm = 1; nm <= kMaxMatrices; ++nm) {
+            Variant v = pick(m, nb, nm, &kgp);
+            if (v && lds_bytes(kgp, nb, nm) > 64 * 1024)
+                GQSA_HIP(hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             static_cast<int>(lds_bytes(kgp, nb, nm))));
+        }
     }
     void* img = nullptr;
     void* carry = nullptr;
@@ -588,45 +846,76 @@ void device_release(gqsa_matrix* m)
     m->d_carry = nullptr;
 }
 
-gqsa_status_t device_gemv(gqsa_matrix* m, const void* x, void* y, int batch, void* stream)
+gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,
+                          void* stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint8_t* img = static_cast<const uint8_t*>(m->d_image);
-    GemvArgs a;
-    a.blocks = img + m->map.blocks;
-    a.wave_info = reinterpret_cast<const int4*>(img + m->map.wave_info);
-    a.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
-    a.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
-    a.carry = static_cast<CarryRecord*>(m->d_carry);
-    a.counters = reinterpret_cast<int*>(a.carry + static_cast<size_t>(m->n_waves) * kMaxRowsPerLaunch);
-    a.N = m->N;
-    a.K = m->K;
-    a.per_wg = static_cast<int>(m->n_blocks / m->n_workgroups);
-    a.extra_wg = static_cast<int>(m->n_blocks % m->n_workgroups);
-    a.n_empty = static_cast<int>(m->n_empty);
-    a.n_ranks = static_cast<int>(m->N - m->n_empty);
-    a.kg = static_cast<int>(m->K / m->G);
+    const gqsa_matrix* m0 = ms[0];
+    GemvArgs a{};
+    for (int i = 0; i < n_mats; ++i) {
+        const gqsa_matrix* m = ms[i];
+        const uint8_t* img = static_cast<const uint8_t*>(m->d_image);
+        MatRun& r = a.run[i];
+        r.blocks = img + m->map.blocks;
+        a.wave_info[i] = reinterpret_cast<const int4*>(img + m->map.wave_info);
+        r.per_wg = static_cast<int>(m->n_blocks / m->n_workgroups);
+        r.extra_wg = static_cast<int>(m->n_blocks % m->n_workgroups);
+        for (int big = 0; big < 2; ++big) {
+            r.per_wave[big] = (r.per_wg + big) / m->waves_per_workgroup;
+            r.extra_wave[big] = (r.per_wg + big) % m->waves_per_workgroup;
+        }
+        MatArgs& o = a.m[i];
+        o.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
+        o.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
+        o.carry = static_cast<CarryRecord*>(m->d_carry);
+        o.counters = reinterpret_cast<int*>(o.carry + static_cast<size_t>(m->n_waves) * kMaxRowsPerLaunch);
+        o.N = m->N;
+        o.n_empty = static_cast<int>(m->n_empty);
+        o.n_ranks = static_cast<int>(m->N - m->n_empty);
+    }
+    a.n_mats = n_mats;
+    a.wpw = m0->waves_per_workgroup;
+    a.n_wg = m0->n_workgroups;
+    a.kg = static_cast<int>(m0->K / m0->G);
     a.nib_lo = 0x000F000Fu;
     a.nib_hi = 0x00F000F0u;
     a.k1024x2 = 0x64006400u;
 
-    const int threads = m->waves_per_workgroup * kLanes;
-    const int grid = m->n_workgroups;
-    // the batch goes out in launches of 8, 4, 2 or 1 rows: the most that fits LDS and is left
-    int done = 0;
-    while (done < batch) {
-        int nb = kMaxRowsPerLaunch, kgp = 0;
-        KernelFn fn = nullptr;
-        for (; nb >= 1; nb /= 2) {
-            if (nb > batch - done) continue;
-            fn = pick(m, nb, &kgp);
-            if (fn) break;
+    const int threads = m0->waves_per_workgroup * kLanes;
+    const int grid = m0->n_workgroups;
+    if (n_mats > 1 && batch == 1) {
+        // several matrices, one activation row: one launch walks them all
+        int kgp = 0;
+        Variant v = pick(m0, 1, n_mats, &kgp);
+        if (!v) return GQSA_ERR_UNSUPPORTED;
+        a.x = static_cast<const uint16_t*>(x);
+        for (int i = 0; i < n_mats; ++i) a.m[i].y = static_cast<uint16_t*>(ys[i]);
+        v.launch(a, dim3(grid), dim3(threads), lds_bytes(kgp, 1, n_mats), s);
+    } else {
+        // one matrix at a time; its batch goes out in launches of 8, 4, 2 or 1 rows: the most
+        // that fits LDS and is left
+        for (int i = 0; i < n_mats; ++i) {
+            GemvArgs one = a;
+            one.n_mats = 1;
+            one.run[0] = a.run[i];
+            one.wave_info[0] = a.wave_info[i];
+            one.m[0] = a.m[i];
+            int done = 0;
+            while (done < batch) {
+                int nb = kMaxRowsPerLaunch, kgp = 0;
+                Variant v;
+                for (; nb >= 1; nb /= 2) {
+                    if (nb > batch - done) continue;
+                    v = pick(m0, nb, 1, &kgp);
+                    if (v) break;
+                }
+                if (!v) return GQSA_ERR_UNSUPPORTED;
+                one.x = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m0->K;
+                one.m[0].y = static_cast<uint16_t*>(ys[i]) + static_cast<size_t>(done) * ms[i]->N;
+                v.launch(one, dim3(grid), dim3(threads), lds_bytes(kgp, nb, 1), s);
+                done += nb;
+            }
         }
-        if (!fn) return GQSA_ERR_UNSUPPORTED;
-        a.x = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m->K;
-        a.y = static_cast<uint16_t*>(y) + static_cast<size_t>(done) * m->N;
-        hipLaunchKernelGGL(fn, dim3(grid), dim3(threads), lds_bytes(kgp, nb), s, a);
-        done += nb;
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;

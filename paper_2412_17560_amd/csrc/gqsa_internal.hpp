@@ -15,6 +15,7 @@ constexpr int kWavesPerWorkgroup = 16; // 1024 threads: one workgroup per comput
 constexpr int kMaxDefaultWorkgroups = 256;  // MI355X: 256 compute units
 constexpr int kMaxWorkgroups = 4096;
 constexpr int kMaxBatch = 16;
+constexpr int kMaxMatricesPerLaunch = 4;
 constexpr int64_t kMaxGroupColumns = 4096;  // 12-bit group-column << 4 | head flag in 16 bits
 constexpr size_t kAlign = 256;
 
@@ -76,6 +77,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
 // device side (gqsa_gemv.hip)
 gqsa_status_t device_upload(gqsa_matrix* m);
 void device_release(gqsa_matrix* m);
-gqsa_status_t device_gemv(gqsa_matrix* m, const void* x, void* y, int batch, void* stream);
+gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,
+                          void* stream);
 
 }  // namespace gqsa

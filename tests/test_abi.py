@@ -108,6 +108,24 @@ def test_gemv_host_side_checks_need_no_gpu():
     assert lib.gqsa_gemv(h.ptr, C.c_void_p(0x1008), fake, 1, None) == 8
 
 
+def test_gemv_multi_host_side_checks_need_no_gpu():
+    W = gi.dense_weight(8, 64, seed=1)
+    W2 = gi.dense_weight(8, 128, seed=1)
+    h, hk = gq.gqsa_pack(W, 16, 4, 0.5), gq.gqsa_pack(W2, 16, 4, 0.5)
+    lib = binding._lib()
+    fake = C.c_void_p(0x1000)
+    hs = (C.c_void_p * 2)(h.ptr.value, hk.ptr.value)
+    ys = (C.c_void_p * 2)(0x2000, 0x3000)
+    assert lib.gqsa_gemv_multi(None, 1, fake, ys, 1, None) == 1
+    assert lib.gqsa_gemv_multi(hs, 0, fake, ys, 1, None) == 3
+    assert lib.gqsa_gemv_multi(hs, 5, fake, ys, 1, None) == 3
+    assert lib.gqsa_gemv_multi(hs, 2, fake, ys, 17, None) == 3
+    assert lib.gqsa_gemv_multi(hs, 2, C.c_void_p(0x1004), ys, 1, None) == 8
+    assert lib.gqsa_gemv_multi(hs, 2, fake, ys, 1, None) == 2          # K differs
+    same = (C.c_void_p * 2)(h.ptr.value, h.ptr.value)
+    assert lib.gqsa_gemv_multi(same, 2, fake, ys, 1, None) == 2        # the same handle twice
+
+
 def test_info_fields():
     W = gi.dense_weight(100, 512, seed=5)
     keep = gi.imbalanced_keep_counts(100, 32, seed=5)

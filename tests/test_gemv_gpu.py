@@ -221,6 +221,71 @@ def test_gemv_error_paths_on_device(torch_cuda):
     assert gq.gqsa_info(h)["on_device"] == 1
 
 
+# ----------------------------------------------------------------------------- several matrices, one launch
+
+@pytest.mark.parametrize("part", [None, (3, 4), (1, 16), (40, 2)])
+@pytest.mark.parametrize("batch", [1, 3])
+def test_gemv_multi_equals_separate_calls(torch_cuda, part, batch):
+    """q/k/v-style: matrices of different N sharing x; the fused launch must give the bits of the
+    separate calls (and both must match the oracle)."""
+    torch = torch_cuda
+    K = 2048
+    shapes = [(300, 0.5, None), (64, 0.0, None), (257, None, "imbalanced"), (128, 1.0, None)]
+    hs, cs = [], []
+    for i, (N, sp, kind) in enumerate(shapes):
+        W = gi.dense_weight(N, K, seed=200 + i)
+        if kind:
+            keep = gi.imbalanced_keep_counts(N, K // 16, seed=200 + i)
+            h = gq.gqsa_pack_rows(W, keep, 16, 4)
+            c = oracle.pack(W, 16, 4, keep_per_row=keep)
+        else:
+            h = gq.gqsa_pack(W, 16, 4, sp)
+            c = oracle.pack(W, 16, 4, sparsity=sp)
+        if part:
+            gq.gqsa_set_partition(h, *part)
+        else:
+            gq.gqsa_set_partition(h, 16, 16)       # equal partition for all four (defaults differ with size)
+        hs.append(h)
+        cs.append(c)
+    x_np = gi.activations(batch, K, seed=77)
+    x = torch.from_numpy(x_np).cuda()
+    ys = [torch.full((batch, c.N), float("nan"), dtype=torch.float16, device="cuda") for c in cs]
+    gq.gqsa_gemv_multi(hs, x, ys)
+    torch.cuda.synchronize()
+    for h, c, y in zip(hs, cs, ys):
+        single = run_gemv(torch, h, x_np)
+        got = y.cpu().numpy()
+        assert np.array_equal(got.view(np.uint16), single.view(np.uint16))
+        ref = oracle.gemv(c, x_np)
+        for b in range(batch):
+            assert oracle.rel_error(got[b], ref[b]) <= TOL
+    # two matrices only, and the fused call again (workspaces are reusable)
+    ys2 = gq.gqsa_gemv_multi(hs[:2], x)
+    torch.cuda.synchronize()
+    for y2, y in zip(ys2, ys[:2]):
+        assert torch.equal(y2, y)
+
+
+def test_gemv_multi_error_paths(torch_cuda):
+    torch = torch_cuda
+    W = gi.dense_weight(32, 256, seed=1)
+    W2 = gi.dense_weight(32, 512, seed=2)
+    h1, h1b, h2 = gq.gqsa_pack(W, 16, 4, 0.5), gq.gqsa_pack(W, 16, 8, 0.5), gq.gqsa_pack(W2, 16, 4, 0.5)
+    x = torch.zeros((1, 256), dtype=torch.float16, device="cuda")
+    y = [torch.zeros((1, 32), dtype=torch.float16, device="cuda") for _ in range(5)]
+    for hs, status in (([h1, h1], 2), ([h1, h1b], 2), ([h1] * 5, 3)):
+        with pytest.raises(gq.GqsaError) as e:
+            gq.gqsa_gemv_multi(hs, x, y[:len(hs)])
+        assert e.value.status == status
+    with pytest.raises(ValueError):
+        gq.gqsa_gemv_multi([h1, h2], x, y[:2])      # K differs: refused by the binding
+    h3 = gq.gqsa_pack(gi.dense_weight(32, 256, seed=3), 16, 4, 0.5)
+    gq.gqsa_set_partition(h3, 2, 8)
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_gemv_multi([h1, h3], x, y[:2])      # partitions differ
+    assert e.value.status == 2
+
+
 # ----------------------------------------------------------------------------- full sizes
 
 @pytest.mark.parametrize("idx", [0, 4, 6])
@@ -256,6 +321,24 @@ def test_imbalanced_stress_full_size(torch_cuda):
     c = oracle.pack(W, 16, 4, keep_per_row=keep)
     assert gq.gqsa_info(h)["needs_fixup"] == 1
     check(torch_cuda, h, c, gi.activations(1, K, seed=seed))
+
+
+def test_llama7b_qkv_and_gate_up_fused_full_size(torch_cuda):
+    """The fused launches the benchmark times: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096)."""
+    torch = torch_cuda
+    x_np = gi.activations(1, 4096, seed=gi.config_seed(2, 0))
+    x = torch.from_numpy(x_np).cuda()
+    for idxs in ((0, 1, 2), (4, 5)):
+        hs, cs = [], []
+        for idx in idxs:
+            name, N, K = gi.LLAMA7B_LAYER[idx]
+            W = gi.dense_weight(N, K, seed=gi.config_seed(2, idx))
+            hs.append(gq.gqsa_pack(W, 16, 4, 0.5))
+            cs.append(oracle.pack(W, 16, 4, sparsity=0.5))
+        ys = gq.gqsa_gemv_multi(hs, x)
+        torch.cuda.synchronize()
+        for y, c in zip(ys, cs):
+            assert oracle.rel_error(y.cpu().numpy()[0], oracle.gemv(c, x_np, threads=8)[0]) <= TOL
 
 
 def test_w8_full_size(torch_cuda):
