@@ -36,6 +36,8 @@ def parse_args():
     p.add_argument("--skip-cpu", action="store_true", help="skip the cpu_baseline leg (for profiling runs)")
     p.add_argument("--skip-extras", action="store_true", help="skip per-shape / dense / stream-read legs")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
+    p.add_argument("--sweep", action="store_true",
+                   help="also time the Llama-3-8B-like shapes at S = 0, 30, 50, 70 %% (about a minute more)")
     p.add_argument("--pmc-calibrate", action="store_true",
                    help="also run 8 plain copies of 256 MiB (known HBM traffic) to calibrate profiler counters")
     return p.parse_args()
@@ -234,6 +236,57 @@ def main():
                               "us_cache_warm": round(us_warm, 3),
                               "distinct_matrices": len(hs), "mode": "back-to-back calls, " + mode})
         out["per_shape"] = per_shape
+
+        # the launches that cover several calls sharing x, by themselves
+        fused = []
+        for label, idxs in (("q/k/v 3 x 4096x4096", (0, 1, 2)), ("gate/up 2 x 11008x4096", (4, 5))):
+            sets = [[layers[l][j][0] for j in idxs] for l in range(args.pool_layers)]
+            us = time_calls(lambda k, sets=sets, idxs=idxs: gq.gqsa_gemv_multi(
+                sets[k % len(sets)], xs[4096], [ys[j] for j in idxs]))
+            b = sum(bytes_per_call[j] for j in idxs)
+            fused.append({"launch": label, "us_cold": round(us, 3), "GBps_cold": round(b / us / 1e3, 1),
+                          "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2)})
+        out["fused_launches"] = fused
+
+        def copies_of(W, bits, sparsity, min_bytes=1 << 30):
+            """Distinct device copies of one packed matrix, enough of them to defeat the caches."""
+            h0 = gq.gqsa_pack(W, 16, bits, sparsity)
+            e = gq.gqsa_export(h0)
+            n = max(2, min_bytes // gq.gqsa_info(h0)["device_bytes"] + 1)
+            hs = [h0]
+            for _ in range(n - 1):
+                hs.append(gq.gqsa_import(e["rowIndex"], e["groups"], e["values"], e["scales"], e["zeros"],
+                                         W.shape[0], W.shape[1], 16, bits))
+            for h in hs:
+                gq.gqsa_upload(h)
+            return hs
+
+        def time_variants(shapes, variants, seed_config):
+            rows = []
+            for idx, (name, N, K) in shapes:
+                W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(seed_config, idx), workers=workers)
+                xk = xs[K] if K in xs else torch.from_numpy(gi.activations(1, K, seed=0)).to(dev)
+                yk = torch.empty((1, N), dtype=torch.float16, device=dev)
+                for bits, sparsity in variants:
+                    hs = copies_of(W, bits, sparsity)
+                    us = time_calls(lambda k, hs=hs, xk=xk, yk=yk: gq.gqsa_gemv(hs[k % len(hs)], xk, yk), n=100)
+                    b = gq.gqsa_info(hs[0])["algorithmic_bytes"]
+                    rows.append({"shape": f"{N}x{K}", "bits": bits, "sparsity": sparsity, "us_cold": round(us, 3),
+                                 "GBps_cold": round(b / us / 1e3, 1),
+                                 "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2)})
+                    for h in hs:
+                        gq.gqsa_free(h)
+                del W
+            return rows
+
+        # dense 4-bit baseline (Eq. 1-3 with nothing pruned: the same kernel at S = 0) and the
+        # 8-bit variant at S = 50 %, on the layer's shapes
+        shapes7 = [(i, gi.LLAMA7B_LAYER[i]) for i in (0, 4, 6)]
+        out["dense_w4_gemv"] = time_variants(shapes7, [(4, 0.0)], 2)
+        out["w8s50_gemv"] = time_variants(shapes7[:1], [(8, 0.5)], 2)
+        if args.sweep:   # Llama-3-8B-like shapes over the sparsity sweep
+            out["llama3_8b_sweep"] = time_variants(list(enumerate(gi.LLAMA3_8B_SHAPES)),
+                                                   [(4, sp) for sp in gi.SPARSITY_SWEEP], 3)
 
         # small batches on the 4096x4096 shape (weights decoded once for up to 8 rows per launch)
         hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]

@@ -151,9 +151,9 @@ __device__ __forceinline__ void decode_w4(const Args& a, uint32_t w, half2_t* q)
     const half2_t k64 = {(_Float16)64.0f, (_Float16)64.0f};
     const uint32_t w2 = w >> 8;
     q[0] = as_half2(and_or(w, a.nib_lo, a.k1024x2)) - k1024;
-    q[1] = as_half2(and_or(w, a.nib_hi, a.k1024x2)) * k16th - k64;
+    q[1] = __builtin_elementwise_fma(as_half2(and_or(w, a.nib_hi, a.k1024x2)), k16th, -k64);
     q[2] = as_half2(and_or(w2, a.nib_lo, a.k1024x2)) - k1024;
-    q[3] = as_half2(and_or(w2, a.nib_hi, a.k1024x2)) * k16th - k64;
+    q[3] = __builtin_elementwise_fma(as_half2(and_or(w2, a.nib_hi, a.k1024x2)), k16th, -k64);
 }
 
 // 8-bit: a byte permute drops each code (bytes of w, element order) into the mantissa of
@@ -276,10 +276,10 @@ __device__ __forceinline__ void load_tile(Tile<BITS>& t, const uint8_t* p, int U
     }
 }
 
-// x in LDS, per activation row: three arrays of 16-byte slots indexed by group-column --
-// elements 0..7, elements 8..15 and (first 4 bytes) the fp32 sum of the 16 -- KGP slots
-// apart, so that one address register plus immediate offsets serves all reads of a gather, and
-// a gather of 16 B per lane spreads over all banks.  Row b starts at b * 48 * KGP.
+// x in LDS, per activation row: elements 0..7 of every group-column in 16-byte slots, elements
+// 8..15 in a second array of 16-byte slots 16*KGP bytes further on, and the fp32 sum of the 16
+// as a dense array of floats at 32*KGP (4 bytes per column: a wavefront's 64 reads of it spread
+// over all banks instead of a quarter of them).  Row b starts at b * 48 * KGP.
 template <int BITS, int KGP, int U, int NB, typename Args>
 __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, const Tile<BITS>& t,
                                              int lane, const uint8_t* xlds, WaveState<NB>& st)
@@ -337,7 +337,7 @@ __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, co
             const uint8_t* xb = xg + b * (48 * KGP);
             const uint4 xl = *reinterpret_cast<const uint4*>(xb);
             const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
-            const float xs = *reinterpret_cast<const float*>(xb + 32 * KGP);
+            const float xs = *reinterpret_cast<const float*>(xlds + b * (48 * KGP) + 32 * KGP + ((t.ix[u] & 0xFFF0u) >> 2));
             dotz[b] = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
         }
         const bool head_here = (t.ix[u] & 1u) != 0;
@@ -553,7 +553,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
             s += half_to_float(w[i] & 0xFFFFu);
             s += half_to_float(w[i] >> 16);
         }
-        *reinterpret_cast<float*>(slot + 32 * KGP) = s;
+        *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * a.kg) * 4) = s;
     };
     const int n_slots = NB * a.kg;                  // x is [NB][K] contiguous: slot c holds x[16c .. 16c+15]
 

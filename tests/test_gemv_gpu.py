@@ -301,20 +301,21 @@ def test_llama7b_layer_shapes_full_size(torch_cuda, idx):
     check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(2, idx)))
 
 
-@pytest.mark.parametrize("sparsity", [0.0, 0.3, 0.7])
+@pytest.mark.parametrize("sparsity", [0.0, 0.3, 0.5, 0.7])
 def test_llama3_8b_sparsity_sweep_full_size(torch_cuda, sparsity):
     for idx, (name, N, K) in enumerate(gi.LLAMA3_8B_SHAPES):
-        if name == "gate_up_proj" and sparsity != 0.0:
-            continue                       # keep the run short: the largest shape once, at S=0
+        if name == "gate_up_proj" and sparsity not in (0.0, 0.5):
+            continue                       # keep the run short: the largest shape at S=0 and S=50%
         W = gi.dense_weight(N, K, seed=gi.config_seed(3, idx))
         h = gq.gqsa_pack(W, 16, 4, sparsity)
         c = oracle.pack(W, 16, 4, sparsity=sparsity)
         check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(3, idx)))
 
 
-def test_imbalanced_stress_full_size(torch_cuda):
-    name, N, K = gi.IMBALANCED_SHAPES[0]
-    seed = gi.config_seed(4, 0)
+@pytest.mark.parametrize("idx", [0, 1])
+def test_imbalanced_stress_full_size(torch_cuda, idx):
+    name, N, K = gi.IMBALANCED_SHAPES[idx]
+    seed = gi.config_seed(4, idx)
     W = gi.dense_weight(N, K, seed=seed)
     keep = gi.imbalanced_keep_counts(N, K // 16, seed=seed)
     h = gq.gqsa_pack_rows(W, keep, 16, 4)
@@ -346,6 +347,28 @@ def test_w8_full_size(torch_cuda):
     h = gq.gqsa_pack(W, 16, 8, 0.5)
     c = oracle.pack(W, 16, 8, sparsity=0.5)
     check(torch_cuda, h, c, gi.activations(2, 4096, seed=gi.config_seed(5, 0)))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_small_batch_full_size(torch_cuda, bits):
+    """14336x4096 S50 with 1, 2, 4, 8 and 16 activation rows (16 = two launches of 8): every
+    output of every row against the oracle, and row 0 identical whatever the batch size."""
+    torch = torch_cuda
+    N, K = 14336, 4096
+    seed = gi.config_seed(5, 1)
+    W = gi.dense_weight(N, K, seed=seed)
+    h = gq.gqsa_pack(W, 16, bits, 0.5)
+    c = oracle.pack(W, 16, bits, sparsity=0.5)
+    x_np = gi.activations(16, K, seed=seed)
+    ref = oracle.gemv(c, x_np, threads=8)
+    first = None
+    for batch in (1, 2, 4, 8, 16):
+        y = run_gemv(torch, h, x_np[:batch])
+        for b in range(batch):
+            assert oracle.rel_error(y[b], ref[b]) <= TOL, (batch, b)
+        if first is None:
+            first = y[0].copy()
+        assert np.array_equal(y[0].view(np.uint16), first.view(np.uint16)), batch
 
 
 # ----------------------------------------------------------------------------- side-by-side kernels
