@@ -28,12 +28,13 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     elements 8h..8h+7 of the group, element 8h+2m in bits 4m..4m+3 and element
     8h+2m+1 in bits 16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j of the
     lane's 16 bytes is element j.
- 5. Side tables (int32): wave_info[n_waves][4] = {rank_base, tail_closed,
-    lead_first, chain_len} with
+ 5. Side tables (int32): wave_info[n_waves][4] = {rank_base, tail_closed +
+    2 * lead_len, lead_first, chain_len} with
       rank_base   = (number of row-head groups at stream positions before
                     worker w's first position) - 1;
       tail_closed = 1 if the first position after the worker's run is at or
                     beyond nnzg or holds a row-head group, else 0;
+      lead_len    = chain_len of worker lead_first (below), 0 if lead_first = -1;
       lead_first  = for a worker (with or without blocks) whose first position
                     b_w*64 holds a stored group that is not a row head: the
                     worker that owns the head group of that group's row; else -1;
@@ -187,6 +188,9 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
                 nxt = int(np.searchsorted(head_pos, e, side="left"))
                 row_last = (int(head_pos[nxt]) if nxt < len(head_pos) else nnzg) - 1
                 wave_info[w, 3] = owner[row_last // LANES] - w + 1
+        for w in range(n_waves):
+            if wave_info[w, 2] >= 0:
+                wave_info[w, 1] += 2 * wave_info[wave_info[w, 2], 3]
 
     parts = [blocks.tobytes(), wave_info.astype("<i4").tobytes(),
              nonempty.astype("<i4").tobytes(), empty.astype("<i4").tobytes()]

@@ -44,11 +44,12 @@ struct MatRun {                  // where a worker's run of blocks is (32 bytes)
     int extra_wave[2];           // ... of which the first extra_wave wavefronts hold one more
 };
 
-struct MatArgs {                 // where results go (56 bytes)
+struct MatArgs {                 // where results go (64 bytes)
     const int32_t* row_of_rank;  // row index of the r-th non-empty row (nullptr: identity)
     const int32_t* empty_rows;
     CarryRecord* carry;          // [worker][kMaxRowsPerLaunch]
     int* counters;               // arrivals per carry chain, indexed by the chain's first worker
+    unsigned long long* slots;   // [worker][kMaxRowsPerLaunch] meeting points of two-worker chains
     uint16_t* y;                 // fp16 [NB][N]
     long long N;
     int n_empty;
@@ -67,7 +68,7 @@ struct GemvArgsT {
     int wpw;                     // wavefronts per workgroup
     MatRun run[NM];              // run[0] completes the first line
     // ---- later lines
-    const int4* wave_info[NM];   // {rank_base, tail_closed, lead_first, chain_len} per worker
+    const int4* wave_info[NM];   // {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len} per worker
     int n_wg;                    // workgroups
     int pad;
     MatArgs m[NM];
@@ -107,6 +108,7 @@ __device__ __forceinline__ MatArgs matrix_args(int i)
     r.empty_rows = src->empty_rows;
     r.carry = src->carry;
     r.counters = src->counters;
+    r.slots = src->slots;
     r.y = src->y;
     r.N = src->N;
     r.n_empty = src->n_empty;
@@ -436,22 +438,36 @@ struct LdsSums {
     float tail;
 };
 struct LdsCounts {
-    int4 info;     // the worker's {rank_base, tail_closed, lead_first, chain_len} in this matrix
+    int4 info;     // the worker's record {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}
     int heads;     // row heads inside its run
     int pad[3];
 };
 
+// A row shared by exactly two workers of different workgroups: each swaps its piece (tagged)
+// into the row's meeting point with one device-scope exchange.  The one that finds the slot
+// empty is done -- its piece travels inside the slot; the one that finds the other's piece adds
+// the two, writes the row and empties the slot for the next launch.  One round trip, no fence:
+// nothing is read through the caches.  (Two fp32 terms: their sum does not depend on the order.)
+__device__ __forceinline__ unsigned long long tagged(float v)
+{
+    return (static_cast<unsigned long long>(__builtin_bit_cast(uint32_t, v)) << 32) | 1ull;
+}
+
 // Carry fix-up of one matrix by lane 0 of a wavefront, after the workgroup's records are in LDS:
 // rows shared inside the workgroup are summed in worker order by the wavefront holding their
-// head; rows spread over several workgroups go through device memory (chain_arrive).
+// head; rows spread over several workgroups go through device memory -- two-worker chains
+// through the exchange above, longer ones through records and an arrival counter (chain_arrive).
+// info = the worker's {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}; lead_len is
+// the chain length of the row this run continues.
 template <int NB>
-__device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave_info, int4 info, int heads,
-                                             const float* own_lead, const float* own_tail,
+__device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave_info, int4 info,
+                                             int heads, const float* own_lead, const float* own_tail,
                                              const LdsCounts* cn, const LdsSums* cs, int wl, int wg, int wpw,
                                              int wave)
 {
     const int rank_open = info.x + heads;
-    if (info.y != 0 && heads > 0) {           // last row ends with the run
+    const int head_w = info.y >> 1;
+    if ((info.y & 1) != 0 && heads > 0) {     // last row ends with the run
 #pragma unroll
         for (int b = 0; b < NB; ++b) store_row(mo, b, rank_open, own_tail[b]);
     }
@@ -471,9 +487,42 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
     }
     if (info.z >= 0) {                        // its first groups continue a row of an earlier worker
         const int fl = info.z - wg * wpw;     // that worker's index in this workgroup (if >= 0)
-        global_lead = fl < 0 || fl + cn[fl < 0 ? 0 : fl].info.w > wpw;
+        global_lead = fl < 0 || fl + head_w > wpw;
     }
-    if (global_tail || global_lead) {
+    const bool tail_pair = global_tail && info.w == 2;
+    const bool lead_pair = global_lead && head_w == 2;
+    if (tail_pair || lead_pair) {
+        unsigned long long got_tail[NB], got_lead[NB];
+        float piece[NB];                      // what this run adds to the row it continues
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            piece[b] = heads == 0 ? own_tail[b] : own_lead[b];
+            got_tail[b] = got_lead[b] = 0;
+            if (tail_pair)
+                got_tail[b] = __hip_atomic_exchange(&mo.slots[wave * kMaxRowsPerLaunch + b], tagged(own_tail[b]),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lead_pair)
+                got_lead[b] = __hip_atomic_exchange(&mo.slots[info.z * kMaxRowsPerLaunch + b], tagged(piece[b]),
+                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (got_tail[b] & 1ull) {         // the other worker's piece was waiting
+                store_row(mo, b, rank_open,
+                          own_tail[b] + __builtin_bit_cast(float, static_cast<uint32_t>(got_tail[b] >> 32)));
+                __hip_atomic_store(&mo.slots[wave * kMaxRowsPerLaunch + b], 0ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (got_lead[b] & 1ull) {
+                store_row(mo, b, info.x,
+                          __builtin_bit_cast(float, static_cast<uint32_t>(got_lead[b] >> 32)) + piece[b]);
+                __hip_atomic_store(&mo.slots[info.z * kMaxRowsPerLaunch + b], 0ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    const bool tail_chain = global_tail && !tail_pair, lead_chain = global_lead && !lead_pair;
+    if (tail_chain || lead_chain) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             CarryRecord* r = &mo.carry[wave * kMaxRowsPerLaunch + b];
@@ -482,8 +531,8 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
             __hip_atomic_store(&r->heads, heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
-        if (global_lead) chain_arrive<NB>(mo, wave_info, info.z);
-        if (global_tail) chain_arrive<NB>(mo, wave_info, wave);
+        if (lead_chain) chain_arrive<NB>(mo, wave_info, info.z);
+        if (tail_chain) chain_arrive<NB>(mo, wave_info, wave);
     }
 }
 
@@ -689,22 +738,22 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         if (NM > 3) park(3, info3);
     }
     __syncthreads();
-    if (lane != 0) return;
     if constexpr (NM == 1) {
+        if (lane != 0) return;
         // everything this worker contributes is still in registers
-        fixup_matrix<NB>(a.m[0], a.wave_info[0], int4{info0.x, info0.y, info0.z, info0.w}, fin.heads, fin.lead,
-                         fin.carry, rec_n, rec_s, wl, wg, wpw, wave);
+        fixup_matrix<NB>(a.m[0], a.wave_info[0], int4{info0.x, info0.y, info0.z, info0.w}, fin.heads,
+                         fin.lead, fin.carry, rec_n, rec_s, wl, wg, wpw, wave);
     } else {
+        // lane i settles matrix i (side by side: the fix-up is a chain of dependent LDS reads)
+        if (lane >= NM) return;
+        const int i = lane;
+        const LdsCounts* cn = rec_n + i * kWavesPerWorkgroup;
+        const LdsSums* cs = rec_s + i * kWavesPerWorkgroup * NB;
+        float own_lead[NB], own_tail[NB];
 #pragma unroll
-        for (int i = 0; i < NM; ++i) {
-            const LdsCounts* cn = rec_n + i * kWavesPerWorkgroup;
-            const LdsSums* cs = rec_s + i * kWavesPerWorkgroup * NB;
-            float own_lead[NB], own_tail[NB];
-#pragma unroll
-            for (int b = 0; b < NB; ++b) { own_lead[b] = cs[wl * NB + b].lead; own_tail[b] = cs[wl * NB + b].tail; }
-            fixup_matrix<NB>(parked[i].m, parked[i].wave_info, cn[wl].info, cn[wl].heads, own_lead, own_tail, cn, cs,
-                             wl, wg, wpw, wave);
-        }
+        for (int b = 0; b < NB; ++b) { own_lead[b] = cs[wl * NB + b].lead; own_tail[b] = cs[wl * NB + b].tail; }
+        fixup_matrix<NB>(parked[i].m, parked[i].wave_info, cn[wl].info, cn[wl].heads, own_lead, own_tail, cn, cs,
+                         wl, wg, wpw, wave);
     }
 }
 
@@ -791,6 +840,19 @@ Variant pick(const gqsa_matrix* m, int nb, int nm, int* kgp)
     return m->bits == 4 ? pick_kernel<4>(kg, nb, nm, kgp) : pick_kernel<8>(kg, nb, nm, kgp);
 }
 
+constexpr size_t counters_offset(int n_waves)
+{
+    return static_cast<size_t>(n_waves) * kMaxRowsPerLaunch * sizeof(CarryRecord);
+}
+constexpr size_t slots_offset(int n_waves)
+{
+    return counters_offset(n_waves) + (static_cast<size_t>(n_waves) + 1) / 2 * 2 * sizeof(int);
+}
+constexpr size_t carry_workspace_bytes(int n_waves)
+{
+    return slots_offset(n_waves) + static_cast<size_t>(n_waves) * kMaxRowsPerLaunch * sizeof(unsigned long long);
+}
+
 #define GQSA_HIP(call)                                                                      \
     do {                                                                                    \
         hipError_t e_ = (call);                                                             \
@@ -819,9 +881,9 @@ gqsa_status_t device_upload(gqsa_matrix* m)
     void* img = nullptr;
     void* carry = nullptr;
     GQSA_HIP(hipMalloc(&img, m->image.size()));
-    // carry records (per worker and activation row) followed by one arrival counter per worker
-    const size_t carry_bytes = static_cast<size_t>(m->n_waves) *
-                               (kMaxRowsPerLaunch * sizeof(CarryRecord) + sizeof(int));
+    // carry records (per worker and activation row), one arrival counter per worker (padded to a
+    // multiple of two), then the meeting points of two-worker chains (per worker and row)
+    const size_t carry_bytes = carry_workspace_bytes(m->n_waves);
     hipError_t e = hipMalloc(&carry, carry_bytes);
     if (e == hipSuccess) e = hipMemcpy(img, m->image.data(), m->image.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(carry, 0, carry_bytes);
@@ -868,7 +930,9 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
         o.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
         o.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
         o.carry = static_cast<CarryRecord*>(m->d_carry);
-        o.counters = reinterpret_cast<int*>(o.carry + static_cast<size_t>(m->n_waves) * kMaxRowsPerLaunch);
+        uint8_t* ws = static_cast<uint8_t*>(m->d_carry);
+        o.counters = reinterpret_cast<int*>(ws + counters_offset(m->n_waves));
+        o.slots = reinterpret_cast<unsigned long long*>(ws + slots_offset(m->n_waves));
         o.N = m->N;
         o.n_empty = static_cast<int>(m->n_empty);
         o.n_ranks = static_cast<int>(m->N - m->n_empty);

@@ -22,7 +22,7 @@ constexpr size_t kAlign = 256;
 // Offsets (bytes) of the regions inside the device image.
 struct ImageMap {
     size_t blocks = 0;      // n_blocks * block_bytes
-    size_t wave_info = 0;   // n_waves * int32[4] {rank_base, tail_closed, lead_first, chain_len}
+    size_t wave_info = 0;   // n_waves * int32[4] {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}
     size_t row_of_rank = 0; // int32 per non-empty row
     size_t empty_rows = 0;  // int32 per empty row
     size_t total = 0;
@@ -59,7 +59,7 @@ struct gqsa_matrix {
     // device side
     int device = -1;
     void* d_image = nullptr;
-    void* d_carry = nullptr;  // n_waves CarryRecord, then n_waves int32 arrival counters
+    void* d_carry = nullptr;  // carry records, arrival counters and meeting points of the fix-up
 
     int64_t nnzg() const { return rowIndex.empty() ? 0 : rowIndex.back(); }
     int code_bytes() const { return G * bits / 8; }

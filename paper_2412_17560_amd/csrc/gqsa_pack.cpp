@@ -248,7 +248,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
 
-    // Per worker: {rank_base, tail_closed, lead_first, chain_len}.
+    // Per worker: {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}.
     //   rank_base   rank (among non-empty rows) of the row that is open when the run starts,
     //               i.e. (row heads before the run) - 1
     //   tail_closed 1 if the row open at the end of the run has no group beyond it
@@ -257,6 +257,8 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     //               without blocks in the middle of a row has it too (it passes 0 along)
     //   chain_len   for a worker that holds the head of a row continuing past its run: the
     //               number of consecutive workers holding groups of that row, else 0
+    //   lead_len    chain_len of worker lead_first (0 without one): tells the worker how the row
+    //               it continues is settled without a look at the other worker's record
     std::vector<int64_t> head_pos;          // stream positions of the row heads, ascending
     head_pos.reserve(nonempty.size());
     for (int32_t n : nonempty) head_pos.push_back(m->rowIndex[n]);
@@ -315,6 +317,8 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         info[4 * w + 2] = lead_first;
         info[4 * w + 3] = chain_len;
     }
+    for (int w = 0; w < n_waves; ++w)
+        if (info[4 * w + 2] >= 0) info[4 * w + 1] += 2 * info[4 * info[4 * w + 2] + 3];
     if (!nonempty.empty())
         std::memcpy(img.data() + map.row_of_rank, nonempty.data(), nonempty.size() * 4);
     if (!empty.empty())

@@ -189,10 +189,12 @@ def test_blob_decodes_back_to_canonical(bits, n_wg, wpw):
         b += n_w
         end = 64 * b
         closed = 1 if end >= nn or exp_heads[end] else 0
-        assert wave_info[w, 1] == closed
-        lead_first, chain_len = -1, 0
+        lead_first, chain_len, lead_len = -1, 0, 0
         if first < nn and not exp_heads[first]:
             lead_first = worker_of[c.rowIndex[row_of[first]]]
+            # workers from the one holding that row's head to the one holding its last group
+            lead_len = worker_of[c.rowIndex[row_of[first] + 1] - 1] - lead_first + 1
+        assert wave_info[w, 1] == closed + 2 * lead_len
         if n_w > 0 and not closed and exp_heads[first:end].any():
             last_row = row_of[end - 1]
             chain_len = worker_of[c.rowIndex[last_row + 1] - 1] - w + 1
