@@ -443,20 +443,33 @@ struct LdsCounts {
     int pad[3];
 };
 
-// A row shared by exactly two workers of different workgroups: each swaps its piece (tagged)
-// into the row's meeting point with one device-scope exchange.  The one that finds the slot
-// empty is done -- its piece travels inside the slot; the one that finds the other's piece adds
-// the two, writes the row and empties the slot for the next launch.  One round trip, no fence:
-// nothing is read through the caches.  (Two fp32 terms: their sum does not depend on the order.)
+// A row whose workers sit in two neighbouring workgroups: each side adds up its workers' pieces
+// through LDS, in worker order, and the two partial sums meet in device memory -- each side
+// swaps its (tagged) sum into the row's meeting point with one device-scope exchange.  The side
+// that finds the slot empty is done: its sum travels inside the slot.  The side that finds the
+// other's sum adds the two, writes the row and empties the slot for the next launch.  One
+// round trip and no fence: nothing is read through the caches.  (Two fp32 terms: their sum
+// does not depend on who adds them.)
 __device__ __forceinline__ unsigned long long tagged(float v)
 {
     return (static_cast<unsigned long long>(__builtin_bit_cast(uint32_t, v)) << 32) | 1ull;
 }
 
-// Carry fix-up of one matrix by lane 0 of a wavefront, after the workgroup's records are in LDS:
-// rows shared inside the workgroup are summed in worker order by the wavefront holding their
-// head; rows spread over several workgroups go through device memory -- two-worker chains
-// through the exchange above, longer ones through records and an arrival counter (chain_arrive).
+// Swap `sum` into the meeting point; true (and the other side's sum in *other) if that was
+// already there.
+__device__ __forceinline__ bool meet(unsigned long long* slot, float sum, float* other)
+{
+    const unsigned long long got = __hip_atomic_exchange(slot, tagged(sum), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((got & 1ull) == 0) return false;
+    *other = __builtin_bit_cast(float, static_cast<uint32_t>(got >> 32));
+    __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return true;
+}
+
+// Carry fix-up of one matrix by one lane of a wavefront, after the workgroup's records are in
+// LDS.  A row whose workers all sit in this workgroup is summed in worker order by the wavefront
+// holding its head; one spread over two workgroups goes through a meeting point (above); only a
+// row spread over three or more workgroups uses records and an arrival counter (chain_arrive).
 // info = the worker's {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}; lead_len is
 // the chain length of the row this run continues.
 template <int NB>
@@ -467,62 +480,48 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
 {
     const int rank_open = info.x + heads;
     const int head_w = info.y >> 1;
+    const int wg_first = wg * wpw, wg_end = wg_first + wpw;     // this workgroup's workers
+    auto piece = [&](int w, int b) {   // what local worker w adds to the row its run continues
+        return cn[w].heads == 0 ? cs[w * NB + b].tail : cs[w * NB + b].lead;
+    };
     if ((info.y & 1) != 0 && heads > 0) {     // last row ends with the run
 #pragma unroll
         for (int b = 0; b < NB; ++b) store_row(mo, b, rank_open, own_tail[b]);
     }
-    bool global_tail = false, global_lead = false;
+    bool chain_tail = false, chain_lead = false;
     if (info.w > 0) {                         // this worker holds the head of a row that continues
-        if (wl + info.w <= wpw) {
+        const int end = wave + info.w;        // one past the row's last worker
+        if (end <= wg_end + wpw) {
+            const int here = (end < wg_end ? end : wg_end) - wave;
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                float sum = own_tail[b];
-                for (int w = wl + 1; w < wl + info.w; ++w)
-                    sum += cn[w].heads == 0 ? cs[w * NB + b].tail : cs[w * NB + b].lead;
-                store_row(mo, b, rank_open, sum);
+                float sum = own_tail[b], other = 0.0f;
+                for (int w = wl + 1; w < wl + here; ++w) sum += piece(w, b);
+                if (end <= wg_end) store_row(mo, b, rank_open, sum);
+                else if (meet(&mo.slots[wave * kMaxRowsPerLaunch + b], sum, &other))
+                    store_row(mo, b, rank_open, sum + other);
             }
         } else {
-            global_tail = true;
+            chain_tail = true;
         }
     }
     if (info.z >= 0) {                        // its first groups continue a row of an earlier worker
-        const int fl = info.z - wg * wpw;     // that worker's index in this workgroup (if >= 0)
-        global_lead = fl < 0 || fl + head_w > wpw;
-    }
-    const bool tail_pair = global_tail && info.w == 2;
-    const bool lead_pair = global_lead && head_w == 2;
-    if (tail_pair || lead_pair) {
-        unsigned long long got_tail[NB], got_lead[NB];
-        float piece[NB];                      // what this run adds to the row it continues
+        const int end = info.z + head_w;      // one past that row's last worker
+        const bool head_here = info.z >= wg_first;
+        const bool two_at_most = head_here ? end <= wg_end + wpw : (info.z >= wg_first - wpw && end <= wg_end);
+        if (!two_at_most) {
+            chain_lead = true;
+        } else if (!head_here && wl == 0) {   // the far side's first worker speaks for all of them
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            piece[b] = heads == 0 ? own_tail[b] : own_lead[b];
-            got_tail[b] = got_lead[b] = 0;
-            if (tail_pair)
-                got_tail[b] = __hip_atomic_exchange(&mo.slots[wave * kMaxRowsPerLaunch + b], tagged(own_tail[b]),
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (lead_pair)
-                got_lead[b] = __hip_atomic_exchange(&mo.slots[info.z * kMaxRowsPerLaunch + b], tagged(piece[b]),
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            if (got_tail[b] & 1ull) {         // the other worker's piece was waiting
-                store_row(mo, b, rank_open,
-                          own_tail[b] + __builtin_bit_cast(float, static_cast<uint32_t>(got_tail[b] >> 32)));
-                __hip_atomic_store(&mo.slots[wave * kMaxRowsPerLaunch + b], 0ull, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            for (int b = 0; b < NB; ++b) {
+                float sum = heads == 0 ? own_tail[b] : own_lead[b], other = 0.0f;
+                for (int w = 1; w < end - wg_first; ++w) sum += piece(w, b);
+                if (meet(&mo.slots[info.z * kMaxRowsPerLaunch + b], sum, &other))
+                    store_row(mo, b, info.x, other + sum);
             }
-            if (got_lead[b] & 1ull) {
-                store_row(mo, b, info.x,
-                          __builtin_bit_cast(float, static_cast<uint32_t>(got_lead[b] >> 32)) + piece[b]);
-                __hip_atomic_store(&mo.slots[info.z * kMaxRowsPerLaunch + b], 0ull, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
+        }                                     // (else: the worker holding the head, or the far side's first, adds this piece)
     }
-    const bool tail_chain = global_tail && !tail_pair, lead_chain = global_lead && !lead_pair;
-    if (tail_chain || lead_chain) {
+    if (chain_tail || chain_lead) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             CarryRecord* r = &mo.carry[wave * kMaxRowsPerLaunch + b];
@@ -531,8 +530,8 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
             __hip_atomic_store(&r->heads, heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
-        if (lead_chain) chain_arrive<NB>(mo, wave_info, info.z);
-        if (tail_chain) chain_arrive<NB>(mo, wave_info, wave);
+        if (chain_lead) chain_arrive<NB>(mo, wave_info, info.z);
+        if (chain_tail) chain_arrive<NB>(mo, wave_info, wave);
     }
 }
 

@@ -81,6 +81,21 @@ def test_partition_sweep_imbalanced(torch_cuda, part):
     check(torch_cuda, h, c, gi.activations(1, K, seed=6))
 
 
+@pytest.mark.parametrize("part", [(8, 4), (5, 7), (16, 2), (3, 16)])
+@pytest.mark.parametrize("batch", [1, 2])
+def test_rows_spanning_two_and_more_workgroups(torch_cuda, part, batch):
+    """Long rows over few blocks per wavefront: a row's workers sit in one, two or three
+    workgroups, several of them on either side of a workgroup boundary (partial sums through LDS
+    on each side, then one meeting point; three or more workgroups through the arrival counter)."""
+    N, K = 9, 5120                       # 320 group-columns per row
+    W = gi.dense_weight(N, K, seed=77)
+    keep = np.array([320, 200, 0, 320, 37, 320, 1, 320, 255], dtype=np.int32)
+    c = oracle.pack(W, 16, 4, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition(h, *part)
+    check(torch_cuda, h, c, gi.activations(batch, K, seed=8))
+
+
 def adversarial_keeps(N, kg):
     one_row = np.zeros(N, dtype=np.int32); one_row[N // 2] = kg
     alternating = np.where(np.arange(N) % 2 == 0, 0, kg).astype(np.int32)
