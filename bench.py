@@ -204,8 +204,9 @@ def main():
 
     # ------------------------------------------------------------------ extras: per shape, baselines
     if not args.skip_extras:
-        def time_calls(fn_of_k, n=200, warm=20):
-            """us per call of n back-to-back calls replayed from a HIP graph (eager if --no-graph)."""
+        def time_calls(fn_of_k, n=200, warm=20, reps=3, spread=None):
+            """us per call of n back-to-back calls replayed from a HIP graph (eager if --no-graph):
+            the fastest of `reps` replays, or -- with a dict to fill in -- their median."""
             with torch.cuda.stream(stream):
                 for k in range(warm):
                     fn_of_k(k)
@@ -220,7 +221,12 @@ def main():
             with torch.cuda.stream(stream):
                 gr.replay()
             torch.cuda.synchronize()
-            return min(timed_region(lambda: gr.replay()) for _ in range(3)) * 1e3 / n
+            times = sorted(timed_region(lambda: gr.replay()) * 1e3 / n for _ in range(reps))
+            if spread is not None:       # median, 10th and 90th percentile over the replays
+                spread.update({"us_median": round(times[len(times) // 2], 3),
+                               "us_p10": round(times[len(times) // 10], 3),
+                               "us_p90": round(times[(9 * len(times)) // 10], 3)})
+            return times[0] if spread is None else times[len(times) // 2]
 
         per_shape = []
         for idx in (0, 4, 6):
@@ -228,14 +234,18 @@ def main():
             hs = [layers[l][idx][0] for l in range(args.pool_layers)]
             if idx == 0:   # q,k,v,o are four distinct matrices of the same shape per layer
                 hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]
-            us = time_calls(lambda k, hs=hs, K=K, idx=idx: gq.gqsa_gemv(hs[k % len(hs)], xs[K], ys[idx]))
+            spread = {}
+            us = time_calls(lambda k, hs=hs, K=K, idx=idx: gq.gqsa_gemv(hs[k % len(hs)], xs[K], ys[idx]),
+                            reps=10, spread=spread)
             us_warm = time_calls(lambda k, hs=hs, K=K, idx=idx: gq.gqsa_gemv(hs[0], xs[K], ys[idx]))
             b = bytes_per_call[idx]
-            per_shape.append({"shape": f"{N}x{K}", "us_cold": round(us, 3),
+            per_shape.append({"shape": f"{N}x{K}", "us_cold": round(us, 3), "us_cold_p10": spread.get("us_p10"),
+                              "us_cold_p90": spread.get("us_p90"),
                               "GBps_cold": round(b / us / 1e3, 1),
                               "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2),
                               "us_cache_warm": round(us_warm, 3),
-                              "distinct_matrices": len(hs), "mode": "back-to-back calls, " + mode})
+                              "distinct_matrices": len(hs),
+                              "mode": "200 back-to-back calls, median of 10 replays, " + mode})
         out["per_shape"] = per_shape
 
         # the launches that cover several calls sharing x, by themselves
@@ -351,6 +361,17 @@ def main():
                 oracle.gemv(c, xh[c.K], threads=threads)
             reps += 1
         dt = time.time() - t0
+        per_shape_cpu = []
+        for c in (canon[0], canon[4], canon[6]):         # one call per shape: 1 thread and all of them
+            def median_ms(threads, reps):
+                ts = []
+                for _ in range(reps):
+                    t1 = time.time()
+                    oracle.gemv(c, xh[c.K], threads=threads)
+                    ts.append((time.time() - t1) * 1e3)
+                return round(sorted(ts)[len(ts) // 2], 3)
+            per_shape_cpu.append({"shape": f"{c.N}x{c.K}", "ms_1_thread": median_ms(1, 3),
+                                  f"ms_{threads}_threads": median_ms(threads, 5)})
         out["cpu_baseline"] = {
             "value": round(bytes_per_step * reps / dt / 1e9, 3),
             "unit": "GB/s",
@@ -358,6 +379,7 @@ def main():
             "kind": "oracle",
             "sample": f"{reps} passes over one layer set (7 GEMVs, same shapes and sparsity) in {dt:.1f} s; "
                       f"{dt / reps * 1e3 / calls_per_step:.2f} ms per call",
+            "per_shape": per_shape_cpu,
         }
 
     print(json.dumps(out))
