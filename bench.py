@@ -37,7 +37,8 @@ def parse_args():
     p.add_argument("--skip-extras", action="store_true", help="skip per-shape / dense / stream-read legs")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
     p.add_argument("--sweep", action="store_true",
-                   help="also time the Llama-3-8B-like shapes at S = 0, 30, 50, 70 %% (about a minute more)")
+                   help="also time the Llama-3-8B-like shapes at S = 0, 30, 50, 70 %% and group sizes 16..128 "
+                        "(about two minutes more)")
     p.add_argument("--pmc-calibrate", action="store_true",
                    help="also run 8 plain copies of 256 MiB (known HBM traffic) to calibrate profiler counters")
     return p.parse_args()
@@ -259,15 +260,15 @@ def main():
                           "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2)})
         out["fused_launches"] = fused
 
-        def copies_of(W, bits, sparsity, min_bytes=1 << 30):
+        def copies_of(W, bits, sparsity, G=16, min_bytes=1 << 30):
             """Distinct device copies of one packed matrix, enough of them to defeat the caches."""
-            h0 = gq.gqsa_pack(W, 16, bits, sparsity)
+            h0 = gq.gqsa_pack(W, G, bits, sparsity)
             e = gq.gqsa_export(h0)
             n = max(2, min_bytes // gq.gqsa_info(h0)["device_bytes"] + 1)
             hs = [h0]
             for _ in range(n - 1):
                 hs.append(gq.gqsa_import(e["rowIndex"], e["groups"], e["values"], e["scales"], e["zeros"],
-                                         W.shape[0], W.shape[1], 16, bits))
+                                         W.shape[0], W.shape[1], G, bits))
             for h in hs:
                 gq.gqsa_upload(h)
             return hs
@@ -278,11 +279,13 @@ def main():
                 W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(seed_config, idx), workers=workers)
                 xk = xs[K] if K in xs else torch.from_numpy(gi.activations(1, K, seed=0)).to(dev)
                 yk = torch.empty((1, N), dtype=torch.float16, device=dev)
-                for bits, sparsity in variants:
-                    hs = copies_of(W, bits, sparsity)
+                for variant in variants:
+                    bits, sparsity = variant[:2]
+                    G = variant[2] if len(variant) > 2 else 16
+                    hs = copies_of(W, bits, sparsity, G)
                     us = time_calls(lambda k, hs=hs, xk=xk, yk=yk: gq.gqsa_gemv(hs[k % len(hs)], xk, yk), n=100)
                     b = gq.gqsa_info(hs[0])["algorithmic_bytes"]
-                    rows.append({"shape": f"{N}x{K}", "bits": bits, "sparsity": sparsity, "us_cold": round(us, 3),
+                    rows.append({"shape": f"{N}x{K}", "bits": bits, "sparsity": sparsity, "G": G, "us_cold": round(us, 3),
                                  "GBps_cold": round(b / us / 1e3, 1),
                                  "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2)})
                     for h in hs:
@@ -295,9 +298,11 @@ def main():
         shapes7 = [(i, gi.LLAMA7B_LAYER[i]) for i in (0, 4, 6)]
         out["dense_w4_gemv"] = time_variants(shapes7, [(4, 0.0)], 2)
         out["w8s50_gemv"] = time_variants(shapes7[:1], [(8, 0.5)], 2)
-        if args.sweep:   # Llama-3-8B-like shapes over the sparsity sweep
+        if args.sweep:   # Llama-3-8B-like shapes over the sparsity sweep; group sizes on 4096x4096
             out["llama3_8b_sweep"] = time_variants(list(enumerate(gi.LLAMA3_8B_SHAPES)),
                                                    [(4, sp) for sp in gi.SPARSITY_SWEEP], 3)
+            out["group_size_sweep"] = time_variants(shapes7[:1] + shapes7[1:2],
+                                                    [(4, sp, G) for G in (16, 32, 64, 128) for sp in (0.0, 0.5)], 2)
 
         # small batches on the 4096x4096 shape (weights decoded once for up to 8 rows per launch)
         hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]

@@ -37,8 +37,8 @@ typedef struct gqsa_matrix* gqsa_handle_t;
 typedef enum {
     GQSA_OK = 0,
     GQSA_ERR_NULL = 1,         /* a required pointer is NULL */
-    GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K/G > 4096, inconsistent arrays */
-    GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 16, batch outside 1..16 */
+    GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K > 65536, inconsistent arrays */
+    GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 16/32/64/128 (8-bit: up to 64), batch outside 1..16 */
     GQSA_ERR_RANGE = 4,        /* sparsity outside [0,1], keep count outside [0,K/G], non-finite W */
     GQSA_ERR_ALLOC = 5,        /* host allocation failed */
     GQSA_ERR_HIP = 6,          /* a HIP runtime call failed (no device, launch error, ...) */
@@ -75,6 +75,8 @@ typedef struct {
  *   out      [host] receives the handle
  * Scale is stored as fp16 (floored at 2^-14); zero-point = round-half-even(-min/scale)
  * clamped to +-2048 and stored as fp16; codes = clamp(round(w/scale)+zero, 0, 2^bits-1).
+ * Group sizes (the axis of the paper's group-size ablation, Sec. 4.5): G = 16, 32, 64 or 128 with
+ * 4-bit codes, 16, 32 or 64 with 8-bit codes (at most 64 code bytes per group); K <= 65536.
  */
 gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bits,
                         double sparsity, gqsa_handle_t* out);
@@ -98,8 +100,9 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
 
 /* Re-partition the group stream over n_workgroups (1..4096) workgroups of waves_per_workgroup
  * (1..16) wavefront workers and rebuild the host copy of the device image.  Only before the
- * handle is uploaded.  The default chosen by pack/import is min(256, ceil(n_blocks/16))
- * workgroups of 16 wavefronts (one workgroup per compute unit of an MI355X). */
+ * handle is uploaded.  The default chosen by pack/import is min(256, n_blocks) workgroups (one per
+ * compute unit of an MI355X) of ceil(n_blocks * (G/16) / (2 * workgroups)) wavefronts, at most 16
+ * and at most ceil(n_blocks / workgroups). */
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
 
 /* Create the device image and carry workspace on the current HIP device (synchronous). */
@@ -112,7 +115,8 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
  *         groups receive +0
  *   batch 1..16
  *   hip_stream a hipStream_t (NULL = the default stream)
- * K/G must not exceed 2048 (x and its group sums are staged in LDS); GQSA_ERR_UNSUPPORTED else.
+ * K must not exceed 32768 (x and its group sums are staged in LDS); GQSA_ERR_UNSUPPORTED else.
+ * Group sizes above 16 run one activation row and one matrix per launch.
  * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
  * bit-identical from run to run.  Does not synchronise.
  */
@@ -129,7 +133,8 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
  *            partition (n_workgroups, waves_per_workgroup); GQSA_ERR_SHAPE otherwise
  *   x_dev    [device] fp16 [batch,K], 16-byte aligned
  *   y_devs   [host] array of n_matrices [device] pointers, y_devs[i] fp16 [batch,N_i]
- * Results are bit-identical to n_matrices separate gqsa_gemv calls.
+ * Results are bit-identical to n_matrices separate gqsa_gemv calls (which is what happens for
+ * batch > 1 and for group sizes above 16).
  */
 gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, const void* x_dev,
                               void* const* y_devs, int batch, void* hip_stream);

@@ -16,18 +16,25 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     w = g*waves_per_workgroup + l; n_waves = n_workgroups*waves_per_workgroup;
     b_w = first block of worker w = sum of the earlier workers' counts.
  3. Superblocks.  A worker's run is cut, from its start, into superblocks of 4
-    blocks as long as 4 fit, then one of 2 blocks if at least 2 remain, then
-    one of 1 block if one remains.  A superblock of U blocks starting at block
-    b covers stream positions 64b .. 64(b+U)-1 of the stream; the position
-    64b + p lives in block b + (p mod U), lane p div U.
- 4. Block.  Each block is (G*bits/8 + 6)*64 bytes: 64 lanes x code bytes, then
+    blocks as long as 4 fit, then of 2 blocks as long as 2 fit, then of 1
+    block -- except that a superblock has at most u_max blocks, u_max = 4 for
+    up to 16 code bytes per group (G*bits/8), 2 for 32, 1 for 64.  A
+    superblock of U blocks starting at block b covers stream positions
+    64b .. 64(b+U)-1 of the stream; the position 64b + p lives in block
+    b + (p mod U), lane p div U.
+ 4. Block.  Each block is (G*bits/8 + 6)*64 bytes: the code planes, then
     64 x uint32 (fp16 scale bits | fp16 zero bits << 16), then 64 x uint16
-    (group-column << 4, plus 1 if the group is the first stored group of its
-    row; group-columns are below 4096).
-    4-bit codes, G = 16: a lane holds two little-endian uint32; word h holds
-    elements 8h..8h+7 of the group, element 8h+2m in bits 4m..4m+3 and element
-    8h+2m+1 in bits 16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j of the
-    lane's 16 bytes is element j.
+    index words.  G = 16*M with M in {1, 2, 4, 8}.  The index word is
+    (group-column * M) << 4 -- sixteen times the number of the 16-element slot
+    of K at which the group starts (slots are below 4096) -- plus 1 if the
+    group is the first stored group of its row.
+    Codes.  A lane's code string has G*bits/8 bytes.  4-bit codes: it is a
+    sequence of little-endian uint32, word h holding elements 8h..8h+7 of the
+    group, element 8h+2m in bits 4m..4m+3 and element 8h+2m+1 in bits
+    16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j is element j.  The string
+    is stored in planes: with P = min(16, G*bits/8) bytes per lane and plane,
+    plane k (64*P bytes, lanes in order) holds bytes k*P .. k*P+P-1 of every
+    lane's string; the planes follow each other.
  5. Side tables (int32): wave_info[n_waves][4] = {rank_base, tail_closed +
     2 * lead_len, lead_first, chain_len} with
       rank_base   = (number of row-head groups at stream positions before
@@ -57,13 +64,16 @@ MAX_WAVES = 4096
 WAVES_PER_WORKGROUP = 16
 
 
-def default_partition(nnzg: int):
+def default_partition(nnzg: int, G: int = 16):
     """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise:
-    workgroups of 16 wavefronts, at most 256 of them, no more than the blocks can feed."""
+    min(256, nblocks) workgroups (at least 1); wavefronts per workgroup =
+    ceil(nblocks * (G/16) / (2 * n_workgroups)), at least 1, at most 16 and at most
+    ceil(nblocks / n_workgroups)."""
     nblocks = (nnzg + LANES - 1) // LANES
-    wgs = (nblocks + WAVES_PER_WORKGROUP - 1) // WAVES_PER_WORKGROUP
-    wgs = max(1, min(MAX_WAVES // WAVES_PER_WORKGROUP, wgs))
-    return wgs, WAVES_PER_WORKGROUP
+    wgs = max(1, min(MAX_WAVES // WAVES_PER_WORKGROUP, nblocks))
+    per_wg = max(1, -(-nblocks // wgs))
+    want = -(-(nblocks * (G // 16)) // (2 * wgs))
+    return wgs, max(1, min(WAVES_PER_WORKGROUP, per_wg, want))
 
 
 def worker_block_counts(nblocks: int, n_workgroups: int, waves_per_workgroup: int) -> np.ndarray:
@@ -83,7 +93,12 @@ def _align(n: int) -> int:
     return (n + ALIGN - 1) // ALIGN * ALIGN
 
 
-def stream_placement(nblocks: int, n_workgroups: int, waves_per_workgroup: int):
+def largest_superblock(code_bytes: int) -> int:
+    """u_max of spec item 3."""
+    return 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
+
+
+def stream_placement(nblocks: int, n_workgroups: int, waves_per_workgroup: int, u_max: int = 4):
     """For every stream position: (block, lane) it is stored at (spec items 2-3)."""
     n_w = worker_block_counts(nblocks, n_workgroups, waves_per_workgroup)
     b_w = np.concatenate(([0], np.cumsum(n_w)[:-1]))
@@ -93,17 +108,17 @@ def stream_placement(nblocks: int, n_workgroups: int, waves_per_workgroup: int):
     w = np.repeat(np.arange(n_w.size), n_w)[blk_of_pos]
     q = pos - LANES * b_w[w]                    # position inside the worker's run
     nw = n_w[w]
-    n4 = nw // 4
-    rem = nw % 4
+    n4 = nw // 4 if u_max >= 4 else np.zeros_like(nw)        # superblocks of 4, of 2, of 1
+    n2 = (nw - 4 * n4) // 2 if u_max >= 2 else np.zeros_like(nw)
     in4 = q < 256 * n4
     qq = q - 256 * n4
-    has2 = rem >= 2
-    in2 = (~in4) & has2 & (qq < 128)
+    in2 = (~in4) & (qq < 128 * n2)
     in1 = (~in4) & (~in2)
+    q1 = qq - 128 * n2
     U = np.where(in4, 4, np.where(in2, 2, 1))
-    sb_blk = np.where(in4, 4 * (q // 256), np.where(in2, 4 * n4, 4 * n4 + np.where(has2, 2, 0)))
-    p = np.where(in4, q % 256, np.where(in2, qq, qq - np.where(has2, 128, 0)))
-    assert (p[in1] < 64).all() and (p >= 0).all()
+    sb_blk = np.where(in4, 4 * (q // 256), np.where(in2, 4 * n4 + 2 * (qq // 128), 4 * n4 + 2 * n2 + q1 // 64))
+    p = np.where(in4, q % 256, np.where(in2, qq % 128, q1 % 64))
+    assert (p >= 0).all() and (q1[in1] >= 0).all()
     block = b_w[w] + sb_blk + (p % U)
     lane = p // U
     return block, lane, b_w, n_w
@@ -111,12 +126,13 @@ def stream_placement(nblocks: int, n_workgroups: int, waves_per_workgroup: int):
 
 def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     """Exact bytes the library must hold on the device for canonical arrays `c`."""
-    if c.G != 16 or c.bits not in (4, 8):
-        raise ValueError("device layout is specified for G=16, bits in {4,8}")
+    if c.G not in (16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
+        raise ValueError("device layout is specified for G in {16,32,64,128}, bits in {4,8}, at most 64 code bytes")
     nnzg = c.nnzg
     nblocks = (nnzg + LANES - 1) // LANES
     code_bytes = c.G * c.bits // 8
     blk_bytes = (code_bytes + 6) * LANES
+    chunks = c.G // 16
 
     ri = np.asarray(c.rowIndex, dtype=np.int64)
     counts = ri[1:] - ri[:-1]
@@ -131,25 +147,28 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     wave_info[:, 1] = 1
     wave_info[:, 2] = -1
     if nblocks > 0:
-        block, lane, b_w, n_w = stream_placement(nblocks, n_workgroups, waves_per_workgroup)
+        block, lane, b_w, n_w = stream_placement(nblocks, n_workgroups, waves_per_workgroup,
+                                                 largest_superblock(code_bytes))
         block = block[:nnzg]
         lane = lane[:nnzg]
         # codes
         vals = np.asarray(c.values, dtype=np.uint8).reshape(nnzg, code_bytes)
         if c.bits == 4:
-            elems = np.empty((nnzg, 16), dtype=np.uint32)
+            elems = np.empty((nnzg, c.G), dtype=np.uint32)
             elems[:, 0::2] = vals & 0xF
             elems[:, 1::2] = vals >> 4
-            words = np.zeros((nnzg, 2), dtype=np.uint32)
-            for h in range(2):
+            words = np.zeros((nnzg, 2 * chunks), dtype=np.uint32)
+            for h in range(2 * chunks):
                 for m in range(4):
                     words[:, h] |= elems[:, 8 * h + 2 * m] << np.uint32(4 * m)
                     words[:, h] |= elems[:, 8 * h + 2 * m + 1] << np.uint32(16 + 4 * m)
-            lane_bytes = words.astype("<u4").view(np.uint8).reshape(nnzg, 8)
+            lane_bytes = words.astype("<u4").view(np.uint8).reshape(nnzg, code_bytes)
         else:
             lane_bytes = vals
-        codes_view = blocks[:, :LANES * code_bytes].reshape(nblocks, LANES, code_bytes)
-        codes_view[block, lane, :] = lane_bytes
+        plane = min(16, code_bytes)
+        for k in range(code_bytes // plane):
+            plane_view = blocks[:, k * LANES * plane:(k + 1) * LANES * plane].reshape(nblocks, LANES, plane)
+            plane_view[block, lane, :] = lane_bytes[:, k * plane:(k + 1) * plane]
         # scale | zero << 16
         sz = (np.asarray(c.scales, dtype=np.uint32) |
               (np.asarray(c.zeros, dtype=np.uint32) << np.uint32(16))).astype("<u4")
@@ -160,9 +179,9 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
         is_head = np.zeros(nnzg, dtype=np.uint16)
         is_head[head_pos] = 1
         gcol = np.asarray(c.groups, dtype=np.int64)
-        if gcol.size and gcol.max() >= 4096:
-            raise ValueError("group-column does not fit 12 bits")
-        idx = ((gcol << 4).astype(np.uint16) | is_head).astype("<u2")
+        if gcol.size and gcol.max() * chunks + chunks - 1 >= 4096:
+            raise ValueError("slot number does not fit 12 bits")
+        idx = (((gcol * chunks) << 4).astype(np.uint16) | is_head).astype("<u2")
         idx_off = sz_off + LANES * 4
         idx_view = blocks[:, idx_off:idx_off + LANES * 2].reshape(nblocks, LANES, 2)
         idx_view[block, lane, :] = idx.view(np.uint8).reshape(nnzg, 2)

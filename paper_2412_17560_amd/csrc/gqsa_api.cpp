@@ -12,9 +12,10 @@ gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
 {
     if (N <= 0 || K <= 0 || G <= 0) return GQSA_ERR_SHAPE;
     if (bits != 4 && bits != 8) return GQSA_ERR_UNSUPPORTED;
-    if (G != 16) return GQSA_ERR_UNSUPPORTED;
+    if (G != 16 && G != 32 && G != 64 && G != 128) return GQSA_ERR_UNSUPPORTED;
+    if (G * bits / 8 > 64) return GQSA_ERR_UNSUPPORTED;       // at most 64 code bytes per group
     if (K % G != 0) return GQSA_ERR_SHAPE;
-    if (K / G > gqsa::kMaxGroupColumns) return GQSA_ERR_SHAPE;
+    if (K / 16 > gqsa::kMaxGroupColumns) return GQSA_ERR_SHAPE;
     if (N > (int64_t{1} << 30)) return GQSA_ERR_SHAPE;
     return GQSA_OK;
 }
@@ -23,7 +24,9 @@ gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
 {
     if (st == GQSA_OK) {
         const int64_t nb = (m->nnzg() + gqsa::kLanes - 1) / gqsa::kLanes;
-        st = gqsa::build_image(m, gqsa::default_workgroups(nb), gqsa::kWavesPerWorkgroup);
+        int wgs = 1, wpw = 1;
+        gqsa::default_partition(nb, m->G, &wgs, &wpw);
+        st = gqsa::build_image(m, wgs, wpw);
     }
     if (st != GQSA_OK) {
         delete m;

@@ -220,12 +220,28 @@ __device__ __forceinline__ void store_row(const MatArgs& m, int b, int rank, flo
     m.y[b * m.N + row] = float_to_half_bits(v);
 }
 
-// The compressed groups of up to four blocks, as loaded (one group per lane per block).
-template <int BITS>
+// Storage format of a group as the kernel is compiled for it: code width and group size
+// G = 16 * M.  A block holds 64 groups, one per lane: the code bytes in planes of at most
+// 16 bytes per lane (each plane one coalesced load), then scale | zero << 16, then the index word.
+template <int BITS_, int M_>
+struct Fmt {
+    static constexpr int BITS = BITS_;
+    static constexpr int M = M_;                         // 16-element chunks per group
+    static constexpr int CB = 16 * M_ * BITS_ / 8;       // code bytes per group
+    static constexpr int CW = CB / 4;                    // code words per group
+    static constexpr int CWC = CW / M_;                  // code words per chunk (2 or 4)
+    static constexpr int PB = CB < 16 ? CB : 16;         // bytes per lane in one code plane
+    static constexpr int PLANES = CB / PB;
+    static constexpr int UMAX = CB <= 16 ? 4 : (CB <= 32 ? 2 : 1);   // blocks of the largest superblock
+    static constexpr int BB = (CB + 6) * kLanes;         // block bytes
+};
+
+// The compressed groups of up to UMAX blocks, as loaded (one group per lane per block).
+template <typename F>
 struct Tile {
-    uint32_t code[4][BITS / 2];
-    uint32_t sz[4];
-    uint32_t ix[4];
+    uint32_t code[F::UMAX][F::CW];
+    uint32_t sz[F::UMAX];
+    uint32_t ix[F::UMAX];
 };
 
 // (1) stream the compressed groups: coalesced loads, all issued before anything waits.  The
@@ -236,44 +252,26 @@ __device__ __forceinline__ T load_at(const uint8_t* base, uint32_t byte_offset)
     return *reinterpret_cast<const T*>(base + byte_offset);
 }
 
-template <int BITS, int U>
-__device__ __forceinline__ void load_tile_n(Tile<BITS>& t, const uint8_t* p, int lane)
+template <typename F>
+__device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int U, int lane)
 {
-    constexpr int CB = 16 * BITS / 8;                 // code bytes per group
-    constexpr int BB = (CB + 6) * kLanes;             // block bytes
     const uint32_t ulane = static_cast<uint32_t>(lane);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if constexpr (BITS == 4) {
-            const uint2 c = load_at<uint2>(p, ulane * 8u + u * BB);
-            t.code[u][0] = c.x; t.code[u][1] = c.y;
-        } else {
-            const uint4 c = load_at<uint4>(p, ulane * 16u + u * BB);
-            t.code[u][0] = c.x; t.code[u][1] = c.y; t.code[u][2] = c.z; t.code[u][3] = c.w;
-        }
-        t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * BB + CB * kLanes));
-        t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * BB + (CB + 4) * kLanes));
-    }
-}
-
-template <int BITS>
-__device__ __forceinline__ void load_tile(Tile<BITS>& t, const uint8_t* p, int U, int lane)
-{
-    constexpr int CB = 16 * BITS / 8;                 // code bytes per group
-    constexpr int BB = (CB + 6) * kLanes;             // block bytes
-    const uint32_t ulane = static_cast<uint32_t>(lane);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < F::UMAX; ++u) {
         if (u < U) {
-            if constexpr (BITS == 4) {
-                const uint2 c = load_at<uint2>(p, ulane * 8u + u * BB);
-                t.code[u][0] = c.x; t.code[u][1] = c.y;
-            } else {
-                const uint4 c = load_at<uint4>(p, ulane * 16u + u * BB);
-                t.code[u][0] = c.x; t.code[u][1] = c.y; t.code[u][2] = c.z; t.code[u][3] = c.w;
+#pragma unroll
+            for (int pl = 0; pl < F::PLANES; ++pl) {
+                if constexpr (F::PB == 8) {
+                    const uint2 c = load_at<uint2>(p, ulane * 8u + u * F::BB);
+                    t.code[u][0] = c.x; t.code[u][1] = c.y;
+                } else {
+                    const uint4 c = load_at<uint4>(p, ulane * 16u + (u * F::BB + pl * 16 * kLanes));
+                    t.code[u][4 * pl + 0] = c.x; t.code[u][4 * pl + 1] = c.y;
+                    t.code[u][4 * pl + 2] = c.z; t.code[u][4 * pl + 3] = c.w;
+                }
             }
-            t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * BB + CB * kLanes));
-            t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * BB + (CB + 4) * kLanes));
+            t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * F::BB + F::CB * kLanes));
+            t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * F::BB + (F::CB + 4) * kLanes));
         }
     }
 }
@@ -282,8 +280,8 @@ __device__ __forceinline__ void load_tile(Tile<BITS>& t, const uint8_t* p, int U
 // 8..15 in a second array of 16-byte slots 16*KGP bytes further on, and the fp32 sum of the 16
 // as a dense array of floats at 32*KGP (4 bytes per column: a wavefront's 64 reads of it spread
 // over all banks instead of a quarter of them).  Row b starts at b * 48 * KGP.
-template <int BITS, int KGP, int U, int NB, typename Args>
-__device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, const Tile<BITS>& t,
+template <typename F, int KGP, int U, int NB, typename Args>
+__device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, const Tile<F>& t,
                                              int lane, const uint8_t* xlds, WaveState<NB>& st)
 {
     // Row heads as wave-uniform lane masks, one per position of the superblock (index word =
@@ -320,27 +318,32 @@ __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, co
     int nh = 0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        Codes c;
-        if constexpr (BITS == 4) {
-            decode_w4(a, t.code[u][0], &c.q[0]);
-            decode_w4(a, t.code[u][1], &c.q[4]);
-        } else {
-            decode_w8(t.code[u][0], &c.q[0]);
-            decode_w8(t.code[u][1], &c.q[2]);
-            decode_w8(t.code[u][2], &c.q[4]);
-            decode_w8(t.code[u][3], &c.q[6]);
-        }
         const float s = half_to_float(t.sz[u] & 0xFFFFu);
         const float z = half_to_float(t.sz[u] >> 16);
-        const uint8_t* xg = xlds + (t.ix[u] & 0xFFF0u);
+        const uint32_t slot = t.ix[u] & 0xFFF0u;        // byte offset of the group's first 16 activations
         float dotz[NB];   // sum_j q_j x_j - z sum_j x_j; times s it is the group's contribution
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const uint8_t* xb = xg + b * (48 * KGP);
-            const uint4 xl = *reinterpret_cast<const uint4*>(xb);
-            const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
-            const float xs = *reinterpret_cast<const float*>(xlds + b * (48 * KGP) + 32 * KGP + ((t.ix[u] & 0xFFF0u) >> 2));
-            dotz[b] = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
+        for (int i = 0; i < F::M; ++i) {                // the group's 16-element chunks
+            Codes c;
+            if constexpr (F::BITS == 4) {
+                decode_w4(a, t.code[u][2 * i], &c.q[0]);
+                decode_w4(a, t.code[u][2 * i + 1], &c.q[4]);
+            } else {
+                decode_w8(t.code[u][4 * i], &c.q[0]);
+                decode_w8(t.code[u][4 * i + 1], &c.q[2]);
+                decode_w8(t.code[u][4 * i + 2], &c.q[4]);
+                decode_w8(t.code[u][4 * i + 3], &c.q[6]);
+            }
+            const uint8_t* xg = xlds + slot + 16 * i;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const uint8_t* xb = xg + b * (48 * KGP);
+                const uint4 xl = *reinterpret_cast<const uint4*>(xb);
+                const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
+                const float xs = *reinterpret_cast<const float*>(xlds + b * (48 * KGP) + 32 * KGP + (slot >> 2) + 4 * i);
+                const float d = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
+                dotz[b] = i == 0 ? d : dotz[b] + d;
+            }
         }
         const bool head_here = (t.ix[u] & 1u) != 0;
         if (simple) {
@@ -556,7 +559,7 @@ struct ParkedArgs {
     const int4* wave_info;
 };
 
-template <int BITS, int KGP, int NB, int NM>
+template <typename F, int KGP, int NB, int NM>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(GemvArgsT<NM> a)
 {
     // x arrays (NB * 48 * KGP bytes), then the wavefronts' records per matrix
@@ -574,7 +577,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     const int wg = blockIdx.x;
     const int wave = wg * wpw + wl;
-    constexpr int BB = (16 * BITS / 8 + 6) * kLanes;
+    constexpr int BB = F::BB;
 
     // a worker's run of blocks in a matrix: the blocks are dealt evenly to the workgroups, a
     // workgroup's blocks evenly to its wavefronts (contiguous runs, equal counts)
@@ -585,7 +588,8 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         left = per_wave + (wl < extra_wave ? 1 : 0);
         p = r.blocks + static_cast<size_t>(wg_first + per_wave * wl + (wl < extra_wave ? wl : extra_wave)) * BB;
     };
-    auto next_size = [](int n) { return n >= 4 ? 4 : (n >= 2 ? 2 : n); };
+    // superblocks of 4, 2, 1 blocks (as far as the format's largest superblock allows)
+    auto next_size = [](int n) { return n >= 4 && F::UMAX >= 4 ? 4 : (n >= 2 && F::UMAX >= 2 ? 2 : (n >= 1 ? 1 : 0)); };
 
     // issue the loads of x first and of the first superblock right behind them, so that the
     // weights are already on their way while x is staged in LDS
@@ -617,9 +621,9 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     // line of the argument block); then the per-matrix worker records (what the fix-up needs to
     // know about this worker; a worker without blocks may still sit inside a row) and the
     // output arguments; then x is staged in LDS.
-    Tile<BITS> cur, nxt;
+    Tile<F> cur, nxt;
     int u_cur = next_size(left);
-    load_tile<BITS>(cur, p, u_cur, lane);
+    load_tile<F>(cur, p, u_cur, lane);
     uint4 lo0 = {0, 0, 0, 0}, hi0 = {0, 0, 0, 0};
     if (tid < n_slots) {
         const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(tid) * 16);
@@ -698,10 +702,14 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
                 run_of(matrix_run<NM>(mi_next), left, p_next);
                 u_next = next_size(left);
             }
-            load_tile<BITS>(nxt, p_next, u_next, lane);   // in flight during this superblock
-            if (u_cur == 4) compute_tile<BITS, KGP, 4, NB>(a, m, cur, lane, xlds, st);
-            else if (u_cur == 2) compute_tile<BITS, KGP, 2, NB>(a, m, cur, lane, xlds, st);
-            else compute_tile<BITS, KGP, 1, NB>(a, m, cur, lane, xlds, st);
+            load_tile<F>(nxt, p_next, u_next, lane);   // in flight during this superblock
+            if constexpr (F::UMAX >= 4) {
+                if (u_cur == 4) compute_tile<F, KGP, 4, NB>(a, m, cur, lane, xlds, st);
+            }
+            if constexpr (F::UMAX >= 2) {
+                if (u_cur == 2) compute_tile<F, KGP, 2, NB>(a, m, cur, lane, xlds, st);
+            }
+            if (u_cur == 1) compute_tile<F, KGP, 1, NB>(a, m, cur, lane, xlds, st);
             if (mi_next != mi || u_next == 0) {           // this matrix's run is complete
                 if (lane == 0) {
                     rec_n[mi * kWavesPerWorkgroup + wl].heads = st.heads;   // (info is filled in below)
@@ -781,62 +789,82 @@ GemvArgsT<NM> first_matrices(const GemvArgs& a)
     return r;
 }
 
-template <int BITS, int KGP, int NB, int NM>
+template <typename F, int KGP, int NB, int NM>
 void launch_variant(const GemvArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s)
 {
-    hipLaunchKernelGGL((gqsa_gemv_kernel<BITS, KGP, NB, NM>), grid, block, lds, s, first_matrices<NM>(a));
+    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB, NM>), grid, block, lds, s, first_matrices<NM>(a));
 }
 
-template <int BITS, int KGP, int NB, int NM>
+template <typename F, int KGP, int NB, int NM>
 Variant variant_if_it_fits()
 {
     Variant v;
     if constexpr (lds_bytes(KGP, NB, NM) <= kMaxLdsBytes) {
-        v.fn = reinterpret_cast<const void*>(&gqsa_gemv_kernel<BITS, KGP, NB, NM>);
-        v.launch = &launch_variant<BITS, KGP, NB, NM>;
+        v.fn = reinterpret_cast<const void*>(&gqsa_gemv_kernel<F, KGP, NB, NM>);
+        v.launch = &launch_variant<F, KGP, NB, NM>;
     }
     return v;
 }
 
-// Compiled variants: 1, 2, 4 or 8 activation rows for one matrix (as far as NB copies of x fit
-// the 160 KB of LDS), and 2, 3 or 4 matrices for one activation row.
-template <int BITS, int KGP>
+// Compiled variants.  Group size 16: 1, 2, 4 or 8 activation rows for one matrix (as far as NB
+// copies of x fit the 160 KB of LDS), and 2, 3 or 4 matrices for one activation row.  Larger
+// groups: one activation row, one matrix.
+template <typename F, int KGP>
 Variant pick_variant(int nb, int nm)
 {
-    if (nm == 1) {
-        switch (nb) {
-            case 1: return variant_if_it_fits<BITS, KGP, 1, 1>();
-            case 2: return variant_if_it_fits<BITS, KGP, 2, 1>();
-            case 4: return variant_if_it_fits<BITS, KGP, 4, 1>();
-            case 8: return variant_if_it_fits<BITS, KGP, 8, 1>();
+    if constexpr (F::M == 1) {
+        if (nm == 1) {
+            switch (nb) {
+                case 1: return variant_if_it_fits<F, KGP, 1, 1>();
+                case 2: return variant_if_it_fits<F, KGP, 2, 1>();
+                case 4: return variant_if_it_fits<F, KGP, 4, 1>();
+                case 8: return variant_if_it_fits<F, KGP, 8, 1>();
+            }
+        } else if (nb == 1) {
+            switch (nm) {
+                case 2: return variant_if_it_fits<F, KGP, 1, 2>();
+                case 3: return variant_if_it_fits<F, KGP, 1, 3>();
+                case 4: return variant_if_it_fits<F, KGP, 1, 4>();
+            }
         }
-    } else if (nb == 1) {
-        switch (nm) {
-            case 2: return variant_if_it_fits<BITS, KGP, 1, 2>();
-            case 3: return variant_if_it_fits<BITS, KGP, 1, 3>();
-            case 4: return variant_if_it_fits<BITS, KGP, 1, 4>();
-        }
+    } else {
+        if (nm == 1 && nb == 1) return variant_if_it_fits<F, KGP, 1, 1>();
     }
     return Variant{};
 }
 
-// The kernel is compiled for group-column counts rounded up to a power of two (the LDS
-// offsets between the x arrays are immediates).
-template <int BITS>
-Variant pick_kernel(int kg, int nb, int nm, int* kgp)
+// The kernel is compiled for counts of 16-element activation slots (K/16) rounded up to a power
+// of two (the LDS offsets between the x arrays are immediates).
+template <typename F>
+Variant pick_kernel(int slots, int nb, int nm, int* kgp)
 {
-    if (kg <= 256) { *kgp = 256; return pick_variant<BITS, 256>(nb, nm); }
-    if (kg <= 512) { *kgp = 512; return pick_variant<BITS, 512>(nb, nm); }
-    if (kg <= 1024) { *kgp = 1024; return pick_variant<BITS, 1024>(nb, nm); }
-    if (kg <= 2048) { *kgp = 2048; return pick_variant<BITS, 2048>(nb, nm); }
+    if (slots <= 256) { *kgp = 256; return pick_variant<F, 256>(nb, nm); }
+    if (slots <= 512) { *kgp = 512; return pick_variant<F, 512>(nb, nm); }
+    if (slots <= 1024) { *kgp = 1024; return pick_variant<F, 1024>(nb, nm); }
+    if (slots <= 2048) { *kgp = 2048; return pick_variant<F, 2048>(nb, nm); }
     *kgp = 0;
     return Variant{};
 }
 
 Variant pick(const gqsa_matrix* m, int nb, int nm, int* kgp)
 {
-    const int kg = static_cast<int>(m->K / m->G);
-    return m->bits == 4 ? pick_kernel<4>(kg, nb, nm, kgp) : pick_kernel<8>(kg, nb, nm, kgp);
+    const int slots = static_cast<int>(m->K / 16);
+    *kgp = 0;
+    if (m->bits == 4) {
+        switch (m->G) {
+            case 16: return pick_kernel<Fmt<4, 1>>(slots, nb, nm, kgp);
+            case 32: return pick_kernel<Fmt<4, 2>>(slots, nb, nm, kgp);
+            case 64: return pick_kernel<Fmt<4, 4>>(slots, nb, nm, kgp);
+            case 128: return pick_kernel<Fmt<4, 8>>(slots, nb, nm, kgp);
+        }
+    } else if (m->bits == 8) {
+        switch (m->G) {
+            case 16: return pick_kernel<Fmt<8, 1>>(slots, nb, nm, kgp);
+            case 32: return pick_kernel<Fmt<8, 2>>(slots, nb, nm, kgp);
+            case 64: return pick_kernel<Fmt<8, 4>>(slots, nb, nm, kgp);
+        }
+    }
+    return Variant{};
 }
 
 constexpr size_t counters_offset(int n_waves)
@@ -939,24 +967,25 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
     a.n_mats = n_mats;
     a.wpw = m0->waves_per_workgroup;
     a.n_wg = m0->n_workgroups;
-    a.kg = static_cast<int>(m0->K / m0->G);
+    a.kg = static_cast<int>(m0->K / 16);       // 16-element activation slots
     a.nib_lo = 0x000F000Fu;
     a.nib_hi = 0x00F000F0u;
     a.k1024x2 = 0x64006400u;
 
     const int threads = m0->waves_per_workgroup * kLanes;
     const int grid = m0->n_workgroups;
-    if (n_mats > 1 && batch == 1) {
+    int kgp_multi = 0;
+    const Variant multi = (n_mats > 1 && batch == 1) ? pick(m0, 1, n_mats, &kgp_multi) : Variant{};
+    if (multi) {
         // several matrices, one activation row: one launch walks them all
-        int kgp = 0;
-        Variant v = pick(m0, 1, n_mats, &kgp);
-        if (!v) return GQSA_ERR_UNSUPPORTED;
+        const int kgp = kgp_multi;
+        const Variant v = multi;
         a.x = static_cast<const uint16_t*>(x);
         for (int i = 0; i < n_mats; ++i) a.m[i].y = static_cast<uint16_t*>(ys[i]);
         v.launch(a, dim3(grid), dim3(threads), lds_bytes(kgp, 1, n_mats), s);
     } else {
         // one matrix at a time; its batch goes out in launches of 8, 4, 2 or 1 rows: the most
-        // that fits LDS and is left
+        // that the format has a kernel for, fits LDS and is left
         for (int i = 0; i < n_mats; ++i) {
             GemvArgs one = a;
             one.n_mats = 1;

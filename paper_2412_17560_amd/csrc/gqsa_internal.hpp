@@ -16,7 +16,7 @@ constexpr int kMaxDefaultWorkgroups = 256;  // MI355X: 256 compute units
 constexpr int kMaxWorkgroups = 4096;
 constexpr int kMaxBatch = 16;
 constexpr int kMaxMatricesPerLaunch = 4;
-constexpr int64_t kMaxGroupColumns = 4096;  // 12-bit group-column << 4 | head flag in 16 bits
+constexpr int64_t kMaxGroupColumns = 4096;  // 16-element slots of K: 12-bit slot << 4 | head flag in 16 bits
 constexpr size_t kAlign = 256;
 
 // Offsets (bytes) of the regions inside the device image.
@@ -71,7 +71,7 @@ namespace gqsa {
 // host packer (gqsa_pack.cpp)
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          const int32_t* keep_per_row, double sparsity, gqsa_matrix* m);
-int default_workgroups(int64_t n_blocks);
+void default_partition(int64_t n_blocks, int G, int* n_workgroups, int* waves_per_workgroup);
 gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup);
 
 // device side (gqsa_gemv.hip)

@@ -174,25 +174,35 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
     return GQSA_OK;
 }
 
-int default_workgroups(int64_t n_blocks)
+// The partition pack/import choose: one workgroup per compute unit as soon as there are 256
+// blocks, and in a workgroup as many wavefronts (at most 16, at most one per block) as give
+// every wavefront about two blocks' worth of 16-element chunks -- matrices of a few MB are bound
+// by how many compute units pull on memory, not by how long a wavefront's run is.
+void default_partition(int64_t n_blocks, int G, int* n_workgroups, int* waves_per_workgroup)
 {
-    int64_t wgs = (n_blocks + kWavesPerWorkgroup - 1) / kWavesPerWorkgroup;
-    return static_cast<int>(std::max<int64_t>(1, std::min<int64_t>(kMaxDefaultWorkgroups, wgs)));
+    const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>(kMaxDefaultWorkgroups, n_blocks));
+    const int64_t per_wg = std::max<int64_t>(1, (n_blocks + wgs - 1) / wgs);
+    const int64_t chunks = n_blocks * (G / 16);
+    const int64_t want = (chunks + 2 * wgs - 1) / (2 * wgs);
+    *n_workgroups = static_cast<int>(wgs);
+    *waves_per_workgroup = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>({kWavesPerWorkgroup, per_wg, want})));
 }
 
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
 // 64-group blocks and dealt in contiguous, near-equal runs first to the workgroups and then,
 // inside each workgroup, to its wavefronts (the nnz-balanced version of the paper's
 // task-centric split, Sec. 3.5; a row may be shared by neighbouring wavefronts).  Inside a run the
-// blocks are taken 4, then 2, then 1 at a time ("superblocks"); in a superblock of U blocks
-// lane l owns U consecutive stream positions, stored one per block so that every block is a
-// fully coalesced, lane-interleaved load:
+// blocks are taken 4, then 2, then 1 at a time ("superblocks"; at most 2 at a time with 32 code
+// bytes per group, 1 with 64); in a superblock of U blocks lane l owns U consecutive stream
+// positions, stored one per block so that every block is a fully coalesced, lane-interleaved load:
 //     stream position (first of superblock) + p  ->  block (p mod U), lane (p div U).
-// Block = 64 x code bytes | 64 x (scale | zero << 16) | 64 x (group-column << 4 | head), the
-// last one being the byte offset of the activation group in LDS with the row-head flag in bit 0.
-// 4-bit code words are nibble-permuted so that one AND per pair of elements yields a packed
-// fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m at bits 4m and
-// element 8h+2m+1 at bits 16+4m.
+// Block = code planes | 64 x (scale | zero << 16) | 64 x (16 * LDS slot | head).  A group of
+// G = 16 M elements has G*bits/8 code bytes; plane k holds bytes 16k..16k+15 of every lane's
+// code string (a single plane of 8 bytes per lane for 4-bit, G = 16).  The index word is the
+// byte offset in LDS of the group's first 16 activations (slot = group-column * M) with the
+// row-head flag in bit 0.  4-bit code words are nibble-permuted so that one AND per pair of
+// elements yields a packed fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m
+// at bits 4m and element 8h+2m+1 at bits 16+4m.
 gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup)
 {
     if (n_workgroups < 1 || n_workgroups > kMaxWorkgroups) return GQSA_ERR_RANGE;
@@ -227,26 +237,39 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         img.assign(map.total, 0);
     } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
 
+    // A lane's code string: 4-bit codes as nibble-permuted words (word h = elements 8h..8h+7),
+    // 8-bit codes as they are.  In the block it is cut into planes of at most 16 bytes per lane.
+    const int chunks = m->G / 16;                    // 16-element chunks per group
+    const int plane_bytes = std::min(cb, 16);
+    std::vector<uint8_t> code(static_cast<size_t>(cb));
     auto put_group = [&](int64_t g, int64_t block, int lane) {
         uint8_t* base = img.data() + static_cast<size_t>(block) * bb;
         const uint8_t* v = &m->values[static_cast<size_t>(g) * cb];
         if (m->bits == 4) {
-            uint32_t word[2] = {0, 0};
-            for (int j = 0; j < 16; ++j) {
-                const uint32_t q = (j & 1) ? (v[j >> 1] >> 4) : (v[j >> 1] & 0xF);
-                const int h = j >> 3, m2 = (j & 7) >> 1;
-                word[h] |= q << ((j & 1) ? 16 + 4 * m2 : 4 * m2);
+            for (int h = 0; h < 2 * chunks; ++h) {
+                uint32_t word = 0;
+                for (int e = 0; e < 8; ++e) {
+                    const int j = 8 * h + e;
+                    const uint32_t q = (j & 1) ? (v[j >> 1] >> 4) : (v[j >> 1] & 0xF);
+                    word |= q << ((e & 1) ? 16 + 4 * (e >> 1) : 4 * (e >> 1));
+                }
+                std::memcpy(&code[4 * static_cast<size_t>(h)], &word, 4);
             }
-            std::memcpy(base + static_cast<size_t>(lane) * 8, word, 8);
         } else {
-            std::memcpy(base + static_cast<size_t>(lane) * cb, v, cb);
+            std::memcpy(code.data(), v, cb);
         }
+        for (int pl = 0; pl * plane_bytes < cb; ++pl)
+            std::memcpy(base + static_cast<size_t>(pl) * kLanes * plane_bytes + static_cast<size_t>(lane) * plane_bytes,
+                        &code[static_cast<size_t>(pl) * plane_bytes], plane_bytes);
         const uint32_t sz = static_cast<uint32_t>(m->scales[g]) |
                             (static_cast<uint32_t>(m->zeros[g]) << 16);
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + lane * 4, &sz, 4);
-        const uint16_t ix = static_cast<uint16_t>((m->groups[g] << 4) | (head[g] ? 1 : 0));
+        // byte offset in LDS of the group's first 16 activations, row-head flag in bit 0
+        const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * chunks) << 4) | (head[g] ? 1 : 0));
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
+    // the largest superblock: as many blocks as keep a wavefront's tile within about 24 registers
+    const int u_max = cb <= 16 ? 4 : (cb <= 32 ? 2 : 1);
 
     // Per worker: {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}.
     //   rank_base   rank (among non-empty rows) of the row that is open when the run starts,
@@ -295,7 +318,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         const int64_t end = (block0 + mine) * kLanes;
         int64_t pos = first, blk = block0, left = mine;
         while (left > 0) {
-            const int U = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
+            const int U = (left >= 4 && u_max >= 4) ? 4 : ((left >= 2 && u_max >= 2) ? 2 : 1);
             for (int p = 0; p < kLanes * U && pos + p < nnz; ++p)
                 put_group(pos + p, blk + p % U, p / U);
             pos += static_cast<int64_t>(kLanes) * U;

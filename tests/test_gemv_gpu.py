@@ -301,6 +301,54 @@ def test_gemv_multi_error_paths(torch_cuda):
     assert e.value.status == 2
 
 
+# ----------------------------------------------------------------------------- other group sizes
+
+@pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+@pytest.mark.parametrize("part", [None, (5, 3), (2, 16)])
+def test_other_group_sizes(torch_cuda, bits, G, part):
+    """G = 32, 64, 128: several 16-element chunks per stored group, code planes, capped
+    superblocks; rows of very different lengths, shared rows, empty rows; batch 1 and 3."""
+    N, K = 150, 2048
+    W = gi.dense_weight(N, K, seed=91)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=91)
+    h = gq.gqsa_pack_rows(W, keep, G, bits)
+    c = oracle.pack(W, G, bits, keep_per_row=keep)
+    if part is not None:
+        gq.gqsa_set_partition(h, *part)
+    check(torch_cuda, h, c, gi.activations(1, K, seed=9))
+    check(torch_cuda, h, c, gi.activations(3, K, seed=10))
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_other_group_sizes_full_size_and_sparsities(torch_cuda, G):
+    """4096x4096 W4 at G = 32, 64, 128, S = 0 and 50 %, default partition."""
+    W = gi.dense_weight(4096, 4096, seed=gi.config_seed(3, 0))
+    for sparsity in (0.0, 0.5):
+        h = gq.gqsa_pack(W, G, 4, sparsity)
+        c = oracle.pack(W, G, 4, sparsity=sparsity)
+        info = gq.gqsa_info(h)
+        assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"])
+        check(torch_cuda, h, c, gi.activations(1, 4096, seed=11))
+
+
+def test_gemv_multi_with_larger_groups_falls_back_to_separate_launches(torch_cuda):
+    torch = torch_cuda
+    K = 1024
+    x_np = gi.activations(1, K, seed=12)
+    x = torch.from_numpy(x_np).cuda()
+    hs, cs = [], []
+    for i, N in enumerate((96, 200)):
+        W = gi.dense_weight(N, K, seed=100 + i)
+        hs.append(gq.gqsa_pack(W, 32, 4, 0.5))
+        cs.append(oracle.pack(W, 32, 4, sparsity=0.5))
+    for h in hs:
+        gq.gqsa_set_partition(h, 3, 4)
+    ys = gq.gqsa_gemv_multi(hs, x)
+    torch.cuda.synchronize()
+    for y, c in zip(ys, cs):
+        assert oracle.rel_error(y.cpu().numpy()[0], oracle.gemv(c, x_np, threads=4)[0]) <= TOL
+
+
 # ----------------------------------------------------------------------------- full sizes
 
 @pytest.mark.parametrize("idx", [0, 4, 6])

@@ -15,12 +15,16 @@ from oracle import layout
 
 
 def test_default_partition():
-    assert oracle.default_partition(0) == (1, 16)
-    assert oracle.default_partition(2048) == (2, 16)           # 32 blocks -> 2 workgroups of 16
-    assert oracle.default_partition(64 * 17) == (2, 16)
-    assert oracle.default_partition(524288) == (256, 16)       # 8192 blocks -> capped at 256 workgroups
-    assert oracle.default_partition(64 * 4096) == (256, 16)
-    assert oracle.default_partition(64 * 1000) == (63, 16)
+    assert oracle.default_partition(0) == (1, 1)
+    assert oracle.default_partition(2048) == (32, 1)            # 32 blocks -> one per workgroup
+    assert oracle.default_partition(64 * 17) == (17, 1)
+    assert oracle.default_partition(524288) == (256, 16)        # 8192 blocks: 32 per workgroup, 2 per wavefront
+    assert oracle.default_partition(64 * 4096) == (256, 8)      # 16 per workgroup -> 8 wavefronts of 2
+    assert oracle.default_partition(64 * 1000) == (256, 2)      # 4 (some 3) per workgroup
+    assert oracle.default_partition(64 * 2048) == (256, 4)
+    assert oracle.default_partition(64 * 1024, G=128) == (256, 4)   # heavy groups: one block per wavefront
+    assert oracle.default_partition(64 * 2048, G=64) == (256, 8)
+    assert oracle.default_partition(1409024) == (256, 16)       # 11008x4096 at S = 50 %
 
 
 def test_two_level_block_deal_by_hand():
@@ -66,10 +70,29 @@ def test_placement_three_workers_7_blocks_by_hand():
     assert (block[447], lane[447]) == (6, 63)
 
 
+def test_placement_with_capped_superblocks_by_hand():
+    # 32 code bytes per group: superblocks of at most 2 blocks -> 7 blocks = 2 + 2 + 2 + 1
+    assert layout.largest_superblock(8) == 4 and layout.largest_superblock(16) == 4
+    assert layout.largest_superblock(32) == 2 and layout.largest_superblock(64) == 1
+    block, lane, _, _ = layout.stream_placement(7, 1, 1, u_max=2)
+    assert (block[0], lane[0]) == (0, 0)
+    assert (block[1], lane[1]) == (1, 0)
+    assert (block[127], lane[127]) == (1, 63)
+    assert (block[128], lane[128]) == (2, 0)
+    assert (block[129], lane[129]) == (3, 0)
+    assert (block[383], lane[383]) == (5, 63)
+    assert (block[384], lane[384]) == (6, 0)
+    assert (block[447], lane[447]) == (6, 63)
+    # 64 code bytes per group: every block by itself -> stream order
+    block, lane, _, _ = layout.stream_placement(7, 1, 1, u_max=1)
+    assert np.array_equal(block, np.arange(448) // 64) and np.array_equal(lane, np.arange(448) % 64)
+
+
+@pytest.mark.parametrize("u_max", [4, 2, 1])
 @pytest.mark.parametrize("nblocks,n_wg,wpw", [(1, 1, 1), (5, 1, 16), (16, 1, 16), (37, 2, 8), (100, 7, 3),
                                                (9, 256, 16)])
-def test_placement_is_a_bijection(nblocks, n_wg, wpw):
-    block, lane, _, _ = layout.stream_placement(nblocks, n_wg, wpw)
+def test_placement_is_a_bijection(nblocks, n_wg, wpw, u_max):
+    block, lane, _, _ = layout.stream_placement(nblocks, n_wg, wpw, u_max)
     slot = block * 64 + lane
     assert np.array_equal(np.sort(slot), np.arange(nblocks * 64))
 
@@ -84,10 +107,22 @@ def hand_counts(nblocks, n_wg, wpw):
     return out
 
 
-def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw):
+def hand_superblocks(n_w, code_bytes):
+    """Superblock sizes of a run of n_w blocks, written out (4s, then 2s, then 1s, capped)."""
+    u_max = 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
+    sizes = []
+    left = n_w
+    for U in (4, 2, 1):
+        while U <= u_max and left >= U:
+            sizes.append(U)
+            left -= U
+    return sizes
+
+
+def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw, G=16):
     """Invert the layout with plain loops, walking workers / superblocks / lanes."""
-    G = 16
     cb = G * bits // 8
+    plane = min(16, cb)
     blk_bytes = (cb + 6) * 64
     nblocks = (nnzg + 63) // 64
     raw = np.frombuffer(blob, dtype=np.uint8)
@@ -100,33 +135,33 @@ def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw):
     b = 0
     counts = hand_counts(nblocks, n_wg, wpw)
     for w in range(n_wg * wpw):
-        n_w = counts[w]
-        sizes = [4] * (n_w // 4)
-        if n_w % 4 >= 2:
-            sizes.append(2)
-        if n_w % 2 == 1:
-            sizes.append(1)
-        for U in sizes:
+        for U in hand_superblocks(counts[w], cb):
             for p in range(64 * U):
                 blk = b + p % U
                 ln = p // U
                 base = blk * blk_bytes
-                cbytes = raw[base + ln * cb: base + (ln + 1) * cb]
+                # the lane's code string, plane by plane
+                cbytes = bytearray()
+                for k in range(cb // plane):
+                    o = base + k * 64 * plane + ln * plane
+                    cbytes += raw[o:o + plane].tobytes()
                 if bits == 4:
-                    for h in range(2):
-                        word = int.from_bytes(cbytes[4 * h:4 * h + 4].tobytes(), "little")
+                    for h in range(G // 8):
+                        word = int.from_bytes(cbytes[4 * h:4 * h + 4], "little")
                         for m in range(4):
                             codes[pos, 8 * h + 2 * m] = (word >> (4 * m)) & 0xF
                             codes[pos, 8 * h + 2 * m + 1] = (word >> (16 + 4 * m)) & 0xF
                 else:
-                    codes[pos] = cbytes
+                    codes[pos] = list(cbytes)
                 o = base + 64 * cb + ln * 4
                 sz = int.from_bytes(raw[o:o + 4].tobytes(), "little")
                 scales[pos] = sz & 0xFFFF
                 zeros[pos] = sz >> 16
                 o = base + 64 * cb + 256 + ln * 2
                 ix = int.from_bytes(raw[o:o + 2].tobytes(), "little")
-                cols[pos] = ix >> 4
+                slot = ix >> 4
+                assert slot % (G // 16) == 0
+                cols[pos] = slot // (G // 16)
                 heads[pos] = bool(ix & 1)
                 assert ix & 0xE == 0
                 pos += 1
@@ -135,27 +170,27 @@ def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw):
     return codes, scales, zeros, cols, heads
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 @pytest.mark.parametrize("n_wg,wpw", [(1, 1), (3, 1), (1, 16), (3, 16), (5, 4), (2, 7)])
-def test_blob_decodes_back_to_canonical(bits, n_wg, wpw):
+def test_blob_decodes_back_to_canonical(bits, G, n_wg, wpw):
     n_waves = n_wg * wpw
-    N, K = 40, 512
+    N, K = 40, 512 * (G // 16)
     W = gi.dense_weight(N, K, seed=41)
-    keep = gi.imbalanced_keep_counts(N, K // 16, seed=41)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=41)
     keep[5] = 0
     keep[N - 1] = 0
-    c = oracle.pack(W, bits=bits, keep_per_row=keep)
+    c = oracle.pack(W, G=G, bits=bits, keep_per_row=keep)
     blob = oracle.device_blob(c, n_wg, wpw)
     assert len(blob) % 256 == 0
-    codes, scales, zeros, cols, heads = decode_blob(blob, N, K, bits, c.nnzg, n_wg, wpw)
+    codes, scales, zeros, cols, heads = decode_blob(blob, N, K, bits, c.nnzg, n_wg, wpw, G)
     nn = c.nnzg
     if bits == 4:
-        v = np.asarray(c.values).reshape(nn, 8)
-        ref = np.empty((nn, 16), dtype=np.int64)
+        v = np.asarray(c.values).reshape(nn, G // 2)
+        ref = np.empty((nn, G), dtype=np.int64)
         ref[:, 0::2] = v & 0xF
         ref[:, 1::2] = v >> 4
     else:
-        ref = np.asarray(c.values).reshape(nn, 16).astype(np.int64)
+        ref = np.asarray(c.values).reshape(nn, G).astype(np.int64)
     assert np.array_equal(codes[:nn], ref)
     assert np.array_equal(scales[:nn], c.scales) and np.array_equal(zeros[:nn], c.zeros)
     assert np.array_equal(cols[:nn], c.groups)
@@ -169,7 +204,7 @@ def test_blob_decodes_back_to_canonical(bits, n_wg, wpw):
     assert np.array_equal(heads[:nn], exp_heads)
     # side tables
     nblocks = (nn + 63) // 64
-    cb = 16 * bits // 8
+    cb = G * bits // 8
     off = (nblocks * (cb + 6) * 64 + 255) // 256 * 256
     wave_info = np.frombuffer(blob, dtype="<i4", count=4 * n_waves, offset=off).reshape(n_waves, 4)
     # brute force: the row and the worker of every stored group

@@ -39,7 +39,7 @@ def test_tiny_config_balanced(bits, sparsity):
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == c.nnzg
-    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg)
+    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, 16)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
 
 
@@ -57,6 +57,37 @@ def test_outliers_and_imbalanced_rows(bits):
             info = gq.gqsa_info(h)
             assert (info["n_workgroups"], info["waves_per_workgroup"]) == part
         assert_same_blob(h, c)
+
+
+@pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+def test_other_group_sizes(bits, G):
+    """Group sizes 32, 64, 128: canonical arrays and the device image (code planes, capped
+    superblocks, index word = first 16-element slot) against the oracle, several partitions."""
+    N, K = 150, 2048
+    W = gi.dense_weight(N, K, seed=91)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=91)
+    h = gq.gqsa_pack_rows(W, keep, G, bits)
+    c = oracle.pack(W, G, bits, keep_per_row=keep)
+    assert_same_canonical(h, c)
+    info = gq.gqsa_info(h)
+    assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(N, K, G, bits, c.nnzg, 1)
+    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, G)
+    for part in (None, (1, 1), (3, 1), (5, 3), (1, 16), (17, 2), (40, 16)):
+        if part is not None:
+            gq.gqsa_set_partition(h, *part)
+        assert_same_blob(h, c)
+    hb = gq.gqsa_pack(W, G, bits, 0.5)
+    cb = oracle.pack(W, G, bits, sparsity=0.5)
+    assert_same_canonical(hb, cb)
+    assert_same_blob(hb, cb)
+
+
+def test_unsupported_group_sizes_are_refused():
+    W = np.zeros((4, 256), dtype=np.float32)
+    for G, bits in ((8, 4), (48, 4), (256, 4), (128, 8)):
+        with pytest.raises(gq.GqsaError) as e:
+            gq.gqsa_pack(W, G, bits, 0.5)
+        assert e.value.status == 3
 
 
 def test_planted_ties_and_constant_groups():
