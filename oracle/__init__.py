@@ -45,7 +45,7 @@ def _load():
     lib.gqsa_oracle_count.restype = C.c_int64
     lib.gqsa_oracle_count.argtypes = [i32p, C.c_int64]
     lib.gqsa_oracle_pack.restype = C.c_int
-    lib.gqsa_oracle_pack.argtypes = [f32p, C.c_int64, C.c_int64, C.c_int, C.c_int, i32p,
+    lib.gqsa_oracle_pack.argtypes = [f32p, C.c_int64, C.c_int64, C.c_int, C.c_int, i32p, f32p,
                                      i32p, i32p, u8p, u16p, u16p]
     lib.gqsa_oracle_densify.restype = C.c_int
     lib.gqsa_oracle_densify.argtypes = [i32p, i32p, u8p, u16p, u16p, C.c_int64, C.c_int64,
@@ -96,8 +96,9 @@ def keep_counts(N: int, K: int, G: int, sparsity: float) -> np.ndarray:
 
 
 def pack(W: np.ndarray, G: int = 16, bits: int = 4, sparsity: float | None = None,
-         keep_per_row: np.ndarray | None = None) -> Canonical:
-    """Group-prune and quantise dense fp32 W[N,K] into the canonical BSR arrays."""
+         keep_per_row: np.ndarray | None = None, hinv_diag: np.ndarray | None = None) -> Canonical:
+    """Group-prune and quantise dense fp32 W[N,K] into the canonical BSR arrays.
+    hinv_diag: diag(H^-1) of Eq. 4 (K positive numbers); None = magnitude saliency."""
     lib = _load()
     W = np.ascontiguousarray(W, dtype=np.float32)
     N, K = W.shape
@@ -114,7 +115,13 @@ def pack(W: np.ndarray, G: int = 16, bits: int = 4, sparsity: float | None = Non
     values = np.zeros(max(nnzg * G * bits // 8, 1), dtype=np.uint8)
     scales = np.zeros(max(nnzg, 1), dtype=np.uint16)
     zeros = np.zeros(max(nnzg, 1), dtype=np.uint16)
-    rc = lib.gqsa_oracle_pack(_ptr(W, C.c_float), N, K, G, bits, _ptr(keep, C.c_int32),
+    dptr = None
+    if hinv_diag is not None:
+        hinv_diag = np.ascontiguousarray(hinv_diag, dtype=np.float32)
+        if hinv_diag.shape != (K,):
+            raise ValueError("hinv_diag must have K entries")
+        dptr = _ptr(hinv_diag, C.c_float)
+    rc = lib.gqsa_oracle_pack(_ptr(W, C.c_float), N, K, G, bits, _ptr(keep, C.c_int32), dptr,
                               _ptr(rowIndex, C.c_int32), _ptr(groups, C.c_int32),
                               _ptr(values, C.c_uint8), _ptr(scales, C.c_uint16),
                               _ptr(zeros, C.c_uint16))

@@ -27,9 +27,13 @@
  * group, for every element, accumulate (q - z) * s * x in float64.
  *
  * Readings of points the paper leaves open (all listed in the design notes):
- *   - saliency is the group's sum of squares (same ordering as its L2 norm and
- *     as the mean of squared magnitudes); the Hessian metric of Eq. 4 needs
- *     calibration activations that do not exist here;
+ *   - saliency of a weight (Sec. 3.1, Eq. 4): w^2 / [H^-1]_kk^2 with H the layer's
+ *     Hessian over its K inputs -- so the caller hands in d = diag(H^-1), one
+ *     positive number per input column (building H needs calibration
+ *     activations, which do not exist here); the group's saliency is the sum of
+ *     its members' (same ordering as the average of Fig. 3).  Without d the
+ *     saliency is the group's sum of squares (d = 1: same ordering as its L2
+ *     norm and as the mean of squared magnitudes);
  *   - round() is round-half-to-even;
  *   - the scale is rounded to fp16 first and that stored value is the one the
  *     zero-point and the codes are computed with; a scale below 2^-14 (constant
@@ -127,14 +131,16 @@ static int sal_cmp(const void* pa, const void* pb)
     return (a->col > b->col) - (a->col < b->col);
 }
 
-/* Fig. 3 / Sec. 3.2: per-group saliency of one row, here the sum of squares of
- * the group's G weights, accumulated in float64 in index order.              */
-static void row_saliency(const float* wrow, int64_t kg, int G, sal_entry* out)
+/* Fig. 3 / Sec. 3.2 with Eq. 4: per-group saliency of one row -- the sum over the
+ * group's G weights of (w / d_k)^2, d = diag(H^-1) of the layer (NULL: d = 1, the
+ * sum of squares), accumulated in float64 in index order.                     */
+static void row_saliency(const float* wrow, const float* hinv_diag, int64_t kg, int G, sal_entry* out)
 {
     for (int64_t c = 0; c < kg; ++c) {
         double acc = 0.0;
         for (int j = 0; j < G; ++j) {
             double w = (double)wrow[c * G + j];
+            if (hinv_diag) w = w / (double)hinv_diag[c * G + j];
             acc += w * w;
         }
         out[c].sal = acc;
@@ -194,10 +200,11 @@ int64_t gqsa_oracle_count(const int32_t* keep_per_row, int64_t N)
  *   rowIndex int32[N+1], groups int32[nnzg], values uint8[nnzg*G*bits/8],
  *   scales/zeros uint16[nnzg] (fp16 bit patterns).
  * keep_per_row[n] = number of groups row n keeps (the most salient ones).
+ * hinv_diag: K positive finite numbers, diag(H^-1) of Eq. 4, or NULL.
  * Returns 0, or a negative number for an argument the definition excludes.
  */
 int gqsa_oracle_pack(const float* W, int64_t N, int64_t K, int G, int bits,
-                     const int32_t* keep_per_row,
+                     const int32_t* keep_per_row, const float* hinv_diag,
                      int32_t* rowIndex, int32_t* groups, uint8_t* values,
                      uint16_t* scales, uint16_t* zeros)
 {
@@ -206,6 +213,9 @@ int gqsa_oracle_pack(const float* W, int64_t N, int64_t K, int G, int bits,
     if (bits != 4 && bits != 8) return -3;
     if (bits == 4 && (G % 2) != 0) return -3;
     const int64_t kg = K / G;
+    if (hinv_diag)
+        for (int64_t k = 0; k < K; ++k)
+            if (!(hinv_diag[k] > 0.0f) || !isfinite(hinv_diag[k])) return -6;
     sal_entry* ent = (sal_entry*)malloc(sizeof(sal_entry) * (size_t)kg);
     uint8_t* keepmask = (uint8_t*)malloc((size_t)kg);
     uint8_t* codes = (uint8_t*)malloc((size_t)G);
@@ -217,7 +227,7 @@ int gqsa_oracle_pack(const float* W, int64_t N, int64_t K, int G, int bits,
         const float* wrow = W + n * K;
         int64_t keep = keep_per_row[n];
         if (keep < 0 || keep > kg) { free(ent); free(keepmask); free(codes); return -5; }
-        row_saliency(wrow, kg, G, ent);
+        row_saliency(wrow, hinv_diag, kg, G, ent);
         qsort(ent, (size_t)kg, sizeof(sal_entry), sal_cmp);
         /* the first kg-keep entries (least salient) are pruned */
         memset(keepmask, 0, (size_t)kg);

@@ -224,6 +224,53 @@ def test_pruning_ties_lower_column_pruned_first():
     assert list(c.groups[c.rowIndex[2]:c.rowIndex[3]]) == [0, 1, 2, 3, 4, 5]
 
 
+def test_hessian_saliency_matches_brute_force():
+    """Eq. 4: saliency of a weight = w^2 / d_k^2, d = diag(H^-1); a group's = the sum over it."""
+    rng = np.random.default_rng(21)
+    N, K, G = 24, 192, 16
+    W = rng.standard_normal((N, K)).astype(np.float32)
+    d = np.exp(rng.standard_normal(K)).astype(np.float32)          # positive, spread over ~2 decades
+    c = oracle.pack(W, G=G, bits=4, sparsity=0.5, hinv_diag=d)
+    sal = ((W.astype(np.float64) / d.astype(np.float64)) ** 2).reshape(N, K // G, G).sum(-1)
+    for n in range(N):
+        kept = np.sort(np.argsort(sal[n], kind="stable")[K // G // 2:])
+        assert np.array_equal(c.groups[c.rowIndex[n]:c.rowIndex[n + 1]], kept)
+    # the selection differs from plain magnitude pruning here, the quantiser does not: every
+    # stored group carries the codes magnitude packing gives that same group
+    m = oracle.pack(W, G=G, bits=4, sparsity=0.0)
+    differs = False
+    for n in range(N):
+        cols = c.groups[c.rowIndex[n]:c.rowIndex[n + 1]]
+        mag = np.sort(np.argsort((W[n].astype(np.float64) ** 2).reshape(-1, G).sum(-1), kind="stable")[K // G // 2:])
+        differs |= not np.array_equal(cols, mag)
+        for i, col in enumerate(cols):
+            g, gm = c.rowIndex[n] + i, m.rowIndex[n] + col
+            assert np.array_equal(c.values[8 * g:8 * g + 8], m.values[8 * gm:8 * gm + 8])
+            assert c.scales[g] == m.scales[gm] and c.zeros[g] == m.zeros[gm]
+    assert differs
+
+
+def test_hessian_saliency_special_cases():
+    W = gi.dense_weight(32, 256, seed=22)
+    base = oracle.pack(W, sparsity=0.5)
+    for const in (1.0, 0.5, 4.0):          # a constant d (exact powers of two) changes nothing
+        c = oracle.pack(W, sparsity=0.5, hinv_diag=np.full(256, const, dtype=np.float32))
+        assert np.array_equal(c.groups, base.groups) and np.array_equal(c.values, base.values)
+    # a huge d on some input columns makes their groups the first to go, a tiny d the last
+    d = np.ones(256, dtype=np.float32)
+    d[0:16] = 1e6          # group-column 0: irrelevant inputs
+    d[32:48] = 1e-6        # group-column 2: inputs that matter most
+    c = oracle.pack(W, sparsity=0.5, hinv_diag=d)
+    for n in range(32):
+        cols = list(c.groups[c.rowIndex[n]:c.rowIndex[n + 1]])
+        assert 0 not in cols and 2 in cols
+    for bad in (0.0, -1.0, np.inf, np.nan):
+        d = np.ones(256, dtype=np.float32)
+        d[7] = bad
+        with pytest.raises(ValueError):
+            oracle.pack(W, sparsity=0.5, hinv_diag=d)
+
+
 def test_sparsity_extremes():
     W = gi.dense_weight(16, 128, seed=4)
     c0 = oracle.pack(W, sparsity=0.0)
