@@ -304,6 +304,16 @@ def main():
             out["group_size_sweep"] = time_variants(shapes7[:1] + shapes7[1:2],
                                                     [(4, sp, G) for G in (16, 32, 64, 128) for sp in (0.0, 0.5)], 2)
 
+        # the offline step (host): prune + quantise + build the device image, 4096x4096
+        Wp = gi.dense_weight_chunked(4096, 4096, seed=gi.config_seed(2, 0), workers=workers)
+        dp = np.exp(np.random.default_rng(1).standard_normal(4096)).astype(np.float32)
+        t0 = time.time(); gq.gqsa_free(gq.gqsa_pack(Wp, 16, 4, 0.5)); t_mag = time.time() - t0
+        t0 = time.time(); gq.gqsa_free(gq.gqsa_pack_hessian(Wp, dp, 16, 4, 0.5)); t_hes = time.time() - t0
+        out["pack_host_4096x4096"] = {"magnitude_s": round(t_mag, 3), "hessian_metric_s": round(t_hes, 3),
+                                      "Mweights_per_s": round(4096 * 4096 / t_mag / 1e6, 1),
+                                      "threads": min(16, os.cpu_count() or 1)}
+        del Wp
+
         # small batches on the 4096x4096 shape (weights decoded once for up to 8 rows per launch)
         hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]
         small_batch = []
@@ -366,6 +376,9 @@ def main():
                 oracle.gemv(c, xh[c.K], threads=threads)
             reps += 1
         dt = time.time() - t0
+        t0 = time.time()
+        oracle.pack(gi.dense_weight_chunked(4096, 4096, seed=gi.config_seed(2, 0), workers=workers), 16, 4, sparsity=0.5)
+        t_opack = time.time() - t0
         per_shape_cpu = []
         for c in (canon[0], canon[4], canon[6]):         # one call per shape: 1 thread and all of them
             def median_ms(threads, reps):
@@ -385,6 +398,7 @@ def main():
             "sample": f"{reps} passes over one layer set (7 GEMVs, same shapes and sparsity) in {dt:.1f} s; "
                       f"{dt / reps * 1e3 / calls_per_step:.2f} ms per call",
             "per_shape": per_shape_cpu,
+            "pack_4096x4096_s_1_thread": round(t_opack, 3),
         }
 
     print(json.dumps(out))

@@ -43,7 +43,8 @@ typedef enum {
     GQSA_ERR_ALLOC = 5,        /* host allocation failed */
     GQSA_ERR_HIP = 6,          /* a HIP runtime call failed (no device, launch error, ...) */
     GQSA_ERR_BUFSIZE = 7,      /* caller buffer smaller than required */
-    GQSA_ERR_ALIGN = 8         /* device pointer not 16-byte aligned */
+    GQSA_ERR_ALIGN = 8,        /* device pointer not 16-byte aligned */
+    GQSA_ERR_IO = 9            /* file could not be opened, read or written (also: truncated) */
 } gqsa_status_t;
 
 typedef struct {
@@ -85,6 +86,17 @@ gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bi
  * example of Sec. 3.2 keeps 1, 2, 0, 1 groups).  keep_per_row [host] int32[N]. */
 gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, int bits,
                              const int32_t* keep_per_row, gqsa_handle_t* out);
+
+/*
+ * Same as gqsa_pack, with the paper's Hessian metric deciding which groups go (Sec. 3.1, Eq. 4):
+ * the saliency of a weight is w^2 / d_k^2, d = diag(H^-1) of the layer's Hessian over its K
+ * inputs, and a group's saliency is the sum over its members (Fig. 3 averages, same order).
+ *   hinv_diag [host] fp32[K], every entry finite and > 0 (GQSA_ERR_RANGE otherwise)
+ * The Hessian itself comes from calibration activations and is the caller's business; d = 1
+ * everywhere gives gqsa_pack.  Quantisation of the kept groups does not depend on d.
+ */
+gqsa_status_t gqsa_pack_hessian(const float* W_host, int64_t N, int64_t K, int G, int bits,
+                                double sparsity, const float* hinv_diag, gqsa_handle_t* out);
 
 /*
  * Build a handle from existing canonical arrays (the BSR listing of Sec. 3.2 plus the
@@ -148,6 +160,16 @@ gqsa_status_t gqsa_export(gqsa_handle_t h, int32_t* rowIndex, int32_t* groups, u
 
 /* Copy the exact bytes of the device image (host copy) into host_buf; bytes >= device_bytes. */
 gqsa_status_t gqsa_export_device_blob(gqsa_handle_t h, void* host_buf, size_t bytes);
+
+/*
+ * The canonical arrays (the Sec. 3.2 listing plus scales and zeros) to and from a file: a 48-byte
+ * header ("GQSABSR1", N, K, G, bits, nnz_groups, reserved; little-endian) followed by rowIndex,
+ * groups, values, scales, zeros.  gqsa_load checks the file like gqsa_import checks its arrays
+ * (GQSA_ERR_SHAPE for an inconsistent or foreign file, GQSA_ERR_IO for one it cannot read to
+ * the end) and chooses the default partition.  Host only.
+ */
+gqsa_status_t gqsa_save(gqsa_handle_t h, const char* path);
+gqsa_status_t gqsa_load(const char* path, gqsa_handle_t* out);
 
 void gqsa_free(gqsa_handle_t h);
 

@@ -17,8 +17,11 @@ from .binding import (  # noqa: F401
     gqsa_import,
     gqsa_info,
     gqsa_launch_floor,
+    gqsa_load,
     gqsa_pack,
+    gqsa_pack_hessian,
     gqsa_pack_rows,
+    gqsa_save,
     gqsa_set_partition,
     gqsa_status_string,
     gqsa_stream_read,

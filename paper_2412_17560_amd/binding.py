@@ -49,6 +49,12 @@ def _lib():
     lib.gqsa_pack.argtypes = [vp, i64, i64, i32, i32, C.c_double, C.POINTER(vp)]
     lib.gqsa_pack_rows.restype = C.c_int
     lib.gqsa_pack_rows.argtypes = [vp, i64, i64, i32, i32, vp, C.POINTER(vp)]
+    lib.gqsa_pack_hessian.restype = C.c_int
+    lib.gqsa_pack_hessian.argtypes = [vp, i64, i64, i32, i32, C.c_double, vp, C.POINTER(vp)]
+    lib.gqsa_save.restype = C.c_int
+    lib.gqsa_save.argtypes = [vp, C.c_char_p]
+    lib.gqsa_load.restype = C.c_int
+    lib.gqsa_load.argtypes = [C.c_char_p, C.POINTER(vp)]
     lib.gqsa_import.restype = C.c_int
     lib.gqsa_import.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, C.POINTER(vp)]
     lib.gqsa_set_partition.restype = C.c_int
@@ -116,6 +122,28 @@ def gqsa_pack(W: np.ndarray, G: int = 16, bits: int = 4, sparsity: float = 0.5) 
     out = C.c_void_p()
     _check(_lib().gqsa_pack(_np_ptr(W), W.shape[0], W.shape[1], G, bits, float(sparsity),
                             C.byref(out)), "gqsa_pack")
+    return GqsaHandle(out.value)
+
+
+def gqsa_pack_hessian(W: np.ndarray, hinv_diag: np.ndarray, G: int = 16, bits: int = 4,
+                      sparsity: float = 0.5) -> GqsaHandle:
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    d = np.ascontiguousarray(hinv_diag, dtype=np.float32)
+    if W.ndim != 2 or d.shape != (W.shape[1],):
+        raise ValueError("W must be [N, K] and hinv_diag [K]")
+    out = C.c_void_p()
+    _check(_lib().gqsa_pack_hessian(_np_ptr(W), W.shape[0], W.shape[1], G, bits, float(sparsity),
+                                    _np_ptr(d), C.byref(out)), "gqsa_pack_hessian")
+    return GqsaHandle(out.value)
+
+
+def gqsa_save(h: GqsaHandle, path: str) -> None:
+    _check(_lib().gqsa_save(h.ptr, os.fsencode(path)), "gqsa_save")
+
+
+def gqsa_load(path: str) -> GqsaHandle:
+    out = C.c_void_p()
+    _check(_lib().gqsa_load(os.fsencode(path), C.byref(out)), "gqsa_load")
     return GqsaHandle(out.value)
 
 

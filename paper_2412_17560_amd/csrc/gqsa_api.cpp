@@ -1,8 +1,11 @@
 // extern "C" surface of libgqsa: argument checking, handle life-cycle, export/import.
 // The arithmetic lives in gqsa_pack.cpp (host) and gqsa_gemv.hip (device).
+#include <climits>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "gqsa_internal.hpp"
 
@@ -49,7 +52,7 @@ gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bi
     if (!(sparsity >= 0.0 && sparsity <= 1.0)) return GQSA_ERR_RANGE;
     gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
     if (!m) return GQSA_ERR_ALLOC;
-    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, nullptr, sparsity, m), out);
+    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, nullptr, sparsity, nullptr, m), out);
 }
 
 gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, int bits,
@@ -60,7 +63,19 @@ gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, i
     if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
     gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
     if (!m) return GQSA_ERR_ALLOC;
-    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, keep_per_row, 0.0, m), out);
+    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, keep_per_row, 0.0, nullptr, m), out);
+}
+
+gqsa_status_t gqsa_pack_hessian(const float* W_host, int64_t N, int64_t K, int G, int bits,
+                                double sparsity, const float* hinv_diag, gqsa_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!W_host || !out || !hinv_diag) return GQSA_ERR_NULL;
+    if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
+    if (!(sparsity >= 0.0 && sparsity <= 1.0)) return GQSA_ERR_RANGE;
+    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
+    if (!m) return GQSA_ERR_ALLOC;
+    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, nullptr, sparsity, hinv_diag, m), out);
 }
 
 gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const uint8_t* values,
@@ -197,6 +212,85 @@ gqsa_status_t gqsa_export_device_blob(gqsa_handle_t h, void* host_buf, size_t by
     return GQSA_OK;
 }
 
+namespace {
+
+// File image of a packed matrix: a 48-byte header, then the canonical arrays, little-endian.
+struct FileHeader {
+    char magic[8];        // "GQSABSR1"
+    int64_t N, K;
+    int32_t G, bits;
+    int64_t nnz_groups;
+    int64_t reserved;
+};
+const char kMagic[8] = {'G', 'Q', 'S', 'A', 'B', 'S', 'R', '1'};
+
+struct FileCloser {
+    std::FILE* f;
+    ~FileCloser() { if (f) std::fclose(f); }
+};
+
+}  // namespace
+
+gqsa_status_t gqsa_save(gqsa_handle_t h, const char* path)
+{
+    if (!h || !path) return GQSA_ERR_NULL;
+    FileCloser file{std::fopen(path, "wb")};
+    if (!file.f) return GQSA_ERR_IO;
+    FileHeader hd{};
+    std::memcpy(hd.magic, kMagic, 8);
+    hd.N = h->N; hd.K = h->K; hd.G = h->G; hd.bits = h->bits; hd.nnz_groups = h->nnzg();
+    bool ok = std::fwrite(&hd, sizeof(hd), 1, file.f) == 1;
+    auto put = [&](const void* p, size_t bytes) {
+        if (ok && bytes) ok = std::fwrite(p, 1, bytes, file.f) == bytes;
+    };
+    put(h->rowIndex.data(), h->rowIndex.size() * 4);
+    put(h->groups.data(), h->groups.size() * 4);
+    put(h->values.data(), h->values.size());
+    put(h->scales.data(), h->scales.size() * 2);
+    put(h->zeros.data(), h->zeros.size() * 2);
+    if (ok) ok = std::fflush(file.f) == 0;
+    return ok ? GQSA_OK : GQSA_ERR_IO;
+}
+
+gqsa_status_t gqsa_load(const char* path, gqsa_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!path || !out) return GQSA_ERR_NULL;
+    FileCloser file{std::fopen(path, "rb")};
+    if (!file.f) return GQSA_ERR_IO;
+    FileHeader hd{};
+    if (std::fread(&hd, sizeof(hd), 1, file.f) != 1) return GQSA_ERR_IO;
+    if (std::memcmp(hd.magic, kMagic, 8) != 0) return GQSA_ERR_SHAPE;
+    if (gqsa_status_t st = check_format(hd.N, hd.K, hd.G, hd.bits)) return st;
+    if (hd.nnz_groups < 0 || hd.nnz_groups > hd.N * (hd.K / hd.G) || hd.nnz_groups > INT32_MAX)
+        return GQSA_ERR_SHAPE;
+    std::vector<int32_t> rowIndex, groups;
+    std::vector<uint8_t> values;
+    std::vector<uint16_t> scales, zeros;
+    try {
+        rowIndex.resize(static_cast<size_t>(hd.N) + 1);
+        groups.resize(static_cast<size_t>(hd.nnz_groups));
+        values.resize(static_cast<size_t>(hd.nnz_groups) * (hd.G * hd.bits / 8));
+        scales.resize(static_cast<size_t>(hd.nnz_groups));
+        zeros.resize(static_cast<size_t>(hd.nnz_groups));
+    } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
+    bool ok = true;
+    auto get = [&](void* p, size_t bytes) {
+        if (ok && bytes) ok = std::fread(p, 1, bytes, file.f) == bytes;
+    };
+    get(rowIndex.data(), rowIndex.size() * 4);
+    get(groups.data(), groups.size() * 4);
+    get(values.data(), values.size());
+    get(scales.data(), scales.size() * 2);
+    get(zeros.data(), zeros.size() * 2);
+    if (!ok) return GQSA_ERR_IO;                             // truncated
+    if (std::fgetc(file.f) != EOF) return GQSA_ERR_SHAPE;     // trailing bytes
+    if (rowIndex[static_cast<size_t>(hd.N)] != hd.nnz_groups) return GQSA_ERR_SHAPE;
+    // the same consistency checks as for arrays handed in directly
+    return gqsa_import(rowIndex.data(), groups.data(), values.data(), scales.data(), zeros.data(), hd.N, hd.K,
+                       hd.G, hd.bits, out);
+}
+
 void gqsa_free(gqsa_handle_t h)
 {
     if (!h) return;
@@ -216,6 +310,7 @@ const char* gqsa_status_string(gqsa_status_t s)
         case GQSA_ERR_HIP: return "HIP runtime error";
         case GQSA_ERR_BUFSIZE: return "buffer too small";
         case GQSA_ERR_ALIGN: return "misaligned device pointer";
+        case GQSA_ERR_IO: return "file could not be opened, read or written";
     }
     return "unknown status";
 }

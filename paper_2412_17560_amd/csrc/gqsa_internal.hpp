@@ -70,7 +70,8 @@ namespace gqsa {
 
 // host packer (gqsa_pack.cpp)
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
-                         const int32_t* keep_per_row, double sparsity, gqsa_matrix* m);
+                         const int32_t* keep_per_row, double sparsity, const float* hinv_diag,
+                         gqsa_matrix* m);
 void default_partition(int64_t n_blocks, int G, int* n_workgroups, int* waves_per_workgroup);
 gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup);
 

@@ -67,15 +67,25 @@ void quantise_group(const float* w, int G, int bits, uint8_t* q_out, uint16_t* s
 }
 
 // Kept group-columns of one row, ascending.  Order of pruning: ascending saliency, and
-// among equal saliencies the lower column goes first.
-bool select_row(const float* wrow, int64_t kg, int G, int64_t keep, std::vector<double>& sal,
-                std::vector<int32_t>& order, std::vector<int32_t>& kept)
+// among equal saliencies the lower column goes first.  Saliency of a weight (Sec. 3.1, Eq. 4):
+// w^2 / d_k^2 with d = diag(H^-1) of the layer's Hessian, handed in by the caller (nullptr:
+// d = 1, the plain sum of squares); a group's saliency is the sum over its members.
+bool select_row(const float* wrow, const float* hinv_diag, int64_t kg, int G, int64_t keep,
+                std::vector<double>& sal, std::vector<int32_t>& order, std::vector<int32_t>& kept)
 {
     bool finite = true;
     for (int64_t c = 0; c < kg; ++c) {
         double acc = 0.0;
         const float* p = wrow + c * G;
-        for (int j = 0; j < G; ++j) acc += static_cast<double>(p[j]) * static_cast<double>(p[j]);
+        if (hinv_diag) {
+            const float* d = hinv_diag + c * G;
+            for (int j = 0; j < G; ++j) {
+                const double t = static_cast<double>(p[j]) / static_cast<double>(d[j]);
+                acc += t * t;
+            }
+        } else {
+            for (int j = 0; j < G; ++j) acc += static_cast<double>(p[j]) * static_cast<double>(p[j]);
+        }
         sal[c] = acc;
         finite &= std::isfinite(acc);
     }
@@ -102,8 +112,12 @@ int64_t balanced_keep(int64_t kg, double sparsity)
 }  // namespace
 
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
-                         const int32_t* keep_per_row, double sparsity, gqsa_matrix* m)
+                         const int32_t* keep_per_row, double sparsity, const float* hinv_diag,
+                         gqsa_matrix* m)
 {
+    if (hinv_diag)
+        for (int64_t k = 0; k < K; ++k)
+            if (!(hinv_diag[k] > 0.0f) || !std::isfinite(hinv_diag[k])) return GQSA_ERR_RANGE;
     const int64_t kg = K / G;
     const int cb = G * bits / 8;
     m->N = N; m->K = K; m->G = G; m->bits = bits;
@@ -145,7 +159,7 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                 const float* wrow = W + n * K;
                 const int64_t g0 = m->rowIndex[n];
                 const int64_t keep = m->rowIndex[n + 1] - g0;
-                if (!select_row(wrow, kg, G, keep, sal, order, kept)) { bad = true; continue; }
+                if (!select_row(wrow, hinv_diag, kg, G, keep, sal, order, kept)) { bad = true; continue; }
                 for (int64_t i = 0; i < keep; ++i) {
                     const int64_t g = g0 + i;
                     const int32_t c = kept[i];

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert gq.gqsa_status_string(0) == "ok"
-    assert len({gq.gqsa_status_string(s) for s in range(9)}) == 9
+    assert len({gq.gqsa_status_string(s) for s in range(10)}) == 10
 
 
 def status_of(fn, *args, **kw):
@@ -138,3 +138,57 @@ def test_info_fields():
     assert info["n_empty_rows"] == int((keep == 0).sum())
     assert info["on_device"] == 0
     assert info["algorithmic_bytes"] == nnz * 22 + 101 * 4 + (512 + 100) * 2
+
+
+def test_pack_hessian_argument_checks():
+    W = np.ones((4, 64), dtype=np.float32)
+    d = np.ones(64, dtype=np.float32)
+    for bad in (0.0, -2.0, np.inf, np.nan):
+        db = d.copy()
+        db[5] = bad
+        assert status_of(gq.gqsa_pack_hessian, W, db, 16, 4, 0.5) == 4
+    assert status_of(gq.gqsa_pack_hessian, W, d, 16, 4, 1.5) == 4
+    assert status_of(gq.gqsa_pack_hessian, W, d, 24, 4, 0.5) == 3
+    lib = C.CDLL(gq.library_path())
+    lib.gqsa_pack_hessian.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_double,
+                                      C.c_void_p, C.c_void_p]
+    out = C.c_void_p()
+    assert lib.gqsa_pack_hessian(C.c_void_p(W.ctypes.data), 4, 64, 16, 4, 0.5, None, C.byref(out)) == 1
+
+
+def test_save_and_load_round_trip_and_damaged_files(tmp_path):
+    W = gi.dense_weight(50, 512, seed=3)
+    keep = gi.imbalanced_keep_counts(50, 512 // 32, seed=3)
+    h = gq.gqsa_pack_rows(W, keep, 32, 4)
+    path = str(tmp_path / "m.gqsa")
+    gq.gqsa_save(h, path)
+    e = gq.gqsa_export(h)
+    assert os.path.getsize(path) == 48 + 51 * 4 + e["groups"].size * 4 + e["values"].size + e["groups"].size * 4
+    h2 = gq.gqsa_load(path)
+    e2 = gq.gqsa_export(h2)
+    for k in e:
+        assert np.array_equal(e[k], e2[k]), k
+    i1, i2 = gq.gqsa_info(h), gq.gqsa_info(h2)
+    assert {k: i1[k] for k in ("N", "K", "G", "bits", "nnz_groups")} == {k: i2[k] for k in ("N", "K", "G", "bits", "nnz_groups")}
+    assert gq.gqsa_export_device_blob(h) == gq.gqsa_export_device_blob(h2)
+    # an empty matrix goes through too
+    h0 = gq.gqsa_pack(W, 16, 8, 1.0)
+    gq.gqsa_save(h0, path)
+    assert gq.gqsa_info(gq.gqsa_load(path))["nnz_groups"] == 0
+    # damaged files are refused with a status, never read past their end
+    gq.gqsa_save(h, path)
+    raw = open(path, "rb").read()
+    cases = {"truncated": (raw[:len(raw) - 7], 9), "header only": (raw[:48], 9), "short header": (raw[:20], 9),
+             "foreign": (b"NOTGQSA!" + raw[8:], 2), "trailing": (raw + b"x", 2),
+             "bad group size": (raw[:24] + (17).to_bytes(4, "little") + raw[28:], 3),
+             "count too large": (raw[:32] + (1 << 40).to_bytes(8, "little") + raw[40:], 2)}
+    descending = bytearray(raw)
+    off = 48 + 51 * 4                       # first two group-columns of row 0 swapped
+    descending[off:off + 4], descending[off + 4:off + 8] = raw[off + 4:off + 8], raw[off:off + 4]
+    if keep[0] >= 2:
+        cases["descending columns"] = (bytes(descending), 2)
+    for name, (data, status) in cases.items():
+        open(path, "wb").write(data)
+        assert status_of(gq.gqsa_load, path) == status, name
+    assert status_of(gq.gqsa_load, str(tmp_path / "missing.gqsa")) == 9
+    assert status_of(gq.gqsa_save, h, str(tmp_path / "no_such_dir" / "m.gqsa")) == 9

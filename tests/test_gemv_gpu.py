@@ -349,6 +349,23 @@ def test_gemv_multi_with_larger_groups_falls_back_to_separate_launches(torch_cud
         assert oracle.rel_error(y.cpu().numpy()[0], oracle.gemv(c, x_np, threads=4)[0]) <= TOL
 
 
+def test_hessian_pruned_and_reloaded_matrices_multiply(torch_cuda, tmp_path):
+    """A matrix pruned by the Hessian metric (Eq. 4) against the oracle, and the same matrix after
+    a trip through a file: identical output bits."""
+    N, K = 300, 4096
+    W = gi.dense_weight(N, K, seed=61)
+    d = np.exp(np.random.default_rng(62).standard_normal(K)).astype(np.float32)
+    h = gq.gqsa_pack_hessian(W, d, 16, 4, 0.5)
+    c = oracle.pack(W, 16, 4, sparsity=0.5, hinv_diag=d)
+    x_np = gi.activations(2, K, seed=63)
+    check(torch_cuda, h, c, x_np)
+    path = str(tmp_path / "layer.gqsa")
+    gq.gqsa_save(h, path)
+    h2 = gq.gqsa_load(path)
+    y1, y2 = run_gemv(torch_cuda, h, x_np), run_gemv(torch_cuda, h2, x_np)
+    assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+
+
 # ----------------------------------------------------------------------------- full sizes
 
 @pytest.mark.parametrize("idx", [0, 4, 6])

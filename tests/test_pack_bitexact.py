@@ -82,6 +82,24 @@ def test_other_group_sizes(bits, G):
     assert_same_blob(hb, cb)
 
 
+@pytest.mark.parametrize("G,bits", [(16, 4), (64, 4), (32, 8)])
+def test_pack_hessian_matches_the_oracle(G, bits):
+    """Pruning by the Hessian metric of Eq. 4 with a positive diagonal spread over decades."""
+    N, K = 200, 2048
+    W = gi.dense_weight(N, K, seed=55)
+    d = np.exp(np.random.default_rng(56).standard_normal(K) * 1.5).astype(np.float32)
+    for sparsity in (0.3, 0.5):
+        h = gq.gqsa_pack_hessian(W, d, G, bits, sparsity)
+        c = oracle.pack(W, G, bits, sparsity=sparsity, hinv_diag=d)
+        assert_same_canonical(h, c)
+        assert_same_blob(h, c)
+    # and it is not the magnitude selection
+    assert not np.array_equal(gq.gqsa_export(h)["groups"], gq.gqsa_export(gq.gqsa_pack(W, G, bits, 0.5))["groups"])
+    # d = 1 is gqsa_pack
+    h1 = gq.gqsa_pack_hessian(W, np.ones(K, dtype=np.float32), G, bits, 0.5)
+    assert gq.gqsa_export_device_blob(h1) == gq.gqsa_export_device_blob(gq.gqsa_pack(W, G, bits, 0.5))
+
+
 def test_unsupported_group_sizes_are_refused():
     W = np.zeros((4, 256), dtype=np.float32)
     for G, bits in ((8, 4), (48, 4), (256, 4), (128, 8)):
