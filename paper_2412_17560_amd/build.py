@@ -18,6 +18,9 @@ COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I
 # device code: gfx950 only; packed-fp32 instruction selection is switched off
 HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
              "-ffp-contract=off"]   # fused multiply-adds only where the source asks for them
+# the GEMV kernel's ten leading scalar parameters arrive in scalar registers at wavefront start
+# (kernel-argument preloading) instead of being loaded from the argument block first
+EXTRA_HIP_FLAGS = {"gqsa_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"]}
 # host arithmetic of the quantiser: every fp32 operation is a single IEEE operation
 HOST_FLAGS = ["-ffp-contract=off", "-fno-fast-math"]
 
@@ -33,7 +36,7 @@ def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
     path = os.path.join(CSRC, src)
     if src.endswith(".hip"):
-        cmd = [_hipcc(), *COMMON, *HIP_FLAGS, "-c", path, "-o", obj]
+        cmd = [_hipcc(), *COMMON, *HIP_FLAGS, *EXTRA_HIP_FLAGS.get(os.path.basename(path), []), "-c", path, "-o", obj]
     else:
         cmd = [_hipcc(), *COMMON, *HOST_FLAGS, "-x", "c++", "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -76,16 +76,18 @@ struct GemvArgsT {
 typedef GemvArgsT<kMaxMatrices> GemvArgs;     // what the host fills in; a launch passes the first NM
 static_assert(offsetof(GemvArgs, run) == 32 && sizeof(MatRun) == 32, "the first matrix's run closes line 0");
 
+constexpr int kArgsOffsetDecl = 48;   // where the argument block sits in the kernel-argument segment (after the preloaded scalars)
+
 // run[i] / m[i] of the kernel's argument block for a wave-uniform i, read from the
 // kernel-argument segment itself (scalar loads from constant memory); indexing the by-value
 // argument with a run-time i would make the compiler copy the whole block to scratch.
-// GemvArgs is the kernel's only parameter, so it sits at offset 0 of the segment.
+// The block follows the kernel's ten scalar parameters (two pointers, eight ints: 48 bytes).
 template <int NM>
 __device__ __forceinline__ MatRun matrix_run(int i)
 {
     typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
     typedef const __attribute__((address_space(4))) MatRun* ConstRunPtr;
-    ConstRunPtr src = (ConstRunPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(GemvArgsT<NM>, run)) + i;
+    ConstRunPtr src = (ConstRunPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffsetDecl + offsetof(GemvArgsT<NM>, run)) + i;
     MatRun r;
     r.blocks = src->blocks;
     r.per_wg = src->per_wg;
@@ -102,7 +104,7 @@ __device__ __forceinline__ MatArgs matrix_args(int i)
 {
     typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
     typedef const __attribute__((address_space(4))) MatArgs* ConstMatPtr;
-    ConstMatPtr src = (ConstMatPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(GemvArgsT<NM>, m)) + i;
+    ConstMatPtr src = (ConstMatPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffsetDecl + offsetof(GemvArgsT<NM>, m)) + i;
     MatArgs r;
     r.row_of_rank = src->row_of_rank;
     r.empty_rows = src->empty_rows;
@@ -559,9 +561,19 @@ struct ParkedArgs {
     const int4* wave_info;
 };
 
+// The leading scalar parameters repeat what the first loads depend on (x, the first matrix's
+// run, the slot count, the wavefronts per workgroup): the file is compiled with kernel-argument
+// preloading for them, so they sit in scalar registers when a wavefront starts instead of being
+// fetched from the argument block first.  The block itself follows at byte kArgsOffset.
+static_assert(kArgsOffsetDecl == 2 * 8 + 8 * 4, "two pointers and eight ints precede the argument block");
+
 template <typename F, int KGP, int NB, int NM>
-__global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(GemvArgsT<NM> a)
+__global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
+    const uint16_t* x_first, const uint8_t* blocks_first, int per_wg_first, int extra_wg_first, int per_wave0_first,
+    int per_wave1_first, int extra_wave0_first, int extra_wave1_first, int kg_first, int wpw_first, GemvArgsT<NM> a)
 {
+    const MatRun run_first = {blocks_first, per_wg_first, extra_wg_first, {per_wave0_first, per_wave1_first},
+                              {extra_wave0_first, extra_wave1_first}};
     // x arrays (NB * 48 * KGP bytes), then the wavefronts' records per matrix
     extern __shared__ __align__(16) uint8_t xlds[];
     LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);            // [matrix][wavefront]
@@ -572,7 +584,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wpw = a.wpw;
+    const int wpw = wpw_first;
     const int n_threads = wpw * kLanes;
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     const int wg = blockIdx.x;
@@ -594,8 +606,8 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     // issue the loads of x first and of the first superblock right behind them, so that the
     // weights are already on their way while x is staged in LDS
     auto stage = [&](int c, uint4 lo, uint4 hi) {   // c = slot over all rows: b * kg + column
-        const int b = NB == 1 ? 0 : c / a.kg;
-        uint8_t* slot = xlds + b * (48 * KGP) + (c - b * a.kg) * 16;
+        const int b = NB == 1 ? 0 : c / kg_first;
+        uint8_t* slot = xlds + b * (48 * KGP) + (c - b * kg_first) * 16;
         *reinterpret_cast<uint4*>(slot) = lo;
         *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -605,14 +617,14 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
             s += half_to_float(w[i] & 0xFFFFu);
             s += half_to_float(w[i] >> 16);
         }
-        *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * a.kg) * 4) = s;
+        *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg_first) * 4) = s;
     };
-    const int n_slots = NB * a.kg;                  // x is [NB][K] contiguous: slot c holds x[16c .. 16c+15]
+    const int n_slots = NB * kg_first;                  // x is [NB][K] contiguous: slot c holds x[16c .. 16c+15]
 
     // the first matrix in which this worker owns blocks
     int mi = 0, left = 0;
     const uint8_t* p = nullptr;
-    run_of(a.run[0], left, p);
+    run_of(run_first, left, p);
     while (left == 0 && mi + 1 < NM) {
         ++mi;
         run_of(matrix_run<NM>(mi), left, p);
@@ -626,7 +638,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     load_tile<F>(cur, p, u_cur, lane);
     uint4 lo0 = {0, 0, 0, 0}, hi0 = {0, 0, 0, 0};
     if (tid < n_slots) {
-        const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(tid) * 16);
+        const uint4* src = reinterpret_cast<const uint4*>(x_first + static_cast<size_t>(tid) * 16);
         lo0 = src[0];
         hi0 = src[1];
     }
@@ -652,7 +664,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
                      "s"(a.m[i].n_empty), "s"(a.wave_info[i]), "s"(a.n_wg));
     if (tid < n_slots) stage(tid, lo0, hi0);
     for (int c = tid + n_threads; c < n_slots; c += n_threads) {
-        const uint4* src = reinterpret_cast<const uint4*>(a.x + static_cast<size_t>(c) * 16);
+        const uint4* src = reinterpret_cast<const uint4*>(x_first + static_cast<size_t>(c) * 16);
         stage(c, src[0], src[1]);
     }
     // rows without stored groups: exactly +0; and this worker's records start out as "nothing"
@@ -792,7 +804,9 @@ GemvArgsT<NM> first_matrices(const GemvArgs& a)
 template <typename F, int KGP, int NB, int NM>
 void launch_variant(const GemvArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s)
 {
-    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB, NM>), grid, block, lds, s, first_matrices<NM>(a));
+    const MatRun& r = a.run[0];
+    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB, NM>), grid, block, lds, s, a.x, r.blocks, r.per_wg, r.extra_wg,
+                       r.per_wave[0], r.per_wave[1], r.extra_wave[0], r.extra_wave[1], a.kg, a.wpw, first_matrices<NM>(a));
 }
 
 template <typename F, int KGP, int NB, int NM>
