@@ -61,11 +61,9 @@ struct GemvArgsT {
     // ---- first 64-byte line
     const uint16_t* x;           // fp16 [NB][K], shared by the matrices
     int n_mats;
-    int kg;                      // group-columns K/G
-    // nibble masks and the fp16 pair (1024, 1024); passed in registers so that mask-and-splice
-    // is one three-operand instruction instead of two with literal operands
-    uint32_t nib_lo, nib_hi, k1024x2;
+    int kg;                      // 16-element activation slots K/16
     int wpw;                     // wavefronts per workgroup
+    int pad0[3];
     MatRun run[NM];              // run[0] completes the first line
     // ---- later lines
     const int4* wave_info[NM];   // {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len} per worker
@@ -147,17 +145,19 @@ struct Codes {
 // 4-bit: the code words are nibble-permuted at pack time (element 2m at bits 4m, element 2m+1
 // at bits 16+4m), so one AND-OR splices a pair of codes into the mantissas of the fp16 pair
 // (1024+q, 1024+q') or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
-template <typename Args>
-__device__ __forceinline__ void decode_w4(const Args& a, uint32_t w, half2_t* q)
+__device__ __forceinline__ void decode_w4(uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
     const half2_t k64 = {(_Float16)64.0f, (_Float16)64.0f};
+    // nibble masks and the fp16 pair (1024, 1024): constants kept in registers, so that
+    // mask-and-splice is one three-operand instruction instead of two with literal operands
+    const uint32_t nib_lo = 0x000F000Fu, nib_hi = 0x00F000F0u, k1024x2 = 0x64006400u;
     const uint32_t w2 = w >> 8;
-    q[0] = as_half2(and_or(w, a.nib_lo, a.k1024x2)) - k1024;
-    q[1] = __builtin_elementwise_fma(as_half2(and_or(w, a.nib_hi, a.k1024x2)), k16th, -k64);
-    q[2] = as_half2(and_or(w2, a.nib_lo, a.k1024x2)) - k1024;
-    q[3] = __builtin_elementwise_fma(as_half2(and_or(w2, a.nib_hi, a.k1024x2)), k16th, -k64);
+    q[0] = as_half2(and_or(w, nib_lo, k1024x2)) - k1024;
+    q[1] = __builtin_elementwise_fma(as_half2(and_or(w, nib_hi, k1024x2)), k16th, -k64);
+    q[2] = as_half2(and_or(w2, nib_lo, k1024x2)) - k1024;
+    q[3] = __builtin_elementwise_fma(as_half2(and_or(w2, nib_hi, k1024x2)), k16th, -k64);
 }
 
 // 8-bit: a byte permute drops each code (bytes of w, element order) into the mantissa of
@@ -328,8 +328,8 @@ __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, co
         for (int i = 0; i < F::M; ++i) {                // the group's 16-element chunks
             Codes c;
             if constexpr (F::BITS == 4) {
-                decode_w4(a, t.code[u][2 * i], &c.q[0]);
-                decode_w4(a, t.code[u][2 * i + 1], &c.q[4]);
+                decode_w4(t.code[u][2 * i], &c.q[0]);
+                decode_w4(t.code[u][2 * i + 1], &c.q[4]);
             } else {
                 decode_w8(t.code[u][4 * i], &c.q[0]);
                 decode_w8(t.code[u][4 * i + 1], &c.q[2]);
@@ -795,7 +795,6 @@ GemvArgsT<NM> first_matrices(const GemvArgs& a)
 {
     GemvArgsT<NM> r{};
     r.x = a.x; r.n_mats = NM; r.kg = a.kg;
-    r.nib_lo = a.nib_lo; r.nib_hi = a.nib_hi; r.k1024x2 = a.k1024x2;
     r.wpw = a.wpw; r.n_wg = a.n_wg;
     for (int i = 0; i < NM; ++i) { r.run[i] = a.run[i]; r.wave_info[i] = a.wave_info[i]; r.m[i] = a.m[i]; }
     return r;
@@ -982,9 +981,6 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
     a.wpw = m0->waves_per_workgroup;
     a.n_wg = m0->n_workgroups;
     a.kg = static_cast<int>(m0->K / 16);       // 16-element activation slots
-    a.nib_lo = 0x000F000Fu;
-    a.nib_hi = 0x00F000F0u;
-    a.k1024x2 = 0x64006400u;
 
     const int threads = m0->waves_per_workgroup * kLanes;
     const int grid = m0->n_workgroups;
