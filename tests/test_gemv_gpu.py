@@ -301,6 +301,30 @@ def test_gemv_multi_error_paths(torch_cuda):
     assert e.value.status == 2
 
 
+@pytest.mark.parametrize("bits", [4, 8])
+def test_largest_and_smallest_reduction_lengths(torch_cuda, bits):
+    """K = 32768 is the most gqsa_gemv takes (x, its halves and group sums fill 96 KB of LDS; a
+    batch of 2 goes out as two launches), K = 16 with one row the least; one more group-column
+    than the limit packs but is refused by gqsa_gemv."""
+    torch = torch_cuda
+    N, K = 48, 32768
+    W = gi.dense_weight(N, K, seed=200 + bits)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=200 + bits)
+    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+    check(torch, h, c, gi.activations(2, K, seed=13))
+    W1 = gi.dense_weight(1, 16, seed=300 + bits)
+    h1 = gq.gqsa_pack(W1, 16, bits, 0.0)
+    check(torch, h1, oracle.pack(W1, 16, bits, sparsity=0.0), gi.activations(3, 16, seed=14))
+    Wb = np.zeros((2, 32768 + 16), dtype=np.float32)
+    hb = gq.gqsa_pack(Wb, 16, bits, 0.5)
+    x = torch.zeros((1, 32768 + 16), dtype=torch.float16, device="cuda")
+    y = torch.zeros((1, 2), dtype=torch.float16, device="cuda")
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_gemv(hb, x, y)
+    assert e.value.status == 3
+
+
 # ----------------------------------------------------------------------------- other group sizes
 
 @pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
