@@ -32,10 +32,11 @@ constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one gfx950 compute unit
 
 constexpr int kMaxMatrices = 4;           // matrices sharing x that one launch can take
 
-// One packed matrix as the kernel sees it, split by when it is needed.  The argument block is
-// read with scalar loads one 64-byte line at a time and every line is a round trip of its own
-// (the block may live in host memory), so everything the first weight load depends on sits in
-// the first line; the rest is fetched in one batch while those weights are on their way.
+// One packed matrix as the kernel sees it, split by when it is needed.  What the first loads
+// depend on (x, the first matrix's run, the slot count, the wavefronts per workgroup) is also
+// passed as leading scalar kernel parameters, which arrive preloaded in scalar registers; the
+// argument block below is read with scalar loads, a 64-byte line per round trip, while the first
+// weights are on their way.
 struct MatRun {                  // where a worker's run of blocks is (32 bytes)
     const uint8_t* blocks;
     int per_wg;                  // blocks per workgroup (the first extra_wg workgroups hold one more)
@@ -49,7 +50,7 @@ struct MatArgs {                 // where results go (64 bytes)
     const int32_t* empty_rows;
     CarryRecord* carry;          // [worker][kMaxRowsPerLaunch]
     int* counters;               // arrivals per carry chain, indexed by the chain's first worker
-    unsigned long long* slots;   // [worker][kMaxRowsPerLaunch] meeting points of two-worker chains
+    unsigned long long* slots;   // [worker][kMaxRowsPerLaunch] meeting points of rows spread over two workgroups
     uint16_t* y;                 // fp16 [NB][N]
     long long N;
     int n_empty;
@@ -58,7 +59,7 @@ struct MatArgs {                 // where results go (64 bytes)
 
 template <int NM>
 struct GemvArgsT {
-    // ---- first 64-byte line
+    // ---- first 64-byte line (x, kg, wpw and run[0] travel as scalar parameters as well)
     const uint16_t* x;           // fp16 [NB][K], shared by the matrices
     int n_mats;
     int kg;                      // 16-element activation slots K/16
@@ -74,7 +75,8 @@ struct GemvArgsT {
 typedef GemvArgsT<kMaxMatrices> GemvArgs;     // what the host fills in; a launch passes the first NM
 static_assert(offsetof(GemvArgs, run) == 32 && sizeof(MatRun) == 32, "the first matrix's run closes line 0");
 
-constexpr int kArgsOffsetDecl = 48;   // where the argument block sits in the kernel-argument segment (after the preloaded scalars)
+// where the argument block sits in the kernel-argument segment: after the ten scalar parameters
+constexpr int kArgsOffset = 48;
 
 // run[i] / m[i] of the kernel's argument block for a wave-uniform i, read from the
 // kernel-argument segment itself (scalar loads from constant memory); indexing the by-value
@@ -85,7 +87,7 @@ __device__ __forceinline__ MatRun matrix_run(int i)
 {
     typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
     typedef const __attribute__((address_space(4))) MatRun* ConstRunPtr;
-    ConstRunPtr src = (ConstRunPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffsetDecl + offsetof(GemvArgsT<NM>, run)) + i;
+    ConstRunPtr src = (ConstRunPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffset + offsetof(GemvArgsT<NM>, run)) + i;
     MatRun r;
     r.blocks = src->blocks;
     r.per_wg = src->per_wg;
@@ -102,7 +104,7 @@ __device__ __forceinline__ MatArgs matrix_args(int i)
 {
     typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
     typedef const __attribute__((address_space(4))) MatArgs* ConstMatPtr;
-    ConstMatPtr src = (ConstMatPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffsetDecl + offsetof(GemvArgsT<NM>, m)) + i;
+    ConstMatPtr src = (ConstMatPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffset + offsetof(GemvArgsT<NM>, m)) + i;
     MatArgs r;
     r.row_of_rank = src->row_of_rank;
     r.empty_rows = src->empty_rows;
@@ -565,7 +567,7 @@ struct ParkedArgs {
 // run, the slot count, the wavefronts per workgroup): the file is compiled with kernel-argument
 // preloading for them, so they sit in scalar registers when a wavefront starts instead of being
 // fetched from the argument block first.  The block itself follows at byte kArgsOffset.
-static_assert(kArgsOffsetDecl == 2 * 8 + 8 * 4, "two pointers and eight ints precede the argument block");
+static_assert(kArgsOffset == 2 * 8 + 8 * 4, "two pointers and eight ints precede the argument block");
 
 template <typename F, int KGP, int NB, int NM>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
