@@ -130,7 +130,8 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
  * K must not exceed 32768 (x and its group sums are staged in LDS); GQSA_ERR_UNSUPPORTED else.
  * Group sizes above 16 run one activation row and one matrix per launch.
  * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
- * bit-identical from run to run.  Does not synchronise.
+ * bit-identical from run to run.  Does not synchronise.  The current HIP device must be the one
+ * the handle was uploaded on (GQSA_ERR_HIP otherwise).
  */
 gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
                         void* hip_stream);

@@ -955,6 +955,11 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const gqsa_matrix* m0 = ms[0];
+    // the device image, its workspace and the kernels' LDS attributes belong to one GPU
+    int dev = -1;
+    GQSA_HIP(hipGetDevice(&dev));
+    for (int i = 0; i < n_mats; ++i)
+        if (ms[i]->device != dev) return GQSA_ERR_HIP;
     GemvArgs a{};
     for (int i = 0; i < n_mats; ++i) {
         const gqsa_matrix* m = ms[i];
