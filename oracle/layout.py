@@ -5,23 +5,19 @@ The layout is a pure permutation/padding of the canonical BSR arrays of the
 paper's Sec. 3.2 listing (rowIndex / groups / values) and the per-group scale
 and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
 
- 1. Stream.  The stored groups in canonical order g = 0..nnzg-1 form a stream;
-    it is padded with null groups (all bytes zero) to nblocks*64 positions,
-    nblocks = ceil(nnzg/64).
- 2. Partition, two levels.  The blocks are dealt to n_workgroups workgroups in
-    contiguous runs: workgroup g gets nblocks div n_workgroups blocks (+1 if
-    g < nblocks mod n_workgroups).  A workgroup's run of m blocks is dealt the
-    same way to its waves_per_workgroup wavefronts: wavefront l gets
-    m div waves_per_workgroup (+1 if l < m mod waves_per_workgroup).  Worker
-    w = g*waves_per_workgroup + l; n_waves = n_workgroups*waves_per_workgroup;
-    b_w = first block of worker w = sum of the earlier workers' counts.
- 3. Superblocks.  A worker's run is cut, from its start, into superblocks of 4
-    blocks as long as 4 fit, then of 2 blocks as long as 2 fit, then of 1
-    block -- except that a superblock has at most u_max blocks, u_max = 4 for
-    up to 16 code bytes per group (G*bits/8), 2 for 32, 1 for 64.  A
-    superblock of U blocks starting at block b covers stream positions
-    64b .. 64(b+U)-1 of the stream; the position 64b + p lives in block
-    b + (p mod U), lane p div U.
+ 1. Stream.  The stored groups in canonical order g = 0..nnzg-1 form a stream.
+    64 consecutive positions make a block, U consecutive blocks a tile, with
+    U = 4 for up to 16 code bytes per group (G*bits/8), 2 for 32, 1 for 64.
+    The stream is padded with null groups (all bytes zero) to whole tiles:
+    ntiles = ceil(nnzg / (64 U)), nblocks = U * ntiles.
+ 2. Partition.  The tiles are dealt to the n_waves = n_workgroups *
+    waves_per_workgroup workers in contiguous runs: worker w gets
+    ntiles div n_waves tiles (+1 if w < ntiles mod n_waves).  b_w = first block
+    of worker w = U * (number of tiles of the earlier workers).  (The grouping
+    of the workers into workgroups does not enter the layout.)
+ 3. Tiles.  A tile starting at block b covers stream positions
+    64b .. 64(b+U)-1; the position 64b + p lives in block b + (p mod U),
+    lane p div U.
  4. Block.  Each block is (G*bits/8 + 6)*64 bytes: the code planes, then
     64 x uint32 (fp16 scale bits | fp16 zero bits << 16), then 64 x uint16
     index words.  G = 16*M with M in {1, 2, 4, 8}.  The index word is
@@ -60,66 +56,58 @@ import numpy as np
 
 LANES = 64
 ALIGN = 256
-MAX_WAVES = 4096
-WAVES_PER_WORKGROUP = 16
+MAX_WORKGROUPS = 4096
 
 
-def default_partition(nnzg: int, G: int = 16):
-    """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise:
-    min(256, nblocks) workgroups (at least 1); wavefronts per workgroup =
-    ceil(nblocks * (G/16) / (2 * n_workgroups)), at least 1, at most 16 and at most
-    ceil(nblocks / n_workgroups)."""
-    nblocks = (nnzg + LANES - 1) // LANES
-    wgs = max(1, min(MAX_WAVES // WAVES_PER_WORKGROUP, nblocks))
-    per_wg = max(1, -(-nblocks // wgs))
-    want = -(-(nblocks * (G // 16)) // (2 * wgs))
-    return wgs, max(1, min(WAVES_PER_WORKGROUP, per_wg, want))
+def tile_blocks(code_bytes: int) -> int:
+    """U of spec item 1."""
+    return 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
 
 
-def worker_block_counts(nblocks: int, n_workgroups: int, waves_per_workgroup: int) -> np.ndarray:
+def default_partition(nnzg: int, K: int, G: int = 16, bits: int = 4):
+    """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise.
+    One tile per worker as long as there are no more workers than half of the wavefront slots
+    of the GPU's 256 compute units (each holds min(3, 160 KiB div (48 * slots)) workgroups of
+    8 wavefronts, slots = K/16 rounded up to a power of two >= 256); beyond that the fewest
+    tiles per worker that respect that bound.  Wavefronts per workgroup: the smallest of 1, 2,
+    4, 8 with 256 workgroups covering the workers, else 8; with 8, an even number of
+    workgroups (> 1)."""
+    ntiles = -(-nnzg // (LANES * tile_blocks(G * bits // 8)))
+    slots = 256
+    while slots < K // 16:
+        slots *= 2
+    budget = 256 * max(1, min(3, (160 * 1024) // (48 * slots))) * 8 // 2
+    per_worker = max(1, -(-ntiles // budget))
+    workers = max(1, -(-ntiles // per_worker))
+    wpw = 1
+    while wpw < 8 and 256 * wpw < workers:
+        wpw *= 2
+    wgs = -(-workers // wpw)
+    if wpw == 8 and wgs > 1 and wgs % 2:
+        wgs += 1
+    return min(wgs, MAX_WORKGROUPS), wpw
+
+
+def worker_block_counts(nblocks: int, n_waves: int, U: int) -> np.ndarray:
     """Blocks owned by every worker (spec item 2)."""
-    base, extra = divmod(nblocks, n_workgroups)
-    out = np.zeros(n_workgroups * waves_per_workgroup, dtype=np.int64)
-    for g in range(n_workgroups):
-        m = base + (1 if g < extra else 0)
-        b2, e2 = divmod(m, waves_per_workgroup)
-        row = np.full(waves_per_workgroup, b2, dtype=np.int64)
-        row[:e2] += 1
-        out[g * waves_per_workgroup:(g + 1) * waves_per_workgroup] = row
-    return out
+    base, extra = divmod(nblocks // U, n_waves)
+    out = np.full(n_waves, base, dtype=np.int64)
+    out[:extra] += 1
+    return out * U
 
 
 def _align(n: int) -> int:
     return (n + ALIGN - 1) // ALIGN * ALIGN
 
 
-def largest_superblock(code_bytes: int) -> int:
-    """u_max of spec item 3."""
-    return 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
-
-
-def stream_placement(nblocks: int, n_workgroups: int, waves_per_workgroup: int, u_max: int = 4):
+def stream_placement(nblocks: int, n_waves: int, U: int):
     """For every stream position: (block, lane) it is stored at (spec items 2-3)."""
-    n_w = worker_block_counts(nblocks, n_workgroups, waves_per_workgroup)
+    n_w = worker_block_counts(nblocks, n_waves, U)
     b_w = np.concatenate(([0], np.cumsum(n_w)[:-1]))
     pos = np.arange(nblocks * LANES, dtype=np.int64)
-    blk_of_pos = pos // LANES
-    # worker owning each block: block counts expanded
-    w = np.repeat(np.arange(n_w.size), n_w)[blk_of_pos]
-    q = pos - LANES * b_w[w]                    # position inside the worker's run
-    nw = n_w[w]
-    n4 = nw // 4 if u_max >= 4 else np.zeros_like(nw)        # superblocks of 4, of 2, of 1
-    n2 = (nw - 4 * n4) // 2 if u_max >= 2 else np.zeros_like(nw)
-    in4 = q < 256 * n4
-    qq = q - 256 * n4
-    in2 = (~in4) & (qq < 128 * n2)
-    in1 = (~in4) & (~in2)
-    q1 = qq - 128 * n2
-    U = np.where(in4, 4, np.where(in2, 2, 1))
-    sb_blk = np.where(in4, 4 * (q // 256), np.where(in2, 4 * n4 + 2 * (qq // 128), 4 * n4 + 2 * n2 + q1 // 64))
-    p = np.where(in4, q % 256, np.where(in2, qq % 128, q1 % 64))
-    assert (p >= 0).all() and (q1[in1] >= 0).all()
-    block = b_w[w] + sb_blk + (p % U)
+    tile = pos // (LANES * U)
+    p = pos % (LANES * U)
+    block = tile * U + (p % U)
     lane = p // U
     return block, lane, b_w, n_w
 
@@ -129,8 +117,9 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     if c.G not in (16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
         raise ValueError("device layout is specified for G in {16,32,64,128}, bits in {4,8}, at most 64 code bytes")
     nnzg = c.nnzg
-    nblocks = (nnzg + LANES - 1) // LANES
     code_bytes = c.G * c.bits // 8
+    U = tile_blocks(code_bytes)
+    nblocks = U * (-(-nnzg // (LANES * U)))
     blk_bytes = (code_bytes + 6) * LANES
     chunks = c.G // 16
 
@@ -147,8 +136,7 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     wave_info[:, 1] = 1
     wave_info[:, 2] = -1
     if nblocks > 0:
-        block, lane, b_w, n_w = stream_placement(nblocks, n_workgroups, waves_per_workgroup,
-                                                 largest_superblock(code_bytes))
+        block, lane, b_w, n_w = stream_placement(nblocks, n_waves, U)
         block = block[:nnzg]
         lane = lane[:nnzg]
         # codes

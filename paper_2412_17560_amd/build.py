@@ -20,7 +20,7 @@ HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "
              "-ffp-contract=off"]   # fused multiply-adds only where the source asks for them
 # the GEMV kernel's ten leading scalar parameters arrive in scalar registers at wavefront start
 # (kernel-argument preloading) instead of being loaded from the argument block first
-EXTRA_HIP_FLAGS = {"gqsa_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"]}
+EXTRA_HIP_FLAGS = {"gqsa_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
 # host arithmetic of the quantiser: every fp32 operation is a single IEEE operation
 HOST_FLAGS = ["-ffp-contract=off", "-fno-fast-math"]
 

@@ -26,9 +26,9 @@ gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
 gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
 {
     if (st == GQSA_OK) {
-        const int64_t nb = (m->nnzg() + gqsa::kLanes - 1) / gqsa::kLanes;
+        const int64_t tile_groups = static_cast<int64_t>(gqsa::kLanes) * gqsa::largest_tile(m->code_bytes());
         int wgs = 1, wpw = 1;
-        gqsa::default_partition(nb, m->G, &wgs, &wpw);
+        gqsa::default_partition((m->nnzg() + tile_groups - 1) / tile_groups, m->K, &wgs, &wpw);
         st = gqsa::build_image(m, wgs, wpw);
     }
     if (st != GQSA_OK) {
@@ -154,10 +154,8 @@ gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, cons
         if ((reinterpret_cast<uintptr_t>(y_devs[i]) & 1u) != 0) return GQSA_ERR_ALIGN;
         const gqsa_matrix* m = handles[i];
         const gqsa_matrix* m0 = handles[0];
-        // one stream of work: same x, same code width, same deal of blocks to wavefronts
+        // one launch: same x, same storage format (N and the partitions may differ)
         if (m->K != m0->K || m->G != m0->G || m->bits != m0->bits) return GQSA_ERR_SHAPE;
-        if (m->n_workgroups != m0->n_workgroups || m->waves_per_workgroup != m0->waves_per_workgroup)
-            return GQSA_ERR_SHAPE;
         for (int j = 0; j < i; ++j)
             if (handles[j] == handles[i]) return GQSA_ERR_SHAPE;   // a handle has one carry workspace
     }

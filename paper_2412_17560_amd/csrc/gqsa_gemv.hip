@@ -8,14 +8,20 @@
 // with its neighbours in a carry fix-up at the end of the same kernel.
 //
 // Wavefront = 64 lanes.  A block is 64 stored groups, one per lane, so that every load is
-// one fully coalesced instruction; in a superblock of U blocks lane l owns the U
+// one fully coalesced instruction; a tile is U blocks (4 at G = 16): lane l owns the U
 // consecutive stream positions U*l .. U*l+U-1, sums them serially and takes part in ONE
-// cross-lane segmented scan per superblock.
+// cross-lane segmented scan per tile.  A wavefront owns whole tiles; with the default partition
+// it owns one or two, requests all of their bytes before anything else and works through the
+// blocks in the order in which they arrive.
+//
+// One launch can carry several matrices that share x (q/k/v, gate/up): the workgroups of the
+// grid are dealt to the matrices, each workgroup works on one of them.
 //
 // Small batches: the kernel is compiled for NB = 1, 2, 4, 8 activation rows per launch; each
 // decoded group is multiplied with all NB rows (weights are read and dequantised once).
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cstddef>
 #include <cstdint>
 #include <cstdio>
@@ -26,26 +32,14 @@ namespace gqsa {
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef int int4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxRowsPerLaunch = 8;      // NB values compiled: 1, 2, 4, 8
 constexpr int kMaxLdsBytes = 160 * 1024;  // LDS of one gfx950 compute unit
 
 constexpr int kMaxMatrices = 4;           // matrices sharing x that one launch can take
 
-// One packed matrix as the kernel sees it, split by when it is needed.  What the first loads
-// depend on (x, the first matrix's run, the slot count, the wavefronts per workgroup) is also
-// passed as leading scalar kernel parameters, which arrive preloaded in scalar registers; the
-// argument block below is read with scalar loads, a 64-byte line per round trip, while the first
-// weights are on their way.
-struct MatRun {                  // where a worker's run of blocks is (32 bytes)
-    const uint8_t* blocks;
-    int per_wg;                  // blocks per workgroup (the first extra_wg workgroups hold one more)
-    int extra_wg;
-    int per_wave[2];             // blocks per wavefront in a workgroup of per_wg (+1) blocks ...
-    int extra_wave[2];           // ... of which the first extra_wave wavefronts hold one more
-};
-
-struct MatArgs {                 // where results go (64 bytes)
+struct MatArgs {                 // where a matrix's results go (64 bytes)
     const int32_t* row_of_rank;  // row index of the r-th non-empty row (nullptr: identity)
     const int32_t* empty_rows;
     CarryRecord* carry;          // [worker][kMaxRowsPerLaunch]
@@ -57,64 +51,49 @@ struct MatArgs {                 // where results go (64 bytes)
     int n_ranks;                 // non-empty rows
 };
 
-template <int NM>
-struct GemvArgsT {
-    // ---- first 64-byte line (x, kg, wpw and run[0] travel as scalar parameters as well)
-    const uint16_t* x;           // fp16 [NB][K], shared by the matrices
-    int n_mats;
-    int kg;                      // 16-element activation slots K/16
-    int wpw;                     // wavefronts per workgroup
-    int pad0[3];
-    MatRun run[NM];              // run[0] completes the first line
-    // ---- later lines
-    const int4* wave_info[NM];   // {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len} per worker
-    int n_wg;                    // workgroups
+// One matrix of a launch (96 bytes of the kernel-argument block).  Worker w of the matrix owns
+// `base` tiles starting at tile base * w + min(w, extra), one more if w < extra.
+struct MatDesc {
+    const uint8_t* blocks;
+    const int4_t* wave_info;     // {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len} per worker
+    int base, extra;
+    int n_wg;                    // workgroups of the launch that work on this matrix
     int pad;
-    MatArgs m[NM];
+    MatArgs out;
 };
-typedef GemvArgsT<kMaxMatrices> GemvArgs;     // what the host fills in; a launch passes the first NM
-static_assert(offsetof(GemvArgs, run) == 32 && sizeof(MatRun) == 32, "the first matrix's run closes line 0");
+struct LaunchArgs {
+    MatDesc m[kMaxMatrices];
+};
+static_assert(sizeof(MatArgs) == 64 && sizeof(MatDesc) == 96, "argument block layout");
 
-// where the argument block sits in the kernel-argument segment: after the ten scalar parameters
-constexpr int kArgsOffset = 48;
+// where the argument block sits in the kernel-argument segment: after the scalar parameters
+// (three pointers and eight ints)
+constexpr int kArgsOffset = 3 * 8 + 8 * 4;
 
-// run[i] / m[i] of the kernel's argument block for a wave-uniform i, read from the
-// kernel-argument segment itself (scalar loads from constant memory); indexing the by-value
-// argument with a run-time i would make the compiler copy the whole block to scratch.
-// The block follows the kernel's ten scalar parameters (two pointers, eight ints: 48 bytes).
-template <int NM>
-__device__ __forceinline__ MatRun matrix_run(int i)
+// The descriptor of matrix i (wave-uniform), read from the kernel-argument segment itself with
+// scalar loads; indexing the by-value argument with a run-time i would make the compiler copy
+// the whole block to scratch.
+__device__ __forceinline__ MatDesc matrix_desc(int i)
 {
     typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
-    typedef const __attribute__((address_space(4))) MatRun* ConstRunPtr;
-    ConstRunPtr src = (ConstRunPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffset + offsetof(GemvArgsT<NM>, run)) + i;
-    MatRun r;
+    typedef const __attribute__((address_space(4))) MatDesc* ConstDescPtr;
+    ConstDescPtr src = (ConstDescPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffset) + i;
+    MatDesc r;
     r.blocks = src->blocks;
-    r.per_wg = src->per_wg;
-    r.extra_wg = src->extra_wg;
-    r.per_wave[0] = src->per_wave[0];
-    r.per_wave[1] = src->per_wave[1];
-    r.extra_wave[0] = src->extra_wave[0];
-    r.extra_wave[1] = src->extra_wave[1];
-    return r;
-}
-
-template <int NM>
-__device__ __forceinline__ MatArgs matrix_args(int i)
-{
-    typedef const __attribute__((address_space(4))) uint8_t* ConstBytePtr;
-    typedef const __attribute__((address_space(4))) MatArgs* ConstMatPtr;
-    ConstMatPtr src = (ConstMatPtr)((ConstBytePtr)__builtin_amdgcn_kernarg_segment_ptr() + kArgsOffset + offsetof(GemvArgsT<NM>, m)) + i;
-    MatArgs r;
-    r.row_of_rank = src->row_of_rank;
-    r.empty_rows = src->empty_rows;
-    r.carry = src->carry;
-    r.counters = src->counters;
-    r.slots = src->slots;
-    r.y = src->y;
-    r.N = src->N;
-    r.n_empty = src->n_empty;
-    r.n_ranks = src->n_ranks;
+    r.wave_info = src->wave_info;
+    r.base = src->base;
+    r.extra = src->extra;
+    r.n_wg = src->n_wg;
+    r.pad = 0;
+    r.out.row_of_rank = src->out.row_of_rank;
+    r.out.empty_rows = src->out.empty_rows;
+    r.out.carry = src->out.carry;
+    r.out.counters = src->out.counters;
+    r.out.slots = src->out.slots;
+    r.out.y = src->out.y;
+    r.out.N = src->out.N;
+    r.out.n_empty = src->out.n_empty;
+    r.out.n_ranks = src->out.n_ranks;
     return r;
 }
 
@@ -236,11 +215,13 @@ struct Fmt {
     static constexpr int CWC = CW / M_;                  // code words per chunk (2 or 4)
     static constexpr int PB = CB < 16 ? CB : 16;         // bytes per lane in one code plane
     static constexpr int PLANES = CB / PB;
-    static constexpr int UMAX = CB <= 16 ? 4 : (CB <= 32 ? 2 : 1);   // blocks of the largest superblock
+    static constexpr int UMAX = largest_tile(CB);        // blocks of a tile
     static constexpr int BB = (CB + 6) * kLanes;         // block bytes
+    static constexpr int TB = UMAX * BB;                 // tile bytes
+    static constexpr int LOADS = UMAX * (PLANES + 2);    // load instructions per tile
 };
 
-// The compressed groups of up to UMAX blocks, as loaded (one group per lane per block).
+// The compressed groups of a tile, as loaded (one group per lane per block).
 template <typename F>
 struct Tile {
     uint32_t code[F::UMAX][F::CW];
@@ -249,34 +230,51 @@ struct Tile {
 };
 
 // (1) stream the compressed groups: coalesced loads, all issued before anything waits.  The
-// block pointer is wave-uniform (scalar base), the lane supplies a 32-bit byte offset.
+// tile pointer is wave-uniform (scalar base), the lane supplies a 32-bit byte offset.
 template <typename T>
 __device__ __forceinline__ T load_at(const uint8_t* base, uint32_t byte_offset)
 {
     return *reinterpret_cast<const T*>(base + byte_offset);
 }
 
+// A tile's loads go out index words first (four small loads: the gathers from LDS need nothing
+// else), then codes and scale/zero block by block; loads return in the order of issue, so the
+// tile can be worked through while its later blocks are still on their way.
 template <typename F>
-__device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int U, int lane)
+__device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int lane)
 {
     const uint32_t ulane = static_cast<uint32_t>(lane);
 #pragma unroll
-    for (int u = 0; u < F::UMAX; ++u) {
-        if (u < U) {
+    for (int u = 0; u < F::UMAX; ++u)
+        t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * F::BB + (F::CB + 4) * kLanes));
 #pragma unroll
-            for (int pl = 0; pl < F::PLANES; ++pl) {
-                if constexpr (F::PB == 8) {
-                    const uint2 c = load_at<uint2>(p, ulane * 8u + u * F::BB);
-                    t.code[u][0] = c.x; t.code[u][1] = c.y;
-                } else {
-                    const uint4 c = load_at<uint4>(p, ulane * 16u + (u * F::BB + pl * 16 * kLanes));
-                    t.code[u][4 * pl + 0] = c.x; t.code[u][4 * pl + 1] = c.y;
-                    t.code[u][4 * pl + 2] = c.z; t.code[u][4 * pl + 3] = c.w;
-                }
+    for (int u = 0; u < F::UMAX; ++u) {
+#pragma unroll
+        for (int pl = 0; pl < F::PLANES; ++pl) {
+            if constexpr (F::PB == 8) {
+                const uint2 c = load_at<uint2>(p, ulane * 8u + u * F::BB);
+                t.code[u][0] = c.x; t.code[u][1] = c.y;
+            } else {
+                const uint4 c = load_at<uint4>(p, ulane * 16u + (u * F::BB + pl * 16 * kLanes));
+                t.code[u][4 * pl + 0] = c.x; t.code[u][4 * pl + 1] = c.y;
+                t.code[u][4 * pl + 2] = c.z; t.code[u][4 * pl + 3] = c.w;
             }
-            t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * F::BB + F::CB * kLanes));
-            t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * F::BB + (F::CB + 4) * kLanes));
         }
+        t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * F::BB + F::CB * kLanes));
+    }
+}
+
+template <typename F>
+__device__ __forceinline__ void decode_chunk(const Tile<F>& t, int u, int i, Codes& c)
+{
+    if constexpr (F::BITS == 4) {
+        decode_w4(t.code[u][2 * i], &c.q[0]);
+        decode_w4(t.code[u][2 * i + 1], &c.q[4]);
+    } else {
+        decode_w8(t.code[u][4 * i], &c.q[0]);
+        decode_w8(t.code[u][4 * i + 1], &c.q[2]);
+        decode_w8(t.code[u][4 * i + 2], &c.q[4]);
+        decode_w8(t.code[u][4 * i + 3], &c.q[6]);
     }
 }
 
@@ -284,11 +282,16 @@ __device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int U, i
 // 8..15 in a second array of 16-byte slots 16*KGP bytes further on, and the fp32 sum of the 16
 // as a dense array of floats at 32*KGP (4 bytes per column: a wavefront's 64 reads of it spread
 // over all banks instead of a quarter of them).  Row b starts at b * 48 * KGP.
-template <typename F, int KGP, int U, int NB, typename Args>
-__device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, const Tile<F>& t,
-                                             int lane, const uint8_t* xlds, WaveState<NB>& st)
+//
+// EAGER: the tile's loads may still be in flight.  All gathers are issued first (they need only
+// the index words, the first of the tile's loads to arrive), then the groups are decoded block
+// by block as their codes come in.  Otherwise the gathers go group by group (fewer registers).
+template <typename F, int KGP, int NB, bool EAGER>
+__device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t, int lane, const uint8_t* xlds,
+                                             WaveState<NB>& st)
 {
-    // Row heads as wave-uniform lane masks, one per position of the superblock (index word =
+    constexpr int U = F::UMAX;
+    // Row heads as wave-uniform lane masks, one per position of the tile (index word =
     // column << 4 | head); counting them is scalar work.
     unsigned long long bal[U];
     unsigned long long hmask = 0;
@@ -301,7 +304,7 @@ __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, co
     }
     // no lane holds two heads (no row shorter than U groups here): branch-free serial sums
     const bool simple = heads_total == static_cast<int>(__popcll(hmask));
-    int heads_before = 0;   // row heads of this superblock in lower lanes
+    int heads_before = 0;   // row heads of this tile in lower lanes
     if (simple) {
         heads_before = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(hmask >> 32),
                        __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(hmask), 0));
@@ -312,43 +315,16 @@ __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, co
                            __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(bal[u]), heads_before));
     }
 
-    // (2)-(4) gather the activation group by real group index, dequantise, multiply:
+    // (5a) the lane's U consecutive groups are added serially: lead = what precedes the lane's
+    // first row head, acc = what follows its last one (everything, if it has none).  fold() adds
+    // group u, given its dotz = sum_j q_j x_j - z sum_j x_j per activation row:
     //   sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j)
-    // (5a) and add serially over the lane's U consecutive groups: lead = what precedes the
-    // lane's first row head, acc = what follows its last one (everything, if it has none)
     float acc[NB], lead[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) { acc[b] = 0.0f; lead[b] = 0.0f; }
     int nh = 0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
+    auto fold = [&](int u, const float* dotz) {
         const float s = half_to_float(t.sz[u] & 0xFFFFu);
-        const float z = half_to_float(t.sz[u] >> 16);
-        const uint32_t slot = t.ix[u] & 0xFFF0u;        // byte offset of the group's first 16 activations
-        float dotz[NB];   // sum_j q_j x_j - z sum_j x_j; times s it is the group's contribution
-#pragma unroll
-        for (int i = 0; i < F::M; ++i) {                // the group's 16-element chunks
-            Codes c;
-            if constexpr (F::BITS == 4) {
-                decode_w4(t.code[u][2 * i], &c.q[0]);
-                decode_w4(t.code[u][2 * i + 1], &c.q[4]);
-            } else {
-                decode_w8(t.code[u][4 * i], &c.q[0]);
-                decode_w8(t.code[u][4 * i + 1], &c.q[2]);
-                decode_w8(t.code[u][4 * i + 2], &c.q[4]);
-                decode_w8(t.code[u][4 * i + 3], &c.q[6]);
-            }
-            const uint8_t* xg = xlds + slot + 16 * i;
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const uint8_t* xb = xg + b * (48 * KGP);
-                const uint4 xl = *reinterpret_cast<const uint4*>(xb);
-                const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
-                const float xs = *reinterpret_cast<const float*>(xlds + b * (48 * KGP) + 32 * KGP + (slot >> 2) + 4 * i);
-                const float d = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
-                dotz[b] = i == 0 ? d : dotz[b] + d;
-            }
-        }
         const bool head_here = (t.ix[u] & 1u) != 0;
         if (simple) {
 #pragma unroll
@@ -368,6 +344,51 @@ __device__ __forceinline__ void compute_tile(const Args& a, const MatArgs& m, co
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(s, dotz[b], acc[b]);
+        }
+    };
+
+    // (2)-(4) gather the activation group by real group index, dequantise, multiply
+    if constexpr (EAGER && NB == 1 && F::M == 1) {
+        uint4 xl[U], xh[U];
+        float xs[U], dotz[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t slot = t.ix[u] & 0xFFF0u;        // byte offset of the group's 16 activations
+            xl[u] = *reinterpret_cast<const uint4*>(xlds + slot);
+            xh[u] = *reinterpret_cast<const uint4*>(xlds + slot + 16 * KGP);
+            xs[u] = *reinterpret_cast<const float*>(xlds + 32 * KGP + (slot >> 2));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            Codes c;
+            decode_chunk<F>(t, u, 0, c);
+            const float z = half_to_float(t.sz[u] >> 16);
+            dotz[u] = __builtin_fmaf(-z, xs[u], dot16(c, xl[u], xh[u]));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) fold(u, &dotz[u]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float z = half_to_float(t.sz[u] >> 16);
+            const uint32_t slot = t.ix[u] & 0xFFF0u;
+            float dotz[NB];
+#pragma unroll
+            for (int i = 0; i < F::M; ++i) {                // the group's 16-element chunks
+                Codes c;
+                decode_chunk<F>(t, u, i, c);
+                const uint8_t* xg = xlds + slot + 16 * i;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const uint8_t* xb = xg + b * (48 * KGP);
+                    const uint4 xl = *reinterpret_cast<const uint4*>(xb);
+                    const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
+                    const float xs = *reinterpret_cast<const float*>(xlds + b * (48 * KGP) + 32 * KGP + (slot >> 2) + 4 * i);
+                    const float d = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
+                    dotz[b] = i == 0 ? d : dotz[b] + d;
+                }
+            }
+            fold(u, dotz);
         }
     }
 
@@ -542,74 +563,83 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
     }
 }
 
-// v_i for i < NM, chosen with scalar selects (arguments by value: an object holding them would
-// be indexed in memory).
-template <int NM>
-__device__ __forceinline__ int pick_of(int i, int v0, int v1, int v2, int v3)
+// Workgroup barrier for data exchanged through LDS only: the wavefront's LDS accesses have
+// completed; its loads from global memory that are still in flight stay in flight (a
+// __syncthreads() would wait for them too).
+__device__ __forceinline__ void lds_barrier()
 {
-    int r = v0;
-    if (NM > 1 && i == 1) r = v1;
-    if (NM > 2 && i == 2) r = v2;
-    if (NM > 3 && i == 3) r = v3;
-    return r;
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// One launch multiplies up to kMaxMatrices packed matrices that share x (q/k/v or gate/up of a
-// decoder layer) -- the wavefront walks its run in the first matrix, then its run in the
-// second, ... as one pipelined stream, so launch, x staging and first-byte latency are paid
-// once.  With one matrix this is the plain GEMV.
-struct ParkedArgs {
-    MatArgs m;
-    const int4* wave_info;
-};
-
 // The leading scalar parameters repeat what the first loads depend on (x, the first matrix's
-// run, the slot count, the wavefronts per workgroup): the file is compiled with kernel-argument
-// preloading for them, so they sit in scalar registers when a wavefront starts instead of being
-// fetched from the argument block first.  The block itself follows at byte kArgsOffset.
-static_assert(kArgsOffset == 2 * 8 + 8 * 4, "two pointers and eight ints precede the argument block");
-
-template <typename F, int KGP, int NB, int NM>
+// tile stream, worker table and deal, the slot count, the wavefronts per workgroup, where the
+// other matrices' workgroups begin): the file is compiled with kernel-argument preloading for
+// them, so they sit in scalar registers when a wavefront starts instead of being fetched from
+// the argument block first.  The block itself follows at byte kArgsOffset.
+template <typename F, int KGP, int NB>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
-    const uint16_t* x_first, const uint8_t* blocks_first, int per_wg_first, int extra_wg_first, int per_wave0_first,
-    int per_wave1_first, int extra_wave0_first, int extra_wave1_first, int kg_first, int wpw_first, GemvArgsT<NM> a)
+    const uint16_t* x, const uint8_t* blocks0, const int4_t* wave_info0, int base0, int extra0, int kg, int wpw,
+    int wg_end0, int wg_end1, int wg_end2, int n_wg0, LaunchArgs a)
 {
-    const MatRun run_first = {blocks_first, per_wg_first, extra_wg_first, {per_wave0_first, per_wave1_first},
-                              {extra_wave0_first, extra_wave1_first}};
-    // x arrays (NB * 48 * KGP bytes), then the wavefronts' records per matrix
+    // x arrays (NB * 48 * KGP bytes), then what the wavefronts tell each other about shared rows
     extern __shared__ __align__(16) uint8_t xlds[];
-    LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);            // [matrix][wavefront]
-    LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + NM * kWavesPerWorkgroup);  // [matrix][wavefront][NB]
-    // the output arguments of every matrix, parked for the fix-up at the end of the kernel (reading
-    // them from the argument block there would put a round trip on the kernel's tail)
-    ParkedArgs* parked = reinterpret_cast<ParkedArgs*>(rec_s + NM * kWavesPerWorkgroup * NB);
+    LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);      // [wavefront]
+    LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + kWavesPerWorkgroup);    // [wavefront][NB]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wpw = wpw_first;
     const int n_threads = wpw * kLanes;
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     const int wg = blockIdx.x;
-    const int wave = wg * wpw + wl;
-    constexpr int BB = F::BB;
 
-    // a worker's run of blocks in a matrix: the blocks are dealt evenly to the workgroups, a
-    // workgroup's blocks evenly to its wavefronts (contiguous runs, equal counts)
-    auto run_of = [&](const MatRun& r, int& left, const uint8_t*& p) {
-        const int big = wg < r.extra_wg ? 1 : 0;              // this workgroup holds per_wg + 1 blocks
-        const int wg_first = r.per_wg * wg + (big ? wg : r.extra_wg);
-        const int per_wave = r.per_wave[big], extra_wave = r.extra_wave[big];
-        left = per_wave + (wl < extra_wave ? 1 : 0);
-        p = r.blocks + static_cast<size_t>(wg_first + per_wave * wl + (wl < extra_wave ? wl : extra_wave)) * BB;
-    };
-    // superblocks of 4, 2, 1 blocks (as far as the format's largest superblock allows)
-    auto next_size = [](int n) { return n >= 4 && F::UMAX >= 4 ? 4 : (n >= 2 && F::UMAX >= 2 ? 2 : (n >= 1 ? 1 : 0)); };
+    // x goes out first: it is small, every wavefront of the workgroup needs it before it can
+    // use any weight, and loads return in the order of issue.  Slot c holds x[16c .. 16c+15]
+    // (x is [NB][K] contiguous); a thread's first two slots travel in registers.
+    constexpr int XPRE = 2;
+    const int n_slots = NB * kg;
+    uint4 xlo[XPRE], xhi[XPRE];
+#pragma unroll
+    for (int j = 0; j < XPRE; ++j) {
+        const int c = tid + j * n_threads;
+        xlo[j] = uint4{0, 0, 0, 0};
+        xhi[j] = uint4{0, 0, 0, 0};
+        if (c < n_slots) {
+            const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(c) * 16);
+            xlo[j] = src[0];
+            xhi[j] = src[1];
+        }
+    }
 
-    // issue the loads of x first and of the first superblock right behind them, so that the
-    // weights are already on their way while x is staged in LDS
+    // which matrix this workgroup works on, and which worker of that matrix this wavefront is
+    const int mi = (wg >= wg_end0 ? 1 : 0) + (wg >= wg_end1 ? 1 : 0) + (wg >= wg_end2 ? 1 : 0);
+    const int lwg = wg - (mi == 0 ? 0 : (mi == 1 ? wg_end0 : (mi == 2 ? wg_end1 : wg_end2)));
+    const int worker = lwg * wpw + wl;
+    const MatDesc md = matrix_desc(mi);
+    const uint8_t* blocks = blocks0;
+    const int4_t* wave_info = wave_info0;
+    int base = base0, extra = extra0, n_wg = n_wg0;
+    if (mi != 0) {      // (a branch, not a select: the first matrix's workgroups do not wait for the descriptor)
+        blocks = md.blocks;
+        wave_info = md.wave_info;
+        base = md.base;
+        extra = md.extra;
+        n_wg = md.n_wg;
+        asm volatile("" : "+s"(base));
+    }
+    // the worker's record {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}: requested
+    // here, between x and the tiles (loads return in the order of issue), with a vector load
+    // through a lane offset the compiler cannot see through -- a scalar load it would move to
+    // the first use of the record, where its latency would be in the way
+    int lane_zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+    const int4_t info_v = wave_info[worker + lane_zero];
+
+    const int n_tiles = base + (worker < extra ? 1 : 0);
+    const uint8_t* p = blocks + static_cast<size_t>(base * worker + (worker < extra ? worker : extra)) * F::TB;
+
     auto stage = [&](int c, uint4 lo, uint4 hi) {   // c = slot over all rows: b * kg + column
-        const int b = NB == 1 ? 0 : c / kg_first;
-        uint8_t* slot = xlds + b * (48 * KGP) + (c - b * kg_first) * 16;
+        const int b = NB == 1 ? 0 : c / kg;
+        uint8_t* slot = xlds + b * (48 * KGP) + (c - b * kg) * 16;
         *reinterpret_cast<uint4*>(slot) = lo;
         *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
@@ -619,231 +649,133 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
             s += half_to_float(w[i] & 0xFFFFu);
             s += half_to_float(w[i] >> 16);
         }
-        *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg_first) * 4) = s;
+        *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg) * 4) = s;
     };
-    const int n_slots = NB * kg_first;                  // x is [NB][K] contiguous: slot c holds x[16c .. 16c+15]
-
-    // the first matrix in which this worker owns blocks
-    int mi = 0, left = 0;
-    const uint8_t* p = nullptr;
-    run_of(run_first, left, p);
-    while (left == 0 && mi + 1 < NM) {
-        ++mi;
-        run_of(matrix_run<NM>(mi), left, p);
-    }
-    // The first superblock's loads go out first, x right behind them (both need only the first
-    // line of the argument block); then the per-matrix worker records (what the fix-up needs to
-    // know about this worker; a worker without blocks may still sit inside a row) and the
-    // output arguments; then x is staged in LDS.
-    Tile<F> cur, nxt;
-    int u_cur = next_size(left);
-    load_tile<F>(cur, p, u_cur, lane);
-    uint4 lo0 = {0, 0, 0, 0}, hi0 = {0, 0, 0, 0};
-    if (tid < n_slots) {
-        const uint4* src = reinterpret_cast<const uint4*>(x_first + static_cast<size_t>(tid) * 16);
-        lo0 = src[0];
-        hi0 = src[1];
-    }
-    // Everything else comes from later lines of the argument block and from the worker table:
-    // requested now, while the weights are on their way.  (Left alone, the compiler issues these
-    // loads where their results are first used -- after the wait for x -- and their latency
-    // would land on the critical path; the worker record is therefore fetched with a vector
-    // load through a lane offset the compiler cannot see through, and the arguments are pinned.)
-    int lane_zero;
-    asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
-    typedef int int4_t __attribute__((ext_vector_type(4)));
-    auto info_of = [&](int i) { return reinterpret_cast<const int4_t*>(a.wave_info[i])[wave + lane_zero]; };
-    const int4_t info0 = info_of(0);
-    const int4_t info1 = NM > 1 ? info_of(1) : int4_t{-1, 1, -1, 0};
-    const int4_t info2 = NM > 2 ? info_of(2) : int4_t{-1, 1, -1, 0};
-    const int4_t info3 = NM > 3 ? info_of(3) : int4_t{-1, 1, -1, 0};
-    MatArgs m = a.m[0];
-    if constexpr (NM > 1) m = matrix_args<NM>(mi);
-    asm volatile("" ::"s"(m.row_of_rank), "s"(m.y), "s"(m.N), "s"(m.n_ranks));
+    // x into LDS (the loads of the tiles are already out), then the workgroup meets
+    auto stage_x_and_meet = [&]() {
 #pragma unroll
-    for (int i = 0; i < NM; ++i)
-        asm volatile("" ::"s"(a.m[i].empty_rows), "s"(a.m[i].carry), "s"(a.m[i].counters), "s"(a.m[i].y),
-                     "s"(a.m[i].n_empty), "s"(a.wave_info[i]), "s"(a.n_wg));
-    if (tid < n_slots) stage(tid, lo0, hi0);
-    for (int c = tid + n_threads; c < n_slots; c += n_threads) {
-        const uint4* src = reinterpret_cast<const uint4*>(x_first + static_cast<size_t>(c) * 16);
-        stage(c, src[0], src[1]);
-    }
-    // rows without stored groups: exactly +0; and this worker's records start out as "nothing"
-#pragma unroll
-    for (int i = 0; i < NM; ++i) {
-        {
-            if (NM > 1 && tid == 0) parked[i] = ParkedArgs{a.m[i], a.wave_info[i]};
-            if (lane == 0) {
-                rec_n[i * kWavesPerWorkgroup + wl].heads = 0;
-#pragma unroll
-                for (int b = 0; b < NB; ++b) rec_s[(i * kWavesPerWorkgroup + wl) * NB + b] = LdsSums{0.0f, 0.0f};
-            }
-            for (int e = wg * n_threads + tid; e < a.m[i].n_empty; e += a.n_wg * n_threads) {
-                const int row = a.m[i].empty_rows[e];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) a.m[i].y[b * a.m[i].N + row] = 0;
-            }
+        for (int j = 0; j < XPRE; ++j) {
+            const int c = tid + j * n_threads;
+            if (c < n_slots) stage(c, xlo[j], xhi[j]);
         }
-    }
-    __syncthreads();
+        for (int c = tid + XPRE * n_threads; c < n_slots; c += n_threads) {
+            const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(c) * 16);
+            stage(c, src[0], src[1]);
+        }
+        lds_barrier();
+    };
+    // (after the barrier: the record is the oldest load still counted, long since there)
+    auto record = [&]() {
+        return int4_t{__builtin_amdgcn_readfirstlane(info_v.x), __builtin_amdgcn_readfirstlane(info_v.y),
+                      __builtin_amdgcn_readfirstlane(info_v.z), __builtin_amdgcn_readfirstlane(info_v.w)};
+    };
 
     WaveState<NB> st;
 #pragma unroll
     for (int b = 0; b < NB; ++b) { st.carry[b] = 0.0f; st.lead[b] = 0.0f; }
-    // The rank bases move to scalar registers here, where every load has arrived anyway: waiting
-    // for the worker records inside the loop would also wait for the superblock prefetched
-    // there, since loads complete in order.
-    const int rb0 = __builtin_amdgcn_readfirstlane(info0.x);
-    const int rb1 = NM > 1 ? __builtin_amdgcn_readfirstlane(info1.x) : 0;
-    const int rb2 = NM > 2 ? __builtin_amdgcn_readfirstlane(info2.x) : 0;
-    const int rb3 = NM > 3 ? __builtin_amdgcn_readfirstlane(info3.x) : 0;
-    asm volatile("" ::"s"(rb0), "s"(rb1), "s"(rb2), "s"(rb3));
-    auto rank_base_of = [=](int i) { return pick_of<NM>(i, rb0, rb1, rb2, rb3); };
-    st.rank = rank_base_of(mi);
     st.heads = 0;
-    WaveState<NB> fin = st;      // the finished run's sums (with one matrix the fix-up takes them from here)
-    if (u_cur > 0) {
-        for (;;) {
-            // where the stream goes on: the next superblock of this run, or the first one of the
-            // worker's run in the next matrix that has blocks for it
-            left -= u_cur;
-            const uint8_t* p_next = p + u_cur * BB;
-            int u_next = next_size(left);
-            int mi_next = mi;
-            while (u_next == 0 && mi_next + 1 < NM) {
-                ++mi_next;
-                run_of(matrix_run<NM>(mi_next), left, p_next);
-                u_next = next_size(left);
-            }
-            load_tile<F>(nxt, p_next, u_next, lane);   // in flight during this superblock
-            if constexpr (F::UMAX >= 4) {
-                if (u_cur == 4) compute_tile<F, KGP, 4, NB>(a, m, cur, lane, xlds, st);
-            }
-            if constexpr (F::UMAX >= 2) {
-                if (u_cur == 2) compute_tile<F, KGP, 2, NB>(a, m, cur, lane, xlds, st);
-            }
-            if (u_cur == 1) compute_tile<F, KGP, 1, NB>(a, m, cur, lane, xlds, st);
-            if (mi_next != mi || u_next == 0) {           // this matrix's run is complete
-                if (lane == 0) {
-                    rec_n[mi * kWavesPerWorkgroup + wl].heads = st.heads;   // (info is filled in below)
-#pragma unroll
-                    for (int b = 0; b < NB; ++b)
-                        rec_s[(mi * kWavesPerWorkgroup + wl) * NB + b] = LdsSums{st.lead[b], st.carry[b]};
-                }
-                if constexpr (NM > 1) {     // (with one matrix the state stays in registers for the fix-up)
-                    fin = st;
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) { st.carry[b] = 0.0f; st.lead[b] = 0.0f; }
-                    st.rank = rank_base_of(mi_next);
-                    st.heads = 0;
-                }
-            }
-            if (u_next == 0) break;
+    Tile<F> cur;
+    int4_t info;
+    if (n_tiles <= 1) {
+        // the whole run is one tile (the default partition's aim): nothing else is in flight
+        // behind it, and its blocks are consumed in the order in which they arrive
+        if (n_tiles == 1) load_tile<F>(cur, p, lane);
+        stage_x_and_meet();
+        info = record();
+        st.rank = info.x;
+        if (n_tiles == 1) compute_tile<F, KGP, NB, true>(md.out, cur, lane, xlds, st);
+    } else {
+        // a run of several tiles: the next tile is requested before the current one is worked on
+        // (the copy at the top of the loop is where the wavefront waits for a tile; inside
+        // compute_tile nothing waits for memory)
+        Tile<F> nxt;
+        load_tile<F>(nxt, p, lane);
+        stage_x_and_meet();
+        info = record();
+        st.rank = info.x;
+        for (int left = n_tiles; left > 0; --left) {
             cur = nxt;
-            u_cur = u_next;
-            p = p_next;
-            if (mi_next != mi) m = matrix_args<NM>(mi_next);
-            mi = mi_next;
+            p += F::TB;
+            if (left > 1) load_tile<F>(nxt, p, lane);      // in flight during this tile
+            compute_tile<F, KGP, NB, false>(md.out, cur, lane, xlds, st);
         }
     }
 
-    if constexpr (NM == 1) fin = st;
+    // rows without stored groups: exactly +0
+    for (int e = lwg * n_threads + tid; e < md.out.n_empty; e += n_wg * n_threads) {
+        const int row = md.out.empty_rows[e];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) md.out.y[b * md.out.N + row] = 0;
+    }
+
+    // A wavefront whose run neither continues an earlier worker's row nor leaves a row open has
+    // nothing to settle with its neighbours: it writes its last row and is done.  (A barrier
+    // does not wait for wavefronts that have ended.)
+    if (info.z < 0 && info.w == 0) {
+        if (lane == 0 && (info.y & 1) != 0 && st.heads > 0) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) store_row(md.out, b, info.x + st.heads, st.carry[b]);
+        }
+        return;
+    }
     // Carry fix-up for the rows a run shares with its neighbours.  Inside a workgroup the
     // pieces meet in LDS; only rows spread over several workgroups go through device memory.
     if (lane == 0) {
-        auto park = [&](int i, int4_t v) { rec_n[i * kWavesPerWorkgroup + wl].info = int4{v.x, v.y, v.z, v.w}; };  // (lane 0's copy)
-        park(0, info0);
-        if (NM > 1) park(1, info1);
-        if (NM > 2) park(2, info2);
-        if (NM > 3) park(3, info3);
-    }
-    __syncthreads();
-    if constexpr (NM == 1) {
-        if (lane != 0) return;
-        // everything this worker contributes is still in registers
-        fixup_matrix<NB>(a.m[0], a.wave_info[0], int4{info0.x, info0.y, info0.z, info0.w}, fin.heads,
-                         fin.lead, fin.carry, rec_n, rec_s, wl, wg, wpw, wave);
-    } else {
-        // lane i settles matrix i (side by side: the fix-up is a chain of dependent LDS reads)
-        if (lane >= NM) return;
-        const int i = lane;
-        const LdsCounts* cn = rec_n + i * kWavesPerWorkgroup;
-        const LdsSums* cs = rec_s + i * kWavesPerWorkgroup * NB;
-        float own_lead[NB], own_tail[NB];
+        rec_n[wl].info = int4{info.x, info.y, info.z, info.w};
+        rec_n[wl].heads = st.heads;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) { own_lead[b] = cs[wl * NB + b].lead; own_tail[b] = cs[wl * NB + b].tail; }
-        fixup_matrix<NB>(parked[i].m, parked[i].wave_info, cn[wl].info, cn[wl].heads, own_lead, own_tail, cn, cs,
-                         wl, wg, wpw, wave);
+        for (int b = 0; b < NB; ++b) rec_s[wl * NB + b] = LdsSums{st.lead[b], st.carry[b]};
     }
+    lds_barrier();
+    if (lane != 0) return;
+    fixup_matrix<NB>(md.out, reinterpret_cast<const int4*>(wave_info), int4{info.x, info.y, info.z, info.w}, st.heads,
+                     st.lead, st.carry, rec_n, rec_s, wl, lwg, wpw, worker);
 }
 
-// A launchable variant: the kernel for NM matrices takes the first NM entries of the host's
-// argument block.
+// A launchable variant of the kernel.
 struct Variant {
     const void* fn = nullptr;    // device function, for attribute setting
-    void (*launch)(const GemvArgs&, dim3, dim3, size_t, hipStream_t) = nullptr;
+    void (*launch)(const LaunchArgs&, const uint16_t*, int, int, const int*, dim3, dim3, size_t, hipStream_t) = nullptr;
     explicit operator bool() const { return fn != nullptr; }
 };
 
-constexpr size_t lds_bytes(int kgp, int nb, int nm)
+constexpr size_t lds_bytes(int kgp, int nb)
 {
-    return static_cast<size_t>(nb) * 48 * kgp +
-           nm * (kWavesPerWorkgroup * (sizeof(LdsCounts) + nb * sizeof(LdsSums)) + sizeof(ParkedArgs));
+    return static_cast<size_t>(nb) * 48 * kgp + kWavesPerWorkgroup * (sizeof(LdsCounts) + nb * sizeof(LdsSums));
 }
 
-template <int NM>
-GemvArgsT<NM> first_matrices(const GemvArgs& a)
+template <typename F, int KGP, int NB>
+void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg, int wpw, const int* wg_end, dim3 grid, dim3 block,
+                    size_t lds, hipStream_t s)
 {
-    GemvArgsT<NM> r{};
-    r.x = a.x; r.n_mats = NM; r.kg = a.kg;
-    r.wpw = a.wpw; r.n_wg = a.n_wg;
-    for (int i = 0; i < NM; ++i) { r.run[i] = a.run[i]; r.wave_info[i] = a.wave_info[i]; r.m[i] = a.m[i]; }
-    return r;
+    const MatDesc& m0 = a.m[0];
+    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB>), grid, block, lds, s, x, m0.blocks, m0.wave_info, m0.base,
+                       m0.extra, kg, wpw, wg_end[0], wg_end[1], wg_end[2], m0.n_wg, a);
 }
 
-template <typename F, int KGP, int NB, int NM>
-void launch_variant(const GemvArgs& a, dim3 grid, dim3 block, size_t lds, hipStream_t s)
-{
-    const MatRun& r = a.run[0];
-    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB, NM>), grid, block, lds, s, a.x, r.blocks, r.per_wg, r.extra_wg,
-                       r.per_wave[0], r.per_wave[1], r.extra_wave[0], r.extra_wave[1], a.kg, a.wpw, first_matrices<NM>(a));
-}
-
-template <typename F, int KGP, int NB, int NM>
+template <typename F, int KGP, int NB>
 Variant variant_if_it_fits()
 {
     Variant v;
-    if constexpr (lds_bytes(KGP, NB, NM) <= kMaxLdsBytes) {
-        v.fn = reinterpret_cast<const void*>(&gqsa_gemv_kernel<F, KGP, NB, NM>);
-        v.launch = &launch_variant<F, KGP, NB, NM>;
+    if constexpr (lds_bytes(KGP, NB) <= kMaxLdsBytes) {
+        v.fn = reinterpret_cast<const void*>(&gqsa_gemv_kernel<F, KGP, NB>);
+        v.launch = &launch_variant<F, KGP, NB>;
     }
     return v;
 }
 
-// Compiled variants.  Group size 16: 1, 2, 4 or 8 activation rows for one matrix (as far as NB
-// copies of x fit the 160 KB of LDS), and 2, 3 or 4 matrices for one activation row.  Larger
-// groups: one activation row, one matrix.
+// Compiled variants.  Group size 16: 1, 2, 4 or 8 activation rows per launch (as far as NB
+// copies of x fit the 160 KB of LDS).  Larger groups: one activation row.
 template <typename F, int KGP>
-Variant pick_variant(int nb, int nm)
+Variant pick_variant(int nb)
 {
+    if (nb == 1) return variant_if_it_fits<F, KGP, 1>();
     if constexpr (F::M == 1) {
-        if (nm == 1) {
-            switch (nb) {
-                case 1: return variant_if_it_fits<F, KGP, 1, 1>();
-                case 2: return variant_if_it_fits<F, KGP, 2, 1>();
-                case 4: return variant_if_it_fits<F, KGP, 4, 1>();
-                case 8: return variant_if_it_fits<F, KGP, 8, 1>();
-            }
-        } else if (nb == 1) {
-            switch (nm) {
-                case 2: return variant_if_it_fits<F, KGP, 1, 2>();
-                case 3: return variant_if_it_fits<F, KGP, 1, 3>();
-                case 4: return variant_if_it_fits<F, KGP, 1, 4>();
-            }
+        switch (nb) {
+            case 2: return variant_if_it_fits<F, KGP, 2>();
+            case 4: return variant_if_it_fits<F, KGP, 4>();
+            case 8: return variant_if_it_fits<F, KGP, 8>();
         }
-    } else {
-        if (nm == 1 && nb == 1) return variant_if_it_fits<F, KGP, 1, 1>();
     }
     return Variant{};
 }
@@ -851,32 +783,32 @@ Variant pick_variant(int nb, int nm)
 // The kernel is compiled for counts of 16-element activation slots (K/16) rounded up to a power
 // of two (the LDS offsets between the x arrays are immediates).
 template <typename F>
-Variant pick_kernel(int slots, int nb, int nm, int* kgp)
+Variant pick_kernel(int slots, int nb, int* kgp)
 {
-    if (slots <= 256) { *kgp = 256; return pick_variant<F, 256>(nb, nm); }
-    if (slots <= 512) { *kgp = 512; return pick_variant<F, 512>(nb, nm); }
-    if (slots <= 1024) { *kgp = 1024; return pick_variant<F, 1024>(nb, nm); }
-    if (slots <= 2048) { *kgp = 2048; return pick_variant<F, 2048>(nb, nm); }
+    if (slots <= 256) { *kgp = 256; return pick_variant<F, 256>(nb); }
+    if (slots <= 512) { *kgp = 512; return pick_variant<F, 512>(nb); }
+    if (slots <= 1024) { *kgp = 1024; return pick_variant<F, 1024>(nb); }
+    if (slots <= 2048) { *kgp = 2048; return pick_variant<F, 2048>(nb); }
     *kgp = 0;
     return Variant{};
 }
 
-Variant pick(const gqsa_matrix* m, int nb, int nm, int* kgp)
+Variant pick(const gqsa_matrix* m, int nb, int* kgp)
 {
     const int slots = static_cast<int>(m->K / 16);
     *kgp = 0;
     if (m->bits == 4) {
         switch (m->G) {
-            case 16: return pick_kernel<Fmt<4, 1>>(slots, nb, nm, kgp);
-            case 32: return pick_kernel<Fmt<4, 2>>(slots, nb, nm, kgp);
-            case 64: return pick_kernel<Fmt<4, 4>>(slots, nb, nm, kgp);
-            case 128: return pick_kernel<Fmt<4, 8>>(slots, nb, nm, kgp);
+            case 16: return pick_kernel<Fmt<4, 1>>(slots, nb, kgp);
+            case 32: return pick_kernel<Fmt<4, 2>>(slots, nb, kgp);
+            case 64: return pick_kernel<Fmt<4, 4>>(slots, nb, kgp);
+            case 128: return pick_kernel<Fmt<4, 8>>(slots, nb, kgp);
         }
     } else if (m->bits == 8) {
         switch (m->G) {
-            case 16: return pick_kernel<Fmt<8, 1>>(slots, nb, nm, kgp);
-            case 32: return pick_kernel<Fmt<8, 2>>(slots, nb, nm, kgp);
-            case 64: return pick_kernel<Fmt<8, 4>>(slots, nb, nm, kgp);
+            case 16: return pick_kernel<Fmt<8, 1>>(slots, nb, kgp);
+            case 32: return pick_kernel<Fmt<8, 2>>(slots, nb, kgp);
+            case 64: return pick_kernel<Fmt<8, 4>>(slots, nb, kgp);
         }
     }
     return Variant{};
@@ -909,16 +841,14 @@ constexpr size_t carry_workspace_bytes(int n_waves)
 gqsa_status_t device_upload(gqsa_matrix* m)
 {
     int kgp = 0;
-    if (!pick(m, 1, 1, &kgp)) return GQSA_ERR_UNSUPPORTED;   // K/G above 2048: x does not fit the LDS layout
+    if (!pick(m, 1, &kgp)) return GQSA_ERR_UNSUPPORTED;   // K/16 above 2048: x does not fit the LDS layout
     int dev = 0;
     GQSA_HIP(hipGetDevice(&dev));
     for (int nb = 1; nb <= kMaxRowsPerLaunch; nb *= 2) {
-        for (int nm = 1; nm <= kMaxMatrices; ++nm) {
-            Variant v = pick(m, nb, nm, &kgp);
-            if (v && lds_bytes(kgp, nb, nm) > 64 * 1024)
-                GQSA_HIP(hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             static_cast<int>(lds_bytes(kgp, nb, nm))));
-        }
+        Variant v = pick(m, nb, &kgp);
+        if (v && lds_bytes(kgp, nb) > 64 * 1024)
+            GQSA_HIP(hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         static_cast<int>(lds_bytes(kgp, nb))));
     }
     void* img = nullptr;
     void* carry = nullptr;
@@ -950,6 +880,68 @@ void device_release(gqsa_matrix* m)
     m->d_carry = nullptr;
 }
 
+namespace {
+
+// Wavefronts per workgroup of a launch of nb activation rows on these matrices, 0 if they
+// cannot share a launch.  One activation row: the partition's own grouping.  Several rows (x
+// takes nb times the LDS, so fewer workgroups fit a compute unit): 8-wavefront partitions are
+// taken sixteen wavefronts to a workgroup where the worker count allows and still gives every
+// compute unit a workgroup (the deal of tiles to workers does not depend on the grouping).
+int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb)
+{
+    const int wpw = ms[0]->waves_per_workgroup;
+    bool regroup = nb > 1 && wpw == 8;
+    int workers = 0;
+    for (int i = 0; i < n_mats; ++i) {
+        if (ms[i]->waves_per_workgroup != wpw) return 0;
+        if (ms[i]->n_waves % kWavesPerWorkgroup != 0) regroup = false;
+        workers += ms[i]->n_waves;
+    }
+    if (workers / kWavesPerWorkgroup < kMaxDefaultWorkgroups) regroup = false;   // not at the price of idle compute units
+    return regroup ? kWavesPerWorkgroup : wpw;
+}
+
+// One launch: nb activation rows (1, 2, 4 or 8) times n_mats matrices that share x and the
+// wavefronts per workgroup.
+gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint16_t* const* ys, int nb, int wpw,
+                     hipStream_t s)
+{
+    const gqsa_matrix* m0 = ms[0];
+    int kgp = 0;
+    const Variant v = pick(m0, nb, &kgp);
+    if (!v) return GQSA_ERR_UNSUPPORTED;
+    LaunchArgs a{};
+    int wg_end[kMaxMatrices] = {INT_MAX, INT_MAX, INT_MAX, INT_MAX};
+    int grid = 0;
+    for (int i = 0; i < n_mats; ++i) {
+        const gqsa_matrix* m = ms[i];
+        const uint8_t* img = static_cast<const uint8_t*>(m->d_image);
+        MatDesc& d = a.m[i];
+        d.blocks = img + m->map.blocks;
+        d.wave_info = reinterpret_cast<const int4_t*>(img + m->map.wave_info);
+        d.base = static_cast<int>(m->n_tiles / m->n_waves);
+        d.extra = static_cast<int>(m->n_tiles % m->n_waves);
+        d.n_wg = m->n_waves / wpw;
+        MatArgs& o = d.out;
+        o.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
+        o.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
+        o.carry = static_cast<CarryRecord*>(m->d_carry);
+        uint8_t* ws = static_cast<uint8_t*>(m->d_carry);
+        o.counters = reinterpret_cast<int*>(ws + counters_offset(m->n_waves));
+        o.slots = reinterpret_cast<unsigned long long*>(ws + slots_offset(m->n_waves));
+        o.y = ys[i];
+        o.N = m->N;
+        o.n_empty = static_cast<int>(m->n_empty);
+        o.n_ranks = static_cast<int>(m->N - m->n_empty);
+        grid += d.n_wg;
+        if (i + 1 < n_mats) wg_end[i] = grid;
+    }
+    v.launch(a, x, static_cast<int>(m0->K / 16), wpw, wg_end, dim3(grid), dim3(wpw * kLanes), lds_bytes(kgp, nb), s);
+    return GQSA_OK;
+}
+
+}  // namespace
+
 gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,
                           void* stream)
 {
@@ -960,71 +952,29 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
     GQSA_HIP(hipGetDevice(&dev));
     for (int i = 0; i < n_mats; ++i)
         if (ms[i]->device != dev) return GQSA_ERR_HIP;
-    GemvArgs a{};
-    for (int i = 0; i < n_mats; ++i) {
-        const gqsa_matrix* m = ms[i];
-        const uint8_t* img = static_cast<const uint8_t*>(m->d_image);
-        MatRun& r = a.run[i];
-        r.blocks = img + m->map.blocks;
-        a.wave_info[i] = reinterpret_cast<const int4*>(img + m->map.wave_info);
-        r.per_wg = static_cast<int>(m->n_blocks / m->n_workgroups);
-        r.extra_wg = static_cast<int>(m->n_blocks % m->n_workgroups);
-        for (int big = 0; big < 2; ++big) {
-            r.per_wave[big] = (r.per_wg + big) / m->waves_per_workgroup;
-            r.extra_wave[big] = (r.per_wg + big) % m->waves_per_workgroup;
+    // the batch goes out in launches of 8, 4, 2 or 1 rows: the most that the format has a
+    // kernel for, fits LDS and is left
+    int done = 0;
+    while (done < batch) {
+        int nb = kMaxRowsPerLaunch, kgp = 0;
+        for (; nb >= 1; nb /= 2) {
+            if (nb <= batch - done && pick(m0, nb, &kgp)) break;
         }
-        MatArgs& o = a.m[i];
-        o.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
-        o.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
-        o.carry = static_cast<CarryRecord*>(m->d_carry);
-        uint8_t* ws = static_cast<uint8_t*>(m->d_carry);
-        o.counters = reinterpret_cast<int*>(ws + counters_offset(m->n_waves));
-        o.slots = reinterpret_cast<unsigned long long*>(ws + slots_offset(m->n_waves));
-        o.N = m->N;
-        o.n_empty = static_cast<int>(m->n_empty);
-        o.n_ranks = static_cast<int>(m->N - m->n_empty);
-    }
-    a.n_mats = n_mats;
-    a.wpw = m0->waves_per_workgroup;
-    a.n_wg = m0->n_workgroups;
-    a.kg = static_cast<int>(m0->K / 16);       // 16-element activation slots
-
-    const int threads = m0->waves_per_workgroup * kLanes;
-    const int grid = m0->n_workgroups;
-    int kgp_multi = 0;
-    const Variant multi = (n_mats > 1 && batch == 1) ? pick(m0, 1, n_mats, &kgp_multi) : Variant{};
-    if (multi) {
-        // several matrices, one activation row: one launch walks them all
-        const int kgp = kgp_multi;
-        const Variant v = multi;
-        a.x = static_cast<const uint16_t*>(x);
-        for (int i = 0; i < n_mats; ++i) a.m[i].y = static_cast<uint16_t*>(ys[i]);
-        v.launch(a, dim3(grid), dim3(threads), lds_bytes(kgp, 1, n_mats), s);
-    } else {
-        // one matrix at a time; its batch goes out in launches of 8, 4, 2 or 1 rows: the most
-        // that the format has a kernel for, fits LDS and is left
-        for (int i = 0; i < n_mats; ++i) {
-            GemvArgs one = a;
-            one.n_mats = 1;
-            one.run[0] = a.run[i];
-            one.wave_info[0] = a.wave_info[i];
-            one.m[0] = a.m[i];
-            int done = 0;
-            while (done < batch) {
-                int nb = kMaxRowsPerLaunch, kgp = 0;
-                Variant v;
-                for (; nb >= 1; nb /= 2) {
-                    if (nb > batch - done) continue;
-                    v = pick(m0, nb, 1, &kgp);
-                    if (v) break;
-                }
-                if (!v) return GQSA_ERR_UNSUPPORTED;
-                one.x = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m0->K;
-                one.m[0].y = static_cast<uint16_t*>(ys[i]) + static_cast<size_t>(done) * ms[i]->N;
-                v.launch(one, dim3(grid), dim3(threads), lds_bytes(kgp, nb, 1), s);
-                done += nb;
+        if (nb < 1) return GQSA_ERR_UNSUPPORTED;
+        const uint16_t* xb = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m0->K;
+        uint16_t* yb[kMaxMatrices];
+        for (int i = 0; i < n_mats; ++i) yb[i] = static_cast<uint16_t*>(ys[i]) + static_cast<size_t>(done) * ms[i]->N;
+        const int together = launch_waves_per_workgroup(ms, n_mats, nb);
+        if (together > 0) {
+            // one launch for all the matrices
+            if (gqsa_status_t st = launch(ms, n_mats, xb, yb, nb, together, s)) return st;
+        } else {
+            for (int i = 0; i < n_mats; ++i) {
+                const int wpw = launch_waves_per_workgroup(ms + i, 1, nb);
+                if (gqsa_status_t st = launch(ms + i, 1, xb, yb + i, nb, wpw, s)) return st;
             }
         }
+        done += nb;
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;

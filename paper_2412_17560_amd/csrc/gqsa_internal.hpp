@@ -19,6 +19,9 @@ constexpr int kMaxMatricesPerLaunch = 4;
 constexpr int64_t kMaxGroupColumns = 4096;  // 16-element slots of K: 12-bit slot << 4 | head flag in 16 bits
 constexpr size_t kAlign = 256;
 
+// Blocks per tile (superblock) for a format with `code_bytes` bytes of codes per group.
+constexpr int largest_tile(int code_bytes) { return code_bytes <= 16 ? 4 : (code_bytes <= 32 ? 2 : 1); }
+
 // Offsets (bytes) of the regions inside the device image.
 struct ImageMap {
     size_t blocks = 0;      // n_blocks * block_bytes
@@ -51,7 +54,8 @@ struct gqsa_matrix {
     int n_workgroups = 0;
     int waves_per_workgroup = 0;
     int n_waves = 0;          // n_workgroups * waves_per_workgroup
-    int64_t n_blocks = 0;
+    int64_t n_blocks = 0;     // 64-group blocks of the padded stream = n_tiles * largest_tile(code_bytes)
+    int64_t n_tiles = 0;
     int64_t n_empty = 0;
     int needs_fixup = 0;
     gqsa::ImageMap map;
@@ -72,7 +76,7 @@ namespace gqsa {
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          const int32_t* keep_per_row, double sparsity, const float* hinv_diag,
                          gqsa_matrix* m);
-void default_partition(int64_t n_blocks, int G, int* n_workgroups, int* waves_per_workgroup);
+void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves_per_workgroup);
 gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup);
 
 // device side (gqsa_gemv.hip)

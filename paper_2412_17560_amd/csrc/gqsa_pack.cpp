@@ -192,24 +192,43 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
 // blocks, and in a workgroup as many wavefronts (at most 16, at most one per block) as give
 // every wavefront about two blocks' worth of 16-element chunks -- matrices of a few MB are bound
 // by how many compute units pull on memory, not by how long a wavefront's run is.
-void default_partition(int64_t n_blocks, int G, int* n_workgroups, int* waves_per_workgroup)
+// Default partition.  The stream is cut into tiles (superblocks) of u_max blocks; a worker
+// (wavefront) holds whole tiles.  One tile per worker -- everything it needs requested at once,
+// one segmented scan to settle it -- as long as the workers are all resident at the same time:
+// a compute unit holds three workgroups of eight wavefronts of this kernel (fewer when x, 48
+// bytes of LDS per 16-element slot of K with the slots rounded up to a power of two >= 256,
+// leaves room for fewer), and a launch may carry two or three matrices (q/k/v, gate/up), so a
+// matrix gets half of the 256 compute units' wavefront slots: beyond that a worker holds 2, 3,
+// ... tiles.  Workgroups of 8 wavefronts; of 4, 2 or 1 when that spreads a small matrix over
+// more compute units.  An even number of 8-wavefront workgroups, so that the small-batch kernels can
+// take the same workers sixteen to a workgroup.
+void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves_per_workgroup)
 {
-    const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>(kMaxDefaultWorkgroups, n_blocks));
-    const int64_t per_wg = std::max<int64_t>(1, (n_blocks + wgs - 1) / wgs);
-    const int64_t chunks = n_blocks * (G / 16);
-    const int64_t want = (chunks + 2 * wgs - 1) / (2 * wgs);
-    *n_workgroups = static_cast<int>(wgs);
-    *waves_per_workgroup = static_cast<int>(std::max<int64_t>(1, std::min<int64_t>({kWavesPerWorkgroup, per_wg, want})));
+    int64_t slots = 256;
+    while (slots < K / 16) slots *= 2;
+    const int64_t wgs_per_cu = std::max<int64_t>(1, std::min<int64_t>(3, (160 * 1024) / (48 * slots)));
+    const int64_t budget = kMaxDefaultWorkgroups * wgs_per_cu * 8 / 2;
+    const int64_t per_worker = std::max<int64_t>(1, (n_tiles + budget - 1) / budget);
+    const int64_t workers = std::max<int64_t>(1, (n_tiles + per_worker - 1) / per_worker);
+    int64_t wpw = 1;
+    while (wpw < 8 && kMaxDefaultWorkgroups * wpw < workers) wpw *= 2;
+    int64_t wgs = (workers + wpw - 1) / wpw;
+    if (wpw == 8 && wgs > 1 && (wgs & 1)) ++wgs;
+    *n_workgroups = static_cast<int>(std::min<int64_t>(wgs, kMaxWorkgroups));
+    *waves_per_workgroup = static_cast<int>(wpw);
 }
 
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
-// 64-group blocks and dealt in contiguous, near-equal runs first to the workgroups and then,
-// inside each workgroup, to its wavefronts (the nnz-balanced version of the paper's
-// task-centric split, Sec. 3.5; a row may be shared by neighbouring wavefronts).  Inside a run the
-// blocks are taken 4, then 2, then 1 at a time ("superblocks"; at most 2 at a time with 32 code
-// bytes per group, 1 with 64); in a superblock of U blocks lane l owns U consecutive stream
-// positions, stored one per block so that every block is a fully coalesced, lane-interleaved load:
-//     stream position (first of superblock) + p  ->  block (p mod U), lane (p div U).
+// 64-group blocks; u_max blocks make a tile (superblock): 4 blocks with up to 16 code bytes per
+// group, 2 with 32, 1 with 64 (a wavefront's tile stays within about 24 registers).  The stream
+// is padded with null groups to whole tiles.  The tiles are dealt in contiguous, near-equal runs
+// to the n_workgroups * waves_per_workgroup workers (wavefronts): worker w gets n_tiles div
+// workers tiles, one more if w < n_tiles mod workers (the nnz-balanced version of the paper's
+// task-centric split, Sec. 3.5; a row may be shared by neighbouring wavefronts).  The deal does
+// not depend on how the workers are grouped into workgroups, so a launch may group them
+// differently.  In a tile of U blocks lane l owns U consecutive stream positions, stored one
+// per block so that every block is a fully coalesced, lane-interleaved load:
+//     stream position (first of the tile) + p  ->  block (p mod U), lane (p div U).
 // Block = code planes | 64 x (scale | zero << 16) | 64 x (16 * LDS slot | head).  A group of
 // G = 16 M elements has G*bits/8 code bytes; plane k holds bytes 16k..16k+15 of every lane's
 // code string (a single plane of 8 bytes per lane for 4-bit, G = 16).  The index word is the
@@ -223,8 +242,11 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     if (waves_per_workgroup < 1 || waves_per_workgroup > kWavesPerWorkgroup) return GQSA_ERR_RANGE;
     const int n_waves = n_workgroups * waves_per_workgroup;
     const int64_t nnz = m->nnzg();
-    const int64_t nb = (nnz + kLanes - 1) / kLanes;
     const int cb = m->code_bytes();
+    const int u_max = largest_tile(cb);
+    const int64_t tile_groups = static_cast<int64_t>(kLanes) * u_max;
+    const int64_t n_tiles = (nnz + tile_groups - 1) / tile_groups;
+    const int64_t nb = n_tiles * u_max;
     const size_t bb = static_cast<size_t>(m->block_bytes());
     auto align = [](size_t v) { return (v + kAlign - 1) / kAlign * kAlign; };
 
@@ -282,9 +304,6 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * chunks) << 4) | (head[g] ? 1 : 0));
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
-    // the largest superblock: as many blocks as keep a wavefront's tile within about 24 registers
-    const int u_max = cb <= 16 ? 4 : (cb <= 32 ? 2 : 1);
-
     // Per worker: {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}.
     //   rank_base   rank (among non-empty rows) of the row that is open when the run starts,
     //               i.e. (row heads before the run) - 1
@@ -303,20 +322,11 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         return static_cast<int64_t>(std::lower_bound(head_pos.begin(), head_pos.end(), pos) -
                                     head_pos.begin());
     };
-    // two-level deal: blocks -> workgroups -> wavefronts
+    // flat deal: tiles -> workers
     std::vector<int64_t> first_block(static_cast<size_t>(n_waves) + 1, 0);
     {
-        const int64_t per_wg = nb / n_workgroups, extra_wg = nb % n_workgroups;
-        int64_t b = 0;
-        for (int g = 0; g < n_workgroups; ++g) {
-            const int64_t in_wg = per_wg + (g < extra_wg ? 1 : 0);
-            const int64_t per_wave = in_wg / waves_per_workgroup, extra_wave = in_wg % waves_per_workgroup;
-            for (int l = 0; l < waves_per_workgroup; ++l) {
-                first_block[static_cast<size_t>(g) * waves_per_workgroup + l] = b;
-                b += per_wave + (l < extra_wave ? 1 : 0);
-            }
-        }
-        first_block[n_waves] = b;
+        const int64_t base = n_tiles / n_waves, extra = n_tiles % n_waves;
+        for (int w = 0; w <= n_waves; ++w) first_block[w] = (base * w + std::min<int64_t>(w, extra)) * u_max;
     }
     auto worker_of = [&](int64_t pos) {   // the worker whose run contains stream position pos
         const int64_t blk = pos / kLanes;
@@ -330,14 +340,11 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         const int64_t mine = first_block[w + 1] - block0;
         const int64_t first = block0 * kLanes;
         const int64_t end = (block0 + mine) * kLanes;
-        int64_t pos = first, blk = block0, left = mine;
-        while (left > 0) {
-            const int U = (left >= 4 && u_max >= 4) ? 4 : ((left >= 2 && u_max >= 2) ? 2 : 1);
-            for (int p = 0; p < kLanes * U && pos + p < nnz; ++p)
-                put_group(pos + p, blk + p % U, p / U);
-            pos += static_cast<int64_t>(kLanes) * U;
-            blk += U;
-            left -= U;
+        int64_t pos = first;
+        for (int64_t blk = block0; blk < block0 + mine; blk += u_max) {
+            for (int p = 0; p < kLanes * u_max && pos + p < nnz; ++p)
+                put_group(pos + p, blk + p % u_max, p / u_max);
+            pos += tile_groups;
         }
         const int64_t hb = heads_below(std::min(first, nnz));
         const int64_t he = heads_below(std::min(end, nnz));
@@ -367,6 +374,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     m->waves_per_workgroup = waves_per_workgroup;
     m->n_waves = n_waves;
     m->n_blocks = nb;
+    m->n_tiles = n_tiles;
     m->n_empty = static_cast<int64_t>(empty.size());
     m->needs_fixup = fix;
     return GQSA_OK;

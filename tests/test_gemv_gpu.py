@@ -59,7 +59,7 @@ def test_tiny_config(torch_cuda):
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("sparsity", [0.0, 0.3, 0.5, 0.7, 1.0])
 def test_balanced_ragged_shapes(torch_cuda, bits, sparsity):
-    # 301 rows x 61 group-columns: nothing aligns with 64-group blocks or 256-group superblocks
+    # 301 rows x 61 group-columns: nothing aligns with 64-group blocks or 256-group tiles
     N, K = 301, 976
     W = gi.dense_weight(N, K, seed=100 + bits)
     h = gq.gqsa_pack(W, 16, bits, sparsity)
@@ -238,11 +238,14 @@ def test_gemv_error_paths_on_device(torch_cuda):
 
 # ----------------------------------------------------------------------------- several matrices, one launch
 
-@pytest.mark.parametrize("part", [None, (3, 4), (1, 16), (40, 2)])
-@pytest.mark.parametrize("batch", [1, 3])
+@pytest.mark.parametrize("part", [None, "mixed", (3, 4), (1, 16), (40, 2), (2, 8)])
+@pytest.mark.parametrize("batch", [1, 3, 8])
 def test_gemv_multi_equals_separate_calls(torch_cuda, part, batch):
     """q/k/v-style: matrices of different N sharing x; the fused launch must give the bits of the
-    separate calls (and both must match the oracle)."""
+    separate calls (and both must match the oracle).  Partitions: the defaults (wavefronts per
+    workgroup differ with the size: separate launches behind the call), different worker counts
+    with the same workgroup size (one launch, each matrix its own share of the grid), equal ones;
+    (2, 8) is taken sixteen wavefronts to a workgroup by the launches of several rows."""
     torch = torch_cuda
     K = 2048
     shapes = [(300, 0.5, None), (64, 0.0, None), (257, None, "imbalanced"), (128, 1.0, None)]
@@ -256,10 +259,10 @@ def test_gemv_multi_equals_separate_calls(torch_cuda, part, batch):
         else:
             h = gq.gqsa_pack(W, 16, 4, sp)
             c = oracle.pack(W, 16, 4, sparsity=sp)
-        if part:
+        if part == "mixed":
+            gq.gqsa_set_partition(h, (5, 1, 9, 2)[i], 4)
+        elif part:
             gq.gqsa_set_partition(h, *part)
-        else:
-            gq.gqsa_set_partition(h, 16, 16)       # equal partition for all four (defaults differ with size)
         hs.append(h)
         cs.append(c)
     x_np = gi.activations(batch, K, seed=77)
@@ -296,9 +299,8 @@ def test_gemv_multi_error_paths(torch_cuda):
         gq.gqsa_gemv_multi([h1, h2], x, y[:2])      # K differs: refused by the binding
     h3 = gq.gqsa_pack(gi.dense_weight(32, 256, seed=3), 16, 4, 0.5)
     gq.gqsa_set_partition(h3, 2, 8)
-    with pytest.raises(gq.GqsaError) as e:
-        gq.gqsa_gemv_multi([h1, h3], x, y[:2])      # partitions differ
-    assert e.value.status == 2
+    gq.gqsa_gemv_multi([h1, h3], x, y[:2])          # partitions may differ
+    torch.cuda.synchronize()
 
 
 @pytest.mark.parametrize("bits", [4, 8])
@@ -330,8 +332,8 @@ def test_largest_and_smallest_reduction_lengths(torch_cuda, bits):
 @pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 @pytest.mark.parametrize("part", [None, (5, 3), (2, 16)])
 def test_other_group_sizes(torch_cuda, bits, G, part):
-    """G = 32, 64, 128: several 16-element chunks per stored group, code planes, capped
-    superblocks; rows of very different lengths, shared rows, empty rows; batch 1 and 3."""
+    """G = 32, 64, 128: several 16-element chunks per stored group, code planes, smaller
+    tiles; rows of very different lengths, shared rows, empty rows; batch 1 and 3."""
     N, K = 150, 2048
     W = gi.dense_weight(N, K, seed=91)
     keep = gi.imbalanced_keep_counts(N, K // G, seed=91)

@@ -15,116 +15,95 @@ from oracle import layout
 
 
 def test_default_partition():
-    assert oracle.default_partition(0) == (1, 1)
-    assert oracle.default_partition(2048) == (32, 1)            # 32 blocks -> one per workgroup
-    assert oracle.default_partition(64 * 17) == (17, 1)
-    assert oracle.default_partition(524288) == (256, 16)        # 8192 blocks: 32 per workgroup, 2 per wavefront
-    assert oracle.default_partition(64 * 4096) == (256, 8)      # 16 per workgroup -> 8 wavefronts of 2
-    assert oracle.default_partition(64 * 1000) == (256, 2)      # 4 (some 3) per workgroup
-    assert oracle.default_partition(64 * 2048) == (256, 4)
-    assert oracle.default_partition(64 * 1024, G=128) == (256, 4)   # heavy groups: one block per wavefront
-    assert oracle.default_partition(64 * 2048, G=64) == (256, 8)
-    assert oracle.default_partition(1409024) == (256, 16)       # 11008x4096 at S = 50 %
+    assert oracle.default_partition(0, 4096) == (1, 1)
+    assert oracle.default_partition(2048, 256) == (8, 1)              # 8 tiles of 256 groups, one per worker
+    assert oracle.default_partition(256 * 17, 4096) == (17, 1)
+    assert oracle.default_partition(256 * 600, 4096) == (150, 4)      # 600 workers: 4 to a workgroup cover them with <= 256 workgroups
+    assert oracle.default_partition(524288, 4096) == (256, 8)         # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront
+    assert oracle.default_partition(1409024, 4096) == (344, 8)        # 11008x4096: 5504 tiles, two per worker
+    assert oracle.default_partition(1409024, 11008) == (344, 8)       # 4096x11008: 48 KiB of LDS for x, still 3 workgroups
+    assert oracle.default_partition(256 * 2049, 4096) == (258, 8)     # 2049 workers -> 257 workgroups -> an even count
+    assert oracle.default_partition(256 * 3072, 4096) == (384, 8)     # the budget: half of 256 x 3 x 8 wavefronts
+    assert oracle.default_partition(256 * 3073, 4096) == (194, 8)     # beyond it two tiles per worker: 1537 workers
+    assert oracle.default_partition(256 * 3072, 32768) == (256, 4)    # x takes 96 KiB: one workgroup per compute unit -> 1024 workers of 3 tiles
+    assert oracle.default_partition(64 * 1024, 4096, G=128) == (256, 4)   # 64 code bytes: a tile is one block, 1024 tiles
+    assert oracle.default_partition(128 * 2048, 4096, G=16, bits=8) == (256, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
 
 
-def test_two_level_block_deal_by_hand():
-    # 23 blocks over 3 workgroups of 4 wavefronts: workgroups get 8, 8, 7; inside: 2,2,2,2 / 2,2,2,2 / 2,2,2,1
-    assert list(layout.worker_block_counts(23, 3, 4)) == [2, 2, 2, 2, 2, 2, 2, 2, 2, 2, 2, 1]
-    # 5 blocks over 2 workgroups of 4: 3 and 2 -> 1,1,1,0 / 1,1,0,0
-    assert list(layout.worker_block_counts(5, 2, 4)) == [1, 1, 1, 0, 1, 1, 0, 0]
-    # LLaMA-7B down_proj at W4S50: 22016 blocks over 256 x 16 -> 86 per workgroup = 6x6 + 10x5
-    c = layout.worker_block_counts(22016, 256, 16)
-    assert list(c[:16]) == [6] * 6 + [5] * 10 and c.sum() == 22016
+def test_tile_deal_by_hand():
+    # 23 tiles of 4 blocks over 12 workers: 1 each, the first 11 one more
+    assert list(layout.worker_block_counts(92, 12, 4)) == [8] * 11 + [4]
+    # 5 tiles of 2 blocks over 8 workers
+    assert list(layout.worker_block_counts(10, 8, 2)) == [2, 2, 2, 2, 2, 0, 0, 0]
+    # LLaMA-7B down_proj at W4S50: 5504 tiles over 344 x 8 workers, two each
+    c = layout.worker_block_counts(22016, 2752, 4)
+    assert set(c) == {8} and c.sum() == 22016
 
 
-def test_placement_single_worker_7_blocks_by_hand():
-    block, lane, b_w, _ = layout.stream_placement(7, 1, 1)
+def test_placement_single_worker_2_tiles_by_hand():
+    block, lane, b_w, _ = layout.stream_placement(8, 1, 4)
     assert list(b_w) == [0]
-    # superblock of 4 blocks: position p -> block p mod 4, lane p div 4
+    # tile of 4 blocks: position p -> block p mod 4, lane p div 4
     assert (block[0], lane[0]) == (0, 0)
     assert (block[1], lane[1]) == (1, 0)
     assert (block[5], lane[5]) == (1, 1)
     assert (block[255], lane[255]) == (3, 63)
-    # then a superblock of 2 blocks (blocks 4,5)
+    # second tile (blocks 4..7)
     assert (block[256], lane[256]) == (4, 0)
     assert (block[257], lane[257]) == (5, 0)
-    assert (block[383], lane[383]) == (5, 63)
-    # then a single block (block 6)
-    assert (block[384], lane[384]) == (6, 0)
-    assert (block[447], lane[447]) == (6, 63)
+    assert (block[260], lane[260]) == (4, 1)
+    assert (block[511], lane[511]) == (7, 63)
 
 
-def test_placement_three_workers_7_blocks_by_hand():
-    block, lane, b_w, _ = layout.stream_placement(7, 3, 1)
-    assert list(b_w) == [0, 3, 5]                        # 3, 2, 2 blocks
-    # worker 0: superblocks of 2 then 1
-    assert (block[1], lane[1]) == (1, 0)
-    assert (block[127], lane[127]) == (1, 63)
-    assert (block[128], lane[128]) == (2, 0)
-    assert (block[191], lane[191]) == (2, 63)
-    # worker 1 starts at stream position 192, a superblock of 2
-    assert (block[192], lane[192]) == (3, 0)
-    assert (block[193], lane[193]) == (4, 0)
-    # worker 2 starts at 320
-    assert (block[320], lane[320]) == (5, 0)
-    assert (block[447], lane[447]) == (6, 63)
+def test_placement_three_workers_by_hand():
+    block, lane, b_w, n_w = layout.stream_placement(16, 3, 4)
+    assert list(n_w) == [8, 4, 4] and list(b_w) == [0, 8, 12]     # 4 tiles: 2, 1, 1
+    # the placement inside a tile does not depend on the worker
+    assert (block[512], lane[512]) == (8, 0)
+    assert (block[513], lane[513]) == (9, 0)
+    assert (block[1023], lane[1023]) == (15, 63)
 
 
-def test_placement_with_capped_superblocks_by_hand():
-    # 32 code bytes per group: superblocks of at most 2 blocks -> 7 blocks = 2 + 2 + 2 + 1
-    assert layout.largest_superblock(8) == 4 and layout.largest_superblock(16) == 4
-    assert layout.largest_superblock(32) == 2 and layout.largest_superblock(64) == 1
-    block, lane, _, _ = layout.stream_placement(7, 1, 1, u_max=2)
+def test_placement_with_smaller_tiles_by_hand():
+    # 32 code bytes per group: tiles of 2 blocks; 64: every block by itself
+    assert layout.tile_blocks(8) == 4 and layout.tile_blocks(16) == 4
+    assert layout.tile_blocks(32) == 2 and layout.tile_blocks(64) == 1
+    block, lane, _, _ = layout.stream_placement(6, 1, 2)
     assert (block[0], lane[0]) == (0, 0)
     assert (block[1], lane[1]) == (1, 0)
     assert (block[127], lane[127]) == (1, 63)
     assert (block[128], lane[128]) == (2, 0)
     assert (block[129], lane[129]) == (3, 0)
     assert (block[383], lane[383]) == (5, 63)
-    assert (block[384], lane[384]) == (6, 0)
-    assert (block[447], lane[447]) == (6, 63)
-    # 64 code bytes per group: every block by itself -> stream order
-    block, lane, _, _ = layout.stream_placement(7, 1, 1, u_max=1)
+    block, lane, _, _ = layout.stream_placement(7, 1, 1)
     assert np.array_equal(block, np.arange(448) // 64) and np.array_equal(lane, np.arange(448) % 64)
 
 
-@pytest.mark.parametrize("u_max", [4, 2, 1])
-@pytest.mark.parametrize("nblocks,n_wg,wpw", [(1, 1, 1), (5, 1, 16), (16, 1, 16), (37, 2, 8), (100, 7, 3),
-                                               (9, 256, 16)])
-def test_placement_is_a_bijection(nblocks, n_wg, wpw, u_max):
-    block, lane, _, _ = layout.stream_placement(nblocks, n_wg, wpw, u_max)
+@pytest.mark.parametrize("U", [4, 2, 1])
+@pytest.mark.parametrize("ntiles,n_waves", [(1, 1), (5, 16), (16, 16), (37, 16), (100, 21), (9, 4096)])
+def test_placement_is_a_bijection(ntiles, n_waves, U):
+    block, lane, _, _ = layout.stream_placement(ntiles * U, n_waves, U)
     slot = block * 64 + lane
-    assert np.array_equal(np.sort(slot), np.arange(nblocks * 64))
+    assert np.array_equal(np.sort(slot), np.arange(ntiles * U * 64))
 
 
-def hand_counts(nblocks, n_wg, wpw):
-    """Blocks per worker, written out with plain loops."""
-    out = []
-    for g in range(n_wg):
-        m = nblocks // n_wg + (1 if g < nblocks % n_wg else 0)
-        for l in range(wpw):
-            out.append(m // wpw + (1 if l < m % wpw else 0))
-    return out
+def hand_tile(code_bytes):
+    return 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
 
 
-def hand_superblocks(n_w, code_bytes):
-    """Superblock sizes of a run of n_w blocks, written out (4s, then 2s, then 1s, capped)."""
-    u_max = 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
-    sizes = []
-    left = n_w
-    for U in (4, 2, 1):
-        while U <= u_max and left >= U:
-            sizes.append(U)
-            left -= U
-    return sizes
+def hand_counts(ntiles, n_waves):
+    """Tiles per worker, written out with a plain loop."""
+    return [ntiles // n_waves + (1 if w < ntiles % n_waves else 0) for w in range(n_waves)]
 
 
 def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw, G=16):
-    """Invert the layout with plain loops, walking workers / superblocks / lanes."""
+    """Invert the layout with plain loops, walking workers / tiles / lanes."""
     cb = G * bits // 8
     plane = min(16, cb)
     blk_bytes = (cb + 6) * 64
-    nblocks = (nnzg + 63) // 64
+    U = hand_tile(cb)
+    ntiles = (nnzg + 64 * U - 1) // (64 * U)
+    nblocks = ntiles * U
     raw = np.frombuffer(blob, dtype=np.uint8)
     codes = np.zeros((nblocks * 64, G), dtype=np.int64)
     scales = np.zeros(nblocks * 64, dtype=np.uint16)
@@ -133,9 +112,9 @@ def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw, G=16):
     heads = np.zeros(nblocks * 64, dtype=bool)
     pos = 0
     b = 0
-    counts = hand_counts(nblocks, n_wg, wpw)
+    counts = hand_counts(ntiles, n_wg * wpw)
     for w in range(n_wg * wpw):
-        for U in hand_superblocks(counts[w], cb):
+        for _ in range(counts[w]):
             for p in range(64 * U):
                 blk = b + p % U
                 ln = p // U
@@ -203,14 +182,16 @@ def test_blob_decodes_back_to_canonical(bits, G, n_wg, wpw):
             exp_heads[c.rowIndex[n]] = True
     assert np.array_equal(heads[:nn], exp_heads)
     # side tables
-    nblocks = (nn + 63) // 64
     cb = G * bits // 8
+    U = hand_tile(cb)
+    ntiles = (nn + 64 * U - 1) // (64 * U)
+    nblocks = ntiles * U
     off = (nblocks * (cb + 6) * 64 + 255) // 256 * 256
     wave_info = np.frombuffer(blob, dtype="<i4", count=4 * n_waves, offset=off).reshape(n_waves, 4)
     # brute force: the row and the worker of every stored group
     row_of = np.repeat(np.arange(N), np.diff(c.rowIndex))
     worker_of = np.empty(nn, dtype=np.int64)
-    counts = hand_counts(nblocks, n_wg, wpw)
+    counts = [U * t for t in hand_counts(ntiles, n_waves)]
     b = 0
     for w in range(n_waves):
         n_w = counts[w]

@@ -39,7 +39,7 @@ def test_tiny_config_balanced(bits, sparsity):
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == c.nnzg
-    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, 16)
+    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, 256, 16, bits)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
 
 
@@ -61,8 +61,8 @@ def test_outliers_and_imbalanced_rows(bits):
 
 @pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 def test_other_group_sizes(bits, G):
-    """Group sizes 32, 64, 128: canonical arrays and the device image (code planes, capped
-    superblocks, index word = first 16-element slot) against the oracle, several partitions."""
+    """Group sizes 32, 64, 128: canonical arrays and the device image (code planes, smaller
+    tiles, index word = first 16-element slot) against the oracle, several partitions."""
     N, K = 150, 2048
     W = gi.dense_weight(N, K, seed=91)
     keep = gi.imbalanced_keep_counts(N, K // G, seed=91)
@@ -71,7 +71,7 @@ def test_other_group_sizes(bits, G):
     assert_same_canonical(h, c)
     info = gq.gqsa_info(h)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(N, K, G, bits, c.nnzg, 1)
-    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, G)
+    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, K, G, bits)
     for part in (None, (1, 1), (3, 1), (5, 3), (1, 16), (17, 2), (40, 16)):
         if part is not None:
             gq.gqsa_set_partition(h, *part)
@@ -130,9 +130,9 @@ def test_full_size_7b_shape_bit_exact():
     assert_same_canonical(h, c)
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
-    assert info["nnz_groups"] == 524288 and info["n_workgroups"] == 256 and info["waves_per_workgroup"] == 16
+    assert info["nnz_groups"] == 524288 and info["n_workgroups"] == 256 and info["waves_per_workgroup"] == 8
     assert info["algorithmic_bytes"] == 7372804
-    assert info["needs_fixup"] == 0      # 128 groups per row: every worker's run ends on a row end
+    assert info["needs_fixup"] == 0      # 128 groups per row: every worker's run (a tile of 256 groups) ends on a row end
 
 
 def test_full_size_down_proj_shape_needs_fixup():
@@ -141,7 +141,7 @@ def test_full_size_down_proj_shape_needs_fixup():
     c = oracle.pack(W, 16, 4, sparsity=0.5)
     assert_same_canonical(h, c)
     assert_same_blob(h, c)
-    assert gq.gqsa_info(h)["needs_fixup"] == 1   # 344 groups per row do not align with 64-group blocks
+    assert gq.gqsa_info(h)["needs_fixup"] == 1   # 344 groups per row do not align with 256-group tiles
 
 
 def test_import_round_trip_and_free_parameters():
