@@ -11,10 +11,10 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     The stream is padded with null groups (all bytes zero) to whole tiles:
     ntiles = ceil(nnzg / (64 U)), nblocks = U * ntiles.
  2. Partition.  The tiles are dealt to the n_waves = n_workgroups *
-    waves_per_workgroup workers in contiguous runs: worker w gets
-    ntiles div n_waves tiles (+1 if w < ntiles mod n_waves).  b_w = first block
-    of worker w = U * (number of tiles of the earlier workers).  (The grouping
-    of the workers into workgroups does not enter the layout.)
+    waves_per_workgroup workers in contiguous runs: worker w gets the tiles
+    floor(w * ntiles / n_waves) .. floor((w+1) * ntiles / n_waves) - 1.
+    b_w = first block of worker w = U * floor(w * ntiles / n_waves).  (The
+    grouping of the workers into workgroups does not enter the layout.)
  3. Tiles.  A tile starting at block b covers stream positions
     64b .. 64(b+U)-1; the position 64b + p lives in block b + (p mod U),
     lane p div U.
@@ -66,34 +66,30 @@ def tile_blocks(code_bytes: int) -> int:
 
 def default_partition(nnzg: int, K: int, G: int = 16, bits: int = 4):
     """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise.
-    One tile per worker as long as there are no more workers than half of the wavefront slots
-    of the GPU's 256 compute units (each holds min(3, 160 KiB div (48 * slots)) workgroups of
-    8 wavefronts, slots = K/16 rounded up to a power of two >= 256); beyond that the fewest
-    tiles per worker that respect that bound.  Wavefronts per workgroup: the smallest of 1, 2,
-    4, 8 with 256 workgroups covering the workers, else 8; with 8, an even number of
-    workgroups (> 1)."""
+    K <= 8192: workers = ntiles (one tile each) up to 8192, beyond that ceil(ntiles / t) with
+    t = ceil(ntiles / 8192) tiles each; 4 wavefronts per workgroup (fewer workers: as many);
+    more than 4 workgroups are rounded up to a multiple of 4.
+    K > 8192: 8 wavefronts per workgroup; 256 * ceil(ntiles / 8192) workgroups from 2048 tiles
+    on, else ceil(ntiles / 8)."""
     ntiles = -(-nnzg // (LANES * tile_blocks(G * bits // 8)))
-    slots = 256
-    while slots < K // 16:
-        slots *= 2
-    budget = 256 * max(1, min(3, (160 * 1024) // (48 * slots))) * 8 // 2
-    per_worker = max(1, -(-ntiles // budget))
-    workers = max(1, -(-ntiles // per_worker))
-    wpw = 1
-    while wpw < 8 and 256 * wpw < workers:
-        wpw *= 2
-    wgs = -(-workers // wpw)
-    if wpw == 8 and wgs > 1 and wgs % 2:
-        wgs += 1
+    if K <= 8192:
+        t = max(1, -(-ntiles // 8192))
+        workers = max(1, -(-ntiles // t))
+        wpw = min(4, workers)
+        wgs = -(-workers // wpw)
+        if wgs > 4:
+            wgs = -(-wgs // 4) * 4
+    else:
+        wpw = 8
+        wgs = 256 * (-(-ntiles // 8192)) if ntiles >= 2048 else max(1, -(-ntiles // 8))
     return min(wgs, MAX_WORKGROUPS), wpw
 
 
 def worker_block_counts(nblocks: int, n_waves: int, U: int) -> np.ndarray:
     """Blocks owned by every worker (spec item 2)."""
-    base, extra = divmod(nblocks // U, n_waves)
-    out = np.full(n_waves, base, dtype=np.int64)
-    out[:extra] += 1
-    return out * U
+    ntiles = nblocks // U
+    first = np.arange(n_waves + 1, dtype=np.int64) * ntiles // n_waves
+    return (first[1:] - first[:-1]) * U
 
 
 def _align(n: int) -> int:

@@ -51,11 +51,14 @@ struct MatArgs {                 // where a matrix's results go (64 bytes)
     int n_ranks;                 // non-empty rows
 };
 
-// One matrix of a launch (96 bytes of the kernel-argument block).  Worker w of the matrix owns
-// `base` tiles starting at tile base * w + min(w, extra), one more if w < extra.
+// One matrix of a launch (104 bytes of the kernel-argument block).  Its T tiles are dealt evenly
+// to its W workers: worker w owns the tiles floor(w T / W) .. floor((w+1) T / W) - 1.  With
+// T = base * W + extra that is base * w + floor(w * extra / W), and the division is a multiply
+// by magic = ceil(2^48 / W) and a shift (exact for w <= W <= 65536, extra < W).
 struct MatDesc {
     const uint8_t* blocks;
     const int4_t* wave_info;     // {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len} per worker
+    unsigned long long magic;
     int base, extra;
     int n_wg;                    // workgroups of the launch that work on this matrix
     int pad;
@@ -64,11 +67,11 @@ struct MatDesc {
 struct LaunchArgs {
     MatDesc m[kMaxMatrices];
 };
-static_assert(sizeof(MatArgs) == 64 && sizeof(MatDesc) == 96, "argument block layout");
+static_assert(sizeof(MatArgs) == 64 && sizeof(MatDesc) == 104, "argument block layout");
 
 // where the argument block sits in the kernel-argument segment: after the scalar parameters
-// (three pointers and eight ints)
-constexpr int kArgsOffset = 3 * 8 + 8 * 4;
+// (three pointers, a 64-bit number and eight ints)
+constexpr int kArgsOffset = 4 * 8 + 8 * 4;
 
 // The descriptor of matrix i (wave-uniform), read from the kernel-argument segment itself with
 // scalar loads; indexing the by-value argument with a run-time i would make the compiler copy
@@ -81,6 +84,7 @@ __device__ __forceinline__ MatDesc matrix_desc(int i)
     MatDesc r;
     r.blocks = src->blocks;
     r.wave_info = src->wave_info;
+    r.magic = src->magic;
     r.base = src->base;
     r.extra = src->extra;
     r.n_wg = src->n_wg;
@@ -247,6 +251,7 @@ __device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int lane
 #pragma unroll
     for (int u = 0; u < F::UMAX; ++u)
         t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * F::BB + (F::CB + 4) * kLanes));
+    __builtin_amdgcn_sched_barrier(0);      // (the order of issue is the order of arrival: keep it)
 #pragma unroll
     for (int u = 0; u < F::UMAX; ++u) {
 #pragma unroll
@@ -261,6 +266,7 @@ __device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int lane
             }
         }
         t.sz[u] = load_at<uint32_t>(p, ulane * 4u + (u * F::BB + F::CB * kLanes));
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -578,8 +584,8 @@ __device__ __forceinline__ void lds_barrier()
 // the argument block first.  The block itself follows at byte kArgsOffset.
 template <typename F, int KGP, int NB>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
-    const uint16_t* x, const uint8_t* blocks0, const int4_t* wave_info0, int base0, int extra0, int kg, int wpw,
-    int wg_end0, int wg_end1, int wg_end2, int n_wg0, LaunchArgs a)
+    const uint16_t* x, const uint8_t* blocks0, const int4_t* wave_info0, unsigned long long magic0, int base0, int extra0,
+    int kg, int wpw, int wg_end0, int wg_end1, int wg_end2, int n_wg0, LaunchArgs a)
 {
     // x arrays (NB * 48 * KGP bytes), then what the wavefronts tell each other about shared rows
     extern __shared__ __align__(16) uint8_t xlds[];
@@ -594,8 +600,9 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 
     // x goes out first: it is small, every wavefront of the workgroup needs it before it can
     // use any weight, and loads return in the order of issue.  Slot c holds x[16c .. 16c+15]
-    // (x is [NB][K] contiguous); a thread's first two slots travel in registers.
-    constexpr int XPRE = 2;
+    // (x is [NB][K] contiguous); a thread's first slot (first two for K above 8192) travels in
+    // registers.
+    constexpr int XPRE = KGP >= 1024 ? 2 : 1;     // (512 threads cover 512 slots; more registers here cost a workgroup per compute unit)
     const int n_slots = NB * kg;
     uint4 xlo[XPRE], xhi[XPRE];
 #pragma unroll
@@ -617,10 +624,12 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     const MatDesc md = matrix_desc(mi);
     const uint8_t* blocks = blocks0;
     const int4_t* wave_info = wave_info0;
+    unsigned long long magic = magic0;
     int base = base0, extra = extra0, n_wg = n_wg0;
     if (mi != 0) {      // (a branch, not a select: the first matrix's workgroups do not wait for the descriptor)
         blocks = md.blocks;
         wave_info = md.wave_info;
+        magic = md.magic;
         base = md.base;
         extra = md.extra;
         n_wg = md.n_wg;
@@ -634,8 +643,14 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
     const int4_t info_v = wave_info[worker + lane_zero];
 
-    const int n_tiles = base + (worker < extra ? 1 : 0);
-    const uint8_t* p = blocks + static_cast<size_t>(base * worker + (worker < extra ? worker : extra)) * F::TB;
+    // the worker's run of tiles (scalar arithmetic)
+    auto first_tile = [&](int w) {
+        const unsigned long long n = static_cast<unsigned long long>(static_cast<unsigned>(w)) * static_cast<unsigned>(extra);
+        return base * w + static_cast<int>((n * magic) >> 48);
+    };
+    const int tile0 = first_tile(worker);
+    const int n_tiles = first_tile(worker + 1) - tile0;
+    const uint8_t* p = blocks + static_cast<size_t>(tile0) * F::TB;
 
     auto stage = [&](int c, uint4 lo, uint4 hi) {   // c = slot over all rows: b * kg + column
         const int b = NB == 1 ? 0 : c / kg;
@@ -676,14 +691,19 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     st.heads = 0;
     Tile<F> cur;
     int4_t info;
-    if (n_tiles <= 1) {
+    if (n_tiles == 1) {
         // the whole run is one tile (the default partition's aim): nothing else is in flight
         // behind it, and its blocks are consumed in the order in which they arrive
-        if (n_tiles == 1) load_tile<F>(cur, p, lane);
+        load_tile<F>(cur, p, lane);
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
-        if (n_tiles == 1) compute_tile<F, KGP, NB, true>(md.out, cur, lane, xlds, st);
+        compute_tile<F, KGP, NB, true>(md.out, cur, lane, xlds, st);
+    } else if (n_tiles == 0) {
+        // a worker without tiles still helps to stage x
+        stage_x_and_meet();
+        info = record();
+        st.rank = info.x;
     } else {
         // a run of several tiles: the next tile is requested before the current one is worked on
         // (the copy at the top of the loop is where the wavefront waits for a tile; inside
@@ -749,8 +769,8 @@ void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg, int wpw, con
                     size_t lds, hipStream_t s)
 {
     const MatDesc& m0 = a.m[0];
-    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB>), grid, block, lds, s, x, m0.blocks, m0.wave_info, m0.base,
-                       m0.extra, kg, wpw, wg_end[0], wg_end[1], wg_end[2], m0.n_wg, a);
+    hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB>), grid, block, lds, s, x, m0.blocks, m0.wave_info, m0.magic,
+                       m0.base, m0.extra, kg, wpw, wg_end[0], wg_end[1], wg_end[2], m0.n_wg, a);
 }
 
 template <typename F, int KGP, int NB>
@@ -884,21 +904,25 @@ namespace {
 
 // Wavefronts per workgroup of a launch of nb activation rows on these matrices, 0 if they
 // cannot share a launch.  One activation row: the partition's own grouping.  Several rows (x
-// takes nb times the LDS, so fewer workgroups fit a compute unit): 8-wavefront partitions are
-// taken sixteen wavefronts to a workgroup where the worker count allows and still gives every
-// compute unit a workgroup (the deal of tiles to workers does not depend on the grouping).
+// takes nb times the LDS, so fewer workgroups fit a compute unit): the workers are taken 16 or
+// 8 to a workgroup where the worker counts allow and every compute unit still gets a workgroup
+// (the deal of tiles to workers does not depend on the grouping).
 int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb)
 {
     const int wpw = ms[0]->waves_per_workgroup;
-    bool regroup = nb > 1 && wpw == 8;
     int workers = 0;
     for (int i = 0; i < n_mats; ++i) {
         if (ms[i]->waves_per_workgroup != wpw) return 0;
-        if (ms[i]->n_waves % kWavesPerWorkgroup != 0) regroup = false;
         workers += ms[i]->n_waves;
     }
-    if (workers / kWavesPerWorkgroup < kMaxDefaultWorkgroups) regroup = false;   // not at the price of idle compute units
-    return regroup ? kWavesPerWorkgroup : wpw;
+    if (nb == 1) return wpw;
+    for (int bigger = kWavesPerWorkgroup; bigger > wpw; bigger /= 2) {
+        bool fits = workers / bigger >= kMaxDefaultWorkgroups;
+        for (int i = 0; i < n_mats; ++i)
+            if (ms[i]->n_waves % bigger != 0) fits = false;
+        if (fits) return bigger;
+    }
+    return wpw;
 }
 
 // One launch: nb activation rows (1, 2, 4 or 8) times n_mats matrices that share x and the
@@ -919,6 +943,7 @@ gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint
         MatDesc& d = a.m[i];
         d.blocks = img + m->map.blocks;
         d.wave_info = reinterpret_cast<const int4_t*>(img + m->map.wave_info);
+        d.magic = ((1ull << 48) + m->n_waves - 1) / m->n_waves;
         d.base = static_cast<int>(m->n_tiles / m->n_waves);
         d.extra = static_cast<int>(m->n_tiles % m->n_waves);
         d.n_wg = m->n_waves / wpw;

@@ -192,28 +192,27 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
 // blocks, and in a workgroup as many wavefronts (at most 16, at most one per block) as give
 // every wavefront about two blocks' worth of 16-element chunks -- matrices of a few MB are bound
 // by how many compute units pull on memory, not by how long a wavefront's run is.
-// Default partition.  The stream is cut into tiles (superblocks) of u_max blocks; a worker
-// (wavefront) holds whole tiles.  One tile per worker -- everything it needs requested at once,
-// one segmented scan to settle it -- as long as the workers are all resident at the same time:
-// a compute unit holds three workgroups of eight wavefronts of this kernel (fewer when x, 48
-// bytes of LDS per 16-element slot of K with the slots rounded up to a power of two >= 256,
-// leaves room for fewer), and a launch may carry two or three matrices (q/k/v, gate/up), so a
-// matrix gets half of the 256 compute units' wavefront slots: beyond that a worker holds 2, 3,
-// ... tiles.  Workgroups of 8 wavefronts; of 4, 2 or 1 when that spreads a small matrix over
-// more compute units.  An even number of 8-wavefront workgroups, so that the small-batch kernels can
-// take the same workers sixteen to a workgroup.
+// Default partition (measured on MI355X).  K up to 8192: one tile per worker -- everything it
+// needs requested at once, one segmented scan to settle it -- up to 8192 workers, beyond that the
+// fewest tiles per worker that keep to that count; workgroups of 4 wavefronts (small workgroups
+// meet sooner after x is staged and fill the compute units more evenly), a multiple of 4
+// of them so that the small-batch kernels can take the same workers 8 or 16 to a workgroup.
+// Larger K, where staging x (48 bytes of LDS per 16 elements) is the larger part of a
+// workgroup's work: 8 wavefronts per workgroup and a multiple of 256 workgroups -- one or more
+// per compute unit, all alike -- with at most 4 tiles per worker.
 void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves_per_workgroup)
 {
-    int64_t slots = 256;
-    while (slots < K / 16) slots *= 2;
-    const int64_t wgs_per_cu = std::max<int64_t>(1, std::min<int64_t>(3, (160 * 1024) / (48 * slots)));
-    const int64_t budget = kMaxDefaultWorkgroups * wgs_per_cu * 8 / 2;
-    const int64_t per_worker = std::max<int64_t>(1, (n_tiles + budget - 1) / budget);
-    const int64_t workers = std::max<int64_t>(1, (n_tiles + per_worker - 1) / per_worker);
-    int64_t wpw = 1;
-    while (wpw < 8 && kMaxDefaultWorkgroups * wpw < workers) wpw *= 2;
-    int64_t wgs = (workers + wpw - 1) / wpw;
-    if (wpw == 8 && wgs > 1 && (wgs & 1)) ++wgs;
+    int64_t wgs = 1, wpw = 1;
+    if (K <= 8192) {
+        const int64_t per_worker = std::max<int64_t>(1, (n_tiles + 8191) / 8192);
+        const int64_t workers = std::max<int64_t>(1, (n_tiles + per_worker - 1) / per_worker);
+        wpw = std::min<int64_t>(4, workers);
+        wgs = (workers + wpw - 1) / wpw;
+        if (wgs > 4) wgs = (wgs + 3) / 4 * 4;
+    } else {
+        wpw = 8;
+        wgs = n_tiles >= 2048 ? kMaxDefaultWorkgroups * ((n_tiles + 8191) / 8192) : std::max<int64_t>(1, (n_tiles + 7) / 8);
+    }
     *n_workgroups = static_cast<int>(std::min<int64_t>(wgs, kMaxWorkgroups));
     *waves_per_workgroup = static_cast<int>(wpw);
 }
@@ -221,10 +220,11 @@ void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
 // 64-group blocks; u_max blocks make a tile (superblock): 4 blocks with up to 16 code bytes per
 // group, 2 with 32, 1 with 64 (a wavefront's tile stays within about 24 registers).  The stream
-// is padded with null groups to whole tiles.  The tiles are dealt in contiguous, near-equal runs
-// to the n_workgroups * waves_per_workgroup workers (wavefronts): worker w gets n_tiles div
-// workers tiles, one more if w < n_tiles mod workers (the nnz-balanced version of the paper's
-// task-centric split, Sec. 3.5; a row may be shared by neighbouring wavefronts).  The deal does
+// is padded with null groups to whole tiles.  The T tiles are dealt in contiguous, near-equal runs
+// to the W = n_workgroups * waves_per_workgroup workers (wavefronts): worker w gets the tiles
+// floor(w T / W) .. floor((w+1) T / W) - 1, so that the workers with one tile more are spread
+// evenly over the workgroups (the nnz-balanced version of the paper's task-centric split,
+// Sec. 3.5; a row may be shared by neighbouring wavefronts).  The deal does
 // not depend on how the workers are grouped into workgroups, so a launch may group them
 // differently.  In a tile of U blocks lane l owns U consecutive stream positions, stored one
 // per block so that every block is a fully coalesced, lane-interleaved load:
@@ -322,12 +322,9 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         return static_cast<int64_t>(std::lower_bound(head_pos.begin(), head_pos.end(), pos) -
                                     head_pos.begin());
     };
-    // flat deal: tiles -> workers
+    // even deal: worker w owns the tiles floor(w T / W) .. floor((w+1) T / W) - 1
     std::vector<int64_t> first_block(static_cast<size_t>(n_waves) + 1, 0);
-    {
-        const int64_t base = n_tiles / n_waves, extra = n_tiles % n_waves;
-        for (int w = 0; w <= n_waves; ++w) first_block[w] = (base * w + std::min<int64_t>(w, extra)) * u_max;
-    }
+    for (int w = 0; w <= n_waves; ++w) first_block[w] = (static_cast<int64_t>(w) * n_tiles / n_waves) * u_max;
     auto worker_of = [&](int64_t pos) {   // the worker whose run contains stream position pos
         const int64_t blk = pos / kLanes;
         return static_cast<int32_t>(std::upper_bound(first_block.begin(), first_block.end(), blk) -

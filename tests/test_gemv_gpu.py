@@ -238,14 +238,14 @@ def test_gemv_error_paths_on_device(torch_cuda):
 
 # ----------------------------------------------------------------------------- several matrices, one launch
 
-@pytest.mark.parametrize("part", [None, "mixed", (3, 4), (1, 16), (40, 2), (2, 8)])
+@pytest.mark.parametrize("part", [None, "mixed", (3, 4), (1, 16), (40, 2), (512, 4), (1024, 4)])
 @pytest.mark.parametrize("batch", [1, 3, 8])
 def test_gemv_multi_equals_separate_calls(torch_cuda, part, batch):
     """q/k/v-style: matrices of different N sharing x; the fused launch must give the bits of the
     separate calls (and both must match the oracle).  Partitions: the defaults (wavefronts per
     workgroup differ with the size: separate launches behind the call), different worker counts
     with the same workgroup size (one launch, each matrix its own share of the grid), equal ones;
-    (2, 8) is taken sixteen wavefronts to a workgroup by the launches of several rows."""
+    with (512, 4) and (1024, 4) the launches of several rows take the workers 8 and 16 to a workgroup."""
     torch = torch_cuda
     K = 2048
     shapes = [(300, 0.5, None), (64, 0.0, None), (257, None, "imbalanced"), (128, 1.0, None)]

@@ -16,25 +16,25 @@ from oracle import layout
 
 def test_default_partition():
     assert oracle.default_partition(0, 4096) == (1, 1)
-    assert oracle.default_partition(2048, 256) == (8, 1)              # 8 tiles of 256 groups, one per worker
-    assert oracle.default_partition(256 * 17, 4096) == (17, 1)
-    assert oracle.default_partition(256 * 600, 4096) == (150, 4)      # 600 workers: 4 to a workgroup cover them with <= 256 workgroups
-    assert oracle.default_partition(524288, 4096) == (256, 8)         # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront
-    assert oracle.default_partition(1409024, 4096) == (344, 8)        # 11008x4096: 5504 tiles, two per worker
-    assert oracle.default_partition(1409024, 11008) == (344, 8)       # 4096x11008: 48 KiB of LDS for x, still 3 workgroups
-    assert oracle.default_partition(256 * 2049, 4096) == (258, 8)     # 2049 workers -> 257 workgroups -> an even count
-    assert oracle.default_partition(256 * 3072, 4096) == (384, 8)     # the budget: half of 256 x 3 x 8 wavefronts
-    assert oracle.default_partition(256 * 3073, 4096) == (194, 8)     # beyond it two tiles per worker: 1537 workers
-    assert oracle.default_partition(256 * 3072, 32768) == (256, 4)    # x takes 96 KiB: one workgroup per compute unit -> 1024 workers of 3 tiles
+    assert oracle.default_partition(256 * 3, 256) == (1, 3)           # 3 tiles of 256 groups, one per wavefront
+    assert oracle.default_partition(2048, 256) == (2, 4)              # 8 tiles
+    assert oracle.default_partition(256 * 17, 4096) == (8, 4)         # 17 workers -> 5 workgroups -> a multiple of 4
+    assert oracle.default_partition(524288, 4096) == (512, 4)         # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront
+    assert oracle.default_partition(1409024, 4096) == (1376, 4)       # 11008x4096: 5504 tiles
+    assert oracle.default_partition(256 * 8192, 4096) == (2048, 4)    # the most workers
+    assert oracle.default_partition(256 * 8193, 4096) == (1028, 4)    # beyond: two tiles per worker, 4097 workers
+    assert oracle.default_partition(1409024, 11008) == (256, 8)       # 4096x11008: one workgroup per compute unit, 2.7 tiles per worker
+    assert oracle.default_partition(256 * 8193, 11008) == (512, 8)
+    assert oracle.default_partition(256 * 100, 32768) == (13, 8)
     assert oracle.default_partition(64 * 1024, 4096, G=128) == (256, 4)   # 64 code bytes: a tile is one block, 1024 tiles
     assert oracle.default_partition(128 * 2048, 4096, G=16, bits=8) == (256, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
 
 
 def test_tile_deal_by_hand():
-    # 23 tiles of 4 blocks over 12 workers: 1 each, the first 11 one more
-    assert list(layout.worker_block_counts(92, 12, 4)) == [8] * 11 + [4]
-    # 5 tiles of 2 blocks over 8 workers
-    assert list(layout.worker_block_counts(10, 8, 2)) == [2, 2, 2, 2, 2, 0, 0, 0]
+    # 23 tiles of 4 blocks over 12 workers: worker w starts at tile floor(23 w / 12) = 0 1 3 5 7 9 11 13 15 17 19 21
+    assert list(layout.worker_block_counts(92, 12, 4)) == [4] + [8] * 11
+    # 5 tiles of 2 blocks over 8 workers: starts 0 0 1 1 2 3 3 4 (5)
+    assert list(layout.worker_block_counts(10, 8, 2)) == [0, 2, 0, 2, 2, 0, 2, 2]
     # LLaMA-7B down_proj at W4S50: 5504 tiles over 344 x 8 workers, two each
     c = layout.worker_block_counts(22016, 2752, 4)
     assert set(c) == {8} and c.sum() == 22016
@@ -57,7 +57,7 @@ def test_placement_single_worker_2_tiles_by_hand():
 
 def test_placement_three_workers_by_hand():
     block, lane, b_w, n_w = layout.stream_placement(16, 3, 4)
-    assert list(n_w) == [8, 4, 4] and list(b_w) == [0, 8, 12]     # 4 tiles: 2, 1, 1
+    assert list(n_w) == [4, 4, 8] and list(b_w) == [0, 4, 8]      # 4 tiles: starts 0, 1, 2 (4)
     # the placement inside a tile does not depend on the worker
     assert (block[512], lane[512]) == (8, 0)
     assert (block[513], lane[513]) == (9, 0)
@@ -93,7 +93,7 @@ def hand_tile(code_bytes):
 
 def hand_counts(ntiles, n_waves):
     """Tiles per worker, written out with a plain loop."""
-    return [ntiles // n_waves + (1 if w < ntiles % n_waves else 0) for w in range(n_waves)]
+    return [(w + 1) * ntiles // n_waves - w * ntiles // n_waves for w in range(n_waves)]
 
 
 def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw, G=16):

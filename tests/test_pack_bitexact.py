@@ -130,7 +130,7 @@ def test_full_size_7b_shape_bit_exact():
     assert_same_canonical(h, c)
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
-    assert info["nnz_groups"] == 524288 and info["n_workgroups"] == 256 and info["waves_per_workgroup"] == 8
+    assert info["nnz_groups"] == 524288 and info["n_workgroups"] == 512 and info["waves_per_workgroup"] == 4
     assert info["algorithmic_bytes"] == 7372804
     assert info["needs_fixup"] == 0      # 128 groups per row: every worker's run (a tile of 256 groups) ends on a row end
 
