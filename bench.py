@@ -180,7 +180,7 @@ def main():
         "eager_ms_per_step": round(eager_ms / args.steps, 6),
         "pool_build_s": round(t_build, 1),
     }
-    # dominant kernel: gqsa_gemv_kernel<4, KGP, 1, NM>; a launch covers one call, or the calls of a
+    # dominant kernel: gqsa_gemv_kernel<Fmt<4, 1>, KGP, 1>; a launch covers one call, or the calls of a
     # layer that share x (q/k/v, gate/up).  Average launch duration is the event-timed region
     # divided by the launches in it (so it contains the gaps between dependent kernels); bytes are
     # the algorithmic bytes of the calls a launch covers.
@@ -190,7 +190,7 @@ def main():
     achieved = (bytes_per_step / launches_per_step) / avg_launch_s / 1e9
     out["roofline"] = {
         "bound": "hbm",
-        "kernel": "gqsa_gemv_kernel<4, KGP, 1, NM>",
+        "kernel": "gqsa_gemv_kernel<Fmt<4, 1>, KGP, 1>",
         "achieved": round(achieved, 2),
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
@@ -200,7 +200,7 @@ def main():
         # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (calibrated on gqsa_copy), mean
         # over the launches of a step; see profiles/*hbm_traffic.md for the runs (the figure for
         # seven separate launches comes from the same counters, one matrix per launch)
-        "traffic": 12978000 if args.separate else 22518758,
+        "traffic": None if args.separate else 22574566,
     }
 
     # ------------------------------------------------------------------ extras: per shape, baselines

@@ -54,7 +54,7 @@ typedef struct {
     int32_t bits;               /* code width */
     int64_t nnz_groups;         /* stored groups = rowIndex[N] */
     int64_t values_bytes;       /* bytes of the canonical `values` array */
-    int64_t n_blocks;           /* 64-group blocks of the device stream */
+    int64_t n_blocks;           /* 64-group blocks of the device stream (padded to whole tiles) */
     int32_t n_workgroups;       /* workgroups the group stream is dealt to */
     int32_t waves_per_workgroup;/* wavefront workers per workgroup */
     int32_t needs_fixup;        /* 1 if some row is shared by two or more wavefront workers */
@@ -110,11 +110,14 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
                           const uint16_t* scales_f16, const uint16_t* zeros_f16,
                           int64_t N, int64_t K, int G, int bits, gqsa_handle_t* out);
 
-/* Re-partition the group stream over n_workgroups (1..4096) workgroups of waves_per_workgroup
- * (1..16) wavefront workers and rebuild the host copy of the device image.  Only before the
- * handle is uploaded.  The default chosen by pack/import is min(256, n_blocks) workgroups (one per
- * compute unit of an MI355X) of ceil(n_blocks * (G/16) / (2 * workgroups)) wavefronts, at most 16
- * and at most ceil(n_blocks / workgroups). */
+/* Re-partition the group stream over n_workgroups (1..4096) x waves_per_workgroup (1..16)
+ * wavefront workers and rebuild the host copy of the device image.  Only before the handle is
+ * uploaded.  The stream is cut into tiles of 4 blocks of 64 groups (2 blocks with 32 code bytes
+ * per group, 1 with 64); worker w owns the tiles floor(w T / W) .. floor((w+1) T / W) - 1 of the
+ * T tiles, W being the worker count.  The default chosen by pack/import/load: for K up to 8192
+ * one tile per worker (at most 8192 workers; more tiles per worker beyond) in workgroups of 4
+ * wavefronts, the workgroup count rounded up to a multiple of 4; for larger K workgroups of 8
+ * wavefronts, 256 of them (one per compute unit of an MI355X) per 8192 tiles. */
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
 
 /* Create the device image and carry workspace on the current HIP device (synchronous). */
@@ -128,7 +131,7 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
  *   batch 1..16
  *   hip_stream a hipStream_t (NULL = the default stream)
  * K must not exceed 32768 (x and its group sums are staged in LDS); GQSA_ERR_UNSUPPORTED else.
- * Group sizes above 16 run one activation row and one matrix per launch.
+ * A launch takes 8, 4, 2 or 1 activation rows (group sizes above 16: one row per launch).
  * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
  * bit-identical from run to run.  Does not synchronise.  The current HIP device must be the one
  * the handle was uploaded on (GQSA_ERR_HIP otherwise).
@@ -139,15 +142,15 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
 /*
  * Several matrices that share the activation vector -- q/k/v or gate/up of a decoder layer, the
  * way the paper's engine runs seven GEMVs per layer (Sec. 4.4) -- in ONE launch:
- * y_devs[i] = W^_i x for i < n_matrices (1..4).  Every wavefront walks its share of the first
- * matrix, then of the second, ... as one pipelined stream, so launch, x staging and first-byte
- * latency are paid once.
- *   handles  [host] array of n_matrices distinct handles with equal K, G, bits and equal
- *            partition (n_workgroups, waves_per_workgroup); GQSA_ERR_SHAPE otherwise
+ * y_devs[i] = W^_i x for i < n_matrices (1..4).  The workgroups of the launch are dealt to the
+ * matrices (each matrix keeps its own partition), so launch and first-byte latency are paid once
+ * and the matrices' weights stream side by side.
+ *   handles  [host] array of n_matrices distinct handles with equal K, G and bits (N may
+ *            differ); GQSA_ERR_SHAPE otherwise
  *   x_dev    [device] fp16 [batch,K], 16-byte aligned
  *   y_devs   [host] array of n_matrices [device] pointers, y_devs[i] fp16 [batch,N_i]
- * Results are bit-identical to n_matrices separate gqsa_gemv calls (which is what happens for
- * batch > 1 and for group sizes above 16).
+ * Results are bit-identical to n_matrices separate gqsa_gemv calls (which is what happens behind
+ * the call when the handles' partitions differ in their wavefronts per workgroup).
  */
 gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, const void* x_dev,
                               void* const* y_devs, int batch, void* hip_stream);

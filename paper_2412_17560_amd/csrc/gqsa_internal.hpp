@@ -19,7 +19,7 @@ constexpr int kMaxMatricesPerLaunch = 4;
 constexpr int64_t kMaxGroupColumns = 4096;  // 16-element slots of K: 12-bit slot << 4 | head flag in 16 bits
 constexpr size_t kAlign = 256;
 
-// Blocks per tile (superblock) for a format with `code_bytes` bytes of codes per group.
+// Blocks per tile for a format with `code_bytes` bytes of codes per group.
 constexpr int largest_tile(int code_bytes) { return code_bytes <= 16 ? 4 : (code_bytes <= 32 ? 2 : 1); }
 
 // Offsets (bytes) of the regions inside the device image.

@@ -218,7 +218,7 @@ void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves
 }
 
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
-// 64-group blocks; u_max blocks make a tile (superblock): 4 blocks with up to 16 code bytes per
+// 64-group blocks; u_max blocks make a tile: 4 blocks with up to 16 code bytes per
 // group, 2 with 32, 1 with 64 (a wavefront's tile stays within about 24 registers).  The stream
 // is padded with null groups to whole tiles.  The T tiles are dealt in contiguous, near-equal runs
 // to the W = n_workgroups * waves_per_workgroup workers (wavefronts): worker w gets the tiles
