@@ -70,8 +70,8 @@ struct LaunchArgs {
 static_assert(sizeof(MatArgs) == 64 && sizeof(MatDesc) == 104, "argument block layout");
 
 // where the argument block sits in the kernel-argument segment: after the scalar parameters
-// (three pointers, a 64-bit number and eight ints)
-constexpr int kArgsOffset = 4 * 8 + 8 * 4;
+// (three pointers, a 64-bit number and six ints: the 14 dwords that can be preloaded)
+constexpr int kArgsOffset = 4 * 8 + 6 * 4;
 
 // The descriptor of matrix i (wave-uniform), read from the kernel-argument segment itself with
 // scalar loads; indexing the by-value argument with a run-time i would make the compiler copy
@@ -578,20 +578,23 @@ __device__ __forceinline__ void lds_barrier()
 }
 
 // The leading scalar parameters repeat what the first loads depend on (x, the first matrix's
-// tile stream, worker table and deal, the slot count, the wavefronts per workgroup, where the
-// other matrices' workgroups begin): the file is compiled with kernel-argument preloading for
-// them, so they sit in scalar registers when a wavefront starts instead of being fetched from
-// the argument block first.  The block itself follows at byte kArgsOffset.
+// tile stream, worker table and deal, the slot count and the wavefronts per workgroup in one
+// word, where the other matrices' workgroups begin): 14 dwords, as many as the hardware preloads;
+// the file is compiled with kernel-argument preloading for them, so they sit in scalar registers
+// when a wavefront starts instead of being fetched from the argument block first.  The block
+// itself follows at byte kArgsOffset.
 template <typename F, int KGP, int NB>
 __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     const uint16_t* x, const uint8_t* blocks0, const int4_t* wave_info0, unsigned long long magic0, int base0, int extra0,
-    int kg, int wpw, int wg_end0, int wg_end1, int wg_end2, int n_wg0, LaunchArgs a)
+    int kg_wpw, int wg_end0, int wg_end1, int wg_end2, LaunchArgs a)
 {
     // x arrays (NB * 48 * KGP bytes), then what the wavefronts tell each other about shared rows
     extern __shared__ __align__(16) uint8_t xlds[];
     LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);      // [wavefront]
     LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + kWavesPerWorkgroup);    // [wavefront][NB]
 
+    const int kg = kg_wpw & 0xFFFF;       // 16-element slots of K
+    const int wpw = kg_wpw >> 16;         // wavefronts per workgroup
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int n_threads = wpw * kLanes;
@@ -625,14 +628,13 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     const uint8_t* blocks = blocks0;
     const int4_t* wave_info = wave_info0;
     unsigned long long magic = magic0;
-    int base = base0, extra = extra0, n_wg = n_wg0;
+    int base = base0, extra = extra0;
     if (mi != 0) {      // (a branch, not a select: the first matrix's workgroups do not wait for the descriptor)
         blocks = md.blocks;
         wave_info = md.wave_info;
         magic = md.magic;
         base = md.base;
         extra = md.extra;
-        n_wg = md.n_wg;
         asm volatile("" : "+s"(base));
     }
     // the worker's record {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}: requested
@@ -658,12 +660,10 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         *reinterpret_cast<uint4*>(slot) = lo;
         *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        float s = 0.0f;
+        const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+        float s = 0.0f;      // sum of the slot's 16 activations, fp32: a pair per instruction
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            s += half_to_float(w[i] & 0xFFFFu);
-            s += half_to_float(w[i] >> 16);
-        }
+        for (int i = 0; i < 8; ++i) s = __builtin_amdgcn_fdot2(as_half2(w[i]), ones, s, false);
         *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg) * 4) = s;
     };
     // x into LDS (the loads of the tiles are already out), then the workgroup meets
@@ -722,7 +722,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     }
 
     // rows without stored groups: exactly +0
-    for (int e = lwg * n_threads + tid; e < md.out.n_empty; e += n_wg * n_threads) {
+    for (int e = lwg * n_threads + tid; e < md.out.n_empty; e += md.n_wg * n_threads) {
         const int row = md.out.empty_rows[e];
 #pragma unroll
         for (int b = 0; b < NB; ++b) md.out.y[b * md.out.N + row] = 0;
@@ -770,7 +770,7 @@ void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg, int wpw, con
 {
     const MatDesc& m0 = a.m[0];
     hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB>), grid, block, lds, s, x, m0.blocks, m0.wave_info, m0.magic,
-                       m0.base, m0.extra, kg, wpw, wg_end[0], wg_end[1], wg_end[2], m0.n_wg, a);
+                       m0.base, m0.extra, kg | (wpw << 16), wg_end[0], wg_end[1], wg_end[2], a);
 }
 
 template <typename F, int KGP, int NB>
