@@ -187,6 +187,14 @@ __device__ __forceinline__ float keep_lanes(unsigned long long mask, float t)
     return r;
 }
 
+// a in the lanes whose bit is set in the wave-uniform mask, b elsewhere
+__device__ __forceinline__ float select_lanes(unsigned long long mask, float a, float b)
+{
+    float r;
+    asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(b), "v"(a), "s"(mask));
+    return r;
+}
+
 __device__ __forceinline__ float read_lane(float v, int lane)
 {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
@@ -239,6 +247,18 @@ template <typename T>
 __device__ __forceinline__ T load_at(const uint8_t* base, uint32_t byte_offset)
 {
     return *reinterpret_cast<const T*>(base + byte_offset);
+}
+
+// Reads from LDS at a byte address given as a number.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_read16(uint32_t address)
+{
+    const u32x4_t v = *(const __attribute__((address_space(3))) u32x4_t*)(uintptr_t)address;
+    return uint4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ float lds_read_float(uint32_t address)
+{
+    return *(const __attribute__((address_space(3))) float*)(uintptr_t)address;
 }
 
 // A tile's loads go out index words first (four small loads: the gathers from LDS need nothing
@@ -353,16 +373,20 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
         }
     };
 
-    // (2)-(4) gather the activation group by real group index, dequantise, multiply
+    // (2)-(4) gather the activation group by real group index, dequantise, multiply.
+    // (LDS addresses as plain numbers: the kernel has no static LDS, so x starts at 0 -- the host
+    // checks that when the kernel is first used; written through the array's symbol every
+    // address would cost an addition of that 0)
+    constexpr uint32_t x0 = 0;
     if constexpr (EAGER && NB == 1 && F::M == 1) {
         uint4 xl[U], xh[U];
         float xs[U], dotz[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const uint32_t slot = t.ix[u] & 0xFFF0u;        // byte offset of the group's 16 activations
-            xl[u] = *reinterpret_cast<const uint4*>(xlds + slot);
-            xh[u] = *reinterpret_cast<const uint4*>(xlds + slot + 16 * KGP);
-            xs[u] = *reinterpret_cast<const float*>(xlds + 32 * KGP + (slot >> 2));
+            xl[u] = lds_read16(x0 + slot);
+            xh[u] = lds_read16(x0 + slot + 16 * KGP);
+            xs[u] = lds_read_float(x0 + 32 * KGP + (slot >> 2));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -383,13 +407,12 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
             for (int i = 0; i < F::M; ++i) {                // the group's 16-element chunks
                 Codes c;
                 decode_chunk<F>(t, u, i, c);
-                const uint8_t* xg = xlds + slot + 16 * i;
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
-                    const uint8_t* xb = xg + b * (48 * KGP);
-                    const uint4 xl = *reinterpret_cast<const uint4*>(xb);
-                    const uint4 xh = *reinterpret_cast<const uint4*>(xb + 16 * KGP);
-                    const float xs = *reinterpret_cast<const float*>(xlds + b * (48 * KGP) + 32 * KGP + (slot >> 2) + 4 * i);
+                    const uint32_t xb = x0 + slot + 16 * i + b * (48 * KGP);
+                    const uint4 xl = lds_read16(xb);
+                    const uint4 xh = lds_read16(xb + 16 * KGP);
+                    const float xs = lds_read_float(x0 + b * (48 * KGP) + 32 * KGP + (slot >> 2) + 4 * i);
                     const float d = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
                     dotz[b] = i == 0 ? d : dotz[b] + d;
                 }
@@ -420,10 +443,10 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         float v = acc[b];
-        v += keep_lanes(~p1, dpp_or_zero<0x111, 0xF>(v));       // row_shr:1
-        v += keep_lanes(~p2, dpp_or_zero<0x112, 0xF>(v));       // row_shr:2
-        v += keep_lanes(~p4, dpp_or_zero<0x114, 0xF>(v));       // row_shr:4
-        v += keep_lanes(~p8, dpp_or_zero<0x118, 0xF>(v));       // row_shr:8
+        v = select_lanes(p1, v, v + dpp_or_zero<0x111, 0xF>(v));       // row_shr:1
+        v = select_lanes(p2, v, v + dpp_or_zero<0x112, 0xF>(v));       // row_shr:2
+        v = select_lanes(p4, v, v + dpp_or_zero<0x114, 0xF>(v));       // row_shr:4
+        v = select_lanes(p8, v, v + dpp_or_zero<0x118, 0xF>(v));       // row_shr:8
         v += keep_lanes(~p16, dpp_or_zero<0x142, 0xA>(v));      // row_bcast:15
         v += keep_lanes(open31, dpp_or_zero<0x143, 0xC>(v));    // row_bcast:31
         // sum flowing into this lane from the left: the previous lane's segment sum (+ carry)
@@ -611,9 +634,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 #pragma unroll
     for (int j = 0; j < XPRE; ++j) {
         const int c = tid + j * n_threads;
-        xlo[j] = uint4{0, 0, 0, 0};
-        xhi[j] = uint4{0, 0, 0, 0};
-        if (c < n_slots) {
+        if (c < n_slots) {       // (the same condition guards the use)
             const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(c) * 16);
             xlo[j] = src[0];
             xhi[j] = src[1];
@@ -866,7 +887,11 @@ gqsa_status_t device_upload(gqsa_matrix* m)
     GQSA_HIP(hipGetDevice(&dev));
     for (int nb = 1; nb <= kMaxRowsPerLaunch; nb *= 2) {
         Variant v = pick(m, nb, &kgp);
-        if (v && lds_bytes(kgp, nb) > 64 * 1024)
+        if (!v) continue;
+        hipFuncAttributes attr{};
+        GQSA_HIP(hipFuncGetAttributes(&attr, v.fn));
+        if (attr.sharedSizeBytes != 0) return GQSA_ERR_HIP;      // the kernel addresses x from LDS offset 0
+        if (lds_bytes(kgp, nb) > 64 * 1024)
             GQSA_HIP(hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                          static_cast<int>(lds_bytes(kgp, nb))));
     }
