@@ -190,8 +190,9 @@ const char* gqsa_status_string(gqsa_status_t s);
 gqsa_status_t gqsa_dense_f16_gemv(const void* W_dev, const void* x_dev, void* y_dev,
                                   int64_t N, int64_t K, int batch, void* hip_stream);
 
-/* Sum `bytes` (multiple of 16) of device memory into sink_dev[0..n_wg-1] (uint32 each, n_wg
- * from gqsa_stream_read_workgroups()); a pure read at full width. */
+/* XOR `bytes` (multiple of 16) of device memory into sink_dev[0..n_wg-1] (uint32 each; n_wg =
+ * gqsa_stream_read_workgroups() entries must be there, a small buffer writes fewer): a pure read
+ * at full width, every workgroup reading its own contiguous share. */
 gqsa_status_t gqsa_stream_read(const void* buf_dev, size_t bytes, void* sink_dev, void* hip_stream);
 int gqsa_stream_read_workgroups(void);
 
