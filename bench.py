@@ -200,7 +200,7 @@ def main():
         # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (calibrated on gqsa_copy), mean
         # over the launches of a step; see profiles/*hbm_traffic.md for the runs (the figure for
         # seven separate launches comes from the same counters, one matrix per launch)
-        "traffic": None if args.separate else 22574566,
+        "traffic": None if args.separate else 22565504,
     }
 
     # ------------------------------------------------------------------ extras: per shape, baselines
