@@ -48,7 +48,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
-              "(the path shards by output rows, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by output rows: every GPU all of x and a slice of y)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

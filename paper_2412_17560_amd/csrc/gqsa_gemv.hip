@@ -10,9 +10,10 @@
 // Wavefront = 64 lanes.  A block is 64 stored groups, one per lane, so that every load is
 // one fully coalesced instruction; a tile is U blocks (4 at G = 16): lane l owns the U
 // consecutive stream positions U*l .. U*l+U-1, sums them serially and takes part in ONE
-// cross-lane segmented scan per tile.  A wavefront owns whole tiles; with the default partition
-// it owns one or two, requests all of their bytes before anything else and works through the
-// blocks in the order in which they arrive.
+// cross-lane segmented scan per tile.  A wavefront owns whole tiles.  With the default partition
+// it owns one on decode shapes: it requests all of its bytes before anything else and works
+// through the blocks in the order in which they arrive; a run of several tiles is worked through
+// with the next tile requested ahead.
 //
 // One launch can carry several matrices that share x (q/k/v, gate/up): the workgroups of the
 // grid are dealt to the matrices, each workgroup works on one of them.

@@ -11,7 +11,7 @@
 namespace gqsa {
 
 constexpr int kLanes = 64;             // one stored group per lane per block
-constexpr int kWavesPerWorkgroup = 16; // 1024 threads: one workgroup per compute unit
+constexpr int kWavesPerWorkgroup = 16; // the most wavefronts a workgroup can have (1024 threads)
 constexpr int kMaxDefaultWorkgroups = 256;  // MI355X: 256 compute units
 constexpr int kMaxWorkgroups = 4096;
 constexpr int kMaxBatch = 16;
