@@ -357,7 +357,9 @@ def test_other_group_sizes_full_size_and_sparsities(torch_cuda, G):
         check(torch_cuda, h, c, gi.activations(1, 4096, seed=11))
 
 
-def test_gemv_multi_with_larger_groups_falls_back_to_separate_launches(torch_cuda):
+def test_gemv_multi_with_larger_groups(torch_cuda):
+    """Two G = 32 matrices of different N in one launch: the oracle's values and the bits of the
+    separate calls."""
     torch = torch_cuda
     K = 1024
     x_np = gi.activations(1, K, seed=12)
@@ -371,8 +373,9 @@ def test_gemv_multi_with_larger_groups_falls_back_to_separate_launches(torch_cud
         gq.gqsa_set_partition(h, 3, 4)
     ys = gq.gqsa_gemv_multi(hs, x)
     torch.cuda.synchronize()
-    for y, c in zip(ys, cs):
+    for h, y, c in zip(hs, ys, cs):
         assert oracle.rel_error(y.cpu().numpy()[0], oracle.gemv(c, x_np, threads=4)[0]) <= TOL
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), run_gemv(torch, h, x_np).view(np.uint16))
 
 
 def test_hessian_pruned_and_reloaded_matrices_multiply(torch_cuda, tmp_path):
