@@ -37,8 +37,8 @@ def parse_args():
     p.add_argument("--skip-extras", action="store_true", help="skip per-shape / dense / stream-read legs")
     p.add_argument("--cpu-seconds", type=float, default=12.0)
     p.add_argument("--sweep", action="store_true",
-                   help="also time the Llama-3-8B-like shapes at S = 0, 30, 50, 70 %% and group sizes 16..128 "
-                        "(about two minutes more)")
+                   help="also time the Llama-3-8B-like shapes at S = 0, 30, 50, 70 %%, group sizes 16..128, the "
+                        "imbalanced stress shapes and small batches on 14336x4096 (about three minutes more)")
     p.add_argument("--pmc-calibrate", action="store_true",
                    help="also run 8 plain copies of 256 MiB (known HBM traffic) to calibrate profiler counters")
     return p.parse_args()
@@ -303,6 +303,49 @@ def main():
                                                    [(4, sp) for sp in gi.SPARSITY_SWEEP], 3)
             out["group_size_sweep"] = time_variants(shapes7[:1] + shapes7[1:2],
                                                     [(4, sp, G) for G in (16, 32, 64, 128) for sp in (0.0, 0.5)], 2)
+
+        if args.sweep:
+            # imbalanced sparsity stress: kept fraction per row ~ Beta(0.5, 0.5), 2 % of the rows
+            # empty, 2 % full (rows of very different lengths, long carry chains)
+            rows = []
+            for idx, (name, N, K) in enumerate(gi.IMBALANCED_SHAPES):
+                seed = gi.config_seed(4, idx)
+                W = gi.dense_weight_chunked(N, K, seed=seed, workers=workers)
+                keep = gi.imbalanced_keep_counts(N, K // 16, seed=seed)
+                h0 = gq.gqsa_pack_rows(W, keep, 16, 4)
+                del W
+                e = gq.gqsa_export(h0)
+                n = max(2, (1 << 30) // gq.gqsa_info(h0)["device_bytes"] + 1)
+                hs = [h0] + [gq.gqsa_import(e["rowIndex"], e["groups"], e["values"], e["scales"], e["zeros"], N, K, 16, 4)
+                             for _ in range(n - 1)]
+                for h in hs:
+                    gq.gqsa_upload(h)
+                xk = torch.from_numpy(gi.activations(1, K, seed=seed)).to(dev)
+                yk = torch.empty((1, N), dtype=torch.float16, device=dev)
+                us = time_calls(lambda k, hs=hs, xk=xk, yk=yk: gq.gqsa_gemv(hs[k % len(hs)], xk, yk), n=60)
+                b = gq.gqsa_info(h0)["algorithmic_bytes"]
+                rows.append({"shape": f"{N}x{K}", "nnz_groups": gq.gqsa_info(h0)["nnz_groups"], "us_cold": round(us, 3),
+                             "GBps_cold": round(b / us / 1e3, 1),
+                             "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2)})
+                for h in hs:
+                    gq.gqsa_free(h)
+            out["imbalanced_stress"] = rows
+            # small batches on the larger shape, 4-bit and 8-bit codes
+            rows = []
+            name, N, K = gi.SMALL_BATCH_SHAPES[1]
+            W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(5, 1), workers=workers)
+            for bits in (4, 8):
+                hs = copies_of(W, bits, 0.5)
+                for B in gi.BATCH_SWEEP:
+                    xb = torch.from_numpy(gi.activations(B, K, seed=gi.config_seed(5, 1))).to(dev)
+                    yb = torch.empty((B, N), dtype=torch.float16, device=dev)
+                    us = time_calls(lambda k, hs=hs, xb=xb, yb=yb: gq.gqsa_gemv(hs[k % len(hs)], xb, yb), n=60)
+                    rows.append({"shape": f"{N}x{K}", "bits": bits, "batch": B, "us_cold": round(us, 3),
+                                 "us_per_row": round(us / B, 3)})
+                for h in hs:
+                    gq.gqsa_free(h)
+            del W
+            out["small_batch_14336x4096"] = rows
 
         # the offline step (host): prune + quantise + build the device image, 4096x4096
         Wp = gi.dense_weight_chunked(4096, 4096, seed=gi.config_seed(2, 0), workers=workers)

@@ -22,6 +22,7 @@
 // decoded group is multiplied with all NB rows (weights are read and dequantised once).
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <climits>
 #include <cstddef>
 #include <cstdint>
@@ -929,11 +930,12 @@ void device_release(gqsa_matrix* m)
 namespace {
 
 // Wavefronts per workgroup of a launch of nb activation rows on these matrices, 0 if they
-// cannot share a launch.  One activation row: the partition's own grouping.  Several rows (x
-// takes nb times the LDS, so fewer workgroups fit a compute unit): the workers are taken 16 or
-// 8 to a workgroup where the worker counts allow and every compute unit still gets a workgroup
-// (the deal of tiles to workers does not depend on the grouping).
-int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb)
+// cannot share a launch.  One activation row: the partition's own grouping.  Several rows: x
+// takes nb times the LDS, so fewer workgroups fit a compute unit; the workers are then taken 8
+// or 16 to a workgroup -- as many as keep about 16 wavefronts on a compute unit -- where the
+// worker counts allow and every compute unit still gets a workgroup (the deal of tiles to
+// workers does not depend on the grouping).
+int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb, size_t lds_per_workgroup)
 {
     const int wpw = ms[0]->waves_per_workgroup;
     int workers = 0;
@@ -942,7 +944,10 @@ int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb)
         workers += ms[i]->n_waves;
     }
     if (nb == 1) return wpw;
-    for (int bigger = kWavesPerWorkgroup; bigger > wpw; bigger /= 2) {
+    const int per_cu = static_cast<int>(std::max<size_t>(1, kMaxLdsBytes / lds_per_workgroup));
+    int want = 1;
+    while (want < kWavesPerWorkgroup && want * per_cu < kWavesPerWorkgroup) want *= 2;
+    for (int bigger = want; bigger > wpw; bigger /= 2) {
         bool fits = workers / bigger >= kMaxDefaultWorkgroups;
         for (int i = 0; i < n_mats; ++i)
             if (ms[i]->n_waves % bigger != 0) fits = false;
@@ -1015,13 +1020,14 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
         const uint16_t* xb = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m0->K;
         uint16_t* yb[kMaxMatrices];
         for (int i = 0; i < n_mats; ++i) yb[i] = static_cast<uint16_t*>(ys[i]) + static_cast<size_t>(done) * ms[i]->N;
-        const int together = launch_waves_per_workgroup(ms, n_mats, nb);
+        const size_t lds = lds_bytes(kgp, nb);
+        const int together = launch_waves_per_workgroup(ms, n_mats, nb, lds);
         if (together > 0) {
             // one launch for all the matrices
             if (gqsa_status_t st = launch(ms, n_mats, xb, yb, nb, together, s)) return st;
         } else {
             for (int i = 0; i < n_mats; ++i) {
-                const int wpw = launch_waves_per_workgroup(ms + i, 1, nb);
+                const int wpw = launch_waves_per_workgroup(ms + i, 1, nb, lds);
                 if (gqsa_status_t st = launch(ms + i, 1, xb, yb + i, nb, wpw, s)) return st;
             }
         }
