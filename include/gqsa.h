@@ -114,10 +114,11 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
  * wavefront workers and rebuild the host copy of the device image.  Only before the handle is
  * uploaded.  The stream is cut into tiles of 4 blocks of 64 groups (2 blocks with 32 code bytes
  * per group, 1 with 64); worker w owns the tiles floor(w T / W) .. floor((w+1) T / W) - 1 of the
- * T tiles, W being the worker count.  The default chosen by pack/import/load: for K up to 8192
- * one tile per worker (at most 8192 workers; more tiles per worker beyond) in workgroups of 4
- * wavefronts, the workgroup count rounded up to a multiple of 4; for larger K workgroups of 8
- * wavefronts, 256 of them (one per compute unit of an MI355X) per 8192 tiles. */
+ * T tiles, W being the worker count.  The default chosen by pack/import/load: for K up to 4096
+ * (or fewer than 2048 tiles) one tile per worker (at most 8192 workers; more tiles per worker
+ * beyond) in workgroups of 4 wavefronts, the workgroup count rounded up to a multiple of 4; for
+ * larger K workgroups of 8 wavefronts, 256, 512 or 768 of them (one to three per compute unit of
+ * an MI355X): the multiple of 256 nearest to 448 T / K. */
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
 
 /* Create the device image and carry workspace on the current HIP device (synchronous). */

@@ -66,13 +66,13 @@ def tile_blocks(code_bytes: int) -> int:
 
 def default_partition(nnzg: int, K: int, G: int = 16, bits: int = 4):
     """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise.
-    K <= 8192: workers = ntiles (one tile each) up to 8192, beyond that ceil(ntiles / t) with
-    t = ceil(ntiles / 8192) tiles each; 4 wavefronts per workgroup (fewer workers: as many);
-    more than 4 workgroups are rounded up to a multiple of 4.
-    K > 8192: 8 wavefronts per workgroup; 256 * ceil(ntiles / 8192) workgroups from 2048 tiles
-    on, else ceil(ntiles / 8)."""
+    K <= 4096 or fewer than 2048 tiles: workers = ntiles (one tile each) up to 8192, beyond that
+    ceil(ntiles / t) with t = ceil(ntiles / 8192) tiles each; 4 wavefronts per workgroup (fewer
+    workers: as many); more than 4 workgroups are rounded up to a multiple of 4.
+    Else: 8 wavefronts per workgroup and 256 * clamp(round(448 * ntiles / K / 256), 1, 3)
+    workgroups (round half up)."""
     ntiles = -(-nnzg // (LANES * tile_blocks(G * bits // 8)))
-    if K <= 8192:
+    if K <= 4096 or ntiles < 2048:
         t = max(1, -(-ntiles // 8192))
         workers = max(1, -(-ntiles // t))
         wpw = min(4, workers)
@@ -81,7 +81,7 @@ def default_partition(nnzg: int, K: int, G: int = 16, bits: int = 4):
             wgs = -(-wgs // 4) * 4
     else:
         wpw = 8
-        wgs = 256 * (-(-ntiles // 8192)) if ntiles >= 2048 else max(1, -(-ntiles // 8))
+        wgs = 256 * max(1, min(3, (448 * ntiles + 128 * K) // (256 * K)))
     return min(wgs, MAX_WORKGROUPS), wpw
 
 

@@ -192,18 +192,19 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
 // blocks, and in a workgroup as many wavefronts (at most 16, at most one per block) as give
 // every wavefront about two blocks' worth of 16-element chunks -- matrices of a few MB are bound
 // by how many compute units pull on memory, not by how long a wavefront's run is.
-// Default partition (measured on MI355X).  K up to 8192: one tile per worker -- everything it
-// needs requested at once, one segmented scan to settle it -- up to 8192 workers, beyond that the
-// fewest tiles per worker that keep to that count; workgroups of 4 wavefronts (small workgroups
-// meet sooner after x is staged and fill the compute units more evenly), a multiple of 4
-// of them so that the small-batch kernels can take the same workers 8 or 16 to a workgroup.
-// Larger K, where staging x (48 bytes of LDS per 16 elements) is the larger part of a
-// workgroup's work: 8 wavefronts per workgroup and a multiple of 256 workgroups -- one or more
-// per compute unit, all alike -- with at most 4 tiles per worker.
+// Default partition (measured on MI355X).  K up to 4096, or fewer than 2048 tiles: one tile per
+// worker -- everything it needs requested at once, one segmented scan to settle it -- up to 8192
+// workers, beyond that the fewest tiles per worker that keep to that count; workgroups of 4
+// wavefronts (small workgroups meet sooner after x is staged and fill the compute units more
+// evenly), a multiple of 4 of them so that the small-batch kernels can take the same workers 8
+// or 16 to a workgroup.  Larger K, where staging x (48 bytes of LDS per 16 elements) is a large
+// part of a workgroup's work: 8 wavefronts per workgroup and 256, 512 or 768 workgroups -- one,
+// two or three per compute unit, all alike -- as many as keep the bytes of x staged by all
+// workgroups to about a quarter of the matrix's: the multiple of 256 nearest to 448 T / K.
 void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves_per_workgroup)
 {
     int64_t wgs = 1, wpw = 1;
-    if (K <= 8192) {
+    if (K <= 4096 || n_tiles < 2048) {
         const int64_t per_worker = std::max<int64_t>(1, (n_tiles + 8191) / 8192);
         const int64_t workers = std::max<int64_t>(1, (n_tiles + per_worker - 1) / per_worker);
         wpw = std::min<int64_t>(4, workers);
@@ -211,7 +212,8 @@ void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves
         if (wgs > 4) wgs = (wgs + 3) / 4 * 4;
     } else {
         wpw = 8;
-        wgs = n_tiles >= 2048 ? kMaxDefaultWorkgroups * ((n_tiles + 8191) / 8192) : std::max<int64_t>(1, (n_tiles + 7) / 8);
+        const int64_t per_cu = (448 * n_tiles + 128 * K) / (256 * K);      // round(448 T / K / 256)
+        wgs = kMaxDefaultWorkgroups * std::max<int64_t>(1, std::min<int64_t>(3, per_cu));
     }
     *n_workgroups = static_cast<int>(std::min<int64_t>(wgs, kMaxWorkgroups));
     *waves_per_workgroup = static_cast<int>(wpw);

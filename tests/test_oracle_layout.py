@@ -23,9 +23,11 @@ def test_default_partition():
     assert oracle.default_partition(1409024, 4096) == (1376, 4)       # 11008x4096: 5504 tiles
     assert oracle.default_partition(256 * 8192, 4096) == (2048, 4)    # the most workers
     assert oracle.default_partition(256 * 8193, 4096) == (1028, 4)    # beyond: two tiles per worker, 4097 workers
-    assert oracle.default_partition(1409024, 11008) == (256, 8)       # 4096x11008: one workgroup per compute unit, 2.7 tiles per worker
-    assert oracle.default_partition(256 * 8193, 11008) == (512, 8)
-    assert oracle.default_partition(256 * 100, 32768) == (13, 8)
+    assert oracle.default_partition(1409024, 11008) == (256, 8)       # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit, 2.7 tiles per worker
+    assert oracle.default_partition(256 * 8191, 8192) == (512, 8)     # 448 T / K = 448 -> two per compute unit
+    assert oracle.default_partition(256 * 28615, 8192) == (768, 8)    # at most three
+    assert oracle.default_partition(256 * 4096, 8192) == (256, 8)     # 4096x8192 at S = 50 %
+    assert oracle.default_partition(256 * 100, 32768) == (28, 4)      # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
     assert oracle.default_partition(64 * 1024, 4096, G=128) == (256, 4)   # 64 code bytes: a tile is one block, 1024 tiles
     assert oracle.default_partition(128 * 2048, 4096, G=16, bits=8) == (256, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
 
