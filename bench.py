@@ -200,7 +200,7 @@ def main():
         # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE (calibrated on gqsa_copy), mean
         # over the launches of a step; see profiles/*hbm_traffic.md for the runs (the figure for
         # seven separate launches comes from the same counters, one matrix per launch)
-        "traffic": None if args.separate else 22565504,
+        "traffic": None if args.separate else 22670080,
     }
 
     # ------------------------------------------------------------------ extras: per shape, baselines
@@ -229,12 +229,31 @@ def main():
                                "us_p90": round(times[(9 * len(times)) // 10], 3)})
             return times[0] if spread is None else times[len(times) // 2]
 
+        extra_handles = []
+
+        def more_copies(h, n):
+            """n further device copies of a packed matrix (so that a pool of one shape exceeds
+            every cache, the 256 MB memory-side one included)."""
+            e = gq.gqsa_export(h)
+            inf = gq.gqsa_info(h)
+            cs = []
+            for _ in range(n):
+                c = gq.gqsa_import(e["rowIndex"], e["groups"], e["values"], e["scales"], e["zeros"],
+                                   inf["N"], inf["K"], inf["G"], inf["bits"])
+                gq.gqsa_upload(c)
+                cs.append(c)
+            extra_handles.extend(cs)
+            return cs
+
+        min_pool = 1 << 30
         per_shape = []
         for idx in (0, 4, 6):
             name, N, K = gi.LLAMA7B_LAYER[idx]
             hs = [layers[l][idx][0] for l in range(args.pool_layers)]
             if idx == 0:   # q,k,v,o are four distinct matrices of the same shape per layer
                 hs = [layers[l][j][0] for l in range(args.pool_layers) for j in range(4)]
+            each = gq.gqsa_info(hs[0])["device_bytes"]
+            hs = hs + more_copies(hs[0], max(0, -(-min_pool // each) - len(hs)))
             spread = {}
             us = time_calls(lambda k, hs=hs, K=K, idx=idx: gq.gqsa_gemv(hs[k % len(hs)], xs[K], ys[idx]),
                             reps=10, spread=spread)
@@ -247,17 +266,27 @@ def main():
                               "us_cache_warm": round(us_warm, 3),
                               "distinct_matrices": len(hs),
                               "mode": "200 back-to-back calls, median of 10 replays, " + mode})
+            for h in extra_handles:
+                gq.gqsa_free(h)
+            extra_handles.clear()
         out["per_shape"] = per_shape
 
         # the launches that cover several calls sharing x, by themselves
         fused = []
         for label, idxs in (("q/k/v 3 x 4096x4096", (0, 1, 2)), ("gate/up 2 x 11008x4096", (4, 5))):
             sets = [[layers[l][j][0] for j in idxs] for l in range(args.pool_layers)]
+            each = sum(gq.gqsa_info(h)["device_bytes"] for h in sets[0])
+            for _ in range(max(0, -(-min_pool // each) - len(sets))):
+                sets.append([more_copies(h, 1)[0] for h in sets[0]])
             us = time_calls(lambda k, sets=sets, idxs=idxs: gq.gqsa_gemv_multi(
                 sets[k % len(sets)], xs[4096], [ys[j] for j in idxs]))
             b = sum(bytes_per_call[j] for j in idxs)
             fused.append({"launch": label, "us_cold": round(us, 3), "GBps_cold": round(b / us / 1e3, 1),
-                          "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2)})
+                          "pct_peak_cold": round(100 * b / us / 1e3 / HBM_PEAK_GBPS, 2),
+                          "distinct_sets": len(sets)})
+            for h in extra_handles:
+                gq.gqsa_free(h)
+            extra_handles.clear()
         out["fused_launches"] = fused
 
         def copies_of(W, bits, sparsity, G=16, min_bytes=1 << 30):

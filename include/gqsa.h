@@ -54,11 +54,11 @@ typedef struct {
     int32_t bits;               /* code width */
     int64_t nnz_groups;         /* stored groups = rowIndex[N] */
     int64_t values_bytes;       /* bytes of the canonical `values` array */
-    int64_t n_blocks;           /* 64-group blocks of the device stream (padded to whole tiles) */
+    int64_t n_blocks;           /* 64-group blocks of the device stream (null groups included) */
     int32_t n_workgroups;       /* workgroups the group stream is dealt to */
     int32_t waves_per_workgroup;/* wavefront workers per workgroup */
     int32_t needs_fixup;        /* 1 if some row is shared by two or more wavefront workers */
-    int32_t reserved0;
+    int32_t span_tiles;         /* tiles per workgroup span that rows are kept inside (0: no such spans) */
     int64_t n_empty_rows;       /* rows without any stored group */
     int64_t device_bytes;       /* size of the device image */
     int64_t algorithmic_bytes;  /* compressed bytes one batch-1 call must move (see README of bench) */
@@ -114,12 +114,32 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
  * wavefront workers and rebuild the host copy of the device image.  Only before the handle is
  * uploaded.  The stream is cut into tiles of 4 blocks of 64 groups (2 blocks with 32 code bytes
  * per group, 1 with 64); worker w owns the tiles floor(w T / W) .. floor((w+1) T / W) - 1 of the
- * T tiles, W being the worker count.  The default chosen by pack/import/load: for K up to 4096
- * (or fewer than 2048 tiles) one tile per worker (at most 8192 workers; more tiles per worker
- * beyond) in workgroups of 4 wavefronts, the workgroup count rounded up to a multiple of 4; for
- * larger K workgroups of 8 wavefronts, 256, 512 or 768 of them (one to three per compute unit of
- * an MI355X): the multiple of 256 nearest to 448 T / K. */
+ * T tiles, W being the worker count.  The default chosen by pack/import/load, by size: for K up
+ * to 4096 (or fewer than 2048 tiles) one tile per worker (at most 8192 workers; more tiles per
+ * worker beyond) in workgroups of 4 wavefronts, the workgroup count rounded up to a multiple of
+ * 4; for larger K workgroups of 8 wavefronts, 256, 512 or 768 of them (one to three per compute
+ * unit of an MI355X): the multiple of 256 nearest to 448 T / K.  If some row would then lie in
+ * two workgroups and 2 MiB of null groups or less keep every row inside one, the default is the
+ * aligned form below with the same wavefronts per workgroup and: small shapes -- spans of 4 t
+ * tiles, t the tiles per worker (raised while the padded stream needs more than 8192 workers),
+ * the workgroup count rounded up to a multiple of 4; large shapes -- the same 256, 512 or 768
+ * workgroups and the smallest span that holds the rows. */
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
+
+/*
+ * Same, with the rows kept inside the workgroups' shares (a row shared by two workgroups costs
+ * both an exchange through device memory at the end of the launch): the stream is cut into spans
+ * of span_tiles tiles, one per workgroup; a row that fits a span but not what is left of the
+ * current one starts at the next span, the positions skipped hold null groups (read like any
+ * other, adding nothing); a longer row starts where the previous one ended.  T = span_tiles *
+ * n_workgroups tiles are dealt as above.
+ *   span_tiles          >= 1
+ *   n_workgroups        1..4096, or 0 for as many as the rows need; GQSA_ERR_RANGE if the rows
+ *                       need more spans than that
+ *   waves_per_workgroup 1..16
+ */
+gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_workgroups,
+                                         int waves_per_workgroup);
 
 /* Create the device image and carry workspace on the current HIP device (synchronous). */
 gqsa_status_t gqsa_upload(gqsa_handle_t h);

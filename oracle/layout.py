@@ -8,8 +8,18 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
  1. Stream.  The stored groups in canonical order g = 0..nnzg-1 form a stream.
     64 consecutive positions make a block, U consecutive blocks a tile, with
     U = 4 for up to 16 code bytes per group (G*bits/8), 2 for 32, 1 for 64.
-    The stream is padded with null groups (all bytes zero) to whole tiles:
+    Plain form (span_tiles = 0): group g sits at position g; the stream is
+    padded with null groups (all bytes zero) to whole tiles:
     ntiles = ceil(nnzg / (64 U)), nblocks = U * ntiles.
+    Aligned form (span_tiles = s > 0): spans of S = 64 U s positions.  The rows
+    are placed in order from position 0; a row with c groups, 0 < c <= S, that
+    does not fit what is left of the current span ((pos mod S) + c > S) starts at
+    the next multiple of S; every other row starts where the previous one ended.
+    Positions without a stored group hold null groups.  n_workgroups must be at
+    least the number of spans the rows reach into; ntiles = s * n_workgroups.
+    Below, "past the last group" means at or beyond L = one past the last stored
+    group's position (L = nnzg in the plain form), and a null group before L
+    counts as part of the row before it.
  2. Partition.  The tiles are dealt to the n_waves = n_workgroups *
     waves_per_workgroup workers in contiguous runs: worker w gets the tiles
     floor(w * ntiles / n_waves) .. floor((w+1) * ntiles / n_waves) - 1.
@@ -36,14 +46,14 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
       rank_base   = (number of row-head groups at stream positions before
                     worker w's first position) - 1;
       tail_closed = 1 if the first position after the worker's run is at or
-                    beyond nnzg or holds a row-head group, else 0;
+                    beyond L or holds a row-head group, else 0;
       lead_len    = chain_len of worker lead_first (below), 0 if lead_first = -1;
       lead_first  = for a worker (with or without blocks) whose first position
-                    b_w*64 holds a stored group that is not a row head: the
+                    b_w*64 is before L and does not hold a row head: the
                     worker that owns the head group of that group's row; else -1;
       chain_len   = for a worker with blocks, tail_closed = 0 and at least one
-                    row head inside its run: (worker owning the last stored
-                    group of the row that is open at the end of its run) - w + 1;
+                    row head inside its run: (worker owning the last position
+                    before the next row head -- or before L -- after its run) - w + 1;
                     else 0;
     row_of_rank[r] = index of the r-th non-empty row; empty_rows = indices of
     the empty rows.
@@ -64,15 +74,42 @@ def tile_blocks(code_bytes: int) -> int:
     return 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
 
 
-def default_partition(nnzg: int, K: int, G: int = 16, bits: int = 4):
-    """(n_workgroups, waves_per_workgroup) the library picks when not told otherwise.
-    K <= 4096 or fewer than 2048 tiles: workers = ntiles (one tile each) up to 8192, beyond that
-    ceil(ntiles / t) with t = ceil(ntiles / 8192) tiles each; 4 wavefronts per workgroup (fewer
-    workers: as many); more than 4 workgroups are rounded up to a multiple of 4.
+def row_positions(rowIndex, span_groups: int):
+    """(first stream position of every row, L) -- spec item 1."""
+    ri = np.asarray(rowIndex, dtype=np.int64)
+    counts = ri[1:] - ri[:-1]
+    if span_groups <= 0:
+        return ri[:-1].copy(), int(ri[-1])
+    pos = 0
+    out = np.zeros(len(counts), dtype=np.int64)
+    for n, c in enumerate(counts.tolist()):
+        if 0 < c <= span_groups and pos % span_groups + c > span_groups:
+            pos = (pos // span_groups + 1) * span_groups
+        out[n] = pos
+        pos += c
+    return out, pos
+
+
+def default_partition(rowIndex, K: int, G: int = 16, bits: int = 4):
+    """(n_workgroups, waves_per_workgroup, span_tiles) the library picks when not told otherwise.
+    By size first.  K <= 4096 or fewer than 2048 tiles: workers = ntiles (one tile each) up to
+    8192, beyond that ceil(ntiles / t) with t = ceil(ntiles / 8192) tiles each; 4 wavefronts per
+    workgroup (fewer workers: as many); more than 4 workgroups are rounded up to a multiple of 4.
     Else: 8 wavefronts per workgroup and 256 * clamp(round(448 * ntiles / K / 256), 1, 3)
-    workgroups (round half up)."""
-    ntiles = -(-nnzg // (LANES * tile_blocks(G * bits // 8)))
-    if K <= 4096 or ntiles < 2048:
+    workgroups (round half up).  That is it (span 0) with fewer than 4 wavefronts per workgroup
+    or a single workgroup.  Otherwise the aligned form is tried: small shapes -- span = 4 t,
+    workgroups = spans reached, rounded up to a multiple of 4 if above 4, t raised by one while
+    that needs more than 8192 workers; large shapes -- the same workgroup count and the smallest
+    span from ceil(ntiles / workgroups) up whose rows reach into no more spans than that.  A
+    try that needs more than (2 MiB / bytes per group) null groups before L, or more than 4096
+    workgroups, ends the search: the plain form by size stands."""
+    ri = np.asarray(rowIndex, dtype=np.int64)
+    nnzg = int(ri[-1])
+    cb = G * bits // 8
+    tile_groups = LANES * tile_blocks(cb)
+    ntiles = -(-nnzg // tile_groups)
+    small = K <= 4096 or ntiles < 2048
+    if small:
         t = max(1, -(-ntiles // 8192))
         workers = max(1, -(-ntiles // t))
         wpw = min(4, workers)
@@ -82,7 +119,35 @@ def default_partition(nnzg: int, K: int, G: int = 16, bits: int = 4):
     else:
         wpw = 8
         wgs = 256 * max(1, min(3, (448 * ntiles + 128 * K) // (256 * K)))
-    return min(wgs, MAX_WORKGROUPS), wpw
+    plain = (min(wgs, MAX_WORKGROUPS), wpw, 0)
+    if wpw < 4 or wgs < 2:
+        return plain
+    max_null = (2 << 20) // (cb + 6)
+    if small:
+        while True:
+            span = wpw * t
+            _, L = row_positions(ri, span * tile_groups)
+            if L - nnzg > max_null:
+                return plain
+            a_wgs = -(-L // (span * tile_groups))
+            if a_wgs > 4:
+                a_wgs = -(-a_wgs // 4) * 4
+            if a_wgs * wpw <= 8192:
+                break
+            t += 1
+    else:
+        a_wgs = wgs
+        span = -(-ntiles // wgs)
+        while True:
+            _, L = row_positions(ri, span * tile_groups)
+            if L - nnzg > max_null:
+                return plain
+            if -(-L // (span * tile_groups)) <= wgs:
+                break
+            span += 1
+    if a_wgs > MAX_WORKGROUPS:
+        return plain
+    return a_wgs, wpw, span
 
 
 def worker_block_counts(nblocks: int, n_waves: int, U: int) -> np.ndarray:
@@ -108,14 +173,13 @@ def stream_placement(nblocks: int, n_waves: int, U: int):
     return block, lane, b_w, n_w
 
 
-def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
+def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int = 0) -> bytes:
     """Exact bytes the library must hold on the device for canonical arrays `c`."""
     if c.G not in (16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
         raise ValueError("device layout is specified for G in {16,32,64,128}, bits in {4,8}, at most 64 code bytes")
     nnzg = c.nnzg
     code_bytes = c.G * c.bits // 8
     U = tile_blocks(code_bytes)
-    nblocks = U * (-(-nnzg // (LANES * U)))
     blk_bytes = (code_bytes + 6) * LANES
     chunks = c.G // 16
 
@@ -123,7 +187,16 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     counts = ri[1:] - ri[:-1]
     nonempty = np.nonzero(counts > 0)[0].astype(np.int32)
     empty = np.nonzero(counts == 0)[0].astype(np.int32)
-    head_pos = ri[:-1][counts > 0]                 # stream position of each row's first group
+    row_pos, L = row_positions(ri, span_tiles * LANES * U)
+    if span_tiles > 0:
+        if -(-L // (span_tiles * LANES * U)) > n_workgroups:
+            raise ValueError("the rows reach into more spans than there are workgroups")
+        nblocks = U * span_tiles * n_workgroups
+    else:
+        nblocks = U * (-(-L // (LANES * U)))
+    head_pos = row_pos[counts > 0]                 # stream position of each row's first group
+    # stream position of every stored group
+    group_pos = np.arange(nnzg, dtype=np.int64) + np.repeat(row_pos - ri[:-1], counts)
 
     n_waves = n_workgroups * waves_per_workgroup
     blocks = np.zeros((nblocks, blk_bytes), dtype=np.uint8)
@@ -133,8 +206,8 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
     wave_info[:, 2] = -1
     if nblocks > 0:
         block, lane, b_w, n_w = stream_placement(nblocks, n_waves, U)
-        block = block[:nnzg]
-        lane = lane[:nnzg]
+        block = block[group_pos]
+        lane = lane[group_pos]
         # codes
         vals = np.asarray(c.values, dtype=np.uint8).reshape(nnzg, code_bytes)
         if c.bits == 4:
@@ -161,7 +234,7 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
         sz_view[block, lane, :] = sz.view(np.uint8).reshape(nnzg, 4)
         # group-column | head flag
         is_head = np.zeros(nnzg, dtype=np.uint16)
-        is_head[head_pos] = 1
+        is_head[ri[:-1][counts > 0]] = 1
         gcol = np.asarray(c.groups, dtype=np.int64)
         if gcol.size and gcol.max() * chunks + chunks - 1 >= 4096:
             raise ValueError("slot number does not fit 12 bits")
@@ -174,22 +247,22 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int) -> bytes:
         wave_info[:, 0] = np.searchsorted(head_pos, first_pos, side="left") - 1
         # tail_closed: does the row that is open at the end of the run stop there?
         end_pos = LANES * (b_w + n_w)
-        head_set = np.zeros(nblocks * LANES + 1, dtype=bool)
+        head_set = np.zeros(max(nblocks * LANES, L) + 1, dtype=bool)
         head_set[head_pos] = True
-        wave_info[:, 1] = np.where(end_pos >= nnzg, 1, head_set[np.minimum(end_pos, nblocks * LANES)])
+        wave_info[:, 1] = np.where(end_pos >= L, 1, head_set[np.minimum(end_pos, nblocks * LANES)])
         # carry chains: which worker owns a given block
         owner = np.repeat(np.arange(n_waves), n_w)
         for w in range(n_waves):
             f = int(first_pos[w])
             e = int(end_pos[w])
-            if f < nnzg and not head_set[f]:
+            if f < L and not head_set[f]:
                 row_head = int(head_pos[np.searchsorted(head_pos, f, side="right") - 1])
                 wave_info[w, 2] = owner[row_head // LANES]
-            heads_inside = (np.searchsorted(head_pos, min(e, nnzg), side="left") -
+            heads_inside = (np.searchsorted(head_pos, min(e, L), side="left") -
                             np.searchsorted(head_pos, f, side="left"))
             if n_w[w] > 0 and wave_info[w, 1] == 0 and heads_inside > 0:
                 nxt = int(np.searchsorted(head_pos, e, side="left"))
-                row_last = (int(head_pos[nxt]) if nxt < len(head_pos) else nnzg) - 1
+                row_last = (int(head_pos[nxt]) if nxt < len(head_pos) else L) - 1
                 wave_info[w, 3] = owner[row_last // LANES] - w + 1
         for w in range(n_waves):
             if wave_info[w, 2] >= 0:

@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     gqsa_pack_rows,
     gqsa_save,
     gqsa_set_partition,
+    gqsa_set_partition_aligned,
     gqsa_status_string,
     gqsa_stream_read,
     gqsa_stream_read_workgroups,

@@ -21,7 +21,7 @@ class _Info(C.Structure):
     _fields_ = [("N", C.c_int64), ("K", C.c_int64), ("G", C.c_int32), ("bits", C.c_int32),
                 ("nnz_groups", C.c_int64), ("values_bytes", C.c_int64), ("n_blocks", C.c_int64),
                 ("n_workgroups", C.c_int32), ("waves_per_workgroup", C.c_int32),
-                ("needs_fixup", C.c_int32), ("reserved0", C.c_int32), ("n_empty_rows", C.c_int64),
+                ("needs_fixup", C.c_int32), ("span_tiles", C.c_int32), ("n_empty_rows", C.c_int64),
                 ("device_bytes", C.c_int64), ("algorithmic_bytes", C.c_int64),
                 ("on_device", C.c_int32), ("reserved", C.c_int32)]
 
@@ -59,6 +59,8 @@ def _lib():
     lib.gqsa_import.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, C.POINTER(vp)]
     lib.gqsa_set_partition.restype = C.c_int
     lib.gqsa_set_partition.argtypes = [vp, i32, i32]
+    lib.gqsa_set_partition_aligned.restype = C.c_int
+    lib.gqsa_set_partition_aligned.argtypes = [vp, i32, i32, i32]
     lib.gqsa_upload.restype = C.c_int
     lib.gqsa_upload.argtypes = [vp]
     lib.gqsa_gemv.restype = C.c_int
@@ -179,6 +181,12 @@ def gqsa_import(rowIndex, groups, values, scales_f16, zeros_f16, N: int, K: int,
 def gqsa_set_partition(h: GqsaHandle, n_workgroups: int, waves_per_workgroup: int = 16) -> None:
     _check(_lib().gqsa_set_partition(h.ptr, int(n_workgroups), int(waves_per_workgroup)),
            "gqsa_set_partition")
+
+
+def gqsa_set_partition_aligned(h: GqsaHandle, span_tiles: int, n_workgroups: int = 0,
+                               waves_per_workgroup: int = 4) -> None:
+    _check(_lib().gqsa_set_partition_aligned(h.ptr, int(span_tiles), int(n_workgroups), int(waves_per_workgroup)),
+           "gqsa_set_partition_aligned")
 
 
 def gqsa_upload(h: GqsaHandle) -> None:

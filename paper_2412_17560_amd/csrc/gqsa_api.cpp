@@ -26,10 +26,9 @@ gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
 gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
 {
     if (st == GQSA_OK) {
-        const int64_t tile_groups = static_cast<int64_t>(gqsa::kLanes) * gqsa::largest_tile(m->code_bytes());
-        int wgs = 1, wpw = 1;
-        gqsa::default_partition((m->nnzg() + tile_groups - 1) / tile_groups, m->K, &wgs, &wpw);
-        st = gqsa::build_image(m, wgs, wpw);
+        int wgs = 1, wpw = 1, span = 0;
+        gqsa::default_partition(*m, &wgs, &wpw, &span);
+        st = gqsa::build_image(m, wgs, wpw, span);
     }
     if (st != GQSA_OK) {
         delete m;
@@ -119,7 +118,16 @@ gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_pe
 {
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
-    return gqsa::build_image(h, n_workgroups, waves_per_workgroup);
+    if (n_workgroups < 1) return GQSA_ERR_RANGE;
+    return gqsa::build_image(h, n_workgroups, waves_per_workgroup, 0);
+}
+
+gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_workgroups, int waves_per_workgroup)
+{
+    if (!h) return GQSA_ERR_NULL;
+    if (h->d_image) return GQSA_ERR_UNSUPPORTED;
+    if (span_tiles < 1) return GQSA_ERR_RANGE;
+    return gqsa::build_image(h, n_workgroups, waves_per_workgroup, span_tiles);
 }
 
 gqsa_status_t gqsa_upload(gqsa_handle_t h)
@@ -181,6 +189,7 @@ gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)
     out->n_workgroups = h->n_workgroups;
     out->waves_per_workgroup = h->waves_per_workgroup;
     out->needs_fixup = h->needs_fixup;
+    out->span_tiles = h->span_tiles;
     out->n_empty_rows = h->n_empty;
     out->device_bytes = static_cast<int64_t>(h->map.total);
     out->algorithmic_bytes = h->nnzg() * (h->code_bytes() + 6) + (h->N + 1) * 4 + (h->K + h->N) * 2;

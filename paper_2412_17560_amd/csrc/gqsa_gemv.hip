@@ -491,15 +491,13 @@ __device__ __forceinline__ void chain_arrive(const MatArgs& m, const int4* wave_
     __hip_atomic_store(&m.counters[first], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ready for the next call
 }
 
-// What a wavefront tells its workgroup about the rows it shares with its neighbours.
-struct LdsSums {
-    float lead;
-    float tail;
-};
-struct LdsCounts {
-    int4 info;     // the worker's record {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}
+// What a wavefront tells its workgroup, per activation row, about the rows it shares with its
+// neighbours: one 16-byte LDS word, so that a neighbour learns it with a single read.
+struct LdsRecord {
+    float lead;    // sum of its groups before its first row head
+    float tail;    // sum of its groups since its last row head (all of them without one)
     int heads;     // row heads inside its run
-    int pad[3];
+    int pad;
 };
 
 // A row whose workers sit in two neighbouring workgroups: each side adds up its workers' pieces
@@ -525,62 +523,83 @@ __device__ __forceinline__ bool meet(unsigned long long* slot, float sum, float*
     return true;
 }
 
-// Carry fix-up of one matrix by one lane of a wavefront, after the workgroup's records are in
-// LDS.  A row whose workers all sit in this workgroup is summed in worker order by the wavefront
-// holding its head; one spread over two workgroups goes through a meeting point (above); only a
-// row spread over three or more workgroups uses records and an arrival counter (chain_arrive).
+// How a worker's shared rows are settled: worked out from its record and its place in the
+// workgroup as soon as the record is there -- scalar arithmetic done while the tiles are still
+// on their way -- so that little is left to do once the sums are known.  A row whose workers
+// all sit in one workgroup is summed by the wavefront holding its head; one spread over two
+// workgroups goes through a meeting point (above); only a row spread over three or more
+// workgroups uses records and an arrival counter (chain_arrive).
+struct FixupPlan {
+    int head_mode;   // the row this run leaves open: 0 none, 1 ends in this workgroup, 2 in the next, 3 further on
+    int head_n;      // workers after this one, in this workgroup, holding pieces of it
+    int lead_mode;   // the row this run continues: 0 someone else adds this piece, 2 this worker speaks
+                     // for the second workgroup of two, 3 three workgroups or more
+    int lead_n;      // mode 2: workers after this one holding pieces of it
+};
+
 // info = the worker's {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}; lead_len is
 // the chain length of the row this run continues.
-template <int NB>
-__device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave_info, int4 info,
-                                             int heads, const float* own_lead, const float* own_tail,
-                                             const LdsCounts* cn, const LdsSums* cs, int wl, int wg, int wpw,
-                                             int wave)
+__device__ __forceinline__ FixupPlan plan_fixup(int4 info, int wl, int wg, int wpw, int wave)
 {
-    const int rank_open = info.x + heads;
-    const int head_w = info.y >> 1;
+    FixupPlan pl{0, 0, 0, 0};
     const int wg_first = wg * wpw, wg_end = wg_first + wpw;     // this workgroup's workers
-    auto piece = [&](int w, int b) {   // what local worker w adds to the row its run continues
-        return cn[w].heads == 0 ? cs[w * NB + b].tail : cs[w * NB + b].lead;
-    };
-    if ((info.y & 1) != 0 && heads > 0) {     // last row ends with the run
-#pragma unroll
-        for (int b = 0; b < NB; ++b) store_row(mo, b, rank_open, own_tail[b]);
-    }
-    bool chain_tail = false, chain_lead = false;
-    if (info.w > 0) {                         // this worker holds the head of a row that continues
+    if (info.w > 0) {
         const int end = wave + info.w;        // one past the row's last worker
-        if (end <= wg_end + wpw) {
-            const int here = (end < wg_end ? end : wg_end) - wave;
+        pl.head_mode = end <= wg_end ? 1 : (end <= wg_end + wpw ? 2 : 3);
+        pl.head_n = (end < wg_end ? end : wg_end) - wave - 1;
+    }
+    if (info.z >= 0) {
+        const int end = info.z + (info.y >> 1);
+        const bool head_here = info.z >= wg_first;
+        const bool two_at_most = head_here ? end <= wg_end + wpw : (info.z >= wg_first - wpw && end <= wg_end);
+        pl.lead_mode = !two_at_most ? 3 : ((!head_here && wl == 0) ? 2 : 0);
+        pl.lead_n = end - wg_first - 1;
+    }
+    return pl;
+}
+
+// Carry fix-up of one matrix by a wavefront, after the workgroup's records are in LDS.  Lane w
+// reads worker w's records -- one LDS read per activation row, all in flight together, whatever
+// the number of pieces -- and the pieces are then added in worker order from the lanes.
+template <int NB>
+__device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave_info, int4 info, FixupPlan pl,
+                                             int heads, const float* own_lead, const float* own_tail,
+                                             const LdsRecord* rec, int lane, int wl, int wpw, int wave)
+{
+    // piece[b] in lane w: what local worker w adds to the row its run continues
+    float piece[NB];
+    {
+        const int w = lane < wpw ? lane : 0;
+        LdsRecord r[NB];
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float sum = own_tail[b], other = 0.0f;
-                for (int w = wl + 1; w < wl + here; ++w) sum += piece(w, b);
-                if (end <= wg_end) store_row(mo, b, rank_open, sum);
+        for (int b = 0; b < NB; ++b) r[b] = rec[w * NB + b];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) piece[b] = r[b].heads == 0 ? r[b].tail : r[b].lead;
+    }
+    const bool writer = lane == 0;
+    const int rank_open = info.x + heads;
+    if (pl.head_mode == 1 || pl.head_mode == 2) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float sum = own_tail[b], other = 0.0f;
+            for (int i = 1; i <= pl.head_n; ++i) sum += read_lane(piece[b], wl + i);
+            if (writer) {
+                if (pl.head_mode == 1) store_row(mo, b, rank_open, sum);
                 else if (meet(&mo.slots[wave * kMaxRowsPerLaunch + b], sum, &other))
                     store_row(mo, b, rank_open, sum + other);
             }
-        } else {
-            chain_tail = true;
         }
     }
-    if (info.z >= 0) {                        // its first groups continue a row of an earlier worker
-        const int end = info.z + head_w;      // one past that row's last worker
-        const bool head_here = info.z >= wg_first;
-        const bool two_at_most = head_here ? end <= wg_end + wpw : (info.z >= wg_first - wpw && end <= wg_end);
-        if (!two_at_most) {
-            chain_lead = true;
-        } else if (!head_here && wl == 0) {   // the far side's first worker speaks for all of them
+    if (pl.lead_mode == 2) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float sum = heads == 0 ? own_tail[b] : own_lead[b], other = 0.0f;
-                for (int w = 1; w < end - wg_first; ++w) sum += piece(w, b);
-                if (meet(&mo.slots[info.z * kMaxRowsPerLaunch + b], sum, &other))
-                    store_row(mo, b, info.x, other + sum);
-            }
-        }                                     // (else: the worker holding the head, or the far side's first, adds this piece)
+        for (int b = 0; b < NB; ++b) {
+            float sum = heads == 0 ? own_tail[b] : own_lead[b], other = 0.0f;
+            for (int i = 1; i <= pl.lead_n; ++i) sum += read_lane(piece[b], i);
+            if (writer && meet(&mo.slots[info.z * kMaxRowsPerLaunch + b], sum, &other))
+                store_row(mo, b, info.x, other + sum);
+        }
     }
-    if (chain_tail || chain_lead) {
+    if ((pl.head_mode == 3 || pl.lead_mode == 3) && writer) {
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             CarryRecord* r = &mo.carry[wave * kMaxRowsPerLaunch + b];
@@ -589,8 +608,8 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
             __hip_atomic_store(&r->heads, heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
-        if (chain_lead) chain_arrive<NB>(mo, wave_info, info.z);
-        if (chain_tail) chain_arrive<NB>(mo, wave_info, wave);
+        if (pl.lead_mode == 3) chain_arrive<NB>(mo, wave_info, info.z);
+        if (pl.head_mode == 3) chain_arrive<NB>(mo, wave_info, wave);
     }
 }
 
@@ -615,8 +634,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 {
     // x arrays (NB * 48 * KGP bytes), then what the wavefronts tell each other about shared rows
     extern __shared__ __align__(16) uint8_t xlds[];
-    LdsCounts* rec_n = reinterpret_cast<LdsCounts*>(xlds + NB * 48 * KGP);      // [wavefront]
-    LdsSums* rec_s = reinterpret_cast<LdsSums*>(rec_n + kWavesPerWorkgroup);    // [wavefront][NB]
+    LdsRecord* rec = reinterpret_cast<LdsRecord*>(xlds + NB * 48 * KGP);        // [wavefront][NB]
 
     const int kg = kg_wpw & 0xFFFF;       // 16-element slots of K
     const int wpw = kg_wpw >> 16;         // wavefronts per workgroup
@@ -707,6 +725,12 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         return int4_t{__builtin_amdgcn_readfirstlane(info_v.x), __builtin_amdgcn_readfirstlane(info_v.y),
                       __builtin_amdgcn_readfirstlane(info_v.z), __builtin_amdgcn_readfirstlane(info_v.w)};
     };
+    // how the rows shared with the neighbours will be settled: decided now, not when the sums are there
+    auto plan = [&](int4_t i) {
+        FixupPlan pl = plan_fixup(int4{i.x, i.y, i.z, i.w}, wl, lwg, wpw, worker);
+        asm volatile("" : "+s"(pl.head_mode), "+s"(pl.head_n), "+s"(pl.lead_mode), "+s"(pl.lead_n));
+        return pl;
+    };
 
     WaveState<NB> st;
 #pragma unroll
@@ -714,6 +738,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     st.heads = 0;
     Tile<F> cur;
     int4_t info;
+    FixupPlan pl;
     if (n_tiles == 1) {
         // the whole run is one tile (the default partition's aim): nothing else is in flight
         // behind it, and its blocks are consumed in the order in which they arrive
@@ -721,12 +746,14 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
+        pl = plan(info);
         compute_tile<F, KGP, NB, true>(md.out, cur, lane, xlds, st);
     } else if (n_tiles == 0) {
         // a worker without tiles still helps to stage x
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
+        pl = plan(info);
     } else {
         // a run of several tiles: the next tile is requested before the current one is worked on
         // (the copy at the top of the loop is where the wavefront waits for a tile; inside
@@ -736,6 +763,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
+        pl = plan(info);
         for (int left = n_tiles; left > 0; --left) {
             cur = nxt;
             p += F::TB;
@@ -751,28 +779,24 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         for (int b = 0; b < NB; ++b) md.out.y[b * md.out.N + row] = 0;
     }
 
-    // A wavefront whose run neither continues an earlier worker's row nor leaves a row open has
-    // nothing to settle with its neighbours: it writes its last row and is done.  (A barrier
-    // does not wait for wavefronts that have ended.)
-    if (info.z < 0 && info.w == 0) {
-        if (lane == 0 && (info.y & 1) != 0 && st.heads > 0) {
+    // the last row of the run, if it ends there
+    if (lane == 0 && (info.y & 1) != 0 && st.heads > 0) {
 #pragma unroll
-            for (int b = 0; b < NB; ++b) store_row(md.out, b, info.x + st.heads, st.carry[b]);
-        }
-        return;
+        for (int b = 0; b < NB; ++b) store_row(md.out, b, info.x + st.heads, st.carry[b]);
     }
+    // A wavefront whose run neither continues an earlier worker's row nor leaves a row open has
+    // nothing to settle with its neighbours.  (A barrier does not wait for wavefronts that have
+    // ended.)
+    if (info.z < 0 && info.w == 0) return;
     // Carry fix-up for the rows a run shares with its neighbours.  Inside a workgroup the
     // pieces meet in LDS; only rows spread over several workgroups go through device memory.
     if (lane == 0) {
-        rec_n[wl].info = int4{info.x, info.y, info.z, info.w};
-        rec_n[wl].heads = st.heads;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) rec_s[wl * NB + b] = LdsSums{st.lead[b], st.carry[b]};
+        for (int b = 0; b < NB; ++b) rec[wl * NB + b] = LdsRecord{st.lead[b], st.carry[b], st.heads, 0};
     }
     lds_barrier();
-    if (lane != 0) return;
-    fixup_matrix<NB>(md.out, reinterpret_cast<const int4*>(wave_info), int4{info.x, info.y, info.z, info.w}, st.heads,
-                     st.lead, st.carry, rec_n, rec_s, wl, lwg, wpw, worker);
+    fixup_matrix<NB>(md.out, reinterpret_cast<const int4*>(wave_info), int4{info.x, info.y, info.z, info.w}, pl, st.heads,
+                     st.lead, st.carry, rec, lane, wl, wpw, worker);
 }
 
 // A launchable variant of the kernel.
@@ -784,7 +808,7 @@ struct Variant {
 
 constexpr size_t lds_bytes(int kgp, int nb)
 {
-    return static_cast<size_t>(nb) * 48 * kgp + kWavesPerWorkgroup * (sizeof(LdsCounts) + nb * sizeof(LdsSums));
+    return static_cast<size_t>(nb) * 48 * kgp + kWavesPerWorkgroup * nb * sizeof(LdsRecord);
 }
 
 template <typename F, int KGP, int NB>

@@ -53,6 +53,7 @@ struct gqsa_matrix {
     // device image (host copy) and its map
     int n_workgroups = 0;
     int waves_per_workgroup = 0;
+    int span_tiles = 0;       // tiles per workgroup span that rows are kept inside; 0: rows follow each other without gaps
     int n_waves = 0;          // n_workgroups * waves_per_workgroup
     int64_t n_blocks = 0;     // 64-group blocks of the padded stream = n_tiles * largest_tile(code_bytes)
     int64_t n_tiles = 0;
@@ -76,8 +77,9 @@ namespace gqsa {
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          const int32_t* keep_per_row, double sparsity, const float* hinv_diag,
                          gqsa_matrix* m);
-void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves_per_workgroup);
-gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup);
+int64_t place_rows(const gqsa_matrix& m, int64_t span_groups, std::vector<int64_t>* row_pos);
+void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles);
+gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles);
 
 // device side (gqsa_gemv.hip)
 gqsa_status_t device_upload(gqsa_matrix* m);

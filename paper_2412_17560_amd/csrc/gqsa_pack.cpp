@@ -192,37 +192,103 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
 // blocks, and in a workgroup as many wavefronts (at most 16, at most one per block) as give
 // every wavefront about two blocks' worth of 16-element chunks -- matrices of a few MB are bound
 // by how many compute units pull on memory, not by how long a wavefront's run is.
-// Default partition (measured on MI355X).  K up to 4096, or fewer than 2048 tiles: one tile per
-// worker -- everything it needs requested at once, one segmented scan to settle it -- up to 8192
-// workers, beyond that the fewest tiles per worker that keep to that count; workgroups of 4
+// Where the rows start in the group stream.  span_groups = 0: one after the other, row n at
+// rowIndex[n].  Otherwise the stream is cut into spans of span_groups positions (one per
+// workgroup) and a row that fits a span but not what is left of the current one starts at the next
+// span; the positions skipped hold null groups (they add nothing to the row before them).  A row
+// longer than a span starts where the previous one ended.  Returns the length of the stream (one
+// past the last stored group).
+int64_t place_rows(const gqsa_matrix& m, int64_t span_groups, std::vector<int64_t>* row_pos)
+{
+    if (row_pos) row_pos->assign(static_cast<size_t>(m.N), 0);
+    int64_t pos = 0;
+    for (int64_t n = 0; n < m.N; ++n) {
+        const int64_t cnt = m.rowIndex[n + 1] - m.rowIndex[n];
+        if (span_groups > 0 && cnt > 0 && cnt <= span_groups && pos % span_groups + cnt > span_groups)
+            pos = (pos / span_groups + 1) * span_groups;
+        if (row_pos) (*row_pos)[static_cast<size_t>(n)] = pos;
+        pos += cnt;
+    }
+    return pos;
+}
+
+namespace {
+
+// Partition by size alone (measured on MI355X).  K up to 4096, or fewer than 2048 tiles: one tile
+// per worker -- everything it needs requested at once, one segmented scan to settle it -- up to
+// 8192 workers, beyond that the fewest tiles per worker that keep to that count; workgroups of 4
 // wavefronts (small workgroups meet sooner after x is staged and fill the compute units more
 // evenly), a multiple of 4 of them so that the small-batch kernels can take the same workers 8
 // or 16 to a workgroup.  Larger K, where staging x (48 bytes of LDS per 16 elements) is a large
 // part of a workgroup's work: 8 wavefronts per workgroup and 256, 512 or 768 workgroups -- one,
 // two or three per compute unit, all alike -- as many as keep the bytes of x staged by all
 // workgroups to about a quarter of the matrix's: the multiple of 256 nearest to 448 T / K.
-void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves_per_workgroup)
+void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t* n_workgroups, int64_t* waves_per_workgroup)
 {
-    int64_t wgs = 1, wpw = 1;
     if (K <= 4096 || n_tiles < 2048) {
-        const int64_t per_worker = std::max<int64_t>(1, (n_tiles + 8191) / 8192);
-        const int64_t workers = std::max<int64_t>(1, (n_tiles + per_worker - 1) / per_worker);
-        wpw = std::min<int64_t>(4, workers);
-        wgs = (workers + wpw - 1) / wpw;
-        if (wgs > 4) wgs = (wgs + 3) / 4 * 4;
+        *per_worker = std::max<int64_t>(1, (n_tiles + 8191) / 8192);
+        const int64_t workers = std::max<int64_t>(1, (n_tiles + *per_worker - 1) / *per_worker);
+        *waves_per_workgroup = std::min<int64_t>(4, workers);
+        *n_workgroups = (workers + *waves_per_workgroup - 1) / *waves_per_workgroup;
+        if (*n_workgroups > 4) *n_workgroups = (*n_workgroups + 3) / 4 * 4;
     } else {
-        wpw = 8;
+        *per_worker = 0;      // (whatever the deal gives)
+        *waves_per_workgroup = 8;
         const int64_t per_cu = (448 * n_tiles + 128 * K) / (256 * K);      // round(448 T / K / 256)
-        wgs = kMaxDefaultWorkgroups * std::max<int64_t>(1, std::min<int64_t>(3, per_cu));
+        *n_workgroups = kMaxDefaultWorkgroups * std::max<int64_t>(1, std::min<int64_t>(3, per_cu));
     }
+}
+
+}  // namespace
+
+// Default partition.  First by size (above).  A row whose groups lie in two workgroups costs
+// both an exchange through device memory at the very end of their work (about 0.6 us on an
+// MI355X, whatever the size of the matrix); null groups cost their bytes.  So, if the rows can be
+// kept inside the workgroups' spans (place_rows) with at most 2 MiB of null groups, they are:
+// spans of 4 t tiles for the small shapes (t tiles per worker, t raised if the padded stream
+// needs more than 8192 workers), the workgroup count again a multiple of 4; for the large ones
+// the same 256, 512 or 768 workgroups with the smallest span that holds the rows.
+void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles)
+{
+    const int64_t tile_groups = static_cast<int64_t>(kLanes) * largest_tile(m.code_bytes());
+    const int64_t nnz = m.nnzg();
+    const int64_t n_tiles = (nnz + tile_groups - 1) / tile_groups;
+    int64_t t = 1, wgs = 1, wpw = 1;
+    partition_by_size(n_tiles, m.K, &t, &wgs, &wpw);
     *n_workgroups = static_cast<int>(std::min<int64_t>(wgs, kMaxWorkgroups));
     *waves_per_workgroup = static_cast<int>(wpw);
+    *span_tiles = 0;
+    if (wpw < 4 || wgs < 2) return;       // a handful of tiles: nothing to keep apart
+    const int64_t max_null_groups = (int64_t{2} << 20) / (m.block_bytes() / kLanes);
+    int64_t span = 0, a_wgs = 0;
+    if (t > 0) {
+        for (;; ++t) {
+            span = wpw * t;
+            const int64_t len = place_rows(m, span * tile_groups, nullptr);
+            if (len - nnz > max_null_groups) return;
+            a_wgs = (len + span * tile_groups - 1) / (span * tile_groups);
+            if (a_wgs > 4) a_wgs = (a_wgs + 3) / 4 * 4;
+            if (a_wgs * wpw <= 8192) break;
+        }
+    } else {
+        a_wgs = wgs;
+        for (span = (n_tiles + wgs - 1) / wgs;; ++span) {
+            const int64_t len = place_rows(m, span * tile_groups, nullptr);
+            if (len - nnz > max_null_groups) return;
+            if ((len + span * tile_groups - 1) / (span * tile_groups) <= wgs) break;
+        }
+    }
+    if (a_wgs > kMaxWorkgroups || span > INT32_MAX / 2) return;
+    *n_workgroups = static_cast<int>(a_wgs);
+    *span_tiles = static_cast<int>(span);
 }
 
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
 // 64-group blocks; u_max blocks make a tile: 4 blocks with up to 16 code bytes per
 // group, 2 with 32, 1 with 64 (a wavefront's tile stays within about 24 registers).  The stream
-// is padded with null groups to whole tiles.  The T tiles are dealt in contiguous, near-equal runs
+// is padded with null groups to whole tiles.  (With span_tiles > 0 the rows are first kept inside
+// spans of that many tiles, one span per workgroup -- place_rows -- and T = span_tiles *
+// n_workgroups; n_workgroups = 0 then stands for as many as the rows need.)  The T tiles are dealt in contiguous, near-equal runs
 // to the W = n_workgroups * waves_per_workgroup workers (wavefronts): worker w gets the tiles
 // floor(w T / W) .. floor((w+1) T / W) - 1, so that the workers with one tile more are spread
 // evenly over the workgroups (the nnz-balanced version of the paper's task-centric split,
@@ -238,26 +304,40 @@ void default_partition(int64_t n_tiles, int64_t K, int* n_workgroups, int* waves
 // row-head flag in bit 0.  4-bit code words are nibble-permuted so that one AND per pair of
 // elements yields a packed fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m
 // at bits 4m and element 8h+2m+1 at bits 16+4m.
-gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup)
+gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles)
 {
-    if (n_workgroups < 1 || n_workgroups > kMaxWorkgroups) return GQSA_ERR_RANGE;
+    if (n_workgroups < 0 || n_workgroups > kMaxWorkgroups || span_tiles < 0) return GQSA_ERR_RANGE;
+    if (n_workgroups == 0 && span_tiles == 0) return GQSA_ERR_RANGE;
     if (waves_per_workgroup < 1 || waves_per_workgroup > kWavesPerWorkgroup) return GQSA_ERR_RANGE;
-    const int n_waves = n_workgroups * waves_per_workgroup;
     const int64_t nnz = m->nnzg();
     const int cb = m->code_bytes();
     const int u_max = largest_tile(cb);
     const int64_t tile_groups = static_cast<int64_t>(kLanes) * u_max;
-    const int64_t n_tiles = (nnz + tile_groups - 1) / tile_groups;
+    if (span_tiles > (int64_t{1} << 40) / tile_groups) return GQSA_ERR_RANGE;
+    // rows -> stream positions; with spans, one span per workgroup
+    std::vector<int64_t> row_pos;
+    const int64_t span_groups = span_tiles * tile_groups;
+    const int64_t len = place_rows(*m, span_groups, &row_pos);       // one past the last stored group
+    int64_t n_tiles = (len + tile_groups - 1) / tile_groups;
+    if (span_tiles > 0) {
+        const int64_t n_spans = std::max<int64_t>(1, (len + span_groups - 1) / span_groups);
+        if (n_workgroups == 0) n_workgroups = static_cast<int>(std::min<int64_t>(n_spans, kMaxWorkgroups + 1));
+        if (n_spans > n_workgroups || n_workgroups > kMaxWorkgroups) return GQSA_ERR_RANGE;
+        n_tiles = static_cast<int64_t>(span_tiles) * n_workgroups;
+    }
+    const int n_waves = n_workgroups * waves_per_workgroup;
     const int64_t nb = n_tiles * u_max;
     const size_t bb = static_cast<size_t>(m->block_bytes());
     auto align = [](size_t v) { return (v + kAlign - 1) / kAlign * kAlign; };
 
     std::vector<int32_t> nonempty, empty;
-    std::vector<uint8_t> head(static_cast<size_t>(nnz) + 1, 0);
+    std::vector<int64_t> head_pos;          // stream positions of the row heads, ascending
+    std::vector<uint8_t> head(static_cast<size_t>(len) + 1, 0);
     for (int64_t n = 0; n < m->N; ++n) {
         if (m->rowIndex[n + 1] > m->rowIndex[n]) {
             nonempty.push_back(static_cast<int32_t>(n));
-            head[m->rowIndex[n]] = 1;
+            head_pos.push_back(row_pos[static_cast<size_t>(n)]);
+            head[static_cast<size_t>(row_pos[static_cast<size_t>(n)])] = 1;
         } else {
             empty.push_back(static_cast<int32_t>(n));
         }
@@ -280,7 +360,10 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     const int chunks = m->G / 16;                    // 16-element chunks per group
     const int plane_bytes = std::min(cb, 16);
     std::vector<uint8_t> code(static_cast<size_t>(cb));
-    auto put_group = [&](int64_t g, int64_t block, int lane) {
+    auto put_group = [&](int64_t g, int64_t pos) {
+        const int64_t p = pos % tile_groups;
+        const int64_t block = pos / tile_groups * u_max + p % u_max;
+        const int lane = static_cast<int>(p / u_max);
         uint8_t* base = img.data() + static_cast<size_t>(block) * bb;
         const uint8_t* v = &m->values[static_cast<size_t>(g) * cb];
         if (m->bits == 4) {
@@ -303,10 +386,15 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
                             (static_cast<uint32_t>(m->zeros[g]) << 16);
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + lane * 4, &sz, 4);
         // byte offset in LDS of the group's first 16 activations, row-head flag in bit 0
-        const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * chunks) << 4) | (head[g] ? 1 : 0));
+        const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * chunks) << 4) | (head[static_cast<size_t>(pos)] ? 1 : 0));
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
-    // Per worker: {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}.
+    for (int64_t n = 0; n < m->N; ++n)
+        for (int64_t g = m->rowIndex[n]; g < m->rowIndex[n + 1]; ++g)
+            put_group(g, row_pos[static_cast<size_t>(n)] + (g - m->rowIndex[n]));
+
+    // Per worker: {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}.  (A null group
+    // between two rows counts as part of the row before it.)
     //   rank_base   rank (among non-empty rows) of the row that is open when the run starts,
     //               i.e. (row heads before the run) - 1
     //   tail_closed 1 if the row open at the end of the run has no group beyond it
@@ -317,9 +405,6 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     //               number of consecutive workers holding groups of that row, else 0
     //   lead_len    chain_len of worker lead_first (0 without one): tells the worker how the row
     //               it continues is settled without a look at the other worker's record
-    std::vector<int64_t> head_pos;          // stream positions of the row heads, ascending
-    head_pos.reserve(nonempty.size());
-    for (int32_t n : nonempty) head_pos.push_back(m->rowIndex[n]);
     auto heads_below = [&](int64_t pos) {
         return static_cast<int64_t>(std::lower_bound(head_pos.begin(), head_pos.end(), pos) -
                                     head_pos.begin());
@@ -335,23 +420,16 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     int32_t* info = reinterpret_cast<int32_t*>(img.data() + map.wave_info);
     int fix = 0;
     for (int w = 0; w < n_waves; ++w) {
-        const int64_t block0 = first_block[w];
-        const int64_t mine = first_block[w + 1] - block0;
-        const int64_t first = block0 * kLanes;
-        const int64_t end = (block0 + mine) * kLanes;
-        int64_t pos = first;
-        for (int64_t blk = block0; blk < block0 + mine; blk += u_max) {
-            for (int p = 0; p < kLanes * u_max && pos + p < nnz; ++p)
-                put_group(pos + p, blk + p % u_max, p / u_max);
-            pos += tile_groups;
-        }
-        const int64_t hb = heads_below(std::min(first, nnz));
-        const int64_t he = heads_below(std::min(end, nnz));
-        const int closed = (end >= nnz || head[end]) ? 1 : 0;
+        const int64_t mine = first_block[w + 1] - first_block[w];
+        const int64_t first = first_block[w] * kLanes;
+        const int64_t end = first_block[w + 1] * kLanes;
+        const int64_t hb = heads_below(std::min(first, len));
+        const int64_t he = heads_below(std::min(end, len));
+        const int closed = (end >= len || head[static_cast<size_t>(end)]) ? 1 : 0;
         int32_t lead_first = -1, chain_len = 0;
-        if (first < nnz && !head[first]) lead_first = worker_of(head_pos[hb - 1]);
+        if (first < len && !head[static_cast<size_t>(first)]) lead_first = worker_of(head_pos[hb - 1]);
         if (mine > 0 && !closed && he > hb) {
-            const int64_t row_last = (he < static_cast<int64_t>(head_pos.size()) ? head_pos[he] : nnz) - 1;
+            const int64_t row_last = (he < static_cast<int64_t>(head_pos.size()) ? head_pos[he] : len) - 1;
             chain_len = worker_of(row_last) - w + 1;
             fix = 1;
         }
@@ -371,6 +449,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     m->map = map;
     m->n_workgroups = n_workgroups;
     m->waves_per_workgroup = waves_per_workgroup;
+    m->span_tiles = span_tiles;
     m->n_waves = n_waves;
     m->n_blocks = nb;
     m->n_tiles = n_tiles;

@@ -134,7 +134,11 @@ def test_info_fields():
     nnz = int(keep.sum())
     assert info["N"] == 100 and info["K"] == 512 and info["G"] == 16 and info["bits"] == 8
     assert info["nnz_groups"] == nnz and info["values_bytes"] == nnz * 16
-    assert info["n_blocks"] == 4 * ((nnz + 255) // 256)    # whole tiles of four 64-group blocks (16 code bytes)
+    # whole tiles of four 64-group blocks (16 code bytes); by default the rows are kept inside the workgroups' spans
+    assert info["span_tiles"] == 4 and info["n_blocks"] == 4 * info["span_tiles"] * info["n_workgroups"]
+    gq.gqsa_set_partition(h, 3, 2)
+    info = gq.gqsa_info(h)
+    assert info["span_tiles"] == 0 and info["n_blocks"] == 4 * ((nnz + 255) // 256)
     assert info["n_empty_rows"] == int((keep == 0).sum())
     assert info["on_device"] == 0
     assert info["algorithmic_bytes"] == nnz * 22 + 101 * 4 + (512 + 100) * 2

@@ -96,6 +96,43 @@ def test_rows_spanning_two_and_more_workgroups(torch_cuda, part, batch):
     check(torch_cuda, h, c, gi.activations(batch, K, seed=8))
 
 
+@pytest.mark.parametrize("part", [(1, 0, 1), (1, 0, 4), (2, 0, 3), (4, 0, 4), (3, 0, 16), (16, 0, 8), (4, 64, 4),
+                                  (1000, 3, 16)])
+@pytest.mark.parametrize("batch", [1, 3])
+def test_rows_kept_inside_workgroup_spans(torch_cuda, part, batch):
+    """The aligned form of the stream: null groups before the span boundaries, workers whose whole
+    run is null, rows longer than a span (shared by workgroups as in the plain form), empty rows."""
+    N, K = 301, 2048
+    W = gi.dense_weight(N, K, seed=78)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=78)
+    keep[[0, 5, 6, 7, 300]] = 0
+    keep[100] = K // 16
+    c = oracle.pack(W, 16, 4, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition_aligned(h, *part)
+    assert gq.gqsa_info(h)["span_tiles"] == part[0]
+    check(torch_cuda, h, c, gi.activations(batch, K, seed=9))
+
+
+@pytest.mark.parametrize("keep_n,expect", [(179, (820, 4, 4)), (77, (316, 4, 4)), (100, (412, 4, 4))])
+def test_default_keeps_rows_inside_workgroups_full_size(torch_cuda, keep_n, expect):
+    """4096x4096 with rows that do not divide the tiles (S = 30 %, 70 %, 61 %): the default keeps
+    every row inside a workgroup; every output checked, also of the plain form with as many workers."""
+    N, K = 4096, 4096
+    W = gi.dense_weight_chunked(N, K, seed=41)
+    keep = np.full(N, keep_n, dtype=np.int32)
+    c = oracle.pack(W, 16, 4, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, 16, 4)
+    info = gq.gqsa_info(h)
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == expect
+    x = gi.activations(1, K, seed=10)
+    check(torch_cuda, h, c, x)
+    gq.gqsa_free(h)
+    h2 = gq.gqsa_pack_rows(W, keep, 16, 4)     # the plain form with the same workers: rows shared by workgroups
+    gq.gqsa_set_partition(h2, expect[0], 4)
+    check(torch_cuda, h2, c, x)
+
+
 def adversarial_keeps(N, kg):
     one_row = np.zeros(N, dtype=np.int32); one_row[N // 2] = kg
     alternating = np.where(np.arange(N) % 2 == 0, 0, kg).astype(np.int32)
@@ -353,7 +390,7 @@ def test_other_group_sizes_full_size_and_sparsities(torch_cuda, G):
         h = gq.gqsa_pack(W, G, 4, sparsity)
         c = oracle.pack(W, G, 4, sparsity=sparsity)
         info = gq.gqsa_info(h)
-        assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"])
+        assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
         check(torch_cuda, h, c, gi.activations(1, 4096, seed=11))
 
 
@@ -406,7 +443,7 @@ def test_llama7b_layer_shapes_full_size(torch_cuda, idx):
     h = gq.gqsa_pack(W, 16, 4, 0.5)
     c = oracle.pack(W, 16, 4, sparsity=0.5)
     info = gq.gqsa_info(h)
-    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"])
+    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
     check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(2, idx)))
 
 

@@ -14,22 +14,47 @@ import oracle
 from oracle import layout
 
 
+def _balanced(n_rows, per_row):
+    return np.arange(n_rows + 1, dtype=np.int64) * per_row
+
+
 def test_default_partition():
-    assert oracle.default_partition(0, 4096) == (1, 1)
-    assert oracle.default_partition(256 * 3, 256) == (1, 3)           # 3 tiles of 256 groups, one per wavefront
-    assert oracle.default_partition(2048, 256) == (2, 4)              # 8 tiles
-    assert oracle.default_partition(256 * 17, 4096) == (8, 4)         # 17 workers -> 5 workgroups -> a multiple of 4
-    assert oracle.default_partition(524288, 4096) == (512, 4)         # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront
-    assert oracle.default_partition(1409024, 4096) == (1376, 4)       # 11008x4096: 5504 tiles
-    assert oracle.default_partition(256 * 8192, 4096) == (2048, 4)    # the most workers
-    assert oracle.default_partition(256 * 8193, 4096) == (1028, 4)    # beyond: two tiles per worker, 4097 workers
-    assert oracle.default_partition(1409024, 11008) == (256, 8)       # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit, 2.7 tiles per worker
-    assert oracle.default_partition(256 * 8191, 8192) == (512, 8)     # 448 T / K = 448 -> two per compute unit
-    assert oracle.default_partition(256 * 28615, 8192) == (768, 8)    # at most three
-    assert oracle.default_partition(256 * 4096, 8192) == (256, 8)     # 4096x8192 at S = 50 %
-    assert oracle.default_partition(256 * 100, 32768) == (28, 4)      # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
-    assert oracle.default_partition(64 * 1024, 4096, G=128) == (256, 4)   # 64 code bytes: a tile is one block, 1024 tiles
-    assert oracle.default_partition(128 * 2048, 4096, G=16, bits=8) == (256, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
+    dp = oracle.default_partition
+    assert dp(_balanced(1, 0), 4096) == (1, 1, 0)
+    assert dp(_balanced(3, 256), 256) == (1, 3, 0)              # 3 tiles of 256 groups, one per wavefront
+    assert dp(_balanced(16, 128), 256) == (2, 4, 4)             # 8 tiles; two rows per tile
+    assert dp(_balanced(17, 256), 4096) == (8, 4, 4)            # 17 workers -> 5 workgroups -> a multiple of 4
+    assert dp(_balanced(4096, 128), 4096) == (512, 4, 4)        # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront; no null group needed
+    assert dp(_balanced(11008, 128), 4096) == (1376, 4, 4)      # 11008x4096: 5504 tiles
+    assert dp(_balanced(8192, 256), 4096) == (2048, 4, 4)       # the most workers
+    assert dp(_balanced(8193, 256), 4096) == (1028, 4, 8)       # beyond: two tiles per worker, 4097 workers
+    assert dp(_balanced(4096, 344), 11008) == (256, 8, 22)      # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
+    assert dp(_balanced(8191, 256), 8192) == (512, 8, 16)       # 448 T / K = 448 -> two per compute unit
+    assert dp(_balanced(28615, 256), 8192) == (768, 8, 38)      # at most three
+    assert dp(_balanced(4096, 256), 8192) == (256, 8, 16)       # 4096x8192 at S = 50 %
+    assert dp(_balanced(100, 256), 32768) == (28, 4, 4)         # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
+    assert dp(_balanced(1024, 64), 4096, G=128) == (256, 4, 4)  # 64 code bytes: a tile is one block, 1024 tiles
+    assert dp(_balanced(2048, 128), 4096, G=16, bits=8) == (256, 4, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
+    # rows that do not divide the spans: null groups keep them inside
+    assert dp(_balanced(4096, 179), 4096) == (820, 4, 4)        # S = 30 %: 5 rows per span of 1024, 820 spans
+    assert dp(_balanced(14336, 179), 4096) == (1304, 4, 8)      # 10024 tiles -> two per worker, 11 rows per span of 2048
+    assert dp(_balanced(4096, 77), 4096) == (316, 4, 4)         # S = 70 %: 13 rows per span, 316 spans
+    # too many null groups (a row of 600 per span of 1024: 424 of 1024 positions empty): the plain deal
+    assert dp(_balanced(12000, 600), 16384) == (768, 8, 0)
+
+
+def test_row_positions():
+    ri = np.array([0, 3, 3, 9, 10, 16, 17])         # rows of 3, 0, 6, 1, 6, 1 groups
+    pos, L = oracle.row_positions(ri, 0)
+    assert pos.tolist() == [0, 3, 3, 9, 10, 16] and L == 17
+    pos, L = oracle.row_positions(ri, 8)             # 3 | skip to 8: 6, 1 | skip to 16: 6, 1
+    assert pos.tolist() == [0, 3, 8, 14, 16, 22] and L == 23
+    pos, L = oracle.row_positions(ri, 9)             # 3 + 6 fill the first span exactly
+    assert pos.tolist() == [0, 3, 3, 9, 10, 16] and L == 17
+    pos, L = oracle.row_positions(ri, 4)             # the rows of 6 are longer than a span: they start where the last one ended
+    assert pos.tolist() == [0, 3, 3, 9, 10, 16] and L == 17
+    pos, L = oracle.row_positions(np.array([0, 4, 8, 9]), 4)   # exact fits need nothing
+    assert pos.tolist() == [0, 4, 8] and L == 9
 
 
 def test_tile_deal_by_hand():

@@ -24,7 +24,7 @@ def assert_same_canonical(h, c):
 def assert_same_blob(h, c):
     info = gq.gqsa_info(h)
     blob = gq.gqsa_export_device_blob(h)
-    ref = oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"])
+    ref = oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
     assert len(blob) == len(ref) == info["device_bytes"]
     assert blob == ref
 
@@ -39,8 +39,68 @@ def test_tiny_config_balanced(bits, sparsity):
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == c.nnzg
-    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, 256, 16, bits)
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == oracle.default_partition(c.rowIndex, 256, 16, bits)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
+
+
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 64), (4, 128)])
+def test_rows_kept_inside_workgroup_spans(bits, G):
+    """The aligned form of the stream: spans, null groups between them, worker records."""
+    N, K = 301, 2048
+    W = gi.dense_weight(N, K, seed=78)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=78)
+    keep[[0, 5, 6, 7, 300]] = 0                         # empty rows at the ends and in a run
+    keep[100] = K // G                                  # a full row
+    h = gq.gqsa_pack_rows(W, keep, G, bits)
+    c = oracle.pack(W, G, bits, keep_per_row=keep)
+    U = 4 if G * bits // 8 <= 16 else (2 if G * bits // 8 <= 32 else 1)
+    for span, wgs, wpw in ((1, 0, 1), (1, 0, 4), (2, 0, 3), (4, 0, 4), (3, 0, 16), (16, 0, 8), (4, 64, 4), (1000, 0, 2), (1000, 3, 16)):
+        _, L = oracle.row_positions(c.rowIndex, span * 64 * U)
+        need = max(1, -(-L // (span * 64 * U)))
+        if need > 4096:
+            continue
+        gq.gqsa_set_partition_aligned(h, span, wgs, wpw)
+        info = gq.gqsa_info(h)
+        assert info["span_tiles"] == span and info["waves_per_workgroup"] == wpw
+        assert info["n_workgroups"] == (wgs if wgs else need)
+        assert info["n_blocks"] == U * span * info["n_workgroups"]
+        assert_same_blob(h, c)
+    # fewer workgroups than the rows need spans; bad arguments
+    _, L = oracle.row_positions(c.rowIndex, 64 * U)
+    need = -(-L // (64 * U))
+    if 1 < need <= 4096:
+        with pytest.raises(gq.GqsaError) as e:
+            gq.gqsa_set_partition_aligned(h, 1, need - 1, 4)
+        assert e.value.status == 4
+    for bad in ((0, 0, 4), (-1, 4, 4), (1, 4097, 4), (1, 0, 0), (1, 0, 17), (1, -1, 4)):
+        with pytest.raises(gq.GqsaError) as e:
+            gq.gqsa_set_partition_aligned(h, *bad)
+        assert e.value.status == 4
+    gq.gqsa_set_partition(h, 5, 3)                       # and back to the plain form
+    assert gq.gqsa_info(h)["span_tiles"] == 0
+    assert_same_blob(h, c)
+
+
+def test_aligned_stream_keeps_rows_inside_spans():
+    """Read back from the image: no row of at most a span's length has groups in two spans."""
+    N, K, G, bits = 500, 4096, 16, 4
+    W = gi.dense_weight(N, K, seed=79)
+    keep = np.full(N, 179, dtype=np.int32)               # S = 30 %: 5 rows per span of 1024, 129 null groups after them
+    h = gq.gqsa_pack_rows(W, keep, G, bits)
+    info = gq.gqsa_info(h)
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == (100, 4, 4)
+    blob = np.frombuffer(gq.gqsa_export_device_blob(h), dtype=np.uint8)
+    nblocks = info["n_blocks"]
+    blk = blob[:nblocks * 896].reshape(nblocks, 896)
+    ix = blk[:, 768:].copy().view("<u2").reshape(nblocks // 4, 4, 64)      # [tile][block][lane]
+    sz = blk[:, 512:768].copy().view("<u4").reshape(nblocks // 4, 4, 64)
+    heads = (ix & 1).transpose(0, 2, 1).reshape(-1)      # stream order: position = tile*256 + lane*4 + block
+    scale = (sz & 0xFFFF).transpose(0, 2, 1).reshape(-1)
+    head_pos = np.nonzero(heads)[0]
+    assert len(head_pos) == N
+    assert np.all(head_pos // 1024 == (head_pos + 178) // 1024)
+    assert np.array_equal(head_pos[:6], [0, 179, 358, 537, 716, 1024])
+    assert np.all(scale[895:1024] == 0) and np.all(ix.transpose(0, 2, 1).reshape(-1)[895:1024] == 0)   # the null groups
 
 
 @pytest.mark.parametrize("bits", [4, 8])
@@ -71,7 +131,7 @@ def test_other_group_sizes(bits, G):
     assert_same_canonical(h, c)
     info = gq.gqsa_info(h)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(N, K, G, bits, c.nnzg, 1)
-    assert (info["n_workgroups"], info["waves_per_workgroup"]) == oracle.default_partition(c.nnzg, K, G, bits)
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == oracle.default_partition(c.rowIndex, K, G, bits)
     for part in (None, (1, 1), (3, 1), (5, 3), (1, 16), (17, 2), (40, 16)):
         if part is not None:
             gq.gqsa_set_partition(h, *part)
