@@ -216,7 +216,8 @@ namespace {
 
 // Partition by size alone (measured on MI355X).  K up to 4096, or fewer than 2048 tiles: one tile
 // per worker -- everything it needs requested at once, one segmented scan to settle it -- up to
-// 8192 workers, beyond that the fewest tiles per worker that keep to that count; workgroups of 4
+// 16384 workers (several rounds of wavefronts per compute unit stream better than a few long
+// runs), beyond that the fewest tiles per worker that keep to that count; workgroups of 4
 // wavefronts (small workgroups meet sooner after x is staged and fill the compute units more
 // evenly), a multiple of 4 of them so that the small-batch kernels can take the same workers 8
 // or 16 to a workgroup.  Larger K, where staging x (48 bytes of LDS per 16 elements) is a large
@@ -226,7 +227,7 @@ namespace {
 void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t* n_workgroups, int64_t* waves_per_workgroup)
 {
     if (K <= 4096 || n_tiles < 2048) {
-        *per_worker = std::max<int64_t>(1, (n_tiles + 8191) / 8192);
+        *per_worker = std::max<int64_t>(1, (n_tiles + 16383) / 16384);
         const int64_t workers = std::max<int64_t>(1, (n_tiles + *per_worker - 1) / *per_worker);
         *waves_per_workgroup = std::min<int64_t>(4, workers);
         *n_workgroups = (workers + *waves_per_workgroup - 1) / *waves_per_workgroup;
@@ -245,8 +246,9 @@ void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t*
 // both an exchange through device memory at the very end of their work (about 0.6 us on an
 // MI355X, whatever the size of the matrix); null groups cost their bytes.  So, if the rows can be
 // kept inside the workgroups' spans (place_rows) with at most 2 MiB of null groups, they are:
-// spans of 4 t tiles for the small shapes (t tiles per worker, t raised if the padded stream
-// needs more than 8192 workers), the workgroup count again a multiple of 4; for the large ones
+// spans of 4 t tiles for the small shapes (t the tiles per worker by size, or one more if that
+// needs too many null groups or more than 16384 workers), the workgroup count again a multiple of
+// 4; for the large ones
 // the same 256, 512 or 768 workgroups with the smallest span that holds the rows.
 void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles)
 {
@@ -262,14 +264,15 @@ void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_w
     const int64_t max_null_groups = (int64_t{2} << 20) / (m.block_bytes() / kLanes);
     int64_t span = 0, a_wgs = 0;
     if (t > 0) {
-        for (;; ++t) {
-            span = wpw * t;
+        bool found = false;
+        for (int64_t tt = t; tt <= t + 1 && !found; ++tt) {     // the tiles per worker by size, or one more
+            span = wpw * tt;
             const int64_t len = place_rows(m, span * tile_groups, nullptr);
-            if (len - nnz > max_null_groups) return;
             a_wgs = (len + span * tile_groups - 1) / (span * tile_groups);
             if (a_wgs > 4) a_wgs = (a_wgs + 3) / 4 * 4;
-            if (a_wgs * wpw <= 8192) break;
+            found = len - nnz <= max_null_groups && a_wgs * wpw <= 16384;
         }
+        if (!found) return;
     } else {
         a_wgs = wgs;
         for (span = (n_tiles + wgs - 1) / wgs;; ++span) {
@@ -309,7 +312,6 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     if (n_workgroups < 0 || n_workgroups > kMaxWorkgroups || span_tiles < 0) return GQSA_ERR_RANGE;
     if (n_workgroups == 0 && span_tiles == 0) return GQSA_ERR_RANGE;
     if (waves_per_workgroup < 1 || waves_per_workgroup > kWavesPerWorkgroup) return GQSA_ERR_RANGE;
-    const int64_t nnz = m->nnzg();
     const int cb = m->code_bytes();
     const int u_max = largest_tile(cb);
     const int64_t tile_groups = static_cast<int64_t>(kLanes) * u_max;

@@ -470,6 +470,22 @@ def test_imbalanced_stress_full_size(torch_cuda, idx):
     check(torch_cuda, h, c, gi.activations(1, K, seed=seed))
 
 
+def test_vocabulary_sized_matrix(torch_cuda):
+    """128256x4096 (the output projection of a LLaMA-3-8B-like model), W4S50: 16.4 M stored groups,
+    64 128 tiles, four per wavefront in 4008 workgroups -- the largest deal the default makes.
+    Every output checked."""
+    N, K = 128256, 4096
+    W = gi.dense_weight_chunked(N, K, seed=51)
+    h = gq.gqsa_pack(W, 16, 4, 0.5)
+    c = oracle.pack(W, 16, 4, sparsity=0.5)
+    del W
+    info = gq.gqsa_info(h)
+    assert info["nnz_groups"] == N * 128
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == (4008, 4, 16)
+    check(torch_cuda, h, c, gi.activations(1, K, seed=52))
+    gq.gqsa_free(h)
+
+
 def test_llama7b_qkv_and_gate_up_fused_full_size(torch_cuda):
     """The fused launches the benchmark times: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096)."""
     torch = torch_cuda
