@@ -64,6 +64,7 @@ typedef struct {
     int64_t algorithmic_bytes;  /* compressed bytes one batch-1 call must move (see README of bench) */
     int32_t on_device;          /* 1 once the device image exists */
     int32_t reserved;
+    int64_t panel_bytes;        /* size of the second image built by gqsa_build_panels, 0 without one */
 } gqsa_info_t;
 
 /*
@@ -140,6 +141,29 @@ gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_pe
  */
 gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_workgroups,
                                          int waves_per_workgroup);
+
+/*
+ * Build a second image of the matrix for calls with 9 to 16 activation rows (the small-batch
+ * side of Sec. 3.5's kernel, which may use the matrix cores): the stored groups of 16 consecutive
+ * output rows ordered by group-column, so that one group-column of such a panel and the
+ * activations under it are a dense 16x16x16 product (absent groups count as zeros).  Codes,
+ * scales and zeros are the same bits as in the canonical arrays; the image takes about 12.5
+ * bytes per stored 4-bit group on top of the first one.  Host only; only before the handle is
+ * uploaded (GQSA_ERR_UNSUPPORTED after); G = 16 only (GQSA_ERR_UNSUPPORTED otherwise).  Once
+ * built, gqsa_upload copies both images and gqsa_gemv / gqsa_gemv_multi use this one for
+ * batch >= 9 (gqsa_gemv_multi: one launch per matrix); results stay within the same bound (fp32
+ * accumulation of exact products, one rounding to fp16) but are not bit-identical to those of
+ * the other kernel.
+ */
+gqsa_status_t gqsa_build_panels(gqsa_handle_t h);
+
+/* gqsa_gemv from the second image whatever the batch (1..16): same arguments, same checks;
+ * GQSA_ERR_UNSUPPORTED if the handle has no such image. */
+gqsa_status_t gqsa_gemv_panels(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch, void* hip_stream);
+
+/* Copy the exact bytes of that second image into host_buf; bytes >= panel_bytes of gqsa_info.
+ * GQSA_ERR_UNSUPPORTED if the handle has none. */
+gqsa_status_t gqsa_export_panel_blob(gqsa_handle_t h, void* host_buf, size_t bytes);
 
 /* Create the device image and carry workspace on the current HIP device (synchronous). */
 gqsa_status_t gqsa_upload(gqsa_handle_t h);

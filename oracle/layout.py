@@ -59,6 +59,28 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     the empty rows.
  6. Blob = blocks, wave_info, row_of_rank, empty_rows, each region starting
     at a multiple of 256 bytes, zero padded, total a multiple of 256 (>= 256).
+
+Second image (panel_blob; G = 16 only), for calls with many activation rows --
+again a pure reordering of the canonical arrays:
+ P1. Panels of 16 consecutive rows (P = ceil(N/16); rows >= N have no groups)
+     and slices of 32 consecutive group-columns (S = ceil(K/16/32); columns
+     >= K/16 have no groups).  Block (p, s) holds the stored groups of panel p
+     whose group-column lies in slice s, ordered by (group-column, row).
+ P2. Header of block (p, s): 36 x uint32 at byte 144 (p S + s) of the image.
+     Word j < 32, for group-column 32 s + j: bit r (r < 16) set if row 16 p + r
+     stores a group in that column; bits 16..31 = number of groups of the block
+     in the columns before it.  Word 32 = start of the block's data in 16-byte
+     units from the start of the data region; word 33 = number of groups of the
+     block; words 34, 35 = 0.  The header region is zero padded to a multiple
+     of 256 bytes.
+ P3. Data region: the blocks' data follow each other in header order without
+     gaps.  A block's data: codes, per group its 2*bits bytes; 8-bit codes as in
+     the canonical `values`; 4-bit codes with every pair of canonical bytes
+     (e0 | e1 << 4), (e2 | e3 << 4) stored as (e0 | e2 << 4), (e1 | e3 << 4);
+     zero padded to a multiple of 16 bytes.  Then parameters: per group uint32
+     fp16 scale bits | fp16 zero bits << 16; zero padded to a multiple of 16
+     bytes.  After the last block 256 zero bytes; the image is zero padded to a
+     multiple of 256 bytes.
 """
 from __future__ import annotations
 
@@ -277,3 +299,59 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
     if len(out) == 0:
         out += b"\0" * ALIGN
     return bytes(out)
+
+
+def panel_blob(c) -> bytes:
+    """Exact bytes of the second (panel) image for canonical arrays `c` (spec items P1-P3)."""
+    if c.G != 16 or c.bits not in (4, 8):
+        raise ValueError("the panel image is specified for G = 16, bits in {4, 8}")
+    cb = 2 * c.bits
+    ri = np.asarray(c.rowIndex, dtype=np.int64)
+    gcol = np.asarray(c.groups, dtype=np.int64)
+    nnzg = c.nnzg
+    P = -(-c.N // 16)
+    S = -(-(c.K // 16) // 32)
+    row = np.repeat(np.arange(c.N, dtype=np.int64), ri[1:] - ri[:-1])
+    blk = (row // 16) * S + gcol // 32
+    # order inside the image: block, then group-column, then row
+    order = np.lexsort((row, gcol, blk))
+    counts = np.bincount(blk, minlength=P * S).astype(np.int64)
+    pad16 = lambda v: (v + 15) // 16 * 16
+    sizes = pad16(counts * cb) + pad16(counts * 4)
+    starts = np.concatenate(([0], np.cumsum(sizes)))
+    header_bytes = _align(P * S * 144)
+    total = _align(header_bytes + int(starts[-1]) + 256)
+    img = np.zeros(total, dtype=np.uint8)
+    vals = np.asarray(c.values, dtype=np.uint8).reshape(nnzg, cb)
+    if c.bits == 4:
+        even, odd = vals[:, 0::2], vals[:, 1::2]                  # (e0 | e1 << 4), (e2 | e3 << 4)
+        stored = np.empty_like(vals)
+        stored[:, 0::2] = (even & 0x0F) | ((odd & 0x0F) << 4)     # e0 | e2 << 4
+        stored[:, 1::2] = (even >> 4) | (odd & 0xF0)              # e1 | e3 << 4
+    else:
+        stored = vals
+    sz = (np.asarray(c.scales, dtype=np.uint32) | (np.asarray(c.zeros, dtype=np.uint32) << np.uint32(16))).astype("<u4")
+    first = np.concatenate(([0], np.cumsum(counts)))          # index into `order` of each block's first group
+    for b in range(P * S):
+        k = int(counts[b])
+        g = order[first[b]:first[b] + k]
+        header = np.zeros(36, dtype=np.uint32)
+        cols = gcol[g] - (b % S) * 32
+        rows = row[g] - (b // S) * 16
+        before = 0
+        for j in range(32):
+            here = rows[cols == j]
+            mask = 0
+            for r in here.tolist():
+                mask |= 1 << r
+            header[j] = mask | (before << 16)
+            before += len(here)
+        header[32] = starts[b] // 16
+        header[33] = k
+        img[b * 144:(b + 1) * 144] = header.astype("<u4").view(np.uint8)
+        if k:
+            base = header_bytes + int(starts[b])
+            img[base:base + k * cb] = stored[g].reshape(-1)
+            pbase = base + int(pad16(k * cb))
+            img[pbase:pbase + 4 * k] = sz[g].view(np.uint8)
+    return img.tobytes()

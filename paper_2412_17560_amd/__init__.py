@@ -10,7 +10,9 @@ from .binding import (  # noqa: F401
     gqsa_copy,
     gqsa_dense_f16_gemv,
     gqsa_export,
+    gqsa_build_panels,
     gqsa_export_device_blob,
+    gqsa_export_panel_blob,
     gqsa_free,
     gqsa_gemv,
     gqsa_gemv_multi,

@@ -23,7 +23,7 @@ class _Info(C.Structure):
                 ("n_workgroups", C.c_int32), ("waves_per_workgroup", C.c_int32),
                 ("needs_fixup", C.c_int32), ("span_tiles", C.c_int32), ("n_empty_rows", C.c_int64),
                 ("device_bytes", C.c_int64), ("algorithmic_bytes", C.c_int64),
-                ("on_device", C.c_int32), ("reserved", C.c_int32)]
+                ("on_device", C.c_int32), ("reserved", C.c_int32), ("panel_bytes", C.c_int64)]
 
 
 def library_path() -> str:
@@ -59,12 +59,18 @@ def _lib():
     lib.gqsa_import.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, C.POINTER(vp)]
     lib.gqsa_set_partition.restype = C.c_int
     lib.gqsa_set_partition.argtypes = [vp, i32, i32]
+    lib.gqsa_build_panels.restype = C.c_int
+    lib.gqsa_build_panels.argtypes = [vp]
+    lib.gqsa_export_panel_blob.restype = C.c_int
+    lib.gqsa_export_panel_blob.argtypes = [vp, vp, C.c_size_t]
     lib.gqsa_set_partition_aligned.restype = C.c_int
     lib.gqsa_set_partition_aligned.argtypes = [vp, i32, i32, i32]
     lib.gqsa_upload.restype = C.c_int
     lib.gqsa_upload.argtypes = [vp]
     lib.gqsa_gemv.restype = C.c_int
     lib.gqsa_gemv.argtypes = [vp, vp, vp, i32, vp]
+    lib.gqsa_gemv_panels.restype = C.c_int
+    lib.gqsa_gemv_panels.argtypes = [vp, vp, vp, i32, vp]
     lib.gqsa_gemv_multi.restype = C.c_int
     lib.gqsa_gemv_multi.argtypes = [C.POINTER(vp), i32, vp, C.POINTER(vp), i32, vp]
     lib.gqsa_info.restype = C.c_int
@@ -189,6 +195,17 @@ def gqsa_set_partition_aligned(h: GqsaHandle, span_tiles: int, n_workgroups: int
            "gqsa_set_partition_aligned")
 
 
+def gqsa_build_panels(h: GqsaHandle) -> None:
+    _check(_lib().gqsa_build_panels(h.ptr), "gqsa_build_panels")
+
+
+def gqsa_export_panel_blob(h: GqsaHandle) -> bytes:
+    n = gqsa_info(h)["panel_bytes"]
+    buf = np.zeros(max(n, 1), dtype=np.uint8)
+    _check(_lib().gqsa_export_panel_blob(h.ptr, _np_ptr(buf), n), "gqsa_export_panel_blob")
+    return buf[:n].tobytes()
+
+
 def gqsa_upload(h: GqsaHandle) -> None:
     _check(_lib().gqsa_upload(h.ptr), "gqsa_upload")
 
@@ -242,8 +259,9 @@ def _dev_ptr(t, dtype_name: str, what: str):
     return C.c_void_p(t.data_ptr())
 
 
-def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None):
-    """y[batch,N] (fp16, device) = W^ x[batch,K]; enqueues on `stream` (default: torch's current)."""
+def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None, panels: bool = False):
+    """y[batch,N] (fp16, device) = W^ x[batch,K]; enqueues on `stream` (default: torch's current).
+    panels=True: gqsa_gemv_panels (the second image, whatever the batch)."""
     import torch
     info = gqsa_info(h)
     if x.dim() == 1:
@@ -255,9 +273,9 @@ def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None):
         y = torch.empty((batch, info["N"]), dtype=torch.float16, device=x.device)
     if tuple(y.shape) != (batch, info["N"]):
         raise ValueError("y must be [batch, N]")
-    _check(_lib().gqsa_gemv(h.ptr, _dev_ptr(x, "torch.float16", "x"),
-                            _dev_ptr(y, "torch.float16", "y"), batch, _stream_ptr(stream)),
-           "gqsa_gemv")
+    fn = _lib().gqsa_gemv_panels if panels else _lib().gqsa_gemv
+    _check(fn(h.ptr, _dev_ptr(x, "torch.float16", "x"), _dev_ptr(y, "torch.float16", "y"), batch,
+              _stream_ptr(stream)), "gqsa_gemv_panels" if panels else "gqsa_gemv")
     return y
 
 

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgqsa.so")
 
-SOURCES = ["gqsa_pack.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_baselines.hip"]
+SOURCES = ["gqsa_pack.cpp", "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_panel_kernel.hip", "gqsa_baselines.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wextra", "-Wno-unused-parameter"]

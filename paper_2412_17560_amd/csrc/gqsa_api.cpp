@@ -38,6 +38,22 @@ gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
     return GQSA_OK;
 }
 
+// The device image, and the panel image if there is one.
+gqsa_status_t upload(gqsa_matrix* m)
+{
+    if (gqsa_status_t st = gqsa::device_upload(m)) return st;
+    if (gqsa_status_t st = gqsa::panels_upload(m)) {
+        gqsa::device_release(m);
+        return st;
+    }
+    return GQSA_OK;
+}
+
+// Calls with this many activation rows or more go to the matrix-core kernel if the handle has a
+// panel image: its time hardly depends on the row count (16 rows' worth of products either way),
+// the wavefront kernel's grows with every row, and they cross between 8 and 12 rows on an MI355X.
+constexpr int kPanelMinBatch = 9;
+
 }  // namespace
 
 extern "C" {
@@ -130,11 +146,18 @@ gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_
     return gqsa::build_image(h, n_workgroups, waves_per_workgroup, span_tiles);
 }
 
+gqsa_status_t gqsa_build_panels(gqsa_handle_t h)
+{
+    if (!h) return GQSA_ERR_NULL;
+    if (h->d_image) return GQSA_ERR_UNSUPPORTED;
+    return gqsa::build_panels(h);
+}
+
 gqsa_status_t gqsa_upload(gqsa_handle_t h)
 {
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_OK;
-    return gqsa::device_upload(h);
+    return upload(h);
 }
 
 gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
@@ -145,9 +168,23 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
     if ((reinterpret_cast<uintptr_t>(x_dev) & 15u) != 0) return GQSA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(y_dev) & 1u) != 0) return GQSA_ERR_ALIGN;
     if (!h->d_image) {
-        if (gqsa_status_t st = gqsa::device_upload(h)) return st;
+        if (gqsa_status_t st = upload(h)) return st;
     }
+    if (h->d_panels && batch >= kPanelMinBatch) return gqsa::panels_gemm(h, x_dev, y_dev, batch, hip_stream);
     return gqsa::device_gemv(&h, 1, x_dev, &y_dev, batch, hip_stream);
+}
+
+gqsa_status_t gqsa_gemv_panels(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch, void* hip_stream)
+{
+    if (!h || !x_dev || !y_dev) return GQSA_ERR_NULL;
+    if (batch < 1 || batch > gqsa::kMaxBatch) return GQSA_ERR_UNSUPPORTED;
+    if (h->panel_image.empty()) return GQSA_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x_dev) & 15u) != 0) return GQSA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(y_dev) & 1u) != 0) return GQSA_ERR_ALIGN;
+    if (!h->d_image) {
+        if (gqsa_status_t st = upload(h)) return st;
+    }
+    return gqsa::panels_gemm(h, x_dev, y_dev, batch, hip_stream);
 }
 
 gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, const void* x_dev,
@@ -167,10 +204,17 @@ gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, cons
         for (int j = 0; j < i; ++j)
             if (handles[j] == handles[i]) return GQSA_ERR_SHAPE;   // a handle has one carry workspace
     }
+    bool panels = batch >= kPanelMinBatch;
     for (int i = 0; i < n_matrices; ++i) {
         if (!handles[i]->d_image) {
-            if (gqsa_status_t st = gqsa::device_upload(handles[i])) return st;
+            if (gqsa_status_t st = upload(handles[i])) return st;
         }
+        if (!handles[i]->d_panels) panels = false;
+    }
+    if (panels) {      // one launch per matrix: at these sizes the products, not the launches, take the time
+        for (int i = 0; i < n_matrices; ++i)
+            if (gqsa_status_t st = gqsa::panels_gemm(handles[i], x_dev, y_devs[i], batch, hip_stream)) return st;
+        return GQSA_OK;
     }
     return gqsa::device_gemv(handles, n_matrices, x_dev, y_devs, batch, hip_stream);
 }
@@ -194,6 +238,7 @@ gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)
     out->device_bytes = static_cast<int64_t>(h->map.total);
     out->algorithmic_bytes = h->nnzg() * (h->code_bytes() + 6) + (h->N + 1) * 4 + (h->K + h->N) * 2;
     out->on_device = h->d_image ? 1 : 0;
+    out->panel_bytes = static_cast<int64_t>(h->panel_image.size());
     return GQSA_OK;
 }
 
@@ -208,6 +253,15 @@ gqsa_status_t gqsa_export(gqsa_handle_t h, int32_t* rowIndex, int32_t* groups, u
         std::memcpy(scales_f16, h->scales.data(), h->scales.size() * 2);
     if (zeros_f16 && !h->zeros.empty())
         std::memcpy(zeros_f16, h->zeros.data(), h->zeros.size() * 2);
+    return GQSA_OK;
+}
+
+gqsa_status_t gqsa_export_panel_blob(gqsa_handle_t h, void* host_buf, size_t bytes)
+{
+    if (!h || !host_buf) return GQSA_ERR_NULL;
+    if (h->panel_image.empty()) return GQSA_ERR_UNSUPPORTED;
+    if (bytes < h->panel_image.size()) return GQSA_ERR_BUFSIZE;
+    std::memcpy(host_buf, h->panel_image.data(), h->panel_image.size());
     return GQSA_OK;
 }
 
@@ -302,6 +356,7 @@ void gqsa_free(gqsa_handle_t h)
 {
     if (!h) return;
     gqsa::device_release(h);
+    gqsa::panels_release(h);
     delete h;
 }
 

@@ -18,6 +18,9 @@ constexpr int kMaxBatch = 16;
 constexpr int kMaxMatricesPerLaunch = 4;
 constexpr int64_t kMaxGroupColumns = 4096;  // 16-element slots of K: 12-bit slot << 4 | head flag in 16 bits
 constexpr size_t kAlign = 256;
+constexpr int kPanelRows = 16;         // output rows per panel of the many-row image (one side of a 16x16x16 product)
+constexpr int kSliceColumns = 32;      // group-columns per block of that image
+constexpr int kPanelHeaderBytes = 144; // a block's header: 32 column words, data offset, group count, 2 spare
 
 // Blocks per tile for a format with `code_bytes` bytes of codes per group.
 constexpr int largest_tile(int code_bytes) { return code_bytes <= 16 ? 4 : (code_bytes <= 32 ? 2 : 1); }
@@ -61,8 +64,13 @@ struct gqsa_matrix {
     int needs_fixup = 0;
     gqsa::ImageMap map;
     std::vector<uint8_t> image;
+    // optional second image for calls with many activation rows (gqsa_panels.cpp)
+    std::vector<uint8_t> panel_image;
+    size_t panel_blocks_offset = 0;   // where the data region starts in it (after the headers)
+    int64_t n_panels = 0, n_slices = 0;
     // device side
     int device = -1;
+    void* d_panels = nullptr;
     void* d_image = nullptr;
     void* d_carry = nullptr;  // carry records, arrival counters and meeting points of the fix-up
 
@@ -80,6 +88,12 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
 int64_t place_rows(const gqsa_matrix& m, int64_t span_groups, std::vector<int64_t>* row_pos);
 void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles);
 gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles);
+
+// many-row image (gqsa_panels.cpp) and its kernel (gqsa_panel_kernel.hip)
+gqsa_status_t build_panels(gqsa_matrix* m);
+gqsa_status_t panels_upload(gqsa_matrix* m);
+void panels_release(gqsa_matrix* m);
+gqsa_status_t panels_gemm(const gqsa_matrix* m, const void* x, void* y, int batch, void* stream);
 
 // device side (gqsa_gemv.hip)
 gqsa_status_t device_upload(gqsa_matrix* m);

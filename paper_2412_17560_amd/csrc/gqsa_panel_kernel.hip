@@ -1,0 +1,230 @@
+// y[b, n] = sum_k W^[n, k] x[b, k] for 9..16 activation rows at once on the matrix cores, from
+// the panel image (gqsa_panels.cpp): a panel's groups of one group-column, 16 rows x 16 weights
+// with the pruned ones zero, times the 16 x 16 activations under them, is one 16x16x16 product.
+// The dequantisation of Eq. 3 stays exact: the matrix cores multiply the integer codes q (exact
+// in fp16) by x with fp32 accumulation, and a second product with a matrix of ones gives the sum
+// of the 16 activations; scale and zero are applied to the two fp32 results per group,
+//     sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j),
+// so no weight is ever rounded to fp16.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstdio>
+
+#include "gqsa_internal.hpp"
+
+namespace gqsa {
+namespace {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kPanelsPerWorkgroup = 4;   // panels a workgroup takes at most (each needs its own sums)
+constexpr int kPanelWaves = 16;      // wavefronts of a workgroup: each takes every 16th half-slice of the panel
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+}
+
+__device__ __forceinline__ uint16_t float_to_half_bits(float v)
+{
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));     // round to nearest even
+}
+
+// Four codes -> four fp16 integers, exactly: 0x6400 | q is the fp16 number 1024 + q (q < 1024).
+template <int BITS>
+__device__ __forceinline__ half4_t decode4(uint32_t code)
+{
+    uint32_t lo, hi;
+    if constexpr (BITS == 4) {     // two bytes (e0 | e2 << 4), (e1 | e3 << 4)
+        const uint32_t t = code | (code << 8);          // first byte in bits 0..7, second in bits 16..23
+        lo = t & 0x000F000Fu;                           // e0, e1
+        hi = (t >> 4) & 0x000F000Fu;                    // e2, e3
+    } else {                       // four bytes, one per element
+        lo = (code & 0xFFu) | ((code & 0xFF00u) << 8);
+        hi = ((code >> 16) & 0xFFu) | ((code >> 8) & 0xFF0000u);
+    }
+    const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
+    const half2_t a = __builtin_bit_cast(half2_t, lo | 0x64006400u) - bias;
+    const half2_t b = __builtin_bit_cast(half2_t, hi | 0x64006400u) - bias;
+    return half4_t{a.x, a.y, b.x, b.y};
+}
+
+// A workgroup takes up to four panels of 16 output rows (blockIdx.x, + gridDim.x, ...); wavefront
+// w takes the half-slices w, w + 16, ... (16 group-columns each) of every one of them, so the
+// activations under a half-slice are loaded once for all of the workgroup's panels.  A block's header is the
+// same for all lanes and is read with scalar loads; which group is a lane's (its row's, in the
+// column at hand) follows from the header with a masked population count.  Nothing is loaded
+// conditionally: a lane whose row has no group in a column reads a neighbouring group (the image
+// ends with spare bytes), and what it computes from it stays in its own column of the product,
+// which it then leaves out.  Likewise the activation rows beyond `batch` are copies of the last
+// one: they only reach result rows that are never stored.
+// Operands of v_mfma_f32_16x16x16_f16 in a wavefront: lane l holds A[l % 16][4 (l / 16) .. + 3],
+// B[4 (l / 16) .. + 3][l % 16] and receives D[4 (l / 16) .. + 3][l % 16].  Here A = the
+// activations (row = activation row, 16 elements of one group-column), B = the codes (column =
+// output row of the panel), so a lane ends up with the sums of output row l % 16 for the
+// activation rows 4 (l / 16) .. + 3 -- and the scale and zero it loaded with its codes are the
+// ones those sums need.
+template <int BITS>
+__global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
+    const uint16_t* __restrict__ x, const uint8_t* __restrict__ headers, const uint8_t* __restrict__ data,
+    uint16_t* __restrict__ y, int N, int K, int n_slices, int batch, int n_panels)
+{
+    constexpr int CB = 2 * BITS;                    // code bytes per group
+    __shared__ float part[kPanelWaves * 4 * kLanes];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 15;                        // activation row (A), output row of the panel (B, D)
+    const int j = lane >> 4;                        // which four of a group's 16 elements
+    const int kg = K >> 4;
+    const uint32_t below = (1u << r) - 1u;
+    const uint32_t row_bit = 1u << r;
+    const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 4 * j;
+    const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    const half4_t ones = {(_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f};
+
+    // the workgroup's panels: blockIdx.x, blockIdx.x + gridDim.x, ... (at most kPanelsPerWorkgroup)
+    float4_t acc[kPanelsPerWorkgroup];
+#pragma unroll
+    for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) acc[pp] = zero4;
+    constexpr int HC = kSliceColumns / 2;
+    const uint32_t code_lane = (BITS == 4 ? 2u : 4u) * j;
+    for (int unit = wl; unit < 2 * n_slices; unit += kPanelWaves) {      // a slice in two halves of 16 group-columns
+        const int s = unit >> 1;
+        const int half = unit & 1;
+        const int col0 = s * kSliceColumns + half * HC;
+        // the activations under these columns, once for all panels of the workgroup; the last
+        // slice may be short: its missing columns (no groups there) take the last column's
+        uint2 xa[HC];
+#pragma unroll
+        for (int c = 0; c < HC; ++c) {
+            const int col = col0 + c < kg ? col0 + c : kg - 1;
+            xa[c] = *reinterpret_cast<const uint2*>(xrow + 16 * col);
+        }
+        // the headers of all the workgroup's panels at once (scalar loads; a panel beyond the
+        // last one stands in as the last one and is not computed)
+        uint32_t hh[kPanelsPerWorkgroup][HC], where[kPanelsPerWorkgroup], count[kPanelsPerWorkgroup];
+#pragma unroll
+        for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
+            const int p = blockIdx.x + pp * gridDim.x;
+            const uint32_t* header = reinterpret_cast<const uint32_t*>(
+                headers + static_cast<size_t>((p < n_panels ? p : n_panels - 1) * n_slices + s) * kPanelHeaderBytes);
+#pragma unroll
+            for (int c = 0; c < HC; ++c) hh[pp][c] = header[half * HC + c];
+            where[pp] = header[32];
+            count[pp] = header[33];
+        }
+#pragma unroll
+        for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
+            const int p = blockIdx.x + pp * gridDim.x;
+            if (p < n_panels) {                         // (the same for the whole workgroup)
+                const uint8_t* codes = data + static_cast<size_t>(where[pp]) * 16;
+                const uint32_t params_offset = (count[pp] * CB + 15u) / 16u * 16u;
+                uint32_t code[HC], sz[HC];
+#pragma unroll
+                for (int c = 0; c < HC; ++c) {
+                    const uint32_t h = hh[pp][c];
+                    const uint32_t idx = (h >> 16) + __builtin_popcount(h & 0xFFFFu & below);
+                    if constexpr (BITS == 4) code[c] = *reinterpret_cast<const uint16_t*>(codes + (idx * CB + code_lane));
+                    else code[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * CB + code_lane));
+                    sz[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * 4u + params_offset));
+                }
+#pragma unroll
+                for (int c = 0; c < HC; ++c) {
+                    const half4_t a = __builtin_bit_cast(half4_t, xa[c]);
+                    const half4_t q = decode4<BITS>(code[c]);
+                    const float4_t d = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, zero4, 0, 0, 0);      // sum_j q_j x_j
+                    const float4_t e = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, zero4, 0, 0, 0);   // sum_j x_j
+                    if ((hh[pp][c] & row_bit) != 0) {
+                        const float sc = half_bits_to_float(sz[c] & 0xFFFFu);
+                        const float z = half_bits_to_float(sz[c] >> 16);
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            acc[pp][v] = __builtin_fmaf(sc, __builtin_fmaf(-z, e[v], d[v]), acc[pp][v]);
+                    }
+                }
+            }
+        }
+    }
+
+    // the wavefronts' sums meet in LDS and are added in wavefront order
+#pragma unroll
+    for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
+        const int p = blockIdx.x + pp * gridDim.x;
+        if (p >= n_panels) break;                       // (the same for the whole workgroup)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part[(wl * 4 + v) * kLanes + lane] = acc[pp][v];
+        __syncthreads();
+        if (tid < 4 * kLanes) {
+            const int v = tid >> 6;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kPanelWaves; ++w) sum += part[(w * 4 + v) * kLanes + lane];
+            const int b = 4 * j + v;                    // activation row
+            const int row = p * kPanelRows + r;         // output row
+            if (b < batch && row < N) y[static_cast<size_t>(b) * N + row] = float_to_half_bits(sum);
+        }
+        __syncthreads();                                // before the next panel's sums
+    }
+}
+
+}  // namespace
+
+#define GQSA_HIP(call)                                                                   \
+    do {                                                                                 \
+        const hipError_t e_ = (call);                                                    \
+        if (e_ != hipSuccess) {                                                          \
+            std::fprintf(stderr, "libgqsa: %s: %s\n", #call, hipGetErrorString(e_));    \
+            return GQSA_ERR_HIP;                                                         \
+        }                                                                                \
+    } while (0)
+
+gqsa_status_t panels_upload(gqsa_matrix* m)
+{
+    if (m->panel_image.empty() || m->d_panels) return GQSA_OK;
+    void* img = nullptr;
+    GQSA_HIP(hipMalloc(&img, m->panel_image.size()));
+    const hipError_t e = hipMemcpy(img, m->panel_image.data(), m->panel_image.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        std::fprintf(stderr, "libgqsa: upload failed: %s\n", hipGetErrorString(e));
+        (void)hipFree(img);
+        return GQSA_ERR_HIP;
+    }
+    m->d_panels = img;
+    return GQSA_OK;
+}
+
+void panels_release(gqsa_matrix* m)
+{
+    if (m->d_panels) (void)hipFree(m->d_panels);
+    m->d_panels = nullptr;
+}
+
+// Up to 16 activation rows in one launch.  x [batch, K], y [batch, N], fp16, on the device.
+gqsa_status_t panels_gemm(const gqsa_matrix* m, const void* x, void* y, int batch, void* stream)
+{
+    if (!m->d_panels || batch < 1 || batch > kPanelRows) return GQSA_ERR_UNSUPPORTED;
+    const uint8_t* img = static_cast<const uint8_t*>(m->d_panels);
+    const uint8_t* data = img + m->panel_blocks_offset;
+    // one workgroup per compute unit unless that gives a workgroup more than four panels
+    const int64_t wgs = std::min<int64_t>(m->n_panels, std::max<int64_t>(kMaxDefaultWorkgroups,
+                                                                         (m->n_panels + kPanelsPerWorkgroup - 1) / kPanelsPerWorkgroup));
+    const dim3 grid(static_cast<unsigned>(wgs)), block(kPanelWaves * kLanes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (m->bits == 4)
+        hipLaunchKernelGGL(gqsa_panel_kernel<4>, grid, block, 0, s, static_cast<const uint16_t*>(x), img,
+                           data, static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
+                           static_cast<int>(m->n_slices), batch, static_cast<int>(m->n_panels));
+    else
+        hipLaunchKernelGGL(gqsa_panel_kernel<8>, grid, block, 0, s, static_cast<const uint16_t*>(x), img,
+                           data, static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
+                           static_cast<int>(m->n_slices), batch, static_cast<int>(m->n_panels));
+    GQSA_HIP(hipGetLastError());
+    return GQSA_OK;
+}
+
+}  // namespace gqsa

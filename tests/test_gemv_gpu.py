@@ -26,17 +26,17 @@ def torch_cuda():
     return torch
 
 
-def run_gemv(torch, h, x_np):
+def run_gemv(torch, h, x_np, panels=False):
     x = torch.from_numpy(np.ascontiguousarray(x_np)).cuda()
     n = gq.gqsa_info(h)["N"]
     y = torch.full((x.shape[0], n), float("nan"), dtype=torch.float16, device="cuda")
-    gq.gqsa_gemv(h, x, y)
+    gq.gqsa_gemv(h, x, y, panels=panels)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
 
-def check(torch, h, c, x_np, tol=TOL):
-    y = run_gemv(torch, h, x_np)
+def check(torch, h, c, x_np, tol=TOL, panels=False):
+    y = run_gemv(torch, h, x_np, panels)
     ref = oracle.gemv(c, x_np, threads=8)
     assert np.isfinite(y).all()
     for b in range(x_np.shape[0]):
@@ -484,6 +484,87 @@ def test_vocabulary_sized_matrix(torch_cuda):
     assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == (4008, 4, 16)
     check(torch_cuda, h, c, gi.activations(1, K, seed=52))
     gq.gqsa_free(h)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("batch", [1, 2, 5, 8, 9, 13, 16])
+def test_panel_kernel_ragged(torch_cuda, bits, batch):
+    """1..16 activation rows on the matrix cores, from the panel image: 301 rows (the last panel
+    has 13), 61 group-columns (the second slice has 29), imbalanced rows, empty rows."""
+    N, K = 301, 976
+    W = gi.dense_weight(N, K, seed=90 + bits)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=90 + bits)
+    keep[[0, 5, 6, 300]] = 0
+    keep[17] = K // 16
+    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    gq.gqsa_build_panels(h)
+    check(torch_cuda, h, c, gi.activations(batch, K, seed=11 + batch), panels=True)
+
+
+def test_panel_kernel_unit_vectors_are_bit_exact(torch_cuda):
+    """x = e_k in 16 activation rows: y[b] is column k_b of W^, and (q - z) s is exact in fp32, so
+    every output is fp16((q - z) s) to the bit -- operand layout of the products, decode, scale
+    and zero with no tolerance."""
+    N, K = 100, 1024
+    W = gi.dense_weight(N, K, seed=95)
+    c = oracle.pack(W, 16, 4, sparsity=0.5)
+    h = gq.gqsa_pack(W, 16, 4, 0.5)
+    gq.gqsa_build_panels(h)
+    ks = [0, 1, 15, 16, 17, 255, 256, 511, 512, 513, 777, 1000, 1008, 1022, 1023, 300]
+    x = np.zeros((16, K), dtype=np.float16)
+    for b, k in enumerate(ks):
+        x[b, k] = 1.0
+    y = run_gemv(torch_cuda, h, x)        # 16 rows: gqsa_gemv itself takes the panel image
+    Wd = oracle.densify(c)
+    ref = Wd[:, ks].T.astype(np.float32).astype(np.float16)
+    assert np.array_equal(y.view(np.uint16), ref.view(np.uint16))
+
+
+def test_panel_kernel_only_from_nine_rows(torch_cuda):
+    """Below 9 activation rows a handle with a panel image runs the wavefront kernel in gqsa_gemv:
+    same bits as a handle without one.  From 9 on it is gqsa_gemv_panels, whose results differ in
+    rounding only."""
+    N, K = 512, 2048
+    W = gi.dense_weight(N, K, seed=96)
+    c = oracle.pack(W, 16, 4, sparsity=0.3)
+    h1 = gq.gqsa_pack(W, 16, 4, 0.3)
+    h2 = gq.gqsa_pack(W, 16, 4, 0.3)
+    gq.gqsa_build_panels(h2)
+    assert gq.gqsa_info(h2)["panel_bytes"] > 0
+    for batch in (1, 4, 8):
+        x = gi.activations(batch, K, seed=12)
+        assert np.array_equal(run_gemv(torch_cuda, h1, x).view(np.uint16), run_gemv(torch_cuda, h2, x).view(np.uint16))
+    x = gi.activations(9, K, seed=13)
+    y, _ = check(torch_cuda, h2, c, x)
+    assert np.array_equal(y.view(np.uint16), run_gemv(torch_cuda, h2, x, panels=True).view(np.uint16))
+    with pytest.raises(gq.GqsaError):
+        gq.gqsa_build_panels(h1)         # not after the upload
+    with pytest.raises(gq.GqsaError) as e:
+        run_gemv(torch_cuda, h1, x, panels=True)     # no such image
+    assert e.value.status == 3
+
+
+@pytest.mark.parametrize("bits,shape_idx", [(4, 0), (8, 1)])
+def test_panel_kernel_full_size(torch_cuda, bits, shape_idx):
+    """4096x4096 (W4) and 14336x4096 (W8) at S = 50 %, 16 activation rows; every output checked.
+    Also several matrices in one call."""
+    name, N, K = gi.SMALL_BATCH_SHAPES[shape_idx]
+    W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(5, shape_idx))
+    c = oracle.pack(W, 16, bits, sparsity=0.5)
+    h = gq.gqsa_pack(W, 16, bits, 0.5)
+    gq.gqsa_build_panels(h)
+    x = gi.activations(16, K, seed=14)
+    y, ref = check(torch_cuda, h, c, x)
+    if shape_idx == 0:
+        h2 = gq.gqsa_pack(W, 16, bits, 0.5)
+        gq.gqsa_build_panels(h2)
+        xt = torch_cuda.from_numpy(x).cuda()
+        ys = [torch_cuda.full((16, N), float("nan"), dtype=torch_cuda.float16, device="cuda") for _ in range(2)]
+        gq.gqsa_gemv_multi([h, h2], xt, ys)
+        torch_cuda.cuda.synchronize()
+        for yy in ys:
+            assert np.array_equal(yy.cpu().numpy().view(np.uint16), y.view(np.uint16))
 
 
 def test_llama7b_qkv_and_gate_up_fused_full_size(torch_cuda):

@@ -104,6 +104,43 @@ def test_aligned_stream_keeps_rows_inside_spans():
 
 
 @pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("shape", [(301, 2048), (16, 512), (33, 16), (1, 4096), (100, 1040)])
+def test_panel_image(bits, shape):
+    """The second image (groups of 16 rows ordered by group-column) against its written layout."""
+    N, K = shape
+    W = gi.dense_weight(N, K, seed=80 + N)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=80 + N)
+    if N > 8:
+        keep[[0, 5, N - 1]] = 0
+        keep[3] = K // 16
+    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+    assert gq.gqsa_info(h)["panel_bytes"] == 0
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_export_panel_blob(h)
+    assert e.value.status == 3
+    gq.gqsa_build_panels(h)
+    ref = oracle.panel_blob(c)
+    assert gq.gqsa_info(h)["panel_bytes"] == len(ref)
+    assert gq.gqsa_export_panel_blob(h) == ref
+    assert_same_blob(h, c)                                  # the first image is untouched
+    # every stored group appears exactly once: the blocks' counts add up
+    P, S = -(-N // 16), -(-(K // 16) // 32)
+    hdr = np.frombuffer(ref, dtype="<u4", count=P * S * 36).reshape(P * S, 36)
+    assert int(hdr[:, 33].sum()) == c.nnzg
+    last = hdr[:, 31].astype(np.int64)
+    assert np.array_equal((last >> 16) + np.array([bin(v & 0xFFFF).count("1") for v in last]), hdr[:, 33])
+
+
+def test_panel_image_other_group_sizes_are_refused():
+    W = gi.dense_weight(8, 256, seed=3)
+    h = gq.gqsa_pack(W, 32, 4, 0.5)
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_build_panels(h)
+    assert e.value.status == 3
+
+
+@pytest.mark.parametrize("bits", [4, 8])
 def test_outliers_and_imbalanced_rows(bits):
     N, K = 333, 1024
     W = gi.dense_weight(N, K, seed=77)
