@@ -289,8 +289,9 @@ def main():
             extra_handles.clear()
         out["fused_launches"] = fused
 
-        def copies_of(W, bits, sparsity, G=16, min_bytes=1 << 30):
-            """Distinct device copies of one packed matrix, enough of them to defeat the caches."""
+        def copies_of(W, bits, sparsity, G=16, min_bytes=1 << 30, panels=False):
+            """Distinct device copies of one packed matrix, enough of them to defeat the caches
+            (panels: each with the second image for many activation rows)."""
             h0 = gq.gqsa_pack(W, G, bits, sparsity)
             e = gq.gqsa_export(h0)
             n = max(2, min_bytes // gq.gqsa_info(h0)["device_bytes"] + 1)
@@ -299,6 +300,8 @@ def main():
                 hs.append(gq.gqsa_import(e["rowIndex"], e["groups"], e["values"], e["scales"], e["zeros"],
                                          W.shape[0], W.shape[1], G, bits))
             for h in hs:
+                if panels:
+                    gq.gqsa_build_panels(h)
                 gq.gqsa_upload(h)
             return hs
 
@@ -376,6 +379,18 @@ def main():
                                  "us_per_row": round(us / B, 3)})
                 for h in hs:
                     gq.gqsa_free(h)
+                # the same with the second image (gqsa_build_panels): 16 output rows x 16 activation
+                # rows x one group-column per matrix-core product; gqsa_gemv takes it from 9 rows on
+                hs = copies_of(W, bits, 0.5, panels=True)
+                for B in (8, 16):
+                    xb = torch.from_numpy(gi.activations(B, K, seed=gi.config_seed(5, 1))).to(dev)
+                    yb = torch.empty((B, N), dtype=torch.float16, device=dev)
+                    us = time_calls(lambda k, hs=hs, xb=xb, yb=yb: gq.gqsa_gemv(hs[k % len(hs)], xb, yb, panels=True), n=60)
+                    for row in rows:
+                        if row["bits"] == bits and row["batch"] == B:
+                            row["us_cold_panels"] = round(us, 3)
+                for h in hs:
+                    gq.gqsa_free(h)
             del W
             out["small_batch_14336x4096"] = rows
 
@@ -397,6 +412,19 @@ def main():
             yb = torch.empty((B, 4096), dtype=torch.float16, device=dev)
             us = time_calls(lambda k, xb=xb, yb=yb: gq.gqsa_gemv(hs[k % len(hs)], xb, yb), n=96)
             small_batch.append({"batch": B, "us_cold": round(us, 3), "us_per_row": round(us / B, 3)})
+        # the same from the second image (matrix cores); gqsa_gemv takes it from 9 rows on
+        Wb = gi.dense_weight_chunked(4096, 4096, seed=gi.config_seed(5, 0), workers=workers)
+        hp = copies_of(Wb, 4, 0.5, panels=True)
+        del Wb
+        for row in small_batch:
+            if row["batch"] in (8, 16):
+                B = row["batch"]
+                xb = torch.from_numpy(gi.activations(B, 4096, seed=gi.config_seed(5, 0))).to(dev)
+                yb = torch.empty((B, 4096), dtype=torch.float16, device=dev)
+                us = time_calls(lambda k, xb=xb, yb=yb: gq.gqsa_gemv(hp[k % len(hp)], xb, yb, panels=True), n=96)
+                row["us_cold_panels"] = round(us, 3)
+        for h in hp:
+            gq.gqsa_free(h)
         out["small_batch_4096x4096"] = small_batch
 
         # achievable read ceiling: plain streaming kernel over 2 GiB

@@ -39,13 +39,13 @@ template <int BITS>
 __device__ __forceinline__ half4_t decode4(uint32_t code)
 {
     uint32_t lo, hi;
-    if constexpr (BITS == 4) {     // two bytes (e0 | e2 << 4), (e1 | e3 << 4)
-        const uint32_t t = code | (code << 8);          // first byte in bits 0..7, second in bits 16..23
+    if constexpr (BITS == 4) {     // two bytes (e0 | e2 << 4), (e1 | e3 << 4), whatever lies above them
+        const uint32_t t = __builtin_amdgcn_perm(0u, code, 0x0c010c00u);      // first byte to bits 0..7, second to 16..23
         lo = t & 0x000F000Fu;                           // e0, e1
         hi = (t >> 4) & 0x000F000Fu;                    // e2, e3
     } else {                       // four bytes, one per element
-        lo = (code & 0xFFu) | ((code & 0xFF00u) << 8);
-        hi = ((code >> 16) & 0xFFu) | ((code >> 8) & 0xFF0000u);
+        lo = __builtin_amdgcn_perm(0u, code, 0x0c010c00u);
+        hi = __builtin_amdgcn_perm(0u, code, 0x0c030c02u);
     }
     const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t a = __builtin_bit_cast(half2_t, lo | 0x64006400u) - bias;
@@ -82,7 +82,6 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const int j = lane >> 4;                        // which four of a group's 16 elements
     const int kg = K >> 4;
     const uint32_t below = (1u << r) - 1u;
-    const uint32_t row_bit = 1u << r;
     const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 4 * j;
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     const half4_t ones = {(_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f};
@@ -133,18 +132,29 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                     else code[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * CB + code_lane));
                     sz[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * 4u + params_offset));
                 }
+                // two columns at a time: the products of the second are under way while the
+                // first one's sums are scaled.  Which lanes have a group in a column is a lane
+                // mask made from the header word with scalar arithmetic (bit r -> lanes r, r + 16, ...)
 #pragma unroll
-                for (int c = 0; c < HC; ++c) {
-                    const half4_t a = __builtin_bit_cast(half4_t, xa[c]);
-                    const half4_t q = decode4<BITS>(code[c]);
-                    const float4_t d = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, zero4, 0, 0, 0);      // sum_j q_j x_j
-                    const float4_t e = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, zero4, 0, 0, 0);   // sum_j x_j
-                    if ((hh[pp][c] & row_bit) != 0) {
-                        const float sc = half_bits_to_float(sz[c] & 0xFFFFu);
-                        const float z = half_bits_to_float(sz[c] >> 16);
+                for (int c = 0; c < HC; c += 2) {
+                    float4_t d[2], e[2];
 #pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            acc[pp][v] = __builtin_fmaf(sc, __builtin_fmaf(-z, e[v], d[v]), acc[pp][v]);
+                    for (int i = 0; i < 2; ++i) {
+                        const half4_t a = __builtin_bit_cast(half4_t, xa[c + i]);
+                        const half4_t q = decode4<BITS>(code[c + i]);
+                        d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, zero4, 0, 0, 0);      // sum_j q_j x_j
+                        e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, zero4, 0, 0, 0);   // sum_j x_j
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
+                        if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
+                            const float sc = half_bits_to_float(sz[c + i] & 0xFFFFu);
+                            const float z = half_bits_to_float(sz[c + i] >> 16);
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                acc[pp][v] = __builtin_fmaf(sc, __builtin_fmaf(-z, e[i][v], d[i][v]), acc[pp][v]);
+                        }
                     }
                 }
             }
