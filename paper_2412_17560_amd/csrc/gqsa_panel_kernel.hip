@@ -1,4 +1,4 @@
-// y[b, n] = sum_k W^[n, k] x[b, k] for 9..16 activation rows at once on the matrix cores, from
+// y[b, n] = sum_k W^[n, k] x[b, k] for up to 16 activation rows at once on the matrix cores, from
 // the panel image (gqsa_panels.cpp): a panel's groups of one group-column, 16 rows x 16 weights
 // with the pruned ones zero, times the 16 x 16 activations under them, is one 16x16x16 product.
 // The dequantisation of Eq. 3 stays exact: the matrix cores multiply the integer codes q (exact
@@ -55,9 +55,9 @@ __device__ __forceinline__ half4_t decode4(uint32_t code)
 
 // A workgroup takes up to four panels of 16 output rows (blockIdx.x, + gridDim.x, ...); wavefront
 // w takes the half-slices w, w + 16, ... (16 group-columns each) of every one of them, so the
-// activations under a half-slice are loaded once for all of the workgroup's panels.  A block's header is the
-// same for all lanes and is read with scalar loads; which group is a lane's (its row's, in the
-// column at hand) follows from the header with a masked population count.  Nothing is loaded
+// activations under a half-slice are loaded once for all of the workgroup's panels.  A block's
+// header is the same for all lanes and is read with scalar loads; which group is a lane's (its
+// row's, in the column at hand) follows from the header with a masked population count.  Nothing is loaded
 // conditionally: a lane whose row has no group in a column reads a neighbouring group (the image
 // ends with spare bytes), and what it computes from it stays in its own column of the product,
 // which it then leaves out.  Likewise the activation rows beyond `batch` are copies of the last
