@@ -35,21 +35,22 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
 }
 
 // Four codes -> four fp16 integers, exactly: 0x6400 | q is the fp16 number 1024 + q (q < 1024).
+// `splice` = 0x64006400 in a register (an AND-OR takes one literal, and the nibble mask is it).
 template <int BITS>
-__device__ __forceinline__ half4_t decode4(uint32_t code)
+__device__ __forceinline__ half4_t decode4(uint32_t code, uint32_t splice)
 {
     uint32_t lo, hi;
     if constexpr (BITS == 4) {     // two bytes (e0 | e2 << 4), (e1 | e3 << 4), whatever lies above them
         const uint32_t t = __builtin_amdgcn_perm(0u, code, 0x0c010c00u);      // first byte to bits 0..7, second to 16..23
-        lo = t & 0x000F000Fu;                           // e0, e1
-        hi = (t >> 4) & 0x000F000Fu;                    // e2, e3
+        lo = (t & 0x000F000Fu) | splice;                // e0, e1
+        hi = ((t >> 4) & 0x000F000Fu) | splice;         // e2, e3
     } else {                       // four bytes, one per element
-        lo = __builtin_amdgcn_perm(0u, code, 0x0c010c00u);
-        hi = __builtin_amdgcn_perm(0u, code, 0x0c030c02u);
+        lo = __builtin_amdgcn_perm(0u, code, 0x0c010c00u) | splice;
+        hi = __builtin_amdgcn_perm(0u, code, 0x0c030c02u) | splice;
     }
     const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
-    const half2_t a = __builtin_bit_cast(half2_t, lo | 0x64006400u) - bias;
-    const half2_t b = __builtin_bit_cast(half2_t, hi | 0x64006400u) - bias;
+    const half2_t a = __builtin_bit_cast(half2_t, lo) - bias;
+    const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
     return half4_t{a.x, a.y, b.x, b.y};
 }
 
@@ -83,13 +84,17 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const int kg = K >> 4;
     const uint32_t below = (1u << r) - 1u;
     const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 4 * j;
+    uint32_t splice;
+    asm volatile("s_mov_b32 %0, 0x64006400" : "=s"(splice));     // (kept out of the compiler's sight as a constant)
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     const half4_t ones = {(_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f};
 
     // the workgroup's panels: blockIdx.x, blockIdx.x + gridDim.x, ... (at most kPanelsPerWorkgroup)
-    float4_t acc[kPanelsPerWorkgroup];
+    float acc[kPanelsPerWorkgroup][4];
 #pragma unroll
-    for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) acc[pp] = zero4;
+    for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[pp][v] = 0.0f;
     constexpr int HC = kSliceColumns / 2;
     const uint32_t code_lane = (BITS == 4 ? 2u : 4u) * j;
     for (int unit = wl; unit < 2 * n_slices; unit += kPanelWaves) {      // a slice in two halves of 16 group-columns
@@ -141,7 +146,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
 #pragma unroll
                     for (int i = 0; i < 2; ++i) {
                         const half4_t a = __builtin_bit_cast(half4_t, xa[c + i]);
-                        const half4_t q = decode4<BITS>(code[c + i]);
+                        const half4_t q = decode4<BITS>(code[c + i], splice);
                         d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, zero4, 0, 0, 0);      // sum_j q_j x_j
                         e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, zero4, 0, 0, 0);   // sum_j x_j
                     }
