@@ -22,6 +22,7 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kPanelsPerWorkgroup = 4;   // panels a workgroup takes at most (each needs its own sums)
+constexpr int kInFlight = 4;          // columns whose products are under way together
 constexpr int kPanelWaves = 16;      // wavefronts of a workgroup: each takes every 16th half-slice of the panel
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h)
@@ -137,21 +138,21 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                     else code[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * CB + code_lane));
                     sz[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * 4u + params_offset));
                 }
-                // two columns at a time: the products of the second are under way while the
+                // four columns at a time: the products of the later ones are under way while the
                 // first one's sums are scaled.  Which lanes have a group in a column is a lane
                 // mask made from the header word with scalar arithmetic (bit r -> lanes r, r + 16, ...)
 #pragma unroll
-                for (int c = 0; c < HC; c += 2) {
-                    float4_t d[2], e[2];
+                for (int c = 0; c < HC; c += kInFlight) {
+                    float4_t d[kInFlight], e[kInFlight];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
+                    for (int i = 0; i < kInFlight; ++i) {
                         const half4_t a = __builtin_bit_cast(half4_t, xa[c + i]);
                         const half4_t q = decode4<BITS>(code[c + i], splice);
                         d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, zero4, 0, 0, 0);      // sum_j q_j x_j
                         e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, zero4, 0, 0, 0);   // sum_j x_j
                     }
 #pragma unroll
-                    for (int i = 0; i < 2; ++i) {
+                    for (int i = 0; i < kInFlight; ++i) {
                         const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
                         if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
                             const float sc = half_bits_to_float(sz[c + i] & 0xFFFFu);
