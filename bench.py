@@ -334,7 +334,7 @@ def main():
             out["llama3_8b_sweep"] = time_variants(list(enumerate(gi.LLAMA3_8B_SHAPES)),
                                                    [(4, sp) for sp in gi.SPARSITY_SWEEP], 3)
             out["group_size_sweep"] = time_variants(shapes7[:1] + shapes7[1:2],
-                                                    [(4, sp, G) for G in (16, 32, 64, 128) for sp in (0.0, 0.5)], 2)
+                                                    [(4, sp, G) for G in (8, 16, 32, 64, 128) for sp in (0.0, 0.5)], 2)
             # a matrix large enough that launch and first-byte latency no longer count: the output
             # projection of a LLaMA-3-8B-like model (vocabulary 128 256), 231 MB at W4S50
             out["vocabulary_projection"] = time_variants([(7, ("lm_head", 128256, 4096))], [(4, 0.5)], 3)

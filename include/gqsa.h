@@ -38,7 +38,7 @@ typedef enum {
     GQSA_OK = 0,
     GQSA_ERR_NULL = 1,         /* a required pointer is NULL */
     GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K > 65536, inconsistent arrays */
-    GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 16/32/64/128 (8-bit: up to 64), batch outside 1..16 */
+    GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 8/16/32/64/128 (8-bit: up to 64), batch outside 1..16 */
     GQSA_ERR_RANGE = 4,        /* sparsity outside [0,1], keep count outside [0,K/G], non-finite W */
     GQSA_ERR_ALLOC = 5,        /* host allocation failed */
     GQSA_ERR_HIP = 6,          /* a HIP runtime call failed (no device, launch error, ...) */
@@ -77,8 +77,9 @@ typedef struct {
  *   out      [host] receives the handle
  * Scale is stored as fp16 (floored at 2^-14); zero-point = round-half-even(-min/scale)
  * clamped to +-2048 and stored as fp16; codes = clamp(round(w/scale)+zero, 0, 2^bits-1).
- * Group sizes (the axis of the paper's group-size ablation, Sec. 4.5): G = 16, 32, 64 or 128 with
- * 4-bit codes, 16, 32 or 64 with 8-bit codes (at most 64 code bytes per group); K <= 65536.
+ * Group sizes (the axis of the paper's group-size ablation, Sec. 4.5): G = 8, 16, 32, 64 or 128
+ * with 4-bit codes, 8, 16, 32 or 64 with 8-bit codes (at most 64 code bytes per group); K a
+ * multiple of 16 and of G, K <= 65536 (G = 8: K <= 32768).
  */
 gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bits,
                         double sparsity, gqsa_handle_t* out);

@@ -30,10 +30,11 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     lane p div U.
  4. Block.  Each block is (G*bits/8 + 6)*64 bytes: the code planes, then
     64 x uint32 (fp16 scale bits | fp16 zero bits << 16), then 64 x uint16
-    index words.  G = 16*M with M in {1, 2, 4, 8}.  The index word is
+    index words.  G = 16*M with M in {1, 2, 4, 8}, or G = 8.  The index word is
     (group-column * M) << 4 -- sixteen times the number of the 16-element slot
     of K at which the group starts (slots are below 4096) -- plus 1 if the
-    group is the first stored group of its row.
+    group is the first stored group of its row; for G = 8 it is group-column
+    << 4 (the number of the 8-element half-slot, below 4096) plus that flag.
     Codes.  A lane's code string has G*bits/8 bytes.  4-bit codes: it is a
     sequence of little-endian uint32, word h holding elements 8h..8h+7 of the
     group, element 8h+2m in bits 4m..4m+3 and element 8h+2m+1 in bits
@@ -197,13 +198,13 @@ def stream_placement(nblocks: int, n_waves: int, U: int):
 
 def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int = 0) -> bytes:
     """Exact bytes the library must hold on the device for canonical arrays `c`."""
-    if c.G not in (16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
-        raise ValueError("device layout is specified for G in {16,32,64,128}, bits in {4,8}, at most 64 code bytes")
+    if c.G not in (8, 16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
+        raise ValueError("device layout is specified for G in {8,16,32,64,128}, bits in {4,8}, at most 64 code bytes")
     nnzg = c.nnzg
     code_bytes = c.G * c.bits // 8
     U = tile_blocks(code_bytes)
     blk_bytes = (code_bytes + 6) * LANES
-    chunks = c.G // 16
+    slots_per_group = max(1, c.G // 16)
 
     ri = np.asarray(c.rowIndex, dtype=np.int64)
     counts = ri[1:] - ri[:-1]
@@ -236,8 +237,8 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
             elems = np.empty((nnzg, c.G), dtype=np.uint32)
             elems[:, 0::2] = vals & 0xF
             elems[:, 1::2] = vals >> 4
-            words = np.zeros((nnzg, 2 * chunks), dtype=np.uint32)
-            for h in range(2 * chunks):
+            words = np.zeros((nnzg, code_bytes // 4), dtype=np.uint32)
+            for h in range(code_bytes // 4):
                 for m in range(4):
                     words[:, h] |= elems[:, 8 * h + 2 * m] << np.uint32(4 * m)
                     words[:, h] |= elems[:, 8 * h + 2 * m + 1] << np.uint32(16 + 4 * m)
@@ -258,9 +259,9 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
         is_head = np.zeros(nnzg, dtype=np.uint16)
         is_head[ri[:-1][counts > 0]] = 1
         gcol = np.asarray(c.groups, dtype=np.int64)
-        if gcol.size and gcol.max() * chunks + chunks - 1 >= 4096:
+        if gcol.size and gcol.max() * slots_per_group + slots_per_group - 1 >= 4096:
             raise ValueError("slot number does not fit 12 bits")
-        idx = (((gcol * chunks) << 4).astype(np.uint16) | is_head).astype("<u2")
+        idx = (((gcol * slots_per_group) << 4).astype(np.uint16) | is_head).astype("<u2")
         idx_off = sz_off + LANES * 4
         idx_view = blocks[:, idx_off:idx_off + LANES * 2].reshape(nblocks, LANES, 2)
         idx_view[block, lane, :] = idx.view(np.uint8).reshape(nnzg, 2)

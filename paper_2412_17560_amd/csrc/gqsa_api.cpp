@@ -1,5 +1,6 @@
 // extern "C" surface of libgqsa: argument checking, handle life-cycle, export/import.
 // The arithmetic lives in gqsa_pack.cpp (host) and gqsa_gemv.hip (device).
+#include <algorithm>
 #include <climits>
 #include <cmath>
 #include <cstdio>
@@ -15,10 +16,10 @@ gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
 {
     if (N <= 0 || K <= 0 || G <= 0) return GQSA_ERR_SHAPE;
     if (bits != 4 && bits != 8) return GQSA_ERR_UNSUPPORTED;
-    if (G != 16 && G != 32 && G != 64 && G != 128) return GQSA_ERR_UNSUPPORTED;
+    if (G != 8 && G != 16 && G != 32 && G != 64 && G != 128) return GQSA_ERR_UNSUPPORTED;
     if (G * bits / 8 > 64) return GQSA_ERR_UNSUPPORTED;       // at most 64 code bytes per group
-    if (K % G != 0) return GQSA_ERR_SHAPE;
-    if (K / 16 > gqsa::kMaxGroupColumns) return GQSA_ERR_SHAPE;
+    if (K % G != 0 || K % 16 != 0) return GQSA_ERR_SHAPE;     // (x is staged in runs of 16, also for G = 8)
+    if (K / std::min(G, 16) > gqsa::kMaxGroupColumns) return GQSA_ERR_SHAPE;
     if (N > (int64_t{1} << 30)) return GQSA_ERR_SHAPE;
     return GQSA_OK;
 }

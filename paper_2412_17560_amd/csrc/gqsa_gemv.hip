@@ -218,15 +218,17 @@ __device__ __forceinline__ void store_row(const MatArgs& m, int b, int rank, flo
 }
 
 // Storage format of a group as the kernel is compiled for it: code width and group size
-// G = 16 * M.  A block holds 64 groups, one per lane: the code bytes in planes of at most
-// 16 bytes per lane (each plane one coalesced load), then scale | zero << 16, then the index word.
+// G = 16 * M, or G = 8 (M = 0: half a chunk).  A block holds 64 groups, one per lane: the code
+// bytes in planes of at most 16 bytes per lane (each plane one coalesced load), then
+// scale | zero << 16, then the index word.
 template <int BITS_, int M_>
 struct Fmt {
     static constexpr int BITS = BITS_;
-    static constexpr int M = M_;                         // 16-element chunks per group
-    static constexpr int CB = 16 * M_ * BITS_ / 8;       // code bytes per group
+    static constexpr int M = M_;                         // 16-element chunks per group (0: G = 8)
+    static constexpr bool HALF = M_ == 0;
+    static constexpr int CB = (HALF ? 8 : 16 * M_) * BITS_ / 8;   // code bytes per group
     static constexpr int CW = CB / 4;                    // code words per group
-    static constexpr int CWC = CW / M_;                  // code words per chunk (2 or 4)
+    static constexpr int CWC = HALF ? CW : CW / (M_ ? M_ : 1);    // code words per chunk (2 or 4; half chunk: 1 or 2)
     static constexpr int PB = CB < 16 ? CB : 16;         // bytes per lane in one code plane
     static constexpr int PLANES = CB / PB;
     static constexpr int UMAX = largest_tile(CB);        // blocks of a tile
@@ -278,7 +280,9 @@ __device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int lane
     for (int u = 0; u < F::UMAX; ++u) {
 #pragma unroll
         for (int pl = 0; pl < F::PLANES; ++pl) {
-            if constexpr (F::PB == 8) {
+            if constexpr (F::PB == 4) {
+                t.code[u][0] = load_at<uint32_t>(p, ulane * 4u + u * F::BB);
+            } else if constexpr (F::PB == 8) {
                 const uint2 c = load_at<uint2>(p, ulane * 8u + u * F::BB);
                 t.code[u][0] = c.x; t.code[u][1] = c.y;
             } else {
@@ -309,7 +313,9 @@ __device__ __forceinline__ void decode_chunk(const Tile<F>& t, int u, int i, Cod
 // x in LDS, per activation row: elements 0..7 of every group-column in 16-byte slots, elements
 // 8..15 in a second array of 16-byte slots 16*KGP bytes further on, and the fp32 sum of the 16
 // as a dense array of floats at 32*KGP (4 bytes per column: a wavefront's 64 reads of it spread
-// over all banks instead of a quarter of them).  Row b starts at b * 48 * KGP.
+// over all banks instead of a quarter of them).  Row b starts at b * 48 * KGP.  (G = 8: the same
+// two arrays -- a group's 8 activations are one slot of the first or of the second -- and a sum
+// per half-slot, 8 bytes per column.)
 //
 // EAGER: the tile's loads may still be in flight.  All gathers are issued first (they need only
 // the index words, the first of the tile's loads to arrive), then the groups are decoded block
@@ -405,6 +411,30 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
             const float z = half_to_float(t.sz[u] >> 16);
             const uint32_t slot = t.ix[u] & 0xFFF0u;
             float dotz[NB];
+            if constexpr (F::HALF) {
+                // G = 8: the index word counts 8-element half-slots; an even one lies in the array
+                // of the slots' first halves, an odd one in the array of their second halves, and
+                // the sums are kept per half-slot
+                Codes c;
+                if constexpr (F::BITS == 4) {
+                    decode_w4(t.code[u][0], &c.q[0]);
+                } else {
+                    decode_w8(t.code[u][0], &c.q[0]);
+                    decode_w8(t.code[u][1], &c.q[2]);
+                }
+                const uint32_t xoff = ((slot >> 5) << 4) + ((slot >> 4) & 1u) * (16 * KGP);
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const uint4 xl = lds_read16(x0 + xoff + b * (48 * KGP));
+                    const float xs = lds_read_float(x0 + b * (48 * KGP) + 32 * KGP + (slot >> 2));
+                    float d = 0.0f;
+                    d = __builtin_amdgcn_fdot2(c.q[0], as_half2(xl.x), d, false);
+                    d = __builtin_amdgcn_fdot2(c.q[1], as_half2(xl.y), d, false);
+                    d = __builtin_amdgcn_fdot2(c.q[2], as_half2(xl.z), d, false);
+                    d = __builtin_amdgcn_fdot2(c.q[3], as_half2(xl.w), d, false);
+                    dotz[b] = __builtin_fmaf(-z, xs, d);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < F::M; ++i) {                // the group's 16-element chunks
                 Codes c;
@@ -702,10 +732,20 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
-        float s = 0.0f;      // sum of the slot's 16 activations, fp32: a pair per instruction
+        if constexpr (F::HALF) {     // G = 8: a sum per half-slot
+            float s0 = 0.0f, s1 = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s = __builtin_amdgcn_fdot2(as_half2(w[i]), ones, s, false);
-        *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg) * 4) = s;
+            for (int i = 0; i < 4; ++i) {
+                s0 = __builtin_amdgcn_fdot2(as_half2(w[i]), ones, s0, false);
+                s1 = __builtin_amdgcn_fdot2(as_half2(w[4 + i]), ones, s1, false);
+            }
+            *reinterpret_cast<float2*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg) * 8) = float2{s0, s1};
+        } else {
+            float s = 0.0f;      // sum of the slot's 16 activations, fp32: a pair per instruction
+#pragma unroll
+            for (int i = 0; i < 8; ++i) s = __builtin_amdgcn_fdot2(as_half2(w[i]), ones, s, false);
+            *reinterpret_cast<float*>(xlds + b * (48 * KGP) + 32 * KGP + (c - b * kg) * 4) = s;
+        }
     };
     // x into LDS (the loads of the tiles are already out), then the workgroup meets
     auto stage_x_and_meet = [&]() {
@@ -866,6 +906,7 @@ Variant pick(const gqsa_matrix* m, int nb, int* kgp)
     *kgp = 0;
     if (m->bits == 4) {
         switch (m->G) {
+            case 8: return pick_kernel<Fmt<4, 0>>(slots, nb, kgp);
             case 16: return pick_kernel<Fmt<4, 1>>(slots, nb, kgp);
             case 32: return pick_kernel<Fmt<4, 2>>(slots, nb, kgp);
             case 64: return pick_kernel<Fmt<4, 4>>(slots, nb, kgp);
@@ -873,6 +914,7 @@ Variant pick(const gqsa_matrix* m, int nb, int* kgp)
         }
     } else if (m->bits == 8) {
         switch (m->G) {
+            case 8: return pick_kernel<Fmt<8, 0>>(slots, nb, kgp);
             case 16: return pick_kernel<Fmt<8, 1>>(slots, nb, kgp);
             case 32: return pick_kernel<Fmt<8, 2>>(slots, nb, kgp);
             case 64: return pick_kernel<Fmt<8, 4>>(slots, nb, kgp);

@@ -304,7 +304,8 @@ void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_w
 // G = 16 M elements has G*bits/8 code bytes; plane k holds bytes 16k..16k+15 of every lane's
 // code string (a single plane of 8 bytes per lane for 4-bit, G = 16).  The index word is the
 // byte offset in LDS of the group's first 16 activations (slot = group-column * M) with the
-// row-head flag in bit 0.  4-bit code words are nibble-permuted so that one AND per pair of
+// row-head flag in bit 0; for G = 8 (half a slot per group; 4 or 8 code bytes) it is 16 times the
+// group-column itself, with that flag.  4-bit code words are nibble-permuted so that one AND per pair of
 // elements yields a packed fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m
 // at bits 4m and element 8h+2m+1 at bits 16+4m.
 gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles)
@@ -359,7 +360,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
 
     // A lane's code string: 4-bit codes as nibble-permuted words (word h = elements 8h..8h+7),
     // 8-bit codes as they are.  In the block it is cut into planes of at most 16 bytes per lane.
-    const int chunks = m->G / 16;                    // 16-element chunks per group
+    const int slots_per_group = m->G >= 16 ? m->G / 16 : 1;    // activation slots a group spans (16 elements each; 8 for G = 8)
     const int plane_bytes = std::min(cb, 16);
     std::vector<uint8_t> code(static_cast<size_t>(cb));
     auto put_group = [&](int64_t g, int64_t pos) {
@@ -369,7 +370,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         uint8_t* base = img.data() + static_cast<size_t>(block) * bb;
         const uint8_t* v = &m->values[static_cast<size_t>(g) * cb];
         if (m->bits == 4) {
-            for (int h = 0; h < 2 * chunks; ++h) {
+            for (int h = 0; h < cb / 4; ++h) {
                 uint32_t word = 0;
                 for (int e = 0; e < 8; ++e) {
                     const int j = 8 * h + e;
@@ -388,7 +389,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
                             (static_cast<uint32_t>(m->zeros[g]) << 16);
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + lane * 4, &sz, 4);
         // byte offset in LDS of the group's first 16 activations, row-head flag in bit 0
-        const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * chunks) << 4) | (head[static_cast<size_t>(pos)] ? 1 : 0));
+        const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * slots_per_group) << 4) | (head[static_cast<size_t>(pos)] ? 1 : 0));
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
     for (int64_t n = 0; n < m->N; ++n)

@@ -43,8 +43,10 @@ def status_of(fn, *args, **kw):
 def test_pack_argument_errors():
     W = gi.dense_weight(8, 64, seed=1)
     assert status_of(gq.gqsa_pack, W, 16, 3, 0.5) == 3          # bits
-    assert status_of(gq.gqsa_pack, W, 8, 4, 0.5) == 3           # G
+    assert status_of(gq.gqsa_pack, W, 4, 4, 0.5) == 3           # G
+    assert status_of(gq.gqsa_pack, W, 24, 4, 0.5) == 3
     assert status_of(gq.gqsa_pack, W[:, :40], 16, 4, 0.5) == 2  # K % G
+    assert status_of(gq.gqsa_pack, W[:, :40], 8, 4, 0.5) == 2   # G = 8: K still a multiple of 16
     assert status_of(gq.gqsa_pack, W, 16, 4, 1.5) == 4
     assert status_of(gq.gqsa_pack, W, 16, 4, -0.1) == 4
     assert status_of(gq.gqsa_pack, W, 16, 4, float("nan")) == 4

@@ -366,7 +366,7 @@ def test_largest_and_smallest_reduction_lengths(torch_cuda, bits):
 
 # ----------------------------------------------------------------------------- other group sizes
 
-@pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+@pytest.mark.parametrize("bits,G", [(4, 8), (8, 8), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 @pytest.mark.parametrize("part", [None, (5, 3), (2, 16)])
 def test_other_group_sizes(torch_cuda, bits, G, part):
     """G = 32, 64, 128: several 16-element chunks per stored group, code planes, smaller
@@ -382,7 +382,7 @@ def test_other_group_sizes(torch_cuda, bits, G, part):
     check(torch_cuda, h, c, gi.activations(3, K, seed=10))
 
 
-@pytest.mark.parametrize("G", [32, 64, 128])
+@pytest.mark.parametrize("G", [8, 32, 64, 128])
 def test_other_group_sizes_full_size_and_sparsities(torch_cuda, G):
     """4096x4096 W4 at G = 32, 64, 128, S = 0 and 50 %, default partition."""
     W = gi.dense_weight(4096, 4096, seed=gi.config_seed(3, 0))

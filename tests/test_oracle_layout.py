@@ -168,8 +168,9 @@ def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw, G=16):
                 o = base + 64 * cb + 256 + ln * 2
                 ix = int.from_bytes(raw[o:o + 2].tobytes(), "little")
                 slot = ix >> 4
-                assert slot % (G // 16) == 0
-                cols[pos] = slot // (G // 16)
+                per_group = max(1, G // 16)     # slots per group (G = 8: the index counts half-slots)
+                assert slot % per_group == 0
+                cols[pos] = slot // per_group
                 heads[pos] = bool(ix & 1)
                 assert ix & 0xE == 0
                 pos += 1
@@ -178,11 +179,11 @@ def decode_blob(blob, N, K, bits, nnzg, n_wg, wpw, G=16):
     return codes, scales, zeros, cols, heads
 
 
-@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+@pytest.mark.parametrize("bits,G", [(4, 8), (8, 8), (4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 @pytest.mark.parametrize("n_wg,wpw", [(1, 1), (3, 1), (1, 16), (3, 16), (5, 4), (2, 7)])
 def test_blob_decodes_back_to_canonical(bits, G, n_wg, wpw):
     n_waves = n_wg * wpw
-    N, K = 40, 512 * (G // 16)
+    N, K = 40, 512 * max(1, G // 16)
     W = gi.dense_weight(N, K, seed=41)
     keep = gi.imbalanced_keep_counts(N, K // G, seed=41)
     keep[5] = 0

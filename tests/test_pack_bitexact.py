@@ -156,7 +156,7 @@ def test_outliers_and_imbalanced_rows(bits):
         assert_same_blob(h, c)
 
 
-@pytest.mark.parametrize("bits,G", [(4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+@pytest.mark.parametrize("bits,G", [(4, 8), (8, 8), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 def test_other_group_sizes(bits, G):
     """Group sizes 32, 64, 128: canonical arrays and the device image (code planes, smaller
     tiles, index word = first 16-element slot) against the oracle, several partitions."""
@@ -199,7 +199,7 @@ def test_pack_hessian_matches_the_oracle(G, bits):
 
 def test_unsupported_group_sizes_are_refused():
     W = np.zeros((4, 256), dtype=np.float32)
-    for G, bits in ((8, 4), (48, 4), (256, 4), (128, 8)):
+    for G, bits in ((4, 4), (48, 4), (256, 4), (128, 8)):
         with pytest.raises(gq.GqsaError) as e:
             gq.gqsa_pack(W, G, bits, 0.5)
         assert e.value.status == 3
