@@ -144,15 +144,16 @@ gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_
                                          int waves_per_workgroup);
 
 /*
- * Build a second image of the matrix for calls with 9 to 16 activation rows (the small-batch
+ * Build a second image of the matrix for calls with several activation rows (the small-batch
  * side of Sec. 3.5's kernel, which may use the matrix cores): the stored groups of 16 consecutive
  * output rows ordered by group-column, so that one group-column of such a panel and the
  * activations under it are a dense 16x16x16 product (absent groups count as zeros).  Codes,
  * scales and zeros are the same bits as in the canonical arrays; the image takes about 12.5
- * bytes per stored 4-bit group on top of the first one.  Host only; only before the handle is
- * uploaded (GQSA_ERR_UNSUPPORTED after); G = 16 only (GQSA_ERR_UNSUPPORTED otherwise).  Once
- * built, gqsa_upload copies both images and gqsa_gemv / gqsa_gemv_multi use this one for
- * batch >= 9 (gqsa_gemv_multi: one launch per matrix); results stay within the same bound (fp32
+ * bytes per stored 4-bit group of 16 on top of the first one.  Host only; only before the handle
+ * is uploaded (GQSA_ERR_UNSUPPORTED after); G >= 16 (GQSA_ERR_UNSUPPORTED for G = 8; a group of
+ * 32, 64 or 128 weights takes 2, 4 or 8 products).  Once built, gqsa_upload copies both images and
+ * gqsa_gemv / gqsa_gemv_multi use this one for batch >= 9 with G = 16 and for batch >= 3 with
+ * the larger groups (gqsa_gemv_multi: one launch per matrix); results stay within the same bound (fp32
  * accumulation of exact products, one rounding to fp16) but are not bit-identical to those of
  * the other kernel.
  */

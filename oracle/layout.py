@@ -61,11 +61,11 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
  6. Blob = blocks, wave_info, row_of_rank, empty_rows, each region starting
     at a multiple of 256 bytes, zero padded, total a multiple of 256 (>= 256).
 
-Second image (panel_blob; G = 16 only), for calls with many activation rows --
+Second image (panel_blob; G >= 16), for calls with many activation rows --
 again a pure reordering of the canonical arrays:
  P1. Panels of 16 consecutive rows (P = ceil(N/16); rows >= N have no groups)
-     and slices of 32 consecutive group-columns (S = ceil(K/16/32); columns
-     >= K/16 have no groups).  Block (p, s) holds the stored groups of panel p
+     and slices of 32 consecutive group-columns (S = ceil(K/G/32); columns
+     >= K/G have no groups).  Block (p, s) holds the stored groups of panel p
      whose group-column lies in slice s, ordered by (group-column, row).
  P2. Header of block (p, s): 36 x uint32 at byte 144 (p S + s) of the image.
      Word j < 32, for group-column 32 s + j: bit r (r < 16) set if row 16 p + r
@@ -304,14 +304,14 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
 
 def panel_blob(c) -> bytes:
     """Exact bytes of the second (panel) image for canonical arrays `c` (spec items P1-P3)."""
-    if c.G != 16 or c.bits not in (4, 8):
-        raise ValueError("the panel image is specified for G = 16, bits in {4, 8}")
-    cb = 2 * c.bits
+    if c.G not in (16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
+        raise ValueError("the panel image is specified for G in {16,32,64,128}, bits in {4,8}, at most 64 code bytes")
+    cb = c.G * c.bits // 8
     ri = np.asarray(c.rowIndex, dtype=np.int64)
     gcol = np.asarray(c.groups, dtype=np.int64)
     nnzg = c.nnzg
     P = -(-c.N // 16)
-    S = -(-(c.K // 16) // 32)
+    S = -(-(c.K // c.G) // 32)
     row = np.repeat(np.arange(c.N, dtype=np.int64), ri[1:] - ri[:-1])
     blk = (row // 16) * S + gcol // 32
     # order inside the image: block, then group-column, then row

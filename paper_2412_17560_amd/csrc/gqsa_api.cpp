@@ -52,8 +52,9 @@ gqsa_status_t upload(gqsa_matrix* m)
 
 // Calls with this many activation rows or more go to the matrix-core kernel if the handle has a
 // panel image: its time hardly depends on the row count (16 rows' worth of products either way),
-// the wavefront kernel's grows with every row, and they cross between 8 and 12 rows on an MI355X.
-constexpr int kPanelMinBatch = 9;
+// the wavefront kernel's grows with every row, and they cross between 8 and 12 rows on an MI355X
+// (group sizes other than 16: between 2 and 3 rows, since that kernel takes them one row per launch).
+constexpr int panel_min_batch(const gqsa_matrix* m) { return m->G == 16 ? 9 : 3; }
 
 }  // namespace
 
@@ -171,7 +172,7 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
     if (!h->d_image) {
         if (gqsa_status_t st = upload(h)) return st;
     }
-    if (h->d_panels && batch >= kPanelMinBatch) return gqsa::panels_gemm(h, x_dev, y_dev, batch, hip_stream);
+    if (h->d_panels && batch >= panel_min_batch(h)) return gqsa::panels_gemm(h, x_dev, y_dev, batch, hip_stream);
     return gqsa::device_gemv(&h, 1, x_dev, &y_dev, batch, hip_stream);
 }
 
@@ -205,7 +206,7 @@ gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, cons
         for (int j = 0; j < i; ++j)
             if (handles[j] == handles[i]) return GQSA_ERR_SHAPE;   // a handle has one carry workspace
     }
-    bool panels = batch >= kPanelMinBatch;
+    bool panels = batch >= panel_min_batch(handles[0]);
     for (int i = 0; i < n_matrices; ++i) {
         if (!handles[i]->d_image) {
             if (gqsa_status_t st = upload(handles[i])) return st;

@@ -22,7 +22,7 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kPanelsPerWorkgroup = 4;   // panels a workgroup takes at most (each needs its own sums)
-constexpr int kInFlight = 4;          // columns whose products are under way together
+constexpr int kInFlight = 4;          // group-columns whose products are under way together
 constexpr int kPanelWaves = 16;      // wavefronts of a workgroup: each takes every 16th half-slice of the panel
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h)
@@ -70,19 +70,22 @@ __device__ __forceinline__ half4_t decode4(uint32_t code, uint32_t splice)
 // output row of the panel), so a lane ends up with the sums of output row l % 16 for the
 // activation rows 4 (l / 16) .. + 3 -- and the scale and zero it loaded with its codes are the
 // ones those sums need.
-template <int BITS>
+// M = 16-element chunks per group (G = 16 M): a group-column then takes M products, chained
+// through the accumulator input since they share scale and zero, and a wavefront's unit of work
+// is 16 / M group-columns (a slice of 32 has 2 M of them).
+template <int BITS, int M>
 __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const uint16_t* __restrict__ x, const uint8_t* __restrict__ headers, const uint8_t* __restrict__ data,
     uint16_t* __restrict__ y, int N, int K, int n_slices, int batch, int n_panels)
 {
-    constexpr int CB = 2 * BITS;                    // code bytes per group
+    constexpr int CB = 2 * BITS * M;                // code bytes per group
     __shared__ float part[kPanelWaves * 4 * kLanes];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15;                        // activation row (A), output row of the panel (B, D)
     const int j = lane >> 4;                        // which four of a group's 16 elements
-    const int kg = K >> 4;
+    const int kg = K / (16 * M);                    // group-columns
     const uint32_t below = (1u << r) - 1u;
     const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 4 * j;
     uint32_t splice;
@@ -96,19 +99,22 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[pp][v] = 0.0f;
-    constexpr int HC = kSliceColumns / 2;
+    constexpr int HC = 16 / M;                      // group-columns of a unit
+    constexpr int UPS = kSliceColumns / HC;         // units per slice
+    constexpr int FLY = HC < kInFlight ? HC : kInFlight;
     const uint32_t code_lane = (BITS == 4 ? 2u : 4u) * j;
-    for (int unit = wl; unit < 2 * n_slices; unit += kPanelWaves) {      // a slice in two halves of 16 group-columns
-        const int s = unit >> 1;
-        const int half = unit & 1;
-        const int col0 = s * kSliceColumns + half * HC;
+    for (int unit = wl; unit < UPS * n_slices; unit += kPanelWaves) {
+        const int s = unit / UPS;
+        const int sub = unit % UPS;
+        const int col0 = s * kSliceColumns + sub * HC;
         // the activations under these columns, once for all panels of the workgroup; the last
         // slice may be short: its missing columns (no groups there) take the last column's
-        uint2 xa[HC];
+        uint2 xa[HC][M];
 #pragma unroll
         for (int c = 0; c < HC; ++c) {
             const int col = col0 + c < kg ? col0 + c : kg - 1;
-            xa[c] = *reinterpret_cast<const uint2*>(xrow + 16 * col);
+#pragma unroll
+            for (int i = 0; i < M; ++i) xa[c][i] = *reinterpret_cast<const uint2*>(xrow + (16 * M) * col + 16 * i);
         }
         // the headers of all the workgroup's panels at once (scalar loads; a panel beyond the
         // last one stands in as the last one and is not computed)
@@ -119,7 +125,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
             const uint32_t* header = reinterpret_cast<const uint32_t*>(
                 headers + static_cast<size_t>((p < n_panels ? p : n_panels - 1) * n_slices + s) * kPanelHeaderBytes);
 #pragma unroll
-            for (int c = 0; c < HC; ++c) hh[pp][c] = header[half * HC + c];
+            for (int c = 0; c < HC; ++c) hh[pp][c] = header[sub * HC + c];
             where[pp] = header[32];
             count[pp] = header[33];
         }
@@ -129,30 +135,40 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
             if (p < n_panels) {                         // (the same for the whole workgroup)
                 const uint8_t* codes = data + static_cast<size_t>(where[pp]) * 16;
                 const uint32_t params_offset = (count[pp] * CB + 15u) / 16u * 16u;
-                uint32_t code[HC], sz[HC];
+                uint32_t code[HC][M], sz[HC];
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
                     const uint32_t h = hh[pp][c];
                     const uint32_t idx = (h >> 16) + __builtin_popcount(h & 0xFFFFu & below);
-                    if constexpr (BITS == 4) code[c] = *reinterpret_cast<const uint16_t*>(codes + (idx * CB + code_lane));
-                    else code[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * CB + code_lane));
+#pragma unroll
+                    for (int i = 0; i < M; ++i) {       // chunk i of the group: 8 (16) code bytes, 2 (4) of them this lane's
+                        if constexpr (BITS == 4)
+                            code[c][i] = *reinterpret_cast<const uint16_t*>(codes + (idx * CB + 8 * i + code_lane));
+                        else
+                            code[c][i] = *reinterpret_cast<const uint32_t*>(codes + (idx * CB + 16 * i + code_lane));
+                    }
                     sz[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * 4u + params_offset));
                 }
                 // four columns at a time: the products of the later ones are under way while the
                 // first one's sums are scaled.  Which lanes have a group in a column is a lane
                 // mask made from the header word with scalar arithmetic (bit r -> lanes r, r + 16, ...)
 #pragma unroll
-                for (int c = 0; c < HC; c += kInFlight) {
-                    float4_t d[kInFlight], e[kInFlight];
+                for (int c = 0; c < HC; c += FLY) {
+                    float4_t d[FLY], e[FLY];
 #pragma unroll
-                    for (int i = 0; i < kInFlight; ++i) {
-                        const half4_t a = __builtin_bit_cast(half4_t, xa[c + i]);
-                        const half4_t q = decode4<BITS>(code[c + i], splice);
-                        d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, zero4, 0, 0, 0);      // sum_j q_j x_j
-                        e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, zero4, 0, 0, 0);   // sum_j x_j
+                    for (int i = 0; i < FLY; ++i) {
+                        d[i] = zero4;
+                        e[i] = zero4;
+#pragma unroll
+                        for (int k = 0; k < M; ++k) {
+                            const half4_t a = __builtin_bit_cast(half4_t, xa[c + i][k]);
+                            const half4_t q = decode4<BITS>(code[c + i][k], splice);
+                            d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, d[i], 0, 0, 0);      // sum_j q_j x_j
+                            e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, e[i], 0, 0, 0);   // sum_j x_j
+                        }
                     }
 #pragma unroll
-                    for (int i = 0; i < kInFlight; ++i) {
+                    for (int i = 0; i < FLY; ++i) {
                         const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
                         if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
                             const float sc = half_bits_to_float(sz[c + i] & 0xFFFFu);
@@ -231,14 +247,21 @@ gqsa_status_t panels_gemm(const gqsa_matrix* m, const void* x, void* y, int batc
                                                                          (m->n_panels + kPanelsPerWorkgroup - 1) / kPanelsPerWorkgroup));
     const dim3 grid(static_cast<unsigned>(wgs)), block(kPanelWaves * kLanes);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (m->bits == 4)
-        hipLaunchKernelGGL(gqsa_panel_kernel<4>, grid, block, 0, s, static_cast<const uint16_t*>(x), img,
-                           data, static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
+    const auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint16_t*>(x), img, data,
+                           static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
                            static_cast<int>(m->n_slices), batch, static_cast<int>(m->n_panels));
-    else
-        hipLaunchKernelGGL(gqsa_panel_kernel<8>, grid, block, 0, s, static_cast<const uint16_t*>(x), img,
-                           data, static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
-                           static_cast<int>(m->n_slices), batch, static_cast<int>(m->n_panels));
+    };
+    switch (m->bits * 1000 + m->G) {
+        case 4016: launch(gqsa_panel_kernel<4, 1>); break;
+        case 4032: launch(gqsa_panel_kernel<4, 2>); break;
+        case 4064: launch(gqsa_panel_kernel<4, 4>); break;
+        case 4128: launch(gqsa_panel_kernel<4, 8>); break;
+        case 8016: launch(gqsa_panel_kernel<8, 1>); break;
+        case 8032: launch(gqsa_panel_kernel<8, 2>); break;
+        case 8064: launch(gqsa_panel_kernel<8, 4>); break;
+        default: return GQSA_ERR_UNSUPPORTED;
+    }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;
 }

@@ -1,15 +1,16 @@
 // Second device image of a packed matrix, for calls with many activation rows: the stored groups
 // of 16 consecutive output rows (a panel), ordered by group-column, so that one group-column of a
 // panel -- up to 16 groups of 16 weights, absent ones zero -- and the 16 x 16 activations under it
-// form a dense 16x16x16 product for the matrix cores.  The row-major stream of the GEMV kernel
+// form a dense 16x16x16 product for the matrix cores (groups of 32, 64 or 128 weights: two, four
+// or eight such products with one scale and zero).  The row-major stream of the GEMV kernel
 // cannot feed them: there every group of a row has its own activations (the gather of Sec. 3.5).
 // Only the order differs from the canonical BSR arrays of Sec. 3.2; codes, scales and zeros
 // (Eq. 1-3) are the same bits.
 //
 // Layout (all little-endian):
 //   panels      P = ceil(N / 16); panel p holds rows 16p .. 16p+15 (rows >= N: no groups)
-//   slices      the K/16 group-columns in runs of 32: S = ceil(K/16 / 32); slice s holds columns
-//               32s .. 32s+31 (columns >= K/16: no groups)
+//   slices      the K/G group-columns in runs of 32: S = ceil(K/G / 32); slice s holds columns
+//               32s .. 32s+31 (columns >= K/G: no groups)
 //   headers     one per block (p, s), at byte 144 (p S + s): uint32[36].  Word j < 32, for column
 //               32s + j: bits 0..15 = which rows of the panel store a group in that column (bit r:
 //               row 16p + r), bits 16..31 = number of groups of the block before that column.
@@ -34,9 +35,9 @@ namespace gqsa {
 
 gqsa_status_t build_panels(gqsa_matrix* m)
 {
-    if (m->G != 16) return GQSA_ERR_UNSUPPORTED;
-    const int cb = m->code_bytes();                  // 8 or 16
-    const int64_t kg = m->K / 16;
+    if (m->G < 16) return GQSA_ERR_UNSUPPORTED;
+    const int cb = m->code_bytes();                  // 8 .. 64
+    const int64_t kg = m->K / m->G;                  // group-columns
     const int64_t P = (m->N + kPanelRows - 1) / kPanelRows;
     const int64_t S = (kg + kSliceColumns - 1) / kSliceColumns;
     auto pad16 = [](size_t v) { return (v + 15) / 16 * 16; };

@@ -486,18 +486,18 @@ def test_vocabulary_sized_matrix(torch_cuda):
     gq.gqsa_free(h)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
 @pytest.mark.parametrize("batch", [1, 2, 5, 8, 9, 13, 16])
-def test_panel_kernel_ragged(torch_cuda, bits, batch):
+def test_panel_kernel_ragged(torch_cuda, bits, G, batch):
     """1..16 activation rows on the matrix cores, from the panel image: 301 rows (the last panel
     has 13), 61 group-columns (the second slice has 29), imbalanced rows, empty rows."""
-    N, K = 301, 976
+    N, K = 301, 61 * G
     W = gi.dense_weight(N, K, seed=90 + bits)
-    keep = gi.imbalanced_keep_counts(N, K // 16, seed=90 + bits)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=90 + bits)
     keep[[0, 5, 6, 300]] = 0
-    keep[17] = K // 16
-    c = oracle.pack(W, 16, bits, keep_per_row=keep)
-    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    keep[17] = K // G
+    c = oracle.pack(W, G, bits, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, G, bits)
     gq.gqsa_build_panels(h)
     check(torch_cuda, h, c, gi.activations(batch, K, seed=11 + batch), panels=True)
 

@@ -103,18 +103,18 @@ def test_aligned_stream_keeps_rows_inside_spans():
     assert np.all(scale[895:1024] == 0) and np.all(ix.transpose(0, 2, 1).reshape(-1)[895:1024] == 0)   # the null groups
 
 
-@pytest.mark.parametrize("bits", [4, 8])
-@pytest.mark.parametrize("shape", [(301, 2048), (16, 512), (33, 16), (1, 4096), (100, 1040)])
-def test_panel_image(bits, shape):
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+@pytest.mark.parametrize("shape", [(301, 2048), (16, 512), (33, 128), (1, 4096), (100, 1152)])
+def test_panel_image(bits, G, shape):
     """The second image (groups of 16 rows ordered by group-column) against its written layout."""
     N, K = shape
     W = gi.dense_weight(N, K, seed=80 + N)
-    keep = gi.imbalanced_keep_counts(N, K // 16, seed=80 + N)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=80 + N)
     if N > 8:
         keep[[0, 5, N - 1]] = 0
-        keep[3] = K // 16
-    h = gq.gqsa_pack_rows(W, keep, 16, bits)
-    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+        keep[3] = K // G
+    h = gq.gqsa_pack_rows(W, keep, G, bits)
+    c = oracle.pack(W, G, bits, keep_per_row=keep)
     assert gq.gqsa_info(h)["panel_bytes"] == 0
     with pytest.raises(gq.GqsaError) as e:
         gq.gqsa_export_panel_blob(h)
@@ -125,16 +125,16 @@ def test_panel_image(bits, shape):
     assert gq.gqsa_export_panel_blob(h) == ref
     assert_same_blob(h, c)                                  # the first image is untouched
     # every stored group appears exactly once: the blocks' counts add up
-    P, S = -(-N // 16), -(-(K // 16) // 32)
+    P, S = -(-N // 16), -(-(K // G) // 32)
     hdr = np.frombuffer(ref, dtype="<u4", count=P * S * 36).reshape(P * S, 36)
     assert int(hdr[:, 33].sum()) == c.nnzg
     last = hdr[:, 31].astype(np.int64)
     assert np.array_equal((last >> 16) + np.array([bin(v & 0xFFFF).count("1") for v in last]), hdr[:, 33])
 
 
-def test_panel_image_other_group_sizes_are_refused():
+def test_panel_image_is_refused_for_groups_of_eight():
     W = gi.dense_weight(8, 256, seed=3)
-    h = gq.gqsa_pack(W, 32, 4, 0.5)
+    h = gq.gqsa_pack(W, 8, 4, 0.5)
     with pytest.raises(gq.GqsaError) as e:
         gq.gqsa_build_panels(h)
     assert e.value.status == 3
