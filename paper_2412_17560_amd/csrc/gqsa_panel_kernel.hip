@@ -85,9 +85,9 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15;                        // activation row (A), output row of the panel (B, D)
     const int j = lane >> 4;                        // which four of a group's 16 elements
-    const int kg = K / (16 * M);                    // group-columns
     const uint32_t below = (1u << r) - 1u;
-    const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 4 * j;
+    const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 8 * (j & 1);
+    const int last_chunk = (K >> 4) - 1;
     uint32_t splice;
     asm volatile("s_mov_b32 %0, 0x64006400" : "=s"(splice));     // (kept out of the compiler's sight as a constant)
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -102,19 +102,31 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     constexpr int HC = 16 / M;                      // group-columns of a unit
     constexpr int UPS = kSliceColumns / HC;         // units per slice
     constexpr int FLY = HC < kInFlight ? HC : kInFlight;
-    const uint32_t code_lane = (BITS == 4 ? 2u : 4u) * j;
+    const uint32_t code_lane = (BITS == 4 ? 1u : 2u) * (4u * (j & 1) + 2u * (j >> 1));      // elements 0-3, 8-11, 4-7, 12-15 of a chunk for j = 0..3
     for (int unit = wl; unit < UPS * n_slices; unit += kPanelWaves) {
         const int s = unit / UPS;
         const int sub = unit % UPS;
         const int col0 = s * kSliceColumns + sub * HC;
-        // the activations under these columns, once for all panels of the workgroup; the last
-        // slice may be short: its missing columns (no groups there) take the last column's
+        // The activations under these columns (16 chunks of 16), once for all panels of the
+        // workgroup, with 16-byte loads: of two neighbouring chunks the lanes 0..31 load the first
+        // (elements 0-7 and 8-15 of it), the lanes 32..63 the second, and a swap between the two
+        // halves of the wavefront hands every lane the four elements it supplies to a product:
+        // elements 0-3, 8-11, 4-7, 12-15 of the chunk for the lanes' j = 0..3 (which element sits in
+        // which of the product's 16 slots does not matter as long as the codes follow suit).
+        // The last slice may be short: chunks beyond K (no groups there) take the last one's.
         uint2 xa[HC][M];
+        {
+            const int chunk0 = col0 * M;
+            uint2* flat = &xa[0][0];
 #pragma unroll
-        for (int c = 0; c < HC; ++c) {
-            const int col = col0 + c < kg ? col0 + c : kg - 1;
-#pragma unroll
-            for (int i = 0; i < M; ++i) xa[c][i] = *reinterpret_cast<const uint2*>(xrow + (16 * M) * col + 16 * i);
+            for (int pr = 0; pr < 8; ++pr) {
+                const int g = chunk0 + 2 * pr + (j >> 1);
+                const uint4 w = *reinterpret_cast<const uint4*>(xrow + 16 * (g < last_chunk ? g : last_chunk));
+                const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+                flat[2 * pr] = uint2{s0[0], s1[0]};
+                flat[2 * pr + 1] = uint2{s0[1], s1[1]};
+            }
         }
         // the headers of all the workgroup's panels at once (scalar loads; a panel beyond the
         // last one stands in as the last one and is not computed)
