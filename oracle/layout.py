@@ -75,13 +75,15 @@ again a pure reordering of the canonical arrays:
      block; words 34, 35 = 0.  The header region is zero padded to a multiple
      of 256 bytes.
  P3. Data region: the blocks' data follow each other in header order without
-     gaps.  A block's data: codes, per group its 2*bits bytes; 8-bit codes as in
-     the canonical `values`; 4-bit codes with every pair of canonical bytes
-     (e0 | e1 << 4), (e2 | e3 << 4) stored as (e0 | e2 << 4), (e1 | e3 << 4);
-     zero padded to a multiple of 16 bytes.  Then parameters: per group uint32
-     fp16 scale bits | fp16 zero bits << 16; zero padded to a multiple of 16
-     bytes.  After the last block 256 zero bytes; the image is zero padded to a
-     multiple of 256 bytes.
+     gaps.  A block's data: one record per group, zero padded as a whole to a
+     multiple of 16 bytes.  Record = the code bytes of quarters 0 and 1, then
+     uint32 fp16 scale bits | fp16 zero bits << 16, then the code bytes of
+     quarters 2 and 3 (G*bits/8 + 4 bytes).  Code bytes: quarter t = 0..3 after
+     quarter, and inside a quarter chunk i = 0..G/16-1 after chunk, the codes of
+     elements 16 i + 4 t .. 16 i + 4 t + 3 (e0..e3): 8-bit codes as four bytes
+     in element order; 4-bit codes as the two bytes (e0 | e2 << 4),
+     (e1 | e3 << 4).  After the last block 256 zero bytes; the image is zero
+     padded to a multiple of 256 bytes.
 """
 from __future__ import annotations
 
@@ -318,20 +320,31 @@ def panel_blob(c) -> bytes:
     order = np.lexsort((row, gcol, blk))
     counts = np.bincount(blk, minlength=P * S).astype(np.int64)
     pad16 = lambda v: (v + 15) // 16 * 16
-    sizes = pad16(counts * cb) + pad16(counts * 4)
+    sizes = pad16(counts * (cb + 4))
     starts = np.concatenate(([0], np.cumsum(sizes)))
     header_bytes = _align(P * S * 144)
     total = _align(header_bytes + int(starts[-1]) + 256)
     img = np.zeros(total, dtype=np.uint8)
+    # every group's codes as elements, then as the record's code bytes
     vals = np.asarray(c.values, dtype=np.uint8).reshape(nnzg, cb)
     if c.bits == 4:
-        even, odd = vals[:, 0::2], vals[:, 1::2]                  # (e0 | e1 << 4), (e2 | e3 << 4)
-        stored = np.empty_like(vals)
-        stored[:, 0::2] = (even & 0x0F) | ((odd & 0x0F) << 4)     # e0 | e2 << 4
-        stored[:, 1::2] = (even >> 4) | (odd & 0xF0)              # e1 | e3 << 4
+        elems = np.empty((nnzg, c.G), dtype=np.uint8)
+        elems[:, 0::2] = vals & 0xF
+        elems[:, 1::2] = vals >> 4
     else:
-        stored = vals
+        elems = vals
+    chunks = c.G // 16
+    e4 = elems.reshape(nnzg, chunks, 4, 4)                      # [group][chunk i][quarter t][e0..e3]
+    e4 = e4.transpose(0, 2, 1, 3)                               # [group][quarter t][chunk i][e0..e3]
+    if c.bits == 4:
+        stored = np.empty((nnzg, 4, chunks, 2), dtype=np.uint8)
+        stored[..., 0] = e4[..., 0] | (e4[..., 2] << 4)
+        stored[..., 1] = e4[..., 1] | (e4[..., 3] << 4)
+    else:
+        stored = e4
+    stored = np.ascontiguousarray(stored).reshape(nnzg, cb)
     sz = (np.asarray(c.scales, dtype=np.uint32) | (np.asarray(c.zeros, dtype=np.uint32) << np.uint32(16))).astype("<u4")
+    records = np.concatenate([stored[:, :cb // 2], sz.view(np.uint8).reshape(nnzg, 4), stored[:, cb // 2:]], axis=1)   # [group][cb + 4]
     first = np.concatenate(([0], np.cumsum(counts)))          # index into `order` of each block's first group
     for b in range(P * S):
         k = int(counts[b])
@@ -352,7 +365,5 @@ def panel_blob(c) -> bytes:
         img[b * 144:(b + 1) * 144] = header.astype("<u4").view(np.uint8)
         if k:
             base = header_bytes + int(starts[b])
-            img[base:base + k * cb] = stored[g].reshape(-1)
-            pbase = base + int(pad16(k * cb))
-            img[pbase:pbase + 4 * k] = sz[g].view(np.uint8)
+            img[base:base + k * (cb + 4)] = records[g].reshape(-1)
     return img.tobytes()

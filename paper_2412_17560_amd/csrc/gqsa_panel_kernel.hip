@@ -37,18 +37,21 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
 
 // Four codes -> four fp16 integers, exactly: 0x6400 | q is the fp16 number 1024 + q (q < 1024).
 // `splice` = 0x64006400 in a register (an AND-OR takes one literal, and the nibble mask is it).
-template <int BITS>
-__device__ __forceinline__ half4_t decode4(uint32_t code, uint32_t splice)
+// 4-bit: `pair` holds the two bytes (e0 | e2 << 4), (e1 | e3 << 4) in bits 0..7 and 16..23.
+__device__ __forceinline__ half4_t decode4_w4(uint32_t pair, uint32_t splice)
 {
-    uint32_t lo, hi;
-    if constexpr (BITS == 4) {     // two bytes (e0 | e2 << 4), (e1 | e3 << 4), whatever lies above them
-        const uint32_t t = __builtin_amdgcn_perm(0u, code, 0x0c010c00u);      // first byte to bits 0..7, second to 16..23
-        lo = (t & 0x000F000Fu) | splice;                // e0, e1
-        hi = ((t >> 4) & 0x000F000Fu) | splice;         // e2, e3
-    } else {                       // four bytes, one per element
-        lo = __builtin_amdgcn_perm(0u, code, 0x0c010c00u) | splice;
-        hi = __builtin_amdgcn_perm(0u, code, 0x0c030c02u) | splice;
-    }
+    const uint32_t lo = (pair & 0x000F000Fu) | splice;            // e0, e1
+    const uint32_t hi = ((pair >> 4) & 0x000F000Fu) | splice;     // e2, e3
+    const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
+    const half2_t a = __builtin_bit_cast(half2_t, lo) - bias;
+    const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
+    return half4_t{a.x, a.y, b.x, b.y};
+}
+// 8-bit: four bytes, one per element.
+__device__ __forceinline__ half4_t decode4_w8(uint32_t code, uint32_t splice)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(0u, code, 0x0c010c00u) | splice;
+    const uint32_t hi = __builtin_amdgcn_perm(0u, code, 0x0c030c02u) | splice;
     const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t a = __builtin_bit_cast(half2_t, lo) - bias;
     const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
@@ -79,6 +82,10 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     uint16_t* __restrict__ y, int N, int K, int n_slices, int batch, int n_panels)
 {
     constexpr int CB = 2 * BITS * M;                // code bytes per group
+    constexpr int RB = CB + 4;                      // record: codes of quarters 0, 1 | scale, zero | codes of quarters 2, 3
+    constexpr int QB = (BITS / 2) * M;              // code bytes of a lane (one quarter of every chunk)
+    constexpr int QW = (QB + 3) / 4;                // ... in registers
+    constexpr bool PAIRED = QB == 2;                // 4-bit, G = 16: codes and scale, zero in one 8-byte load
     __shared__ float part[kPanelWaves * 4 * kLanes];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -102,7 +109,16 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     constexpr int HC = 16 / M;                      // group-columns of a unit
     constexpr int UPS = kSliceColumns / HC;         // units per slice
     constexpr int FLY = HC < kInFlight ? HC : kInFlight;
-    const uint32_t code_lane = (BITS == 4 ? 1u : 2u) * (4u * (j & 1) + 2u * (j >> 1));      // elements 0-3, 8-11, 4-7, 12-15 of a chunk for j = 0..3
+    // a lane supplies elements 0-3, 8-11, 4-7, 12-15 of every chunk for j = 0..3: quarters 0, 2, 1, 3
+    const uint32_t quarter = 2u * (j & 1) + (j >> 1);
+    const uint32_t code_lane = quarter * QB + (quarter >= 2 ? 4u : 0u);     // where its codes start in a record
+    // PAIRED: lanes of quarters 0, 1 load bytes 0..7 of the 12-byte record (codes, then scale | zero),
+    // lanes of quarters 2, 3 bytes 4..11 (scale | zero, then codes); a byte permute with a selector
+    // that differs by lane puts the lane's two code bytes into bits 0..7 and 16..23, another one
+    // picks the scale | zero word
+    const uint32_t pair_load = quarter >= 2 ? 4u : 0u;
+    const uint32_t sel_codes = 0x0c010c00u + (quarter & 1u) * 0x00020002u + (quarter >= 2 ? 0x00040004u : 0u);
+    const uint32_t sel_sz = quarter >= 2 ? 0x03020100u : 0x07060504u;
     for (int unit = wl; unit < UPS * n_slices; unit += kPanelWaves) {
         const int s = unit / UPS;
         const int sub = unit % UPS;
@@ -130,7 +146,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
         }
         // the headers of all the workgroup's panels at once (scalar loads; a panel beyond the
         // last one stands in as the last one and is not computed)
-        uint32_t hh[kPanelsPerWorkgroup][HC], where[kPanelsPerWorkgroup], count[kPanelsPerWorkgroup];
+        uint32_t hh[kPanelsPerWorkgroup][HC], where[kPanelsPerWorkgroup];
 #pragma unroll
         for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
             const int p = blockIdx.x + pp * gridDim.x;
@@ -139,27 +155,34 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
 #pragma unroll
             for (int c = 0; c < HC; ++c) hh[pp][c] = header[sub * HC + c];
             where[pp] = header[32];
-            count[pp] = header[33];
         }
 #pragma unroll
         for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
             const int p = blockIdx.x + pp * gridDim.x;
             if (p < n_panels) {                         // (the same for the whole workgroup)
-                const uint8_t* codes = data + static_cast<size_t>(where[pp]) * 16;
-                const uint32_t params_offset = (count[pp] * CB + 15u) / 16u * 16u;
-                uint32_t code[HC][M], sz[HC];
+                const uint8_t* records = data + static_cast<size_t>(where[pp]) * 16;
+                uint32_t code[HC][PAIRED ? 2 : QW], sz[HC];
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
                     const uint32_t h = hh[pp][c];
                     const uint32_t idx = (h >> 16) + __builtin_popcount(h & 0xFFFFu & below);
-#pragma unroll
-                    for (int i = 0; i < M; ++i) {       // chunk i of the group: 8 (16) code bytes, 2 (4) of them this lane's
-                        if constexpr (BITS == 4)
-                            code[c][i] = *reinterpret_cast<const uint16_t*>(codes + (idx * CB + 8 * i + code_lane));
-                        else
-                            code[c][i] = *reinterpret_cast<const uint32_t*>(codes + (idx * CB + 16 * i + code_lane));
+                    if constexpr (PAIRED) {
+                        const uint2 w = *reinterpret_cast<const uint2*>(records + (idx * RB + pair_load));
+                        code[c][0] = w.x;
+                        code[c][1] = w.y;
+                    } else {
+                        const uint8_t* mine = records + (idx * RB + code_lane);
+                        if constexpr (QW == 1) {
+                            code[c][0] = *reinterpret_cast<const uint32_t*>(mine);
+                        } else if constexpr (QW == 2) {
+                            const uint2 w = *reinterpret_cast<const uint2*>(mine);
+                            code[c][0] = w.x; code[c][1] = w.y;
+                        } else {
+                            const uint4 w = *reinterpret_cast<const uint4*>(mine);
+                            code[c][0] = w.x; code[c][1] = w.y; code[c][2] = w.z; code[c][3] = w.w;
+                        }
+                        sz[c] = *reinterpret_cast<const uint32_t*>(records + (idx * RB + CB / 2));
                     }
-                    sz[c] = *reinterpret_cast<const uint32_t*>(codes + (idx * 4u + params_offset));
                 }
                 // four columns at a time: the products of the later ones are under way while the
                 // first one's sums are scaled.  Which lanes have a group in a column is a lane
@@ -174,7 +197,14 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
 #pragma unroll
                         for (int k = 0; k < M; ++k) {
                             const half4_t a = __builtin_bit_cast(half4_t, xa[c + i][k]);
-                            const half4_t q = decode4<BITS>(code[c + i][k], splice);
+                            half4_t q;
+                            if constexpr (PAIRED) {
+                                q = decode4_w4(__builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_codes), splice);
+                            } else if constexpr (BITS == 4) {     // chunk k: two bytes, the lower or the upper half of a word
+                                q = decode4_w4(__builtin_amdgcn_perm(0u, code[c + i][k / 2], (k & 1) ? 0x0c030c02u : 0x0c010c00u), splice);
+                            } else {
+                                q = decode4_w8(code[c + i][k], splice);
+                            }
                             d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, d[i], 0, 0, 0);      // sum_j q_j x_j
                             e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, e[i], 0, 0, 0);   // sum_j x_j
                         }
@@ -183,8 +213,11 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                     for (int i = 0; i < FLY; ++i) {
                         const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
                         if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
-                            const float sc = half_bits_to_float(sz[c + i] & 0xFFFFu);
-                            const float z = half_bits_to_float(sz[c + i] >> 16);
+                            uint32_t sz_word;
+                            if constexpr (PAIRED) sz_word = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
+                            else sz_word = sz[c + i];
+                            const float sc = half_bits_to_float(sz_word & 0xFFFFu);
+                            const float z = half_bits_to_float(sz_word >> 16);
 #pragma unroll
                             for (int v = 0; v < 4; ++v)
                                 acc[pp][v] = __builtin_fmaf(sc, __builtin_fmaf(-z, e[i][v], d[i][v]), acc[pp][v]);

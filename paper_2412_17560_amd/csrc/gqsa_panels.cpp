@@ -17,14 +17,17 @@
 //               Word 32 = where the block's data start, in 16-byte units from the start of the data
 //               region; word 33 = number of groups of the block; words 34, 35 = 0.  The header
 //               region is padded to a multiple of 256 bytes.
-//   data        per block, in the order of the headers: codes -- the block's groups ordered by
-//               (column, row), each with its 2*bits code bytes; 4-bit codes with the nibbles of
-//               every byte pair regrouped so that two masks split a lane's four codes into two
-//               pairs: canonical bytes (e0 | e1 << 4), (e2 | e3 << 4) become (e0 | e2 << 4),
-//               (e1 | e3 << 4); 8-bit codes as they are -- padded to a multiple of 16 bytes; then
-//               parameters: uint32 per group in the same order, fp16 scale | fp16 zero << 16,
-//               padded to a multiple of 16 bytes.  The region ends with 256 zero bytes and the image
-//               is padded to a multiple of 256 bytes.
+//   data        per block, in the order of the headers: one record per group, the block's groups
+//               ordered by (column, row); the block is padded to a multiple of 16 bytes.  Record =
+//               the code bytes of quarters 0 and 1, then uint32 fp16 scale | fp16 zero << 16, then
+//               the code bytes of quarters 2 and 3 (with 2 code bytes per quarter a lane's codes
+//               and the scale and zero are one 8-byte load).  Quarter t (t = 0..3) holds, chunk
+//               after chunk of 16 elements, the codes of the elements 4t .. 4t+3 of every chunk --
+//               what one lane supplies to the products -- so a lane's codes are contiguous.  A quarter of a chunk is 2 bytes of
+//               4-bit codes, elements e0..e3 as (e0 | e2 << 4), (e1 | e3 << 4) (two masks split
+//               them into two fp16 pairs), or 4 bytes of 8-bit codes in element order.
+//               The region ends with 256 zero bytes and the image is padded to a multiple of 256
+//               bytes.
 #include <algorithm>
 #include <cstring>
 #include <new>
@@ -38,6 +41,7 @@ gqsa_status_t build_panels(gqsa_matrix* m)
     if (m->G < 16) return GQSA_ERR_UNSUPPORTED;
     const int cb = m->code_bytes();                  // 8 .. 64
     const int64_t kg = m->K / m->G;                  // group-columns
+    const int chunks = m->G / 16;
     const int64_t P = (m->N + kPanelRows - 1) / kPanelRows;
     const int64_t S = (kg + kSliceColumns - 1) / kSliceColumns;
     auto pad16 = [](size_t v) { return (v + 15) / 16 * 16; };
@@ -50,7 +54,7 @@ gqsa_status_t build_panels(gqsa_matrix* m)
             ++count[static_cast<size_t>((n / kPanelRows) * S + m->groups[g] / kSliceColumns)];
     std::vector<uint64_t> start(static_cast<size_t>(P * S) + 1, 0);     // bytes
     for (int64_t b = 0; b < P * S; ++b)
-        start[b + 1] = start[b] + pad16(static_cast<size_t>(count[b]) * cb) + pad16(static_cast<size_t>(count[b]) * 4);
+        start[b + 1] = start[b] + pad16(static_cast<size_t>(count[b]) * (cb + 4));
     if (start.back() / 16 > UINT32_MAX) return GQSA_ERR_SHAPE;
     const size_t header_bytes = pad256(static_cast<size_t>(P * S) * kPanelHeaderBytes);
     const size_t total = pad256(header_bytes + start.back() + 256);
@@ -71,8 +75,7 @@ gqsa_status_t build_panels(gqsa_matrix* m)
         for (int64_t s = 0; s < S; ++s) {
             const size_t b = static_cast<size_t>(p * S + s);
             uint32_t* header = reinterpret_cast<uint32_t*>(img.data() + b * kPanelHeaderBytes);
-            uint8_t* codes = img.data() + header_bytes + start[b];
-            uint8_t* params = codes + pad16(static_cast<size_t>(count[b]) * cb);
+            uint8_t* records = img.data() + header_bytes + start[b];
             uint32_t k = 0;
             for (int j = 0; j < kSliceColumns; ++j) {
                 const int64_t c = s * kSliceColumns + j;
@@ -83,17 +86,22 @@ gqsa_status_t build_panels(gqsa_matrix* m)
                         const int64_t g = cur[r]++;
                         mask |= 1u << r;
                         const uint8_t* v = &m->values[static_cast<size_t>(g) * cb];
-                        uint8_t* out = codes + static_cast<size_t>(k) * cb;
-                        if (m->bits == 4) {
-                            for (int i = 0; i < cb; i += 2) {      // (e0 | e1 << 4), (e2 | e3 << 4) -> (e0 | e2 << 4), (e1 | e3 << 4)
-                                out[i] = static_cast<uint8_t>((v[i] & 0x0F) | ((v[i + 1] & 0x0F) << 4));
-                                out[i + 1] = static_cast<uint8_t>((v[i] >> 4) | (v[i + 1] & 0xF0));
+                        uint8_t* out = records + static_cast<size_t>(k) * (cb + 4);
+                        const int qb = m->bits / 2;                 // bytes of a quarter of a chunk: 2 or 4
+                        for (int t = 0; t < 4; ++t) {
+                            for (int i = 0; i < chunks; ++i) {
+                                const uint8_t* src = v + static_cast<size_t>(i) * 4 * qb + static_cast<size_t>(t) * qb;
+                                uint8_t* dst = out + (static_cast<size_t>(t) * chunks + i) * qb + (t >= 2 ? 4 : 0);
+                                if (m->bits == 4) {    // (e0 | e1 << 4), (e2 | e3 << 4) -> (e0 | e2 << 4), (e1 | e3 << 4)
+                                    dst[0] = static_cast<uint8_t>((src[0] & 0x0F) | ((src[1] & 0x0F) << 4));
+                                    dst[1] = static_cast<uint8_t>((src[0] >> 4) | (src[1] & 0xF0));
+                                } else {
+                                    std::memcpy(dst, src, 4);
+                                }
                             }
-                        } else {
-                            std::memcpy(out, v, cb);
                         }
                         const uint32_t sz = static_cast<uint32_t>(m->scales[g]) | (static_cast<uint32_t>(m->zeros[g]) << 16);
-                        std::memcpy(params + static_cast<size_t>(k) * 4, &sz, 4);
+                        std::memcpy(out + cb / 2, &sz, 4);
                         ++k;
                     }
                 }
