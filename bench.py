@@ -380,7 +380,7 @@ def main():
                 for h in hs:
                     gq.gqsa_free(h)
                 # the same with the second image (gqsa_build_panels): 16 output rows x 16 activation
-                # rows x one group-column per matrix-core product; gqsa_gemv takes it from 9 rows on
+                # rows x one group-column per matrix-core product; gqsa_gemv takes it from 5 rows on
                 hs = copies_of(W, bits, 0.5, panels=True)
                 for B in (8, 16):
                     xb = torch.from_numpy(gi.activations(B, K, seed=gi.config_seed(5, 1))).to(dev)
@@ -412,7 +412,7 @@ def main():
             yb = torch.empty((B, 4096), dtype=torch.float16, device=dev)
             us = time_calls(lambda k, xb=xb, yb=yb: gq.gqsa_gemv(hs[k % len(hs)], xb, yb), n=96)
             small_batch.append({"batch": B, "us_cold": round(us, 3), "us_per_row": round(us / B, 3)})
-        # the same from the second image (matrix cores); gqsa_gemv takes it from 9 rows on
+        # the same from the second image (matrix cores); gqsa_gemv takes it from 5 rows on
         Wb = gi.dense_weight_chunked(4096, 4096, seed=gi.config_seed(5, 0), workers=workers)
         hp = copies_of(Wb, 4, 0.5, panels=True)
         del Wb

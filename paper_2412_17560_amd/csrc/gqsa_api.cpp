@@ -52,9 +52,9 @@ gqsa_status_t upload(gqsa_matrix* m)
 
 // Calls with this many activation rows or more go to the matrix-core kernel if the handle has a
 // panel image: its time hardly depends on the row count (16 rows' worth of products either way),
-// the wavefront kernel's grows with every row, and they cross between 8 and 12 rows on an MI355X
+// the wavefront kernel's grows with every row, and they cross between 4 and 5 rows on an MI355X
 // (group sizes other than 16: between 2 and 3 rows, since that kernel takes them one row per launch).
-constexpr int panel_min_batch(const gqsa_matrix* m) { return m->G == 16 ? 9 : 3; }
+constexpr int panel_min_batch(const gqsa_matrix* m) { return m->G == 16 ? 5 : 3; }
 
 }  // namespace
 

@@ -521,9 +521,9 @@ def test_panel_kernel_unit_vectors_are_bit_exact(torch_cuda):
     assert np.array_equal(y.view(np.uint16), ref.view(np.uint16))
 
 
-def test_panel_kernel_only_from_nine_rows(torch_cuda):
-    """Below 9 activation rows a handle with a panel image runs the wavefront kernel in gqsa_gemv:
-    same bits as a handle without one.  From 9 on it is gqsa_gemv_panels, whose results differ in
+def test_panel_kernel_only_from_five_rows(torch_cuda):
+    """Below 5 activation rows a handle with a panel image runs the wavefront kernel in gqsa_gemv:
+    same bits as a handle without one.  From 5 on it is gqsa_gemv_panels, whose results differ in
     rounding only."""
     N, K = 512, 2048
     W = gi.dense_weight(N, K, seed=96)
@@ -532,10 +532,10 @@ def test_panel_kernel_only_from_nine_rows(torch_cuda):
     h2 = gq.gqsa_pack(W, 16, 4, 0.3)
     gq.gqsa_build_panels(h2)
     assert gq.gqsa_info(h2)["panel_bytes"] > 0
-    for batch in (1, 4, 8):
+    for batch in (1, 3, 4):
         x = gi.activations(batch, K, seed=12)
         assert np.array_equal(run_gemv(torch_cuda, h1, x).view(np.uint16), run_gemv(torch_cuda, h2, x).view(np.uint16))
-    x = gi.activations(9, K, seed=13)
+    x = gi.activations(5, K, seed=13)
     y, _ = check(torch_cuda, h2, c, x)
     assert np.array_equal(y.view(np.uint16), run_gemv(torch_cuda, h2, x, panels=True).view(np.uint16))
     with pytest.raises(gq.GqsaError):
