@@ -82,8 +82,10 @@ again a pure reordering of the canonical arrays:
      quarter, and inside a quarter chunk i = 0..G/16-1 after chunk, the codes of
      elements 16 i + 4 t .. 16 i + 4 t + 3 (e0..e3): 8-bit codes as four bytes
      in element order; 4-bit codes as the two bytes (e0 | e2 << 4),
-     (e1 | e3 << 4).  After the last block 256 zero bytes; the image is zero
-     padded to a multiple of 256 bytes.
+     (e1 | e3 << 4).  Exception, 8-bit codes with G = 16: the scale | zero
+     word is stored twice, record = quarter 0, word, quarter 1, quarter 2, word,
+     quarter 3 (24 bytes).  After the last block 256 zero bytes; the image is
+     zero padded to a multiple of 256 bytes.
 """
 from __future__ import annotations
 
@@ -320,7 +322,9 @@ def panel_blob(c) -> bytes:
     order = np.lexsort((row, gcol, blk))
     counts = np.bincount(blk, minlength=P * S).astype(np.int64)
     pad16 = lambda v: (v + 15) // 16 * 16
-    sizes = pad16(counts * (cb + 4))
+    twice = c.bits == 8 and c.G == 16
+    rb = cb + (8 if twice else 4)
+    sizes = pad16(counts * rb)
     starts = np.concatenate(([0], np.cumsum(sizes)))
     header_bytes = _align(P * S * 144)
     total = _align(header_bytes + int(starts[-1]) + 256)
@@ -344,7 +348,11 @@ def panel_blob(c) -> bytes:
         stored = e4
     stored = np.ascontiguousarray(stored).reshape(nnzg, cb)
     sz = (np.asarray(c.scales, dtype=np.uint32) | (np.asarray(c.zeros, dtype=np.uint32) << np.uint32(16))).astype("<u4")
-    records = np.concatenate([stored[:, :cb // 2], sz.view(np.uint8).reshape(nnzg, 4), stored[:, cb // 2:]], axis=1)   # [group][cb + 4]
+    szb = sz.view(np.uint8).reshape(nnzg, 4)
+    if twice:
+        records = np.concatenate([stored[:, 0:4], szb, stored[:, 4:8], stored[:, 8:12], szb, stored[:, 12:16]], axis=1)
+    else:
+        records = np.concatenate([stored[:, :cb // 2], szb, stored[:, cb // 2:]], axis=1)                 # [group][rb]
     first = np.concatenate(([0], np.cumsum(counts)))          # index into `order` of each block's first group
     for b in range(P * S):
         k = int(counts[b])
@@ -365,5 +373,5 @@ def panel_blob(c) -> bytes:
         img[b * 144:(b + 1) * 144] = header.astype("<u4").view(np.uint8)
         if k:
             base = header_bytes + int(starts[b])
-            img[base:base + k * (cb + 4)] = records[g].reshape(-1)
+            img[base:base + k * rb] = records[g].reshape(-1)
     return img.tobytes()

@@ -47,11 +47,12 @@ __device__ __forceinline__ half4_t decode4_w4(uint32_t pair, uint32_t splice)
     const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
     return half4_t{a.x, a.y, b.x, b.y};
 }
-// 8-bit: four bytes, one per element.
-__device__ __forceinline__ half4_t decode4_w8(uint32_t code, uint32_t splice)
+// 8-bit: four bytes, one per element, in the word of the pair (upper, lower) that `sel` names:
+// sel = 0x0c010c00 for the lower word, 0x0c050c04 for the upper one.
+__device__ __forceinline__ half4_t decode4_w8(uint32_t upper, uint32_t lower, uint32_t sel, uint32_t splice)
 {
-    const uint32_t lo = __builtin_amdgcn_perm(0u, code, 0x0c010c00u) | splice;
-    const uint32_t hi = __builtin_amdgcn_perm(0u, code, 0x0c030c02u) | splice;
+    const uint32_t lo = __builtin_amdgcn_perm(upper, lower, sel) | splice;                  // bytes 0, 1
+    const uint32_t hi = __builtin_amdgcn_perm(upper, lower, sel + 0x00020002u) | splice;    // bytes 2, 3
     const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t a = __builtin_bit_cast(half2_t, lo) - bias;
     const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
@@ -82,7 +83,8 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     uint16_t* __restrict__ y, int N, int K, int n_slices, int batch, int n_panels)
 {
     constexpr int CB = 2 * BITS * M;                // code bytes per group
-    constexpr int RB = CB + 4;                      // record: codes of quarters 0, 1 | scale, zero | codes of quarters 2, 3
+    constexpr bool PAIRED8 = BITS == 8 && M == 1;   // 8-bit, G = 16: quarter 0, word, quarter 1, quarter 2, word, quarter 3
+    constexpr int RB = CB + (PAIRED8 ? 8 : 4);      // record: codes of quarters 0, 1 | scale, zero | codes of quarters 2, 3
     constexpr int QB = (BITS / 2) * M;              // code bytes of a lane (one quarter of every chunk)
     constexpr int QW = (QB + 3) / 4;                // ... in registers
     constexpr bool PAIRED = QB == 2;                // 4-bit, G = 16: codes and scale, zero in one 8-byte load
@@ -116,9 +118,13 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     // lanes of quarters 2, 3 bytes 4..11 (scale | zero, then codes); a byte permute with a selector
     // that differs by lane puts the lane's two code bytes into bits 0..7 and 16..23, another one
     // picks the scale | zero word
-    const uint32_t pair_load = quarter >= 2 ? 4u : 0u;
-    const uint32_t sel_codes = 0x0c010c00u + (quarter & 1u) * 0x00020002u + (quarter >= 2 ? 0x00040004u : 0u);
-    const uint32_t sel_sz = quarter >= 2 ? 0x03020100u : 0x07060504u;
+    // PAIRED8: quarters 0 and 2 load (codes, word), quarters 1 and 3 (word, codes); the permutes of
+    // the decode take the code bytes from whichever of the two it is
+    const uint32_t pair_load = PAIRED8 ? 4u * quarter + (quarter >= 2 ? 4u : 0u) : (quarter >= 2 ? 4u : 0u);
+    const uint32_t sel_codes = PAIRED8 ? 0x0c010c00u + (quarter & 1u) * 0x00040004u
+                                       : 0x0c010c00u + (quarter & 1u) * 0x00020002u + (quarter >= 2 ? 0x00040004u : 0u);
+    const uint32_t sel_sz = PAIRED8 ? ((quarter & 1u) ? 0x03020100u : 0x07060504u)
+                                    : (quarter >= 2 ? 0x03020100u : 0x07060504u);
     for (int unit = wl; unit < UPS * n_slices; unit += kPanelWaves) {
         const int s = unit / UPS;
         const int sub = unit % UPS;
@@ -161,12 +167,12 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
             const int p = blockIdx.x + pp * gridDim.x;
             if (p < n_panels) {                         // (the same for the whole workgroup)
                 const uint8_t* records = data + static_cast<size_t>(where[pp]) * 16;
-                uint32_t code[HC][PAIRED ? 2 : QW], sz[HC];
+                uint32_t code[HC][(PAIRED || PAIRED8) ? 2 : QW], sz[HC];
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
                     const uint32_t h = hh[pp][c];
                     const uint32_t idx = (h >> 16) + __builtin_popcount(h & 0xFFFFu & below);
-                    if constexpr (PAIRED) {
+                    if constexpr (PAIRED || PAIRED8) {
                         const uint2 w = *reinterpret_cast<const uint2*>(records + (idx * RB + pair_load));
                         code[c][0] = w.x;
                         code[c][1] = w.y;
@@ -198,12 +204,14 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                         for (int k = 0; k < M; ++k) {
                             const half4_t a = __builtin_bit_cast(half4_t, xa[c + i][k]);
                             half4_t q;
-                            if constexpr (PAIRED) {
+                            if constexpr (PAIRED8) {
+                                q = decode4_w8(code[c + i][1], code[c + i][0], sel_codes, splice);
+                            } else if constexpr (PAIRED) {
                                 q = decode4_w4(__builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_codes), splice);
                             } else if constexpr (BITS == 4) {     // chunk k: two bytes, the lower or the upper half of a word
                                 q = decode4_w4(__builtin_amdgcn_perm(0u, code[c + i][k / 2], (k & 1) ? 0x0c030c02u : 0x0c010c00u), splice);
                             } else {
-                                q = decode4_w8(code[c + i][k], splice);
+                                q = decode4_w8(0u, code[c + i][k], 0x0c010c00u, splice);
                             }
                             d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, d[i], 0, 0, 0);      // sum_j q_j x_j
                             e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, e[i], 0, 0, 0);   // sum_j x_j
@@ -214,7 +222,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                         const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
                         if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
                             uint32_t sz_word;
-                            if constexpr (PAIRED) sz_word = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
+                            if constexpr (PAIRED || PAIRED8) sz_word = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
                             else sz_word = sz[c + i];
                             const float sc = half_bits_to_float(sz_word & 0xFFFFu);
                             const float z = half_bits_to_float(sz_word >> 16);

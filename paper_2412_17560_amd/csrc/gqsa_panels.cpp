@@ -26,6 +26,9 @@
 //               what one lane supplies to the products -- so a lane's codes are contiguous.  A quarter of a chunk is 2 bytes of
 //               4-bit codes, elements e0..e3 as (e0 | e2 << 4), (e1 | e3 << 4) (two masks split
 //               them into two fp16 pairs), or 4 bytes of 8-bit codes in element order.
+//               8-bit codes with G = 16 (4 code bytes per quarter): the scale | zero word is
+//               stored twice, record = quarter 0, scale | zero, quarter 1, quarter 2, scale | zero,
+//               quarter 3 (24 bytes), so that every lane's codes and the word are one 8-byte load.
 //               The region ends with 256 zero bytes and the image is padded to a multiple of 256
 //               bytes.
 #include <algorithm>
@@ -42,6 +45,8 @@ gqsa_status_t build_panels(gqsa_matrix* m)
     const int cb = m->code_bytes();                  // 8 .. 64
     const int64_t kg = m->K / m->G;                  // group-columns
     const int chunks = m->G / 16;
+    const bool twice = m->bits == 8 && chunks == 1;            // scale | zero stored twice (see above)
+    const int rb = cb + (twice ? 8 : 4);                       // record bytes
     const int64_t P = (m->N + kPanelRows - 1) / kPanelRows;
     const int64_t S = (kg + kSliceColumns - 1) / kSliceColumns;
     auto pad16 = [](size_t v) { return (v + 15) / 16 * 16; };
@@ -54,7 +59,7 @@ gqsa_status_t build_panels(gqsa_matrix* m)
             ++count[static_cast<size_t>((n / kPanelRows) * S + m->groups[g] / kSliceColumns)];
     std::vector<uint64_t> start(static_cast<size_t>(P * S) + 1, 0);     // bytes
     for (int64_t b = 0; b < P * S; ++b)
-        start[b + 1] = start[b] + pad16(static_cast<size_t>(count[b]) * (cb + 4));
+        start[b + 1] = start[b] + pad16(static_cast<size_t>(count[b]) * rb);
     if (start.back() / 16 > UINT32_MAX) return GQSA_ERR_SHAPE;
     const size_t header_bytes = pad256(static_cast<size_t>(P * S) * kPanelHeaderBytes);
     const size_t total = pad256(header_bytes + start.back() + 256);
@@ -86,12 +91,13 @@ gqsa_status_t build_panels(gqsa_matrix* m)
                         const int64_t g = cur[r]++;
                         mask |= 1u << r;
                         const uint8_t* v = &m->values[static_cast<size_t>(g) * cb];
-                        uint8_t* out = records + static_cast<size_t>(k) * (cb + 4);
+                        uint8_t* out = records + static_cast<size_t>(k) * rb;
                         const int qb = m->bits / 2;                 // bytes of a quarter of a chunk: 2 or 4
                         for (int t = 0; t < 4; ++t) {
                             for (int i = 0; i < chunks; ++i) {
                                 const uint8_t* src = v + static_cast<size_t>(i) * 4 * qb + static_cast<size_t>(t) * qb;
-                                uint8_t* dst = out + (static_cast<size_t>(t) * chunks + i) * qb + (t >= 2 ? 4 : 0);
+                                uint8_t* dst = twice ? out + 4 * t + (t >= 1 ? 4 : 0) + (t >= 3 ? 4 : 0)
+                                                     : out + (static_cast<size_t>(t) * chunks + i) * qb + (t >= 2 ? 4 : 0);
                                 if (m->bits == 4) {    // (e0 | e1 << 4), (e2 | e3 << 4) -> (e0 | e2 << 4), (e1 | e3 << 4)
                                     dst[0] = static_cast<uint8_t>((src[0] & 0x0F) | ((src[1] & 0x0F) << 4));
                                     dst[1] = static_cast<uint8_t>((src[0] >> 4) | (src[1] & 0xF0));
@@ -101,7 +107,12 @@ gqsa_status_t build_panels(gqsa_matrix* m)
                             }
                         }
                         const uint32_t sz = static_cast<uint32_t>(m->scales[g]) | (static_cast<uint32_t>(m->zeros[g]) << 16);
-                        std::memcpy(out + cb / 2, &sz, 4);
+                        if (twice) {
+                            std::memcpy(out + 4, &sz, 4);
+                            std::memcpy(out + 16, &sz, 4);
+                        } else {
+                            std::memcpy(out + cb / 2, &sz, 4);
+                        }
                         ++k;
                     }
                 }
