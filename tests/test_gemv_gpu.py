@@ -567,6 +567,66 @@ def test_panel_kernel_full_size(torch_cuda, bits, shape_idx):
             assert np.array_equal(yy.cpu().numpy().view(np.uint16), y.view(np.uint16))
 
 
+def test_graph_replays_match_eager(torch_cuda):
+    """The calls captured in a HIP graph (as the benchmark and a decoder would issue them) and
+    replayed several times, with eager work and synchronisation between the replays: every replay
+    gives the bits of the eager calls.  Rows shared by wavefronts and by workgroups (the fix-up
+    leaves its counters and meeting points ready for the next launch by itself), several
+    matrices per launch, and the matrix-core kernel."""
+    torch = torch_cuda
+    N, K = 257, 2048
+    W = gi.dense_weight(N, K, seed=61)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=61)
+    ha = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition(ha, 37, 3)                         # chains across workgroups
+    hb = gq.gqsa_pack_rows(W, keep, 16, 4)                    # default: rows kept inside the workgroups
+    hc = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition(hc, 5, 4)
+    hp = gq.gqsa_pack_rows(W, keep, 16, 8)
+    gq.gqsa_build_panels(hp)
+    x1 = torch.from_numpy(gi.activations(1, K, seed=62)).cuda()
+    x3 = torch.from_numpy(gi.activations(3, K, seed=63)).cuda()
+    x16 = torch.from_numpy(gi.activations(16, K, seed=64)).cuda()
+
+    def outputs():
+        return [torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((3, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((16, N), float("nan"), dtype=torch.float16, device="cuda")]
+
+    def issue(ys):
+        gq.gqsa_gemv(ha, x1, ys[0])
+        gq.gqsa_gemv(ha, x3, ys[1])
+        gq.gqsa_gemv_multi([hb, hc], x1, [ys[2], ys[3]])
+        gq.gqsa_gemv(hp, x16, ys[4])
+
+    eager = outputs()
+    issue(eager)
+    torch.cuda.synchronize()
+    want = [y.cpu().numpy().view(np.uint16).copy() for y in eager]
+    assert all(np.isfinite(y.cpu().numpy()).all() for y in eager)
+
+    ys = outputs()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        issue(ys)                                           # (uploads and first-use set-up happen outside the capture)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        issue(ys)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        for y in ys:
+            y.fill_(float("nan"))                          # eager work between the replays
+        issue(outputs())                                    # and the same kernels, eagerly, on the handles' workspaces
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for y, w in zip(ys, want):
+            assert np.array_equal(y.cpu().numpy().view(np.uint16), w), f"replay {replay}"
+
+
 def test_llama7b_qkv_and_gate_up_fused_full_size(torch_cuda):
     """The fused launches the benchmark times: q/k/v (3 x 4096x4096) and gate/up (2 x 11008x4096)."""
     torch = torch_cuda
