@@ -63,7 +63,9 @@ typedef struct {
     int64_t device_bytes;       /* size of the device image */
     int64_t algorithmic_bytes;  /* compressed bytes one batch-1 call must move (see README of bench) */
     int32_t on_device;          /* 1 once the device image exists */
-    int32_t reserved;
+    int32_t panel_integer_zeros;/* 1 if the second image exists and every stored zero is an integer of magnitude
+                                   <= 1024: its kernel then subtracts the zero from the codes (exactly, in fp16)
+                                   before the product instead of from the product's sum afterwards */
     int64_t panel_bytes;        /* size of the second image built by gqsa_build_panels, 0 without one */
 } gqsa_info_t;
 

@@ -23,7 +23,7 @@ class _Info(C.Structure):
                 ("n_workgroups", C.c_int32), ("waves_per_workgroup", C.c_int32),
                 ("needs_fixup", C.c_int32), ("span_tiles", C.c_int32), ("n_empty_rows", C.c_int64),
                 ("device_bytes", C.c_int64), ("algorithmic_bytes", C.c_int64),
-                ("on_device", C.c_int32), ("reserved", C.c_int32), ("panel_bytes", C.c_int64)]
+                ("on_device", C.c_int32), ("panel_integer_zeros", C.c_int32), ("panel_bytes", C.c_int64)]
 
 
 def library_path() -> str:

@@ -241,6 +241,7 @@ gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)
     out->algorithmic_bytes = h->nnzg() * (h->code_bytes() + 6) + (h->N + 1) * 4 + (h->K + h->N) * 2;
     out->on_device = h->d_image ? 1 : 0;
     out->panel_bytes = static_cast<int64_t>(h->panel_image.size());
+    out->panel_integer_zeros = (!h->panel_image.empty() && h->panel_integer_zeros) ? 1 : 0;
     return GQSA_OK;
 }
 

@@ -68,6 +68,7 @@ struct gqsa_matrix {
     std::vector<uint8_t> panel_image;
     size_t panel_blocks_offset = 0;   // where the data region starts in it (after the headers)
     int64_t n_panels = 0, n_slices = 0;
+    bool panel_integer_zeros = false; // every zero an integer of magnitude <= 1024: the kernel may take it off the codes
     // device side
     int device = -1;
     void* d_panels = nullptr;

@@ -23,7 +23,9 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kPanelsPerWorkgroup = 4;   // panels a workgroup takes at most (each needs its own sums)
 constexpr int kInFlight = 4;          // group-columns whose products are under way together
-constexpr int kPanelWaves = 16;      // wavefronts of a workgroup: each takes every 16th half-slice of the panel
+constexpr int kPanelWaves = 16;      // wavefronts of a workgroup: each takes every 16th unit (a run of group-columns) of the panel
+constexpr int kWaveLds = 9216;        // bytes of LDS a wavefront stages records in (16 x 9 KB = 144 of the 160 KB)
+constexpr int kMaxUnitBytes = 3072;   // records of one panel in one unit, at most (16 rows x the unit's columns)
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h)
 {
@@ -35,39 +37,50 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
     return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));     // round to nearest even
 }
 
-// Four codes -> four fp16 integers, exactly: 0x6400 | q is the fp16 number 1024 + q (q < 1024).
-// `splice` = 0x64006400 in a register (an AND-OR takes one literal, and the nibble mask is it).
-// 4-bit: `pair` holds the two bytes (e0 | e2 << 4), (e1 | e3 << 4) in bits 0..7 and 16..23.
-__device__ __forceinline__ half4_t decode4_w4(uint32_t pair, uint32_t splice)
+// Four codes -> four fp16 numbers, exactly: 0x6400 | q is the fp16 number 1024 + q (q < 1024), and
+// 0x6400 | q << 4 is 1024 + 16 q, which one fused multiply-add turns into q (x 1/16, - 64: both
+// steps exact).  `splice` = 0x64006400.  What is subtracted comes from the caller: 1024 and 64
+// for the plain codes, 1024 + z and 64 + z for codes minus zero (exact for an integer z of at most
+// 1024 in magnitude: every intermediate and the result are integers below 2048).
+// 4-bit: `pair` holds the two bytes (e0 | e2 << 4), (e1 | e3 << 4) in bits 0..7 and 16..23;
+// `nib` = 0x000F000F and `nib << 4`, kept in vector registers so that AND and OR are one instruction.
+struct DecodeConstants {
+    uint32_t splice, nib_lo, nib_hi;
+    half2_t sixteenth;
+};
+__device__ __forceinline__ half4_t decode4_w4(uint32_t pair, const DecodeConstants& k, half2_t off_lo, half2_t off_hi)
 {
-    const uint32_t lo = (pair & 0x000F000Fu) | splice;            // e0, e1
-    const uint32_t hi = ((pair >> 4) & 0x000F000Fu) | splice;     // e2, e3
-    const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
-    const half2_t a = __builtin_bit_cast(half2_t, lo) - bias;
-    const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
+    const uint32_t lo = (pair & k.nib_lo) | k.splice;            // 1024 + e0, 1024 + e1
+    const uint32_t hi = (pair & k.nib_hi) | k.splice;            // 1024 + 16 e2, 1024 + 16 e3
+    const half2_t a = __builtin_bit_cast(half2_t, lo) - off_lo;
+    const half2_t b = __builtin_elementwise_fma(__builtin_bit_cast(half2_t, hi), k.sixteenth, -off_hi);
     return half4_t{a.x, a.y, b.x, b.y};
 }
 // 8-bit: four bytes, one per element, in the word of the pair (upper, lower) that `sel` names:
 // sel = 0x0c010c00 for the lower word, 0x0c050c04 for the upper one.
-__device__ __forceinline__ half4_t decode4_w8(uint32_t upper, uint32_t lower, uint32_t sel, uint32_t splice)
+__device__ __forceinline__ half4_t decode4_w8(uint32_t upper, uint32_t lower, uint32_t sel, const DecodeConstants& k, half2_t off_lo)
 {
-    const uint32_t lo = __builtin_amdgcn_perm(upper, lower, sel) | splice;                  // bytes 0, 1
-    const uint32_t hi = __builtin_amdgcn_perm(upper, lower, sel + 0x00020002u) | splice;    // bytes 2, 3
-    const half2_t bias = {(_Float16)1024.0f, (_Float16)1024.0f};
-    const half2_t a = __builtin_bit_cast(half2_t, lo) - bias;
-    const half2_t b = __builtin_bit_cast(half2_t, hi) - bias;
+    const uint32_t lo = __builtin_amdgcn_perm(upper, lower, sel) | k.splice;                  // bytes 0, 1
+    const uint32_t hi = __builtin_amdgcn_perm(upper, lower, sel + 0x00020002u) | k.splice;    // bytes 2, 3
+    const half2_t a = __builtin_bit_cast(half2_t, lo) - off_lo;
+    const half2_t b = __builtin_bit_cast(half2_t, hi) - off_lo;
     return half4_t{a.x, a.y, b.x, b.y};
 }
 
 // A workgroup takes up to four panels of 16 output rows (blockIdx.x, + gridDim.x, ...); wavefront
-// w takes the half-slices w, w + 16, ... (16 group-columns each) of every one of them, so the
-// activations under a half-slice are loaded once for all of the workgroup's panels.  A block's
-// header is the same for all lanes and is read with scalar loads; which group is a lane's (its
-// row's, in the column at hand) follows from the header with a masked population count.  Nothing is loaded
-// conditionally: a lane whose row has no group in a column reads a neighbouring group (the image
-// ends with spare bytes), and what it computes from it stays in its own column of the product,
-// which it then leaves out.  Likewise the activation rows beyond `batch` are copies of the last
-// one: they only reach result rows that are never stored.
+// w takes the units w, w + 16, ... (a unit = a run of group-columns, half a slice or less) of
+// every one of them, so the activations under a unit are loaded once for all of the workgroup's
+// panels.  A block's header is the same for all lanes and is read with scalar loads.  The records
+// of a panel in a unit are contiguous in the image; the wavefront copies them from global memory
+// straight into its own part of LDS, 1 KiB per instruction with nothing passing through
+// registers (all of its panels at once when they fit, else two and two), and every lane then
+// reads its group's codes, scale and zero from there: which group is a lane's (its row's, in the
+// column at hand) follows from the header with a masked population count.  Fetching 8 bytes per
+// lane from global memory instead kept 1.5 KB per wavefront under way where this keeps 6 KB.
+// No lane reads conditionally: one whose row has no group in a column reads a neighbouring
+// record (or the bytes behind the last one), and what it computes from it stays in its own
+// column of the product, which it then leaves out.  Likewise the activation rows beyond `batch`
+// are copies of the last one: they only reach result rows that are never stored.
 // Operands of v_mfma_f32_16x16x16_f16 in a wavefront: lane l holds A[l % 16][4 (l / 16) .. + 3],
 // B[4 (l / 16) .. + 3][l % 16] and receives D[4 (l / 16) .. + 3][l % 16].  Here A = the
 // activations (row = activation row, 16 elements of one group-column), B = the codes (column =
@@ -76,8 +89,13 @@ __device__ __forceinline__ half4_t decode4_w8(uint32_t upper, uint32_t lower, ui
 // ones those sums need.
 // M = 16-element chunks per group (G = 16 M): a group-column then takes M products, chained
 // through the accumulator input since they share scale and zero, and a wavefront's unit of work
-// is 16 / M group-columns (a slice of 32 has 2 M of them).
-template <int BITS, int M>
+// is 16 / M group-columns with 4-bit codes, 8 / M with 8-bit codes (so that 16 rows x the unit's
+// columns are at most 3 KiB of records).
+// INTZ: every zero of the matrix is an integer of at most 1024 in magnitude (what Eq. 1 produces,
+// short of extreme groups): the zero is then taken off the codes before the product, exactly, so
+// sum_j (q_j - z) x_j comes out of one product and only the scale is left to apply; otherwise the
+// zero is an arbitrary fp16 number and multiplies the second product's sum of activations.
+template <int BITS, int M, bool INTZ>
 __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const uint16_t* __restrict__ x, const uint8_t* __restrict__ headers, const uint8_t* __restrict__ data,
     uint16_t* __restrict__ y, int N, int K, int n_slices, int batch, int n_panels)
@@ -88,17 +106,24 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     constexpr int QB = (BITS / 2) * M;              // code bytes of a lane (one quarter of every chunk)
     constexpr int QW = (QB + 3) / 4;                // ... in registers
     constexpr bool PAIRED = QB == 2;                // 4-bit, G = 16: codes and scale, zero in one 8-byte load
-    __shared__ float part[kPanelWaves * 4 * kLanes];
+    __shared__ __attribute__((aligned(16))) uint8_t staged[kPanelWaves * kWaveLds];
+    float* part = reinterpret_cast<float*>(staged);            // the same memory once the products are done
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wl = __builtin_amdgcn_readfirstlane(tid >> 6);
+    uint8_t* mine = staged + wl * kWaveLds;                     // this wavefront's staging area
     const int r = lane & 15;                        // activation row (A), output row of the panel (B, D)
     const int j = lane >> 4;                        // which four of a group's 16 elements
     const uint32_t below = (1u << r) - 1u;
     const uint16_t* xrow = x + static_cast<size_t>(r < batch ? r : batch - 1) * K + 8 * (j & 1);
     const int last_chunk = (K >> 4) - 1;
-    uint32_t splice;
-    asm volatile("s_mov_b32 %0, 0x64006400" : "=s"(splice));     // (kept out of the compiler's sight as a constant)
+    DecodeConstants dk;       // (kept out of the compiler's sight as constants: it would split the AND-OR)
+    asm volatile("s_mov_b32 %0, 0x64006400" : "=s"(dk.splice));
+    asm volatile("v_mov_b32 %0, 0x000F000F" : "=v"(dk.nib_lo));
+    asm volatile("v_mov_b32 %0, 0x00F000F0" : "=v"(dk.nib_hi));
+    dk.sixteenth = half2_t{(_Float16)0.0625f, (_Float16)0.0625f};
+    const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+    const half2_t k64 = {(_Float16)64.0f, (_Float16)64.0f};
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     const half4_t ones = {(_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f};
 
@@ -108,9 +133,12 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[pp][v] = 0.0f;
-    constexpr int HC = 16 / M;                      // group-columns of a unit
+    constexpr int HC = (BITS == 4 ? 16 : 8) / M;    // group-columns of a unit: 16 rows x HC columns x RB bytes <= kMaxUnitBytes
+    static_assert(HC >= 1 && kPanelRows * HC * RB <= kMaxUnitBytes, "a unit's records must fit their staging area");
+    constexpr int XCH = HC * M;                     // 16-element chunks of activations under a unit
     constexpr int UPS = kSliceColumns / HC;         // units per slice
-    constexpr int FLY = HC < kInFlight ? HC : kInFlight;
+    constexpr int kFly = (INTZ || M > 1) ? kInFlight : 2;      // (two sums per column without INTZ: registers)
+    constexpr int FLY = HC < kFly ? HC : kFly;
     // a lane supplies elements 0-3, 8-11, 4-7, 12-15 of every chunk for j = 0..3: quarters 0, 2, 1, 3
     const uint32_t quarter = 2u * (j & 1) + (j >> 1);
     const uint32_t code_lane = quarter * QB + (quarter >= 2 ? 4u : 0u);     // where its codes start in a record
@@ -129,7 +157,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
         const int s = unit / UPS;
         const int sub = unit % UPS;
         const int col0 = s * kSliceColumns + sub * HC;
-        // The activations under these columns (16 chunks of 16), once for all panels of the
+        // The activations under these columns (XCH chunks of 16), once for all panels of the
         // workgroup, with 16-byte loads: of two neighbouring chunks the lanes 0..31 load the first
         // (elements 0-7 and 8-15 of it), the lanes 32..63 the second, and a swap between the two
         // halves of the wavefront hands every lane the four elements it supplies to a product:
@@ -141,7 +169,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
             const int chunk0 = col0 * M;
             uint2* flat = &xa[0][0];
 #pragma unroll
-            for (int pr = 0; pr < 8; ++pr) {
+            for (int pr = 0; pr < XCH / 2; ++pr) {
                 const int g = chunk0 + 2 * pr + (j >> 1);
                 const uint4 w = *reinterpret_cast<const uint4*>(xrow + 16 * (g < last_chunk ? g : last_chunk));
                 const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
@@ -162,31 +190,65 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
             for (int c = 0; c < HC; ++c) hh[pp][c] = header[sub * HC + c];
             where[pp] = header[32];
         }
+        // Where each panel's records of this unit lie (they are contiguous: first group of the
+        // first column .. last group of the last column) and where they go in the wavefront's
+        // staging area: one after the other, each rounded up to 16 bytes plus room for one more
+        // record (a lane without a group may read the one behind the last).  All four panels are
+        // staged at once when they fit, else two and two.
+        constexpr uint32_t kSpare = (RB + 15u) & ~15u;
+        static_assert(2 * (kMaxUnitBytes + kSpare) <= kWaveLds, "two panels' worth must fit a wavefront's staging area");
+        uint32_t first[kPanelsPerWorkgroup], bytes[kPanelsPerWorkgroup], room[kPanelsPerWorkgroup], slot[kPanelsPerWorkgroup];
 #pragma unroll
         for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
+            const uint32_t last = hh[pp][HC - 1];
+            first[pp] = hh[pp][0] >> 16;
+            bytes[pp] = ((last >> 16) + __builtin_popcount(last & 0xFFFFu) - first[pp]) * RB;     // <= kMaxUnitBytes
+            room[pp] = ((bytes[pp] + 15u) & ~15u) + kSpare;
+        }
+        const bool two_and_two = room[0] + room[1] + room[2] + room[3] > static_cast<uint32_t>(kWaveLds);
+        slot[0] = 0;
+        slot[1] = room[0];
+        slot[2] = two_and_two ? 0 : room[0] + room[1];
+        slot[3] = slot[2] + room[2];
+#pragma unroll
+        for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
+            if (pp == 0 || (pp == 2 && two_and_two)) {
+                // stage: every lane copies 16 bytes per KiB of a panel's records, global memory ->
+                // LDS directly (lane l's bytes land at the given LDS address + 16 l), no registers
+#pragma unroll
+                for (int q = pp; q < kPanelsPerWorkgroup; ++q) {
+                    const int p = blockIdx.x + q * gridDim.x;
+                    if (p < n_panels && (q < pp + 2 || !two_and_two)) {
+                        const uint8_t* src = data + static_cast<size_t>(where[q]) * 16 + first[q] * RB;
+#pragma unroll
+                        for (int i = 0; i < kMaxUnitBytes / 1024; ++i) {
+                            const uint32_t o = 16u * lane + 1024u * i;
+                            if (o < bytes[q])
+                                __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(src + o),
+                                                                 (__attribute__((address_space(3))) void*)(mine + slot[q] + 1024u * i),
+                                                                 16, 0, 0);
+                        }
+                    }
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
             const int p = blockIdx.x + pp * gridDim.x;
             if (p < n_panels) {                         // (the same for the whole workgroup)
-                const uint8_t* records = data + static_cast<size_t>(where[pp]) * 16;
+                const uint8_t* records = mine + slot[pp];           // in LDS
+                const uint32_t before0 = first[pp];
                 uint32_t code[HC][(PAIRED || PAIRED8) ? 2 : QW], sz[HC];
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
                     const uint32_t h = hh[pp][c];
-                    const uint32_t idx = (h >> 16) + __builtin_popcount(h & 0xFFFFu & below);
+                    const uint32_t idx = ((h >> 16) - before0) + __builtin_popcount(h & 0xFFFFu & below);
                     if constexpr (PAIRED || PAIRED8) {
-                        const uint2 w = *reinterpret_cast<const uint2*>(records + (idx * RB + pair_load));
-                        code[c][0] = w.x;
-                        code[c][1] = w.y;
+                        const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + pair_load));
+                        code[c][0] = w[0];
+                        code[c][1] = w[1];
                     } else {
-                        const uint8_t* mine = records + (idx * RB + code_lane);
-                        if constexpr (QW == 1) {
-                            code[c][0] = *reinterpret_cast<const uint32_t*>(mine);
-                        } else if constexpr (QW == 2) {
-                            const uint2 w = *reinterpret_cast<const uint2*>(mine);
-                            code[c][0] = w.x; code[c][1] = w.y;
-                        } else {
-                            const uint4 w = *reinterpret_cast<const uint4*>(mine);
-                            code[c][0] = w.x; code[c][1] = w.y; code[c][2] = w.z; code[c][3] = w.w;
-                        }
+                        const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + code_lane));
+#pragma unroll
+                        for (int t = 0; t < QW; ++t) code[c][t] = w[t];
                         sz[c] = *reinterpret_cast<const uint32_t*>(records + (idx * RB + CB / 2));
                     }
                 }
@@ -196,8 +258,18 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
 #pragma unroll
                 for (int c = 0; c < HC; c += FLY) {
                     float4_t d[FLY], e[FLY];
+                    uint32_t sz_word[FLY];
 #pragma unroll
                     for (int i = 0; i < FLY; ++i) {
+                        if constexpr (PAIRED || PAIRED8) sz_word[i] = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
+                        else sz_word[i] = sz[c + i];
+                        half2_t off_lo = k1024, off_hi = k64;
+                        if constexpr (INTZ) {
+                            const half2_t both = __builtin_bit_cast(half2_t, sz_word[i]);
+                            const half2_t zz = {both.y, both.y};
+                            off_lo = k1024 + zz;
+                            off_hi = k64 + zz;
+                        }
                         d[i] = zero4;
                         e[i] = zero4;
 #pragma unroll
@@ -205,30 +277,32 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                             const half4_t a = __builtin_bit_cast(half4_t, xa[c + i][k]);
                             half4_t q;
                             if constexpr (PAIRED8) {
-                                q = decode4_w8(code[c + i][1], code[c + i][0], sel_codes, splice);
+                                q = decode4_w8(code[c + i][1], code[c + i][0], sel_codes, dk, off_lo);
                             } else if constexpr (PAIRED) {
-                                q = decode4_w4(__builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_codes), splice);
+                                q = decode4_w4(__builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_codes), dk, off_lo, off_hi);
                             } else if constexpr (BITS == 4) {     // chunk k: two bytes, the lower or the upper half of a word
-                                q = decode4_w4(__builtin_amdgcn_perm(0u, code[c + i][k / 2], (k & 1) ? 0x0c030c02u : 0x0c010c00u), splice);
+                                q = decode4_w4(__builtin_amdgcn_perm(0u, code[c + i][k / 2], (k & 1) ? 0x0c030c02u : 0x0c010c00u), dk, off_lo, off_hi);
                             } else {
-                                q = decode4_w8(0u, code[c + i][k], 0x0c010c00u, splice);
+                                q = decode4_w8(0u, code[c + i][k], 0x0c010c00u, dk, off_lo);
                             }
-                            d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, d[i], 0, 0, 0);      // sum_j q_j x_j
-                            e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, e[i], 0, 0, 0);   // sum_j x_j
+                            d[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, q, d[i], 0, 0, 0);      // sum_j q_j x_j, or sum_j (q_j - z) x_j
+                            if constexpr (!INTZ) e[i] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, ones, e[i], 0, 0, 0);   // sum_j x_j
                         }
                     }
 #pragma unroll
                     for (int i = 0; i < FLY; ++i) {
                         const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
                         if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
-                            uint32_t sz_word;
-                            if constexpr (PAIRED || PAIRED8) sz_word = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
-                            else sz_word = sz[c + i];
-                            const float sc = half_bits_to_float(sz_word & 0xFFFFu);
-                            const float z = half_bits_to_float(sz_word >> 16);
+                            const float sc = half_bits_to_float(sz_word[i] & 0xFFFFu);
+                            if constexpr (INTZ) {
 #pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                acc[pp][v] = __builtin_fmaf(sc, __builtin_fmaf(-z, e[i][v], d[i][v]), acc[pp][v]);
+                                for (int v = 0; v < 4; ++v) acc[pp][v] = __builtin_fmaf(sc, d[i][v], acc[pp][v]);
+                            } else {
+                                const float z = half_bits_to_float(sz_word[i] >> 16);
+#pragma unroll
+                                for (int v = 0; v < 4; ++v)
+                                    acc[pp][v] = __builtin_fmaf(sc, __builtin_fmaf(-z, e[i][v], d[i][v]), acc[pp][v]);
+                            }
                         }
                     }
                 }
@@ -236,7 +310,9 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
         }
     }
 
-    // the wavefronts' sums meet in LDS and are added in wavefront order
+    // the wavefronts' sums meet in LDS (the staging areas, once every wavefront is done with its
+    // own) and are added in wavefront order
+    __syncthreads();
 #pragma unroll
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
         const int p = blockIdx.x + pp * gridDim.x;
@@ -305,14 +381,21 @@ gqsa_status_t panels_gemm(const gqsa_matrix* m, const void* x, void* y, int batc
                            static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
                            static_cast<int>(m->n_slices), batch, static_cast<int>(m->n_panels));
     };
-    switch (m->bits * 1000 + m->G) {
-        case 4016: launch(gqsa_panel_kernel<4, 1>); break;
-        case 4032: launch(gqsa_panel_kernel<4, 2>); break;
-        case 4064: launch(gqsa_panel_kernel<4, 4>); break;
-        case 4128: launch(gqsa_panel_kernel<4, 8>); break;
-        case 8016: launch(gqsa_panel_kernel<8, 1>); break;
-        case 8032: launch(gqsa_panel_kernel<8, 2>); break;
-        case 8064: launch(gqsa_panel_kernel<8, 4>); break;
+    switch (m->bits * 1000 + m->G + (m->panel_integer_zeros ? 500 : 0)) {
+        case 4016: launch(gqsa_panel_kernel<4, 1, false>); break;
+        case 4032: launch(gqsa_panel_kernel<4, 2, false>); break;
+        case 4064: launch(gqsa_panel_kernel<4, 4, false>); break;
+        case 4128: launch(gqsa_panel_kernel<4, 8, false>); break;
+        case 8016: launch(gqsa_panel_kernel<8, 1, false>); break;
+        case 8032: launch(gqsa_panel_kernel<8, 2, false>); break;
+        case 8064: launch(gqsa_panel_kernel<8, 4, false>); break;
+        case 4516: launch(gqsa_panel_kernel<4, 1, true>); break;
+        case 4532: launch(gqsa_panel_kernel<4, 2, true>); break;
+        case 4564: launch(gqsa_panel_kernel<4, 4, true>); break;
+        case 4628: launch(gqsa_panel_kernel<4, 8, true>); break;
+        case 8516: launch(gqsa_panel_kernel<8, 1, true>); break;
+        case 8532: launch(gqsa_panel_kernel<8, 2, true>); break;
+        case 8564: launch(gqsa_panel_kernel<8, 4, true>); break;
         default: return GQSA_ERR_UNSUPPORTED;
     }
     GQSA_HIP(hipGetLastError());

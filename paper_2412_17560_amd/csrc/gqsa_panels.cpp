@@ -32,6 +32,7 @@
 //               The region ends with 256 zero bytes and the image is padded to a multiple of 256
 //               bytes.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <new>
 
@@ -122,6 +123,13 @@ gqsa_status_t build_panels(gqsa_matrix* m)
             header[33] = k;
         }
     }
+    // may the kernel subtract the zero from the codes in fp16?  Exact only for integers up to 1024
+    bool integer_zeros = true;
+    for (const uint16_t zb : m->zeros) {
+        const float z = static_cast<float>(__builtin_bit_cast(_Float16, zb));
+        if (!(z == std::nearbyint(z) && std::fabs(z) <= 1024.0f)) { integer_zeros = false; break; }
+    }
+    m->panel_integer_zeros = integer_zeros;
     m->panel_image.swap(img);
     m->panel_blocks_offset = header_bytes;
     m->n_panels = P;

@@ -545,6 +545,48 @@ def test_panel_kernel_only_from_five_rows(torch_cuda):
     assert e.value.status == 3
 
 
+@pytest.mark.parametrize("bits,G,sparsity", [(4, 16, 0.0), (4, 16, 0.2), (8, 16, 0.0), (4, 64, 0.1), (8, 64, 0.0)])
+def test_panel_kernel_dense_panels(torch_cuda, bits, G, sparsity):
+    """Four panels per workgroup (769 panels on 256 workgroups) that are dense or nearly so: a
+    wavefront's staging area in LDS then holds two panels' records at a time, not four (and the
+    fullest records a unit can have, 16 rows x all its columns).  The last panel has 5 rows."""
+    N, K = 16 * 768 + 5, 32 * G
+    W = gi.dense_weight_chunked(N, K, seed=98)
+    c = oracle.pack(W, G, bits, sparsity=sparsity)
+    h = gq.gqsa_pack(W, G, bits, sparsity)
+    gq.gqsa_build_panels(h)
+    check(torch_cuda, h, c, gi.activations(16, K, seed=16), panels=True)
+
+
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 64), (8, 32)])
+@pytest.mark.parametrize("zeros", ["fractional", "large", "extreme_integers"])
+def test_panel_kernel_any_zero(torch_cuda, bits, G, zeros):
+    """The matrix-core kernel subtracts the zero from the codes only when every stored zero is an
+    integer of at most 1024 in magnitude (then exactly); trained zeros (Sec. 3.4) may be any fp16
+    number and take the other form of Eq. 3, s (sum q x - z sum x).  Fractional zeros, zeros
+    beyond 1024, and integer zeros at +-1024 with the codes at both ends of their range."""
+    N, K = 77, 40 * G
+    W = gi.dense_weight(N, K, seed=97)
+    c = oracle.pack(W, G, bits, sparsity=0.4)
+    rng = np.random.default_rng(3)
+    z = c.zeros.view(np.float16).astype(np.float32)
+    if zeros == "fractional":
+        z = z + rng.standard_normal(c.nnzg).astype(np.float32) * 3
+    elif zeros == "large":
+        z[::7] = 1025.0
+        z[3::11] = -2048.0
+    else:
+        z[::2] = 1024.0
+        z[1::2] = -1024.0
+        c.values[: c.values.size // 2] = 0xFF
+        c.values[c.values.size // 2:] = 0x00
+    c.zeros = z.astype(np.float16).view(np.uint16)
+    h = gq.gqsa_import(c.rowIndex, c.groups, c.values, c.scales, c.zeros, N, K, G, bits)
+    gq.gqsa_build_panels(h)
+    assert gq.gqsa_info(h)["panel_integer_zeros"] == (1 if zeros == "extreme_integers" else 0)
+    check(torch_cuda, h, c, gi.activations(16, K, seed=15), panels=True)
+
+
 @pytest.mark.parametrize("bits,shape_idx", [(4, 0), (8, 1)])
 def test_panel_kernel_full_size(torch_cuda, bits, shape_idx):
     """4096x4096 (W4) and 14336x4096 (W8) at S = 50 %, 16 activation rows; every output checked.

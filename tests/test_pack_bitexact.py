@@ -132,6 +132,29 @@ def test_panel_image(bits, G, shape):
     assert np.array_equal((last >> 16) + np.array([bin(v & 0xFFFF).count("1") for v in last]), hdr[:, 33])
 
 
+def test_panel_image_notes_whether_zeros_are_small_integers():
+    """gqsa_info tells which form of Eq. 3 the matrix-core kernel will take: zero off the codes
+    (exact in fp16 only for integer zeros up to 1024 in magnitude) or off the product's sum."""
+    N, K = 40, 512
+    c = oracle.pack(gi.dense_weight(N, K, seed=7), 16, 4, sparsity=0.5)
+
+    def flag(zeros_f16):
+        h = gq.gqsa_import(c.rowIndex, c.groups, c.values, c.scales, zeros_f16.view(np.uint16), N, K, 16, 4)
+        assert gq.gqsa_info(h)["panel_integer_zeros"] == 0          # no second image yet
+        gq.gqsa_build_panels(h)
+        return gq.gqsa_info(h)["panel_integer_zeros"]
+
+    z = c.zeros.view(np.float16).copy()
+    assert flag(z) == 1                                             # what Eq. 1 gives
+    for bad in (0.5, 1025.0, -1026.0, np.inf, np.nan, 6e-8):
+        zz = z.copy()
+        zz[c.nnzg // 2] = bad
+        assert flag(zz) == 0, bad
+    zz = z.copy()
+    zz[0], zz[1], zz[2] = 1024.0, -1024.0, -0.0
+    assert flag(zz) == 1
+
+
 def test_panel_image_is_refused_for_groups_of_eight():
     W = gi.dense_weight(8, 256, seed=3)
     h = gq.gqsa_pack(W, 8, 4, 0.5)
