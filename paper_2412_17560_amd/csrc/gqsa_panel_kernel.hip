@@ -164,19 +164,14 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
         // elements 0-3, 8-11, 4-7, 12-15 of the chunk for the lanes' j = 0..3 (which element sits in
         // which of the product's 16 slots does not matter as long as the codes follow suit).
         // The last slice may be short: chunks beyond K (no groups there) take the last one's.
+        // (The loads are issued here, ahead of everything; the swap waits until the records' loads
+        // have been issued too, so that nothing is held up by the activations' arrival.)
         uint2 xa[HC][M];
-        {
-            const int chunk0 = col0 * M;
-            uint2* flat = &xa[0][0];
+        uint4 xw[XCH / 2];
 #pragma unroll
-            for (int pr = 0; pr < XCH / 2; ++pr) {
-                const int g = chunk0 + 2 * pr + (j >> 1);
-                const uint4 w = *reinterpret_cast<const uint4*>(xrow + 16 * (g < last_chunk ? g : last_chunk));
-                const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
-                const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
-                flat[2 * pr] = uint2{s0[0], s1[0]};
-                flat[2 * pr + 1] = uint2{s0[1], s1[1]};
-            }
+        for (int pr = 0; pr < XCH / 2; ++pr) {
+            const int g = col0 * M + 2 * pr + (j >> 1);
+            xw[pr] = *reinterpret_cast<const uint4*>(xrow + 16 * (g < last_chunk ? g : last_chunk));
         }
         // the headers of all the workgroup's panels at once (scalar loads; a panel beyond the
         // last one stands in as the last one and is not computed)
@@ -228,6 +223,16 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                                                                  (__attribute__((address_space(3))) void*)(mine + slot[q] + 1024u * i),
                                                                  16, 0, 0);
                         }
+                    }
+                }
+                if (pp == 0) {
+                    uint2* flat = &xa[0][0];
+#pragma unroll
+                    for (int pr = 0; pr < XCH / 2; ++pr) {
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(xw[pr].x, xw[pr].z, false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(xw[pr].y, xw[pr].w, false, false);
+                        flat[2 * pr] = uint2{s0[0], s1[0]};
+                        flat[2 * pr + 1] = uint2{s0[1], s1[1]};
                     }
                 }
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -310,26 +315,30 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
         }
     }
 
-    // the wavefronts' sums meet in LDS (the staging areas, once every wavefront is done with its
-    // own) and are added in wavefront order
+    // The wavefronts' sums meet in LDS (the staging areas, once every wavefront is done with its
+    // own): all panels' at once, then wavefront w adds up, in wavefront order, the sixteen
+    // contributions to the activation rows 4 j + (w % 4) of panel w / 4 and stores them.
+    static_assert(kPanelWaves == 4 * kPanelsPerWorkgroup, "one wavefront per (panel, accumulator register) below");
+    static_assert(kPanelsPerWorkgroup * kPanelWaves * 4 * kLanes * sizeof(float) <= sizeof(staged), "the sums must fit the staging areas");
     __syncthreads();
 #pragma unroll
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
-        const int p = blockIdx.x + pp * gridDim.x;
-        if (p >= n_panels) break;                       // (the same for the whole workgroup)
+        if (static_cast<int>(blockIdx.x + pp * gridDim.x) >= n_panels) break;      // (the same for the whole workgroup)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) part[(wl * 4 + v) * kLanes + lane] = acc[pp][v];
-        __syncthreads();
-        if (tid < 4 * kLanes) {
-            const int v = tid >> 6;
+        for (int v = 0; v < 4; ++v) part[((pp * 4 + v) * kPanelWaves + wl) * kLanes + lane] = acc[pp][v];
+    }
+    __syncthreads();
+    {
+        const int pp = wl >> 2, v = wl & 3;
+        const int p = blockIdx.x + pp * gridDim.x;
+        if (p < n_panels) {
             float sum = 0.0f;
 #pragma unroll
-            for (int w = 0; w < kPanelWaves; ++w) sum += part[(w * 4 + v) * kLanes + lane];
+            for (int w = 0; w < kPanelWaves; ++w) sum += part[((pp * 4 + v) * kPanelWaves + w) * kLanes + lane];
             const int b = 4 * j + v;                    // activation row
             const int row = p * kPanelRows + r;         // output row
             if (b < batch && row < N) y[static_cast<size_t>(b) * N + row] = float_to_half_bits(sum);
         }
-        __syncthreads();                                // before the next panel's sums
     }
 }
 
