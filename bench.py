@@ -423,6 +423,22 @@ def main():
                 yb = torch.empty((B, 4096), dtype=torch.float16, device=dev)
                 us = time_calls(lambda k, xb=xb, yb=yb: gq.gqsa_gemv(hp[k % len(hp)], xb, yb, panels=True), n=96)
                 row["us_cold_panels"] = round(us, 3)
+        # q/k/v at 8 and 16 rows: three matrices on the same activations in one launch of the
+        # matrix-core kernel (a workgroup's panels come from all three and share the activations
+        # it loads) against three launches
+        qkv = []
+        trios = [hp[i:i + 3] for i in range(0, len(hp) - 2, 3)]
+        for B in (8, 16):
+            xb = torch.from_numpy(gi.activations(B, 4096, seed=gi.config_seed(5, 0))).to(dev)
+            ybs = [torch.empty((B, 4096), dtype=torch.float16, device=dev) for _ in range(3)]
+            one = time_calls(lambda k, xb=xb, ybs=ybs: gq.gqsa_gemv_multi(trios[k % len(trios)], xb, ybs), n=48)
+
+            def three(k, xb=xb, ybs=ybs):
+                for h, yb in zip(trios[k % len(trios)], ybs):
+                    gq.gqsa_gemv(h, xb, yb, panels=True)
+            qkv.append({"batch": B, "us_one_launch": round(one, 3), "us_three_launches": round(time_calls(three, n=48), 3),
+                        "distinct_sets": len(trios)})
+        out["small_batch_qkv_3x4096x4096_panels"] = qkv
         for h in hp:
             gq.gqsa_free(h)
         out["small_batch_4096x4096"] = small_batch

@@ -172,7 +172,7 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
     if (!h->d_image) {
         if (gqsa_status_t st = upload(h)) return st;
     }
-    if (h->d_panels && batch >= panel_min_batch(h)) return gqsa::panels_gemm(h, x_dev, y_dev, batch, hip_stream);
+    if (h->d_panels && batch >= panel_min_batch(h)) return gqsa::panels_gemm(&h, 1, x_dev, &y_dev, batch, hip_stream);
     return gqsa::device_gemv(&h, 1, x_dev, &y_dev, batch, hip_stream);
 }
 
@@ -186,7 +186,7 @@ gqsa_status_t gqsa_gemv_panels(gqsa_handle_t h, const void* x_dev, void* y_dev, 
     if (!h->d_image) {
         if (gqsa_status_t st = upload(h)) return st;
     }
-    return gqsa::panels_gemm(h, x_dev, y_dev, batch, hip_stream);
+    return gqsa::panels_gemm(&h, 1, x_dev, &y_dev, batch, hip_stream);
 }
 
 gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, const void* x_dev,
@@ -213,9 +213,22 @@ gqsa_status_t gqsa_gemv_multi(const gqsa_handle_t* handles, int n_matrices, cons
         }
         if (!handles[i]->d_panels) panels = false;
     }
-    if (panels) {      // one launch per matrix: at these sizes the products, not the launches, take the time
+    if (panels) {
+        // One launch when the matrices can share a kernel variant (the zero is handled the same
+        // way in all of them): a workgroup's panels then come from different matrices and the
+        // activations, most of what a compute unit reads, are loaded once for all of them.
+        // (Not beyond four panels per compute unit's workgroup: a second round of workgroups
+        // would leave most compute units idle.)
+        bool alike = true;
+        int64_t panels_in_all = 0;
+        for (int i = 0; i < n_matrices; ++i) {
+            if (handles[i]->panel_integer_zeros != handles[0]->panel_integer_zeros) alike = false;
+            panels_in_all += handles[i]->n_panels;
+        }
+        if (alike && n_matrices > 1 && panels_in_all <= 4 * gqsa::kMaxDefaultWorkgroups)
+            return gqsa::panels_gemm(handles, n_matrices, x_dev, y_devs, batch, hip_stream);
         for (int i = 0; i < n_matrices; ++i)
-            if (gqsa_status_t st = gqsa::panels_gemm(handles[i], x_dev, y_devs[i], batch, hip_stream)) return st;
+            if (gqsa_status_t st = gqsa::panels_gemm(&handles[i], 1, x_dev, &y_devs[i], batch, hip_stream)) return st;
         return GQSA_OK;
     }
     return gqsa::device_gemv(handles, n_matrices, x_dev, y_devs, batch, hip_stream);

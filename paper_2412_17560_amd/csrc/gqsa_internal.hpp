@@ -94,7 +94,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
 gqsa_status_t build_panels(gqsa_matrix* m);
 gqsa_status_t panels_upload(gqsa_matrix* m);
 void panels_release(gqsa_matrix* m);
-gqsa_status_t panels_gemm(const gqsa_matrix* m, const void* x, void* y, int batch, void* stream);
+gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, void* const* ys, int batch, void* stream);
 
 // device side (gqsa_gemv.hip)
 gqsa_status_t device_upload(gqsa_matrix* m);

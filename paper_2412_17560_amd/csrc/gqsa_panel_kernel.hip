@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstdio>
+#include <type_traits>
 
 #include "gqsa_internal.hpp"
 
@@ -67,6 +68,19 @@ __device__ __forceinline__ half4_t decode4_w8(uint32_t upper, uint32_t lower, ui
     return half4_t{a.x, a.y, b.x, b.y};
 }
 
+// The matrices of a launch: up to four that are multiplied with the same activations (q/k/v,
+// gate/up: same K, group size and code width; N may differ).  Their panels are numbered through,
+// matrix after matrix, so the panels of a workgroup (blockIdx.x, + gridDim.x, ...) may belong to
+// different matrices and still share the activations they load.
+// (The images themselves come as separate read-only kernel arguments: the compiler reads a
+// block's header with scalar loads only from memory it knows nothing writes to.)
+struct PanelTargets {
+    uint16_t* y[kMaxMatricesPerLaunch];
+    int N[kMaxMatricesPerLaunch];
+    int first[kMaxMatricesPerLaunch];       // panels of the matrices before this one (entries past the last matrix: `total`)
+    int total;                  // panels of all matrices
+};
+
 // A workgroup takes up to four panels of 16 output rows (blockIdx.x, + gridDim.x, ...); wavefront
 // w takes the units w, w + 16, ... (a unit = a run of group-columns, half a slice or less) of
 // every one of them, so the activations under a unit are loaded once for all of the workgroup's
@@ -95,10 +109,16 @@ __device__ __forceinline__ half4_t decode4_w8(uint32_t upper, uint32_t lower, ui
 // short of extreme groups): the zero is then taken off the codes before the product, exactly, so
 // sum_j (q_j - z) x_j comes out of one product and only the scale is left to apply; otherwise the
 // zero is an arbitrary fp16 number and multiplies the second product's sum of activations.
-template <int BITS, int M, bool INTZ>
+// MULTI: more than one matrix in the launch (the lookups of a panel's matrix cost scalar
+// registers, which the headers of four panels already fill: one matrix keeps its own code).
+template <int BITS, int M, bool INTZ, bool MULTI>
 __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
-    const uint16_t* __restrict__ x, const uint8_t* __restrict__ headers, const uint8_t* __restrict__ data,
-    uint16_t* __restrict__ y, int N, int K, int n_slices, int batch, int n_panels)
+    const uint16_t* __restrict__ x,
+    const uint8_t* __restrict__ headers0, const uint8_t* __restrict__ headers1,
+    const uint8_t* __restrict__ headers2, const uint8_t* __restrict__ headers3,
+    const uint8_t* __restrict__ data0, const uint8_t* __restrict__ data1,
+    const uint8_t* __restrict__ data2, const uint8_t* __restrict__ data3,
+    const PanelTargets src, int K, int n_slices, int batch)
 {
     constexpr int CB = 2 * BITS * M;                // code bytes per group
     constexpr bool PAIRED8 = BITS == 8 && M == 1;   // 8-bit, G = 16: quarter 0, word, quarter 1, quarter 2, word, quarter 3
@@ -127,7 +147,28 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const float4_t zero4 = {0.0f, 0.0f, 0.0f, 0.0f};
     const half4_t ones = {(_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f, (_Float16)1.0f};
 
-    // the workgroup's panels: blockIdx.x, blockIdx.x + gridDim.x, ... (at most kPanelsPerWorkgroup)
+    // the workgroup's panels: blockIdx.x, blockIdx.x + gridDim.x, ... (at most kPanelsPerWorkgroup),
+    // each in its matrix; one past the last stands in as the last and is not computed
+    const auto locate = [&](int pp, int& m, int& p) {
+        const int v = static_cast<int>(blockIdx.x + pp * gridDim.x);
+        const bool is_live = v < src.total;
+        const int vc = is_live ? v : src.total - 1;
+        if constexpr (MULTI) {
+            // (selects among values at fixed places of the argument block: no load depends on another)
+            static_assert(kMaxMatricesPerLaunch == 4, "written out for four matrices");
+            const int f1 = src.first[1], f2 = src.first[2], f3 = src.first[3];
+            m = (vc >= f1 ? 1 : 0) + (vc >= f2 ? 1 : 0) + (vc >= f3 ? 1 : 0);
+            p = vc - (m == 0 ? 0 : m == 1 ? f1 : m == 2 ? f2 : f3);
+        } else {
+            m = 0;
+            p = vc;
+        }
+        return is_live;
+    };
+    int mat[kPanelsPerWorkgroup], pan[kPanelsPerWorkgroup];
+    bool live[kPanelsPerWorkgroup];
+#pragma unroll
+    for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) live[pp] = locate(pp, mat[pp], pan[pp]);
     float acc[kPanelsPerWorkgroup][4];
 #pragma unroll
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp)
@@ -178,9 +219,11 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
         uint32_t hh[kPanelsPerWorkgroup][HC], where[kPanelsPerWorkgroup];
 #pragma unroll
         for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
-            const int p = blockIdx.x + pp * gridDim.x;
+            // (the choice is made here, at the load: a header is read with scalar loads only if the
+            // compiler can trace its address to a read-only argument)
+            const uint8_t* headers = !MULTI || mat[pp] == 0 ? headers0 : mat[pp] == 1 ? headers1 : mat[pp] == 2 ? headers2 : headers3;
             const uint32_t* header = reinterpret_cast<const uint32_t*>(
-                headers + static_cast<size_t>((p < n_panels ? p : n_panels - 1) * n_slices + s) * kPanelHeaderBytes);
+                headers + static_cast<size_t>(pan[pp] * n_slices + s) * kPanelHeaderBytes);
 #pragma unroll
             for (int c = 0; c < HC; ++c) hh[pp][c] = header[sub * HC + c];
             where[pp] = header[32];
@@ -212,14 +255,14 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                 // LDS directly (lane l's bytes land at the given LDS address + 16 l), no registers
 #pragma unroll
                 for (int q = pp; q < kPanelsPerWorkgroup; ++q) {
-                    const int p = blockIdx.x + q * gridDim.x;
-                    if (p < n_panels && (q < pp + 2 || !two_and_two)) {
-                        const uint8_t* src = data + static_cast<size_t>(where[q]) * 16 + first[q] * RB;
+                    if (live[q] && (q < pp + 2 || !two_and_two)) {
+                        const uint8_t* data = !MULTI || mat[q] == 0 ? data0 : mat[q] == 1 ? data1 : mat[q] == 2 ? data2 : data3;
+                        const uint8_t* from = data + static_cast<size_t>(where[q]) * 16 + first[q] * RB;
 #pragma unroll
                         for (int i = 0; i < kMaxUnitBytes / 1024; ++i) {
                             const uint32_t o = 16u * lane + 1024u * i;
                             if (o < bytes[q])
-                                __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(src + o),
+                                __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(from + o),
                                                                  (__attribute__((address_space(3))) void*)(mine + slot[q] + 1024u * i),
                                                                  16, 0, 0);
                         }
@@ -235,10 +278,9 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                         flat[2 * pr + 1] = uint2{s0[1], s1[1]};
                     }
                 }
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the records are in LDS before any lane reads them
             }
-            const int p = blockIdx.x + pp * gridDim.x;
-            if (p < n_panels) {                         // (the same for the whole workgroup)
+            if (live[pp]) {                             // (the same for the whole workgroup)
                 const uint8_t* records = mine + slot[pp];           // in LDS
                 const uint32_t before0 = first[pp];
                 uint32_t code[HC][(PAIRED || PAIRED8) ? 2 : QW], sz[HC];
@@ -323,21 +365,23 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     __syncthreads();
 #pragma unroll
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
-        if (static_cast<int>(blockIdx.x + pp * gridDim.x) >= n_panels) break;      // (the same for the whole workgroup)
+        if (!live[pp]) break;                           // (the same for the whole workgroup)
 #pragma unroll
         for (int v = 0; v < 4; ++v) part[((pp * 4 + v) * kPanelWaves + wl) * kLanes + lane] = acc[pp][v];
     }
     __syncthreads();
     {
         const int pp = wl >> 2, v = wl & 3;
-        const int p = blockIdx.x + pp * gridDim.x;
-        if (p < n_panels) {
+        int m, p;
+        if (locate(pp, m, p)) {
             float sum = 0.0f;
 #pragma unroll
             for (int w = 0; w < kPanelWaves; ++w) sum += part[((pp * 4 + v) * kPanelWaves + w) * kLanes + lane];
             const int b = 4 * j + v;                    // activation row
             const int row = p * kPanelRows + r;         // output row
-            if (b < batch && row < N) y[static_cast<size_t>(b) * N + row] = float_to_half_bits(sum);
+            const int n = !MULTI || m == 0 ? src.N[0] : m == 1 ? src.N[1] : m == 2 ? src.N[2] : src.N[3];
+            uint16_t* y = !MULTI || m == 0 ? src.y[0] : m == 1 ? src.y[1] : m == 2 ? src.y[2] : src.y[3];
+            if (b < batch && row < n) y[static_cast<size_t>(b) * n + row] = float_to_half_bits(sum);
         }
     }
 }
@@ -374,39 +418,70 @@ void panels_release(gqsa_matrix* m)
     m->d_panels = nullptr;
 }
 
-// Up to 16 activation rows in one launch.  x [batch, K], y [batch, N], fp16, on the device.
-gqsa_status_t panels_gemm(const gqsa_matrix* m, const void* x, void* y, int batch, void* stream)
+// Up to 16 activation rows in one launch, for up to four matrices that share them (same K, group
+// size, code width and handling of the zero; the caller checks).  x [batch, K], ys[i] [batch, N_i],
+// fp16, on the device.
+gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, void* const* ys, int batch, void* stream)
 {
-    if (!m->d_panels || batch < 1 || batch > kPanelRows) return GQSA_ERR_UNSUPPORTED;
-    const uint8_t* img = static_cast<const uint8_t*>(m->d_panels);
-    const uint8_t* data = img + m->panel_blocks_offset;
+    if (n < 1 || n > kMaxMatricesPerLaunch || batch < 1 || batch > kPanelRows) return GQSA_ERR_UNSUPPORTED;
+    PanelTargets src{};
+    const uint8_t* headers[kMaxMatricesPerLaunch];
+    const uint8_t* data[kMaxMatricesPerLaunch];
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const gqsa_matrix* m = ms[i];
+        if (!m->d_panels) return GQSA_ERR_UNSUPPORTED;
+        if (m->K != ms[0]->K || m->G != ms[0]->G || m->bits != ms[0]->bits || m->n_slices != ms[0]->n_slices ||
+            m->panel_integer_zeros != ms[0]->panel_integer_zeros)
+            return GQSA_ERR_SHAPE;
+        const uint8_t* img = static_cast<const uint8_t*>(m->d_panels);
+        headers[i] = img;
+        data[i] = img + m->panel_blocks_offset;
+        src.y[i] = static_cast<uint16_t*>(ys[i]);
+        src.N[i] = static_cast<int>(m->N);
+        src.first[i] = static_cast<int>(total);
+        total += m->n_panels;
+    }
+    if (total > INT32_MAX) return GQSA_ERR_SHAPE;
+    for (int i = n; i < kMaxMatricesPerLaunch; ++i) {
+        src.first[i] = static_cast<int>(total);
+        headers[i] = headers[0];
+        data[i] = data[0];
+    }
+    src.total = static_cast<int>(total);
+    const gqsa_matrix* m = ms[0];
     // one workgroup per compute unit unless that gives a workgroup more than four panels
-    const int64_t wgs = std::min<int64_t>(m->n_panels, std::max<int64_t>(kMaxDefaultWorkgroups,
-                                                                         (m->n_panels + kPanelsPerWorkgroup - 1) / kPanelsPerWorkgroup));
+    const int64_t wgs = std::min<int64_t>(total, std::max<int64_t>(kMaxDefaultWorkgroups,
+                                                                   (total + kPanelsPerWorkgroup - 1) / kPanelsPerWorkgroup));
     const dim3 grid(static_cast<unsigned>(wgs)), block(kPanelWaves * kLanes);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const auto launch = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint16_t*>(x), img, data,
-                           static_cast<uint16_t*>(y), static_cast<int>(m->N), static_cast<int>(m->K),
-                           static_cast<int>(m->n_slices), batch, static_cast<int>(m->n_panels));
+        hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint16_t*>(x), headers[0], headers[1], headers[2],
+                           headers[3], data[0], data[1], data[2], data[3], src, static_cast<int>(m->K),
+                           static_cast<int>(m->n_slices), batch);
     };
-    switch (m->bits * 1000 + m->G + (m->panel_integer_zeros ? 500 : 0)) {
-        case 4016: launch(gqsa_panel_kernel<4, 1, false>); break;
-        case 4032: launch(gqsa_panel_kernel<4, 2, false>); break;
-        case 4064: launch(gqsa_panel_kernel<4, 4, false>); break;
-        case 4128: launch(gqsa_panel_kernel<4, 8, false>); break;
-        case 8016: launch(gqsa_panel_kernel<8, 1, false>); break;
-        case 8032: launch(gqsa_panel_kernel<8, 2, false>); break;
-        case 8064: launch(gqsa_panel_kernel<8, 4, false>); break;
-        case 4516: launch(gqsa_panel_kernel<4, 1, true>); break;
-        case 4532: launch(gqsa_panel_kernel<4, 2, true>); break;
-        case 4564: launch(gqsa_panel_kernel<4, 4, true>); break;
-        case 4628: launch(gqsa_panel_kernel<4, 8, true>); break;
-        case 8516: launch(gqsa_panel_kernel<8, 1, true>); break;
-        case 8532: launch(gqsa_panel_kernel<8, 2, true>); break;
-        case 8564: launch(gqsa_panel_kernel<8, 4, true>); break;
-        default: return GQSA_ERR_UNSUPPORTED;
-    }
+    const auto pick = [&](auto multi) {
+        constexpr bool kMulti = decltype(multi)::value;
+        switch (m->bits * 1000 + m->G + (m->panel_integer_zeros ? 500 : 0)) {
+            case 4016: launch(gqsa_panel_kernel<4, 1, false, kMulti>); break;
+            case 4032: launch(gqsa_panel_kernel<4, 2, false, kMulti>); break;
+            case 4064: launch(gqsa_panel_kernel<4, 4, false, kMulti>); break;
+            case 4128: launch(gqsa_panel_kernel<4, 8, false, kMulti>); break;
+            case 8016: launch(gqsa_panel_kernel<8, 1, false, kMulti>); break;
+            case 8032: launch(gqsa_panel_kernel<8, 2, false, kMulti>); break;
+            case 8064: launch(gqsa_panel_kernel<8, 4, false, kMulti>); break;
+            case 4516: launch(gqsa_panel_kernel<4, 1, true, kMulti>); break;
+            case 4532: launch(gqsa_panel_kernel<4, 2, true, kMulti>); break;
+            case 4564: launch(gqsa_panel_kernel<4, 4, true, kMulti>); break;
+            case 4628: launch(gqsa_panel_kernel<4, 8, true, kMulti>); break;
+            case 8516: launch(gqsa_panel_kernel<8, 1, true, kMulti>); break;
+            case 8532: launch(gqsa_panel_kernel<8, 2, true, kMulti>); break;
+            case 8564: launch(gqsa_panel_kernel<8, 4, true, kMulti>); break;
+            default: return false;
+        }
+        return true;
+    };
+    if (!(n > 1 ? pick(std::true_type{}) : pick(std::false_type{}))) return GQSA_ERR_UNSUPPORTED;
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;
 }

@@ -545,6 +545,41 @@ def test_panel_kernel_only_from_five_rows(torch_cuda):
     assert e.value.status == 3
 
 
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32)])
+def test_panel_kernel_several_matrices_share_a_launch(torch_cuda, bits, G):
+    """q/k/v-like: three matrices of different N (4200 rows: 263 panels, more than one per
+    workgroup; 130 and 70 rows: ragged last panels) and different sparsity on the same
+    activations, 16 and 7 rows.  One launch gives the bits of three separate calls and stays
+    within the bound against the oracle; a fourth matrix whose zeros are not integers (the other
+    form of Eq. 3) makes the call fall back to one launch per matrix, same bits again."""
+    torch = torch_cuda
+    K = 24 * G
+    shapes = [(4200, 0.5), (130, 0.3), (70, 0.0)]
+    hs, cs = [], []
+    for i, (N, sp) in enumerate(shapes):
+        W = gi.dense_weight(N, K, seed=120 + i)
+        cs.append(oracle.pack(W, G, bits, sparsity=sp))
+        h = gq.gqsa_pack(W, G, bits, sp)
+        gq.gqsa_build_panels(h)
+        hs.append(h)
+    c4 = oracle.pack(gi.dense_weight(50, K, seed=124), G, bits, sparsity=0.5)
+    c4.zeros = (c4.zeros.view(np.float16) + np.float16(0.25)).view(np.uint16)
+    h4 = gq.gqsa_import(c4.rowIndex, c4.groups, c4.values, c4.scales, c4.zeros, 50, K, G, bits)
+    gq.gqsa_build_panels(h4)
+    assert gq.gqsa_info(h4)["panel_integer_zeros"] == 0
+    for batch in (16, 7):
+        x = gi.activations(batch, K, seed=17 + batch)
+        xt = torch.from_numpy(x).cuda()
+        single = [check(torch, h, c, x, panels=True)[0] for h, c in zip(hs + [h4], cs + [c4])]
+        for group in (hs, hs + [h4], [h4] + hs[:2]):
+            ys = [torch.full((batch, gq.gqsa_info(h)["N"]), float("nan"), dtype=torch.float16, device="cuda") for h in group]
+            gq.gqsa_gemv_multi(group, xt, ys)
+            torch.cuda.synchronize()
+            for h, yy in zip(group, ys):
+                want = single[(hs + [h4]).index(h)]
+                assert np.array_equal(yy.cpu().numpy().view(np.uint16), want.view(np.uint16))
+
+
 @pytest.mark.parametrize("bits,G,sparsity", [(4, 16, 0.0), (4, 16, 0.2), (8, 16, 0.0), (4, 64, 0.1), (8, 64, 0.0)])
 def test_panel_kernel_dense_panels(torch_cuda, bits, G, sparsity):
     """Four panels per workgroup (769 panels on 256 workgroups) that are dense or nearly so: a
