@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     const uint8_t* __restrict__ headers2, const uint8_t* __restrict__ headers3,
     const uint8_t* __restrict__ data0, const uint8_t* __restrict__ data1,
     const uint8_t* __restrict__ data2, const uint8_t* __restrict__ data3,
-    const PanelTargets src, int K, int n_slices, int batch)
+    const PanelTargets tgt, int K, int n_slices, int batch)
 {
     constexpr int CB = 2 * BITS * M;                // code bytes per group
     constexpr bool PAIRED8 = BITS == 8 && M == 1;   // 8-bit, G = 16: quarter 0, word, quarter 1, quarter 2, word, quarter 3
@@ -151,12 +151,12 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     // each in its matrix; one past the last stands in as the last and is not computed
     const auto locate = [&](int pp, int& m, int& p) {
         const int v = static_cast<int>(blockIdx.x + pp * gridDim.x);
-        const bool is_live = v < src.total;
-        const int vc = is_live ? v : src.total - 1;
+        const bool is_live = v < tgt.total;
+        const int vc = is_live ? v : tgt.total - 1;
         if constexpr (MULTI) {
             // (selects among values at fixed places of the argument block: no load depends on another)
             static_assert(kMaxMatricesPerLaunch == 4, "written out for four matrices");
-            const int f1 = src.first[1], f2 = src.first[2], f3 = src.first[3];
+            const int f1 = tgt.first[1], f2 = tgt.first[2], f3 = tgt.first[3];
             m = (vc >= f1 ? 1 : 0) + (vc >= f2 ? 1 : 0) + (vc >= f3 ? 1 : 0);
             p = vc - (m == 0 ? 0 : m == 1 ? f1 : m == 2 ? f2 : f3);
         } else {
@@ -379,8 +379,8 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
             for (int w = 0; w < kPanelWaves; ++w) sum += part[((pp * 4 + v) * kPanelWaves + w) * kLanes + lane];
             const int b = 4 * j + v;                    // activation row
             const int row = p * kPanelRows + r;         // output row
-            const int n = !MULTI || m == 0 ? src.N[0] : m == 1 ? src.N[1] : m == 2 ? src.N[2] : src.N[3];
-            uint16_t* y = !MULTI || m == 0 ? src.y[0] : m == 1 ? src.y[1] : m == 2 ? src.y[2] : src.y[3];
+            const int n = !MULTI || m == 0 ? tgt.N[0] : m == 1 ? tgt.N[1] : m == 2 ? tgt.N[2] : tgt.N[3];
+            uint16_t* y = !MULTI || m == 0 ? tgt.y[0] : m == 1 ? tgt.y[1] : m == 2 ? tgt.y[2] : tgt.y[3];
             if (b < batch && row < n) y[static_cast<size_t>(b) * n + row] = float_to_half_bits(sum);
         }
     }
@@ -424,7 +424,7 @@ void panels_release(gqsa_matrix* m)
 gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, void* const* ys, int batch, void* stream)
 {
     if (n < 1 || n > kMaxMatricesPerLaunch || batch < 1 || batch > kPanelRows) return GQSA_ERR_UNSUPPORTED;
-    PanelTargets src{};
+    PanelTargets tgt{};
     const uint8_t* headers[kMaxMatricesPerLaunch];
     const uint8_t* data[kMaxMatricesPerLaunch];
     int64_t total = 0;
@@ -437,18 +437,18 @@ gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, vo
         const uint8_t* img = static_cast<const uint8_t*>(m->d_panels);
         headers[i] = img;
         data[i] = img + m->panel_blocks_offset;
-        src.y[i] = static_cast<uint16_t*>(ys[i]);
-        src.N[i] = static_cast<int>(m->N);
-        src.first[i] = static_cast<int>(total);
+        tgt.y[i] = static_cast<uint16_t*>(ys[i]);
+        tgt.N[i] = static_cast<int>(m->N);
+        tgt.first[i] = static_cast<int>(total);
         total += m->n_panels;
     }
     if (total > INT32_MAX) return GQSA_ERR_SHAPE;
     for (int i = n; i < kMaxMatricesPerLaunch; ++i) {
-        src.first[i] = static_cast<int>(total);
+        tgt.first[i] = static_cast<int>(total);
         headers[i] = headers[0];
         data[i] = data[0];
     }
-    src.total = static_cast<int>(total);
+    tgt.total = static_cast<int>(total);
     const gqsa_matrix* m = ms[0];
     // one workgroup per compute unit unless that gives a workgroup more than four panels
     const int64_t wgs = std::min<int64_t>(total, std::max<int64_t>(kMaxDefaultWorkgroups,
@@ -457,7 +457,7 @@ gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, vo
     hipStream_t s = static_cast<hipStream_t>(stream);
     const auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint16_t*>(x), headers[0], headers[1], headers[2],
-                           headers[3], data[0], data[1], data[2], data[3], src, static_cast<int>(m->K),
+                           headers[3], data[0], data[1], data[2], data[3], tgt, static_cast<int>(m->K),
                            static_cast<int>(m->n_slices), batch);
     };
     const auto pick = [&](auto multi) {
