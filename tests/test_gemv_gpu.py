@@ -580,6 +580,41 @@ def test_panel_kernel_several_matrices_share_a_launch(torch_cuda, bits, G):
                 assert np.array_equal(yy.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
 
+def test_panel_kernel_seeded_shapes(torch_cuda):
+    """Forty seeded draws of (code width, group size, N, K, per-row keep counts, activation rows):
+    row counts that leave the last panel ragged or give a workgroup one to four panels, K from one
+    group-column to several slices with a short last one, rows from empty to full."""
+    rng = np.random.default_rng(2024)
+    formats = [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)]
+    for case in range(40):
+        bits, G = formats[case % len(formats)]
+        N = int(rng.choice([1, 15, 16, 17, 100, 257, 1000, 4100, 4200, 8300]))
+        cols = int(rng.choice([1, 2, 15, 16, 17, 31, 32, 33, 47, 64, 70]))
+        if N > 1000:
+            cols = min(cols, 33)
+        K = cols * G
+        batch = int(rng.integers(1, 17))
+        style = case % 4
+        if style == 0:
+            keep = rng.integers(0, cols + 1, size=N)
+        elif style == 1:
+            keep = np.full(N, cols)
+        elif style == 2:
+            keep = np.where(rng.random(N) < 0.5, 0, rng.integers(0, cols + 1, size=N))
+        else:
+            keep = np.full(N, (cols + 1) // 2)
+        keep = keep.astype(np.int32)
+        W = gi.dense_weight(N, K, seed=500 + case)
+        c = oracle.pack(W, G, bits, keep_per_row=keep)
+        h = gq.gqsa_pack_rows(W, keep, G, bits)
+        gq.gqsa_build_panels(h)
+        try:
+            check(torch_cuda, h, c, gi.activations(batch, K, seed=600 + case), panels=True)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: bits={bits} G={G} N={N} K={K} batch={batch} style={style}: {e}")
+        gq.gqsa_free(h)
+
+
 @pytest.mark.parametrize("bits,G,sparsity", [(4, 16, 0.0), (4, 16, 0.2), (8, 16, 0.0), (4, 64, 0.1), (8, 64, 0.0)])
 def test_panel_kernel_dense_panels(torch_cuda, bits, G, sparsity):
     """Four panels per workgroup (769 panels on 256 workgroups) that are dense or nearly so: a
