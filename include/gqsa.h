@@ -183,7 +183,8 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
  *   batch 1..16
  *   hip_stream a hipStream_t (NULL = the default stream)
  * K must not exceed 32768 (x and its group sums are staged in LDS); GQSA_ERR_UNSUPPORTED else.
- * A launch takes 8, 4, 2 or 1 activation rows (group sizes other than 16: one row per launch).
+ * A launch takes 8, 4, 2 or 1 activation rows; 3 go to the kernel for 4 and 7 to the kernel for 8
+ * (group sizes other than 16: one row per launch).
  * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
  * bit-identical from run to run.  Does not synchronise.  The current HIP device must be the one
  * the handle was uploaded on (GQSA_ERR_HIP otherwise).

@@ -47,8 +47,9 @@ struct MatArgs {                 // where a matrix's results go (64 bytes)
     CarryRecord* carry;          // [worker][kMaxRowsPerLaunch]
     int* counters;               // arrivals per carry chain, indexed by the chain's first worker
     unsigned long long* slots;   // [worker][kMaxRowsPerLaunch] meeting points of rows spread over two workgroups
-    uint16_t* y;                 // fp16 [NB][N]
-    long long N;
+    uint16_t* y;                 // fp16 [rows][N]
+    int N;
+    int last_row;                // activation rows of this launch - 1 (a kernel for NB rows may be given fewer)
     int n_empty;
     int n_ranks;                 // non-empty rows
 };
@@ -98,6 +99,7 @@ __device__ __forceinline__ MatDesc matrix_desc(int i)
     r.out.slots = src->out.slots;
     r.out.y = src->out.y;
     r.out.N = src->out.N;
+    r.out.last_row = src->out.last_row;
     r.out.n_empty = src->out.n_empty;
     r.out.n_ranks = src->out.n_ranks;
     return r;
@@ -214,7 +216,8 @@ __device__ __forceinline__ void store_row(const MatArgs& m, int b, int rank, flo
 {
     if (static_cast<unsigned>(rank) >= static_cast<unsigned>(m.n_ranks)) return;  // never for a valid image
     const int row = m.row_of_rank ? m.row_of_rank[rank] : rank;
-    m.y[b * m.N + row] = float_to_half_bits(v);
+    if ((b == 3 || b == 7) && b > m.last_row) return;     // a row the caller does not have: the 4th of 3, the 8th of 7
+    m.y[static_cast<size_t>(b) * m.N + row] = float_to_half_bits(v);
 }
 
 // Storage format of a group as the kernel is compiled for it: code width and group size
@@ -667,7 +670,10 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     LdsRecord* rec = reinterpret_cast<LdsRecord*>(xlds + NB * 48 * KGP);        // [wavefront][NB]
 
     const int kg = kg_wpw & 0xFFFF;       // 16-element slots of K
-    const int wpw = kg_wpw >> 16;         // wavefronts per workgroup
+    const int wpw = (kg_wpw >> 16) & 0xFF;    // wavefronts per workgroup
+    // slots of x that exist: the caller may have fewer than NB rows (3 for a kernel of 4, 7 for
+    // one of 8); the rows beyond take the last slot's activations and their sums are never stored
+    const int last_slot = ((kg_wpw >> 24) + 1) * kg - 1;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int n_threads = wpw * kLanes;
@@ -685,7 +691,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     for (int j = 0; j < XPRE; ++j) {
         const int c = tid + j * n_threads;
         if (c < n_slots) {       // (the same condition guards the use)
-            const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(c) * 16);
+            const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(NB > 2 ? min(c, last_slot) : c) * 16);
             xlo[j] = src[0];
             xhi[j] = src[1];
         }
@@ -755,7 +761,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
             if (c < n_slots) stage(c, xlo[j], xhi[j]);
         }
         for (int c = tid + XPRE * n_threads; c < n_slots; c += n_threads) {
-            const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(c) * 16);
+            const uint4* src = reinterpret_cast<const uint4*>(x + static_cast<size_t>(NB > 2 ? min(c, last_slot) : c) * 16);
             stage(c, src[0], src[1]);
         }
         lds_barrier();
@@ -816,7 +822,8 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     for (int e = lwg * n_threads + tid; e < md.out.n_empty; e += md.n_wg * n_threads) {
         const int row = md.out.empty_rows[e];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) md.out.y[b * md.out.N + row] = 0;
+        for (int b = 0; b < NB; ++b)
+            if (!((b == 3 || b == 7) && b > md.out.last_row)) md.out.y[static_cast<size_t>(b) * md.out.N + row] = 0;
     }
 
     // the last row of the run, if it ends there
@@ -842,7 +849,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
 // A launchable variant of the kernel.
 struct Variant {
     const void* fn = nullptr;    // device function, for attribute setting
-    void (*launch)(const LaunchArgs&, const uint16_t*, int, int, const int*, dim3, dim3, size_t, hipStream_t) = nullptr;
+    void (*launch)(const LaunchArgs&, const uint16_t*, int, int, int, const int*, dim3, dim3, size_t, hipStream_t) = nullptr;
     explicit operator bool() const { return fn != nullptr; }
 };
 
@@ -852,12 +859,12 @@ constexpr size_t lds_bytes(int kgp, int nb)
 }
 
 template <typename F, int KGP, int NB>
-void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg, int wpw, const int* wg_end, dim3 grid, dim3 block,
+void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg, int wpw, int rows, const int* wg_end, dim3 grid, dim3 block,
                     size_t lds, hipStream_t s)
 {
     const MatDesc& m0 = a.m[0];
     hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB>), grid, block, lds, s, x, m0.blocks, m0.wave_info, m0.magic,
-                       m0.base, m0.extra, kg | (wpw << 16), wg_end[0], wg_end[1], wg_end[2], a);
+                       m0.base, m0.extra, kg | (wpw << 16) | ((rows - 1) << 24), wg_end[0], wg_end[1], wg_end[2], a);
 }
 
 template <typename F, int KGP, int NB>
@@ -1022,9 +1029,9 @@ int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb, size_
     return wpw;
 }
 
-// One launch: nb activation rows (1, 2, 4 or 8) times n_mats matrices that share x and the
-// wavefronts per workgroup.
-gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint16_t* const* ys, int nb, int wpw,
+// One launch: the kernel for nb activation rows (1, 2, 4 or 8), of which the caller has `rows`
+// (nb, or one fewer), times n_mats matrices that share x and the wavefronts per workgroup.
+gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint16_t* const* ys, int nb, int rows, int wpw,
                      hipStream_t s)
 {
     const gqsa_matrix* m0 = ms[0];
@@ -1052,13 +1059,14 @@ gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint
         o.counters = reinterpret_cast<int*>(ws + counters_offset(m->n_waves));
         o.slots = reinterpret_cast<unsigned long long*>(ws + slots_offset(m->n_waves));
         o.y = ys[i];
-        o.N = m->N;
+        o.N = static_cast<int>(m->N);
+        o.last_row = rows - 1;
         o.n_empty = static_cast<int>(m->n_empty);
         o.n_ranks = static_cast<int>(m->N - m->n_empty);
         grid += d.n_wg;
         if (i + 1 < n_mats) wg_end[i] = grid;
     }
-    v.launch(a, x, static_cast<int>(m0->K / 16), wpw, wg_end, dim3(grid), dim3(wpw * kLanes), lds_bytes(kgp, nb), s);
+    v.launch(a, x, static_cast<int>(m0->K / 16), wpw, rows, wg_end, dim3(grid), dim3(wpw * kLanes), lds_bytes(kgp, nb), s);
     return GQSA_OK;
 }
 
@@ -1075,12 +1083,21 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
     for (int i = 0; i < n_mats; ++i)
         if (ms[i]->device != dev) return GQSA_ERR_HIP;
     // the batch goes out in launches of 8, 4, 2 or 1 rows: the most that the format has a
-    // kernel for, fits LDS and is left
+    // kernel for, fits LDS and is left -- except that 3 rows go to the kernel for 4 and 7 to the
+    // kernel for 8 (measured: a launch for 4 rows takes less than launches for 2 and for 1;
+    // with two rows missing the smaller launches win on the larger matrices)
     int done = 0;
     while (done < batch) {
-        int nb = kMaxRowsPerLaunch, kgp = 0;
-        for (; nb >= 1; nb /= 2) {
-            if (nb <= batch - done && pick(m0, nb, &kgp)) break;
+        const int left = batch - done;
+        int nb = kMaxRowsPerLaunch, kgp = 0, rows = 0;
+        if ((left == 3 || left == 7) && pick(m0, left + 1, &kgp)) {
+            nb = left + 1;
+            rows = left;
+        } else {
+            for (; nb >= 1; nb /= 2) {
+                if (nb <= left && pick(m0, nb, &kgp)) break;
+            }
+            rows = nb;
         }
         if (nb < 1) return GQSA_ERR_UNSUPPORTED;
         const uint16_t* xb = static_cast<const uint16_t*>(x) + static_cast<size_t>(done) * m0->K;
@@ -1090,14 +1107,14 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
         const int together = launch_waves_per_workgroup(ms, n_mats, nb, lds);
         if (together > 0) {
             // one launch for all the matrices
-            if (gqsa_status_t st = launch(ms, n_mats, xb, yb, nb, together, s)) return st;
+            if (gqsa_status_t st = launch(ms, n_mats, xb, yb, nb, rows, together, s)) return st;
         } else {
             for (int i = 0; i < n_mats; ++i) {
                 const int wpw = launch_waves_per_workgroup(ms + i, 1, nb, lds);
-                if (gqsa_status_t st = launch(ms + i, 1, xb, yb + i, nb, wpw, s)) return st;
+                if (gqsa_status_t st = launch(ms + i, 1, xb, yb + i, nb, rows, wpw, s)) return st;
             }
         }
-        done += nb;
+        done += rows;
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;

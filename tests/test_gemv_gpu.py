@@ -210,9 +210,48 @@ def test_small_batches(torch_cuda, bits):
     h = gq.gqsa_pack(W, 16, bits, 0.5)
     x = gi.activations(16, K, seed=10)
     y16, _ = check(torch_cuda, h, c, x)
-    for b in (1, 2, 4, 8):
+    for b in range(1, 16):
         yb, _ = check(torch_cuda, h, c, x[:b])
         assert np.array_equal(yb.view(np.uint16), y16[:b].view(np.uint16))
+
+
+@pytest.mark.parametrize("part", [None, (37, 3)])
+def test_three_and_seven_rows_in_the_kernels_for_four_and_eight(torch_cuda, part):
+    """3 rows run in the kernel for 4 and 7 in the kernel for 8 (also as the tail of 11 and 15):
+    the rows that are not there must neither be read past the end of x nor reach y.  y sits in
+    the middle of a larger buffer of a marker value; rows shared by wavefronts and workgroups,
+    rows without groups (their zero fill), several matrices per launch."""
+    torch = torch_cuda
+    N, K = 300, 2048
+    W = gi.dense_weight(N, K, seed=62)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=62)
+    keep[[0, 7, 299]] = 0
+    c = oracle.pack(W, 16, 4, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, 16, 4)
+    h2 = gq.gqsa_pack_rows(W, keep, 16, 4)
+    if part:
+        gq.gqsa_set_partition(h, *part)
+        gq.gqsa_set_partition(h2, *part)
+    x16 = gi.activations(16, K, seed=11)
+    y16 = run_gemv(torch, h, x16)
+    marker = np.float16(-777.0)
+    for b in (3, 7, 11, 15):
+        xt = torch.from_numpy(x16[:b].copy()).cuda()              # exactly b rows: nothing behind them is ours
+        big = torch.full((b + 4, N), float(marker), dtype=torch.float16, device="cuda")
+        big2 = torch.full((b + 4, N), float(marker), dtype=torch.float16, device="cuda")
+        gq.gqsa_gemv(h, xt, big[2:2 + b])
+        torch.cuda.synchronize()
+        out = big.cpu().numpy()
+        assert np.array_equal(out[2:2 + b].view(np.uint16), y16[:b].view(np.uint16))
+        assert (out[:2] == marker).all() and (out[2 + b:] == marker).all()
+        big.fill_(float(marker))
+        gq.gqsa_gemv_multi([h, h2], xt, [big[2:2 + b], big2[2:2 + b]])
+        torch.cuda.synchronize()
+        for o in (big.cpu().numpy(), big2.cpu().numpy()):
+            assert np.array_equal(o[2:2 + b].view(np.uint16), y16[:b].view(np.uint16))
+            assert (o[:2] == marker).all() and (o[2 + b:] == marker).all()
+    err = max(oracle.rel_error(y16[i], oracle.gemv(c, x16, threads=8)[i]) for i in range(16))
+    assert err <= TOL
 
 
 @pytest.mark.parametrize("part", [None, (37, 3)])
