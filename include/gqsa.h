@@ -154,8 +154,8 @@ gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_
  * bytes per stored 4-bit group of 16 on top of the first one.  Host only; only before the handle
  * is uploaded (GQSA_ERR_UNSUPPORTED after); G >= 16 (GQSA_ERR_UNSUPPORTED for G = 8; a group of
  * 32, 64 or 128 weights takes 2, 4 or 8 products).  Once built, gqsa_upload copies both images and
- * gqsa_gemv / gqsa_gemv_multi use this one for batch >= 5 with G = 16 and for batch >= 3 with
- * the larger groups (gqsa_gemv_multi: still one launch, the workgroups' panels taken from all the
+ * gqsa_gemv / gqsa_gemv_multi use this one for batch >= 5 with G = 16 and K <= 8192 and for
+ * batch >= 3 with larger K or larger groups (gqsa_gemv_multi: still one launch, the workgroups' panels taken from all the
  * matrices so that they share the activations they load, if the matrices have at most 1024 panels
  * of 16 rows together and their zeros are either all small integers or not -- else one launch
  * per matrix; same bits either way); results stay within the same bound (fp32

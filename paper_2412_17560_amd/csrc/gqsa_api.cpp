@@ -53,8 +53,10 @@ gqsa_status_t upload(gqsa_matrix* m)
 // Calls with this many activation rows or more go to the matrix-core kernel if the handle has a
 // panel image: its time hardly depends on the row count (16 rows' worth of products either way),
 // the wavefront kernel's grows with every row, and they cross between 4 and 5 rows on an MI355X
-// (group sizes other than 16: between 2 and 3 rows, since that kernel takes them one row per launch).
-constexpr int panel_min_batch(const gqsa_matrix* m) { return m->G == 16 ? 5 : 3; }
+// for K up to 8192 and between 2 and 3 rows beyond (4096x11008, 4096x14336: every workgroup of
+// the wavefront kernel stages all of x; group sizes other than 16: between 2 and 3 rows as well,
+// since that kernel takes them one row per launch).
+constexpr int panel_min_batch(const gqsa_matrix* m) { return m->G == 16 && m->K <= 8192 ? 5 : 3; }
 
 }  // namespace
 

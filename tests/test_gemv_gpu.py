@@ -582,6 +582,17 @@ def test_panel_kernel_only_from_five_rows(torch_cuda):
     with pytest.raises(gq.GqsaError) as e:
         run_gemv(torch_cuda, h1, x, panels=True)     # no such image
     assert e.value.status == 3
+    # K above 8192: from 3 rows on
+    N, K = 48, 8208
+    W = gi.dense_weight(N, K, seed=99)
+    c = oracle.pack(W, 16, 4, sparsity=0.5)
+    h1 = gq.gqsa_pack(W, 16, 4, 0.5)
+    h2 = gq.gqsa_pack(W, 16, 4, 0.5)
+    gq.gqsa_build_panels(h2)
+    x = gi.activations(3, K, seed=18)
+    assert np.array_equal(run_gemv(torch_cuda, h1, x[:2]).view(np.uint16), run_gemv(torch_cuda, h2, x[:2]).view(np.uint16))
+    y, _ = check(torch_cuda, h2, c, x)
+    assert np.array_equal(y.view(np.uint16), run_gemv(torch_cuda, h2, x, panels=True).view(np.uint16))
 
 
 @pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32)])
