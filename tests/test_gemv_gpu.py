@@ -746,6 +746,10 @@ def test_graph_replays_match_eager(torch_cuda):
     gq.gqsa_set_partition(hc, 5, 4)
     hp = gq.gqsa_pack_rows(W, keep, 16, 8)
     gq.gqsa_build_panels(hp)
+    hq = [gq.gqsa_pack_rows(W, keep, 16, 4) for _ in range(3)]   # three matrices in one launch of the matrix-core kernel
+    for h in hq:
+        gq.gqsa_build_panels(h)
+    x7 = torch.from_numpy(gi.activations(7, K, seed=65)).cuda()
     x1 = torch.from_numpy(gi.activations(1, K, seed=62)).cuda()
     x3 = torch.from_numpy(gi.activations(3, K, seed=63)).cuda()
     x16 = torch.from_numpy(gi.activations(16, K, seed=64)).cuda()
@@ -755,13 +759,19 @@ def test_graph_replays_match_eager(torch_cuda):
                 torch.full((3, N), float("nan"), dtype=torch.float16, device="cuda"),
                 torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda"),
                 torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda"),
-                torch.full((16, N), float("nan"), dtype=torch.float16, device="cuda")]
+                torch.full((16, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda")]
 
     def issue(ys):
         gq.gqsa_gemv(ha, x1, ys[0])
         gq.gqsa_gemv(ha, x3, ys[1])
         gq.gqsa_gemv_multi([hb, hc], x1, [ys[2], ys[3]])
         gq.gqsa_gemv(hp, x16, ys[4])
+        gq.gqsa_gemv_multi(hq, x7, ys[5:8])
+        gq.gqsa_gemv(hb, x7, ys[8])                         # 7 rows in the kernel for 8
 
     eager = outputs()
     issue(eager)
