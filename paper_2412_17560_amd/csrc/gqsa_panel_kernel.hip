@@ -24,7 +24,7 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kPanelsPerWorkgroup = 4;   // panels a workgroup takes at most (each needs its own sums)
 constexpr int kInFlight = 4;          // group-columns whose products are under way together
-constexpr int kPanelWaves = 16;      // wavefronts of a workgroup: each takes every 16th unit (a run of group-columns) of the panel
+constexpr int kPanelWaves = 16;      // wavefronts of a workgroup (or 8, see WAVES): each takes every 16th (8th) unit (a run of group-columns) of the panel
 constexpr int kWaveLds = 9216;        // bytes of LDS a wavefront stages records in (16 x 9 KB = 144 of the 160 KB)
 constexpr int kMaxUnitBytes = 3072;   // records of one panel in one unit, at most (16 rows x the unit's columns)
 
@@ -111,8 +111,12 @@ struct PanelTargets {
 // zero is an arbitrary fp16 number and multiplies the second product's sum of activations.
 // MULTI: more than one matrix in the launch (the lookups of a panel's matrix cost scalar
 // registers, which the headers of four panels already fill: one matrix keeps its own code).
-template <int BITS, int M, bool INTZ, bool MULTI>
-__global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
+// WAVES: 16 wavefronts per workgroup and one workgroup per compute unit, or -- for launches of
+// more workgroups than compute units -- 8 and two: the loads of one then run under the products
+// of the other (workgroups of 16 wavefronts can only follow one another, each loading, then
+// computing).  Either way four wavefronts per SIMD unit, 128 vector registers each.
+template <int BITS, int M, bool INTZ, bool MULTI, int WAVES>
+__global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
     const uint16_t* __restrict__ x,
     const uint8_t* __restrict__ headers0, const uint8_t* __restrict__ headers1,
     const uint8_t* __restrict__ headers2, const uint8_t* __restrict__ headers3,
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     constexpr int QB = (BITS / 2) * M;              // code bytes of a lane (one quarter of every chunk)
     constexpr int QW = (QB + 3) / 4;                // ... in registers
     constexpr bool PAIRED = QB == 2;                // 4-bit, G = 16: codes and scale, zero in one 8-byte load
-    __shared__ __attribute__((aligned(16))) uint8_t staged[kPanelWaves * kWaveLds];
+    __shared__ __attribute__((aligned(16))) uint8_t staged[WAVES * kWaveLds];
     float* part = reinterpret_cast<float*>(staged);            // the same memory once the products are done
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -194,7 +198,7 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
                                        : 0x0c010c00u + (quarter & 1u) * 0x00020002u + (quarter >= 2 ? 0x00040004u : 0u);
     const uint32_t sel_sz = PAIRED8 ? ((quarter & 1u) ? 0x03020100u : 0x07060504u)
                                     : (quarter >= 2 ? 0x03020100u : 0x07060504u);
-    for (int unit = wl; unit < UPS * n_slices; unit += kPanelWaves) {
+    for (int unit = wl; unit < UPS * n_slices; unit += WAVES) {
         const int s = unit / UPS;
         const int sub = unit % UPS;
         const int col0 = s * kSliceColumns + sub * HC;
@@ -358,25 +362,25 @@ __global__ __launch_bounds__(kPanelWaves * kLanes) void gqsa_panel_kernel(
     }
 
     // The wavefronts' sums meet in LDS (the staging areas, once every wavefront is done with its
-    // own): all panels' at once, then wavefront w adds up, in wavefront order, the sixteen
-    // contributions to the activation rows 4 j + (w % 4) of panel w / 4 and stores them.
-    static_assert(kPanelWaves == 4 * kPanelsPerWorkgroup, "one wavefront per (panel, accumulator register) below");
-    static_assert(kPanelsPerWorkgroup * kPanelWaves * 4 * kLanes * sizeof(float) <= sizeof(staged), "the sums must fit the staging areas");
+    // own): all panels' at once, then the wavefronts share out the (panel, accumulator register)
+    // pairs: pair t = the activation rows 4 j + (t % 4) of panel t / 4, whose contributions are
+    // added in wavefront order and stored.
+    static_assert(kPanelsPerWorkgroup * WAVES * 4 * kLanes * sizeof(float) <= sizeof(staged), "the sums must fit the staging areas");
     __syncthreads();
 #pragma unroll
     for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
         if (!live[pp]) break;                           // (the same for the whole workgroup)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) part[((pp * 4 + v) * kPanelWaves + wl) * kLanes + lane] = acc[pp][v];
+        for (int v = 0; v < 4; ++v) part[((pp * 4 + v) * WAVES + wl) * kLanes + lane] = acc[pp][v];
     }
     __syncthreads();
-    {
-        const int pp = wl >> 2, v = wl & 3;
+    for (int t = wl; t < 4 * kPanelsPerWorkgroup; t += WAVES) {      // t = (panel, accumulator register)
+        const int pp = t >> 2, v = t & 3;
         int m, p;
         if (locate(pp, m, p)) {
             float sum = 0.0f;
 #pragma unroll
-            for (int w = 0; w < kPanelWaves; ++w) sum += part[((pp * 4 + v) * kPanelWaves + w) * kLanes + lane];
+            for (int w = 0; w < WAVES; ++w) sum += part[(t * WAVES + w) * kLanes + lane];
             const int b = 4 * j + v;                    // activation row
             const int row = p * kPanelRows + r;         // output row
             const int n = !MULTI || m == 0 ? tgt.N[0] : m == 1 ? tgt.N[1] : m == 2 ? tgt.N[2] : tgt.N[3];
@@ -453,35 +457,42 @@ gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, vo
     // one workgroup per compute unit unless that gives a workgroup more than four panels
     const int64_t wgs = std::min<int64_t>(total, std::max<int64_t>(kMaxDefaultWorkgroups,
                                                                    (total + kPanelsPerWorkgroup - 1) / kPanelsPerWorkgroup));
-    const dim3 grid(static_cast<unsigned>(wgs)), block(kPanelWaves * kLanes);
+    // more workgroups than compute units: smaller ones, two to a compute unit (see WAVES)
+    const bool halves = n == 1 && wgs > kMaxDefaultWorkgroups;
+    const dim3 grid(static_cast<unsigned>(wgs)), block((halves ? kPanelWaves / 2 : kPanelWaves) * kLanes);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, block, 0, s, static_cast<const uint16_t*>(x), headers[0], headers[1], headers[2],
                            headers[3], data[0], data[1], data[2], data[3], tgt, static_cast<int>(m->K),
                            static_cast<int>(m->n_slices), batch);
     };
-    const auto pick = [&](auto multi) {
+    const auto pick = [&](auto multi, auto waves) {
         constexpr bool kMulti = decltype(multi)::value;
+        constexpr int kWaves = decltype(waves)::value;
         switch (m->bits * 1000 + m->G + (m->panel_integer_zeros ? 500 : 0)) {
-            case 4016: launch(gqsa_panel_kernel<4, 1, false, kMulti>); break;
-            case 4032: launch(gqsa_panel_kernel<4, 2, false, kMulti>); break;
-            case 4064: launch(gqsa_panel_kernel<4, 4, false, kMulti>); break;
-            case 4128: launch(gqsa_panel_kernel<4, 8, false, kMulti>); break;
-            case 8016: launch(gqsa_panel_kernel<8, 1, false, kMulti>); break;
-            case 8032: launch(gqsa_panel_kernel<8, 2, false, kMulti>); break;
-            case 8064: launch(gqsa_panel_kernel<8, 4, false, kMulti>); break;
-            case 4516: launch(gqsa_panel_kernel<4, 1, true, kMulti>); break;
-            case 4532: launch(gqsa_panel_kernel<4, 2, true, kMulti>); break;
-            case 4564: launch(gqsa_panel_kernel<4, 4, true, kMulti>); break;
-            case 4628: launch(gqsa_panel_kernel<4, 8, true, kMulti>); break;
-            case 8516: launch(gqsa_panel_kernel<8, 1, true, kMulti>); break;
-            case 8532: launch(gqsa_panel_kernel<8, 2, true, kMulti>); break;
-            case 8564: launch(gqsa_panel_kernel<8, 4, true, kMulti>); break;
+            case 4016: launch(gqsa_panel_kernel<4, 1, false, kMulti, kWaves>); break;
+            case 4032: launch(gqsa_panel_kernel<4, 2, false, kMulti, kWaves>); break;
+            case 4064: launch(gqsa_panel_kernel<4, 4, false, kMulti, kWaves>); break;
+            case 4128: launch(gqsa_panel_kernel<4, 8, false, kMulti, kWaves>); break;
+            case 8016: launch(gqsa_panel_kernel<8, 1, false, kMulti, kWaves>); break;
+            case 8032: launch(gqsa_panel_kernel<8, 2, false, kMulti, kWaves>); break;
+            case 8064: launch(gqsa_panel_kernel<8, 4, false, kMulti, kWaves>); break;
+            case 4516: launch(gqsa_panel_kernel<4, 1, true, kMulti, kWaves>); break;
+            case 4532: launch(gqsa_panel_kernel<4, 2, true, kMulti, kWaves>); break;
+            case 4564: launch(gqsa_panel_kernel<4, 4, true, kMulti, kWaves>); break;
+            case 4628: launch(gqsa_panel_kernel<4, 8, true, kMulti, kWaves>); break;
+            case 8516: launch(gqsa_panel_kernel<8, 1, true, kMulti, kWaves>); break;
+            case 8532: launch(gqsa_panel_kernel<8, 2, true, kMulti, kWaves>); break;
+            case 8564: launch(gqsa_panel_kernel<8, 4, true, kMulti, kWaves>); break;
             default: return false;
         }
         return true;
     };
-    if (!(n > 1 ? pick(std::true_type{}) : pick(std::false_type{}))) return GQSA_ERR_UNSUPPORTED;
+    using Whole = std::integral_constant<int, kPanelWaves>;
+    using Half = std::integral_constant<int, kPanelWaves / 2>;
+    const bool ok = n > 1 ? pick(std::true_type{}, Whole{})
+                          : (halves ? pick(std::false_type{}, Half{}) : pick(std::false_type{}, Whole{}));
+    if (!ok) return GQSA_ERR_UNSUPPORTED;
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;
 }

@@ -630,6 +630,18 @@ def test_panel_kernel_several_matrices_share_a_launch(torch_cuda, bits, G):
                 assert np.array_equal(yy.cpu().numpy().view(np.uint16), want.view(np.uint16))
 
 
+@pytest.mark.parametrize("bits,G,sparsity", [(4, 16, 0.5), (8, 16, 0.3), (4, 64, 0.5), (4, 16, 0.0)])
+def test_panel_kernel_more_workgroups_than_compute_units(torch_cuda, bits, G, sparsity):
+    """More than 1024 panels (17 603 rows: 1101 panels, the last with 3 rows): 276 workgroups of
+    8 wavefronts, two to a compute unit, each wavefront with several units of the panels."""
+    N, K = 17603, 40 * G
+    W = gi.dense_weight_chunked(N, K, seed=130)
+    c = oracle.pack(W, G, bits, sparsity=sparsity)
+    h = gq.gqsa_pack(W, G, bits, sparsity)
+    gq.gqsa_build_panels(h)
+    check(torch_cuda, h, c, gi.activations(13, K, seed=19), panels=True)
+
+
 def test_panel_kernel_seeded_shapes(torch_cuda):
     """Forty seeded draws of (code width, group size, N, K, per-row keep counts, activation rows):
     row counts that leave the last panel ragged or give a workgroup one to four panels, K from one
