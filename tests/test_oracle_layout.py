@@ -264,3 +264,59 @@ def test_blob_of_empty_matrix():
                           np.tile(np.array([-1, 1, -1, 0]), (16, 1)))
     assert list(np.frombuffer(blob, dtype="<i4", count=8, offset=256)) == list(range(8))
     assert len(blob) == 512
+
+
+@pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
+def test_panel_blob_decodes_back_to_the_dequantised_matrix(bits, G):
+    """The second image read as its consumer reads it -- header word of a column (row mask, groups
+    before it), data offset, a group's record (codes by quarters and chunks, the 4-bit bytes
+    regrouped, scale | zero in the middle; 8-bit codes with G = 16: the word stored twice) -- gives
+    back W^ of Eq. 3 exactly, every stored group once.  Pins the written layout of that image to
+    the canonical arrays, independently of the code that builds it."""
+    N, K = 45, 70 * G            # 3 panels (the last with 13 rows), 3 slices (the last with 6 columns)
+    W = gi.dense_weight(N, K, seed=31)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=31)
+    keep[[2, 44]] = 0
+    keep[5] = K // G
+    c = oracle.pack(W, G, bits, keep_per_row=keep)
+    blob = np.frombuffer(layout.panel_blob(c), dtype=np.uint8)
+    P, S, chunks = -(-N // 16), -(-(K // G) // 32), G // 16
+    cb = G * bits // 8
+    twice = bits == 8 and G == 16
+    rb = cb + (8 if twice else 4)
+    qb = bits // 2                                   # bytes of a quarter of a chunk
+    header_bytes = -(-(P * S * 144) // 256) * 256
+    headers = blob[: P * S * 144].view("<u4").reshape(P * S, 36)
+    data = blob[header_bytes:]
+    dense = np.zeros((N, K), dtype=np.float64)
+    seen = 0
+    for p in range(P):
+        for s in range(S):
+            h = headers[p * S + s]
+            base = int(h[32]) * 16
+            for j in range(32):
+                mask, before = int(h[j]) & 0xFFFF, int(h[j]) >> 16
+                rows = [r for r in range(16) if mask >> r & 1]
+                for rank, r in enumerate(rows):
+                    rec = data[base + (before + rank) * rb: base + (before + rank + 1) * rb]
+                    q = np.zeros(G, dtype=np.int64)
+                    for t in range(4):
+                        for i in range(chunks):
+                            at = (4 * t + (4 if t >= 1 else 0) + (4 if t >= 3 else 0)) if twice \
+                                else (t * chunks + i) * qb + (4 if t >= 2 else 0)
+                            b = rec[at: at + qb]
+                            if bits == 4:
+                                e = [b[0] & 15, b[1] & 15, b[0] >> 4, b[1] >> 4]
+                            else:
+                                e = list(b)
+                            q[16 * i + 4 * t: 16 * i + 4 * t + 4] = e
+                    words = [rec[4:8], rec[16:20]] if twice else [rec[cb // 2: cb // 2 + 4]]
+                    assert all(bytes(w) == bytes(words[0]) for w in words)
+                    sc, z = (float(v) for v in np.frombuffer(bytes(words[0]), dtype=np.float16))
+                    n, col = 16 * p + r, 32 * s + j
+                    assert n < N and col < K // G
+                    dense[n, col * G: (col + 1) * G] = (q - z) * sc
+                    seen += 1
+            assert int(h[33]) == (int(h[31]) >> 16) + bin(int(h[31]) & 0xFFFF).count("1")
+    assert seen == c.nnzg
+    assert np.array_equal(dense, oracle.densify(c))
