@@ -187,10 +187,9 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
     // a lane supplies elements 0-3, 8-11, 4-7, 12-15 of every chunk for j = 0..3: quarters 0, 2, 1, 3
     const uint32_t quarter = 2u * (j & 1) + (j >> 1);
     const uint32_t code_lane = quarter * QB + (quarter >= 2 ? 4u : 0u);     // where its codes start in a record
-    // PAIRED: lanes of quarters 0, 1 load bytes 0..7 of the 12-byte record (codes, then scale | zero),
-    // lanes of quarters 2, 3 bytes 4..11 (scale | zero, then codes); a byte permute with a selector
-    // that differs by lane puts the lane's two code bytes into bits 0..7 and 16..23, another one
-    // picks the scale | zero word
+    // PAIRED: a lane reads the whole 12-byte record (codes of quarters 0, 1 | scale, zero | codes of
+    // quarters 2, 3); a byte permute with a selector that differs by lane puts the lane's two code
+    // bytes, from the first or the third word, into bits 0..7 and 16..23
     // PAIRED8: quarters 0 and 2 load (codes, word), quarters 1 and 3 (word, codes); the permutes of
     // the decode take the code bytes from whichever of the two it is
     const uint32_t pair_load = PAIRED8 ? 4u * quarter + (quarter >= 2 ? 4u : 0u) : (quarter >= 2 ? 4u : 0u);
@@ -288,11 +287,17 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                 const uint8_t* records = mine + slot[pp];           // in LDS
                 const uint32_t before0 = first[pp];
                 uint32_t code[HC][(PAIRED || PAIRED8) ? 2 : QW], sz[HC];
+                constexpr bool TRI = PAIRED;     // all three words of the 12-byte record: the middle one is scale | zero as it is
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
                     const uint32_t h = hh[pp][c];
                     const uint32_t idx = ((h >> 16) - before0) + __builtin_popcount(h & 0xFFFFu & below);
-                    if constexpr (PAIRED || PAIRED8) {
+                    if constexpr (TRI) {
+                        const uint32_t* w = reinterpret_cast<const uint32_t*>(records + idx * RB);
+                        code[c][0] = w[0];
+                        sz[c] = w[1];
+                        code[c][1] = w[2];
+                    } else if constexpr (PAIRED || PAIRED8) {
                         const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + pair_load));
                         code[c][0] = w[0];
                         code[c][1] = w[1];
@@ -312,7 +317,8 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                     uint32_t sz_word[FLY];
 #pragma unroll
                     for (int i = 0; i < FLY; ++i) {
-                        if constexpr (PAIRED || PAIRED8) sz_word[i] = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
+                        if constexpr (TRI) sz_word[i] = sz[c + i];
+                        else if constexpr (PAIRED || PAIRED8) sz_word[i] = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
                         else sz_word[i] = sz[c + i];
                         half2_t off_lo = k1024, off_hi = k64;
                         if constexpr (INTZ) {
@@ -330,7 +336,7 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                             if constexpr (PAIRED8) {
                                 q = decode4_w8(code[c + i][1], code[c + i][0], sel_codes, dk, off_lo);
                             } else if constexpr (PAIRED) {
-                                q = decode4_w4(__builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_codes), dk, off_lo, off_hi);
+                                q = decode4_w4(__builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_codes), dk, off_lo, off_hi);   // (same selectors: bytes 0..3 = word 0, 4..7 = word 2)
                             } else if constexpr (BITS == 4) {     // chunk k: two bytes, the lower or the upper half of a word
                                 q = decode4_w4(__builtin_amdgcn_perm(0u, code[c + i][k / 2], (k & 1) ? 0x0c030c02u : 0x0c010c00u), dk, off_lo, off_hi);
                             } else {
