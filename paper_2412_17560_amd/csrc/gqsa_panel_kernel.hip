@@ -190,8 +190,9 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
     // PAIRED: a lane reads the whole 12-byte record (codes of quarters 0, 1 | scale, zero | codes of
     // quarters 2, 3); a byte permute with a selector that differs by lane puts the lane's two code
     // bytes, from the first or the third word, into bits 0..7 and 16..23
-    // PAIRED8: quarters 0 and 2 load (codes, word), quarters 1 and 3 (word, codes); the permutes of
-    // the decode take the code bytes from whichever of the two it is
+    // PAIRED8: a lane reads the 12 bytes (quarter, scale | zero, quarter) that hold its quarter; the
+    // permutes of the decode take the code bytes from the first or the third word
+    const uint32_t half_of_record = quarter >= 2 ? 12u : 0u;
     const uint32_t pair_load = PAIRED8 ? 4u * quarter + (quarter >= 2 ? 4u : 0u) : (quarter >= 2 ? 4u : 0u);
     const uint32_t sel_codes = PAIRED8 ? 0x0c010c00u + (quarter & 1u) * 0x00040004u
                                        : 0x0c010c00u + (quarter & 1u) * 0x00020002u + (quarter >= 2 ? 0x00040004u : 0u);
@@ -287,13 +288,14 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                 const uint8_t* records = mine + slot[pp];           // in LDS
                 const uint32_t before0 = first[pp];
                 uint32_t code[HC][(PAIRED || PAIRED8) ? 2 : QW], sz[HC];
-                constexpr bool TRI = PAIRED;     // all three words of the 12-byte record: the middle one is scale | zero as it is
+                constexpr bool TRI = PAIRED || PAIRED8;     // three words, the middle one is scale | zero as it is: the whole 12-byte
+                                                            // record, or the half of the 24-byte one that holds the lane's quarter
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
                     const uint32_t h = hh[pp][c];
                     const uint32_t idx = ((h >> 16) - before0) + __builtin_popcount(h & 0xFFFFu & below);
                     if constexpr (TRI) {
-                        const uint32_t* w = reinterpret_cast<const uint32_t*>(records + idx * RB);
+                        const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + (PAIRED8 ? half_of_record : 0u)));
                         code[c][0] = w[0];
                         sz[c] = w[1];
                         code[c][1] = w[2];
