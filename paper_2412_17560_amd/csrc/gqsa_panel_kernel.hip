@@ -193,11 +193,8 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
     // PAIRED8: a lane reads the 12 bytes (quarter, scale | zero, quarter) that hold its quarter; the
     // permutes of the decode take the code bytes from the first or the third word
     const uint32_t half_of_record = quarter >= 2 ? 12u : 0u;
-    const uint32_t pair_load = PAIRED8 ? 4u * quarter + (quarter >= 2 ? 4u : 0u) : (quarter >= 2 ? 4u : 0u);
     const uint32_t sel_codes = PAIRED8 ? 0x0c010c00u + (quarter & 1u) * 0x00040004u
                                        : 0x0c010c00u + (quarter & 1u) * 0x00020002u + (quarter >= 2 ? 0x00040004u : 0u);
-    const uint32_t sel_sz = PAIRED8 ? ((quarter & 1u) ? 0x03020100u : 0x07060504u)
-                                    : (quarter >= 2 ? 0x03020100u : 0x07060504u);
     for (int unit = wl; unit < UPS * n_slices; unit += WAVES) {
         const int s = unit / UPS;
         const int sub = unit % UPS;
@@ -299,10 +296,6 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                         code[c][0] = w[0];
                         sz[c] = w[1];
                         code[c][1] = w[2];
-                    } else if constexpr (PAIRED || PAIRED8) {
-                        const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + pair_load));
-                        code[c][0] = w[0];
-                        code[c][1] = w[1];
                     } else {
                         const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + code_lane));
 #pragma unroll
@@ -319,9 +312,7 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                     uint32_t sz_word[FLY];
 #pragma unroll
                     for (int i = 0; i < FLY; ++i) {
-                        if constexpr (TRI) sz_word[i] = sz[c + i];
-                        else if constexpr (PAIRED || PAIRED8) sz_word[i] = __builtin_amdgcn_perm(code[c + i][1], code[c + i][0], sel_sz);
-                        else sz_word[i] = sz[c + i];
+                        sz_word[i] = sz[c + i];
                         half2_t off_lo = k1024, off_hi = k64;
                         if constexpr (INTZ) {
                             const half2_t both = __builtin_bit_cast(half2_t, sz_word[i]);

@@ -20,15 +20,15 @@
 //   data        per block, in the order of the headers: one record per group, the block's groups
 //               ordered by (column, row); the block is padded to a multiple of 16 bytes.  Record =
 //               the code bytes of quarters 0 and 1, then uint32 fp16 scale | fp16 zero << 16, then
-//               the code bytes of quarters 2 and 3 (with 2 code bytes per quarter a lane's codes
-//               and the scale and zero are one 8-byte load).  Quarter t (t = 0..3) holds, chunk
+//               the code bytes of quarters 2 and 3 (with 2 code bytes per quarter the record is
+//               12 bytes, which a lane reads whole).  Quarter t (t = 0..3) holds, chunk
 //               after chunk of 16 elements, the codes of the elements 4t .. 4t+3 of every chunk --
 //               what one lane supplies to the products -- so a lane's codes are contiguous.  A quarter of a chunk is 2 bytes of
 //               4-bit codes, elements e0..e3 as (e0 | e2 << 4), (e1 | e3 << 4) (two masks split
 //               them into two fp16 pairs), or 4 bytes of 8-bit codes in element order.
 //               8-bit codes with G = 16 (4 code bytes per quarter): the scale | zero word is
 //               stored twice, record = quarter 0, scale | zero, quarter 1, quarter 2, scale | zero,
-//               quarter 3 (24 bytes), so that every lane's codes and the word are one 8-byte load.
+//               quarter 3 (24 bytes), so that the 12 bytes around the word hold a lane's codes.
 //               The region ends with 256 zero bytes and the image is padded to a multiple of 256
 //               bytes.
 #include <algorithm>
