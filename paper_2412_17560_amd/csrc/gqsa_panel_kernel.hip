@@ -129,7 +129,7 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
     constexpr int RB = CB + (PAIRED8 ? 8 : 4);      // record: codes of quarters 0, 1 | scale, zero | codes of quarters 2, 3
     constexpr int QB = (BITS / 2) * M;              // code bytes of a lane (one quarter of every chunk)
     constexpr int QW = (QB + 3) / 4;                // ... in registers
-    constexpr bool PAIRED = QB == 2;                // 4-bit, G = 16: codes and scale, zero in one 8-byte load
+    constexpr bool PAIRED = QB == 2;                // 4-bit, G = 16: a 12-byte record, read whole
     __shared__ __attribute__((aligned(16))) uint8_t staged[WAVES * kWaveLds];
     float* part = reinterpret_cast<float*>(staged);            // the same memory once the products are done
     const int tid = threadIdx.x;
