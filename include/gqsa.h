@@ -130,6 +130,12 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
  * 256, 512 or 768 workgroups and the smallest span that holds the rows. */
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
 
+/* That default, for a matrix known by its row pointers alone (host only, no handle is built):
+ * out[3] = {n_workgroups, waves_per_workgroup, span_tiles} (span_tiles as in
+ * gqsa_set_partition_aligned, 0 for the plain deal).  rowIndex [host] int32[N+1] as in gqsa_import. */
+gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t K, int G, int bits,
+                                     int32_t out[3]);
+
 /*
  * Same, with the rows kept inside the workgroups' shares (a row shared by two workgroups costs
  * both an exchange through device memory at the end of the launch): the stream is cut into spans
@@ -187,7 +193,9 @@ gqsa_status_t gqsa_upload(gqsa_handle_t h);
  * (group sizes other than 16: one row per launch).
  * fp32 accumulation, one round-to-nearest-even to fp16 per output.  Results are
  * bit-identical from run to run.  Does not synchronise.  The current HIP device must be the one
- * the handle was uploaded on (GQSA_ERR_HIP otherwise).
+ * the handle was uploaded on (GQSA_ERR_HIP otherwise).  A handle that is not on the device yet is
+ * uploaded by its first call (allocations, a synchronous copy): call gqsa_upload before
+ * capturing a stream -- a first call on a capturing stream is refused (GQSA_ERR_UNSUPPORTED).
  */
 gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
                         void* hip_stream);
@@ -231,31 +239,6 @@ gqsa_status_t gqsa_load(const char* path, gqsa_handle_t* out);
 void gqsa_free(gqsa_handle_t h);
 
 const char* gqsa_status_string(gqsa_status_t s);
-
-/* ------------------------------------------------------------------------------------------
- * Side-by-side kernels measured next to the GQSA path (same GPU, same harness): a dense fp16
- * GEMV (the FP16 baseline of the paper's Tab. 4 / Tab. 13), a read-only streaming kernel that
- * measures the achievable HBM read rate, and an empty launch.  The dense 4-bit baseline of
- * Tab. 4 / Tab. 10 (Eq. 1-3 with nothing pruned) is gqsa_pack with sparsity 0.
- * ------------------------------------------------------------------------------------------ */
-
-/* y[batch,N] = W[N,K] x[batch,K], all fp16 [device], fp32 accumulation. */
-gqsa_status_t gqsa_dense_f16_gemv(const void* W_dev, const void* x_dev, void* y_dev,
-                                  int64_t N, int64_t K, int batch, void* hip_stream);
-
-/* XOR `bytes` (multiple of 16) of device memory into sink_dev[0..n_wg-1] (uint32 each; n_wg =
- * gqsa_stream_read_workgroups() entries must be there, a small buffer writes fewer): a pure read
- * at full width, every workgroup reading its own contiguous share. */
-gqsa_status_t gqsa_stream_read(const void* buf_dev, size_t bytes, void* sink_dev, void* hip_stream);
-int gqsa_stream_read_workgroups(void);
-
-/* dst[0..bytes) = src[0..bytes), both [device], 16-byte aligned, bytes a multiple of 16: a kernel
- * of exactly known HBM traffic, used to calibrate the profiler's byte counters. */
-gqsa_status_t gqsa_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
-
-/* Launch an empty kernel with the GEMV's geometry (n_workgroups x 1024 threads, lds_bytes of
- * LDS): the cost of a launch by itself, for the benchmark report.  sink_dev [device] non-NULL. */
-gqsa_status_t gqsa_launch_floor(int n_workgroups, int lds_bytes, void* sink_dev, void* hip_stream);
 
 #ifdef __cplusplus
 }

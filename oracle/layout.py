@@ -93,7 +93,6 @@ import numpy as np
 
 LANES = 64
 ALIGN = 256
-MAX_WORKGROUPS = 4096
 
 
 def tile_blocks(code_bytes: int) -> int:
@@ -115,66 +114,6 @@ def row_positions(rowIndex, span_groups: int):
         out[n] = pos
         pos += c
     return out, pos
-
-
-def default_partition(rowIndex, K: int, G: int = 16, bits: int = 4):
-    """(n_workgroups, waves_per_workgroup, span_tiles) the library picks when not told otherwise.
-    By size first.  K <= 4096 or fewer than 2048 tiles: workers = ntiles (one tile each) up to
-    16384, beyond that ceil(ntiles / t) with t = ceil(ntiles / 16384) tiles each; 4 wavefronts per
-    workgroup (fewer workers: as many); more than 4 workgroups are rounded up to a multiple of 4.
-    Else: 8 wavefronts per workgroup and 256 * clamp(round(448 * ntiles / K / 256), 1, 3)
-    workgroups (round half up).  That is it (span 0) with fewer than 4 wavefronts per workgroup
-    or a single workgroup.  Otherwise the aligned form is tried: small shapes -- span = 4 t, then
-    4 (t + 1); workgroups = spans reached, rounded up to a multiple of 4 if above 4; the first of
-    the two that needs at most (2 MiB / bytes per group) null groups before L and at most 16384
-    workers is taken; large shapes -- the same workgroup count and the smallest span from
-    ceil(ntiles / workgroups) up whose rows reach into no more spans than that, unless a try
-    needs more null groups than that bound.  Otherwise, or with more than 4096 workgroups, the
-    plain form by size stands."""
-    ri = np.asarray(rowIndex, dtype=np.int64)
-    nnzg = int(ri[-1])
-    cb = G * bits // 8
-    tile_groups = LANES * tile_blocks(cb)
-    ntiles = -(-nnzg // tile_groups)
-    small = K <= 4096 or ntiles < 2048
-    if small:
-        t = max(1, -(-ntiles // 16384))
-        workers = max(1, -(-ntiles // t))
-        wpw = min(4, workers)
-        wgs = -(-workers // wpw)
-        if wgs > 4:
-            wgs = -(-wgs // 4) * 4
-    else:
-        wpw = 8
-        wgs = 256 * max(1, min(3, (448 * ntiles + 128 * K) // (256 * K)))
-    plain = (min(wgs, MAX_WORKGROUPS), wpw, 0)
-    if wpw < 4 or wgs < 2:
-        return plain
-    max_null = (2 << 20) // (cb + 6)
-    if small:
-        for tt in (t, t + 1):
-            span = wpw * tt
-            _, L = row_positions(ri, span * tile_groups)
-            a_wgs = -(-L // (span * tile_groups))
-            if a_wgs > 4:
-                a_wgs = -(-a_wgs // 4) * 4
-            if L - nnzg <= max_null and a_wgs * wpw <= 16384:
-                break
-        else:
-            return plain
-    else:
-        a_wgs = wgs
-        span = -(-ntiles // wgs)
-        while True:
-            _, L = row_positions(ri, span * tile_groups)
-            if L - nnzg > max_null:
-                return plain
-            if -(-L // (span * tile_groups)) <= wgs:
-                break
-            span += 1
-    if a_wgs > MAX_WORKGROUPS:
-        return plain
-    return a_wgs, wpw, span
 
 
 def worker_block_counts(nblocks: int, n_waves: int, U: int) -> np.ndarray:

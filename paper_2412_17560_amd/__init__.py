@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     GqsaError,
     GqsaHandle,
     gqsa_copy,
+    gqsa_default_partition,
     gqsa_dense_f16_gemv,
     gqsa_export,
     gqsa_build_panels,

@@ -37,7 +37,9 @@ def _lib():
     # PyTorch ships its own HIP runtime (same SONAME as the system one).  Streams and device
     # pointers handed to libgqsa come from PyTorch, so both must live in ONE runtime: import
     # torch first, and the loader resolves libgqsa's libamdhip64 to the copy already mapped.
-    import torch  # noqa: F401
+    # (A host-only build named by GQSA_LIBRARY has no HIP runtime to share.)
+    if not _build.HOST_ONLY:
+        import torch  # noqa: F401
     path = _build.LIB
     if not os.path.exists(path):
         _build.build()           # nothing built yet: build once, in-tree
@@ -69,6 +71,8 @@ def _lib():
     lib.gqsa_upload.argtypes = [vp]
     lib.gqsa_gemv.restype = C.c_int
     lib.gqsa_gemv.argtypes = [vp, vp, vp, i32, vp]
+    lib.gqsa_default_partition.restype = C.c_int
+    lib.gqsa_default_partition.argtypes = [vp, i64, i64, i32, i32, C.POINTER(C.c_int32 * 3)]
     lib.gqsa_gemv_panels.restype = C.c_int
     lib.gqsa_gemv_panels.argtypes = [vp, vp, vp, i32, vp]
     lib.gqsa_gemv_multi.restype = C.c_int
@@ -257,6 +261,15 @@ def _dev_ptr(t, dtype_name: str, what: str):
     if str(t.dtype) != dtype_name:
         raise ValueError(f"{what} must be {dtype_name}")
     return C.c_void_p(t.data_ptr())
+
+
+def gqsa_default_partition(rowIndex, K: int, G: int = 16, bits: int = 4):
+    """(n_workgroups, waves_per_workgroup, span_tiles) the library would choose for these row pointers."""
+    ri = np.ascontiguousarray(rowIndex, dtype=np.int32)
+    out = (C.c_int32 * 3)()
+    _check(_lib().gqsa_default_partition(C.c_void_p(ri.ctypes.data), ri.size - 1, K, G, bits, C.byref(out)),
+           "gqsa_default_partition")
+    return (int(out[0]), int(out[1]), int(out[2]))
 
 
 def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None, panels: bool = False):

@@ -9,7 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libgqsa.so")
+# the library the binding loads: the in-tree build, unless GQSA_LIBRARY names another one (the
+# sanitizer leg of the tests points it at the host-only build below)
+LIB = os.environ.get("GQSA_LIBRARY") or os.path.join(HERE, "libgqsa.so")
+HOST_ONLY = bool(os.environ.get("GQSA_LIBRARY"))
+SANITIZED_LIB = os.path.join(OBJ, "libgqsa_host_asan.so")
 
 SOURCES = ["gqsa_pack.cpp", "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_panel_kernel.hip", "gqsa_baselines.hip"]
 
@@ -60,5 +64,31 @@ def build() -> str:
     return LIB
 
 
+def build_sanitized() -> str:
+    """Host-only build of the library -- packer, image builders and the C boundary, the device
+    side replaced by stubs that answer GQSA_ERR_HIP -- with AddressSanitizer and
+    UndefinedBehaviorSanitizer (host code only; no GPU code is compiled or sanitized)."""
+    os.makedirs(OBJ, exist_ok=True)
+    srcs = [os.path.join(CSRC, f) for f in ("gqsa_pack.cpp", "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_host_stubs.cpp")]
+    cmd = [_hipcc(), "-x", "c++", "-O1", "-g", "-fPIC", "-shared", "-std=c++17", "-fno-gpu-sanitize",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-shared-libsan", "-fno-omit-frame-pointer",
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, *HOST_FLAGS, *srcs, "-o", SANITIZED_LIB, "-lpthread"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"sanitizer build failed: {' '.join(cmd)}\n{r.stdout}\n{r.stderr}")
+    return SANITIZED_LIB
+
+
+def sanitizer_runtime() -> str:
+    """Path of the AddressSanitizer runtime the sanitized library needs preloaded."""
+    r = subprocess.run([_hipcc(), "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = r.stdout.strip()
+    if os.path.isabs(path) and os.path.exists(path):
+        return path
+    r = subprocess.run([_hipcc(), "--print-runtime-dir"], capture_output=True, text=True)
+    return os.path.join(r.stdout.strip(), "libclang_rt.asan-x86_64.so")
+
+
 if __name__ == "__main__":
-    print(build())
+    import sys
+    print(build_sanitized() if "--asan" in sys.argv[1:] else build())

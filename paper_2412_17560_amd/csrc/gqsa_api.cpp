@@ -5,12 +5,26 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
+#include <stdexcept>
 #include <vector>
 
 #include "gqsa_internal.hpp"
 
 namespace {
+
+// Nothing is thrown across the C boundary: whatever the host code below throws -- in practice a
+// failed allocation (std::bad_alloc, std::length_error) -- becomes a status.
+template <typename Body>
+gqsa_status_t guarded(Body&& body) noexcept
+{
+    try {
+        return body();
+    } catch (...) {
+        return GQSA_ERR_ALLOC;
+    }
+}
 
 gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
 {
@@ -24,19 +38,27 @@ gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
     return GQSA_OK;
 }
 
-gqsa_status_t finish(gqsa_matrix* m, gqsa_status_t st, gqsa_handle_t* out)
+// Choose the default partition and build the device image; the handle goes to the caller only
+// if all of that worked (and is destroyed otherwise, also when something below throws).
+gqsa_status_t finish(std::unique_ptr<gqsa_matrix> m, gqsa_status_t st, gqsa_handle_t* out)
 {
-    if (st == GQSA_OK) {
-        int wgs = 1, wpw = 1, span = 0;
-        gqsa::default_partition(*m, &wgs, &wpw, &span);
-        st = gqsa::build_image(m, wgs, wpw, span);
-    }
-    if (st != GQSA_OK) {
-        delete m;
-        return st;
-    }
-    *out = m;
+    if (st != GQSA_OK) return st;
+    int wgs = 1, wpw = 1, span = 0;
+    gqsa::default_partition(*m, &wgs, &wpw, &span);
+    st = gqsa::build_image(m.get(), wgs, wpw, span);
+    if (st != GQSA_OK) return st;
+    *out = m.release();
     return GQSA_OK;
+}
+
+gqsa_status_t pack_any(const float* W, int64_t N, int64_t K, int G, int bits, const int32_t* keep_per_row,
+                       double sparsity, const float* hinv_diag, gqsa_handle_t* out)
+{
+    return guarded([&]() -> gqsa_status_t {
+        std::unique_ptr<gqsa_matrix> m(new gqsa_matrix);
+        const gqsa_status_t st = gqsa::pack_dense(W, N, K, G, bits, keep_per_row, sparsity, hinv_diag, m.get());
+        return finish(std::move(m), st, out);
+    });
 }
 
 // The device image, and the panel image if there is one.
@@ -69,9 +91,7 @@ gqsa_status_t gqsa_pack(const float* W_host, int64_t N, int64_t K, int G, int bi
     if (!W_host || !out) return GQSA_ERR_NULL;
     if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
     if (!(sparsity >= 0.0 && sparsity <= 1.0)) return GQSA_ERR_RANGE;
-    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
-    if (!m) return GQSA_ERR_ALLOC;
-    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, nullptr, sparsity, nullptr, m), out);
+    return pack_any(W_host, N, K, G, bits, nullptr, sparsity, nullptr, out);
 }
 
 gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, int bits,
@@ -80,9 +100,7 @@ gqsa_status_t gqsa_pack_rows(const float* W_host, int64_t N, int64_t K, int G, i
     if (out) *out = nullptr;
     if (!W_host || !out || !keep_per_row) return GQSA_ERR_NULL;
     if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
-    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
-    if (!m) return GQSA_ERR_ALLOC;
-    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, keep_per_row, 0.0, nullptr, m), out);
+    return pack_any(W_host, N, K, G, bits, keep_per_row, 0.0, nullptr, out);
 }
 
 gqsa_status_t gqsa_pack_hessian(const float* W_host, int64_t N, int64_t K, int G, int bits,
@@ -92,9 +110,7 @@ gqsa_status_t gqsa_pack_hessian(const float* W_host, int64_t N, int64_t K, int G
     if (!W_host || !out || !hinv_diag) return GQSA_ERR_NULL;
     if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
     if (!(sparsity >= 0.0 && sparsity <= 1.0)) return GQSA_ERR_RANGE;
-    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
-    if (!m) return GQSA_ERR_ALLOC;
-    return finish(m, gqsa::pack_dense(W_host, N, K, G, bits, nullptr, sparsity, hinv_diag, m), out);
+    return pack_any(W_host, N, K, G, bits, nullptr, sparsity, hinv_diag, out);
 }
 
 gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const uint8_t* values,
@@ -118,20 +134,36 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
             if (g > rowIndex[n] && groups[g] <= groups[g - 1]) return GQSA_ERR_SHAPE;
         }
     }
-    gqsa_matrix* m = new (std::nothrow) gqsa_matrix;
-    if (!m) return GQSA_ERR_ALLOC;
-    m->N = N; m->K = K; m->G = G; m->bits = bits;
-    try {
+    return guarded([&]() -> gqsa_status_t {
+        std::unique_ptr<gqsa_matrix> m(new gqsa_matrix);
+        m->N = N; m->K = K; m->G = G; m->bits = bits;
         m->rowIndex.assign(rowIndex, rowIndex + N + 1);
         m->groups.assign(groups, groups + nnz);
         m->values.assign(values, values + nnz * (G * bits / 8));
         m->scales.assign(scales_f16, scales_f16 + nnz);
         m->zeros.assign(zeros_f16, zeros_f16 + nnz);
-    } catch (const std::bad_alloc&) {
-        delete m;
-        return GQSA_ERR_ALLOC;
+        return finish(std::move(m), GQSA_OK, out);
+    });
+}
+
+gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t K, int G, int bits, int32_t out[3])
+{
+    if (!rowIndex || !out) return GQSA_ERR_NULL;
+    if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
+    if (rowIndex[0] != 0) return GQSA_ERR_SHAPE;
+    for (int64_t n = 0; n < N; ++n) {
+        const int64_t cnt = static_cast<int64_t>(rowIndex[n + 1]) - rowIndex[n];
+        if (cnt < 0 || cnt > K / G) return GQSA_ERR_SHAPE;
     }
-    return finish(m, GQSA_OK, out);
+    return guarded([&]() -> gqsa_status_t {
+        gqsa_matrix m;
+        m.N = N; m.K = K; m.G = G; m.bits = bits;
+        m.rowIndex.assign(rowIndex, rowIndex + N + 1);
+        int wgs = 1, wpw = 1, span = 0;
+        gqsa::default_partition(m, &wgs, &wpw, &span);
+        out[0] = wgs; out[1] = wpw; out[2] = span;
+        return GQSA_OK;
+    });
 }
 
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup)
@@ -139,7 +171,7 @@ gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_pe
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
     if (n_workgroups < 1) return GQSA_ERR_RANGE;
-    return gqsa::build_image(h, n_workgroups, waves_per_workgroup, 0);
+    return guarded([&] { return gqsa::build_image(h, n_workgroups, waves_per_workgroup, 0); });
 }
 
 gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_workgroups, int waves_per_workgroup)
@@ -147,14 +179,14 @@ gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
     if (span_tiles < 1) return GQSA_ERR_RANGE;
-    return gqsa::build_image(h, n_workgroups, waves_per_workgroup, span_tiles);
+    return guarded([&] { return gqsa::build_image(h, n_workgroups, waves_per_workgroup, span_tiles); });
 }
 
 gqsa_status_t gqsa_build_panels(gqsa_handle_t h)
 {
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
-    return gqsa::build_panels(h);
+    return guarded([&] { return gqsa::build_panels(h); });
 }
 
 gqsa_status_t gqsa_upload(gqsa_handle_t h)
@@ -172,6 +204,7 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
     if ((reinterpret_cast<uintptr_t>(x_dev) & 15u) != 0) return GQSA_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(y_dev) & 1u) != 0) return GQSA_ERR_ALIGN;
     if (!h->d_image) {
+        if (gqsa::stream_is_capturing(hip_stream)) return GQSA_ERR_UNSUPPORTED;   // an upload cannot be captured
         if (gqsa_status_t st = upload(h)) return st;
     }
     if (h->d_panels && batch >= panel_min_batch(h)) return gqsa::panels_gemm(&h, 1, x_dev, &y_dev, batch, hip_stream);
@@ -343,31 +376,31 @@ gqsa_status_t gqsa_load(const char* path, gqsa_handle_t* out)
     if (gqsa_status_t st = check_format(hd.N, hd.K, hd.G, hd.bits)) return st;
     if (hd.nnz_groups < 0 || hd.nnz_groups > hd.N * (hd.K / hd.G) || hd.nnz_groups > INT32_MAX)
         return GQSA_ERR_SHAPE;
-    std::vector<int32_t> rowIndex, groups;
-    std::vector<uint8_t> values;
-    std::vector<uint16_t> scales, zeros;
-    try {
+    return guarded([&]() -> gqsa_status_t {
+        std::vector<int32_t> rowIndex, groups;
+        std::vector<uint8_t> values;
+        std::vector<uint16_t> scales, zeros;
         rowIndex.resize(static_cast<size_t>(hd.N) + 1);
         groups.resize(static_cast<size_t>(hd.nnz_groups));
         values.resize(static_cast<size_t>(hd.nnz_groups) * (hd.G * hd.bits / 8));
         scales.resize(static_cast<size_t>(hd.nnz_groups));
         zeros.resize(static_cast<size_t>(hd.nnz_groups));
-    } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
-    bool ok = true;
-    auto get = [&](void* p, size_t bytes) {
-        if (ok && bytes) ok = std::fread(p, 1, bytes, file.f) == bytes;
-    };
-    get(rowIndex.data(), rowIndex.size() * 4);
-    get(groups.data(), groups.size() * 4);
-    get(values.data(), values.size());
-    get(scales.data(), scales.size() * 2);
-    get(zeros.data(), zeros.size() * 2);
-    if (!ok) return GQSA_ERR_IO;                             // truncated
-    if (std::fgetc(file.f) != EOF) return GQSA_ERR_SHAPE;     // trailing bytes
-    if (rowIndex[static_cast<size_t>(hd.N)] != hd.nnz_groups) return GQSA_ERR_SHAPE;
-    // the same consistency checks as for arrays handed in directly
-    return gqsa_import(rowIndex.data(), groups.data(), values.data(), scales.data(), zeros.data(), hd.N, hd.K,
-                       hd.G, hd.bits, out);
+        bool ok = true;
+        auto get = [&](void* p, size_t bytes) {
+            if (ok && bytes) ok = std::fread(p, 1, bytes, file.f) == bytes;
+        };
+        get(rowIndex.data(), rowIndex.size() * 4);
+        get(groups.data(), groups.size() * 4);
+        get(values.data(), values.size());
+        get(scales.data(), scales.size() * 2);
+        get(zeros.data(), zeros.size() * 2);
+        if (!ok) return GQSA_ERR_IO;                             // truncated
+        if (std::fgetc(file.f) != EOF) return GQSA_ERR_SHAPE;     // trailing bytes
+        if (rowIndex[static_cast<size_t>(hd.N)] != hd.nnz_groups) return GQSA_ERR_SHAPE;
+        // the same consistency checks as for arrays handed in directly
+        return gqsa_import(rowIndex.data(), groups.data(), values.data(), scales.data(), zeros.data(), hd.N, hd.K,
+                           hd.G, hd.bits, out);
+    });
 }
 
 void gqsa_free(gqsa_handle_t h)

@@ -7,6 +7,7 @@
 #include <cstdint>
 #include <cstdio>
 
+#include "gqsa_bench.h"
 #include "gqsa_internal.hpp"
 
 namespace {

@@ -495,20 +495,22 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
     st.heads += heads_total;
 }
 
-// Cross-workgroup carry chain (a row whose groups are spread over wavefronts of more than
-// one workgroup).  Every holder of a piece publishes its record with device-scope stores,
-// then reports to the chain's counter; the last one to report adds the pieces in worker
-// order (so the sum does not depend on arrival order) and writes the row.  All accesses to
-// the records and counters are device-scope atomics, ordered by program order plus a wait
-// for the stores to complete -- no cache write-back or invalidate is needed.
+// Cross-workgroup carry chain (a row whose groups are spread over wavefronts of three or more
+// workgroups).  Every holder of a piece publishes its record with device-scope stores, then
+// reports to the chain's counter; the last one to report adds the pieces in worker order (so
+// the sum does not depend on arrival order) and writes the row.  The report is a device-scope
+// acquire-release read-modify-write: the record stores of every reporter happen before its
+// report, and the last reporter's reads of the records happen after it has seen all the others'
+// reports -- the ordering is the language's, not an accident of how stores complete.  (This path
+// is rare -- rows longer than a workgroup's whole share -- so the cache write-back and invalidate
+// that the release and the acquire cost are paid by few wavefronts.)
 template <int NB>
 __device__ __forceinline__ void chain_arrive(const MatArgs& m, const int4* wave_info, int first)
 {
     const int4 head_info = wave_info[first];
     const int len = head_info.w;
-    const int old = __hip_atomic_fetch_add(&m.counters[first], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int old = __hip_atomic_fetch_add(&m.counters[first], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     if (old != len - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     for (int b = 0; b < NB; ++b) {
         const CarryRecord* r0 = &m.carry[first * kMaxRowsPerLaunch + b];
         const int heads0 = __hip_atomic_load(&r0->heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -640,7 +642,7 @@ __device__ __forceinline__ void fixup_matrix(const MatArgs& mo, const int4* wave
             __hip_atomic_store(&r->tail, own_tail[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&r->heads, heads, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the stores have completed
+        // (the reports below release these stores at device scope)
         if (pl.lead_mode == 3) chain_arrive<NB>(mo, wave_info, info.z);
         if (pl.head_mode == 3) chain_arrive<NB>(mo, wave_info, wave);
     }
@@ -1118,6 +1120,13 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;
+}
+
+bool stream_is_capturing(void* stream)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &st) != hipSuccess) return false;
+    return st != hipStreamCaptureStatusNone;
 }
 
 }  // namespace gqsa

@@ -101,5 +101,6 @@ gqsa_status_t device_upload(gqsa_matrix* m);
 void device_release(gqsa_matrix* m);
 gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,
                           void* stream);
+bool stream_is_capturing(void* stream);
 
 }  // namespace gqsa

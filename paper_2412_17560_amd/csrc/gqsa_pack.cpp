@@ -2,9 +2,10 @@
 // storage (paper Sec. 3.2) and construction of the device image.
 //
 //   - group pruning: weights are grouped along the row (K) dimension in runs of G, each
-//     group gets one saliency, the least salient groups of a row are dropped (Fig. 3);
-//     here the saliency is the group's sum of squares, because the Hessian metric of
-//     Eq. 4 needs calibration activations;
+//     group gets one saliency, the least salient groups of a row are dropped (Fig. 3); the
+//     saliency is the Hessian metric of Eq. 4 when the caller supplies diag(H^-1) (building
+//     H needs calibration activations, which is the caller's business), else the group's sum
+//     of squares;
 //   - quantisation of the kept groups: Eq. 1 (scale, zero-point) and Eq. 2 (codes);
 //   - storage: the BSR arrays rowIndex / groups / values of the Sec. 3.2 listing plus
 //     one fp16 scale and zero per stored group.
@@ -145,8 +146,10 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
     unsigned nthreads = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
     if (N * K < (1 << 20)) nthreads = 1;
     std::atomic<int64_t> next_row{0};
-    std::atomic<bool> bad{false};
-    auto work = [&]() {
+    std::atomic<bool> bad{false}, out_of_memory{false};
+    // (a worker thread must not let an exception escape: that would end the process)
+    auto work = [&]() noexcept {
+      try {
         std::vector<double> sal(kg);
         std::vector<int32_t> order(kg), kept;
         std::vector<uint8_t> q(G);
@@ -176,22 +179,28 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                 }
             }
         }
+      } catch (...) {
+        out_of_memory = true;
+      }
     };
     if (nthreads == 1) {
         work();
     } else {
         std::vector<std::thread> pool;
-        for (unsigned t = 0; t < nthreads; ++t) pool.emplace_back(work);
+        try {
+            pool.reserve(nthreads);
+            for (unsigned t = 0; t < nthreads; ++t) pool.emplace_back(work);
+        } catch (...) {
+            // no more threads to be had: the ones that started (or this one) do all the rows
+        }
+        if (pool.empty()) work();
         for (auto& t : pool) t.join();
     }
+    if (out_of_memory) return GQSA_ERR_ALLOC;
     if (bad) return GQSA_ERR_RANGE;
     return GQSA_OK;
 }
 
-// The partition pack/import choose: one workgroup per compute unit as soon as there are 256
-// blocks, and in a workgroup as many wavefronts (at most 16, at most one per block) as give
-// every wavefront about two blocks' worth of 16-element chunks -- matrices of a few MB are bound
-// by how many compute units pull on memory, not by how long a wavefront's run is.
 // Where the rows start in the group stream.  span_groups = 0: one after the other, row n at
 // rowIndex[n].  Otherwise the stream is cut into spans of span_groups positions (one per
 // workgroup) and a row that fits a span but not what is left of the current one starts at the next

@@ -1,11 +1,16 @@
 // y[b, n] = sum_k W^[n, k] x[b, k] for up to 16 activation rows at once on the matrix cores, from
 // the panel image (gqsa_panels.cpp): a panel's groups of one group-column, 16 rows x 16 weights
 // with the pruned ones zero, times the 16 x 16 activations under them, is one 16x16x16 product.
-// The dequantisation of Eq. 3 stays exact: the matrix cores multiply the integer codes q (exact
-// in fp16) by x with fp32 accumulation, and a second product with a matrix of ones gives the sum
-// of the 16 activations; scale and zero are applied to the two fp32 results per group,
-//     sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j),
-// so no weight is ever rounded to fp16.
+// The dequantisation of Eq. 3 stays exact -- no weight is ever rounded to fp16 -- in both forms
+// of the kernel (INTZ, chosen per matrix when the image is built):
+//   - every stored zero is an integer of at most 1024 in magnitude (what Eq. 1 yields): the zero
+//     is taken off the codes in fp16 before the product (q - z is an exact small integer there),
+//     the matrix cores multiply it by x with fp32 accumulation, the scale is applied to the sum:
+//         sum_j (q_j - z) s x_j  =  s * sum_j (q_j - z) x_j;
+//   - any other zero (Sec. 3.4 trains scale and zero freely): the matrix cores multiply the codes
+//     q themselves (exact in fp16) by x, a second product with a matrix of ones gives the sum of
+//     the 16 activations, and scale and zero are applied to the two fp32 results per group:
+//         sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -427,6 +432,11 @@ void panels_release(gqsa_matrix* m)
 gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, void* const* ys, int batch, void* stream)
 {
     if (n < 1 || n > kMaxMatricesPerLaunch || batch < 1 || batch > kPanelRows) return GQSA_ERR_UNSUPPORTED;
+    // the images belong to the GPU they were uploaded on
+    int dev = -1;
+    GQSA_HIP(hipGetDevice(&dev));
+    for (int i = 0; i < n; ++i)
+        if (ms[i]->device != dev) return GQSA_ERR_HIP;
     PanelTargets tgt{};
     const uint8_t* headers[kMaxMatricesPerLaunch];
     const uint8_t* data[kMaxMatricesPerLaunch];

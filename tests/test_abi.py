@@ -16,9 +16,16 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "gqsa.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(gqsa_[a-z0-9_]+)\s*\(", text)))
+    """Every function declared in include/*.h (gqsa.h: the product; gqsa_bench.h: the measuring instruments)."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(gqsa_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -198,3 +205,36 @@ def test_save_and_load_round_trip_and_damaged_files(tmp_path):
         assert status_of(gq.gqsa_load, path) == status, name
     assert status_of(gq.gqsa_load, str(tmp_path / "missing.gqsa")) == 9
     assert status_of(gq.gqsa_save, h, str(tmp_path / "no_such_dir" / "m.gqsa")) == 9
+
+
+def _balanced(n_rows, per_row):
+    return np.arange(n_rows + 1, dtype=np.int64) * per_row
+
+
+def test_default_partition_hand_table():
+    """The partition the library chooses by itself, against values worked out by hand from its
+    documented rule (include/gqsa.h, gqsa_set_partition)."""
+    dp = gq.gqsa_default_partition
+    assert dp(_balanced(1, 0), 4096) == (1, 1, 0)
+    assert dp(_balanced(3, 256), 4096) == (1, 3, 0)             # 3 tiles of 256 groups, one per wavefront
+    assert dp(_balanced(16, 128), 4096) == (2, 4, 4)            # 8 tiles; two rows per tile
+    assert dp(_balanced(17, 256), 4096) == (8, 4, 4)            # 17 workers -> 5 workgroups -> a multiple of 4
+    assert dp(_balanced(4096, 128), 4096) == (512, 4, 4)        # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront; no null group needed
+    assert dp(_balanced(11008, 128), 4096) == (1376, 4, 4)      # 11008x4096: 5504 tiles
+    assert dp(_balanced(8193, 256), 4096) == (2052, 4, 4)       # still one tile per worker
+    assert dp(_balanced(16384, 256), 4096) == (4096, 4, 4)      # the most workers
+    assert dp(_balanced(16385, 256), 4096) == (2052, 4, 8)      # beyond: two tiles per worker, 8193 workers
+    assert dp(_balanced(4096, 344), 11008) == (256, 8, 22)      # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
+    assert dp(_balanced(8191, 256), 8192) == (512, 8, 16)       # 448 T / K = 448 -> two per compute unit
+    assert dp(_balanced(28615, 256), 8192) == (768, 8, 38)      # at most three
+    assert dp(_balanced(4096, 256), 8192) == (256, 8, 16)       # 4096x8192 at S = 50 %
+    assert dp(_balanced(100, 256), 32768) == (28, 4, 4)         # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
+    assert dp(_balanced(2048, 32), 4096, G=128) == (256, 4, 4)  # 64 code bytes: a tile is one block, 1024 tiles
+    assert dp(_balanced(2048, 128), 4096, G=16, bits=8) == (256, 4, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
+    # rows that do not divide the spans: null groups keep them inside
+    assert dp(_balanced(4096, 179), 4096) == (820, 4, 4)        # S = 30 %: 5 rows per span of 1024, 820 spans
+    assert dp(_balanced(14336, 179), 4096) == (1304, 4, 8)      # 10024 tiles: 5 rows per span of 1024 would need 5 MB of null groups, 11 per span of 2048 need 1.4 MB
+    assert dp(_balanced(4096, 205), 4096) == (456, 4, 8)        # 4 rows per span of 1024: 2.9 MB; 9 per span of 2048: 1.2 MB
+    assert dp(_balanced(4096, 77), 4096) == (316, 4, 4)         # S = 70 %: 13 rows per span, 316 spans
+    # too many null groups (a row of 600 per span of 1024: 424 of 1024 positions empty): the plain deal
+    assert dp(_balanced(12000, 600), 16384) == (768, 8, 0)

@@ -487,14 +487,21 @@ def test_llama7b_layer_shapes_full_size(torch_cuda, idx):
 
 
 @pytest.mark.parametrize("sparsity", [0.0, 0.3, 0.5, 0.7])
-def test_llama3_8b_sparsity_sweep_full_size(torch_cuda, sparsity):
-    for idx, (name, N, K) in enumerate(gi.LLAMA3_8B_SHAPES):
-        if name == "gate_up_proj" and sparsity not in (0.0, 0.5):
-            continue                       # keep the run short: the largest shape at S=0 and S=50%
-        W = gi.dense_weight(N, K, seed=gi.config_seed(3, idx))
-        h = gq.gqsa_pack(W, 16, 4, sparsity)
-        c = oracle.pack(W, 16, 4, sparsity=sparsity)
-        check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(3, idx)))
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_llama3_8b_sparsity_sweep_full_size(torch_cuda, idx, sparsity):
+    """Every shape of the LLaMA-3-8B-like set at every sparsity of the sweep, at full size, with the
+    default partition (the launch configuration the benchmark times): the device image bit for
+    bit and every output against the oracle."""
+    name, N, K = gi.LLAMA3_8B_SHAPES[idx]
+    W = gi.dense_weight(N, K, seed=gi.config_seed(3, idx))
+    h = gq.gqsa_pack(W, 16, 4, sparsity)
+    c = oracle.pack(W, 16, 4, sparsity=sparsity)
+    info = gq.gqsa_info(h)
+    part = (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
+    assert part == gq.gqsa_default_partition(c.rowIndex, K)
+    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, *part)
+    check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(3, idx)))
+    gq.gqsa_free(h)
 
 
 @pytest.mark.parametrize("idx", [0, 1])
@@ -845,6 +852,28 @@ def test_w8_full_size(torch_cuda):
     h = gq.gqsa_pack(W, 16, 8, 0.5)
     c = oracle.pack(W, 16, 8, sparsity=0.5)
     check(torch_cuda, h, c, gi.activations(2, 4096, seed=gi.config_seed(5, 0)))
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_small_batch_4096x4096_wavefront_kernel_full_size(torch_cuda, bits):
+    """4096x4096 S50 with 1, 2, 4, 8 and 16 activation rows on the wavefront kernel (a handle
+    without the second image), default partition: every output of every row against the oracle,
+    every row identical whatever the batch size it was part of."""
+    torch = torch_cuda
+    N, K = 4096, 4096
+    seed = gi.config_seed(5, 0)
+    W = gi.dense_weight(N, K, seed=seed)
+    h = gq.gqsa_pack(W, 16, bits, 0.5)
+    c = oracle.pack(W, 16, bits, sparsity=0.5)
+    assert gq.gqsa_info(h)["panel_bytes"] == 0
+    x_np = gi.activations(16, K, seed=seed)
+    ref = oracle.gemv(c, x_np, threads=8)
+    y16 = run_gemv(torch, h, x_np)
+    for batch in (1, 2, 3, 4, 8, 16):
+        y = run_gemv(torch, h, x_np[:batch])
+        for b in range(batch):
+            assert oracle.rel_error(y[b], ref[b]) <= TOL, (batch, b)
+        assert np.array_equal(y.view(np.uint16), y16[:batch].view(np.uint16)), batch
 
 
 @pytest.mark.parametrize("bits", [4, 8])

@@ -39,7 +39,7 @@ def test_tiny_config_balanced(bits, sparsity):
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == c.nnzg
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == oracle.default_partition(c.rowIndex, 256, 16, bits)
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == gq.gqsa_default_partition(c.rowIndex, 256, 16, bits)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
 
 
@@ -191,7 +191,7 @@ def test_other_group_sizes(bits, G):
     assert_same_canonical(h, c)
     info = gq.gqsa_info(h)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(N, K, G, bits, c.nnzg, 1)
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == oracle.default_partition(c.rowIndex, K, G, bits)
+    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == gq.gqsa_default_partition(c.rowIndex, K, G, bits)
     for part in (None, (1, 1), (3, 1), (5, 3), (1, 16), (17, 2), (40, 16)):
         if part is not None:
             gq.gqsa_set_partition(h, *part)
