@@ -201,6 +201,27 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
                         void* hip_stream);
 
 /*
+ * gqsa_gemv for callers that cannot allocate device memory or let a library do so: code whose
+ * launches are being captured into a HIP graph, tight serving loops, harnesses that forbid it.
+ * Same arguments, same checks, same kernels (the wavefront kernel, whatever the batch) and the
+ * same bits in y as gqsa_gemv gives without a second image -- but nothing is allocated or freed
+ * by the call, and the fix-up workspace (carry records, arrival counters and meeting points of
+ * rows shared by wavefronts) is not the handle's: it is a fixed array inside the library's device
+ * code, 3 211 264 bytes (196 per wavefront worker, 16384 workers), of which every GPU that the
+ * library is used on holds one copy until the process ends.
+ *   - the handle must already be on the device (gqsa_upload): GQSA_ERR_UNSUPPORTED otherwise;
+ *   - a handle whose partition has more than 16384 wavefront workers (n_workgroups x
+ *     waves_per_workgroup of gqsa_info; no default partition has) is refused with GQSA_ERR_BUFSIZE
+ *     and a message on stderr;
+ *   - all calls on one GPU share the array, whatever the handle: calls that may overlap in time
+ *     on one GPU (different streams) race on it and give wrong results; calls on one stream are
+ *     ordered and safe.  The part of the array a call uses is cleared by a small kernel ahead of
+ *     the GEMV (no memset node, so the call can be captured).
+ */
+gqsa_status_t gqsa_gemv_static(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch,
+                               void* hip_stream);
+
+/*
  * Several matrices that share the activation vector -- q/k/v or gate/up of a decoder layer, the
  * way the paper's engine runs seven GEMVs per layer (Sec. 4.4) -- in ONE launch:
  * y_devs[i] = W^_i x for i < n_matrices (1..4).  The workgroups of the launch are dealt to the

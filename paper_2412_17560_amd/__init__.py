@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     gqsa_free,
     gqsa_gemv,
     gqsa_gemv_multi,
+    gqsa_gemv_static,
     gqsa_import,
     gqsa_info,
     gqsa_launch_floor,

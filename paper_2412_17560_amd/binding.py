@@ -71,6 +71,8 @@ def _lib():
     lib.gqsa_upload.argtypes = [vp]
     lib.gqsa_gemv.restype = C.c_int
     lib.gqsa_gemv.argtypes = [vp, vp, vp, i32, vp]
+    lib.gqsa_gemv_static.restype = C.c_int
+    lib.gqsa_gemv_static.argtypes = [vp, vp, vp, i32, vp]
     lib.gqsa_default_partition.restype = C.c_int
     lib.gqsa_default_partition.argtypes = [vp, i64, i64, i32, i32, C.POINTER(C.c_int32 * 3)]
     lib.gqsa_gemv_panels.restype = C.c_int
@@ -270,6 +272,16 @@ def gqsa_default_partition(rowIndex, K: int, G: int = 16, bits: int = 4):
     _check(_lib().gqsa_default_partition(C.c_void_p(ri.ctypes.data), ri.size - 1, K, G, bits, C.byref(out)),
            "gqsa_default_partition")
     return (int(out[0]), int(out[1]), int(out[2]))
+
+
+def gqsa_gemv_static(h: GqsaHandle, x, y, stream=None):
+    """gqsa_gemv without any allocation: y must be given, the handle must be on the device."""
+    info = gqsa_info(h)
+    if x.dim() != 2 or x.shape[1] != info["K"] or tuple(y.shape) != (x.shape[0], info["N"]):
+        raise ValueError("x must be [batch, K] and y [batch, N]")
+    _check(_lib().gqsa_gemv_static(h.ptr, _dev_ptr(x, "torch.float16", "x"), _dev_ptr(y, "torch.float16", "y"),
+                                   x.shape[0], _stream_ptr(stream)), "gqsa_gemv_static")
+    return y
 
 
 def gqsa_gemv(h: GqsaHandle, x, y=None, stream=None, panels: bool = False):

@@ -211,6 +211,16 @@ gqsa_status_t gqsa_gemv(gqsa_handle_t h, const void* x_dev, void* y_dev, int bat
     return gqsa::device_gemv(&h, 1, x_dev, &y_dev, batch, hip_stream);
 }
 
+gqsa_status_t gqsa_gemv_static(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch, void* hip_stream)
+{
+    if (!h || !x_dev || !y_dev) return GQSA_ERR_NULL;
+    if (batch < 1 || batch > gqsa::kMaxBatch) return GQSA_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(x_dev) & 15u) != 0) return GQSA_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(y_dev) & 1u) != 0) return GQSA_ERR_ALIGN;
+    if (!h->d_image) return GQSA_ERR_UNSUPPORTED;       // an upload allocates: the caller does it beforehand
+    return gqsa::device_gemv_static(h, x_dev, y_dev, batch, hip_stream);
+}
+
 gqsa_status_t gqsa_gemv_panels(gqsa_handle_t h, const void* x_dev, void* y_dev, int batch, void* hip_stream)
 {
     if (!h || !x_dev || !y_dev) return GQSA_ERR_NULL;

@@ -27,8 +27,19 @@
 #include <cstddef>
 #include <cstdint>
 #include <cstdio>
+#include <mutex>
 
 #include "gqsa_internal.hpp"
+
+// Fix-up workspace of gqsa_gemv_static (at the end of this file), for callers that must not
+// allocate: carry records, arrival counters and meeting points for up to kScratchWorkers wavefront
+// workers -- the most a default partition deals to -- at 196 bytes each.  Every GPU the library
+// runs on holds its own copy (3.1 MiB) from the first use of the library to the end of the process.
+// In host code the name stands for the symbol, not for memory a kernel could address: the device
+// address is asked for once per GPU (scratch_address) and only that pointer is handed to kernels.
+constexpr int kScratchWorkers = 16384;
+constexpr size_t kScratchBytes = static_cast<size_t>(kScratchWorkers) * 196;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace gqsa {
 namespace {
@@ -954,6 +965,8 @@ constexpr size_t carry_workspace_bytes(int n_waves)
         }                                                                                   \
     } while (0)
 
+gqsa_status_t scratch_address(int dev, void** out);      // (with the static workspace, below)
+
 }  // namespace
 
 gqsa_status_t device_upload(gqsa_matrix* m)
@@ -991,6 +1004,9 @@ gqsa_status_t device_upload(gqsa_matrix* m)
     m->d_image = img;
     m->d_carry = carry;
     m->device = dev;
+    // (the set-up call of a GPU is also where the address of the static workspace on it is learnt)
+    void* unused = nullptr;
+    (void)scratch_address(dev, &unused);
     return GQSA_OK;
 }
 
@@ -1034,7 +1050,7 @@ int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb, size_
 // One launch: the kernel for nb activation rows (1, 2, 4 or 8), of which the caller has `rows`
 // (nb, or one fewer), times n_mats matrices that share x and the wavefronts per workgroup.
 gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint16_t* const* ys, int nb, int rows, int wpw,
-                     hipStream_t s)
+                     void* workspace, hipStream_t s)
 {
     const gqsa_matrix* m0 = ms[0];
     int kgp = 0;
@@ -1056,8 +1072,8 @@ gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint
         MatArgs& o = d.out;
         o.row_of_rank = m->n_empty ? reinterpret_cast<const int32_t*>(img + m->map.row_of_rank) : nullptr;
         o.empty_rows = reinterpret_cast<const int32_t*>(img + m->map.empty_rows);
-        o.carry = static_cast<CarryRecord*>(m->d_carry);
-        uint8_t* ws = static_cast<uint8_t*>(m->d_carry);
+        uint8_t* ws = static_cast<uint8_t*>(workspace ? workspace : m->d_carry);
+        o.carry = reinterpret_cast<CarryRecord*>(ws);
         o.counters = reinterpret_cast<int*>(ws + counters_offset(m->n_waves));
         o.slots = reinterpret_cast<unsigned long long*>(ws + slots_offset(m->n_waves));
         o.y = ys[i];
@@ -1075,7 +1091,7 @@ gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint
 }  // namespace
 
 gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,
-                          void* stream)
+                          void* stream, void* workspace)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
     const gqsa_matrix* m0 = ms[0];
@@ -1109,17 +1125,77 @@ gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, voi
         const int together = launch_waves_per_workgroup(ms, n_mats, nb, lds);
         if (together > 0) {
             // one launch for all the matrices
-            if (gqsa_status_t st = launch(ms, n_mats, xb, yb, nb, rows, together, s)) return st;
+            if (gqsa_status_t st = launch(ms, n_mats, xb, yb, nb, rows, together, workspace, s)) return st;
         } else {
             for (int i = 0; i < n_mats; ++i) {
                 const int wpw = launch_waves_per_workgroup(ms + i, 1, nb, lds);
-                if (gqsa_status_t st = launch(ms + i, 1, xb, yb + i, nb, rows, wpw, s)) return st;
+                if (gqsa_status_t st = launch(ms + i, 1, xb, yb + i, nb, rows, wpw, workspace, s)) return st;
             }
         }
         done += rows;
     }
     GQSA_HIP(hipGetLastError());
     return GQSA_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same GEMV for callers that must not allocate (code under stream capture, serving loops,
+// harnesses that forbid it): the fix-up workspace -- carry records, arrival counters, meeting
+// points -- does not come from the handle's allocation but from an array that is part of the
+// library's device code, one copy per GPU for the life of the process.
+static_assert(kScratchBytes == carry_workspace_bytes(kScratchWorkers), "size of the static workspace");
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch[kMaxDevices];               // device address of `scratch` on every GPU seen so far
+std::mutex g_scratch_mutex;
+
+// The array's name is a host-side stand-in, not an address a kernel can use: the address on
+// the current GPU is asked for once per GPU and kept.
+gqsa_status_t scratch_address(int dev, void** out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return GQSA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch[dev]) {
+        void* p = nullptr;
+        GQSA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return GQSA_ERR_HIP;
+        g_scratch[dev] = p;
+    }
+    *out = g_scratch[dev];
+    return GQSA_OK;
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t* p, unsigned n)
+{
+    for (unsigned i = blockIdx.x * 256u + threadIdx.x; i < n; i += gridDim.x * 256u) p[i] = 0u;
+}
+
+}  // namespace
+
+gqsa_status_t device_gemv_static(gqsa_matrix* m, const void* x, void* y, int batch, void* stream)
+{
+    if (m->n_waves > kScratchWorkers) {
+        std::fprintf(stderr, "libgqsa: gqsa_gemv_static: the handle's partition has %d wavefront workers, the static "
+                             "workspace holds %d\n", m->n_waves, kScratchWorkers);
+        return GQSA_ERR_BUFSIZE;
+    }
+    int dev = -1;
+    GQSA_HIP(hipGetDevice(&dev));
+    if (m->device != dev) return GQSA_ERR_HIP;
+    void* ws = nullptr;
+    if (gqsa_status_t st = scratch_address(dev, &ws)) return st;
+    if (m->needs_fixup) {
+        // The array keeps what the last call left.  A call that ran to its end leaves counters and
+        // meeting points at zero, one that was cut short need not: clear this call's part of them
+        // (with a kernel: a memset node must not end up in a captured graph).
+        const size_t first = counters_offset(m->n_waves), bytes = carry_workspace_bytes(m->n_waves) - first;
+        const unsigned words = static_cast<unsigned>(bytes / 4);
+        hipLaunchKernelGGL(zero_words_kernel, dim3((words + 255u) / 256u), dim3(256), 0, static_cast<hipStream_t>(stream),
+                           reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(ws) + first), words);
+    }
+    return device_gemv(&m, 1, x, &y, batch, stream, ws);
 }
 
 bool stream_is_capturing(void* stream)

@@ -99,8 +99,10 @@ gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, vo
 // device side (gqsa_gemv.hip)
 gqsa_status_t device_upload(gqsa_matrix* m);
 void device_release(gqsa_matrix* m);
+// (workspace: nullptr = every handle's own carry workspace)
 gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,
-                          void* stream);
+                          void* stream, void* workspace = nullptr);
+gqsa_status_t device_gemv_static(gqsa_matrix* m, const void* x, void* y, int batch, void* stream);
 bool stream_is_capturing(void* stream);
 
 }  // namespace gqsa

@@ -31,7 +31,8 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = C.CDLL(gq.library_path())
     names = declared_functions()
-    assert "gqsa_pack" in names and "gqsa_gemv" in names and len(names) >= 12
+    assert "gqsa_pack" in names and "gqsa_gemv" in names and "gqsa_gemv_static" in names
+    assert "gqsa_stream_read" in names and len(names) >= 25
     for name in names:
         assert hasattr(lib, name), f"libgqsa.so does not export {name}"
 
@@ -115,6 +116,46 @@ def test_gemv_host_side_checks_need_no_gpu():
     assert lib.gqsa_gemv(h.ptr, fake, fake, 0, None) == 3
     assert lib.gqsa_gemv(h.ptr, fake, fake, 17, None) == 3
     assert lib.gqsa_gemv(h.ptr, C.c_void_p(0x1008), fake, 1, None) == 8
+
+
+def test_gemv_static_host_side_checks_need_no_gpu():
+    """The entry point that allocates nothing never uploads: a handle that is not on the device is refused."""
+    W = gi.dense_weight(8, 64, seed=1)
+    h = gq.gqsa_pack(W, 16, 4, 0.5)
+    lib = binding._lib()
+    fake = C.c_void_p(0x1000)
+    assert lib.gqsa_gemv_static(None, fake, fake, 1, None) == 1
+    assert lib.gqsa_gemv_static(h.ptr, fake, fake, 0, None) == 3
+    assert lib.gqsa_gemv_static(h.ptr, fake, fake, 17, None) == 3
+    assert lib.gqsa_gemv_static(h.ptr, C.c_void_p(0x1008), fake, 1, None) == 8
+    assert lib.gqsa_gemv_static(h.ptr, fake, fake, 1, None) == 3       # not uploaded
+    assert gq.gqsa_info(h)["on_device"] == 0
+
+
+@pytest.mark.skipif(bool(os.environ.get("GQSA_LIBRARY")),
+                    reason="a sanitizer's operator new ends the process on an impossible request instead of throwing")
+def test_allocation_failure_is_a_status_not_an_exception():
+    """A device image far beyond the address space (2^31 tiles per span x 4096 spans): the failed
+    allocation inside the library comes back as GQSA_ERR_ALLOC and the handle stays usable."""
+    W = gi.dense_weight(8, 64, seed=1)
+    h = gq.gqsa_pack(W, 16, 4, 0.5)
+    before = gq.gqsa_export_device_blob(h)
+    assert status_of(gq.gqsa_set_partition_aligned, h, 2**31 - 1, 4096, 16) == 5
+    assert gq.gqsa_export_device_blob(h) == before
+    assert gq.gqsa_info(h)["span_tiles"] != 2**31 - 1
+
+
+def test_default_partition_entry_checks_its_arguments():
+    lib = binding._lib()
+    ri = np.array([0, 2, 3], dtype=np.int32)
+    out = (C.c_int32 * 3)()
+    assert lib.gqsa_default_partition(None, 2, 64, 16, 4, C.byref(out)) == 1
+    assert lib.gqsa_default_partition(C.c_void_p(ri.ctypes.data), 2, 64, 16, 4, None) == 1
+    assert lib.gqsa_default_partition(C.c_void_p(ri.ctypes.data), 2, 64, 16, 5, C.byref(out)) == 3
+    assert lib.gqsa_default_partition(C.c_void_p(ri.ctypes.data), 2, 24, 16, 4, C.byref(out)) == 2
+    bad = np.array([0, 9, 3], dtype=np.int32)                      # 9 groups in a row of 4 columns
+    assert lib.gqsa_default_partition(C.c_void_p(bad.ctypes.data), 2, 64, 16, 4, C.byref(out)) == 2
+    assert gq.gqsa_default_partition(ri, 64) == (1, 1, 0)
 
 
 def test_gemv_multi_host_side_checks_need_no_gpu():
