@@ -103,6 +103,29 @@ gqsa_status_t gqsa_pack_hessian(const float* W_host, int64_t N, int64_t K, int G
                                 double sparsity, const float* hinv_diag, gqsa_handle_t* out);
 
 /*
+ * The same offline pre-processing on the GPU (Sec. 3.2, Fig. 3; Eq. 1-2; Eq. 4): saliency of every
+ * group, pruning of every row, quantisation of the kept groups and the blocks of the device image
+ * are computed by HIP kernels from a matrix that already lies in device memory -- the same
+ * arithmetic as gqsa_pack / gqsa_pack_rows / gqsa_pack_hessian operation for operation, hence
+ * the same bits in the canonical arrays and in the device image.
+ *   W_dev          [device] row-major fp32 [N,K], finite (GQSA_ERR_RANGE otherwise)
+ *   sparsity       as in gqsa_pack; ignored when keep_per_row is given
+ *   keep_per_row   [host] int32[N] as in gqsa_pack_rows, or NULL
+ *   hinv_diag_dev  [device] fp32[K] as in gqsa_pack_hessian (finite, > 0: GQSA_ERR_RANGE
+ *                  otherwise), or NULL for the sum-of-squares saliency
+ *   hip_stream     the kernels and copies run on it; the call waits for it before it returns
+ *   out            [host] receives a handle that is already on the device (the current one);
+ *                  its canonical arrays and its host copy of the image have been copied back,
+ *                  so export, save and info work as for a host-packed handle
+ * Allocates device memory (the image, the workspace, temporaries of about 14 bytes per stored
+ * group) and synchronises: not for use under stream capture.  The default partition is chosen
+ * as by gqsa_pack; gqsa_set_partition is not possible afterwards (the handle is uploaded).
+ */
+gqsa_status_t gqsa_pack_device(const float* W_dev, int64_t N, int64_t K, int G, int bits, double sparsity,
+                               const int32_t* keep_per_row, const float* hinv_diag_dev, void* hip_stream,
+                               gqsa_handle_t* out);
+
+/*
  * Build a handle from existing canonical arrays (the BSR listing of Sec. 3.2 plus the
  * per-group parameters of Eq. 1, which Sec. 3.4 fine-tunes freely -- so scale and zero
  * are arbitrary finite fp16 values here).  All arrays [host]; they are copied.

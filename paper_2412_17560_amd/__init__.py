@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     gqsa_launch_floor,
     gqsa_load,
     gqsa_pack,
+    gqsa_pack_device,
     gqsa_pack_hessian,
     gqsa_pack_rows,
     gqsa_save,

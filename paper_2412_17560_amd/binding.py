@@ -53,6 +53,8 @@ def _lib():
     lib.gqsa_pack_rows.argtypes = [vp, i64, i64, i32, i32, vp, C.POINTER(vp)]
     lib.gqsa_pack_hessian.restype = C.c_int
     lib.gqsa_pack_hessian.argtypes = [vp, i64, i64, i32, i32, C.c_double, vp, C.POINTER(vp)]
+    lib.gqsa_pack_device.restype = C.c_int
+    lib.gqsa_pack_device.argtypes = [vp, i64, i64, i32, i32, C.c_double, vp, vp, vp, C.POINTER(vp)]
     lib.gqsa_save.restype = C.c_int
     lib.gqsa_save.argtypes = [vp, C.c_char_p]
     lib.gqsa_load.restype = C.c_int
@@ -148,6 +150,27 @@ def gqsa_pack_hessian(W: np.ndarray, hinv_diag: np.ndarray, G: int = 16, bits: i
     out = C.c_void_p()
     _check(_lib().gqsa_pack_hessian(_np_ptr(W), W.shape[0], W.shape[1], G, bits, float(sparsity),
                                     _np_ptr(d), C.byref(out)), "gqsa_pack_hessian")
+    return GqsaHandle(out.value)
+
+
+def gqsa_pack_device(W, G: int = 16, bits: int = 4, sparsity: float = 0.5, keep_per_row=None, hinv_diag=None,
+                     stream=None) -> GqsaHandle:
+    """gqsa_pack / gqsa_pack_rows / gqsa_pack_hessian on the GPU: W a float32 device tensor [N, K],
+    hinv_diag a float32 device tensor [K] or None, keep_per_row a host int32 array [N] or None."""
+    if W.dim() != 2:
+        raise ValueError("W must be [N, K]")
+    keep = None
+    if keep_per_row is not None:
+        keep = np.ascontiguousarray(keep_per_row, dtype=np.int32)
+        if keep.shape != (W.shape[0],):
+            raise ValueError("keep_per_row must be [N]")
+    if hinv_diag is not None and tuple(hinv_diag.shape) != (W.shape[1],):
+        raise ValueError("hinv_diag must be [K]")
+    out = C.c_void_p()
+    _check(_lib().gqsa_pack_device(_dev_ptr(W, "torch.float32", "W"), W.shape[0], W.shape[1], G, bits, float(sparsity),
+                                   _np_ptr(keep) if keep is not None else None,
+                                   _dev_ptr(hinv_diag, "torch.float32", "hinv_diag") if hinv_diag is not None else None,
+                                   _stream_ptr(stream), C.byref(out)), "gqsa_pack_device")
     return GqsaHandle(out.value)
 
 

@@ -15,7 +15,8 @@ LIB = os.environ.get("GQSA_LIBRARY") or os.path.join(HERE, "libgqsa.so")
 HOST_ONLY = bool(os.environ.get("GQSA_LIBRARY"))
 SANITIZED_LIB = os.path.join(OBJ, "libgqsa_host_asan.so")
 
-SOURCES = ["gqsa_pack.cpp", "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_panel_kernel.hip", "gqsa_baselines.hip"]
+SOURCES = ["gqsa_pack.cpp", "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_panel_kernel.hip", "gqsa_pack_device.hip",
+           "gqsa_baselines.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wextra", "-Wno-unused-parameter"]
@@ -55,7 +56,7 @@ def _compile(src: str) -> str:
 
 def build() -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB, "-lpthread"]
     r = subprocess.run(cmd, capture_output=True, text=True)

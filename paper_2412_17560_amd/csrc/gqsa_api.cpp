@@ -113,6 +113,29 @@ gqsa_status_t gqsa_pack_hessian(const float* W_host, int64_t N, int64_t K, int G
     return pack_any(W_host, N, K, G, bits, nullptr, sparsity, hinv_diag, out);
 }
 
+gqsa_status_t gqsa_pack_device(const float* W_dev, int64_t N, int64_t K, int G, int bits, double sparsity,
+                               const int32_t* keep_per_row, const float* hinv_diag_dev, void* hip_stream,
+                               gqsa_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!W_dev || !out) return GQSA_ERR_NULL;
+    if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
+    if (!keep_per_row && !(sparsity >= 0.0 && sparsity <= 1.0)) return GQSA_ERR_RANGE;
+    if ((reinterpret_cast<uintptr_t>(W_dev) & 3u) != 0 || (reinterpret_cast<uintptr_t>(hinv_diag_dev) & 3u) != 0)
+        return GQSA_ERR_ALIGN;
+    return guarded([&]() -> gqsa_status_t {
+        std::unique_ptr<gqsa_matrix> m(new gqsa_matrix);
+        m->N = N; m->K = K; m->G = G; m->bits = bits;
+        if (gqsa_status_t st = gqsa::row_pointers(m.get(), keep_per_row, sparsity)) return st;
+        if (gqsa_status_t st = gqsa::pack_on_device(W_dev, hinv_diag_dev, m.get(), hip_stream)) {
+            gqsa::device_release(m.get());
+            return st;
+        }
+        *out = m.release();
+        return GQSA_OK;
+    });
+}
+
 gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const uint8_t* values,
                           const uint16_t* scales_f16, const uint16_t* zeros_f16,
                           int64_t N, int64_t K, int G, int bits, gqsa_handle_t* out)

@@ -969,7 +969,7 @@ gqsa_status_t scratch_address(int dev, void** out);      // (with the static wor
 
 }  // namespace
 
-gqsa_status_t device_upload(gqsa_matrix* m)
+gqsa_status_t device_upload(gqsa_matrix* m, void* filled_image)
 {
     int kgp = 0;
     if (!pick(m, 1, &kgp)) return GQSA_ERR_UNSUPPORTED;   // K/16 above 2048: x does not fit the LDS layout
@@ -985,19 +985,19 @@ gqsa_status_t device_upload(gqsa_matrix* m)
             GQSA_HIP(hipFuncSetAttribute(v.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
                                          static_cast<int>(lds_bytes(kgp, nb))));
     }
-    void* img = nullptr;
+    void* img = filled_image;
     void* carry = nullptr;
-    GQSA_HIP(hipMalloc(&img, m->image.size()));
+    if (!img) GQSA_HIP(hipMalloc(&img, m->image.size()));
     // carry records (per worker and activation row), one arrival counter per worker (padded to a
     // multiple of two), then the meeting points of two-worker chains (per worker and row)
     const size_t carry_bytes = carry_workspace_bytes(m->n_waves);
     hipError_t e = hipMalloc(&carry, carry_bytes);
-    if (e == hipSuccess) e = hipMemcpy(img, m->image.data(), m->image.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess && !filled_image) e = hipMemcpy(img, m->image.data(), m->image.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(carry, 0, carry_bytes);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         std::fprintf(stderr, "libgqsa: upload failed: %s\n", hipGetErrorString(e));
-        (void)hipFree(img);
+        if (!filled_image) (void)hipFree(img);      // (a caller's image stays the caller's on failure)
         (void)hipFree(carry);
         return GQSA_ERR_HIP;
     }

@@ -8,7 +8,8 @@
 
 namespace gqsa {
 
-gqsa_status_t device_upload(gqsa_matrix*) { return GQSA_ERR_HIP; }
+gqsa_status_t device_upload(gqsa_matrix*, void*) { return GQSA_ERR_HIP; }
+gqsa_status_t pack_on_device(const float*, const float*, gqsa_matrix*, void*) { return GQSA_ERR_HIP; }
 void device_release(gqsa_matrix*) {}
 gqsa_status_t device_gemv(gqsa_matrix* const*, int, const void*, void* const*, int, void*, void*) { return GQSA_ERR_HIP; }
 gqsa_status_t device_gemv_static(gqsa_matrix*, const void*, void*, int, void*) { return GQSA_ERR_HIP; }

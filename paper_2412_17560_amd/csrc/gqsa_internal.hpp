@@ -88,7 +88,13 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          gqsa_matrix* m);
 int64_t place_rows(const gqsa_matrix& m, int64_t span_groups, std::vector<int64_t>* row_pos);
 void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles);
-gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles);
+gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles,
+                          bool fill_blocks = true, std::vector<int64_t>* row_pos_out = nullptr);
+int64_t balanced_keep(int64_t groups_per_row, double sparsity);
+gqsa_status_t row_pointers(gqsa_matrix* m, const int32_t* keep_per_row, double sparsity);
+
+// GPU packer (gqsa_pack_device.hip)
+gqsa_status_t pack_on_device(const float* W_dev, const float* hinv_dev, gqsa_matrix* m, void* stream);
 
 // many-row image (gqsa_panels.cpp) and its kernel (gqsa_panel_kernel.hip)
 gqsa_status_t build_panels(gqsa_matrix* m);
@@ -97,7 +103,7 @@ void panels_release(gqsa_matrix* m);
 gqsa_status_t panels_gemm(const gqsa_matrix* const* ms, int n, const void* x, void* const* ys, int batch, void* stream);
 
 // device side (gqsa_gemv.hip)
-gqsa_status_t device_upload(gqsa_matrix* m);
+gqsa_status_t device_upload(gqsa_matrix* m, void* filled_image = nullptr);   // (filled_image: a device copy of m->image that the handle takes over)
 void device_release(gqsa_matrix* m);
 // (workspace: nullptr = every handle's own carry workspace)
 gqsa_status_t device_gemv(gqsa_matrix* const* ms, int n_mats, const void* x, void* const* ys, int batch,

@@ -103,6 +103,8 @@ bool select_row(const float* wrow, const float* hinv_diag, int64_t kg, int G, in
     return true;
 }
 
+}  // namespace
+
 int64_t balanced_keep(int64_t kg, double sparsity)
 {
     double drop = std::floor(sparsity * static_cast<double>(kg) + 0.5);
@@ -110,7 +112,23 @@ int64_t balanced_keep(int64_t kg, double sparsity)
     return kg - static_cast<int64_t>(drop);
 }
 
-}  // namespace
+// Row pointers from the kept count of every row (keep_per_row, or the same count for every row
+// from the sparsity).
+gqsa_status_t row_pointers(gqsa_matrix* m, const int32_t* keep_per_row, double sparsity)
+{
+    const int64_t kg = m->K / m->G;
+    m->rowIndex.assign(static_cast<size_t>(m->N) + 1, 0);
+    const int64_t uniform_keep = keep_per_row ? -1 : balanced_keep(kg, sparsity);
+    int64_t total = 0;
+    for (int64_t n = 0; n < m->N; ++n) {
+        const int64_t keep = keep_per_row ? keep_per_row[n] : uniform_keep;
+        if (keep < 0 || keep > kg) return GQSA_ERR_RANGE;
+        total += keep;
+        if (total > std::numeric_limits<int32_t>::max()) return GQSA_ERR_SHAPE;
+        m->rowIndex[n + 1] = static_cast<int32_t>(total);
+    }
+    return GQSA_OK;
+}
 
 gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          const int32_t* keep_per_row, double sparsity, const float* hinv_diag,
@@ -123,18 +141,9 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
     const int cb = G * bits / 8;
     m->N = N; m->K = K; m->G = G; m->bits = bits;
     try {
-        m->rowIndex.assign(static_cast<size_t>(N) + 1, 0);
+        if (gqsa_status_t st = row_pointers(m, keep_per_row, sparsity)) return st;
     } catch (const std::bad_alloc&) { return GQSA_ERR_ALLOC; }
-
-    const int64_t uniform_keep = keep_per_row ? -1 : balanced_keep(kg, sparsity);
-    int64_t total = 0;
-    for (int64_t n = 0; n < N; ++n) {
-        const int64_t keep = keep_per_row ? keep_per_row[n] : uniform_keep;
-        if (keep < 0 || keep > kg) return GQSA_ERR_RANGE;
-        total += keep;
-        if (total > std::numeric_limits<int32_t>::max()) return GQSA_ERR_SHAPE;
-        m->rowIndex[n + 1] = static_cast<int32_t>(total);
-    }
+    const int64_t total = m->nnzg();
     try {
         m->groups.assign(total, 0);
         m->values.assign(static_cast<size_t>(total) * cb, 0);
@@ -317,7 +326,10 @@ void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_w
 // group-column itself, with that flag.  4-bit code words are nibble-permuted so that one AND per pair of
 // elements yields a packed fp16 pair: word h of a group holds elements 8h..8h+7, element 8h+2m
 // at bits 4m and element 8h+2m+1 at bits 16+4m.
-gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles)
+// (fill_blocks = false leaves the blocks empty -- the GPU packer writes them -- and row_pos_out,
+// if given, receives the first stream position of every row.)
+gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles, bool fill_blocks,
+                          std::vector<int64_t>* row_pos_out)
 {
     if (n_workgroups < 0 || n_workgroups > kMaxWorkgroups || span_tiles < 0) return GQSA_ERR_RANGE;
     if (n_workgroups == 0 && span_tiles == 0) return GQSA_ERR_RANGE;
@@ -401,9 +413,10 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
         const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * slots_per_group) << 4) | (head[static_cast<size_t>(pos)] ? 1 : 0));
         std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
     };
-    for (int64_t n = 0; n < m->N; ++n)
-        for (int64_t g = m->rowIndex[n]; g < m->rowIndex[n + 1]; ++g)
-            put_group(g, row_pos[static_cast<size_t>(n)] + (g - m->rowIndex[n]));
+    if (fill_blocks)
+        for (int64_t n = 0; n < m->N; ++n)
+            for (int64_t g = m->rowIndex[n]; g < m->rowIndex[n + 1]; ++g)
+                put_group(g, row_pos[static_cast<size_t>(n)] + (g - m->rowIndex[n]));
 
     // Per worker: {rank_base, tail_closed + 2 * lead_len, lead_first, chain_len}.  (A null group
     // between two rows counts as part of the row before it.)
@@ -457,6 +470,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     if (!empty.empty())
         std::memcpy(img.data() + map.empty_rows, empty.data(), empty.size() * 4);
 
+    if (row_pos_out) row_pos_out->swap(row_pos);
     m->image.swap(img);
     m->map = map;
     m->n_workgroups = n_workgroups;
