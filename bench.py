@@ -200,7 +200,7 @@ def main():
         "eager_ms_per_step": round(eager_ms / args.steps, 6),
         "pool_build_s": round(t_build, 1),
     }
-    # dominant kernel: gqsa_gemv_kernel<Fmt<4, 1>, KGP, 1>; a launch covers one call, or the calls of a
+    # dominant kernel: gqsa_gemv_kernel<Fmt<4, 1, 0>, KGP, 1>; a launch covers one call, or the calls of a
     # layer that share x (q/k/v, gate/up).  Average launch duration is the event-timed region
     # divided by the launches in it (so it contains the gaps between dependent kernels); bytes are
     # the algorithmic bytes of the calls a launch covers.
@@ -219,7 +219,7 @@ def main():
         pass
     out["roofline"] = {
         "bound": "hbm",
-        "kernel": "gqsa_gemv_kernel<Fmt<4, 1>, KGP, 1>",
+        "kernel": "gqsa_gemv_kernel<Fmt<4, 1, 0>, KGP, 1>",
         "achieved": round(achieved, 2),
         "peak": HBM_PEAK_GBPS,
         "unit": "GB/s",
@@ -385,7 +385,7 @@ def main():
                 inf = gq.gqsa_info(hs[0])
                 row = {"shape": f"{N}x{K}", "bits": bits, "S": sparsity, "G": G}
                 row.update(rate(inf["algorithmic_bytes"], us))
-                row["partition"] = [inf["n_workgroups"], inf["waves_per_workgroup"], inf["span_tiles"]]
+                row["partition"] = list(gq.gqsa_partition(hs[0]))
                 rows.append(row)
                 for h in hs:
                     gq.gqsa_free(h)

@@ -54,7 +54,7 @@ typedef struct {
     int32_t bits;               /* code width */
     int64_t nnz_groups;         /* stored groups = rowIndex[N] */
     int64_t values_bytes;       /* bytes of the canonical `values` array */
-    int64_t n_blocks;           /* 64-group blocks of the device stream (null groups included) */
+    int64_t n_blocks;           /* blocks of the device stream (tile_lanes positions each, null groups included) */
     int32_t n_workgroups;       /* workgroups the group stream is dealt to */
     int32_t waves_per_workgroup;/* wavefront workers per workgroup */
     int32_t needs_fixup;        /* 1 if some row is shared by two or more wavefront workers */
@@ -67,6 +67,10 @@ typedef struct {
                                    <= 1024: its kernel then subtracts the zero from the codes (exactly, in fp16)
                                    before the product instead of from the product's sum afterwards */
     int64_t panel_bytes;        /* size of the second image built by gqsa_build_panels, 0 without one */
+    int32_t tile_blocks;        /* blocks per tile of the device stream */
+    int32_t tile_lanes;         /* stream positions per block: the lanes of a wavefront that take a group (64, or 32..60) */
+    int32_t span_per_worker;    /* 1 if a span is one wavefront worker's run (rows never straddle workers), 0 if a workgroup's */
+    int32_t reserved0;
 } gqsa_info_t;
 
 /*
@@ -141,23 +145,36 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
  * wavefront workers and rebuild the host copy of the device image.  Only before the handle is
  * uploaded.  The stream is cut into tiles of 4 blocks of 64 groups (2 blocks with 32 code bytes
  * per group, 1 with 64); worker w owns the tiles floor(w T / W) .. floor((w+1) T / W) - 1 of the
- * T tiles, W being the worker count.  The default chosen by pack/import/load, by size: for K up
- * to 4096 (or fewer than 2048 tiles) one tile per worker (at most 16384 workers; more tiles per
- * worker beyond) in workgroups of 4 wavefronts, the workgroup count rounded up to a multiple of
- * 4; for larger K workgroups of 8 wavefronts, 256, 512 or 768 of them (one to three per compute
- * unit of an MI355X): the multiple of 256 nearest to 448 T / K.  If some row would then lie in
- * two workgroups and 2 MiB of null groups or less keep every row inside one, the default is the
- * aligned form below with the same wavefronts per workgroup and: small shapes -- spans of 4 t
- * tiles, t the tiles per worker (or one more, if that takes too many null groups or more than
- * 16384 workers), the workgroup count rounded up to a multiple of 4; large shapes -- the same
- * 256, 512 or 768 workgroups and the smallest span that holds the rows. */
+ * T tiles, W being the worker count.
+ *
+ * The default chosen by pack/import/load (Sec. 3.5's task-centric split: a worker's share is a
+ * count of stored groups, not of rows):
+ *  (1) rows kept inside the workers' runs, if empty positions amounting to at most an eighth of
+ *      the stored groups and at most 16384 workers achieve that (gqsa_set_partition_rows below):
+ *      of the tile shapes the kernel has (for G = 16: 3..6 blocks with 32, 36, .. 64 lanes in use;
+ *      else the format's own block count with 64 lanes) and 1..4 tiles per worker, among those
+ *      within 1/16 of the stored groups of the fewest empty positions: the fewest tiles per
+ *      worker, then the fewest lane slots (workers x tiles x blocks), then the block count nearest
+ *      to 4.  Workgroups of 4 wavefronts for K up to 4096, of 8 beyond, their count rounded up to
+ *      a multiple of 4.  Matrices pruned to the same count in every row take this form.
+ *  (2) otherwise by size: for K up to 4096 (or fewer than 2048 tiles) one tile per worker (at
+ *      most 16384 workers; more tiles per worker beyond) in workgroups of 4 wavefronts, the
+ *      workgroup count rounded up to a multiple of 4; for larger K workgroups of 8 wavefronts,
+ *      256, 512 or 768 of them (one to three per compute unit of an MI355X): the multiple of 256
+ *      nearest to 448 T / K.  If some row would then lie in two workgroups and 2 MiB of null
+ *      groups or less keep every row inside one, the aligned form below with the same wavefronts
+ *      per workgroup and: small shapes -- spans of 4 t tiles, t the tiles per worker (or one
+ *      more, if that takes too many null groups or more than 16384 workers), the workgroup count
+ *      rounded up to a multiple of 4; large shapes -- the same 256, 512 or 768 workgroups and the
+ *      smallest span that holds the rows. */
 gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_per_workgroup);
 
 /* That default, for a matrix known by its row pointers alone (host only, no handle is built):
- * out[3] = {n_workgroups, waves_per_workgroup, span_tiles} (span_tiles as in
- * gqsa_set_partition_aligned, 0 for the plain deal).  rowIndex [host] int32[N+1] as in gqsa_import. */
+ * out[6] = {n_workgroups, waves_per_workgroup, span_tiles, tile_blocks, tile_lanes, span_per_worker}
+ * (span_tiles as in gqsa_set_partition_aligned / tiles_per_worker of gqsa_set_partition_rows, 0
+ * for the plain deal).  rowIndex [host] int32[N+1] as in gqsa_import. */
 gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t K, int G, int bits,
-                                     int32_t out[3]);
+                                     int32_t out[6]);
 
 /*
  * Same, with the rows kept inside the workgroups' shares (a row shared by two workgroups costs
@@ -173,6 +190,24 @@ gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t
  */
 gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_workgroups,
                                          int waves_per_workgroup);
+
+/*
+ * Same, with the rows kept inside the single workers' runs.  A tile has tile_blocks blocks of
+ * tile_lanes stream positions (tile_lanes of a wavefront's 64 lanes take a group of every block;
+ * a block then has tile_lanes entries in each of its arrays), and every worker is a span of
+ * tiles_per_worker tiles of its own (rows placed as above).  A worker whose rows all fit its span
+ * shares no row with a neighbour: it writes its rows and ends, and the launch has no fix-up
+ * phase (Sec. 3.5's straggler problem does not arise where the rows are of similar length; the
+ * positions left empty pay for it).  T = tiles_per_worker * n_workgroups * waves_per_workgroup.
+ *   tile_blocks, tile_lanes   a tile shape the kernel is compiled for -- G = 16: 3..6 blocks and
+ *                       32, 36, .. 64 lanes; any format: its own block count (4, 2 or 1, see
+ *                       gqsa_set_partition) with 64 lanes -- else GQSA_ERR_UNSUPPORTED
+ *   tiles_per_worker    >= 1
+ *   n_workgroups        1..4096, or 0 for as many as the rows need; GQSA_ERR_RANGE if they need more
+ *   waves_per_workgroup 1..16
+ */
+gqsa_status_t gqsa_set_partition_rows(gqsa_handle_t h, int tile_blocks, int tile_lanes, int tiles_per_worker,
+                                      int n_workgroups, int waves_per_workgroup);
 
 /*
  * Build a second image of the matrix for calls with several activation rows (the small-batch

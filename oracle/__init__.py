@@ -196,4 +196,4 @@ def rel_error(y: np.ndarray, y_ref: np.ndarray) -> float:
     return float(np.max(np.abs(y - y_ref) / den))
 
 
-from .layout import device_blob, panel_blob, row_positions  # noqa: E402,F401
+from .layout import device_blob, device_blob_for, panel_blob, row_positions  # noqa: E402,F401

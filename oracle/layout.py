@@ -6,17 +6,21 @@ paper's Sec. 3.2 listing (rowIndex / groups / values) and the per-group scale
 and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
 
  1. Stream.  The stored groups in canonical order g = 0..nnzg-1 form a stream.
-    64 consecutive positions make a block, U consecutive blocks a tile, with
-    U = 4 for up to 16 code bytes per group (G*bits/8), 2 for 32, 1 for 64.
+    LN consecutive positions make a block, U consecutive blocks a tile.  By
+    default LN = 64 (one position per lane of a wavefront) and U = 4 for up to
+    16 code bytes per group (G*bits/8), 2 for 32, 1 for 64; a partition may name
+    another tile shape (tile_blocks = U, tile_lanes = LN <= 64).
     Plain form (span_tiles = 0): group g sits at position g; the stream is
     padded with null groups (all bytes zero) to whole tiles:
-    ntiles = ceil(nnzg / (64 U)), nblocks = U * ntiles.
-    Aligned form (span_tiles = s > 0): spans of S = 64 U s positions.  The rows
+    ntiles = ceil(nnzg / (LN U)), nblocks = U * ntiles.
+    Aligned form (span_tiles = s > 0): spans of S = LN U s positions.  The rows
     are placed in order from position 0; a row with c groups, 0 < c <= S, that
     does not fit what is left of the current span ((pos mod S) + c > S) starts at
     the next multiple of S; every other row starts where the previous one ended.
-    Positions without a stored group hold null groups.  n_workgroups must be at
-    least the number of spans the rows reach into; ntiles = s * n_workgroups.
+    Positions without a stored group hold null groups.  There is one span per
+    workgroup (nspans = n_workgroups) or, if span_per_worker, one per worker
+    (nspans = n_workgroups * waves_per_workgroup); nspans must be at least the
+    number of spans the rows reach into; ntiles = s * nspans.
     Below, "past the last group" means at or beyond L = one past the last stored
     group's position (L = nnzg in the plain form), and a null group before L
     counts as part of the row before it.
@@ -26,10 +30,10 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     b_w = first block of worker w = U * floor(w * ntiles / n_waves).  (The
     grouping of the workers into workgroups does not enter the layout.)
  3. Tiles.  A tile starting at block b covers stream positions
-    64b .. 64(b+U)-1; the position 64b + p lives in block b + (p mod U),
+    LN b .. LN (b+U) - 1; the position LN b + p lives in block b + (p mod U),
     lane p div U.
- 4. Block.  Each block is (G*bits/8 + 6)*64 bytes: the code planes, then
-    64 x uint32 (fp16 scale bits | fp16 zero bits << 16), then 64 x uint16
+ 4. Block.  Each block is (G*bits/8 + 6)*LN bytes: the code planes, then
+    LN x uint32 (fp16 scale bits | fp16 zero bits << 16), then LN x uint16
     index words.  G = 16*M with M in {1, 2, 4, 8}, or G = 8.  The index word is
     (group-column * M) << 4 -- sixteen times the number of the 16-element slot
     of K at which the group starts (slots are below 4096) -- plus 1 if the
@@ -40,7 +44,7 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
     group, element 8h+2m in bits 4m..4m+3 and element 8h+2m+1 in bits
     16+4m..16+4m+3 (m = 0..3).  8-bit codes: byte j is element j.  The string
     is stored in planes: with P = min(16, G*bits/8) bytes per lane and plane,
-    plane k (64*P bytes, lanes in order) holds bytes k*P .. k*P+P-1 of every
+    plane k (LN*P bytes, lanes in order) holds bytes k*P .. k*P+P-1 of every
     lane's string; the planes follow each other.
  5. Side tables (int32): wave_info[n_waves][4] = {rank_base, tail_closed +
     2 * lead_len, lead_first, chain_len} with
@@ -50,7 +54,7 @@ and zero of Eq. 1; it adds no arithmetic.  The specification, restated:
                     beyond L or holds a row-head group, else 0;
       lead_len    = chain_len of worker lead_first (below), 0 if lead_first = -1;
       lead_first  = for a worker (with or without blocks) whose first position
-                    b_w*64 is before L and does not hold a row head: the
+                    b_w*LN is before L and does not hold a row head: the
                     worker that owns the head group of that group's row; else -1;
       chain_len   = for a worker with blocks, tail_closed = 0 and at least one
                     row head inside its run: (worker owning the last position
@@ -95,7 +99,7 @@ LANES = 64
 ALIGN = 256
 
 
-def tile_blocks(code_bytes: int) -> int:
+def default_tile_blocks(code_bytes: int) -> int:
     """U of spec item 1."""
     return 4 if code_bytes <= 16 else (2 if code_bytes <= 32 else 1)
 
@@ -127,39 +131,46 @@ def _align(n: int) -> int:
     return (n + ALIGN - 1) // ALIGN * ALIGN
 
 
-def stream_placement(nblocks: int, n_waves: int, U: int):
+def stream_placement(nblocks: int, n_waves: int, U: int, LN: int = LANES):
     """For every stream position: (block, lane) it is stored at (spec items 2-3)."""
     n_w = worker_block_counts(nblocks, n_waves, U)
     b_w = np.concatenate(([0], np.cumsum(n_w)[:-1]))
-    pos = np.arange(nblocks * LANES, dtype=np.int64)
-    tile = pos // (LANES * U)
-    p = pos % (LANES * U)
+    pos = np.arange(nblocks * LN, dtype=np.int64)
+    tile = pos // (LN * U)
+    p = pos % (LN * U)
     block = tile * U + (p % U)
     lane = p // U
     return block, lane, b_w, n_w
 
 
-def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int = 0) -> bytes:
+def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int = 0, tile_blocks: int = 0,
+                tile_lanes: int = LANES, span_per_worker: bool = False) -> bytes:
     """Exact bytes the library must hold on the device for canonical arrays `c`."""
     if c.G not in (8, 16, 32, 64, 128) or c.bits not in (4, 8) or c.G * c.bits // 8 > 64:
         raise ValueError("device layout is specified for G in {8,16,32,64,128}, bits in {4,8}, at most 64 code bytes")
     nnzg = c.nnzg
     code_bytes = c.G * c.bits // 8
-    U = tile_blocks(code_bytes)
-    blk_bytes = (code_bytes + 6) * LANES
+    U = tile_blocks or default_tile_blocks(code_bytes)
+    LN = tile_lanes or LANES
+    if not (1 <= LN <= LANES):
+        raise ValueError("a block has 1..64 positions")
+    blk_bytes = (code_bytes + 6) * LN
     slots_per_group = max(1, c.G // 16)
 
     ri = np.asarray(c.rowIndex, dtype=np.int64)
     counts = ri[1:] - ri[:-1]
     nonempty = np.nonzero(counts > 0)[0].astype(np.int32)
     empty = np.nonzero(counts == 0)[0].astype(np.int32)
-    row_pos, L = row_positions(ri, span_tiles * LANES * U)
+    row_pos, L = row_positions(ri, span_tiles * LN * U)
     if span_tiles > 0:
-        if -(-L // (span_tiles * LANES * U)) > n_workgroups:
-            raise ValueError("the rows reach into more spans than there are workgroups")
-        nblocks = U * span_tiles * n_workgroups
+        nspans = n_workgroups * (waves_per_workgroup if span_per_worker else 1)
+        if -(-L // (span_tiles * LN * U)) > nspans:
+            raise ValueError("the rows reach into more spans than there are")
+        nblocks = U * span_tiles * nspans
     else:
-        nblocks = U * (-(-L // (LANES * U)))
+        if span_per_worker:
+            raise ValueError("spans per worker need span_tiles > 0")
+        nblocks = U * (-(-L // (LN * U)))
     head_pos = row_pos[counts > 0]                 # stream position of each row's first group
     # stream position of every stored group
     group_pos = np.arange(nnzg, dtype=np.int64) + np.repeat(row_pos - ri[:-1], counts)
@@ -171,7 +182,7 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
     wave_info[:, 1] = 1
     wave_info[:, 2] = -1
     if nblocks > 0:
-        block, lane, b_w, n_w = stream_placement(nblocks, n_waves, U)
+        block, lane, b_w, n_w = stream_placement(nblocks, n_waves, U, LN)
         block = block[group_pos]
         lane = lane[group_pos]
         # codes
@@ -190,13 +201,13 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
             lane_bytes = vals
         plane = min(16, code_bytes)
         for k in range(code_bytes // plane):
-            plane_view = blocks[:, k * LANES * plane:(k + 1) * LANES * plane].reshape(nblocks, LANES, plane)
+            plane_view = blocks[:, k * LN * plane:(k + 1) * LN * plane].reshape(nblocks, LN, plane)
             plane_view[block, lane, :] = lane_bytes[:, k * plane:(k + 1) * plane]
         # scale | zero << 16
         sz = (np.asarray(c.scales, dtype=np.uint32) |
               (np.asarray(c.zeros, dtype=np.uint32) << np.uint32(16))).astype("<u4")
-        sz_off = LANES * code_bytes
-        sz_view = blocks[:, sz_off:sz_off + LANES * 4].reshape(nblocks, LANES, 4)
+        sz_off = LN * code_bytes
+        sz_view = blocks[:, sz_off:sz_off + LN * 4].reshape(nblocks, LN, 4)
         sz_view[block, lane, :] = sz.view(np.uint8).reshape(nnzg, 4)
         # group-column | head flag
         is_head = np.zeros(nnzg, dtype=np.uint16)
@@ -205,17 +216,17 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
         if gcol.size and gcol.max() * slots_per_group + slots_per_group - 1 >= 4096:
             raise ValueError("slot number does not fit 12 bits")
         idx = (((gcol * slots_per_group) << 4).astype(np.uint16) | is_head).astype("<u2")
-        idx_off = sz_off + LANES * 4
-        idx_view = blocks[:, idx_off:idx_off + LANES * 2].reshape(nblocks, LANES, 2)
+        idx_off = sz_off + LN * 4
+        idx_view = blocks[:, idx_off:idx_off + LN * 2].reshape(nblocks, LN, 2)
         idx_view[block, lane, :] = idx.view(np.uint8).reshape(nnzg, 2)
         # rank_base: heads strictly before the worker's first stream position, minus one
-        first_pos = LANES * b_w
+        first_pos = LN * b_w
         wave_info[:, 0] = np.searchsorted(head_pos, first_pos, side="left") - 1
         # tail_closed: does the row that is open at the end of the run stop there?
-        end_pos = LANES * (b_w + n_w)
-        head_set = np.zeros(max(nblocks * LANES, L) + 1, dtype=bool)
+        end_pos = LN * (b_w + n_w)
+        head_set = np.zeros(max(nblocks * LN, L) + 1, dtype=bool)
         head_set[head_pos] = True
-        wave_info[:, 1] = np.where(end_pos >= L, 1, head_set[np.minimum(end_pos, nblocks * LANES)])
+        wave_info[:, 1] = np.where(end_pos >= L, 1, head_set[np.minimum(end_pos, nblocks * LN)])
         # carry chains: which worker owns a given block
         owner = np.repeat(np.arange(n_waves), n_w)
         for w in range(n_waves):
@@ -223,13 +234,13 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
             e = int(end_pos[w])
             if f < L and not head_set[f]:
                 row_head = int(head_pos[np.searchsorted(head_pos, f, side="right") - 1])
-                wave_info[w, 2] = owner[row_head // LANES]
+                wave_info[w, 2] = owner[row_head // LN]
             heads_inside = (np.searchsorted(head_pos, min(e, L), side="left") -
                             np.searchsorted(head_pos, f, side="left"))
             if n_w[w] > 0 and wave_info[w, 1] == 0 and heads_inside > 0:
                 nxt = int(np.searchsorted(head_pos, e, side="left"))
                 row_last = (int(head_pos[nxt]) if nxt < len(head_pos) else L) - 1
-                wave_info[w, 3] = owner[row_last // LANES] - w + 1
+                wave_info[w, 3] = owner[row_last // LN] - w + 1
         for w in range(n_waves):
             if wave_info[w, 2] >= 0:
                 wave_info[w, 1] += 2 * wave_info[wave_info[w, 2], 3]
@@ -243,6 +254,13 @@ def device_blob(c, n_workgroups: int, waves_per_workgroup: int, span_tiles: int 
     if len(out) == 0:
         out += b"\0" * ALIGN
     return bytes(out)
+
+
+def device_blob_for(c, partition: dict) -> bytes:
+    """device_blob for a partition given by name (the keys n_workgroups, waves_per_workgroup, span_tiles,
+    tile_blocks, tile_lanes, span_per_worker; other keys are ignored)."""
+    return device_blob(c, partition["n_workgroups"], partition["waves_per_workgroup"], partition["span_tiles"],
+                       partition["tile_blocks"], partition["tile_lanes"], bool(partition["span_per_worker"]))
 
 
 def panel_blob(c) -> bytes:

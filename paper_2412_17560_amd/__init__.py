@@ -26,9 +26,11 @@ from .binding import (  # noqa: F401
     gqsa_pack_device,
     gqsa_pack_hessian,
     gqsa_pack_rows,
+    gqsa_partition,
     gqsa_save,
     gqsa_set_partition,
     gqsa_set_partition_aligned,
+    gqsa_set_partition_rows,
     gqsa_status_string,
     gqsa_stream_read,
     gqsa_stream_read_workgroups,

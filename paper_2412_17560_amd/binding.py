@@ -23,7 +23,9 @@ class _Info(C.Structure):
                 ("n_workgroups", C.c_int32), ("waves_per_workgroup", C.c_int32),
                 ("needs_fixup", C.c_int32), ("span_tiles", C.c_int32), ("n_empty_rows", C.c_int64),
                 ("device_bytes", C.c_int64), ("algorithmic_bytes", C.c_int64),
-                ("on_device", C.c_int32), ("panel_integer_zeros", C.c_int32), ("panel_bytes", C.c_int64)]
+                ("on_device", C.c_int32), ("panel_integer_zeros", C.c_int32), ("panel_bytes", C.c_int64),
+                ("tile_blocks", C.c_int32), ("tile_lanes", C.c_int32), ("span_per_worker", C.c_int32),
+                ("reserved0", C.c_int32)]
 
 
 def library_path() -> str:
@@ -76,7 +78,9 @@ def _lib():
     lib.gqsa_gemv_static.restype = C.c_int
     lib.gqsa_gemv_static.argtypes = [vp, vp, vp, i32, vp]
     lib.gqsa_default_partition.restype = C.c_int
-    lib.gqsa_default_partition.argtypes = [vp, i64, i64, i32, i32, C.POINTER(C.c_int32 * 3)]
+    lib.gqsa_default_partition.argtypes = [vp, i64, i64, i32, i32, C.POINTER(C.c_int32 * 6)]
+    lib.gqsa_set_partition_rows.restype = C.c_int
+    lib.gqsa_set_partition_rows.argtypes = [vp, i32, i32, i32, i32, i32]
     lib.gqsa_gemv_panels.restype = C.c_int
     lib.gqsa_gemv_panels.argtypes = [vp, vp, vp, i32, vp]
     lib.gqsa_gemv_multi.restype = C.c_int
@@ -224,6 +228,12 @@ def gqsa_set_partition_aligned(h: GqsaHandle, span_tiles: int, n_workgroups: int
            "gqsa_set_partition_aligned")
 
 
+def gqsa_set_partition_rows(h: GqsaHandle, tile_blocks: int, tile_lanes: int = 64, tiles_per_worker: int = 1,
+                            n_workgroups: int = 0, waves_per_workgroup: int = 4) -> None:
+    _check(_lib().gqsa_set_partition_rows(h.ptr, int(tile_blocks), int(tile_lanes), int(tiles_per_worker),
+                                          int(n_workgroups), int(waves_per_workgroup)), "gqsa_set_partition_rows")
+
+
 def gqsa_build_panels(h: GqsaHandle) -> None:
     _check(_lib().gqsa_build_panels(h.ptr), "gqsa_build_panels")
 
@@ -289,12 +299,20 @@ def _dev_ptr(t, dtype_name: str, what: str):
 
 
 def gqsa_default_partition(rowIndex, K: int, G: int = 16, bits: int = 4):
-    """(n_workgroups, waves_per_workgroup, span_tiles) the library would choose for these row pointers."""
+    """(n_workgroups, waves_per_workgroup, span_tiles, tile_blocks, tile_lanes, span_per_worker) the library would
+    choose for these row pointers."""
     ri = np.ascontiguousarray(rowIndex, dtype=np.int32)
-    out = (C.c_int32 * 3)()
+    out = (C.c_int32 * 6)()
     _check(_lib().gqsa_default_partition(C.c_void_p(ri.ctypes.data), ri.size - 1, K, G, bits, C.byref(out)),
            "gqsa_default_partition")
-    return (int(out[0]), int(out[1]), int(out[2]))
+    return tuple(int(v) for v in out)
+
+
+def gqsa_partition(h: GqsaHandle):
+    """The handle's partition, in the order of gqsa_default_partition."""
+    info = gqsa_info(h)
+    return tuple(info[k] for k in ("n_workgroups", "waves_per_workgroup", "span_tiles", "tile_blocks", "tile_lanes",
+                                   "span_per_worker"))
 
 
 def gqsa_gemv_static(h: GqsaHandle, x, y, stream=None):

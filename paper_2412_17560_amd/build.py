@@ -15,8 +15,9 @@ LIB = os.environ.get("GQSA_LIBRARY") or os.path.join(HERE, "libgqsa.so")
 HOST_ONLY = bool(os.environ.get("GQSA_LIBRARY"))
 SANITIZED_LIB = os.path.join(OBJ, "libgqsa_host_asan.so")
 
-SOURCES = ["gqsa_pack.cpp", "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_gemv.hip", "gqsa_panel_kernel.hip", "gqsa_pack_device.hip",
-           "gqsa_baselines.hip"]
+# (gqsa_gemv.hip is compiled four times: whole, and once per further tile size -- "file:part")
+SOURCES = ["gqsa_gemv.hip", "gqsa_gemv.hip:1", "gqsa_gemv.hip:2", "gqsa_gemv.hip:3", "gqsa_pack.cpp",
+           "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_panel_kernel.hip", "gqsa_pack_device.hip", "gqsa_baselines.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
           "-Wall", "-Wextra", "-Wno-unused-parameter"]
@@ -38,10 +39,12 @@ def _hipcc() -> str:
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+    src, _, part = src.partition(":")
+    obj = os.path.join(OBJ, os.path.splitext(src)[0] + (f"_part{part}" if part else "") + ".o")
     path = os.path.join(CSRC, src)
     if src.endswith(".hip"):
-        cmd = [_hipcc(), *COMMON, *HIP_FLAGS, *EXTRA_HIP_FLAGS.get(os.path.basename(path), []), "-c", path, "-o", obj]
+        defines = [f"-DGQSA_GEMV_PART={part}"] if part else []
+        cmd = [_hipcc(), *COMMON, *HIP_FLAGS, *EXTRA_HIP_FLAGS.get(os.path.basename(path), []), *defines, "-c", path, "-o", obj]
     else:
         cmd = [_hipcc(), *COMMON, *HOST_FLAGS, "-x", "c++", "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -56,7 +59,7 @@ def _compile(src: str) -> str:
 
 def build() -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB, "-lpthread"]
     r = subprocess.run(cmd, capture_output=True, text=True)

@@ -43,9 +43,7 @@ gqsa_status_t check_format(int64_t N, int64_t K, int G, int bits)
 gqsa_status_t finish(std::unique_ptr<gqsa_matrix> m, gqsa_status_t st, gqsa_handle_t* out)
 {
     if (st != GQSA_OK) return st;
-    int wgs = 1, wpw = 1, span = 0;
-    gqsa::default_partition(*m, &wgs, &wpw, &span);
-    st = gqsa::build_image(m.get(), wgs, wpw, span);
+    st = gqsa::build_image(m.get(), gqsa::default_partition(*m));
     if (st != GQSA_OK) return st;
     *out = m.release();
     return GQSA_OK;
@@ -169,7 +167,7 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
     });
 }
 
-gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t K, int G, int bits, int32_t out[3])
+gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t K, int G, int bits, int32_t out[6])
 {
     if (!rowIndex || !out) return GQSA_ERR_NULL;
     if (gqsa_status_t st = check_format(N, K, G, bits)) return st;
@@ -182,9 +180,9 @@ gqsa_status_t gqsa_default_partition(const int32_t* rowIndex, int64_t N, int64_t
         gqsa_matrix m;
         m.N = N; m.K = K; m.G = G; m.bits = bits;
         m.rowIndex.assign(rowIndex, rowIndex + N + 1);
-        int wgs = 1, wpw = 1, span = 0;
-        gqsa::default_partition(m, &wgs, &wpw, &span);
-        out[0] = wgs; out[1] = wpw; out[2] = span;
+        const gqsa::Partition part = gqsa::default_partition(m);
+        out[0] = part.n_workgroups; out[1] = part.waves_per_workgroup; out[2] = part.span_tiles;
+        out[3] = part.tile_blocks; out[4] = part.tile_lanes; out[5] = part.span_per_worker;
         return GQSA_OK;
     });
 }
@@ -194,7 +192,12 @@ gqsa_status_t gqsa_set_partition(gqsa_handle_t h, int n_workgroups, int waves_pe
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
     if (n_workgroups < 1) return GQSA_ERR_RANGE;
-    return guarded([&] { return gqsa::build_image(h, n_workgroups, waves_per_workgroup, 0); });
+    return guarded([&] {
+        gqsa::Partition part;
+        part.n_workgroups = n_workgroups;
+        part.waves_per_workgroup = waves_per_workgroup;
+        return gqsa::build_image(h, part);
+    });
 }
 
 gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_workgroups, int waves_per_workgroup)
@@ -202,7 +205,31 @@ gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_
     if (!h) return GQSA_ERR_NULL;
     if (h->d_image) return GQSA_ERR_UNSUPPORTED;
     if (span_tiles < 1) return GQSA_ERR_RANGE;
-    return guarded([&] { return gqsa::build_image(h, n_workgroups, waves_per_workgroup, span_tiles); });
+    return guarded([&] {
+        gqsa::Partition part;
+        part.n_workgroups = n_workgroups;
+        part.waves_per_workgroup = waves_per_workgroup;
+        part.span_tiles = span_tiles;
+        return gqsa::build_image(h, part);
+    });
+}
+
+gqsa_status_t gqsa_set_partition_rows(gqsa_handle_t h, int tile_blocks, int tile_lanes, int tiles_per_worker,
+                                      int n_workgroups, int waves_per_workgroup)
+{
+    if (!h) return GQSA_ERR_NULL;
+    if (h->d_image) return GQSA_ERR_UNSUPPORTED;
+    if (tiles_per_worker < 1 || tile_blocks < 1 || tile_lanes < 1) return GQSA_ERR_RANGE;
+    return guarded([&] {
+        gqsa::Partition part;
+        part.n_workgroups = n_workgroups;
+        part.waves_per_workgroup = waves_per_workgroup;
+        part.span_tiles = tiles_per_worker;
+        part.tile_blocks = tile_blocks;
+        part.tile_lanes = tile_lanes;
+        part.span_per_worker = 1;
+        return gqsa::build_image(h, part);
+    });
 }
 
 gqsa_status_t gqsa_build_panels(gqsa_handle_t h)
@@ -317,6 +344,9 @@ gqsa_status_t gqsa_info(gqsa_handle_t h, gqsa_info_t* out)
     out->waves_per_workgroup = h->waves_per_workgroup;
     out->needs_fixup = h->needs_fixup;
     out->span_tiles = h->span_tiles;
+    out->tile_blocks = h->tile_blocks;
+    out->tile_lanes = h->tile_lanes;
+    out->span_per_worker = h->span_per_worker;
     out->n_empty_rows = h->n_empty;
     out->device_bytes = static_cast<int64_t>(h->map.total);
     out->algorithmic_bytes = h->nnzg() * (h->code_bytes() + 6) + (h->N + 1) * 4 + (h->K + h->N) * 2;

@@ -31,6 +31,14 @@
 
 #include "gqsa_internal.hpp"
 
+// This file is compiled several times: once whole (GQSA_GEMV_PART 0: the kernels for the formats'
+// own tile sizes and all the host code) and once per further tile size (parts 1..3: tiles of 3, 4 and 5
+// blocks with a chosen count of lanes in use, both code widths, group size 16), so that the kernels build side by side.
+#ifndef GQSA_GEMV_PART
+#define GQSA_GEMV_PART 0
+#endif
+
+#if GQSA_GEMV_PART == 0
 // Fix-up workspace of gqsa_gemv_static (at the end of this file), for callers that must not
 // allocate: carry records, arrival counters and meeting points for up to kScratchWorkers wavefront
 // workers -- the most a default partition deals to -- at 196 bytes each.  Every GPU the library
@@ -40,9 +48,9 @@
 constexpr int kScratchWorkers = 16384;
 constexpr size_t kScratchBytes = static_cast<size_t>(kScratchWorkers) * 196;
 static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+#endif
 
 namespace gqsa {
-namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef int int4_t __attribute__((ext_vector_type(4)));
@@ -82,6 +90,21 @@ struct LaunchArgs {
     MatDesc m[kMaxMatrices];
 };
 static_assert(sizeof(MatArgs) == 64 && sizeof(MatDesc) == 104, "argument block layout");
+
+// A launchable variant of the kernel.
+struct Variant {
+    const void* fn = nullptr;    // device function, for attribute setting
+    void (*launch)(const LaunchArgs&, const uint16_t*, int, const int*, dim3, dim3, size_t, hipStream_t) = nullptr;
+    explicit operator bool() const { return fn != nullptr; }
+};
+
+// The variants for tiles of `u` blocks that the other compilations of this file hold (an empty
+// Variant from the parts that do not have that size).
+Variant tile_variant_part1(int bits, int u, int slots, int nb, int* kgp);
+Variant tile_variant_part2(int bits, int u, int slots, int nb, int* kgp);
+Variant tile_variant_part3(int bits, int u, int slots, int nb, int* kgp);
+
+namespace {
 
 // where the argument block sits in the kernel-argument segment: after the scalar parameters
 // (three pointers, a 64-bit number and six ints: the 14 dwords that can be preloaded)
@@ -145,7 +168,7 @@ struct Codes {
 // 4-bit: the code words are nibble-permuted at pack time (element 2m at bits 4m, element 2m+1
 // at bits 16+4m), so one AND-OR splices a pair of codes into the mantissas of the fp16 pair
 // (1024+q, 1024+q') or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
-__device__ __forceinline__ void decode_w4(uint32_t w, half2_t* q)
+[[maybe_unused]] __device__ __forceinline__ void decode_w4(uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const half2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
@@ -162,7 +185,7 @@ __device__ __forceinline__ void decode_w4(uint32_t w, half2_t* q)
 
 // 8-bit: a byte permute drops each code (bytes of w, element order) into the mantissa of
 // 1024.0 (0x64xx), one packed subtract removes the bias.
-__device__ __forceinline__ void decode_w8(uint32_t w, half2_t* q)
+[[maybe_unused]] __device__ __forceinline__ void decode_w8(uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
     const uint32_t k64s = 0x64646464u;
@@ -231,12 +254,16 @@ __device__ __forceinline__ void store_row(const MatArgs& m, int b, int rank, flo
     m.y[static_cast<size_t>(b) * m.N + row] = float_to_half_bits(v);
 }
 
-// Storage format of a group as the kernel is compiled for it: code width and group size
-// G = 16 * M, or G = 8 (M = 0: half a chunk).  A block holds 64 groups, one per lane: the code
-// bytes in planes of at most 16 bytes per lane (each plane one coalesced load), then
-// scale | zero << 16, then the index word.
-template <int BITS_, int M_>
+// Storage format of a group as the kernel is compiled for it: code width, group size
+// G = 16 * M, or G = 8 (M = 0: half a chunk), and blocks per tile.  U_ = 0: the format's own
+// count, and a block holds 64 groups, one per lane: the code bytes in planes of at most 16 bytes
+// per lane (each plane one coalesced load), then scale | zero << 16, then the index word.
+// U_ > 0 (FLEX): U_ blocks of L groups each, L <= 64 given at launch -- the same three arrays
+// with L entries, the lanes from L on take no group (partitions that keep whole rows inside a
+// wavefront's run choose U_ and L so that the rows fill the tiles).
+template <int BITS_, int M_, int U_ = 0>
 struct Fmt {
+    static constexpr bool FLEX = U_ != 0;
     static constexpr int BITS = BITS_;
     static constexpr int M = M_;                         // 16-element chunks per group (0: G = 8)
     static constexpr bool HALF = M_ == 0;
@@ -245,9 +272,9 @@ struct Fmt {
     static constexpr int CWC = HALF ? CW : CW / (M_ ? M_ : 1);    // code words per chunk (2 or 4; half chunk: 1 or 2)
     static constexpr int PB = CB < 16 ? CB : 16;         // bytes per lane in one code plane
     static constexpr int PLANES = CB / PB;
-    static constexpr int UMAX = largest_tile(CB);        // blocks of a tile
-    static constexpr int BB = (CB + 6) * kLanes;         // block bytes
-    static constexpr int TB = UMAX * BB;                 // tile bytes
+    static constexpr int UMAX = U_ ? U_ : largest_tile(CB);   // blocks of a tile
+    static constexpr int BB = (CB + 6) * kLanes;         // block bytes (of a 64-lane block)
+    static constexpr int TB = UMAX * BB;                 // tile bytes (of 64-lane blocks)
     static constexpr int LOADS = UMAX * (PLANES + 2);    // load instructions per tile
 };
 
@@ -257,6 +284,24 @@ struct Tile {
     uint32_t code[F::UMAX][F::CW];
     uint32_t sz[F::UMAX];
     uint32_t ix[F::UMAX];
+};
+
+// The fields of a group's index word and its scale, as masks.  In tiles of a chosen shape the
+// lanes that take no group hold all-zero masks, so that their words read as a null group's (no
+// row head, slot 0, scale 0) at no extra instruction: the masks take the place of literals.
+template <bool FLEX>
+struct LaneMasks {
+    uint32_t head, slot, scale;
+    __device__ __forceinline__ explicit LaneMasks(bool lane_in_use)
+    {
+        if constexpr (FLEX) {
+            head = lane_in_use ? 1u : 0u;
+            slot = lane_in_use ? 0xFFF0u : 0u;
+            scale = lane_in_use ? 0xFFFFu : 0u;
+        } else {
+            head = 1u; slot = 0xFFF0u; scale = 0xFFFFu;
+        }
+    }
 };
 
 // (1) stream the compressed groups: coalesced loads, all issued before anything waits.  The
@@ -283,9 +328,37 @@ __device__ __forceinline__ float lds_read_float(uint32_t address)
 // else), then codes and scale/zero block by block; loads return in the order of issue, so the
 // tile can be worked through while its later blocks are still on their way.
 template <typename F>
-__device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int lane)
+__device__ __forceinline__ void load_tile(Tile<F>& t, const uint8_t* p, int lane, int lanes_in_use)
 {
     const uint32_t ulane = static_cast<uint32_t>(lane);
+    if constexpr (F::FLEX) {
+        // blocks of L = lanes_in_use entries: block u at p + u * L * (CB + 6) (a scalar), its arrays at
+        // lane offsets that depend on L.  The lanes from L on load what lane 0 loads (a stored
+        // group's words: finite numbers) and mask it away when they use it (LaneMasks); all
+        // lanes load, so the loads are straight-line code like any other tile's and x, requested
+        // before them, can be awaited alone.
+        static_assert(F::PLANES == 1, "tiles of a chosen shape: one code plane");
+        const uint32_t L = static_cast<uint32_t>(lanes_in_use);
+        const uint32_t bb = L * (F::CB + 6);
+        const uint32_t l = ulane < L ? ulane : 0u;
+        const uint32_t off_ix = l * 2u + L * (F::CB + 4), off_sz = l * 4u + L * F::CB;
+#pragma unroll
+        for (int u = 0; u < F::UMAX; ++u) t.ix[u] = load_at<uint16_t>(p + u * bb, off_ix);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < F::UMAX; ++u) {
+            if constexpr (F::PB == 8) {
+                const uint2 c = load_at<uint2>(p + u * bb, l * 8u);
+                t.code[u][0] = c.x; t.code[u][1] = c.y;
+            } else {
+                const uint4 c = load_at<uint4>(p + u * bb, l * 16u);
+                t.code[u][0] = c.x; t.code[u][1] = c.y; t.code[u][2] = c.z; t.code[u][3] = c.w;
+            }
+            t.sz[u] = load_at<uint32_t>(p + u * bb, off_sz);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < F::UMAX; ++u)
         t.ix[u] = load_at<uint16_t>(p, ulane * 2u + (u * F::BB + (F::CB + 4) * kLanes));
@@ -336,7 +409,7 @@ __device__ __forceinline__ void decode_chunk(const Tile<F>& t, int u, int i, Cod
 // by block as their codes come in.  Otherwise the gathers go group by group (fewer registers).
 template <typename F, int KGP, int NB, bool EAGER>
 __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t, int lane, const uint8_t* xlds,
-                                             WaveState<NB>& st)
+                                             WaveState<NB>& st, const LaneMasks<F::FLEX> mask)
 {
     constexpr int U = F::UMAX;
     // Row heads as wave-uniform lane masks, one per position of the tile (index word =
@@ -346,7 +419,7 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
     int heads_total = 0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        bal[u] = __ballot((t.ix[u] & 1u) != 0);
+        bal[u] = __ballot((t.ix[u] & mask.head) != 0);
         hmask |= bal[u];
         heads_total += __popcll(bal[u]);
     }
@@ -372,8 +445,8 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
     for (int b = 0; b < NB; ++b) { acc[b] = 0.0f; lead[b] = 0.0f; }
     int nh = 0;
     auto fold = [&](int u, const float* dotz) {
-        const float s = half_to_float(t.sz[u] & 0xFFFFu);
-        const bool head_here = (t.ix[u] & 1u) != 0;
+        const float s = half_to_float(t.sz[u] & mask.scale);
+        const bool head_here = (t.ix[u] & mask.head) != 0;
         if (simple) {
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
@@ -401,21 +474,29 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
     // address would cost an addition of that 0)
     constexpr uint32_t x0 = 0;
     if constexpr (EAGER && NB == 1 && F::M == 1) {
+        // (at most four groups' activations are under way at a time: enough to cover the latency
+        // of LDS, and the registers do not grow with the tile)
+        constexpr int AHEAD = U < 4 ? U : 4;
         uint4 xl[U], xh[U];
         float xs[U], dotz[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t slot = t.ix[u] & 0xFFF0u;        // byte offset of the group's 16 activations
+        auto gather = [&](int u) {
+            const uint32_t slot = t.ix[u] & mask.slot;        // byte offset of the group's 16 activations
             xl[u] = lds_read16(x0 + slot);
             xh[u] = lds_read16(x0 + slot + 16 * KGP);
             xs[u] = lds_read_float(x0 + 32 * KGP + (slot >> 2));
-        }
+        };
+#pragma unroll
+        for (int u = 0; u < AHEAD; ++u) gather(u);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             Codes c;
             decode_chunk<F>(t, u, 0, c);
             const float z = half_to_float(t.sz[u] >> 16);
             dotz[u] = __builtin_fmaf(-z, xs[u], dot16(c, xl[u], xh[u]));
+            if (u + AHEAD < U) {
+                gather(u + AHEAD);
+                __builtin_amdgcn_sched_barrier(0x47F);     // (LDS reads stay behind this point: no more than AHEAD groups under way)
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) fold(u, &dotz[u]);
@@ -423,7 +504,7 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float z = half_to_float(t.sz[u] >> 16);
-            const uint32_t slot = t.ix[u] & 0xFFF0u;
+            const uint32_t slot = t.ix[u] & mask.slot;
             float dotz[NB];
             if constexpr (F::HALF) {
                 // G = 8: the index word counts 8-element half-slots; an even one lies in the array
@@ -683,10 +764,11 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     LdsRecord* rec = reinterpret_cast<LdsRecord*>(xlds + NB * 48 * KGP);        // [wavefront][NB]
 
     const int kg = kg_wpw & 0xFFFF;       // 16-element slots of K
-    const int wpw = (kg_wpw >> 16) & 0xFF;    // wavefronts per workgroup
+    const int wpw = (kg_wpw >> 16) & 0x1F;    // wavefronts per workgroup
+    const int lanes_in_use = F::FLEX ? ((kg_wpw >> 21) & 0x7F) : kLanes;     // groups per block
     // slots of x that exist: the caller may have fewer than NB rows (3 for a kernel of 4, 7 for
     // one of 8); the rows beyond take the last slot's activations and their sums are never stored
-    const int last_slot = ((kg_wpw >> 24) + 1) * kg - 1;
+    const int last_slot = (((kg_wpw >> 28) & 7) + 1) * kg - 1;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int n_threads = wpw * kLanes;
@@ -742,7 +824,8 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     };
     const int tile0 = first_tile(worker);
     const int n_tiles = first_tile(worker + 1) - tile0;
-    const uint8_t* p = blocks + static_cast<size_t>(tile0) * F::TB;
+    const uint32_t tile_bytes = F::FLEX ? static_cast<uint32_t>(F::UMAX * (F::CB + 6) * lanes_in_use) : static_cast<uint32_t>(F::TB);
+    const uint8_t* p = blocks + static_cast<size_t>(tile0) * tile_bytes;
 
     auto stage = [&](int c, uint4 lo, uint4 hi) {   // c = slot over all rows: b * kg + column
         const int b = NB == 1 ? 0 : c / kg;
@@ -791,6 +874,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         return pl;
     };
 
+    const LaneMasks<F::FLEX> mask(lane < lanes_in_use);
     WaveState<NB> st;
 #pragma unroll
     for (int b = 0; b < NB; ++b) { st.carry[b] = 0.0f; st.lead[b] = 0.0f; }
@@ -801,33 +885,34 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     if (n_tiles == 1) {
         // the whole run is one tile (the default partition's aim): nothing else is in flight
         // behind it, and its blocks are consumed in the order in which they arrive
-        load_tile<F>(cur, p, lane);
+        load_tile<F>(cur, p, lane, lanes_in_use);
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
         pl = plan(info);
-        compute_tile<F, KGP, NB, true>(md.out, cur, lane, xlds, st);
-    } else if (n_tiles == 0) {
-        // a worker without tiles still helps to stage x
+        compute_tile<F, KGP, NB, true>(md.out, cur, lane, xlds, st, mask);
+    } else if (F::FLEX || n_tiles == 0) {
+        // a worker without tiles still helps to stage x.  (Tiles of a chosen shape come one to a
+        // worker -- the host builds no other partition of them -- so that kernel has no loop over tiles.)
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
         pl = plan(info);
-    } else {
+    } else if constexpr (!F::FLEX) {
         // a run of several tiles: the next tile is requested before the current one is worked on
         // (the copy at the top of the loop is where the wavefront waits for a tile; inside
         // compute_tile nothing waits for memory)
         Tile<F> nxt;
-        load_tile<F>(nxt, p, lane);
+        load_tile<F>(nxt, p, lane, lanes_in_use);
         stage_x_and_meet();
         info = record();
         st.rank = info.x;
         pl = plan(info);
         for (int left = n_tiles; left > 0; --left) {
             cur = nxt;
-            p += F::TB;
-            if (left > 1) load_tile<F>(nxt, p, lane);      // in flight during this tile
-            compute_tile<F, KGP, NB, false>(md.out, cur, lane, xlds, st);
+            p += tile_bytes;
+            if (left > 1) load_tile<F>(nxt, p, lane, lanes_in_use);      // in flight during this tile
+            compute_tile<F, KGP, NB, false>(md.out, cur, lane, xlds, st, mask);
         }
     }
 
@@ -859,25 +944,19 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
                      st.lead, st.carry, rec, lane, wl, wpw, worker);
 }
 
-// A launchable variant of the kernel.
-struct Variant {
-    const void* fn = nullptr;    // device function, for attribute setting
-    void (*launch)(const LaunchArgs&, const uint16_t*, int, int, int, const int*, dim3, dim3, size_t, hipStream_t) = nullptr;
-    explicit operator bool() const { return fn != nullptr; }
-};
-
 constexpr size_t lds_bytes(int kgp, int nb)
 {
     return static_cast<size_t>(nb) * 48 * kgp + kWavesPerWorkgroup * nb * sizeof(LdsRecord);
 }
 
+// (kg_wpw_rows: slots of K | wavefronts per workgroup << 16 | lanes in use << 21 | (activation rows - 1) << 28)
 template <typename F, int KGP, int NB>
-void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg, int wpw, int rows, const int* wg_end, dim3 grid, dim3 block,
+void launch_variant(const LaunchArgs& a, const uint16_t* x, int kg_wpw_rows, const int* wg_end, dim3 grid, dim3 block,
                     size_t lds, hipStream_t s)
 {
     const MatDesc& m0 = a.m[0];
     hipLaunchKernelGGL((gqsa_gemv_kernel<F, KGP, NB>), grid, block, lds, s, x, m0.blocks, m0.wave_info, m0.magic,
-                       m0.base, m0.extra, kg | (wpw << 16) | ((rows - 1) << 24), wg_end[0], wg_end[1], wg_end[2], a);
+                       m0.base, m0.extra, kg_wpw_rows, wg_end[0], wg_end[1], wg_end[2], a);
 }
 
 template <typename F, int KGP, int NB>
@@ -920,10 +999,45 @@ Variant pick_kernel(int slots, int nb, int* kgp)
     return Variant{};
 }
 
+#if GQSA_GEMV_PART != 0
+// The two (code width, blocks per tile) pairs of this compilation.
+#if GQSA_GEMV_PART == 1
+#define GQSA_PART_NAME tile_variant_part1
+#define GQSA_PART_PAIRS {4, 3}, {8, 3}
+#elif GQSA_GEMV_PART == 2
+#define GQSA_PART_NAME tile_variant_part2
+#define GQSA_PART_PAIRS {4, 4}, {8, 4}
+#else
+#define GQSA_PART_NAME tile_variant_part3
+#define GQSA_PART_PAIRS {4, 5}, {8, 5}
+#endif
+struct BitsAndBlocks { int bits, u; };
+constexpr BitsAndBlocks kPairs[2] = {GQSA_PART_PAIRS};
+
+}  // namespace
+
+Variant GQSA_PART_NAME(int bits, int u, int slots, int nb, int* kgp)
+{
+    if (bits == kPairs[0].bits && u == kPairs[0].u) return pick_kernel<Fmt<kPairs[0].bits, 1, kPairs[0].u>>(slots, nb, kgp);
+    if (bits == kPairs[1].bits && u == kPairs[1].u) return pick_kernel<Fmt<kPairs[1].bits, 1, kPairs[1].u>>(slots, nb, kgp);
+    return Variant{};
+}
+
+}  // namespace gqsa
+
+#else   // GQSA_GEMV_PART == 0: the formats' own tile sizes, and the host side
+
 Variant pick(const gqsa_matrix* m, int nb, int* kgp)
 {
     const int slots = static_cast<int>(m->K / 16);
     *kgp = 0;
+    if (m->tile_blocks != largest_tile(m->code_bytes()) || m->tile_lanes != kLanes) {     // tiles of a chosen shape
+        if (m->G != 16) return Variant{};
+        Variant (*const parts[3])(int, int, int, int, int*) = {tile_variant_part1, tile_variant_part2, tile_variant_part3};
+        for (auto part : parts)
+            if (Variant v = part(m->bits, m->tile_blocks, slots, nb, kgp)) return v;
+        return Variant{};
+    }
     if (m->bits == 4) {
         switch (m->G) {
             case 8: return pick_kernel<Fmt<4, 0>>(slots, nb, kgp);
@@ -1031,7 +1145,9 @@ int launch_waves_per_workgroup(gqsa_matrix* const* ms, int n_mats, int nb, size_
     const int wpw = ms[0]->waves_per_workgroup;
     int workers = 0;
     for (int i = 0; i < n_mats; ++i) {
-        if (ms[i]->waves_per_workgroup != wpw) return 0;
+        if (ms[i]->waves_per_workgroup != wpw || ms[i]->tile_blocks != ms[0]->tile_blocks ||
+            ms[i]->tile_lanes != ms[0]->tile_lanes)
+            return 0;
         workers += ms[i]->n_waves;
     }
     if (nb == 1) return wpw;
@@ -1084,7 +1200,8 @@ gqsa_status_t launch(gqsa_matrix* const* ms, int n_mats, const uint16_t* x, uint
         grid += d.n_wg;
         if (i + 1 < n_mats) wg_end[i] = grid;
     }
-    v.launch(a, x, static_cast<int>(m0->K / 16), wpw, rows, wg_end, dim3(grid), dim3(wpw * kLanes), lds_bytes(kgp, nb), s);
+    const int kg_wpw_rows = static_cast<int>(m0->K / 16) | (wpw << 16) | (m0->tile_lanes << 21) | ((rows - 1) << 28);
+    v.launch(a, x, kg_wpw_rows, wg_end, dim3(grid), dim3(wpw * kLanes), lds_bytes(kgp, nb), s);
     return GQSA_OK;
 }
 
@@ -1206,3 +1323,5 @@ bool stream_is_capturing(void* stream)
 }
 
 }  // namespace gqsa
+
+#endif  // GQSA_GEMV_PART == 0

@@ -22,8 +22,32 @@ constexpr int kPanelRows = 16;         // output rows per panel of the many-row 
 constexpr int kSliceColumns = 32;      // group-columns per block of that image
 constexpr int kPanelHeaderBytes = 144; // a block's header: 32 column words, data offset, group count, 2 spare
 
-// Blocks per tile for a format with `code_bytes` bytes of codes per group.
+// Blocks per tile for a format with `code_bytes` bytes of codes per group, unless the partition
+// names another count.
 constexpr int largest_tile(int code_bytes) { return code_bytes <= 16 ? 4 : (code_bytes <= 32 ? 2 : 1); }
+// Tile shapes the GEMV kernel is compiled for: the format's own block count with all 64 lanes
+// of a block in use, and for G = 16 also 3, 4 or 5 blocks per tile with any
+// multiple of 4 lanes from 32 to 64 in use (a tile then holds lanes * blocks stream positions);
+// tiles of such a chosen shape come one to a worker.
+constexpr bool tile_shape_is_own(int code_bytes, int blocks, int lanes)
+{
+    return blocks == largest_tile(code_bytes) && lanes == kLanes;
+}
+constexpr bool tile_shape_supported(int code_bytes, int G, int blocks, int lanes)
+{
+    if (tile_shape_is_own(code_bytes, blocks, lanes)) return true;
+    return G == 16 && blocks >= 3 && blocks <= 5 && lanes >= 32 && lanes <= kLanes && lanes % 4 == 0;
+}
+
+// How the group stream of a matrix is laid out for the wavefront workers.
+struct Partition {
+    int n_workgroups = 1;
+    int waves_per_workgroup = 1;
+    int span_tiles = 0;          // 0: rows follow each other without gaps; else tiles per span that rows are kept inside
+    int tile_blocks = 0;         // blocks per tile (0: the format's own count)
+    int tile_lanes = 0;          // lanes of a block in use = stream positions per block (0: all 64)
+    int span_per_worker = 0;     // 0: one span per workgroup; 1: one span per wavefront worker
+};
 
 // Offsets (bytes) of the regions inside the device image.
 struct ImageMap {
@@ -56,9 +80,12 @@ struct gqsa_matrix {
     // device image (host copy) and its map
     int n_workgroups = 0;
     int waves_per_workgroup = 0;
-    int span_tiles = 0;       // tiles per workgroup span that rows are kept inside; 0: rows follow each other without gaps
+    int span_tiles = 0;       // tiles per span that rows are kept inside; 0: rows follow each other without gaps
+    int span_per_worker = 0;  // 1: a span is one wavefront worker's run (rows then never straddle workers); 0: a workgroup's
+    int tile_blocks = 0;      // blocks per tile
+    int tile_lanes = 0;       // stream positions per block (lanes in use), 64 unless the partition says otherwise
     int n_waves = 0;          // n_workgroups * waves_per_workgroup
-    int64_t n_blocks = 0;     // 64-group blocks of the padded stream = n_tiles * largest_tile(code_bytes)
+    int64_t n_blocks = 0;     // blocks of the padded stream = n_tiles * tile_blocks
     int64_t n_tiles = 0;
     int64_t n_empty = 0;
     int needs_fixup = 0;
@@ -77,7 +104,8 @@ struct gqsa_matrix {
 
     int64_t nnzg() const { return rowIndex.empty() ? 0 : rowIndex.back(); }
     int code_bytes() const { return G * bits / 8; }
-    int block_bytes() const { return (code_bytes() + 6) * gqsa::kLanes; }
+    int group_bytes() const { return code_bytes() + 6; }     // codes, scale, zero, index word
+    int block_bytes() const { return group_bytes() * (tile_lanes ? tile_lanes : gqsa::kLanes); }
 };
 
 namespace gqsa {
@@ -87,9 +115,9 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                          const int32_t* keep_per_row, double sparsity, const float* hinv_diag,
                          gqsa_matrix* m);
 int64_t place_rows(const gqsa_matrix& m, int64_t span_groups, std::vector<int64_t>* row_pos);
-void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles);
-gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles,
-                          bool fill_blocks = true, std::vector<int64_t>* row_pos_out = nullptr);
+Partition default_partition(const gqsa_matrix& m);
+gqsa_status_t build_image(gqsa_matrix* m, const Partition& part, bool fill_blocks = true,
+                          std::vector<int64_t>* row_pos_out = nullptr);
 int64_t balanced_keep(int64_t groups_per_row, double sparsity);
 gqsa_status_t row_pointers(gqsa_matrix* m, const int32_t* keep_per_row, double sparsity);
 

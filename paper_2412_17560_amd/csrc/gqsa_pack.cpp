@@ -258,28 +258,111 @@ void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t*
     }
 }
 
+// Rows kept inside the workers' runs: tiles of U blocks with L of the 64 lanes in use (L * U
+// stream positions), t tiles per worker, every worker a span of its own (place_rows) -- a worker
+// then holds whole rows only, settles them with its one segmented scan per tile and ends; there
+// is no fix-up, no second barrier, nothing for a workgroup to wait for.  (Measured on an MI355X:
+// with the rows of 4096x4096 at 30 % sparsity shared between wavefronts a call takes 5.0 us; kept
+// apart it takes 4.8 us even in tiles of 4 x 64, where 30 % of the stream is null groups, and
+// 4.3 us in tiles of 3 x 60.)  The shape is chosen so that few positions stay empty: 179 groups
+// per row fit 3 x 60, two rows of 77 fit 3 x 52, 205 fit 4 x 52.  Eligible: the shapes the
+// kernel has (tile_shape_supported) that leave at most an eighth of the stored groups' count of
+// positions empty with at most 16384 workers -- one tile per worker; if no shape is eligible
+// (e.g. more than 16384 tiles), 2, 3 or 4 tiles per worker of the format's own shape, the fewest
+// that make it eligible.  Of the eligible shapes, those within 1/16 of the stored groups of the
+// fewest empty positions; of these the format's own shape if it is among them (its kernel has
+// nothing to mask), else the fewest blocks per tile (more wavefronts, each done sooner), then the
+// most lanes in use.  For K up to 4096 only: beyond, a workgroup's share of x decides the
+// partition (partition_by_size).
+bool partition_by_rows(const gqsa_matrix& m, Partition* out)
+{
+    if (m.K > 4096) return false;
+    const int cb = m.code_bytes();
+    const int64_t nnz = m.nnzg();
+    if (nnz == 0) return false;
+    int64_t longest = 0;
+    bool uniform = true;          // every non-empty row as long as the longest: placement in closed form
+    for (int64_t n = 0; n < m.N; ++n) longest = std::max<int64_t>(longest, m.rowIndex[n + 1] - m.rowIndex[n]);
+    int64_t n_rows = 0;
+    for (int64_t n = 0; n < m.N; ++n) {
+        const int64_t c = m.rowIndex[n + 1] - m.rowIndex[n];
+        if (c > 0) ++n_rows;
+        if (c > 0 && c != longest) uniform = false;
+    }
+    const int wpw = 4;
+    struct Cand { int u, l, t; int64_t spans, pad; };
+    const Cand* best = nullptr;
+    std::vector<Cand> cands;
+    for (int t = 1; t <= 4 && !best; ++t) {
+        cands.clear();
+        int64_t least = INT64_MAX;
+        for (int u = 1; u <= 8; ++u) {
+            for (int l = 32; l <= kLanes; l += 4) {
+                if (!tile_shape_supported(cb, m.G, u, l)) continue;
+                if (t > 1 && !tile_shape_is_own(cb, u, l)) continue;      // tiles of a chosen shape come one to a worker
+                const int64_t span = static_cast<int64_t>(l) * u * t;
+                if (longest > span) continue;
+                int64_t spans;
+                if (uniform) {
+                    const int64_t per_span = span / longest;
+                    spans = (n_rows + per_span - 1) / per_span;
+                } else {
+                    const int64_t len = place_rows(m, span, nullptr);
+                    spans = (len + span - 1) / span;
+                }
+                const int64_t pad = spans * span - nnz;
+                if (spans > 16384 || pad > nnz / 8) continue;
+                cands.push_back(Cand{u, l, t, spans, pad});
+                least = std::min(least, pad);
+            }
+        }
+        for (const Cand& c : cands) {
+            if (c.pad > least + nnz / 16) continue;
+            if (!best) { best = &c; continue; }
+            const bool own_c = tile_shape_is_own(cb, c.u, c.l), own_b = tile_shape_is_own(cb, best->u, best->l);
+            const bool better = own_c != own_b ? own_c : c.u != best->u ? c.u < best->u : c.l > best->l;
+            if (better) best = &c;
+        }
+    }
+    if (!best) return false;
+    int64_t wgs = (best->spans + wpw - 1) / wpw;
+    if (wgs > 4) wgs = (wgs + 3) / 4 * 4;
+    if (wgs > kMaxWorkgroups) return false;
+    out->n_workgroups = static_cast<int>(wgs);
+    out->waves_per_workgroup = wpw;
+    out->span_tiles = best->t;
+    out->tile_blocks = best->u;
+    out->tile_lanes = best->l;
+    out->span_per_worker = 1;
+    return true;
+}
+
 }  // namespace
 
-// Default partition.  First by size (above).  A row whose groups lie in two workgroups costs
-// both an exchange through device memory at the very end of their work (about 0.6 us on an
-// MI355X, whatever the size of the matrix); null groups cost their bytes.  So, if the rows can be
-// kept inside the workgroups' spans (place_rows) with at most 2 MiB of null groups, they are:
-// spans of 4 t tiles for the small shapes (t the tiles per worker by size, or one more if that
-// needs too many null groups or more than 16384 workers), the workgroup count again a multiple of
-// 4; for the large ones
+// Default partition.  If the rows can be kept inside the workers' runs cheaply, they are
+// (partition_by_rows).  Otherwise by size (partition_by_size), with tiles of the format's own
+// block count, and then: a row whose groups lie in two workgroups costs both an exchange through
+// device memory at the very end of their work (about 0.6 us on an MI355X, whatever the size of
+// the matrix); null groups cost their bytes.  So, if the rows can be kept inside the workgroups'
+// spans (place_rows) with at most 2 MiB of null groups, they are: spans of 4 t tiles for the
+// small shapes (t the tiles per worker by size, or one more if that needs too many null groups
+// or more than 16384 workers), the workgroup count again a multiple of 4; for the large ones
 // the same 256, 512 or 768 workgroups with the smallest span that holds the rows.
-void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_workgroup, int* span_tiles)
+Partition default_partition(const gqsa_matrix& m)
 {
-    const int64_t tile_groups = static_cast<int64_t>(kLanes) * largest_tile(m.code_bytes());
+    Partition part;
+    if (partition_by_rows(m, &part)) return part;
+    part.tile_blocks = largest_tile(m.code_bytes());
+    part.tile_lanes = kLanes;
+    const int64_t tile_groups = static_cast<int64_t>(kLanes) * part.tile_blocks;
     const int64_t nnz = m.nnzg();
     const int64_t n_tiles = (nnz + tile_groups - 1) / tile_groups;
     int64_t t = 1, wgs = 1, wpw = 1;
     partition_by_size(n_tiles, m.K, &t, &wgs, &wpw);
-    *n_workgroups = static_cast<int>(std::min<int64_t>(wgs, kMaxWorkgroups));
-    *waves_per_workgroup = static_cast<int>(wpw);
-    *span_tiles = 0;
-    if (wpw < 4 || wgs < 2) return;       // a handful of tiles: nothing to keep apart
-    const int64_t max_null_groups = (int64_t{2} << 20) / (m.block_bytes() / kLanes);
+    part.n_workgroups = static_cast<int>(std::min<int64_t>(wgs, kMaxWorkgroups));
+    part.waves_per_workgroup = static_cast<int>(wpw);
+    if (wpw < 4 || wgs < 2) return part;       // a handful of tiles: nothing to keep apart
+    const int64_t max_null_groups = (int64_t{2} << 20) / m.group_bytes();
     int64_t span = 0, a_wgs = 0;
     if (t > 0) {
         bool found = false;
@@ -290,26 +373,30 @@ void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_w
             if (a_wgs > 4) a_wgs = (a_wgs + 3) / 4 * 4;
             found = len - nnz <= max_null_groups && a_wgs * wpw <= 16384;
         }
-        if (!found) return;
+        if (!found) return part;
     } else {
         a_wgs = wgs;
         for (span = (n_tiles + wgs - 1) / wgs;; ++span) {
             const int64_t len = place_rows(m, span * tile_groups, nullptr);
-            if (len - nnz > max_null_groups) return;
+            if (len - nnz > max_null_groups) return part;
             if ((len + span * tile_groups - 1) / (span * tile_groups) <= wgs) break;
         }
     }
-    if (a_wgs > kMaxWorkgroups || span > INT32_MAX / 2) return;
-    *n_workgroups = static_cast<int>(a_wgs);
-    *span_tiles = static_cast<int>(span);
+    if (a_wgs > kMaxWorkgroups || span > INT32_MAX / 2) return part;
+    part.n_workgroups = static_cast<int>(a_wgs);
+    part.span_tiles = static_cast<int>(span);
+    return part;
 }
 
 // Device image.  The stored groups, in canonical order, form a stream that is cut into
-// 64-group blocks; u_max blocks make a tile: 4 blocks with up to 16 code bytes per
-// group, 2 with 32, 1 with 64 (a wavefront's tile stays within about 24 registers).  The stream
-// is padded with null groups to whole tiles.  (With span_tiles > 0 the rows are first kept inside
-// spans of that many tiles, one span per workgroup -- place_rows -- and T = span_tiles *
-// n_workgroups; n_workgroups = 0 then stands for as many as the rows need.)  The T tiles are dealt in contiguous, near-equal runs
+// blocks of L groups (part.tile_lanes: the lanes of a wavefront that take a group, 64 by default);
+// U blocks make a tile -- part.tile_blocks, by default 4 blocks with up to 16
+// code bytes per group, 2 with 32, 1 with 64 (a wavefront's tile stays within about 24
+// registers).  The stream is padded with null groups to whole tiles.  With span_tiles > 0 the
+// rows are first kept inside spans of that many tiles (place_rows): one span per workgroup and
+// T = span_tiles * n_workgroups, or (span_per_worker) one span per wavefront worker and
+// T = span_tiles * n_workgroups * waves_per_workgroup; n_workgroups = 0 then stands for as many
+// as the rows need.  The T tiles are dealt in contiguous, near-equal runs
 // to the W = n_workgroups * waves_per_workgroup workers (wavefronts): worker w gets the tiles
 // floor(w T / W) .. floor((w+1) T / W) - 1, so that the workers with one tile more are spread
 // evenly over the workgroups (the nnz-balanced version of the paper's task-centric split,
@@ -318,7 +405,7 @@ void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_w
 // differently.  In a tile of U blocks lane l owns U consecutive stream positions, stored one
 // per block so that every block is a fully coalesced, lane-interleaved load:
 //     stream position (first of the tile) + p  ->  block (p mod U), lane (p div U).
-// Block = code planes | 64 x (scale | zero << 16) | 64 x (16 * LDS slot | head).  A group of
+// Block = code planes | L x (scale | zero << 16) | L x (16 * LDS slot | head).  A group of
 // G = 16 M elements has G*bits/8 code bytes; plane k holds bytes 16k..16k+15 of every lane's
 // code string (a single plane of 8 bytes per lane for 4-bit, G = 16).  The index word is the
 // byte offset in LDS of the group's first 16 activations (slot = group-column * M) with the
@@ -328,30 +415,38 @@ void default_partition(const gqsa_matrix& m, int* n_workgroups, int* waves_per_w
 // at bits 4m and element 8h+2m+1 at bits 16+4m.
 // (fill_blocks = false leaves the blocks empty -- the GPU packer writes them -- and row_pos_out,
 // if given, receives the first stream position of every row.)
-gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgroup, int span_tiles, bool fill_blocks,
-                          std::vector<int64_t>* row_pos_out)
+gqsa_status_t build_image(gqsa_matrix* m, const Partition& part, bool fill_blocks, std::vector<int64_t>* row_pos_out)
 {
+    int n_workgroups = part.n_workgroups;
+    const int waves_per_workgroup = part.waves_per_workgroup, span_tiles = part.span_tiles;
     if (n_workgroups < 0 || n_workgroups > kMaxWorkgroups || span_tiles < 0) return GQSA_ERR_RANGE;
     if (n_workgroups == 0 && span_tiles == 0) return GQSA_ERR_RANGE;
     if (waves_per_workgroup < 1 || waves_per_workgroup > kWavesPerWorkgroup) return GQSA_ERR_RANGE;
+    if (part.span_per_worker && span_tiles == 0) return GQSA_ERR_RANGE;
     const int cb = m->code_bytes();
-    const int u_max = largest_tile(cb);
-    const int64_t tile_groups = static_cast<int64_t>(kLanes) * u_max;
+    const int u_max = part.tile_blocks ? part.tile_blocks : largest_tile(cb);
+    const int lanes = part.tile_lanes ? part.tile_lanes : kLanes;
+    if (!tile_shape_supported(cb, m->G, u_max, lanes)) return GQSA_ERR_UNSUPPORTED;
+    // (the kernels for tiles of a chosen shape take one tile per worker)
+    if (!tile_shape_is_own(cb, u_max, lanes) && !(part.span_per_worker && span_tiles == 1)) return GQSA_ERR_UNSUPPORTED;
+    const int64_t tile_groups = static_cast<int64_t>(lanes) * u_max;
     if (span_tiles > (int64_t{1} << 40) / tile_groups) return GQSA_ERR_RANGE;
-    // rows -> stream positions; with spans, one span per workgroup
+    // rows -> stream positions; with spans, one span per workgroup or per worker
     std::vector<int64_t> row_pos;
     const int64_t span_groups = span_tiles * tile_groups;
     const int64_t len = place_rows(*m, span_groups, &row_pos);       // one past the last stored group
     int64_t n_tiles = (len + tile_groups - 1) / tile_groups;
     if (span_tiles > 0) {
         const int64_t n_spans = std::max<int64_t>(1, (len + span_groups - 1) / span_groups);
-        if (n_workgroups == 0) n_workgroups = static_cast<int>(std::min<int64_t>(n_spans, kMaxWorkgroups + 1));
-        if (n_spans > n_workgroups || n_workgroups > kMaxWorkgroups) return GQSA_ERR_RANGE;
-        n_tiles = static_cast<int64_t>(span_tiles) * n_workgroups;
+        const int64_t per_wg = part.span_per_worker ? waves_per_workgroup : 1;      // spans of a workgroup
+        const int64_t wgs_needed = (n_spans + per_wg - 1) / per_wg;
+        if (n_workgroups == 0) n_workgroups = static_cast<int>(std::min<int64_t>(wgs_needed, kMaxWorkgroups + 1));
+        if (wgs_needed > n_workgroups || n_workgroups > kMaxWorkgroups) return GQSA_ERR_RANGE;
+        n_tiles = static_cast<int64_t>(span_tiles) * n_workgroups * per_wg;
     }
     const int n_waves = n_workgroups * waves_per_workgroup;
     const int64_t nb = n_tiles * u_max;
-    const size_t bb = static_cast<size_t>(m->block_bytes());
+    const size_t bb = static_cast<size_t>(m->group_bytes()) * lanes;
     auto align = [](size_t v) { return (v + kAlign - 1) / kAlign * kAlign; };
 
     std::vector<int32_t> nonempty, empty;
@@ -404,14 +499,14 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
             std::memcpy(code.data(), v, cb);
         }
         for (int pl = 0; pl * plane_bytes < cb; ++pl)
-            std::memcpy(base + static_cast<size_t>(pl) * kLanes * plane_bytes + static_cast<size_t>(lane) * plane_bytes,
+            std::memcpy(base + static_cast<size_t>(pl) * lanes * plane_bytes + static_cast<size_t>(lane) * plane_bytes,
                         &code[static_cast<size_t>(pl) * plane_bytes], plane_bytes);
         const uint32_t sz = static_cast<uint32_t>(m->scales[g]) |
                             (static_cast<uint32_t>(m->zeros[g]) << 16);
-        std::memcpy(base + static_cast<size_t>(kLanes) * cb + lane * 4, &sz, 4);
+        std::memcpy(base + static_cast<size_t>(lanes) * cb + lane * 4, &sz, 4);
         // byte offset in LDS of the group's first 16 activations, row-head flag in bit 0
         const uint16_t ix = static_cast<uint16_t>(((m->groups[g] * slots_per_group) << 4) | (head[static_cast<size_t>(pos)] ? 1 : 0));
-        std::memcpy(base + static_cast<size_t>(kLanes) * cb + kLanes * 4 + lane * 2, &ix, 2);
+        std::memcpy(base + static_cast<size_t>(lanes) * cb + lanes * 4 + lane * 2, &ix, 2);
     };
     if (fill_blocks)
         for (int64_t n = 0; n < m->N; ++n)
@@ -438,7 +533,7 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     std::vector<int64_t> first_block(static_cast<size_t>(n_waves) + 1, 0);
     for (int w = 0; w <= n_waves; ++w) first_block[w] = (static_cast<int64_t>(w) * n_tiles / n_waves) * u_max;
     auto worker_of = [&](int64_t pos) {   // the worker whose run contains stream position pos
-        const int64_t blk = pos / kLanes;
+        const int64_t blk = pos / lanes;
         return static_cast<int32_t>(std::upper_bound(first_block.begin(), first_block.end(), blk) -
                                     first_block.begin() - 1);
     };
@@ -446,8 +541,8 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     int fix = 0;
     for (int w = 0; w < n_waves; ++w) {
         const int64_t mine = first_block[w + 1] - first_block[w];
-        const int64_t first = first_block[w] * kLanes;
-        const int64_t end = first_block[w + 1] * kLanes;
+        const int64_t first = first_block[w] * lanes;
+        const int64_t end = first_block[w + 1] * lanes;
         const int64_t hb = heads_below(std::min(first, len));
         const int64_t he = heads_below(std::min(end, len));
         const int closed = (end >= len || head[static_cast<size_t>(end)]) ? 1 : 0;
@@ -476,6 +571,9 @@ gqsa_status_t build_image(gqsa_matrix* m, int n_workgroups, int waves_per_workgr
     m->n_workgroups = n_workgroups;
     m->waves_per_workgroup = waves_per_workgroup;
     m->span_tiles = span_tiles;
+    m->span_per_worker = part.span_per_worker ? 1 : 0;
+    m->tile_blocks = u_max;
+    m->tile_lanes = lanes;
     m->n_waves = n_waves;
     m->n_blocks = nb;
     m->n_tiles = n_tiles;

@@ -40,7 +40,7 @@ struct PackArgs {
     uint8_t* blocks;           // device image, blocks region (zeroed beforehand)
     int* status;               // bit 0: a non-finite saliency; bit 1: a bad entry of hinv
     long long K;
-    int kg, G, bits, cb, U, bb, slots_per_group;
+    int kg, G, bits, cb, U, L, bb, slots_per_group;     // (U blocks per tile, L lanes in use per block)
 };
 
 __device__ __forceinline__ uint16_t half_bits(float f) { return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f)); }
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void pack_rows_kernel(PackArgs a)
         a.zeros[g] = zb;
         // where the group sits in the image: tile of U blocks, lane l owns U consecutive positions
         const long long pos = a.row_pos[n] + i;
-        const long long tile_groups = 64ll * a.U;
+        const long long tile_groups = static_cast<long long>(a.L) * a.U;
         const long long p = pos % tile_groups;
         const long long block = pos / tile_groups * a.U + p % a.U;
         const int lane = static_cast<int>(p / a.U);
@@ -164,18 +164,18 @@ __global__ __launch_bounds__(kThreads) void pack_rows_kernel(PackArgs a)
                 }
                 *reinterpret_cast<uint32_t*>(vout + 4 * h) = canon;
                 const int byte = 4 * h;             // of the lane's code string
-                *reinterpret_cast<uint32_t*>(base + (byte / pb) * 64 * pb + lane * pb + byte % pb) = image;
+                *reinterpret_cast<uint32_t*>(base + (byte / pb) * a.L * pb + lane * pb + byte % pb) = image;
             } else {
                 for (int half = 0; half < 2; ++half) {
                     const uint32_t word = q8[4 * half] | (q8[4 * half + 1] << 8) | (q8[4 * half + 2] << 16) | (q8[4 * half + 3] << 24);
                     const int byte = 8 * h + 4 * half;
                     *reinterpret_cast<uint32_t*>(vout + byte) = word;
-                    *reinterpret_cast<uint32_t*>(base + (byte / pb) * 64 * pb + lane * pb + byte % pb) = word;
+                    *reinterpret_cast<uint32_t*>(base + (byte / pb) * a.L * pb + lane * pb + byte % pb) = word;
                 }
             }
         }
-        *reinterpret_cast<uint32_t*>(base + 64 * cb + lane * 4) = static_cast<uint32_t>(sb) | (static_cast<uint32_t>(zb) << 16);
-        *reinterpret_cast<uint16_t*>(base + 64 * cb + 256 + lane * 2) =
+        *reinterpret_cast<uint32_t*>(base + a.L * cb + lane * 4) = static_cast<uint32_t>(sb) | (static_cast<uint32_t>(zb) << 16);
+        *reinterpret_cast<uint16_t*>(base + a.L * (cb + 4) + lane * 2) =
             static_cast<uint16_t>(((c * a.slots_per_group) << 4) | (i == 0 ? 1 : 0));
     }
 }
@@ -214,10 +214,8 @@ gqsa_status_t pack_on_device(const float* W_dev, const float* hinv_dev, gqsa_mat
     if (m->K / m->G > kMaxColumns) return GQSA_ERR_SHAPE;
     // the layout of the image follows from the row pointers alone: partition, row positions,
     // per-worker records, row tables (host), with the blocks left empty
-    int wgs = 1, wpw = 1, span = 0;
-    default_partition(*m, &wgs, &wpw, &span);
     std::vector<int64_t> row_pos;
-    if (gqsa_status_t st = build_image(m, wgs, wpw, span, /*fill_blocks=*/false, &row_pos)) return st;
+    if (gqsa_status_t st = build_image(m, default_partition(*m), /*fill_blocks=*/false, &row_pos)) return st;
     m->groups.assign(static_cast<size_t>(nnz), 0);
     m->values.assign(static_cast<size_t>(nnz) * cb, 0);
     m->scales.assign(static_cast<size_t>(nnz), 0);
@@ -255,7 +253,8 @@ gqsa_status_t pack_on_device(const float* W_dev, const float* hinv_dev, gqsa_mat
     a.G = m->G;
     a.bits = m->bits;
     a.cb = cb;
-    a.U = largest_tile(cb);
+    a.U = m->tile_blocks;
+    a.L = m->tile_lanes;
     a.bb = m->block_bytes();
     a.slots_per_group = m->G >= 16 ? m->G / 16 : 1;
     if (hinv_dev)

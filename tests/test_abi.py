@@ -148,14 +148,14 @@ def test_allocation_failure_is_a_status_not_an_exception():
 def test_default_partition_entry_checks_its_arguments():
     lib = binding._lib()
     ri = np.array([0, 2, 3], dtype=np.int32)
-    out = (C.c_int32 * 3)()
+    out = (C.c_int32 * 6)()
     assert lib.gqsa_default_partition(None, 2, 64, 16, 4, C.byref(out)) == 1
     assert lib.gqsa_default_partition(C.c_void_p(ri.ctypes.data), 2, 64, 16, 4, None) == 1
     assert lib.gqsa_default_partition(C.c_void_p(ri.ctypes.data), 2, 64, 16, 5, C.byref(out)) == 3
     assert lib.gqsa_default_partition(C.c_void_p(ri.ctypes.data), 2, 24, 16, 4, C.byref(out)) == 2
     bad = np.array([0, 9, 3], dtype=np.int32)                      # 9 groups in a row of 4 columns
     assert lib.gqsa_default_partition(C.c_void_p(bad.ctypes.data), 2, 64, 16, 4, C.byref(out)) == 2
-    assert gq.gqsa_default_partition(ri, 64) == (1, 1, 0)
+    assert gq.gqsa_default_partition(ri, 64) == (1, 1, 0, 4, 64, 0)      # three groups fill no tile: one worker, one padded tile
 
 
 def test_gemv_multi_host_side_checks_need_no_gpu():
@@ -184,11 +184,13 @@ def test_info_fields():
     nnz = int(keep.sum())
     assert info["N"] == 100 and info["K"] == 512 and info["G"] == 16 and info["bits"] == 8
     assert info["nnz_groups"] == nnz and info["values_bytes"] == nnz * 16
-    # whole tiles of four 64-group blocks (16 code bytes); by default the rows are kept inside the workgroups' spans
-    assert info["span_tiles"] == 4 and info["n_blocks"] == 4 * info["span_tiles"] * info["n_workgroups"]
+    # short rows (at most 32 groups) fill tiles of any shape well: by default whole rows per worker, one tile each
+    assert info["span_tiles"] == 1 and info["span_per_worker"] == 1 and info["needs_fixup"] == 0
+    assert info["n_blocks"] == info["tile_blocks"] * info["n_workgroups"] * info["waves_per_workgroup"]
+    assert info["n_blocks"] * info["tile_lanes"] <= nnz + nnz // 8 + info["tile_blocks"] * info["tile_lanes"] * 4 * 3
     gq.gqsa_set_partition(h, 3, 2)
     info = gq.gqsa_info(h)
-    assert info["span_tiles"] == 0 and info["n_blocks"] == 4 * ((nnz + 255) // 256)
+    assert info["span_tiles"] == 0 and info["n_blocks"] == 4 * ((nnz + 255) // 256) and info["tile_lanes"] == 64
     assert info["n_empty_rows"] == int((keep == 0).sum())
     assert info["on_device"] == 0
     assert info["algorithmic_bytes"] == nnz * 22 + 101 * 4 + (512 + 100) * 2
@@ -254,28 +256,41 @@ def _balanced(n_rows, per_row):
 
 def test_default_partition_hand_table():
     """The partition the library chooses by itself, against values worked out by hand from its
-    documented rule (include/gqsa.h, gqsa_set_partition)."""
+    documented rule (include/gqsa.h, gqsa_set_partition): (workgroups, wavefronts per workgroup,
+    tiles per span, blocks per tile, lanes in use, span per worker)."""
     dp = gq.gqsa_default_partition
-    assert dp(_balanced(1, 0), 4096) == (1, 1, 0)
-    assert dp(_balanced(3, 256), 4096) == (1, 3, 0)             # 3 tiles of 256 groups, one per wavefront
-    assert dp(_balanced(16, 128), 4096) == (2, 4, 4)            # 8 tiles; two rows per tile
-    assert dp(_balanced(17, 256), 4096) == (8, 4, 4)            # 17 workers -> 5 workgroups -> a multiple of 4
-    assert dp(_balanced(4096, 128), 4096) == (512, 4, 4)        # 4096x4096 at S = 50 %: 2048 tiles, one per wavefront; no null group needed
-    assert dp(_balanced(11008, 128), 4096) == (1376, 4, 4)      # 11008x4096: 5504 tiles
-    assert dp(_balanced(8193, 256), 4096) == (2052, 4, 4)       # still one tile per worker
-    assert dp(_balanced(16384, 256), 4096) == (4096, 4, 4)      # the most workers
-    assert dp(_balanced(16385, 256), 4096) == (2052, 4, 8)      # beyond: two tiles per worker, 8193 workers
-    assert dp(_balanced(4096, 344), 11008) == (256, 8, 22)      # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
-    assert dp(_balanced(8191, 256), 8192) == (512, 8, 16)       # 448 T / K = 448 -> two per compute unit
-    assert dp(_balanced(28615, 256), 8192) == (768, 8, 38)      # at most three
-    assert dp(_balanced(4096, 256), 8192) == (256, 8, 16)       # 4096x8192 at S = 50 %
-    assert dp(_balanced(100, 256), 32768) == (28, 4, 4)         # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
-    assert dp(_balanced(2048, 32), 4096, G=128) == (256, 4, 4)  # 64 code bytes: a tile is one block, 1024 tiles
-    assert dp(_balanced(2048, 128), 4096, G=16, bits=8) == (256, 4, 4)  # 16 code bytes: tiles of 4 blocks, 1024 tiles
-    # rows that do not divide the spans: null groups keep them inside
-    assert dp(_balanced(4096, 179), 4096) == (820, 4, 4)        # S = 30 %: 5 rows per span of 1024, 820 spans
-    assert dp(_balanced(14336, 179), 4096) == (1304, 4, 8)      # 10024 tiles: 5 rows per span of 1024 would need 5 MB of null groups, 11 per span of 2048 need 1.4 MB
-    assert dp(_balanced(4096, 205), 4096) == (456, 4, 8)        # 4 rows per span of 1024: 2.9 MB; 9 per span of 2048: 1.2 MB
-    assert dp(_balanced(4096, 77), 4096) == (316, 4, 4)         # S = 70 %: 13 rows per span, 316 spans
+    assert dp(_balanced(1, 0), 4096) == (1, 1, 0, 4, 64, 0)                # nothing stored: the plain deal of no tiles
+    # K <= 4096, rows that fill tiles of the format's own shape: whole rows per worker, one tile each
+    assert dp(_balanced(3, 256), 4096) == (1, 4, 1, 4, 64, 1)              # 3 tiles of 256 groups, a row each
+    assert dp(_balanced(16, 128), 4096) == (2, 4, 1, 4, 64, 1)             # 8 tiles; two rows per tile
+    assert dp(_balanced(17, 256), 4096) == (8, 4, 1, 4, 64, 1)             # 17 workers -> 5 workgroups -> a multiple of 4
+    assert dp(_balanced(4096, 128), 4096) == (512, 4, 1, 4, 64, 1)         # 4096x4096 at S = 50 %: 2048 tiles
+    assert dp(_balanced(11008, 128), 4096) == (1376, 4, 1, 4, 64, 1)       # 11008x4096: 5504 tiles
+    assert dp(_balanced(8193, 256), 4096) == (2052, 4, 1, 4, 64, 1)
+    assert dp(_balanced(16384, 256), 4096) == (4096, 4, 1, 4, 64, 1)       # the most workers
+    assert dp(_balanced(16385, 256), 4096) == (2052, 4, 2, 4, 64, 1)       # beyond: two tiles (two rows) per worker, 8193 workers
+    assert dp(_balanced(128256, 128), 4096) == (4008, 4, 4, 4, 64, 1)      # 64128 tiles: four per worker
+    assert dp(_balanced(2048, 32), 4096, G=128) == (256, 4, 1, 1, 64, 1)   # 64 code bytes: a tile is one block, two rows in it
+    assert dp(_balanced(2048, 128), 4096, G=16, bits=8) == (256, 4, 1, 4, 64, 1)   # 16 code bytes: tiles of 4 blocks
+    assert dp(_balanced(4096, 100), 4096, G=32) == (208, 4, 2, 4, 64, 1)   # no other shape for G = 32: 2 rows in 256 leave 28 % empty, 5 rows in two tiles 2.4 %
+    # rows that do not fill such tiles: a shape that they do fill
+    assert dp(_balanced(4096, 179), 4096) == (1024, 4, 1, 3, 60, 1)        # S = 30 %: 179 of 3 x 60 = 180 positions, a row per worker
+    assert dp(_balanced(14336, 179), 4096) == (3584, 4, 1, 3, 60, 1)
+    assert dp(_balanced(4096, 179), 4096, bits=8) == (1024, 4, 1, 3, 60, 1)
+    assert dp(_balanced(4096, 205), 4096) == (1024, 4, 1, 4, 52, 1)        # 205 of 4 x 52 = 208 (three blocks hold 192 at most)
+    assert dp(_balanced(4096, 77), 4096) == (512, 4, 1, 3, 52, 1)          # S = 70 %: two rows (154) of 3 x 52 = 156
+    alternating = np.concatenate(([0], np.cumsum(np.tile([256, 8], 500))))
+    assert dp(alternating, 4096) == (128, 4, 1, 5, 56, 1)                   # a long and a short row (264) of 5 x 56 = 280: 6 % empty
+    alternating = np.concatenate(([0], np.cumsum(np.tile([256, 100], 500))))
+    assert dp(alternating, 4096) == (64, 4, 3, 4, 64, 1)                    # 356 fit no tile twice; two pairs (712) in three tiles (768): 250 workers
+    # rows that fill nothing well: the deal by size, rows kept inside the workgroups' spans
+    uneven = np.concatenate(([0], np.cumsum(np.tile([250, 30, 3, 140], 250))))
+    assert dp(uneven, 4096) == (128, 4, 4, 4, 64, 0)
+    # K > 4096: by size
+    assert dp(_balanced(4096, 344), 11008) == (256, 8, 22, 4, 64, 0)       # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
+    assert dp(_balanced(8191, 256), 8192) == (512, 8, 16, 4, 64, 0)        # 448 T / K = 448 -> two per compute unit
+    assert dp(_balanced(28615, 256), 8192) == (768, 8, 38, 4, 64, 0)       # at most three
+    assert dp(_balanced(4096, 256), 8192) == (256, 8, 16, 4, 64, 0)        # 4096x8192 at S = 50 %
+    assert dp(_balanced(100, 256), 32768) == (28, 4, 4, 4, 64, 0)          # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
     # too many null groups (a row of 600 per span of 1024: 424 of 1024 positions empty): the plain deal
-    assert dp(_balanced(12000, 600), 16384) == (768, 8, 0)
+    assert dp(_balanced(12000, 600), 16384) == (768, 8, 0, 4, 64, 0)

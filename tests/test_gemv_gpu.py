@@ -114,22 +114,84 @@ def test_rows_kept_inside_workgroup_spans(torch_cuda, part, batch):
     check(torch_cuda, h, c, gi.activations(batch, K, seed=9))
 
 
-@pytest.mark.parametrize("keep_n,expect", [(179, (820, 4, 4)), (77, (316, 4, 4)), (100, (412, 4, 4))])
-def test_default_keeps_rows_inside_workgroups_full_size(torch_cuda, keep_n, expect):
-    """4096x4096 with rows that do not divide the tiles (S = 30 %, 70 %, 61 %): the default keeps
-    every row inside a workgroup; every output checked, also of the plain form with as many workers."""
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("shape", [(3, 60, 0, 4), (3, 44, 0, 1), (4, 32, 0, 4), (4, 64, 0, 16), (5, 36, 0, 3), (5, 64, 40, 8), (3, 32, 0, 4)])
+def test_rows_kept_inside_workers_tiles(torch_cuda, shape, bits):
+    """Tiles of a chosen shape (3, 4, 5 blocks; 32..64 lanes in use), one per worker, whole rows in
+    them -- and, with 3 x 32, rows longer than a tile, shared by workers as in the other forms;
+    ragged rows, empty rows, workers whose tile is null; every kernel for 1, 2, 4, 8 activation
+    rows (3 and 7 rows run in the kernels for 4 and 8)."""
+    N, K = 301, 2048
+    W = gi.dense_weight(N, K, seed=78)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=78)
+    keep[[0, 5, 6, 7, 300]] = 0
+    keep[100] = K // 16
+    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    u, lanes, wgs, wpw = shape
+    gq.gqsa_set_partition_rows(h, u, lanes, 1, wgs, wpw)
+    assert gq.gqsa_info(h)["needs_fixup"] == (1 if u * lanes < 128 else 0)
+    for batch in (1, 2, 3, 4, 7, 8, 16):
+        check(torch_cuda, h, c, gi.activations(batch, K, seed=9 + batch))
+
+
+def test_rows_of_a_batch_are_the_single_row_results_with_chosen_tile_shapes(torch_cuda):
+    """Tiles of 3 x 60 (179 groups per row): every batch size gives, row for row, the bits of the
+    one-row call; q/k/v-like matrices of that shape share a launch and give the bits of separate
+    calls; a matrix of another tile shape in the same call goes out in a launch of its own."""
+    torch = torch_cuda
+    K = 4096
+    hs, cs = [], []
+    for i, (N, keep_n) in enumerate(((512, 179), (128, 179), (130, 179), (256, 77))):
+        W = gi.dense_weight(N, K, seed=300 + i)
+        keep = np.full(N, keep_n, dtype=np.int32)
+        hs.append(gq.gqsa_pack_rows(W, keep, 16, 4))
+        cs.append(oracle.pack(W, 16, 4, keep_per_row=keep))
+    assert [gq.gqsa_partition(h)[3:5] for h in hs] == [(3, 60), (3, 60), (3, 60), (3, 52)]
+    x16 = gi.activations(16, K, seed=31)
+    y16 = run_gemv(torch, hs[0], x16)
+    for batch in (1, 2, 3, 4, 5, 7, 8, 11):
+        y = run_gemv(torch, hs[0], x16[:batch])
+        assert np.array_equal(y.view(np.uint16), y16[:batch].view(np.uint16)), batch
+    for batch in (1, 4):
+        x = torch.from_numpy(x16[:batch]).cuda()
+        for group in (hs[:3], hs):
+            ys = gq.gqsa_gemv_multi(group, x)
+            torch.cuda.synchronize()
+            for h, c, y in zip(group, cs, ys):
+                got = y.cpu().numpy()
+                assert np.array_equal(got.view(np.uint16), run_gemv(torch, h, x16[:batch]).view(np.uint16))
+                ref = oracle.gemv(c, x16[:batch])
+                for b in range(batch):
+                    assert oracle.rel_error(got[b], ref[b]) <= TOL
+
+
+@pytest.mark.parametrize("keep_n,expect,aligned", [(179, (1024, 4, 1, 3, 60, 1), (820, 4, 4)), (77, (512, 4, 1, 3, 52, 1), (316, 4, 4)),
+                                                   (100, (512, 4, 1, 4, 52, 1), (412, 4, 4)), (205, (1024, 4, 1, 4, 52, 1), (456, 4, 8))])
+def test_default_keeps_rows_inside_workers_full_size(torch_cuda, keep_n, expect, aligned):
+    """4096x4096 with rows that do not divide the tiles of 4 x 64 (S = 30 %, 70 %, 61 %, 20 %): the default
+    takes a tile shape that whole rows fill and no worker shares a row; every output checked, also
+    of the form that keeps the rows inside the workgroups' spans and of the plain form with as
+    many workers (rows shared by wavefronts and by workgroups)."""
     N, K = 4096, 4096
     W = gi.dense_weight_chunked(N, K, seed=41)
     keep = np.full(N, keep_n, dtype=np.int32)
     c = oracle.pack(W, 16, 4, keep_per_row=keep)
     h = gq.gqsa_pack_rows(W, keep, 16, 4)
+    assert gq.gqsa_partition(h) == expect
     info = gq.gqsa_info(h)
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == expect
+    assert info["needs_fixup"] == 0
+    assert gq.gqsa_export_device_blob(h) == oracle.device_blob_for(c, info)
     x = gi.activations(1, K, seed=10)
     check(torch_cuda, h, c, x)
     gq.gqsa_free(h)
+    h1 = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition_aligned(h1, aligned[2], aligned[0], aligned[1])
+    assert gq.gqsa_partition(h1) == aligned + (4, 64, 0) and gq.gqsa_info(h1)["needs_fixup"] == 1
+    check(torch_cuda, h1, c, x)
+    gq.gqsa_free(h1)
     h2 = gq.gqsa_pack_rows(W, keep, 16, 4)     # the plain form with the same workers: rows shared by workgroups
-    gq.gqsa_set_partition(h2, expect[0], 4)
+    gq.gqsa_set_partition(h2, aligned[0], 4)
     check(torch_cuda, h2, c, x)
 
 
@@ -429,7 +491,7 @@ def test_other_group_sizes_full_size_and_sparsities(torch_cuda, G):
         h = gq.gqsa_pack(W, G, 4, sparsity)
         c = oracle.pack(W, G, 4, sparsity=sparsity)
         info = gq.gqsa_info(h)
-        assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
+        assert gq.gqsa_export_device_blob(h) == oracle.device_blob_for(c, info)
         check(torch_cuda, h, c, gi.activations(1, 4096, seed=11))
 
 
@@ -482,7 +544,7 @@ def test_llama7b_layer_shapes_full_size(torch_cuda, idx):
     h = gq.gqsa_pack(W, 16, 4, 0.5)
     c = oracle.pack(W, 16, 4, sparsity=0.5)
     info = gq.gqsa_info(h)
-    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
+    assert gq.gqsa_export_device_blob(h) == oracle.device_blob_for(c, info)
     check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(2, idx)))
 
 
@@ -497,9 +559,8 @@ def test_llama3_8b_sparsity_sweep_full_size(torch_cuda, idx, sparsity):
     h = gq.gqsa_pack(W, 16, 4, sparsity)
     c = oracle.pack(W, 16, 4, sparsity=sparsity)
     info = gq.gqsa_info(h)
-    part = (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
-    assert part == gq.gqsa_default_partition(c.rowIndex, K)
-    assert gq.gqsa_export_device_blob(h) == oracle.device_blob(c, *part)
+    assert gq.gqsa_partition(h) == gq.gqsa_default_partition(c.rowIndex, K)
+    assert gq.gqsa_export_device_blob(h) == oracle.device_blob_for(c, info)
     check(torch_cuda, h, c, gi.activations(1, K, seed=gi.config_seed(3, idx)))
     gq.gqsa_free(h)
 
@@ -518,7 +579,7 @@ def test_imbalanced_stress_full_size(torch_cuda, idx):
 
 def test_vocabulary_sized_matrix(torch_cuda):
     """128256x4096 (the output projection of a LLaMA-3-8B-like model), W4S50: 16.4 M stored groups,
-    64 128 tiles, four per wavefront in 4008 workgroups -- the largest deal the default makes.
+    64 128 tiles, four (eight rows) per wavefront in 4008 workgroups -- the largest deal the default makes.
     Every output checked."""
     N, K = 128256, 4096
     W = gi.dense_weight_chunked(N, K, seed=51)
@@ -527,7 +588,7 @@ def test_vocabulary_sized_matrix(torch_cuda):
     del W
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == N * 128
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == (4008, 4, 16)
+    assert gq.gqsa_partition(h) == (4008, 4, 4, 4, 64, 1)
     check(torch_cuda, h, c, gi.activations(1, K, seed=52))
     gq.gqsa_free(h)
 

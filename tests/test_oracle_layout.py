@@ -64,8 +64,8 @@ def test_placement_three_workers_by_hand():
 
 def test_placement_with_smaller_tiles_by_hand():
     # 32 code bytes per group: tiles of 2 blocks; 64: every block by itself
-    assert layout.tile_blocks(8) == 4 and layout.tile_blocks(16) == 4
-    assert layout.tile_blocks(32) == 2 and layout.tile_blocks(64) == 1
+    assert layout.default_tile_blocks(8) == 4 and layout.default_tile_blocks(16) == 4
+    assert layout.default_tile_blocks(32) == 2 and layout.default_tile_blocks(64) == 1
     block, lane, _, _ = layout.stream_placement(6, 1, 2)
     assert (block[0], lane[0]) == (0, 0)
     assert (block[1], lane[1]) == (1, 0)
@@ -222,6 +222,84 @@ def test_blob_decodes_back_to_canonical(bits, G, n_wg, wpw):
     off = (off + 4 * len(nonempty) + 255) // 256 * 256
     assert list(np.frombuffer(blob, dtype="<i4", count=len(empty), offset=off)) == empty
     assert len(blob) == (off + 4 * len(empty) + 255) // 256 * 256
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("U,LN,n_wg,wpw", [(3, 60, 5, 4), (4, 36, 9, 2), (5, 64, 3, 4), (4, 64, 3, 7)])
+def test_blob_with_a_span_per_worker_and_a_tile_shape_decodes_back(bits, U, LN, n_wg, wpw):
+    """Spans per worker, tiles of U blocks with LN lanes in use (spec items 1, 3, 4), read back with
+    plain loops: worker w's tile is blocks wU .. wU+U-1 of (cb + 6) * LN bytes, position p of the
+    tile in block p mod U at entry p div U; the rows come back whole, in order, each inside one
+    worker's tile, everything else is null, and no worker shares a row."""
+    N, K, G = 40, 1024, 16
+    cb = G * bits // 8
+    W = gi.dense_weight(N, K, seed=43)
+    keep = gi.imbalanced_keep_counts(N, K // G, seed=43)
+    keep = np.minimum(keep, 40)
+    keep[[5, N - 1]] = 0
+    c = oracle.pack(W, G=G, bits=bits, keep_per_row=keep)
+    n_waves = n_wg * wpw
+    blob = oracle.device_blob(c, n_wg, wpw, 1, U, LN, True)
+    raw = np.frombuffer(blob, dtype=np.uint8)
+    bb = (cb + 6) * LN
+    got_rows = []          # (worker, [columns], [scale bits], [zero bits], [[codes]])
+    for w in range(n_waves):
+        current = None
+        for p in range(U * LN):
+            base = (w * U + p % U) * bb
+            e = p // U
+            code = raw[base + e * cb:base + (e + 1) * cb]
+            sz = int.from_bytes(raw[base + LN * cb + 4 * e:base + LN * cb + 4 * e + 4].tobytes(), "little")
+            ix = int.from_bytes(raw[base + LN * (cb + 4) + 2 * e:base + LN * (cb + 4) + 2 * e + 2].tobytes(), "little")
+            if ix & 1:
+                current = (w, [], [], [], [])
+                got_rows.append(current)
+            if sz == 0 and ix == 0 and not code.any():
+                continue                                 # a null group (no stored scale is 0: the floor is 2^-14)
+            assert current is not None, "a stored group before the first row head of a tile"
+            current[1].append(ix >> 4)
+            current[2].append(sz & 0xFFFF)
+            current[3].append(sz >> 16)
+            if bits == 4:
+                q = []
+                for h in range(2):
+                    word = int.from_bytes(code[4 * h:4 * h + 4].tobytes(), "little")
+                    for m in range(4):
+                        q += [(word >> (4 * m)) & 0xF, (word >> (16 + 4 * m)) & 0xF]
+                current[4].append(q)
+            else:
+                current[4].append(list(code))
+    rows = [n for n in range(N) if keep[n] > 0]
+    assert len(got_rows) == len(rows)
+    workers = []
+    for (w, cols, sc, ze, q), n in zip(got_rows, rows):
+        g0, g1 = c.rowIndex[n], c.rowIndex[n + 1]
+        assert cols == list(c.groups[g0:g1]) and sc == list(c.scales[g0:g1]) and ze == list(c.zeros[g0:g1])
+        v = np.asarray(c.values).reshape(c.nnzg, cb)[g0:g1]
+        if bits == 4:
+            ref = np.empty((g1 - g0, G), dtype=np.int64)
+            ref[:, 0::2] = v & 0xF
+            ref[:, 1::2] = v >> 4
+        else:
+            ref = v.astype(np.int64)
+        assert np.array_equal(np.array(q), ref)
+        workers.append(w)
+    assert workers == sorted(workers)
+    # greedy placement by hand: a row goes to the current worker's tile if it still fits
+    w, used, expect = 0, 0, []
+    for n in rows:
+        if used + keep[n] > U * LN:
+            w, used = w + 1, 0
+        expect.append(w)
+        used += keep[n]
+    assert workers == expect
+    # worker records: rank of the row open at the start = (rows before the worker) - 1; nothing shared
+    off = (n_waves * U * bb + 255) // 256 * 256
+    wave_info = np.frombuffer(blob, dtype="<i4", count=4 * n_waves, offset=off).reshape(n_waves, 4)
+    for w in range(n_waves):
+        assert list(wave_info[w]) == [sum(1 for x in expect if x < w) - 1, 1, -1, 0]
+    with pytest.raises(ValueError):
+        oracle.device_blob(c, 1, 1, 1, U, LN, True)      # more spans needed than workers
 
 
 def test_blob_of_empty_matrix():

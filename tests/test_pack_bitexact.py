@@ -24,7 +24,7 @@ def assert_same_canonical(h, c):
 def assert_same_blob(h, c):
     info = gq.gqsa_info(h)
     blob = gq.gqsa_export_device_blob(h)
-    ref = oracle.device_blob(c, info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
+    ref = oracle.device_blob_for(c, info)
     assert len(blob) == len(ref) == info["device_bytes"]
     assert blob == ref
 
@@ -39,7 +39,7 @@ def test_tiny_config_balanced(bits, sparsity):
     assert_same_blob(h, c)
     info = gq.gqsa_info(h)
     assert info["nnz_groups"] == c.nnzg
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == gq.gqsa_default_partition(c.rowIndex, 256, 16, bits)
+    assert gq.gqsa_partition(h) == gq.gqsa_default_partition(c.rowIndex, 256, 16, bits)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(256, 256, 16, bits, c.nnzg, 1)
 
 
@@ -87,8 +87,9 @@ def test_aligned_stream_keeps_rows_inside_spans():
     W = gi.dense_weight(N, K, seed=79)
     keep = np.full(N, 179, dtype=np.int32)               # S = 30 %: 5 rows per span of 1024, 129 null groups after them
     h = gq.gqsa_pack_rows(W, keep, G, bits)
+    gq.gqsa_set_partition_aligned(h, 4, 0, 4)
     info = gq.gqsa_info(h)
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == (100, 4, 4)
+    assert gq.gqsa_partition(h) == (100, 4, 4, 4, 64, 0)
     blob = np.frombuffer(gq.gqsa_export_device_blob(h), dtype=np.uint8)
     nblocks = info["n_blocks"]
     blk = blob[:nblocks * 896].reshape(nblocks, 896)
@@ -101,6 +102,73 @@ def test_aligned_stream_keeps_rows_inside_spans():
     assert np.all(head_pos // 1024 == (head_pos + 178) // 1024)
     assert np.array_equal(head_pos[:6], [0, 179, 358, 537, 716, 1024])
     assert np.all(scale[895:1024] == 0) and np.all(ix.transpose(0, 2, 1).reshape(-1)[895:1024] == 0)   # the null groups
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_rows_kept_inside_workers_tiles(bits):
+    """The form with one span per worker and tiles of a chosen shape (blocks per tile, lanes in
+    use): the image against the oracle's for uniform and ragged rows, the sizes that follow from
+    the shape, and what the library refuses."""
+    N, K = 301, 2048
+    W = gi.dense_weight(N, K, seed=78)
+    keep = gi.imbalanced_keep_counts(N, K // 16, seed=78)
+    keep[[0, 5, 6, 7, 300]] = 0
+    keep[100] = K // 16                                  # the longest row: 128 groups
+    h = gq.gqsa_pack_rows(W, keep, 16, bits)
+    c = oracle.pack(W, 16, bits, keep_per_row=keep)
+    for (u, lanes, wgs, wpw) in ((3, 60, 0, 4), (3, 44, 0, 1), (4, 32, 0, 4), (4, 64, 0, 16), (5, 36, 0, 3), (5, 64, 40, 8)):
+        gq.gqsa_set_partition_rows(h, u, lanes, 1, wgs, wpw)
+        info = gq.gqsa_info(h)
+        _, L = oracle.row_positions(c.rowIndex, u * lanes)
+        spans = -(-L // (u * lanes))
+        assert (info["tile_blocks"], info["tile_lanes"], info["span_tiles"], info["span_per_worker"]) == (u, lanes, 1, 1)
+        assert info["n_workgroups"] == (wgs if wgs else -(-spans // wpw)) and info["waves_per_workgroup"] == wpw
+        assert info["n_blocks"] == u * info["n_workgroups"] * wpw
+        assert info["needs_fixup"] == 0                 # every row fits a tile of these shapes
+        assert_same_blob(h, c)
+    # rows longer than a tile are shared by workers as in the other forms
+    gq.gqsa_set_partition_rows(h, 3, 32, 1, 0, 4)
+    assert gq.gqsa_info(h)["needs_fixup"] == 1
+    assert_same_blob(h, c)
+    # several tiles per worker: of the format's own shape only
+    gq.gqsa_set_partition_rows(h, 4, 64, 3, 0, 2)
+    assert gq.gqsa_partition(h)[2:] == (3, 4, 64, 1)
+    assert_same_blob(h, c)
+    for (args, status) in (((3, 60, 2, 0, 4), 3), ((2, 64, 1, 0, 4), 3), ((6, 64, 1, 0, 4), 3), ((3, 62, 1, 0, 4), 3),
+                           ((3, 28, 1, 0, 4), 3), ((3, 68, 1, 0, 4), 3), ((0, 64, 1, 0, 4), 4), ((3, 0, 1, 0, 4), 4),
+                           ((3, 60, 0, 0, 4), 4), ((3, 60, 1, 1, 4), 4), ((3, 60, 1, 0, 17), 4), ((3, 60, 1, 4097, 4), 4)):
+        with pytest.raises(gq.GqsaError) as e:
+            gq.gqsa_set_partition_rows(h, *args)
+        assert e.value.status == status, args
+    # other group sizes have their own shape only
+    h64 = gq.gqsa_pack(W, 64, 4, 0.5)
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_set_partition_rows(h64, 3, 60, 1, 0, 4)
+    assert e.value.status == 3
+    gq.gqsa_set_partition_rows(h64, 2, 64, 1, 0, 4)
+    assert_same_blob(h64, oracle.pack(W, 64, 4, sparsity=0.5))
+
+
+def test_default_keeps_uniform_rows_inside_workers_tiles():
+    """Read back from the image: at S = 30 % (179 groups per row) every worker's tile of 3 x 60
+    positions holds one row -- its head in lane 0 of block 0, one null group at the end."""
+    N, K = 500, 4096
+    W = gi.dense_weight(N, K, seed=79)
+    h = gq.gqsa_pack(W, 16, 4, 0.3)
+    assert gq.gqsa_partition(h) == (128, 4, 1, 3, 60, 1)       # 500 workers -> 125 workgroups -> a multiple of 4
+    info = gq.gqsa_info(h)
+    assert info["n_blocks"] == 3 * 512 and info["device_bytes"] >= 3 * 512 * 60 * 14
+    blob = np.frombuffer(gq.gqsa_export_device_blob(h), dtype=np.uint8)
+    blk = blob[:info["n_blocks"] * 840].reshape(-1, 3, 840)     # [tile][block][60 x (8 + 4 + 2) bytes]
+    ix = blk[:, :, 720:].copy().view("<u2")                      # [tile][block][lane]
+    sz = blk[:, :, 480:720].copy().view("<u4")
+    heads = (ix & 1).transpose(0, 2, 1).reshape(-1, 180)         # stream order inside a tile: position = 3 * lane + block
+    scale = (sz & 0xFFFF).transpose(0, 2, 1).reshape(-1, 180)
+    assert np.all(heads[:N, 0] == 1) and heads[:N, 1:].sum() == 0
+    assert np.all(scale[:N, :179] != 0) and np.all(scale[:N, 179] == 0)
+    assert not blk[N:].any()                                     # the workers beyond the rows hold null tiles
+    cols = (ix >> 4).transpose(0, 2, 1).reshape(-1, 180)[:N, :179]
+    assert np.array_equal(cols.reshape(-1), oracle.pack(W, 16, 4, sparsity=0.3).groups)
 
 
 @pytest.mark.parametrize("bits,G", [(4, 16), (8, 16), (4, 32), (4, 64), (4, 128), (8, 32), (8, 64)])
@@ -191,7 +259,7 @@ def test_other_group_sizes(bits, G):
     assert_same_canonical(h, c)
     info = gq.gqsa_info(h)
     assert info["algorithmic_bytes"] == oracle.algorithmic_bytes(N, K, G, bits, c.nnzg, 1)
-    assert (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"]) == gq.gqsa_default_partition(c.rowIndex, K, G, bits)
+    assert gq.gqsa_partition(h) == gq.gqsa_default_partition(c.rowIndex, K, G, bits)
     for part in (None, (1, 1), (3, 1), (5, 3), (1, 16), (17, 2), (40, 16)):
         if part is not None:
             gq.gqsa_set_partition(h, *part)

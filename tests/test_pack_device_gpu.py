@@ -32,10 +32,9 @@ def assert_same_bits(h, c):
                        ("zeros", c.zeros)):
         assert np.array_equal(e[name], want), name
     info = gq.gqsa_info(h)
-    part = (info["n_workgroups"], info["waves_per_workgroup"], info["span_tiles"])
-    assert part == gq.gqsa_default_partition(c.rowIndex, c.K, c.G, c.bits)
+    assert gq.gqsa_partition(h) == gq.gqsa_default_partition(c.rowIndex, c.K, c.G, c.bits)
     blob = gq.gqsa_export_device_blob(h)
-    assert blob == oracle.device_blob(c, *part)
+    assert blob == oracle.device_blob_for(c, info)
     assert info["on_device"] == 1
     return blob
 

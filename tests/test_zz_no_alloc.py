@@ -27,7 +27,9 @@ def _packed(N, K, seed, part):
     h = gq.gqsa_pack_rows(W, keep, 16, 4)
     if part:
         gq.gqsa_set_partition(h, *part)          # rows shared by wavefronts of several workgroups
-    assert gq.gqsa_info(h)["needs_fixup"] == 1
+        assert gq.gqsa_info(h)["needs_fixup"] == 1
+    else:
+        assert gq.gqsa_info(h)["needs_fixup"] == 0      # (the default here: whole rows per worker, tiles of a chosen shape)
     return h, oracle.pack(W, 16, 4, keep_per_row=keep)
 
 
