@@ -285,7 +285,24 @@ def main():
         small.append({"bytes": int(nbytes), "us_cold": round(us, 3), "GBps_cold": round(nbytes / us / 1e3, 1)})
     out["stream_read_matrix_sized"] = small
     out["empty_launch_us"] = round(time_calls(lambda k: gq.gqsa_launch_floor(256, 9216, sink)), 3)
-    del big
+    # our own dense fp16 GEMV on the same shapes (pool of distinct fp16 matrices > 1 GB), beside a
+    # plain streaming read of as many bytes issued the same way (one launch per matrix, cold)
+    dense = []
+    for idx in (0, 4, 6):
+        name, N, K = gi.LLAMA7B_LAYER[idx]
+        nbytes = N * K * 2
+        nslices = big.numel() // nbytes
+        us_read = time_calls(lambda k, nbytes=nbytes, nslices=nslices: gq.gqsa_stream_read(
+            big[(k % nslices) * nbytes:(k % nslices + 1) * nbytes], sink), n=100)
+        n_mats = max(2, int(MIN_POOL // nbytes) + 1)
+        Ws = [torch.randn((N, K), dtype=torch.float16, device=dev) * 0.02 for _ in range(n_mats)]
+        yb = torch.empty((1, N), dtype=torch.float16, device=dev)
+        us = time_calls(lambda k, Ws=Ws, K=K, yb=yb: gq.gqsa_dense_f16_gemv(Ws[k % len(Ws)], xs[K], yb), n=100)
+        b = nbytes + (N + K) * 2
+        dense.append({"shape": f"{N}x{K}", "us_cold": round(us, 3), "GBps_cold": round(b / us / 1e3, 1),
+                      "stream_read_same_bytes_us": round(us_read, 3), "frac_of_stream_read_rate": round(us_read / us, 3)})
+        del Ws
+    out["dense_f16_gemv"] = dense
 
     # ------------------------------------------------------------------ single calls of the layer's shapes
     extra_handles = []
@@ -371,7 +388,9 @@ def main():
             return xs[K]
         return torch.from_numpy(gi.activations(B, K, seed=seed)).to(dev)
 
-    def time_variants(shapes, variants, seed_config, n=100):
+    def time_variants(shapes, variants, seed_config, n=100, read_buf=None):
+        """us per call over pools of distinct packed matrices; with read_buf also a plain streaming
+        read of as many bytes as a matrix's device image, issued the same way (cold slices)."""
         rows = []
         for idx, (name, N, K) in shapes:
             W = gi.dense_weight_chunked(N, K, seed=gi.config_seed(seed_config, idx), workers=workers)
@@ -386,6 +405,13 @@ def main():
                 row = {"shape": f"{N}x{K}", "bits": bits, "S": sparsity, "G": G}
                 row.update(rate(inf["algorithmic_bytes"], us))
                 row["partition"] = list(gq.gqsa_partition(hs[0]))
+                if read_buf is not None:
+                    nbytes = inf["device_bytes"] // 4096 * 4096
+                    nslices = read_buf.numel() // nbytes
+                    us_read = time_calls(lambda k, nbytes=nbytes, nslices=nslices: gq.gqsa_stream_read(
+                        read_buf[(k % nslices) * nbytes:(k % nslices + 1) * nbytes], sink), n=n)
+                    row["stream_read_same_bytes_us"] = round(us_read, 3)
+                    row["us_over_stream_read"] = round(us / us_read, 3)
                 rows.append(row)
                 for h in hs:
                     gq.gqsa_free(h)
@@ -396,7 +422,9 @@ def main():
     # variant at S = 50 %, on the layer's shapes
     shapes7 = [(i, gi.LLAMA7B_LAYER[i]) for i in (0, 4, 6)]
     out["dense_w4_gemv"] = time_variants(shapes7, [(4, 0.0)], 2)
-    out["w8s50_gemv"] = time_variants(shapes7, [(8, 0.5)], 2)
+    shapes5 = [(i, s5) for i, s5 in enumerate(gi.SMALL_BATCH_SHAPES)]
+    out["w8s50_gemv"] = time_variants(shapes7, [(8, 0.5)], 2, read_buf=big) + time_variants(shapes5[1:], [(8, 0.5)], 5, read_buf=big)
+    del big
 
     # LLaMA-3-8B-like shapes over the sparsity sweep (the axes of the paper's kernel benchmark,
     # Sec. 4.4 / Fig. 6, which states that the GEMV gets faster as the sparsity rises)
@@ -507,19 +535,6 @@ def main():
                                     "Mweights_per_s": round(4096 * 4096 / median(ts) / 1e6, 1),
                                     "speedup_over_host": round(t_mag / median(ts), 2)}
     del Wp, Wd, dd
-
-    # our own dense fp16 GEMV on the same shapes (pool of distinct fp16 matrices > 1 GB)
-    dense = []
-    for idx in (0, 4, 6):
-        name, N, K = gi.LLAMA7B_LAYER[idx]
-        n_mats = max(2, int(MIN_POOL // (N * K * 2)) + 1)
-        Ws = [torch.randn((N, K), dtype=torch.float16, device=dev) * 0.02 for _ in range(n_mats)]
-        yb = torch.empty((1, N), dtype=torch.float16, device=dev)
-        us = time_calls(lambda k, Ws=Ws, K=K, yb=yb: gq.gqsa_dense_f16_gemv(Ws[k % len(Ws)], xs[K], yb))
-        b = N * K * 2 + (N + K) * 2
-        dense.append({"shape": f"{N}x{K}", "us_cold": round(us, 3), "GBps_cold": round(b / us / 1e3, 1)})
-        del Ws
-    out["dense_f16_gemv"] = dense
 
     finish(args, out, gi, xs, bytes_per_step, calls_per_step, workers)
 

@@ -15,9 +15,17 @@ namespace {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 1024;
-constexpr int kGrid = 256;
 constexpr int kReadGrid = 8192;
 constexpr int kReadThreads = 256;
+
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16 bytes that will not be read again: a streaming (non-temporal) load.
+__device__ __forceinline__ uint4 stream_load16(const uint4* p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return uint4{v.x, v.y, v.z, v.w};
+}
 
 __device__ __forceinline__ float dot8(uint4 w, uint4 x, float acc)
 {
@@ -28,33 +36,77 @@ __device__ __forceinline__ float dot8(uint4 w, uint4 x, float acc)
     return acc;
 }
 
-// One wavefront per output row at a time; lanes stride over K in 16-byte pieces.
-__global__ __launch_bounds__(kThreads) void dense_f16_gemv_kernel(const uint16_t* W, const uint16_t* x,
-                                                                  uint16_t* y, long long N, long long K)
+// v from the lane CTRL names (DPP); lanes without a source lane, or outside ROW_MASK, read 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or_zero(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF,
+                                                                 ROW_MASK == 0xF));
+}
+
+// Sum over the wavefront, in lane 63: shifts inside the rows of 16 lanes, then the row totals
+// handed on (lane 15 -> row 1, lane 47 -> row 3, lane 31 -> rows 2 and 3).
+__device__ __forceinline__ float wave_sum_in_last_lane(float v)
+{
+    v += dpp_or_zero<0x111, 0xF>(v);      // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);      // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);      // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);      // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);      // row_bcast:15
+    v += dpp_or_zero<0x143, 0xC>(v);      // row_bcast:31
+    return v;
+}
+
+// Dense fp16 GEMV, one output row per wavefront: x staged once per workgroup of kDenseWaves rows
+// (an eighth of the bytes the workgroup streams), the row's 16-byte pieces requested eight per
+// lane at a time (8 KB per wavefront under way) with streaming loads, fp32 accumulation in two
+// chains, a DPP sum at the end.  Workgroups: one per kDenseWaves rows -- 512 for 4096 rows --
+// so that several are resident per compute unit and one's loads run under another's arithmetic.
+constexpr int kDenseWaves = 8;
+constexpr int kDenseInFlight = 8;
+
+__global__ __launch_bounds__(kDenseWaves * 64) void dense_f16_gemv_kernel(const uint16_t* W, const uint16_t* x,
+                                                                          uint16_t* y, long long N, long long K)
 {
     extern __shared__ __align__(16) uint8_t lds[];
     uint4* xs = reinterpret_cast<uint4*>(lds);
     const int tid = threadIdx.x, lane = tid & 63;
-    const long long k8 = K / 8;
-    for (long long i = tid; i < k8; i += blockDim.x) xs[i] = reinterpret_cast<const uint4*>(x)[i];
-    __syncthreads();
-    const long long waves = static_cast<long long>(gridDim.x) * (blockDim.x >> 6);
-    for (long long row = static_cast<long long>(blockIdx.x) * (blockDim.x >> 6) + (tid >> 6); row < N;
-         row += waves) {
-        const uint4* wr = reinterpret_cast<const uint4*>(W + row * K);
-        float acc0 = 0.0f, acc1 = 0.0f;
-        long long i = lane;
-        for (; i + 64 < k8; i += 128) {
-            const uint4 a = wr[i], b = wr[i + 64];
-            acc0 = dot8(a, xs[i], acc0);
-            acc1 = dot8(b, xs[i + 64], acc1);
-        }
-        if (i < k8) acc0 = dot8(wr[i], xs[i], acc0);
-        float acc = acc0 + acc1;
+    const int k8 = static_cast<int>(K / 8);
+    const long long row = static_cast<long long>(blockIdx.x) * kDenseWaves + (tid >> 6);
+    const uint4* wr = reinterpret_cast<const uint4*>(W + (row < N ? row : 0) * K);
+    // the row's first pieces go out before x is staged: they are the long wait
+    uint4 w[kDenseInFlight];
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
-        if (lane == 0) y[row] = __builtin_bit_cast(uint16_t, static_cast<_Float16>(acc));
+    for (int j = 0; j < kDenseInFlight; ++j) {
+        const int i = lane + 64 * j;
+        w[j] = stream_load16(wr + (i < k8 ? i : 0));
     }
+    for (int i = tid; i < k8; i += kDenseWaves * 64) xs[i] = reinterpret_cast<const uint4*>(x)[i];
+    __syncthreads();
+    float acc0 = 0.0f, acc1 = 0.0f;
+    for (int base = 0; base < k8; base += 64 * kDenseInFlight) {
+        uint4 cur[kDenseInFlight];
+#pragma unroll
+        for (int j = 0; j < kDenseInFlight; ++j) cur[j] = w[j];
+        const int next = base + 64 * kDenseInFlight;
+        if (next < k8) {
+#pragma unroll
+            for (int j = 0; j < kDenseInFlight; ++j) {
+                const int i = next + lane + 64 * j;
+                w[j] = stream_load16(wr + (i < k8 ? i : 0));
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kDenseInFlight; j += 2) {
+            const int i0 = base + lane + 64 * j, i1 = i0 + 64;
+            // (pieces past the end of the row were loaded from its start: they count as zero)
+            const float a = dot8(cur[j], xs[i0 < k8 ? i0 : 0], 0.0f), b = dot8(cur[j + 1], xs[i1 < k8 ? i1 : 0], 0.0f);
+            acc0 += i0 < k8 ? a : 0.0f;
+            acc1 += i1 < k8 ? b : 0.0f;
+        }
+    }
+    const float total = wave_sum_in_last_lane(acc0 + acc1);
+    if (lane == 63 && row < N) y[row] = __builtin_bit_cast(uint16_t, static_cast<_Float16>(total));
 }
 
 // Every workgroup reads its own contiguous share of the buffer, four 16-byte loads per thread
@@ -118,7 +170,8 @@ gqsa_status_t gqsa_dense_f16_gemv(const void* W_dev, const void* x_dev, void* y_
         return GQSA_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     for (int b = 0; b < batch; ++b) {
-        hipLaunchKernelGGL(dense_f16_gemv_kernel, dim3(kGrid), dim3(kThreads), static_cast<size_t>(K) * 2, s,
+        hipLaunchKernelGGL(dense_f16_gemv_kernel, dim3(static_cast<unsigned>((N + kDenseWaves - 1) / kDenseWaves)),
+                           dim3(kDenseWaves * 64), static_cast<size_t>(K) * 2, s,
                            static_cast<const uint16_t*>(W_dev),
                            static_cast<const uint16_t*>(x_dev) + static_cast<size_t>(b) * K,
                            static_cast<uint16_t*>(y_dev) + static_cast<size_t>(b) * N,

@@ -28,6 +28,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <mutex>
+#include <type_traits>
 
 #include "gqsa_internal.hpp"
 
@@ -293,15 +294,12 @@ template <bool FLEX>
 struct LaneMasks {
     uint32_t head, slot, scale;
     __device__ __forceinline__ explicit LaneMasks(bool lane_in_use)
-    {
-        if constexpr (FLEX) {
-            head = lane_in_use ? 1u : 0u;
-            slot = lane_in_use ? 0xFFF0u : 0u;
-            scale = lane_in_use ? 0xFFFFu : 0u;
-        } else {
-            head = 1u; slot = 0xFFF0u; scale = 0xFFFFu;
-        }
-    }
+        : head(lane_in_use ? 1u : 0u), slot(lane_in_use ? 0xFFF0u : 0u), scale(lane_in_use ? 0xFFFFu : 0u) {}
+};
+template <>
+struct LaneMasks<false> {          // every lane takes a group: the masks are literals
+    [[maybe_unused]] static constexpr uint32_t head = 1u, slot = 0xFFF0u, scale = 0xFFFFu;
+    __device__ __forceinline__ explicit LaneMasks(bool) {}
 };
 
 // (1) stream the compressed groups: coalesced loads, all issued before anything waits.  The
@@ -400,7 +398,9 @@ __device__ __forceinline__ void decode_chunk(const Tile<F>& t, int u, int i, Cod
 // x in LDS, per activation row: elements 0..7 of every group-column in 16-byte slots, elements
 // 8..15 in a second array of 16-byte slots 16*KGP bytes further on, and the fp32 sum of the 16
 // as a dense array of floats at 32*KGP (4 bytes per column: a wavefront's 64 reads of it spread
-// over all banks instead of a quarter of them).  Row b starts at b * 48 * KGP.  (G = 8: the same
+// over all banks instead of a quarter of them; with one 16-byte slot per sum the three reads of
+// a group would share an address and save a shift, but the kernels for several activation rows,
+// which LDS bounds, took 5 % longer).  Row b starts at b * 48 * KGP.  (G = 8: the same
 // two arrays -- a group's 8 activations are one slot of the first or of the second -- and a sum
 // per half-slot, 8 bytes per column.)
 //
@@ -440,11 +440,16 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
     // first row head, acc = what follows its last one (everything, if it has none).  fold() adds
     // group u, given its dotz = sum_j q_j x_j - z sum_j x_j per activation row:
     //   sum_j (q_j - z) s x_j  =  s * (sum_j q_j x_j  -  z * sum_j x_j)
+    // SIMPLE (no lane holds two heads): the heads of block u are the lanes of bal[u], which
+    // selects straight from its scalar register pair; a block without heads (most: a row of a
+    // multiple of U groups puts all its heads into block 0) just adds.
     float acc[NB], lead[NB];
 #pragma unroll
     for (int b = 0; b < NB; ++b) { acc[b] = 0.0f; lead[b] = 0.0f; }
     int nh = 0;
-    auto fold = [&](int u, const float* dotz) {
+    // (in the loops over groups below -- several activation rows, several tiles -- the plain form:
+    // per-lane selects on the head flag, no branch per block: 3 % faster there)
+    auto fold_in_loop = [&](int u, const float* dotz) {
         const float s = half_to_float(t.sz[u] & mask.scale);
         const bool head_here = (t.ix[u] & mask.head) != 0;
         if (simple) {
@@ -455,6 +460,33 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
             }
         } else {
             if (head_here) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    if (nh == 0) lead[b] = acc[b];
+                    else store_row(m, b, st.rank + heads_before + nh, acc[b]);   // a whole row inside one lane
+                    acc[b] = 0.0f;
+                }
+                ++nh;
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(s, dotz[b], acc[b]);
+        }
+    };
+    auto fold = [&](auto simple_tag, int u, const float* dotz) {
+        const float s = half_to_float(t.sz[u] & mask.scale);
+        if constexpr (decltype(simple_tag)::value) {
+            if (bal[u] == 0) {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) acc[b] = __builtin_fmaf(s, dotz[b], acc[b]);
+            } else {
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    lead[b] = select_lanes(bal[u], acc[b], lead[b]);     // the only head of this lane
+                    acc[b] = __builtin_fmaf(s, dotz[b], keep_lanes(~bal[u], acc[b]));
+                }
+            }
+        } else {
+            if ((t.ix[u] & mask.head) != 0) {
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     if (nh == 0) lead[b] = acc[b];
@@ -498,14 +530,19 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
                 __builtin_amdgcn_sched_barrier(0x47F);     // (LDS reads stay behind this point: no more than AHEAD groups under way)
             }
         }
+        if (simple) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) fold(u, &dotz[u]);
+            for (int u = 0; u < U; ++u) fold(std::true_type{}, u, &dotz[u]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) fold(std::false_type{}, u, &dotz[u]);
+        }
     } else {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const float z = half_to_float(t.sz[u] >> 16);
             const uint32_t slot = t.ix[u] & mask.slot;
-            float dotz[NB];
+            float dotz[NB];          // sum_j q_j x_j - z sum_j x_j of group u for every activation row
             if constexpr (F::HALF) {
                 // G = 8: the index word counts 8-element half-slots; an even one lies in the array
                 // of the slots' first halves, an odd one in the array of their second halves, and
@@ -544,7 +581,7 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
                     dotz[b] = i == 0 ? d : dotz[b] + d;
                 }
             }
-            fold(u, dotz);
+            fold_in_loop(u, dotz);
         }
     }
 
