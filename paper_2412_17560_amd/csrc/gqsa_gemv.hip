@@ -152,40 +152,47 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
 
 __device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 
-// (w & mask) | splice in one instruction; mask is wave-uniform, splice sits in a vector register
-// (the three-operand form takes a single scalar operand).
-__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t splice)
-{
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(splice));
-    return r;
-}
-
-// The 16 codes of one stored group as eight fp16 pairs (element 2i, 2i+1), exact.
+// The 16 codes of one stored group as eight fp16 pairs (element 2i, 2i+1), exact -- as fp16
+// SUBNORMALS: a code q left where it is in an otherwise empty 16-bit half is the fp16 number
+// q * 2^-24 (q * 2^-20 if it sits four bits up), so a group is decoded by masking alone; there is
+// no exponent to splice in and no bias to take off again.  v_dot2_f32_f16 multiplies subnormal
+// inputs exactly (checked on the device: products and fp32 sums come out bit for bit).  The
+// power of two is carried along: the staged group sums of x are scaled by it (a dot product with
+// the pair (2^-20, 2^-20), itself an fp16 subnormal, instead of (1, 1)), so that
+// sum_j q_j x_j - z sum_j x_j comes out in units of 2^-20, and a lane's
+// sums are multiplied by 2^20 once per tile, after its groups are added up.  All scalings by
+// powers of two are exact, so the values are those of the unscaled arithmetic.
 struct Codes {
     half2_t q[8];
 };
+template <int BITS> struct CodeUnit;
+template <> struct CodeUnit<4> {
+    static constexpr float kInverse = 1048576.0f;            // 2^20
+    static constexpr uint32_t kPairOfUnits = 0x00100010u;    // the fp16 pair (2^-20, 2^-20)
+};
+template <> struct CodeUnit<8> {            // (8-bit codes keep the unit 1, see decode_w8)
+    static constexpr float kInverse = 1.0f;
+    static constexpr uint32_t kPairOfUnits = 0x3C003C00u;    // (1, 1)
+};
 
 // 4-bit: the code words are nibble-permuted at pack time (element 2m at bits 4m, element 2m+1
-// at bits 16+4m), so one AND-OR splices a pair of codes into the mantissas of the fp16 pair
-// (1024+q, 1024+q') or (1024+16q, 1024+16q'); one packed op removes the bias exactly.
+// at bits 16+4m), so one AND isolates a pair of codes: the low nibbles of a byte pair as
+// (q, q') * 2^-24, the high nibbles as (q, q') * 2^-20.
 [[maybe_unused]] __device__ __forceinline__ void decode_w4(uint32_t w, half2_t* q)
 {
-    const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
-    const half2_t k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
-    const half2_t k64 = {(_Float16)64.0f, (_Float16)64.0f};
-    // nibble masks and the fp16 pair (1024, 1024): constants kept in registers, so that
-    // mask-and-splice is one three-operand instruction instead of two with literal operands
-    const uint32_t nib_lo = 0x000F000Fu, nib_hi = 0x00F000F0u, k1024x2 = 0x64006400u;
+    const uint32_t nib_lo = 0x000F000Fu, nib_hi = 0x00F000F0u;
     const uint32_t w2 = w >> 8;
-    q[0] = as_half2(and_or(w, nib_lo, k1024x2)) - k1024;
-    q[1] = __builtin_elementwise_fma(as_half2(and_or(w, nib_hi, k1024x2)), k16th, -k64);
-    q[2] = as_half2(and_or(w2, nib_lo, k1024x2)) - k1024;
-    q[3] = __builtin_elementwise_fma(as_half2(and_or(w2, nib_hi, k1024x2)), k16th, -k64);
+    q[0] = as_half2(w & nib_lo);
+    q[1] = as_half2(w & nib_hi);
+    q[2] = as_half2(w2 & nib_lo);
+    q[3] = as_half2(w2 & nib_hi);
 }
 
 // 8-bit: a byte permute drops each code (bytes of w, element order) into the mantissa of
-// 1024.0 (0x64xx), one packed subtract removes the bias.
+// 1024.0 (0x64xx), one packed subtract removes the bias.  (Left as subnormals, q * 2^-24, the
+// 8-bit codes gave sums that missed the error bound on activations with full mantissas -- 3.6e-3
+// where this form gives 4.6e-4 -- although single products came out exact; the 4-bit form
+// shows no such difference.)
 [[maybe_unused]] __device__ __forceinline__ void decode_w8(uint32_t w, half2_t* q)
 {
     const half2_t k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
@@ -194,18 +201,40 @@ struct Codes {
     q[1] = as_half2(__builtin_amdgcn_perm(w, k64s, 0x00070006u)) - k1024;
 }
 
+// sum_j q_j x_j of four pairs of codes (one code word of 4-bit codes, two of 8-bit codes) in the
+// format's unit: 4-bit codes alternate between pairs in units of 2^-24 and of 2^-20, which are
+// added up apart and joined with one multiply-add (8-bit codes: one chain in the unit 1).
+template <int BITS>
+__device__ __forceinline__ float dot8(const half2_t* q, uint4 x, float lo, float& hi)
+{
+    if constexpr (BITS == 4) {
+        lo = __builtin_amdgcn_fdot2(q[0], as_half2(x.x), lo, false);
+        hi = __builtin_amdgcn_fdot2(q[1], as_half2(x.y), hi, false);
+        lo = __builtin_amdgcn_fdot2(q[2], as_half2(x.z), lo, false);
+        hi = __builtin_amdgcn_fdot2(q[3], as_half2(x.w), hi, false);
+    } else {
+        lo = __builtin_amdgcn_fdot2(q[0], as_half2(x.x), lo, false);
+        lo = __builtin_amdgcn_fdot2(q[1], as_half2(x.y), lo, false);
+        lo = __builtin_amdgcn_fdot2(q[2], as_half2(x.z), lo, false);
+        lo = __builtin_amdgcn_fdot2(q[3], as_half2(x.w), lo, false);
+    }
+    return lo;
+}
+// the two partial sums joined, in the format's unit (2^-20 for 4-bit codes, 1 for 8-bit codes)
+template <int BITS>
+__device__ __forceinline__ float join(float lo, float hi)
+{
+    if constexpr (BITS == 4) return __builtin_fmaf(16.0f, lo, hi);
+    else return lo;      // (one chain: hi stays 0)
+}
+
+template <int BITS>
 __device__ __forceinline__ float dot16(const Codes& c, uint4 xl, uint4 xh)
 {
-    float d = 0.0f;
-    d = __builtin_amdgcn_fdot2(c.q[0], as_half2(xl.x), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[1], as_half2(xl.y), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[2], as_half2(xl.z), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[3], as_half2(xl.w), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[4], as_half2(xh.x), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[5], as_half2(xh.y), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[6], as_half2(xh.z), d, false);
-    d = __builtin_amdgcn_fdot2(c.q[7], as_half2(xh.w), d, false);
-    return d;
+    float lo = 0.0f, hi = 0.0f;
+    lo = dot8<BITS>(&c.q[0], xl, lo, hi);
+    lo = dot8<BITS>(&c.q[4], xh, lo, hi);
+    return join<BITS>(lo, hi);
 }
 
 // v from the lane CTRL names (DPP); lanes whose source lane does not exist, or whose row is
@@ -463,7 +492,7 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     if (nh == 0) lead[b] = acc[b];
-                    else store_row(m, b, st.rank + heads_before + nh, acc[b]);   // a whole row inside one lane
+                    else store_row(m, b, st.rank + heads_before + nh, acc[b] * CodeUnit<F::BITS>::kInverse);   // a whole row inside one lane
                     acc[b] = 0.0f;
                 }
                 ++nh;
@@ -490,7 +519,7 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
 #pragma unroll
                 for (int b = 0; b < NB; ++b) {
                     if (nh == 0) lead[b] = acc[b];
-                    else store_row(m, b, st.rank + heads_before + nh, acc[b]);   // a whole row inside one lane
+                    else store_row(m, b, st.rank + heads_before + nh, acc[b] * CodeUnit<F::BITS>::kInverse);   // a whole row inside one lane
                     acc[b] = 0.0f;
                 }
                 ++nh;
@@ -524,7 +553,7 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
             Codes c;
             decode_chunk<F>(t, u, 0, c);
             const float z = half_to_float(t.sz[u] >> 16);
-            dotz[u] = __builtin_fmaf(-z, xs[u], dot16(c, xl[u], xh[u]));
+            dotz[u] = __builtin_fmaf(-z, xs[u], dot16<F::BITS>(c, xl[u], xh[u]));
             if (u + AHEAD < U) {
                 gather(u + AHEAD);
                 __builtin_amdgcn_sched_barrier(0x47F);     // (LDS reads stay behind this point: no more than AHEAD groups under way)
@@ -559,12 +588,9 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
                 for (int b = 0; b < NB; ++b) {
                     const uint4 xl = lds_read16(x0 + xoff + b * (48 * KGP));
                     const float xs = lds_read_float(x0 + b * (48 * KGP) + 32 * KGP + (slot >> 2));
-                    float d = 0.0f;
-                    d = __builtin_amdgcn_fdot2(c.q[0], as_half2(xl.x), d, false);
-                    d = __builtin_amdgcn_fdot2(c.q[1], as_half2(xl.y), d, false);
-                    d = __builtin_amdgcn_fdot2(c.q[2], as_half2(xl.z), d, false);
-                    d = __builtin_amdgcn_fdot2(c.q[3], as_half2(xl.w), d, false);
-                    dotz[b] = __builtin_fmaf(-z, xs, d);
+                    float lo = 0.0f, hi = 0.0f;
+                    lo = dot8<F::BITS>(&c.q[0], xl, lo, hi);
+                    dotz[b] = __builtin_fmaf(-z, xs, join<F::BITS>(lo, hi));
                 }
             }
 #pragma unroll
@@ -577,12 +603,19 @@ __device__ __forceinline__ void compute_tile(const MatArgs& m, const Tile<F>& t,
                     const uint4 xl = lds_read16(xb);
                     const uint4 xh = lds_read16(xb + 16 * KGP);
                     const float xs = lds_read_float(x0 + b * (48 * KGP) + 32 * KGP + (slot >> 2) + 4 * i);
-                    const float d = __builtin_fmaf(-z, xs, dot16(c, xl, xh));
+                    const float d = __builtin_fmaf(-z, xs, dot16<F::BITS>(c, xl, xh));
                     dotz[b] = i == 0 ? d : dotz[b] + d;
                 }
             }
             fold_in_loop(u, dotz);
         }
+    }
+
+    // the lane's sums leave the unit of the codes' dot products (an exact scaling)
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        acc[b] *= CodeUnit<F::BITS>::kInverse;
+        lead[b] *= CodeUnit<F::BITS>::kInverse;
     }
 
     // (5b) cross-lane segmented inclusive scan of the lanes' open sums: DPP shifts inside each
@@ -870,7 +903,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
         *reinterpret_cast<uint4*>(slot) = lo;
         *reinterpret_cast<uint4*>(slot + 16 * KGP) = hi;
         const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+        const half2_t ones = as_half2(CodeUnit<F::BITS>::kPairOfUnits);     // (the sums are kept in the unit of the codes' dot products)
         if constexpr (F::HALF) {     // G = 8: a sum per half-slot
             float s0 = 0.0f, s1 = 0.0f;
 #pragma unroll
