@@ -151,12 +151,18 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
  * count of stored groups, not of rows):
  *  (1) rows kept inside the workers' runs, if empty positions amounting to at most an eighth of
  *      the stored groups and at most 16384 workers achieve that (gqsa_set_partition_rows below):
- *      of the tile shapes the kernel has (for G = 16: 3..6 blocks with 32, 36, .. 64 lanes in use;
- *      else the format's own block count with 64 lanes) and 1..4 tiles per worker, among those
- *      within 1/16 of the stored groups of the fewest empty positions: the fewest tiles per
- *      worker, then the fewest lane slots (workers x tiles x blocks), then the block count nearest
- *      to 4.  Workgroups of 4 wavefronts for K up to 4096, of 8 beyond, their count rounded up to
- *      a multiple of 4.  Matrices pruned to the same count in every row take this form.
+ *      of the tile shapes the kernel has (for G = 16: 3, 4, 5 blocks -- 4-bit codes also 6 and
+ *      8 -- with 32, 36, .. 64 lanes in use; else the format's own block count with 64 lanes),
+ *      one tile per worker (if none is eligible and K <= 4096: 2, 3 or 4 tiles of the format's
+ *      own shape, the fewest that are), among those within 1/16 of the stored groups of the
+ *      fewest empty positions --
+ *      K <= 4096: the format's own shape if it is among them, else the fewest blocks per tile,
+ *      then the most lanes in use; workgroups of 4 wavefronts;
+ *      K > 4096 (a workgroup stages all of x: fewer, larger workgroups): only with at least
+ *      2048 workers; the fewest workers, then the most lanes in use, then the fewest blocks;
+ *      workgroups of 8 wavefronts.
+ *      The workgroup count is rounded up to a multiple of 4.  Matrices pruned to the same count
+ *      in every row take this form.
  *  (2) otherwise by size: for K up to 4096 (or fewer than 2048 tiles) one tile per worker (at
  *      most 16384 workers; more tiles per worker beyond) in workgroups of 4 wavefronts, the
  *      workgroup count rounded up to a multiple of 4; for larger K workgroups of 8 wavefronts,
@@ -199,10 +205,11 @@ gqsa_status_t gqsa_set_partition_aligned(gqsa_handle_t h, int span_tiles, int n_
  * shares no row with a neighbour: it writes its rows and ends, and the launch has no fix-up
  * phase (Sec. 3.5's straggler problem does not arise where the rows are of similar length; the
  * positions left empty pay for it).  T = tiles_per_worker * n_workgroups * waves_per_workgroup.
- *   tile_blocks, tile_lanes   a tile shape the kernel is compiled for -- G = 16: 3..6 blocks and
- *                       32, 36, .. 64 lanes; any format: its own block count (4, 2 or 1, see
- *                       gqsa_set_partition) with 64 lanes -- else GQSA_ERR_UNSUPPORTED
- *   tiles_per_worker    >= 1
+ *   tile_blocks, tile_lanes   a tile shape the kernel is compiled for -- G = 16: 3, 4, 5 blocks
+ *                       (4-bit codes: also 6, 8) and 32, 36, .. 64 lanes; any format: its own
+ *                       block count (4, 2 or 1, see gqsa_set_partition) with 64 lanes -- else
+ *                       GQSA_ERR_UNSUPPORTED
+ *   tiles_per_worker    1; of the format's own shape also more
  *   n_workgroups        1..4096, or 0 for as many as the rows need; GQSA_ERR_RANGE if they need more
  *   waves_per_workgroup 1..16
  */

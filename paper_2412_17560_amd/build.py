@@ -16,7 +16,7 @@ HOST_ONLY = bool(os.environ.get("GQSA_LIBRARY"))
 SANITIZED_LIB = os.path.join(OBJ, "libgqsa_host_asan.so")
 
 # (gqsa_gemv.hip is compiled four times: whole, and once per further tile size -- "file:part")
-SOURCES = ["gqsa_gemv.hip", "gqsa_gemv.hip:1", "gqsa_gemv.hip:2", "gqsa_gemv.hip:3", "gqsa_pack.cpp",
+SOURCES = ["gqsa_gemv.hip", "gqsa_gemv.hip:1", "gqsa_gemv.hip:2", "gqsa_gemv.hip:3", "gqsa_gemv.hip:4", "gqsa_pack.cpp",
            "gqsa_panels.cpp", "gqsa_api.cpp", "gqsa_panel_kernel.hip", "gqsa_pack_device.hip", "gqsa_baselines.hip"]
 
 COMMON = ["-O3", "-fPIC", "-std=c++17", "-I", os.path.join(ROOT, "include"), "-I", CSRC,

@@ -33,8 +33,8 @@
 #include "gqsa_internal.hpp"
 
 // This file is compiled several times: once whole (GQSA_GEMV_PART 0: the kernels for the formats'
-// own tile sizes and all the host code) and once per further tile size (parts 1..3: tiles of 3, 4 and 5
-// blocks with a chosen count of lanes in use, both code widths, group size 16), so that the kernels build side by side.
+// own tile sizes and all the host code) and once per further tile size (parts 1..4: tiles of 3, 4, 5 and -- 4-bit codes -- 6 and 8
+// blocks with a chosen count of lanes in use, group size 16), so that the kernels build side by side.
 #ifndef GQSA_GEMV_PART
 #define GQSA_GEMV_PART 0
 #endif
@@ -104,6 +104,7 @@ struct Variant {
 Variant tile_variant_part1(int bits, int u, int slots, int nb, int* kgp);
 Variant tile_variant_part2(int bits, int u, int slots, int nb, int* kgp);
 Variant tile_variant_part3(int bits, int u, int slots, int nb, int* kgp);
+Variant tile_variant_part4(int bits, int u, int slots, int nb, int* kgp);
 
 namespace {
 
@@ -153,15 +154,21 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
 __device__ __forceinline__ half2_t as_half2(uint32_t v) { return __builtin_bit_cast(half2_t, v); }
 
 // The 16 codes of one stored group as eight fp16 pairs (element 2i, 2i+1), exact -- as fp16
-// SUBNORMALS: a code q left where it is in an otherwise empty 16-bit half is the fp16 number
-// q * 2^-24 (q * 2^-20 if it sits four bits up), so a group is decoded by masking alone; there is
-// no exponent to splice in and no bias to take off again.  v_dot2_f32_f16 multiplies subnormal
-// inputs exactly (checked on the device: products and fp32 sums come out bit for bit).  The
-// power of two is carried along: the staged group sums of x are scaled by it (a dot product with
-// the pair (2^-20, 2^-20), itself an fp16 subnormal, instead of (1, 1)), so that
-// sum_j q_j x_j - z sum_j x_j comes out in units of 2^-20, and a lane's
-// sums are multiplied by 2^20 once per tile, after its groups are added up.  All scalings by
-// powers of two are exact, so the values are those of the unscaled arithmetic.
+// SUBNORMALS: a code q moved to bits 4..7 of an otherwise empty 16-bit half is the fp16 number
+// 16 q * 2^-24 = q * 2^-20, so a group is decoded by shifting and masking alone; there is no
+// exponent to splice in and no bias to take off again (14 instead of 18 vector instructions per
+// group).  v_dot2_f32_f16 multiplies subnormal inputs exactly; its adder, though, aligns the
+// products by the operands' nominal exponents and does not renormalise a subnormal one first,
+// so every leading zero of the code's mantissa costs a bit of the sum's 24: measured on the
+// device against float64, the error of a 16-term dot product relative to the sum of |terms| is
+// 2.0e-8 with normal operands, 9.3e-8 with codes at bits 4..7 and 2.3e-6 with codes at bits 0..3.
+// Hence all four nibbles of a 16-bit half are brought to bits 4..7 (three shifts per code word
+// instead of one); left in place the low nibbles saved another 3 instructions per group and
+// 1.5 % of a launch, but the worst error against the oracle rose from 4.7e-4 to 5.6-7.5e-4.
+// The power of two is carried along: the staged group sums of x are scaled by it (a dot product
+// with the pair (2^-20, 2^-20), itself an fp16 subnormal, instead of (1, 1)), so that
+// sum_j q_j x_j - z sum_j x_j comes out in units of 2^-20, and a lane's sums are multiplied by
+// 2^20 once per tile, after its groups are added up (scalings by powers of two are exact).
 struct Codes {
     half2_t q[8];
 };
@@ -171,21 +178,20 @@ template <> struct CodeUnit<4> {
     static constexpr uint32_t kPairOfUnits = 0x00100010u;    // the fp16 pair (2^-20, 2^-20)
 };
 template <> struct CodeUnit<8> {            // (8-bit codes keep the unit 1, see decode_w8)
-    static constexpr float kInverse = 1.0f;
-    static constexpr uint32_t kPairOfUnits = 0x3C003C00u;    // (1, 1)
+    [[maybe_unused]] static constexpr float kInverse = 1.0f;
+    [[maybe_unused]] static constexpr uint32_t kPairOfUnits = 0x3C003C00u;    // (1, 1)
 };
 
 // 4-bit: the code words are nibble-permuted at pack time (element 2m at bits 4m, element 2m+1
-// at bits 16+4m), so one AND isolates a pair of codes: the low nibbles of a byte pair as
-// (q, q') * 2^-24, the high nibbles as (q, q') * 2^-20.
+// at bits 16+4m), so a shift and one AND isolate a pair of codes at bits 4..7 and 20..23:
+// (q, q') * 2^-20.
 [[maybe_unused]] __device__ __forceinline__ void decode_w4(uint32_t w, half2_t* q)
 {
-    const uint32_t nib_lo = 0x000F000Fu, nib_hi = 0x00F000F0u;
-    const uint32_t w2 = w >> 8;
-    q[0] = as_half2(w & nib_lo);
+    const uint32_t nib_hi = 0x00F000F0u;
+    q[0] = as_half2((w << 4) & nib_hi);
     q[1] = as_half2(w & nib_hi);
-    q[2] = as_half2(w2 & nib_lo);
-    q[3] = as_half2(w2 & nib_hi);
+    q[2] = as_half2((w >> 4) & nib_hi);
+    q[3] = as_half2((w >> 8) & nib_hi);
 }
 
 // 8-bit: a byte permute drops each code (bytes of w, element order) into the mantissa of
@@ -202,8 +208,7 @@ template <> struct CodeUnit<8> {            // (8-bit codes keep the unit 1, see
 }
 
 // sum_j q_j x_j of four pairs of codes (one code word of 4-bit codes, two of 8-bit codes) in the
-// format's unit: 4-bit codes alternate between pairs in units of 2^-24 and of 2^-20, which are
-// added up apart and joined with one multiply-add (8-bit codes: one chain in the unit 1).
+// format's unit, in two chains (4-bit codes; 8-bit codes: one chain in the unit 1).
 template <int BITS>
 __device__ __forceinline__ float dot8(const half2_t* q, uint4 x, float lo, float& hi)
 {
@@ -224,7 +229,7 @@ __device__ __forceinline__ float dot8(const half2_t* q, uint4 x, float lo, float
 template <int BITS>
 __device__ __forceinline__ float join(float lo, float hi)
 {
-    if constexpr (BITS == 4) return __builtin_fmaf(16.0f, lo, hi);
+    if constexpr (BITS == 4) return lo + hi;
     else return lo;      // (one chain: hi stays 0)
 }
 
@@ -1077,9 +1082,12 @@ Variant pick_kernel(int slots, int nb, int* kgp)
 #elif GQSA_GEMV_PART == 2
 #define GQSA_PART_NAME tile_variant_part2
 #define GQSA_PART_PAIRS {4, 4}, {8, 4}
-#else
+#elif GQSA_GEMV_PART == 3
 #define GQSA_PART_NAME tile_variant_part3
 #define GQSA_PART_PAIRS {4, 5}, {8, 5}
+#else
+#define GQSA_PART_NAME tile_variant_part4
+#define GQSA_PART_PAIRS {4, 6}, {4, 8}
 #endif
 struct BitsAndBlocks { int bits, u; };
 constexpr BitsAndBlocks kPairs[2] = {GQSA_PART_PAIRS};
@@ -1103,7 +1111,8 @@ Variant pick(const gqsa_matrix* m, int nb, int* kgp)
     *kgp = 0;
     if (m->tile_blocks != largest_tile(m->code_bytes()) || m->tile_lanes != kLanes) {     // tiles of a chosen shape
         if (m->G != 16) return Variant{};
-        Variant (*const parts[3])(int, int, int, int, int*) = {tile_variant_part1, tile_variant_part2, tile_variant_part3};
+        Variant (*const parts[4])(int, int, int, int, int*) = {tile_variant_part1, tile_variant_part2, tile_variant_part3,
+                                                               tile_variant_part4};
         for (auto part : parts)
             if (Variant v = part(m->bits, m->tile_blocks, slots, nb, kgp)) return v;
         return Variant{};

@@ -26,9 +26,9 @@ constexpr int kPanelHeaderBytes = 144; // a block's header: 32 column words, dat
 // names another count.
 constexpr int largest_tile(int code_bytes) { return code_bytes <= 16 ? 4 : (code_bytes <= 32 ? 2 : 1); }
 // Tile shapes the GEMV kernel is compiled for: the format's own block count with all 64 lanes
-// of a block in use, and for G = 16 also 3, 4 or 5 blocks per tile with any
-// multiple of 4 lanes from 32 to 64 in use (a tile then holds lanes * blocks stream positions);
-// tiles of such a chosen shape come one to a worker.
+// of a block in use, and for G = 16 also 3, 4 or 5 blocks per tile (4-bit codes: 6 and 8 as well)
+// with any multiple of 4 lanes from 32 to 64 in use (a tile then holds lanes * blocks stream
+// positions); tiles of such a chosen shape come one to a worker.
 constexpr bool tile_shape_is_own(int code_bytes, int blocks, int lanes)
 {
     return blocks == largest_tile(code_bytes) && lanes == kLanes;
@@ -36,7 +36,7 @@ constexpr bool tile_shape_is_own(int code_bytes, int blocks, int lanes)
 constexpr bool tile_shape_supported(int code_bytes, int G, int blocks, int lanes)
 {
     if (tile_shape_is_own(code_bytes, blocks, lanes)) return true;
-    return G == 16 && blocks >= 3 && blocks <= 5 && lanes >= 32 && lanes <= kLanes && lanes % 4 == 0;
+    return G == 16 && ((blocks >= 3 && blocks <= 5) || (code_bytes == 8 && (blocks == 6 || blocks == 8))) && lanes >= 32 && lanes <= kLanes && lanes % 4 == 0;
 }
 
 // How the group stream of a matrix is laid out for the wavefront workers.

@@ -265,18 +265,21 @@ void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t*
 // with the rows of 4096x4096 at 30 % sparsity shared between wavefronts a call takes 5.0 us; kept
 // apart it takes 4.8 us even in tiles of 4 x 64, where 30 % of the stream is null groups, and
 // 4.3 us in tiles of 3 x 60.)  The shape is chosen so that few positions stay empty: 179 groups
-// per row fit 3 x 60, two rows of 77 fit 3 x 52, 205 fit 4 x 52.  Eligible: the shapes the
-// kernel has (tile_shape_supported) that leave at most an eighth of the stored groups' count of
-// positions empty with at most 16384 workers -- one tile per worker; if no shape is eligible
-// (e.g. more than 16384 tiles), 2, 3 or 4 tiles per worker of the format's own shape, the fewest
-// that make it eligible.  Of the eligible shapes, those within 1/16 of the stored groups of the
-// fewest empty positions; of these the format's own shape if it is among them (its kernel has
-// nothing to mask), else the fewest blocks per tile (more wavefronts, each done sooner), then the
-// most lanes in use.  For K up to 4096 only: beyond, a workgroup's share of x decides the
-// partition (partition_by_size).
+// per row fit 3 x 60, two rows of 77 fit 3 x 52, 205 fit 4 x 52, 344 fit 6 x 60, 448 fit 8 x 56.
+// Eligible: the shapes the kernel has (tile_shape_supported) that leave at most an eighth of the
+// stored groups' count of positions empty with at most 16384 workers -- one tile per worker; for
+// K up to 4096, if no shape is eligible (e.g. more than 16384 tiles), 2, 3 or 4 tiles per worker
+// of the format's own shape, the fewest that make it eligible.  Of the eligible shapes, those
+// within 1/16 of the stored groups of the fewest empty positions; of these
+//   K <= 4096: the format's own shape if it is among them (its kernel has nothing to mask), else
+//   the fewest blocks per tile (more wavefronts, each done sooner), then the most lanes in use;
+//   K > 4096, where every workgroup stages all of x and workgroups are of 8 wavefronts: only with
+//   2048 workers or more (a workgroup per compute unit); the fewest workers, then the most lanes
+//   in use, then the fewest blocks (4096x11008 at 50 %: 6.2 us in tiles of 6 x 60 against 6.6 us
+//   with the rows kept inside the workgroups' spans; 4096x14336 at 70 %: 5.6 against 6.1 us).
 bool partition_by_rows(const gqsa_matrix& m, Partition* out)
 {
-    if (m.K > 4096) return false;
+    const bool wide = m.K > 4096;     // x is a large part of what a workgroup reads: fewer, larger workgroups
     const int cb = m.code_bytes();
     const int64_t nnz = m.nnzg();
     if (nnz == 0) return false;
@@ -289,11 +292,11 @@ bool partition_by_rows(const gqsa_matrix& m, Partition* out)
         if (c > 0) ++n_rows;
         if (c > 0 && c != longest) uniform = false;
     }
-    const int wpw = 4;
+    const int wpw = wide ? 8 : 4;
     struct Cand { int u, l, t; int64_t spans, pad; };
     const Cand* best = nullptr;
     std::vector<Cand> cands;
-    for (int t = 1; t <= 4 && !best; ++t) {
+    for (int t = 1; t <= (wide ? 1 : 4) && !best; ++t) {
         cands.clear();
         int64_t least = INT64_MAX;
         for (int u = 1; u <= 8; ++u) {
@@ -312,6 +315,7 @@ bool partition_by_rows(const gqsa_matrix& m, Partition* out)
                 }
                 const int64_t pad = spans * span - nnz;
                 if (spans > 16384 || pad > nnz / 8) continue;
+                if (wide && spans < 8 * kMaxDefaultWorkgroups) continue;      // fewer than a workgroup per compute unit
                 cands.push_back(Cand{u, l, t, spans, pad});
                 least = std::min(least, pad);
             }
@@ -320,7 +324,8 @@ bool partition_by_rows(const gqsa_matrix& m, Partition* out)
             if (c.pad > least + nnz / 16) continue;
             if (!best) { best = &c; continue; }
             const bool own_c = tile_shape_is_own(cb, c.u, c.l), own_b = tile_shape_is_own(cb, best->u, best->l);
-            const bool better = own_c != own_b ? own_c : c.u != best->u ? c.u < best->u : c.l > best->l;
+            const bool better = wide ? (c.spans != best->spans ? c.spans < best->spans : c.l != best->l ? c.l > best->l : c.u < best->u)
+                                     : (own_c != own_b ? own_c : c.u != best->u ? c.u < best->u : c.l > best->l);
             if (better) best = &c;
         }
     }

@@ -268,7 +268,7 @@ def test_default_partition_hand_table():
     assert dp(_balanced(11008, 128), 4096) == (1376, 4, 1, 4, 64, 1)       # 11008x4096: 5504 tiles
     assert dp(_balanced(8193, 256), 4096) == (2052, 4, 1, 4, 64, 1)
     assert dp(_balanced(16384, 256), 4096) == (4096, 4, 1, 4, 64, 1)       # the most workers
-    assert dp(_balanced(16385, 256), 4096) == (2052, 4, 2, 4, 64, 1)       # beyond: two tiles (two rows) per worker, 8193 workers
+    assert dp(_balanced(16385, 256), 4096) == (2052, 4, 1, 8, 64, 1)       # beyond: two rows per tile of 8 x 64, 8193 workers
     assert dp(_balanced(128256, 128), 4096) == (4008, 4, 4, 4, 64, 1)      # 64128 tiles: four per worker
     assert dp(_balanced(2048, 32), 4096, G=128) == (256, 4, 1, 1, 64, 1)   # 64 code bytes: a tile is one block, two rows in it
     assert dp(_balanced(2048, 128), 4096, G=16, bits=8) == (256, 4, 1, 4, 64, 1)   # 16 code bytes: tiles of 4 blocks
@@ -282,15 +282,22 @@ def test_default_partition_hand_table():
     alternating = np.concatenate(([0], np.cumsum(np.tile([256, 8], 500))))
     assert dp(alternating, 4096) == (128, 4, 1, 5, 56, 1)                   # a long and a short row (264) of 5 x 56 = 280: 6 % empty
     alternating = np.concatenate(([0], np.cumsum(np.tile([256, 100], 500))))
-    assert dp(alternating, 4096) == (64, 4, 3, 4, 64, 1)                    # 356 fit no tile twice; two pairs (712) in three tiles (768): 250 workers
-    # rows that fill nothing well: the deal by size, rows kept inside the workgroups' spans
+    assert dp(alternating, 4096) == (128, 4, 1, 6, 60, 1)                   # a pair (356) of 6 x 60 = 360
     uneven = np.concatenate(([0], np.cumsum(np.tile([250, 30, 3, 140], 250))))
-    assert dp(uneven, 4096) == (128, 4, 4, 4, 64, 0)
-    # K > 4096: by size
-    assert dp(_balanced(4096, 344), 11008) == (256, 8, 22, 4, 64, 0)       # 4096x11008: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
-    assert dp(_balanced(8191, 256), 8192) == (512, 8, 16, 4, 64, 0)        # 448 T / K = 448 -> two per compute unit
-    assert dp(_balanced(28615, 256), 8192) == (768, 8, 38, 4, 64, 0)       # at most three
-    assert dp(_balanced(4096, 256), 8192) == (256, 8, 16, 4, 64, 0)        # 4096x8192 at S = 50 %
+    assert dp(uneven, 4096) == (64, 4, 1, 8, 56, 1)                         # the four rows (423) of 8 x 56 = 448; 8 x 60 would leave 13.5 % empty, no smaller tile holds them
+    # K > 4096, rows that fill a tile shape and at least a workgroup of 8 workers per compute unit: whole rows per
+    # worker, the shape with the fewest workers (then the most lanes in use)
+    assert dp(_balanced(4096, 344), 11008) == (512, 8, 1, 6, 60, 1)        # 4096x11008 at S = 50 %: a row of 344 in 6 x 60 = 360
+    assert dp(_balanced(4096, 448), 14336) == (512, 8, 1, 8, 56, 1)        # 4096x14336: 448 = 8 x 56
+    assert dp(_balanced(4096, 269), 14336) == (512, 8, 1, 5, 56, 1)        # at S = 70 %: 269 of 280
+    assert dp(_balanced(4096, 256), 8192) == (256, 8, 1, 8, 64, 1)         # 4096x8192 at S = 50 %: two rows in 8 x 64, 2048 workers
+    assert dp(_balanced(8191, 256), 8192) == (512, 8, 1, 8, 64, 1)         # 4096 workers
+    assert dp(_balanced(4096, 206), 11008) == (256, 8, 1, 8, 52, 1)        # two rows of 206 in 8 x 52 = 416: 2048 workers (4 x 52 would take 4096)
+    # K > 4096 otherwise: by size
+    assert dp(_balanced(4096, 344), 11008, bits=8) == (256, 8, 22, 4, 64, 0)   # 8-bit codes have no tile of 6 blocks: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
+    assert dp(_balanced(4096, 688), 11008) == (512, 8, 22, 4, 64, 0)       # a row of 688 fits no tile: 448 T / K = 448 -> two per compute unit
+    assert dp(_balanced(3000, 256), 8192) == (376, 8, 1, 4, 64, 1)         # two rows per tile of 8 x 64 would be 1500 workers, fewer than 8 per compute unit: a row per 4 x 64
+    assert dp(_balanced(2000, 256), 8192) == (500, 4, 4, 4, 64, 0)         # 2000 workers at most: too few; and fewer than 2048 tiles: the small shapes' deal
     assert dp(_balanced(100, 256), 32768) == (28, 4, 4, 4, 64, 0)          # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
     # too many null groups (a row of 600 per span of 1024: 424 of 1024 positions empty): the plain deal
     assert dp(_balanced(12000, 600), 16384) == (768, 8, 0, 4, 64, 0)

@@ -134,12 +134,22 @@ def test_rows_kept_inside_workers_tiles(bits):
     gq.gqsa_set_partition_rows(h, 4, 64, 3, 0, 2)
     assert gq.gqsa_partition(h)[2:] == (3, 4, 64, 1)
     assert_same_blob(h, c)
-    for (args, status) in (((3, 60, 2, 0, 4), 3), ((2, 64, 1, 0, 4), 3), ((6, 64, 1, 0, 4), 3), ((3, 62, 1, 0, 4), 3),
+    for (args, status) in (((3, 60, 2, 0, 4), 3), ((2, 64, 1, 0, 4), 3), ((7, 64, 1, 0, 4), 3), ((9, 64, 1, 0, 4), 3), ((3, 62, 1, 0, 4), 3),
                            ((3, 28, 1, 0, 4), 3), ((3, 68, 1, 0, 4), 3), ((0, 64, 1, 0, 4), 4), ((3, 0, 1, 0, 4), 4),
                            ((3, 60, 0, 0, 4), 4), ((3, 60, 1, 1, 4), 4), ((3, 60, 1, 0, 17), 4), ((3, 60, 1, 4097, 4), 4)):
         with pytest.raises(gq.GqsaError) as e:
             gq.gqsa_set_partition_rows(h, *args)
         assert e.value.status == status, args
+    # tiles of 6 and 8 blocks: 4-bit codes only
+    for u in (6, 8):
+        if bits == 4:
+            gq.gqsa_set_partition_rows(h, u, 48, 1, 0, 8)
+            assert gq.gqsa_partition(h)[2:] == (1, u, 48, 1) and gq.gqsa_info(h)["needs_fixup"] == 0
+            assert_same_blob(h, c)
+        else:
+            with pytest.raises(gq.GqsaError) as e:
+                gq.gqsa_set_partition_rows(h, u, 48, 1, 0, 8)
+            assert e.value.status == 3
     # other group sizes have their own shape only
     h64 = gq.gqsa_pack(W, 64, 4, 0.5)
     with pytest.raises(gq.GqsaError) as e:
