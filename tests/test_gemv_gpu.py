@@ -828,14 +828,17 @@ def test_graph_replays_match_eager(torch_cuda):
     replayed several times, with eager work and synchronisation between the replays: every replay
     gives the bits of the eager calls.  Rows shared by wavefronts and by workgroups (the fix-up
     leaves its counters and meeting points ready for the next launch by itself), several
-    matrices per launch, and the matrix-core kernel."""
+    matrices per launch, tiles of a chosen shape, and the matrix-core kernel."""
     torch = torch_cuda
     N, K = 257, 2048
     W = gi.dense_weight(N, K, seed=61)
     keep = gi.imbalanced_keep_counts(N, K // 16, seed=61)
     ha = gq.gqsa_pack_rows(W, keep, 16, 4)
     gq.gqsa_set_partition(ha, 37, 3)                         # chains across workgroups
-    hb = gq.gqsa_pack_rows(W, keep, 16, 4)                    # default: rows kept inside the workgroups
+    hb = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition_aligned(hb, 4, 0, 4)               # rows kept inside the workgroups' spans
+    hf = gq.gqsa_pack_rows(W, keep, 16, 4)
+    gq.gqsa_set_partition_rows(hf, 5, 60, 1, 0, 4)            # tiles of a chosen shape, whole rows per worker
     hc = gq.gqsa_pack_rows(W, keep, 16, 4)
     gq.gqsa_set_partition(hc, 5, 4)
     hp = gq.gqsa_pack_rows(W, keep, 16, 8)
@@ -857,7 +860,9 @@ def test_graph_replays_match_eager(torch_cuda):
                 torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
                 torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
                 torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
-                torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda")]
+                torch.full((7, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((1, N), float("nan"), dtype=torch.float16, device="cuda"),
+                torch.full((3, N), float("nan"), dtype=torch.float16, device="cuda")]
 
     def issue(ys):
         gq.gqsa_gemv(ha, x1, ys[0])
@@ -866,6 +871,8 @@ def test_graph_replays_match_eager(torch_cuda):
         gq.gqsa_gemv(hp, x16, ys[4])
         gq.gqsa_gemv_multi(hq, x7, ys[5:8])
         gq.gqsa_gemv(hb, x7, ys[8])                         # 7 rows in the kernel for 8
+        gq.gqsa_gemv(hf, x1, ys[9])
+        gq.gqsa_gemv(hf, x3, ys[10])
 
     eager = outputs()
     issue(eager)
