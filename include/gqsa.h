@@ -39,7 +39,8 @@ typedef enum {
     GQSA_ERR_NULL = 1,         /* a required pointer is NULL */
     GQSA_ERR_SHAPE = 2,        /* N<=0, K<=0, K % G != 0, K > 65536, inconsistent arrays */
     GQSA_ERR_UNSUPPORTED = 3,  /* bits not 4/8, G not 8/16/32/64/128 (8-bit: up to 64), batch outside 1..16 */
-    GQSA_ERR_RANGE = 4,        /* sparsity outside [0,1], keep count outside [0,K/G], non-finite W */
+    GQSA_ERR_RANGE = 4,        /* sparsity outside [0,1], keep count outside [0,K/G], non-finite W, a kept group whose
+                                  range / (2^n - 1) is beyond the largest fp16 number (its scale could not be stored) */
     GQSA_ERR_ALLOC = 5,        /* host allocation failed */
     GQSA_ERR_HIP = 6,          /* a HIP runtime call failed (no device, launch error, ...) */
     GQSA_ERR_BUFSIZE = 7,      /* caller buffer smaller than required */

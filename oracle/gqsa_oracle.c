@@ -151,8 +151,9 @@ static void row_saliency(const float* wrow, const float* hinv_diag, int64_t kg, 
 /* ---------------------------------------------------------------- quantiser */
 
 /* Eq. 1 + Eq. 2 for one kept group.  Writes G codes (one per byte, unpacked),
- * and the fp16 bit patterns of scale and zero.                               */
-static void quantise_group(const float* w, int G, int bits,
+ * and the fp16 bit patterns of scale and zero.  Returns 0 (and writes nothing)
+ * if the scale of Eq. 1 is beyond the fp16 range the parameters are stored in. */
+static int quantise_group(const float* w, int G, int bits,
                            uint8_t* codes, uint16_t* scale_h, uint16_t* zero_h)
 {
     const float qmax = (float)((1 << bits) - 1);
@@ -164,6 +165,7 @@ static void quantise_group(const float* w, int G, int bits,
     volatile float range = mx - mn;             /* volatile: one fp32 op each */
     volatile float s32 = range / qmax;
     uint16_t sh = gqsa_oracle_f32_to_f16(s32);
+    if ((sh & 0x7FFFu) >= 0x7C00u) return 0;    /* Eq. 1's scale does not fit fp16: Eq. 3 could not undo it */
     float sf = gqsa_oracle_f16_to_f32(sh);
     const float floor_scale = 6.103515625e-05f; /* 2^-14, smallest normal fp16 */
     if (!(sf >= floor_scale)) {
@@ -183,6 +185,7 @@ static void quantise_group(const float* w, int G, int bits,
         if (q > qmax) q = qmax;
         codes[j] = (uint8_t)q;
     }
+    return 1;
 }
 
 /* ---------------------------------------------------------------- pack      */
@@ -234,7 +237,10 @@ int gqsa_oracle_pack(const float* W, int64_t N, int64_t K, int G, int bits,
         for (int64_t i = kg - keep; i < kg; ++i) keepmask[ent[i].col] = 1;
         for (int64_t c = 0; c < kg; ++c) {
             if (!keepmask[c]) continue;
-            quantise_group(wrow + c * G, G, bits, codes, &scales[g], &zeros[g]);
+            if (!quantise_group(wrow + c * G, G, bits, codes, &scales[g], &zeros[g])) {
+                free(ent); free(keepmask); free(codes);
+                return -7;
+            }
             groups[g] = (int32_t)c;
             if (bits == 8) {
                 memcpy(values + g * G, codes, (size_t)G);

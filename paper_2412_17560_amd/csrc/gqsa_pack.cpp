@@ -42,7 +42,9 @@ inline float half_value(uint16_t b)
 // Eq. 1 and Eq. 2 on one kept group of G weights.  The scale is rounded to fp16 first and
 // the rounded value is the one the zero-point and the codes are derived from, so that the
 // kernel's (q - z) * s uses exactly the parameters the codes were made with.
-void quantise_group(const float* w, int G, int bits, uint8_t* q_out, uint16_t* s_out,
+// False if the group cannot be stored: its range over 2^n - 1 is beyond the largest fp16 number,
+// so the scale of Eq. 1 would be infinite and Eq. 3 could not give the weights back.
+bool quantise_group(const float* w, int G, int bits, uint8_t* q_out, uint16_t* s_out,
                     uint16_t* z_out)
 {
     const float levels = static_cast<float>((1 << bits) - 1);
@@ -50,6 +52,7 @@ void quantise_group(const float* w, int G, int bits, uint8_t* q_out, uint16_t* s
     const float lo = *mm.first, hi = *mm.second;
     float s = (hi - lo) / levels;
     uint16_t sb = half_bits(s);
+    if ((sb & 0x7FFFu) >= 0x7C00u) return false;
     s = half_value(sb);
     constexpr float kMinScale = 0x1p-14f;  // smallest normal fp16: constant groups, underflow
     if (!(s >= kMinScale)) {
@@ -65,6 +68,7 @@ void quantise_group(const float* w, int G, int bits, uint8_t* q_out, uint16_t* s
         q = std::min(levels, std::max(0.0f, q));
         q_out[j] = static_cast<uint8_t>(q);
     }
+    return true;
 }
 
 // Kept group-columns of one row, ascending.  Order of pruning: ascending saliency, and
@@ -176,8 +180,10 @@ gqsa_status_t pack_dense(const float* W, int64_t N, int64_t K, int G, int bits,
                     const int64_t g = g0 + i;
                     const int32_t c = kept[i];
                     m->groups[g] = c;
-                    quantise_group(wrow + static_cast<int64_t>(c) * G, G, bits, q.data(),
-                                   &m->scales[g], &m->zeros[g]);
+                    if (!quantise_group(wrow + static_cast<int64_t>(c) * G, G, bits, q.data(), &m->scales[g], &m->zeros[g])) {
+                        bad = true;
+                        continue;
+                    }
                     uint8_t* dst = &m->values[static_cast<size_t>(g) * cb];
                     if (bits == 8) {
                         std::memcpy(dst, q.data(), G);

@@ -38,7 +38,7 @@ struct PackArgs {
     uint16_t* scales;
     uint16_t* zeros;
     uint8_t* blocks;           // device image, blocks region (zeroed beforehand)
-    int* status;               // bit 0: a non-finite saliency; bit 1: a bad entry of hinv
+    int* status;               // bit 0: a non-finite saliency; bit 1: a bad entry of hinv; bit 2: a scale beyond fp16
     long long K;
     int kg, G, bits, cb, U, L, bb, slots_per_group;     // (U blocks per tile, L lanes in use per block)
 };
@@ -124,6 +124,7 @@ __global__ __launch_bounds__(kThreads) void pack_rows_kernel(PackArgs a)
         }
         float s = (hi - lo) / levels;
         uint16_t sb = half_bits(s);
+        if ((sb & 0x7FFFu) >= 0x7C00u) atomicOr(a.status, 4);      // the group's range is beyond what an fp16 scale holds
         s = half_value(sb);
         const float kMinScale = 0x1p-14f;
         if (!(s >= kMinScale)) {
@@ -272,7 +273,7 @@ gqsa_status_t pack_on_device(const float* W_dev, const float* hinv_dev, gqsa_mat
     }
     GQSA_HIP(hipMemcpyAsync(m->image.data(), img, blocks_bytes, hipMemcpyDeviceToHost, s));
     GQSA_HIP(hipStreamSynchronize(s));
-    if (status != 0) return GQSA_ERR_RANGE;                // non-finite weights, or a bad diag(H^-1)
+    if (status != 0) return GQSA_ERR_RANGE;                // non-finite weights, a bad diag(H^-1), or a scale beyond fp16
     // the image is where the GEMV wants it already: the handle takes it over
     if (gqsa_status_t st = device_upload(m, img)) return st;
     guard.p = nullptr;

@@ -353,3 +353,31 @@ def test_import_round_trip_and_free_parameters():
     h = gq.gqsa_import(c.rowIndex, c.groups, c.values, c.scales, c.zeros, 50, 256, 16, 4)
     assert_same_canonical(h, c)
     assert_same_blob(h, c)
+
+
+def test_group_range_beyond_an_fp16_scale_is_refused():
+    """Eq. 1's scale is stored in fp16: a kept group whose range over 2^n - 1 rounds to infinity
+    cannot be dequantised by Eq. 3; the library and the oracle both refuse the matrix, and accept
+    the largest range that still fits."""
+    W = gi.dense_weight(8, 64, seed=3)
+    ok = W.copy()
+    ok[2, 16] = 0.0
+    ok[2, 17] = 15.0 * 65504.0                  # scale = 65504 exactly, the largest fp16 number
+    ok[2, 18:32] = 1000.0
+    h = gq.gqsa_pack(ok, 16, 4, 0.0)
+    c = oracle.pack(ok, 16, 4, sparsity=0.0)
+    assert_same_canonical(h, c)
+    assert int(gq.gqsa_export(h)["scales"][2 * 4 + 1]) == 0x7BFF
+    bad = ok.copy()
+    bad[2, 17] = 15.0 * 65536.0                 # rounds to infinity in fp16
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_pack(bad, 16, 4, 0.0)
+    assert e.value.status == 4
+    with pytest.raises(ValueError):
+        oracle.pack(bad, 16, 4, sparsity=0.0)
+    # pruned away, the group is no obstacle
+    keep = np.full(8, 4, dtype=np.int32)
+    small = bad.copy()
+    small[2, 16:32] = 0.0
+    small[2, 17] = 0.0
+    assert_same_canonical(gq.gqsa_pack_rows(small, keep, 16, 4), oracle.pack(small, 16, 4, keep_per_row=keep))

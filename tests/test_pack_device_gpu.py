@@ -180,3 +180,12 @@ def test_w8_small_batch_shape_full_size_and_save_load(torch_cuda, tmp_path):
     gq.gqsa_save(h, path)                       # a GPU-packed handle saves like any other
     h2 = gq.gqsa_load(path)
     assert gq.gqsa_export_device_blob(h2) == blob
+
+
+def test_group_range_beyond_an_fp16_scale_is_refused_on_the_gpu(torch_cuda):
+    W = gi.dense_weight(8, 64, seed=3)
+    W[2, 16] = 0.0
+    W[2, 17] = 15.0 * 65536.0
+    with pytest.raises(gq.GqsaError) as e:
+        gq.gqsa_pack_device(torch_cuda.from_numpy(W).cuda(), 16, 4, 0.0)
+    assert e.value.status == 4
