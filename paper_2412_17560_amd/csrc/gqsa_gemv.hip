@@ -854,7 +854,9 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     // use any weight, and loads return in the order of issue.  Slot c holds x[16c .. 16c+15]
     // (x is [NB][K] contiguous); a thread's first slot (first two for K above 8192) travels in
     // registers.
-    constexpr int XPRE = KGP >= 1024 ? 2 : 1;     // (512 threads cover 512 slots; more registers here cost a workgroup per compute unit)
+    // (one slot per thread covers K up to 4096 with one activation row; with several rows, or larger K, two:
+    // what is not requested here is requested behind the tile and arrives behind it)
+    constexpr int XPRE = (KGP >= 512 || NB == 2 || NB == 4) ? 2 : 1;      // (8 rows: the registers are not there)
     const int n_slots = NB * kg;
     uint4 xlo[XPRE], xhi[XPRE];
 #pragma unroll
