@@ -856,7 +856,7 @@ __global__ __launch_bounds__(kWavesPerWorkgroup * kLanes) void gqsa_gemv_kernel(
     // registers.
     // (one slot per thread covers K up to 4096 with one activation row; with several rows, or larger K, two:
     // what is not requested here is requested behind the tile and arrives behind it)
-    constexpr int XPRE = (KGP >= 512 || NB == 2 || NB == 4) ? 2 : 1;      // (8 rows: the registers are not there)
+    constexpr int XPRE = (KGP >= 512 || NB == 2 || NB == 4 || (NB == 8 && F::BITS == 4)) ? 2 : 1;      // (8 rows of 8-bit codes: the registers are not there)
     const int n_slots = NB * kg;
     uint4 xlo[XPRE], xhi[XPRE];
 #pragma unroll
