@@ -222,7 +222,13 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
         }
         // the headers of all the workgroup's panels at once (scalar loads; a panel beyond the
         // last one stands in as the last one and is not computed)
-        uint32_t hh[kPanelsPerWorkgroup][HC], where[kPanelsPerWorkgroup];
+        // (where 4 x HC words do not fit the scalar registers -- AGAIN -- only the first and the
+        // last column's word of each panel are read here, and all of a panel's words a second
+        // time, from the scalar cache, when its products start)
+        constexpr bool AGAIN = kPanelsPerWorkgroup * HC > 32;
+        uint32_t hh_all[AGAIN ? 1 : kPanelsPerWorkgroup][AGAIN ? 1 : HC];
+        uint32_t header_at[kPanelsPerWorkgroup];        // byte offset of the unit's first word in the panel's matrix's headers
+        uint32_t h_first[kPanelsPerWorkgroup], h_last[kPanelsPerWorkgroup], where[kPanelsPerWorkgroup];
 #pragma unroll
         for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
             // (the choice is made here, at the load: a header is read with scalar loads only if the
@@ -230,8 +236,13 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
             const uint8_t* headers = !MULTI || mat[pp] == 0 ? headers0 : mat[pp] == 1 ? headers1 : mat[pp] == 2 ? headers2 : headers3;
             const uint32_t* header = reinterpret_cast<const uint32_t*>(
                 headers + static_cast<size_t>(pan[pp] * n_slices + s) * kPanelHeaderBytes);
+            header_at[pp] = static_cast<uint32_t>((pan[pp] * n_slices + s) * kPanelHeaderBytes + sub * HC * 4);
+            if constexpr (!AGAIN) {
 #pragma unroll
-            for (int c = 0; c < HC; ++c) hh[pp][c] = header[sub * HC + c];
+                for (int c = 0; c < HC; ++c) hh_all[pp][c] = header[sub * HC + c];
+            }
+            h_first[pp] = header[sub * HC];
+            h_last[pp] = header[sub * HC + HC - 1];
             where[pp] = header[32];
         }
         // Where each panel's records of this unit lie (they are contiguous: first group of the
@@ -244,8 +255,8 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
         uint32_t first[kPanelsPerWorkgroup], bytes[kPanelsPerWorkgroup], room[kPanelsPerWorkgroup], slot[kPanelsPerWorkgroup];
 #pragma unroll
         for (int pp = 0; pp < kPanelsPerWorkgroup; ++pp) {
-            const uint32_t last = hh[pp][HC - 1];
-            first[pp] = hh[pp][0] >> 16;
+            const uint32_t last = h_last[pp];
+            first[pp] = h_first[pp] >> 16;
             bytes[pp] = ((last >> 16) + __builtin_popcount(last & 0xFFFFu) - first[pp]) * RB;     // <= kMaxUnitBytes
             room[pp] = ((bytes[pp] + 15u) & ~15u) + kSpare;
         }
@@ -289,12 +300,24 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
             if (live[pp]) {                             // (the same for the whole workgroup)
                 const uint8_t* records = mine + slot[pp];           // in LDS
                 const uint32_t before0 = first[pp];
+                uint32_t hh[HC];
+                if constexpr (!AGAIN) {
+#pragma unroll
+                    for (int c = 0; c < HC; ++c) hh[c] = hh_all[pp][c];
+                } else {
+                    uint32_t at = header_at[pp];
+                    asm volatile("" : "+s"(at));            // (a read of its own, not the values kept from above)
+                    const uint8_t* headers = !MULTI || mat[pp] == 0 ? headers0 : mat[pp] == 1 ? headers1 : mat[pp] == 2 ? headers2 : headers3;
+                    const uint32_t* again = reinterpret_cast<const uint32_t*>(headers + at);
+#pragma unroll
+                    for (int c = 0; c < HC; ++c) hh[c] = again[c];
+                }
                 uint32_t code[HC][(PAIRED || PAIRED8) ? 2 : QW], sz[HC];
                 constexpr bool TRI = PAIRED || PAIRED8;     // three words, the middle one is scale | zero as it is: the whole 12-byte
                                                             // record, or the half of the 24-byte one that holds the lane's quarter
 #pragma unroll
                 for (int c = 0; c < HC; ++c) {
-                    const uint32_t h = hh[pp][c];
+                    const uint32_t h = hh[c];
                     const uint32_t idx = ((h >> 16) - before0) + __builtin_popcount(h & 0xFFFFu & below);
                     if constexpr (TRI) {
                         const uint32_t* w = reinterpret_cast<const uint32_t*>(records + (idx * RB + (PAIRED8 ? half_of_record : 0u)));
@@ -346,7 +369,7 @@ __global__ __launch_bounds__(WAVES * kLanes, 4) void gqsa_panel_kernel(
                     }
 #pragma unroll
                     for (int i = 0; i < FLY; ++i) {
-                        const unsigned long long lanes = static_cast<unsigned long long>(hh[pp][c + i] & 0xFFFFu) * 0x0001000100010001ull;
+                        const unsigned long long lanes = static_cast<unsigned long long>(hh[c + i] & 0xFFFFu) * 0x0001000100010001ull;
                         if (__builtin_amdgcn_inverse_ballot_w64(lanes)) {
                             const float sc = half_bits_to_float(sz_word[i] & 0xFFFFu);
                             if constexpr (INTZ) {
