@@ -27,6 +27,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+N_SIMD_UNITS = 1024      # 256 compute units x 4
+CLOCK_HZ = 2.4e9         # peak engine clock
 MIN_POOL = 1 << 30       # distinct matrices behind every "cold" figure: four times the 256 MB memory-side cache
 
 
@@ -474,8 +476,16 @@ def main():
                 bw = inf["algorithmic_bytes"] + (B - 1) * (K + N) * 2
                 bp = infp["panel_bytes"] + B * (K + N) * 2
                 flops = 2.0 * 16 * inf["nnz_groups"] * B
+                mc = rate(bp, usp)
+                # its rooflines: HBM over the panel image's bytes, and the matrix cores' share of the
+                # launch -- one 16x16x16 product per (panel, 16-element chunk of K), 16 cycles of a
+                # SIMD unit's matrix core each (what SQ_VALU_MFMA_BUSY_CYCLES counts, profiles/)
+                products = ((N + 15) // 16) * (K // 16)
+                mc["roofline"] = {"bound": "hbm", "achieved": mc["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                  "frac": round(mc["GBps"] / HBM_PEAK_GBPS, 4),
+                                  "mfma_busy_frac": round(products * 16 / (N_SIMD_UNITS * usp * 1e-6 * CLOCK_HZ), 4)}
                 rows.append({"shape": f"{N}x{K}", "bits": bits, "batch": B,
-                             "wavefront_kernel": rate(bw, us), "matrix_core_kernel": rate(bp, usp),
+                             "wavefront_kernel": rate(bw, us), "matrix_core_kernel": mc,
                              "matrix_core_TFLOPs_dense_equivalent": round(2.0 * N * K * B / usp / 1e6, 1),
                              "TFLOPs_stored_weights": round(flops / min(us, usp) / 1e6, 2),
                              "gqsa_gemv_uses": "matrix_core_kernel" if B >= 5 else "wavefront_kernel"})
@@ -483,8 +493,9 @@ def main():
                 gq.gqsa_free(h)
         del W
     out["small_batch"] = rows
-    out["small_batch_note"] = ("roofline of the matrix-core kernel: bound = hbm over the panel image's bytes (pct_peak); its "
-                               "matrix-core occupancy is in profiles/ (rocprofv3 counters of the same launches)")
+    out["small_batch_note"] = ("roofline of the matrix-core kernel: bound = hbm over the panel image's bytes; mfma_busy_frac = "
+                               "products x 16 cycles / (1024 SIMD units x launch time x 2.4 GHz), the count that "
+                               "SQ_VALU_MFMA_BUSY_CYCLES gives for the same launches in profiles/")
 
     # q/k/v at 8 and 16 rows: three matrices on the same activations in one launch of the
     # matrix-core kernel (a workgroup's panels come from all three and share the activations it
