@@ -245,9 +245,11 @@ namespace {
 // wavefronts (small workgroups meet sooner after x is staged and fill the compute units more
 // evenly), a multiple of 4 of them so that the small-batch kernels can take the same workers 8
 // or 16 to a workgroup.  Larger K, where staging x (48 bytes of LDS per 16 elements) is a large
-// part of a workgroup's work: 8 wavefronts per workgroup and 256, 512 or 768 workgroups -- one,
-// two or three per compute unit, all alike -- as many as keep the bytes of x staged by all
-// workgroups to about a quarter of the matrix's: the multiple of 256 nearest to 448 T / K.
+// part of a workgroup's work: 8 wavefronts per workgroup and 256 or 512 workgroups -- one or two
+// per compute unit, all alike -- as many as keep the bytes of x staged by all workgroups to
+// about a quarter of the matrix's: the multiple of 256 nearest to 448 T / K, at most 512 (a third
+// workgroup per compute unit measured slower on every large shape: 23.1 against 22.5 us on
+// 28672x8192 at 50 %, 30 against 24 us with the uneven rows of the stress shape of that size).
 void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t* n_workgroups, int64_t* waves_per_workgroup)
 {
     if (K <= 4096 || n_tiles < 2048) {
@@ -260,7 +262,7 @@ void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t*
         *per_worker = 0;      // (whatever the deal gives)
         *waves_per_workgroup = 8;
         const int64_t per_cu = (448 * n_tiles + 128 * K) / (256 * K);      // round(448 T / K / 256)
-        *n_workgroups = kMaxDefaultWorkgroups * std::max<int64_t>(1, std::min<int64_t>(3, per_cu));
+        *n_workgroups = kMaxDefaultWorkgroups * std::max<int64_t>(1, std::min<int64_t>(2, per_cu));
     }
 }
 
@@ -358,7 +360,7 @@ bool partition_by_rows(const gqsa_matrix& m, Partition* out)
 // spans (place_rows) with at most 2 MiB of null groups, they are: spans of 4 t tiles for the
 // small shapes (t the tiles per worker by size, or one more if that needs too many null groups
 // or more than 16384 workers), the workgroup count again a multiple of 4; for the large ones
-// the same 256, 512 or 768 workgroups with the smallest span that holds the rows.
+// the same 256 or 512 workgroups with the smallest span that holds the rows.
 Partition default_partition(const gqsa_matrix& m)
 {
     Partition part;

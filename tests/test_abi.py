@@ -300,4 +300,4 @@ def test_default_partition_hand_table():
     assert dp(_balanced(2000, 256), 8192) == (500, 4, 4, 4, 64, 0)         # 2000 workers at most: too few; and fewer than 2048 tiles: the small shapes' deal
     assert dp(_balanced(100, 256), 32768) == (28, 4, 4, 4, 64, 0)          # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
     # too many null groups (a row of 600 per span of 1024: 424 of 1024 positions empty): the plain deal
-    assert dp(_balanced(12000, 600), 16384) == (768, 8, 0, 4, 64, 0)
+    assert dp(_balanced(12000, 600), 16384) == (512, 8, 0, 4, 64, 0)
