@@ -168,7 +168,7 @@ gqsa_status_t gqsa_import(const int32_t* rowIndex, const int32_t* groups, const 
  *      most 16384 workers; more tiles per worker beyond) in workgroups of 4 wavefronts, the
  *      workgroup count rounded up to a multiple of 4; for larger K workgroups of 8 wavefronts,
  *      256 or 512 of them (one or two per compute unit of an MI355X): the multiple of 256
- *      nearest to 448 T / K, at most 512.  If some row would then lie in two workgroups and 2 MiB of null
+ *      nearest to 448 T / K (beyond K = 8192: the one below), at most 512.  If some row would then lie in two workgroups and 2 MiB of null
  *      groups or less keep every row inside one, the aligned form below with the same wavefronts
  *      per workgroup and: small shapes -- spans of 4 t tiles, t the tiles per worker (or one
  *      more, if that takes too many null groups or more than 16384 workers), the workgroup count

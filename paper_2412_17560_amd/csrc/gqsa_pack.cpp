@@ -247,7 +247,8 @@ namespace {
 // or 16 to a workgroup.  Larger K, where staging x (48 bytes of LDS per 16 elements) is a large
 // part of a workgroup's work: 8 wavefronts per workgroup and 256 or 512 workgroups -- one or two
 // per compute unit, all alike -- as many as keep the bytes of x staged by all workgroups to
-// about a quarter of the matrix's: the multiple of 256 nearest to 448 T / K, at most 512 (a third
+// about a quarter of the matrix's: the multiple of 256 nearest to 448 T / K (beyond K = 8192 the
+// one below), at most 512 (a third
 // workgroup per compute unit measured slower on every large shape: 23.1 against 22.5 us on
 // 28672x8192 at 50 %, 30 against 24 us with the uneven rows of the stress shape of that size).
 void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t* n_workgroups, int64_t* waves_per_workgroup)
@@ -261,7 +262,10 @@ void partition_by_size(int64_t n_tiles, int64_t K, int64_t* per_worker, int64_t*
     } else {
         *per_worker = 0;      // (whatever the deal gives)
         *waves_per_workgroup = 8;
-        const int64_t per_cu = (448 * n_tiles + 128 * K) / (256 * K);      // round(448 T / K / 256)
+        // round(448 T / K / 256); beyond K = 8192, where a workgroup stages 22 KB of x and more before
+        // it can start, rounded down (4096x11008 and 4096x14336 without pruning: 10.1 and 12.3 us with
+        // 256 workgroups against 10.9 and 12.9 us with 512)
+        const int64_t per_cu = (448 * n_tiles + (K > 8192 ? 0 : 128 * K)) / (256 * K);
         *n_workgroups = kMaxDefaultWorkgroups * std::max<int64_t>(1, std::min<int64_t>(2, per_cu));
     }
 }

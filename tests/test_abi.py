@@ -295,7 +295,7 @@ def test_default_partition_hand_table():
     assert dp(_balanced(4096, 206), 11008) == (256, 8, 1, 8, 52, 1)        # two rows of 206 in 8 x 52 = 416: 2048 workers (4 x 52 would take 4096)
     # K > 4096 otherwise: by size
     assert dp(_balanced(4096, 344), 11008, bits=8) == (256, 8, 22, 4, 64, 0)   # 8-bit codes have no tile of 6 blocks: 448 T / K = 224 -> one workgroup per compute unit; 16 rows (21.5 tiles) per span of 22
-    assert dp(_balanced(4096, 688), 11008) == (512, 8, 22, 4, 64, 0)       # a row of 688 fits no tile: 448 T / K = 448 -> two per compute unit
+    assert dp(_balanced(4096, 688), 11008) == (256, 8, 43, 4, 64, 0)       # a row of 688 fits no tile: 448 T / K = 448 = 1.75 x 256, rounded down beyond K = 8192; 16 rows = 43 tiles per span
     assert dp(_balanced(3000, 256), 8192) == (376, 8, 1, 4, 64, 1)         # two rows per tile of 8 x 64 would be 1500 workers, fewer than 8 per compute unit: a row per 4 x 64
     assert dp(_balanced(2000, 256), 8192) == (500, 4, 4, 4, 64, 0)         # 2000 workers at most: too few; and fewer than 2048 tiles: the small shapes' deal
     assert dp(_balanced(100, 256), 32768) == (28, 4, 4, 4, 64, 0)          # few tiles: one per wavefront, whatever K (25 workgroups -> a multiple of 4)
